@@ -1,0 +1,212 @@
+"""Seeded synthetic request traces and candidate request-to-replica assignments.
+
+This module only *draws inputs*: arrival times, prompt/output lengths, the replica
+table (cost coefficients and availability windows) and batches of candidate
+assignments.  It contains none of the evaluator's arithmetic (no cost model, no
+queue, no metric), so both the CPU oracle's tests and the GPU path's tests can use
+it without sharing any of the method between them.
+
+The traces stand in for the production traces the paper replays (ShareGPT /
+LongBench derived request traces and Azure-Functions derived cluster membership,
+Section 7 "System Evaluation", Experimental setup): they keep their structure
+(Poisson or bursty arrivals, heavy-tailed lengths, elastic replica membership) with
+every parameter fixed and seeded here.
+
+Randomness: numpy ``Generator(PCG64(SeedSequence([seed, stream, row])))``.  Every
+array has a stream of its own and every assignment row a generator of its own, so a
+single candidate row can be regenerated without materialising the whole batch.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Optional
+
+import numpy as np
+
+UINT64_MAX = np.uint64(0xFFFFFFFFFFFFFFFF)
+
+# (prefill_base_us, prefill_per_tok_us, decode_base_us, decode_per_kctx_us)
+COEF_STANDARD = (2000, 3, 25, 5)
+COEF_FAST = (1200, 2, 15, 3)
+COEF_SLOW = (3500, 5, 40, 8)
+
+_STREAM_ARRIVAL, _STREAM_PROMPT, _STREAM_OUT, _STREAM_REPLICA, _STREAM_ASSIGN = 1, 2, 3, 4, 5
+
+
+def _rng(seed: int, stream: int, row: int = 0) -> np.random.Generator:
+    return np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, stream, row])))
+
+
+@dataclass(frozen=True)
+class TraceSpec:
+    name: str
+    seed: int
+    C: int
+    R: int
+    M: int
+    B: int
+    arrivals: str          # "poisson" | "gamma_cv4" | "diurnal"
+    rate: float            # mean requests per second
+    lengths: str           # "lognormal" | "bimodal"
+    replicas: str          # "homogeneous" | "hetero_elastic"
+    assign: str            # "uniform" | "half_jsq5" | "jsq1"
+
+
+SPECS = (
+    TraceSpec("cfg0_tiny", 0, 64, 256, 4, 8, "poisson", 20.0, "lognormal", "homogeneous", "uniform"),
+    TraceSpec("cfg1_jsq_mix", 1, 1024, 4096, 8, 32, "poisson", 200.0, "lognormal", "homogeneous", "half_jsq5"),
+    TraceSpec("cfg2_bursty", 2, 4096, 16384, 32, 32, "gamma_cv4", 800.0, "bimodal", "homogeneous", "uniform"),
+    TraceSpec("cfg3_hetero_elastic", 3, 8192, 32768, 64, 64, "poisson", 1500.0, "lognormal",
+              "hetero_elastic", "uniform"),
+    TraceSpec("cfg4_mutation_sweep", 4, 16384, 131072, 128, 64, "diurnal", 3000.0, "bimodal",
+              "homogeneous", "jsq1"),
+)
+
+
+@dataclass
+class Trace:
+    """One observed request trace plus the recipe for its candidate assignments."""
+    spec: TraceSpec
+    arrival_us: np.ndarray      # uint64[R], non-decreasing
+    prompt_len: np.ndarray      # int32[R]
+    out_len: np.ndarray         # int32[R]
+    coef: np.ndarray            # uint32[M, 4]
+    t_on_us: np.ndarray         # uint64[M]
+    t_off_us: np.ndarray        # uint64[M]
+    B: int
+    slo_ttft_us: int = 500_000
+    slo_tpot_us: int = 50_000
+    penalty_us: int = 3_600_000_000
+    _jsq_base: Optional[np.ndarray] = field(default=None, repr=False)
+
+    @property
+    def R(self) -> int:
+        return int(self.arrival_us.shape[0])
+
+    @property
+    def M(self) -> int:
+        return int(self.coef.shape[0])
+
+    @property
+    def C(self) -> int:
+        return self.spec.C
+
+    # ---- candidate assignments -------------------------------------------------
+    def jsq_base(self) -> np.ndarray:
+        """Greedy join-shortest-queue by accumulated prompt tokens (ties: lowest id)."""
+        if self._jsq_base is None:
+            load = np.zeros(self.M, dtype=np.int64)
+            base = np.empty(self.R, dtype=np.uint16)
+            prompts = self.prompt_len.tolist()
+            for r, p in enumerate(prompts):
+                m = int(np.argmin(load))
+                base[r] = m
+                load[m] += p
+            self._jsq_base = base
+        return self._jsq_base
+
+    def assignment_row(self, c: int) -> np.ndarray:
+        """Candidate row ``c`` as uint16[R]; depends only on (seed, c)."""
+        spec, R, M = self.spec, self.R, self.M
+        rng = _rng(spec.seed, _STREAM_ASSIGN, c)
+        if spec.assign == "uniform" or (spec.assign == "half_jsq5" and c < spec.C // 2):
+            return rng.integers(0, M, size=R, dtype=np.uint16)
+        frac = 0.05 if spec.assign == "half_jsq5" else 0.01
+        row = self.jsq_base().copy()
+        n = max(1, int(round(frac * R)))
+        pos = rng.integers(0, R, size=n)
+        row[pos] = rng.integers(0, M, size=n, dtype=np.uint16)
+        return row
+
+    def assignment_rows(self, lo: int, hi: int) -> np.ndarray:
+        out = np.empty((hi - lo, self.R), dtype=np.uint16)
+        for i, c in enumerate(range(lo, hi)):
+            out[i] = self.assignment_row(c)
+        return out
+
+
+def _arrivals(spec: TraceSpec, R: int, rate_scale: float) -> np.ndarray:
+    rng = _rng(spec.seed, _STREAM_ARRIVAL)
+    rate = spec.rate
+    if spec.arrivals == "poisson":
+        t = np.cumsum(rng.exponential(1.0 / rate, size=R))
+    elif spec.arrivals == "gamma_cv4":
+        # renewal process with squared CV 16: shape 1/16, mean gap 1/rate
+        t = np.cumsum(rng.gamma(1.0 / 16.0, 16.0 / rate, size=R))
+    elif spec.arrivals == "diurnal":
+        # rate(t) = rate * (1 + 0.5 sin(2 pi t / 600 s)), by thinning a 1.5*rate process
+        lam_max = 1.5 * rate
+        n = int(2.5 * R) + 4096
+        cand = np.cumsum(rng.exponential(1.0 / lam_max, size=n))
+        keep = rng.random(n) * lam_max < rate * (1.0 + 0.5 * np.sin(2.0 * np.pi * cand / 600.0))
+        t = cand[keep]
+        if t.shape[0] < R:
+            raise RuntimeError("thinning produced too few arrivals")
+        t = t[:R]
+    else:
+        raise ValueError(spec.arrivals)
+    t = t / rate_scale
+    return np.floor(t * 1e6).astype(np.uint64)
+
+
+def _lengths(spec: TraceSpec, R: int):
+    rp, ro = _rng(spec.seed, _STREAM_PROMPT), _rng(spec.seed, _STREAM_OUT)
+    if spec.lengths == "lognormal":
+        prompt = np.clip(np.floor(rp.lognormal(6.0, 1.0, size=R)), 16, 4096)
+        out = np.clip(np.floor(ro.lognormal(5.0, 1.0, size=R)), 1, 1024)
+    elif spec.lengths == "bimodal":
+        short = rp.lognormal(5.0, 0.8, size=R)
+        long_ = rp.lognormal(8.0, 0.5, size=R)
+        pick_long = rp.random(R) >= 0.7
+        prompt = np.clip(np.floor(np.where(pick_long, long_, short)), 16, 32768)
+        out = np.clip(np.floor(ro.lognormal(5.5, 1.2, size=R)), 1, 2048)
+    else:
+        raise ValueError(spec.lengths)
+    return prompt.astype(np.int32), out.astype(np.int32)
+
+
+def _replicas(spec: TraceSpec, M: int, arrival_us: np.ndarray):
+    coef = np.empty((M, 4), dtype=np.uint32)
+    t_on = np.zeros(M, dtype=np.uint64)
+    t_off = np.full(M, UINT64_MAX, dtype=np.uint64)
+    if spec.replicas == "homogeneous":
+        coef[:] = COEF_STANDARD
+    elif spec.replicas == "hetero_elastic":
+        kinds = (COEF_STANDARD, COEF_FAST, COEF_SLOW)
+        for m in range(M):
+            coef[m] = kinds[m % 3]
+        rng = _rng(spec.seed, _STREAM_REPLICA)
+        last = int(arrival_us[-1])
+        xy = rng.integers(0, last + 1, size=(M, 2), dtype=np.uint64)
+        t_on = xy.min(axis=1).astype(np.uint64)
+        t_off = xy.max(axis=1).astype(np.uint64)
+    else:
+        raise ValueError(spec.replicas)
+    return coef, t_on, t_off
+
+
+def make_trace(cfg: int, *, C: Optional[int] = None, R: Optional[int] = None, M: Optional[int] = None,
+               B: Optional[int] = None, rate_scale: float = 1.0) -> Trace:
+    """Build configuration ``cfg`` (0..4).  ``C``/``R``/``M``/``B`` shrink or reshape it for
+    tests; ``rate_scale`` > 1 compresses arrivals to make a saturated variant."""
+    base = SPECS[cfg]
+    spec = TraceSpec(base.name, base.seed, C or base.C, R or base.R, M or base.M, B or base.B,
+                     base.arrivals, base.rate, base.lengths, base.replicas, base.assign)
+    arrival = _arrivals(spec, spec.R, rate_scale)
+    prompt, out = _lengths(spec, spec.R)
+    coef, t_on, t_off = _replicas(spec, spec.M, arrival)
+    return Trace(spec, arrival, prompt, out, coef, t_on, t_off, spec.B)
+
+
+def custom_trace(arrival_us, prompt_len, out_len, coef, t_on_us=None, t_off_us=None, *, B: int,
+                 slo_ttft_us: int = 500_000, slo_tpot_us: int = 50_000,
+                 penalty_us: int = 3_600_000_000, name: str = "custom") -> Trace:
+    """Wrap hand-made arrays (edge-case tests) in a Trace."""
+    arrival = np.asarray(arrival_us, dtype=np.uint64)
+    coef = np.asarray(coef, dtype=np.uint32).reshape(-1, 4)
+    M = coef.shape[0]
+    t_on = np.zeros(M, dtype=np.uint64) if t_on_us is None else np.asarray(t_on_us, dtype=np.uint64)
+    t_off = np.full(M, UINT64_MAX, dtype=np.uint64) if t_off_us is None else np.asarray(t_off_us, dtype=np.uint64)
+    spec = TraceSpec(name, 0, 0, int(arrival.shape[0]), M, B, "custom", 0.0, "custom", "custom", "uniform")
+    return Trace(spec, arrival, np.asarray(prompt_len, dtype=np.int32), np.asarray(out_len, dtype=np.int32),
+                 coef, t_on, t_off, B, slo_ttft_us, slo_tpot_us, penalty_us)

@@ -1,0 +1,339 @@
+"""Pins for the CPU oracle (no GPU needed).
+
+Each test ties the oracle to something other than itself: hand-worked values
+(tests/golden/hand_trace.txt), closed forms from queueing theory, a second definition
+of the B-slot queue as an order statistic, sweep-line invariants, exhaustive
+enumeration of tiny instances, and numpy reductions for the no-wait case.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import Oracle
+from paper_2604_07144_amd import traces
+from tests import refdefs
+
+STD = traces.COEF_STANDARD
+U64MAX = 0xFFFFFFFFFFFFFFFF
+
+
+def make(arrival, prompt, out, coef=(STD,), t_on=None, t_off=None, B=2, slo=(500_000, 50_000), penalty=3_600_000_000):
+    coef = np.asarray(coef, dtype=np.uint32).reshape(-1, 4)
+    M = coef.shape[0]
+    t_on = [0] * M if t_on is None else t_on
+    t_off = [U64MAX] * M if t_off is None else t_off
+    return Oracle(arrival, prompt, out, coef, t_on, t_off, B, slo[0], slo[1], penalty)
+
+
+# ----------------------------------------------------------------------------- P1
+HAND = dict(arrival=[0, 1000, 1500, 2000], prompt=[100, 1024, 1025, 16], out=[10, 100, 1, 20])
+HAND_CASES = {
+    "base": dict(B=2),
+    "b1": dict(B=1),
+    "ton": dict(B=2, t_on=[3000]),
+    "toff": dict(B=2, t_off=[5000], penalty=1_000_000),
+    "tightslo": dict(B=2, slo=(6000, 30)),
+}
+COLS = ("sum_e2e_us", "sum_ttft_us", "sum_tpot_us", "makespan_us", "p99_ttft_us", "p99_tpot_us", "p99_e2e_us",
+        "slo_ok", "n_rejected")
+
+
+def read_golden(golden_dir):
+    rows = {}
+    with open(os.path.join(golden_dir, "hand_trace.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            parts = line.split()
+            rows[parts[0]] = [int(x) for x in parts[1:]]
+    return rows
+
+
+@pytest.mark.parametrize("case", sorted(HAND_CASES))
+def test_hand_worked_trace(case, golden_dir):
+    want = read_golden(golden_dir)[case]
+    orc = make(HAND["arrival"], HAND["prompt"], HAND["out"], **HAND_CASES[case])
+    got = orc.eval_row(np.zeros(4, dtype=np.uint16))
+    assert [int(got[c]) for c in COLS] == want
+
+
+def test_hand_worked_per_request_values():
+    orc = make(HAND["arrival"], HAND["prompt"], HAND["out"], B=2)
+    _, d = orc.eval_row(np.zeros(4, dtype=np.uint16), detail=True)
+    assert d["start_us"].tolist() == [0, 1000, 2600, 7710]
+    assert d["finish_us"].tolist() == [2600, 9072, 7710, 10358]
+    assert d["ttft_us"].tolist() == [2300, 5072, 6175, 7758]
+    assert d["tpot_us"].tolist() == [30, 30, 35, 30]
+    assert d["e2e_us"].tolist() == [2600, 8072, 6210, 8358]
+
+
+# ------------------------------------------------------------------- histogram bins
+def test_hist_hand_checked_values():
+    # value -> (bin, lower edge), worked by hand from "octave cut into 128 sub-bins"
+    table = {0: (0, 0), 127: (127, 127), 128: (128, 128), 255: (255, 255), 256: (256, 256), 257: (256, 256),
+             258: (257, 258), 2300: (655, 2288), 7758: (882, 7744), 50000: (1219, 49920),
+             500000: (1652, 499712), 2**38 - 2**30 - 1: (4094, 2**38 - 2**31),
+             2**38 - 2**30: (4095, 2**38 - 2**30), 2**38: (4095, 2**38 - 2**30), 2**63: (4095, 2**38 - 2**30),
+             U64MAX: (4095, 2**38 - 2**30)}
+    for v, (b, lo) in table.items():
+        assert oracle.hist_bin(v) == b, v
+        assert oracle.hist_lower(b) == lo, v
+
+
+def test_hist_properties():
+    rng = np.random.default_rng(5)
+    vals = np.unique(np.concatenate([np.arange(0, 2048), 2 ** rng.uniform(7, 39, 4000)]).astype(np.uint64))
+    bins = np.array([oracle.hist_bin(int(v)) for v in vals])
+    assert np.all(np.diff(bins) >= 0)                       # monotone
+    assert bins.max() <= 4095
+    edges = np.array([oracle.hist_lower(b) for b in range(4096)], dtype=object)
+    assert all(edges[b] < edges[b + 1] for b in range(4095))  # strictly increasing edges
+    for v, b in zip(vals.tolist(), bins.tolist()):
+        lo = edges[b]
+        assert lo <= v                                      # value is in its bin
+        if b < 4095:
+            assert v < edges[b + 1]
+            if v >= 128:
+                assert (edges[b + 1] - lo) * 128 <= lo      # relative width <= 1/128
+        assert oracle.hist_bin(int(lo)) == b                # edge maps back to its bin
+    for v in range(256):
+        assert oracle.hist_lower(oracle.hist_bin(v)) == v   # exact below 256
+
+
+# ----------------------------------------------------------------------------- P2
+def test_single_slot_matches_lindley_closed_form():
+    rng = np.random.default_rng(11)
+    n = 300
+    arrival = np.cumsum(rng.integers(0, 6000, n)).astype(np.uint64) + 17
+    prompt = rng.integers(1, 5000, n).astype(np.int32)
+    out = rng.integers(1, 300, n).astype(np.int32)
+    svc = np.array([sum(refdefs.service_terms(p, o, STD)[::2]) for p, o in zip(prompt, out)])
+    for t_on in (0, 40_000):
+        orc = make(arrival, prompt, out, B=1, t_on=[t_on])
+        _, d = orc.eval_row(np.zeros(n, dtype=np.uint16), detail=True)
+        want = refdefs.lindley_finish_times(arrival.astype(np.int64), svc, t_on)
+        assert d["finish_us"].astype(np.int64).tolist() == want.tolist()
+        assert (d["finish_us"] > arrival).all() and d["rejected"].sum() == 0
+
+
+def test_deterministic_queue_wait_grows_linearly():
+    # D/D/1: spacing delta, identical service S > delta  =>  wait_n = n * (S - delta)
+    n, delta = 200, 1000
+    arrival = (np.arange(n) * delta).astype(np.uint64)
+    prompt = np.full(n, 64, dtype=np.int32)
+    out = np.full(n, 10, dtype=np.int32)
+    prefill, per_tok, decode = refdefs.service_terms(64, 10, STD)
+    S = prefill + decode
+    assert S > delta
+    orc = make(arrival, prompt, out, B=1)
+    _, d = orc.eval_row(np.zeros(n, dtype=np.uint16), detail=True)
+    wait = d["start_us"].astype(np.int64) - arrival.astype(np.int64)
+    assert wait.tolist() == [i * (S - delta) for i in range(n)]
+    assert d["ttft_us"].tolist() == [i * (S - delta) + prefill for i in range(n)]
+
+
+def test_md1_mean_wait_pollaczek_khinchine():
+    # Poisson arrivals, identical requests, one slot: E[wait] = rho * S / (2 (1 - rho))
+    rng = np.random.default_rng(3)
+    n = 400_000
+    prefill, _, decode = refdefs.service_terms(256, 40, STD)
+    S = prefill + decode
+    for rho in (0.3, 0.7):
+        lam = rho / S
+        arrival = np.floor(np.cumsum(rng.exponential(1.0 / lam, n))).astype(np.uint64)
+        orc = make(arrival, np.full(n, 256, np.int32), np.full(n, 40, np.int32), B=1)
+        _, d = orc.eval_row(np.zeros(n, dtype=np.uint16), detail=True)
+        wait = (d["start_us"] - arrival).astype(np.float64).mean()
+        want = rho * S / (2 * (1 - rho))
+        assert abs(wait - want) / want < 0.03, (rho, wait, want)
+
+
+# ----------------------------------------------------------------------------- P3 / P4
+def _random_problem(seed, n, M, B, load, windows):
+    rng = np.random.default_rng(seed)
+    arrival = np.cumsum(rng.integers(0, int(12000 / load) + 1, n)).astype(np.uint64) + 5
+    prompt = rng.integers(1, 6000, n).astype(np.int32)
+    out = rng.integers(1, 400, n).astype(np.int32)
+    kinds = [STD, traces.COEF_FAST, traces.COEF_SLOW]
+    coef = [kinds[m % 3] for m in range(M)]
+    if windows:
+        span = int(arrival[-1])
+        xy = rng.integers(0, span + 1, size=(M, 2))
+        t_on, t_off = xy.min(1).tolist(), xy.max(1).tolist()
+    else:
+        t_on, t_off = [0] * M, [U64MAX] * M
+    row = rng.integers(0, M + (1 if windows else 0), n).astype(np.uint16)   # some ids == M: invalid
+    return arrival, prompt, out, coef, t_on, t_off, row
+
+
+@pytest.mark.parametrize("seed,n,M,B,load,windows", [
+    (1, 400, 3, 4, 6.0, False), (2, 400, 2, 1, 3.0, False), (3, 500, 5, 8, 20.0, True),
+    (4, 300, 1, 64, 200.0, False), (5, 600, 4, 3, 0.5, True), (6, 64, 2, 64, 50.0, True)])
+def test_order_statistic_definition_and_invariants(seed, n, M, B, load, windows):
+    arrival, prompt, out, coef, t_on, t_off, row = _random_problem(seed, n, M, B, load, windows)
+    penalty = 77_000_000
+    orc = make(arrival, prompt, out, coef, t_on, t_off, B=B, penalty=penalty)
+    met, d = orc.eval_row(row, detail=True)
+    n_rej = 0
+    for m in range(M):
+        idx = np.flatnonzero(row == m)
+        terms = [refdefs.service_terms(prompt[r], out[r], coef[m]) for r in idx]
+        svc = [t[0] + t[2] for t in terms]
+        st, fi, rj = refdefs.order_statistic_replay(arrival[idx], svc, B, t_on[m], t_off[m])
+        # second definition agrees request by request
+        assert d["rejected"][idx].tolist() == rj
+        for k, r in enumerate(idx):
+            if rj[k]:
+                n_rej += 1
+                assert d["ttft_us"][r] == d["e2e_us"][r] == d["tpot_us"][r] == penalty
+                continue
+            assert int(d["start_us"][r]) == st[k] and int(d["finish_us"][r]) == fi[k]
+            # invariants
+            assert st[k] >= int(arrival[r]) and st[k] >= t_on[m] and st[k] < t_off[m]
+            assert int(d["ttft_us"][r]) == st[k] - int(arrival[r]) + terms[k][0]
+            assert int(d["e2e_us"][r]) == int(d["ttft_us"][r]) + terms[k][2]
+            assert int(d["tpot_us"][r]) == terms[k][1]
+        served = [k for k in range(len(idx)) if not rj[k]]
+        assert all(st[a] <= st[b] for a, b in zip(served, served[1:]))         # starts non-decreasing
+        assert rj == sorted(rj)                                                  # rejections are a suffix
+        assert refdefs.max_concurrency(st, fi) <= B                              # never more than B in service
+    n_rej += int((row >= M).sum())
+    assert d["rejected"][row >= M].all()
+    assert int(met["n_rejected"]) == n_rej == int(d["rejected"].sum())
+    # aggregates are the plain reductions of the per-request values
+    assert int(met["sum_e2e_us"]) == int(d["e2e_us"].astype(object).sum())
+    assert int(met["sum_ttft_us"]) == int(d["ttft_us"].astype(object).sum())
+    assert int(met["sum_tpot_us"]) == int(d["tpot_us"].astype(object).sum())
+    ok = (d["ttft_us"] <= 500_000) & (d["tpot_us"] <= 50_000)
+    assert int(met["slo_ok"]) == int(ok.sum())
+    served_mask = ~d["rejected"]
+    want_makespan = int(d["finish_us"][served_mask].max() - arrival[0]) if served_mask.any() else 0
+    assert int(met["makespan_us"]) == want_makespan
+
+
+# ----------------------------------------------------------------------------- P5
+@pytest.mark.parametrize("R,M,B", [(8, 3, 1), (8, 3, 2), (7, 2, 3), (6, 3, 8)])
+def test_brute_force_all_assignments(R, M, B):
+    rng = np.random.default_rng(100 + R + M + B)
+    arrival = np.cumsum(rng.integers(0, 3000, R)).astype(np.uint64)
+    prompt = rng.integers(1, 3000, R).astype(np.int32)
+    out = rng.integers(1, 200, R).astype(np.int32)
+    coef = [STD, traces.COEF_FAST, traces.COEF_SLOW][:M]
+    t_on = [0, 4000, 0][:M]
+    t_off = [U64MAX, U64MAX, 9000][:M]
+    penalty = 5_000_000
+    orc = make(arrival, prompt, out, coef, t_on, t_off, B=B, penalty=penalty)
+    rows = np.array(list(itertools.product(range(M), repeat=R)), dtype=np.uint16)
+    got = orc.eval_batch(rows, nthreads=2)
+    more = make(arrival, prompt, out, coef, t_on, t_off, B=B + 1, penalty=penalty).eval_batch(rows)
+    for c, row in enumerate(rows):
+        ttft = np.zeros(R, dtype=object); e2e = np.zeros(R, dtype=object); last = 0; nrej = 0
+        for m in range(M):
+            idx = np.flatnonzero(row == m)
+            terms = [refdefs.service_terms(prompt[r], out[r], coef[m]) for r in idx]
+            st, fi, rj = refdefs.order_statistic_replay(arrival[idx], [t[0] + t[2] for t in terms], B, t_on[m], t_off[m])
+            for k, r in enumerate(idx):
+                if rj[k]:
+                    ttft[r] = e2e[r] = penalty; nrej += 1
+                else:
+                    ttft[r] = st[k] - int(arrival[r]) + terms[k][0]
+                    e2e[r] = fi[k] - int(arrival[r]); last = max(last, fi[k])
+        assert int(got["sum_ttft_us"][c]) == sum(ttft) and int(got["sum_e2e_us"][c]) == sum(e2e)
+        assert int(got["n_rejected"][c]) == nrej
+        assert int(got["makespan_us"][c]) == (last - int(arrival[0]) if nrej < R else 0)
+        assert int(got["p99_ttft_us"][c]) == oracle.hist_lower(oracle.hist_bin(max(ttft)))   # R<=100: p99 = max
+        assert int(got["p99_e2e_us"][c]) == oracle.hist_lower(oracle.hist_bin(max(e2e)))
+    # one more slot never hurts when nobody is turned away by a closing window
+    always_on = np.array([all(t_off[m] == U64MAX for m in row) for row in rows])
+    assert (more["sum_ttft_us"][always_on] <= got["sum_ttft_us"][always_on]).all()
+
+
+# ----------------------------------------------------------------------------- P6
+def test_no_wait_case_reduces_to_vector_arithmetic():
+    tr = traces.make_trace(0)
+    R, M = tr.R, tr.M
+    orc = Oracle.from_trace(tr, B=R)         # as many slots as requests: nobody waits
+    rows = tr.assignment_rows(0, 8)
+    got = orc.eval_batch(rows)
+    a, b, c, d = STD
+    prefill = a + b * tr.prompt_len.astype(np.int64)
+    per_tok = c + d * ((tr.prompt_len.astype(np.int64) + 1023) // 1024)
+    e2e = prefill + tr.out_len.astype(np.int64) * per_tok
+    k = -(-99 * R // 100)
+    for col, vals in (("p99_ttft_us", prefill), ("p99_tpot_us", per_tok), ("p99_e2e_us", e2e)):
+        # the nearest-rank percentile commutes with the monotone map value -> bin -> lower edge
+        pct = int(np.percentile(vals, 99, method="inverted_cdf"))
+        assert pct == int(np.sort(vals)[k - 1])
+        assert (got[col] == oracle.hist_lower(oracle.hist_bin(pct))).all()
+    assert (got["sum_ttft_us"] == prefill.sum()).all()
+    assert (got["sum_e2e_us"] == e2e.sum()).all()
+    assert (got["sum_tpot_us"] == per_tok.sum()).all()
+    assert (got["slo_ok"] == int(((prefill <= tr.slo_ttft_us) & (per_tok <= tr.slo_tpot_us)).sum())).all()
+    assert (got["n_rejected"] == 0).all()
+    want_makespan = int((tr.arrival_us.astype(np.int64) + e2e).max() - int(tr.arrival_us[0]))
+    assert (got["makespan_us"] == want_makespan).all()
+
+
+def test_queue_membership_is_a_stable_partition():
+    # the replica's queue is its requests in index order: a stable argsort of the row
+    tr = traces.make_trace(0)
+    row = tr.assignment_row(3)
+    orc = Oracle.from_trace(tr, B=1)
+    _, d = orc.eval_row(row, detail=True)
+    order = np.argsort(row, kind="stable")
+    for m in range(tr.M):
+        q = order[row[order] == m]
+        assert (np.diff(q) > 0).all()
+        assert (np.diff(d["start_us"][q].astype(np.int64)) > 0).all()   # B=1: strictly one after another
+
+
+# ----------------------------------------------------------------------------- P7
+def test_metamorphic_relabel_shift_and_row_order():
+    tr = traces.make_trace(1, C=16, R=1024, rate_scale=40.0)
+    rows = tr.assignment_rows(0, 16)
+    orc = Oracle.from_trace(tr, B=4)
+    base = orc.eval_batch(rows, nthreads=4)
+    assert (base["sum_ttft_us"] > (2000 + 3 * tr.prompt_len.astype(np.int64)).sum()).any()   # queueing happens
+    # identical always-on replicas: relabelling them changes nothing
+    perm = np.random.default_rng(0).permutation(tr.M).astype(np.uint16)
+    assert (orc.eval_batch(perm[rows]) == base).all()
+    # shifting every time stamp by a constant changes nothing
+    shift = 123_456_789
+    shifted = Oracle.from_trace(tr, B=4, arrival_us=tr.arrival_us + np.uint64(shift), t_on_us=tr.t_on_us + np.uint64(shift))
+    assert (shifted.eval_batch(rows) == base).all()
+    # candidates are independent: order and batch composition do not matter
+    p = np.random.default_rng(1).permutation(16)
+    assert (orc.eval_batch(rows[p]) == base[p]).all()
+    assert orc.eval_row(rows[5]) == base[5]
+
+
+def test_window_edge_cases():
+    arrival = [10, 20, 30, 40]
+    prompt, out = [100] * 4, [10] * 4
+    row = np.zeros(4, dtype=np.uint16)
+    P = 9_999_999
+    # never available (t_on == t_off): everything rejected, makespan 0
+    m = make(arrival, prompt, out, t_on=[25], t_off=[25], penalty=P).eval_row(row)
+    assert int(m["n_rejected"]) == 4 and int(m["makespan_us"]) == 0 and int(m["sum_e2e_us"]) == 4 * P
+    assert int(m["slo_ok"]) == 0
+    # window entirely before the trace: all rejected; entirely after: all wait for t_on
+    assert int(make(arrival, prompt, out, t_on=[0], t_off=[10], penalty=P).eval_row(row)["n_rejected"]) == 4
+    m = make(arrival, prompt, out, t_on=[1000], B=4).eval_row(row)
+    assert int(m["n_rejected"]) == 0 and int(m["sum_ttft_us"]) == sum(1000 - a + 2300 for a in arrival)
+    # t_off is exclusive: a start exactly at t_off is rejected, one microsecond earlier is served
+    assert int(make(arrival, prompt, out, t_off=[40], B=4, penalty=P).eval_row(row)["n_rejected"]) == 1
+    assert int(make(arrival, prompt, out, t_off=[41], B=4, penalty=P).eval_row(row)["n_rejected"]) == 0
+    # invalid replica ids are rejected, valid ones unaffected
+    m = make(arrival, prompt, out, B=4, penalty=P).eval_row(np.array([0, 1, 65535, 0], dtype=np.uint16))
+    assert int(m["n_rejected"]) == 2 and int(m["sum_ttft_us"]) == 2 * 2300 + 2 * P
+    # SLO holds at equality
+    m = make(arrival, prompt, out, B=4, slo=(2300, 30)).eval_row(row)
+    assert int(m["slo_ok"]) == 4
+    m = make(arrival, prompt, out, B=4, slo=(2299, 30)).eval_row(row)
+    assert int(m["slo_ok"]) == 0
+    m = make(arrival, prompt, out, B=4, slo=(2300, 29)).eval_row(row)
+    assert int(m["slo_ok"]) == 0
