@@ -47,8 +47,8 @@
  *  batch occupancy does not change a request's service time; all slots start free at
  *  time 0; the earliest-free slot is taken, lowest index on ties; TPOT is decode time
  *  per output token, which is exactly c + d*ceil(prompt/1024); SLO is met at equality;
- *  a rejected request counts with ttft = tpot = e2e = penalty in sums and histograms
- *  and never in the makespan; percentiles use the nearest-rank rule over all R
+ *  a rejected request counts with ttft = tpot = e2e = penalty in sums and histograms,
+ *  never meets the SLO and never enters the makespan; percentiles use the nearest-rank rule over all R
  *  requests on a 4096-bin log-linear histogram and report the bin's lower edge.
  *
  * Pins (tests that run without a GPU): hand-worked traces, the single-slot Lindley
@@ -218,7 +218,8 @@ int orc_eval_row(const orc_problem *p, const uint16_t *row, orc_metrics *out, co
             if (!any_served || fin[r] > last_finish) last_finish = fin[r];
             any_served = 1;
         }
-        if (ttft[r] <= p->slo_ttft_us && tpot[r] <= p->slo_tpot_us) mt.slo_ok++;
+        /* an unserved request never meets the SLO, whatever the penalty value */
+        if (!rej[r] && ttft[r] <= p->slo_ttft_us && tpot[r] <= p->slo_tpot_us) mt.slo_ok++;
         mt.sum_e2e_us += e2e[r];
         mt.sum_ttft_us += ttft[r];
         mt.sum_tpot_us += tpot[r];

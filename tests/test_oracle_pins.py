@@ -208,7 +208,7 @@ def test_order_statistic_definition_and_invariants(seed, n, M, B, load, windows)
     assert int(met["sum_e2e_us"]) == int(d["e2e_us"].astype(object).sum())
     assert int(met["sum_ttft_us"]) == int(d["ttft_us"].astype(object).sum())
     assert int(met["sum_tpot_us"]) == int(d["tpot_us"].astype(object).sum())
-    ok = (d["ttft_us"] <= 500_000) & (d["tpot_us"] <= 50_000)
+    ok = (d["ttft_us"] <= 500_000) & (d["tpot_us"] <= 50_000) & ~d["rejected"]
     assert int(met["slo_ok"]) == int(ok.sum())
     served_mask = ~d["rejected"]
     want_makespan = int(d["finish_us"][served_mask].max() - arrival[0]) if served_mask.any() else 0
@@ -320,6 +320,9 @@ def test_window_edge_cases():
     m = make(arrival, prompt, out, t_on=[25], t_off=[25], penalty=P).eval_row(row)
     assert int(m["n_rejected"]) == 4 and int(m["makespan_us"]) == 0 and int(m["sum_e2e_us"]) == 4 * P
     assert int(m["slo_ok"]) == 0
+    # an unserved request never meets the SLO, even when the penalty is below the thresholds
+    m = make(arrival, prompt, out, t_off=[30], B=4, penalty=5).eval_row(row)
+    assert int(m["n_rejected"]) == 2 and int(m["slo_ok"]) == 2 and int(m["sum_ttft_us"]) == 2 * 2300 + 10
     # window entirely before the trace: all rejected; entirely after: all wait for t_on
     assert int(make(arrival, prompt, out, t_on=[0], t_off=[10], penalty=P).eval_row(row)["n_rejected"]) == 4
     m = make(arrival, prompt, out, t_on=[1000], B=4).eval_row(row)
