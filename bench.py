@@ -1,0 +1,146 @@
+#!/usr/bin/env python3
+"""Benchmark: candidate-request simulations per second on one MI355X.
+
+One step = one ap_eval_candidates call over the whole candidate batch of the chosen
+configuration (all stages of the path), with trace, cost model and assignments already
+resident in HBM.  Prints ONE JSON line with the throughput, the HBM roofline of the
+evaluation kernel (algorithmic bytes / measured kernel time) and the CPU oracle timed on
+this host on a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 0..4] [--rate-scale S]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+TABLE_BYTES_PER_REQUEST = 16   # arrival + prefill/decode/tpot-class inputs, per replica type
+
+
+def algorithmic_bytes(C: int, R: int, n_types: int) -> int:
+    """Bytes the method itself must move per call: every uint16 assignment once, one 64-byte
+    record per candidate, the per-request tables once."""
+    return 2 * C * R + 64 * C + TABLE_BYTES_PER_REQUEST * n_types * R
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=4, help="workload configuration 0..4 (default: the largest)")
+    ap.add_argument("--rate-scale", type=float, default=1.0, help=">1 compresses arrivals (saturated variant)")
+    ap.add_argument("--rows", type=int, default=0, help="use only the first ROWS candidates (0 = all)")
+    ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the oracle sample (0 = auto)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this path runs on one GPU; candidates are independent, so more GPUs would only "
+              "split the rows. Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2604_07144_amd import binding, traces
+
+    torch.cuda.set_device(0)
+    tr = traces.make_trace(args.config, rate_scale=args.rate_scale)
+    C = args.rows if args.rows else tr.C
+    R, M = tr.R, tr.M
+    n_types = len({tuple(int(x) for x in row) for row in tr.coef})
+
+    # inputs resident in HBM before anything is timed (rows drawn and uploaded in slabs)
+    d_assign = torch.empty((C, R), dtype=torch.int16, device="cuda")
+    slab = max(1, (256 << 20) // (2 * R))
+    for lo in range(0, C, slab):
+        hi = min(C, lo + slab)
+        d_assign[lo:hi] = torch.from_numpy(tr.assignment_rows(lo, hi).view(np.int16)).cuda()
+    d_out = torch.zeros((C, 8), dtype=torch.int64, device="cuda")
+
+    h = binding.ap_workload_create(tr.arrival_us, tr.prompt_len, tr.out_len)
+    try:
+        binding.ap_costmodel_set(h, binding.make_replicas(tr.coef, tr.t_on_us, tr.t_off_us), tr.B,
+                                 tr.slo_ttft_us, tr.slo_tpot_us, tr.penalty_us)
+        stream = torch.cuda.current_stream()
+
+        def step():
+            binding.ap_eval_candidates(h, d_assign.data_ptr(), C, d_out.data_ptr(), stream.cuda_stream)
+
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        # HIP events on the stream the kernels are launched on: per-launch device time
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        t0 = time.perf_counter()
+        for a, b in ev:
+            a.record(stream)
+            step()
+            b.record(stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        kernel_ms = [a.elapsed_time(b) for a, b in ev]
+        got = d_out.cpu().numpy().view(binding.METRICS_DTYPE).reshape(-1)
+    finally:
+        binding.ap_workload_destroy(h)
+
+    sims = C * R
+    ms_per_step = wall * 1e3 / args.steps
+    avg_kernel_s = float(np.mean(kernel_ms)) * 1e-3
+    alg = algorithmic_bytes(C, R, n_types)
+    achieved = alg / avg_kernel_s / 1e9
+
+    result = {
+        "metric": "candidate-request simulations/s",
+        "value": sims / (wall / args.steps),
+        "unit": "sims/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32",
+        "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}] {tr.spec.name}: C={C} R={R} M={M} B={tr.B}"
+                               + (f" arrival rate x{args.rate_scale:g}" if args.rate_scale != 1.0 else ""),
+                   "candidates": C, "requests": R, "replicas": M, "slots": tr.B, "replica_types": n_types},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "k_eval_candidates", "kernel_ms_avg": avg_kernel_s * 1e3,
+                     "kernel_ms_min": float(np.min(kernel_ms)), "algorithmic_bytes": alg},
+        "mean_ttft_us_row0": int(got["sum_ttft_us"][0]) / R,
+        "rejected_row0": int(got["n_rejected"][0]),
+    }
+
+    if not args.no_cpu:
+        import oracle
+        threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")), 16)
+        n_cpu = args.cpu_rows or max(threads, min(C, int(6e8 // max(1, R * M))))
+        pick = np.unique(np.linspace(0, C - 1, n_cpu).astype(np.int64))
+        rows = np.stack([tr.assignment_row(int(c)) for c in pick])
+        orc = oracle.Oracle.from_trace(tr)
+        t0 = time.perf_counter()
+        want = orc.eval_batch(rows, nthreads=threads)
+        cpu_s = time.perf_counter() - t0
+        same = got[pick].tobytes() == want.tobytes()
+        result["cpu_baseline"] = {"value": len(pick) * R / cpu_s, "unit": "sims/s", "cores": threads,
+                                  "kind": "oracle",
+                                  "sample": f"{len(pick)} of {C} candidate rows (evenly spaced), all {R} requests, "
+                                            f"{cpu_s:.2f} s wall on {threads} threads",
+                                  "matches_gpu": bool(same)}
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,139 @@
+/*
+ * autopoiesis_eval.h -- C ABI of the MI355X (gfx950) candidate-assignment evaluator.
+ *
+ * The library scores many candidate request-to-replica assignments against one
+ * observed request trace: the evaluator step of the paper's policy-evolution loop
+ * (Section 5.3 "Evaluator": the snapshotted runtime trace is replayed against each
+ * candidate; Section 7.3 "Convergence analysis": candidates are evaluated
+ * independently), specialised to the workload-assignment dimension of a serving plan
+ * (Section 2.1 "Serving plans", item (i)) and to per-request objectives (Appendix
+ * "Discussion and Limitation", adaptability to diverse serving objectives: per-request
+ * latency is tracked through the replay and reduced to a percentile or to the number
+ * of requests meeting a latency threshold).
+ *
+ * Per candidate, requests are grouped by replica in arrival order, every replica is
+ * replayed as a B-slot first-come-first-served continuous-batching queue (Section 5.3
+ * "Serving simulator"; B is the maximum per-replica batch size b^max of the Notations
+ * table) under an integer-microsecond prefill/decode cost model (the shape of the
+ * serve-latency equation of Appendix "Serving Simulator": a prefill term plus a decode
+ * term that grows with context), and the per-request latencies are reduced to the
+ * ap_metrics record below.
+ *
+ * All calls return an ap_status and never throw or abort.  Out-parameters are left
+ * untouched on error.  Every kernel runs on the device that is current when the
+ * workload is created; the evaluation is asynchronous on the caller's stream.
+ */
+#ifndef AUTOPOIESIS_EVAL_H
+#define AUTOPOIESIS_EVAL_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ap_workload ap_workload; /* opaque; the library owns every device copy */
+
+typedef enum {
+    AP_OK = 0,
+    AP_ERR_INVALID = 1, /* null pointer, zero size, unsorted arrivals, non-positive length ... */
+    AP_ERR_RANGE = 2,   /* a documented capacity of the device path is exceeded */
+    AP_ERR_ALLOC = 3,   /* host or device allocation failed */
+    AP_ERR_DEVICE = 4,  /* a HIP call failed */
+    AP_ERR_STATE = 5    /* evaluation requested before a cost model was set */
+} ap_status;
+
+/* One replica (Section 4, data plane: the snapshot carries cluster resource
+ * availability; Section 8.2 "Elastic Cluster Dynamics").  Service time of a request on
+ * this replica, in microseconds:
+ *     prefill = prefill_base_us + prefill_per_tok_us * prompt_len
+ *     tpot    = decode_base_us  + decode_per_kctx_us * ceil(prompt_len / 1024)
+ *     decode  = out_len * tpot
+ * The replica exists during [t_on_us, t_off_us): nothing starts before t_on_us; a
+ * request whose start would be >= t_off_us is rejected; started requests drain.
+ * Always available = {0, UINT64_MAX}. */
+typedef struct {
+    uint32_t prefill_base_us;
+    uint32_t prefill_per_tok_us;
+    uint32_t decode_base_us;
+    uint32_t decode_per_kctx_us;
+    uint64_t t_on_us;
+    uint64_t t_off_us;
+} ap_replica;
+
+/* Latency thresholds (met at equality) and the latency charged to a request that is
+ * not served (replica id >= M, or replica gone): the penalty latency of Appendix
+ * "Serving Simulator", Memory Feasibility. */
+typedef struct {
+    uint64_t ttft_us;
+    uint64_t tpot_us;
+    uint64_t penalty_us;
+} ap_slo;
+
+/* Per-candidate result, 64 bytes.  Sums and counts run over all R requests; a rejected
+ * request contributes ttft = tpot = e2e = penalty_us and never meets the SLO.
+ * makespan_us = latest finish of a served request minus the first arrival (0 if none
+ * was served): the trace completion time of Section 5.1 "Objective".
+ * p99_* = nearest-rank 99th percentile (rank ceil(0.99 R)) on the 4096-bin histogram
+ * of ap_hist_bin, reported as the lower edge of the bin. */
+typedef struct {
+    uint64_t sum_e2e_us;
+    uint64_t sum_ttft_us;
+    uint64_t sum_tpot_us;
+    uint64_t makespan_us;
+    uint64_t p99_ttft_us;
+    uint64_t p99_tpot_us;
+    uint64_t p99_e2e_us;
+    uint32_t slo_ok;     /* requests with ttft <= slo.ttft_us and tpot <= slo.tpot_us */
+    uint32_t n_rejected;
+} ap_metrics;
+
+/* Capacities of the device path (exceeding one gives AP_ERR_RANGE, never a wrong result). */
+#define AP_MAX_SLOTS 64u      /* B */
+#define AP_MAX_REPLICAS 1024u /* M; additionally M*B*4 bytes of slot state must fit in LDS, see ap_costmodel_set */
+
+/* Take a trace snapshot (Section 4: a sliding window of request arrivals).
+ *   arrival_us, prompt_len, out_len : HOST arrays of R elements, copied; the caller keeps its buffers.
+ *   arrival_us must be non-decreasing; prompt_len and out_len must be >= 1; R >= 1.
+ * On success *out owns device copies on the current device.  Errors: AP_ERR_INVALID, AP_ERR_ALLOC,
+ * AP_ERR_DEVICE. */
+ap_status ap_workload_create(const uint64_t *arrival_us, const int32_t *prompt_len, const int32_t *out_len,
+                             uint32_t R, ap_workload **out);
+
+/* Attach (or replace) the replica table, the slot count and the SLOs.
+ *   replicas : HOST array of M entries, copied.  1 <= M <= AP_MAX_REPLICAS, 1 <= B <= AP_MAX_SLOTS,
+ *              t_on_us <= t_off_us for every replica (AP_ERR_INVALID otherwise).
+ * The device keeps time as 32-bit microseconds relative to the first arrival.  The call
+ * proves that no finish time can leave that range (latest arrival or t_on, plus the sum
+ * of every request's largest service time, must be below 2^32 - 1 us, about 71 minutes)
+ * and that the per-candidate working set fits in the 160 KiB of LDS; otherwise it
+ * returns AP_ERR_RANGE and the workload keeps its previous cost model, if any.
+ * Synchronous (small host-to-device copies). */
+ap_status ap_costmodel_set(ap_workload *w, const ap_replica *replicas, uint32_t M, uint32_t B, const ap_slo *slo);
+
+/* Score C candidates.
+ *   d_assign : DEVICE pointer, uint16 [C][R] row-major; d_assign[c*R + r] is the replica of request r
+ *              under candidate c.  A value >= M is not an error: that request is rejected.
+ *   d_out    : DEVICE pointer to C ap_metrics records (8-byte aligned); only these are written.
+ *   hip_stream : a hipStream_t passed as void* (NULL = the default stream).
+ * Asynchronous: kernels are enqueued on hip_stream and the call returns without waiting.
+ * It allocates nothing.  One evaluation per workload may be in flight at a time.
+ * C == 0 is a no-op.  Errors: AP_ERR_INVALID (null pointers), AP_ERR_STATE, AP_ERR_DEVICE. */
+ap_status ap_eval_candidates(const ap_workload *w, const uint16_t *d_assign, uint32_t C, ap_metrics *d_out,
+                             void *hip_stream);
+
+/* Release the workload and its device memory.  NULL is accepted. */
+ap_status ap_workload_destroy(ap_workload *w);
+
+const char *ap_status_str(ap_status s);
+
+/* The histogram behind the p99 fields (host helpers; the device uses the same map).
+ * Bins 0..127 hold 0..127 exactly; each octave [2^e, 2^(e+1)), e >= 7, is cut into 128
+ * equal sub-bins; values >= 2^38 - 2^30 us fall in bin 4095. */
+uint32_t ap_hist_bin(uint64_t value_us);
+uint64_t ap_hist_lower(uint32_t bin);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AUTOPOIESIS_EVAL_H */

@@ -1,0 +1,124 @@
+"""ctypes binding of ``libautopoiesis_eval.so``: the same names as the C ABI
+(``include/autopoiesis_eval.h``), argument marshalling only.  Every step of the
+evaluation runs in the library's HIP kernels; PyTorch is used by callers for device
+memory and streams.  There is no fallback: a missing library raises at load time.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libautopoiesis_eval.so")
+
+AP_OK, AP_ERR_INVALID, AP_ERR_RANGE, AP_ERR_ALLOC, AP_ERR_DEVICE, AP_ERR_STATE = range(6)
+AP_MAX_SLOTS = 64
+AP_MAX_REPLICAS = 1024
+
+# numpy views of the ABI structs
+REPLICA_DTYPE = np.dtype([("prefill_base_us", "<u4"), ("prefill_per_tok_us", "<u4"), ("decode_base_us", "<u4"),
+                          ("decode_per_kctx_us", "<u4"), ("t_on_us", "<u8"), ("t_off_us", "<u8")])
+METRICS_DTYPE = np.dtype([("sum_e2e_us", "<u8"), ("sum_ttft_us", "<u8"), ("sum_tpot_us", "<u8"),
+                          ("makespan_us", "<u8"), ("p99_ttft_us", "<u8"), ("p99_tpot_us", "<u8"),
+                          ("p99_e2e_us", "<u8"), ("slo_ok", "<u4"), ("n_rejected", "<u4")])
+assert REPLICA_DTYPE.itemsize == 32 and METRICS_DTYPE.itemsize == 64
+
+
+class ApSlo(C.Structure):
+    _fields_ = [("ttft_us", C.c_uint64), ("tpot_us", C.c_uint64), ("penalty_us", C.c_uint64)]
+
+
+class ApError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {ap_status_str(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load the HIP library built in-tree; raise if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: run `python -m paper_2604_07144_amd.build` "
+                                    "(there is no CPU fallback)")
+        L = C.CDLL(LIB_PATH)
+        L.ap_workload_create.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.POINTER(C.c_void_p)]
+        L.ap_workload_create.restype = C.c_int
+        L.ap_costmodel_set.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.POINTER(ApSlo)]
+        L.ap_costmodel_set.restype = C.c_int
+        L.ap_eval_candidates.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p]
+        L.ap_eval_candidates.restype = C.c_int
+        L.ap_workload_destroy.argtypes = [C.c_void_p]
+        L.ap_workload_destroy.restype = C.c_int
+        L.ap_status_str.argtypes = [C.c_int]
+        L.ap_status_str.restype = C.c_char_p
+        L.ap_hist_bin.argtypes = [C.c_uint64]
+        L.ap_hist_bin.restype = C.c_uint32
+        L.ap_hist_lower.argtypes = [C.c_uint32]
+        L.ap_hist_lower.restype = C.c_uint64
+        _lib = L
+    return _lib
+
+
+def ap_status_str(status: int) -> str:
+    return lib().ap_status_str(int(status)).decode()
+
+
+def ap_hist_bin(value_us: int) -> int:
+    return int(lib().ap_hist_bin(int(value_us)))
+
+
+def ap_hist_lower(bin_index: int) -> int:
+    return int(lib().ap_hist_lower(int(bin_index)))
+
+
+def _check(status: int, where: str) -> None:
+    if status != AP_OK:
+        raise ApError(status, where)
+
+
+def ap_workload_create(arrival_us, prompt_len, out_len) -> int:
+    """Host arrays in, opaque workload handle out."""
+    arrival = np.ascontiguousarray(arrival_us, dtype=np.uint64)
+    prompt = np.ascontiguousarray(prompt_len, dtype=np.int32)
+    out = np.ascontiguousarray(out_len, dtype=np.int32)
+    if not (arrival.ndim == prompt.ndim == out.ndim == 1 and arrival.shape == prompt.shape == out.shape):
+        raise ValueError("arrival_us, prompt_len and out_len must be 1-D arrays of one length")
+    handle = C.c_void_p()
+    _check(lib().ap_workload_create(arrival.ctypes.data, prompt.ctypes.data, out.ctypes.data,
+                                    arrival.shape[0], C.byref(handle)), "ap_workload_create")
+    return handle.value
+
+
+def make_replicas(coef, t_on_us, t_off_us) -> np.ndarray:
+    """Pack (a, b, c, d) rows and windows into an array of ap_replica."""
+    coef = np.asarray(coef, dtype=np.uint32).reshape(-1, 4)
+    rep = np.zeros(coef.shape[0], dtype=REPLICA_DTYPE)
+    rep["prefill_base_us"], rep["prefill_per_tok_us"] = coef[:, 0], coef[:, 1]
+    rep["decode_base_us"], rep["decode_per_kctx_us"] = coef[:, 2], coef[:, 3]
+    rep["t_on_us"] = np.asarray(t_on_us, dtype=np.uint64)
+    rep["t_off_us"] = np.asarray(t_off_us, dtype=np.uint64)
+    return rep
+
+
+def ap_costmodel_set(workload: int, replicas: np.ndarray, B: int, slo_ttft_us: int, slo_tpot_us: int,
+                     penalty_us: int) -> None:
+    replicas = np.ascontiguousarray(replicas, dtype=REPLICA_DTYPE)
+    slo = ApSlo(int(slo_ttft_us), int(slo_tpot_us), int(penalty_us))
+    _check(lib().ap_costmodel_set(workload, replicas.ctypes.data, replicas.shape[0], int(B), C.byref(slo)),
+           "ap_costmodel_set")
+
+
+def ap_eval_candidates(workload: int, d_assign_ptr: int, n_candidates: int, d_out_ptr: int, stream: int = 0) -> None:
+    """Device pointers (ints) in; asynchronous on ``stream`` (a hipStream_t as int, 0 = default)."""
+    _check(lib().ap_eval_candidates(workload, C.c_void_p(d_assign_ptr), int(n_candidates), C.c_void_p(d_out_ptr),
+                                    C.c_void_p(stream)), "ap_eval_candidates")
+
+
+def ap_workload_destroy(workload: int) -> None:
+    _check(lib().ap_workload_destroy(workload), "ap_workload_destroy")

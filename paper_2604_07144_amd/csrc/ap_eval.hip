@@ -1,0 +1,590 @@
+// Candidate-assignment evaluator for MI355X (gfx950): kernels and C ABI.
+//
+// One workgroup scores one candidate at a time.  The trace is walked in time chunks;
+// for every chunk the workgroup
+//   (1) counts the chunk's requests per replica        (replica histogram, LDS atomics),
+//   (2) turns the counts into offsets                  (wavefront exclusive scans),
+//   (3) scatters request indices by replica, stably    (rank inside a wavefront by ballots),
+//   (4) replays every replica's queue segment, one wavefront per replica: the B
+//       slot-free times live one per lane and persist in LDS between chunks,
+//   (5) feeds TTFT / TPOT / E2E of every served request into LDS histograms and
+//       per-lane sums.
+// After the last chunk the histograms give the p99 values and one 64-byte record is
+// written.  Grouping by replica in arrival order is the per-instance queue order of
+// Section 8.3 (Setup); the B-slot queue is continuous batching with maximum batch size
+// b^max (Section 5.3 "Serving simulator"); the reductions are the per-request
+// objectives of Appendix "Discussion and Limitation" (adaptability to diverse serving
+// objectives).
+//
+// Time on the device is 32-bit microseconds relative to the first arrival;
+// ap_costmodel_set proves that no finish time can overflow before it enables the path.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "autopoiesis_eval.h"
+
+namespace {
+
+constexpr uint32_t kWave = 64;
+constexpr uint32_t kWaves = 16;                 // wavefronts per workgroup
+constexpr uint32_t kThreads = kWave * kWaves;   // 1024
+constexpr uint32_t kBins = 4096;
+constexpr uint32_t kMaxGroups = 4;              // 64-request groups per wavefront per chunk
+constexpr uint32_t kMaxChunk = kThreads * kMaxGroups;
+constexpr uint32_t kNever = 0xFFFFFFFFu;        // "no such time": larger than every reachable time
+constexpr uint32_t kNoKey = 0xFFFFFFFFu;
+
+struct DevReplica {
+    uint32_t a, b, c, d;      // cost coefficients
+    uint32_t t_on, t_off;     // window, relative microseconds (t_off == kNever: never leaves)
+};
+
+struct EvalParams {
+    const uint32_t* arrival;  // [R] relative microseconds
+    const uint32_t* prompt;   // [R]
+    const uint32_t* outlen;   // [R]
+    const DevReplica* rep;    // [M]
+    uint32_t R, M, B, chunk, key_bits;
+    uint32_t slo_ttft, slo_tpot;
+    uint32_t penalty_bin, k99;
+    uint64_t penalty;
+    // byte offsets into dynamic LDS
+    uint32_t off_slots, off_cnt, off_qstart, off_list, off_arr, off_prompt, off_out, off_misc;
+};
+
+// ----------------------------------------------------------------------------------
+// wavefront helpers (64 lanes)
+// ----------------------------------------------------------------------------------
+template <int kCtrl>
+__device__ __forceinline__ uint32_t dpp_move(uint32_t v) {
+    // lanes whose source is outside the row keep their own value
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, kCtrl, 0xF, 0xF, false);
+}
+
+// Minimum over the 64 lanes, returned as a wave-uniform value.
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
+    v = min(v, dpp_move<0xB1>(v));    // quad_perm [1,0,3,2]
+    v = min(v, dpp_move<0x4E>(v));    // quad_perm [2,3,0,1]
+    v = min(v, dpp_move<0x141>(v));   // row_half_mirror
+    v = min(v, dpp_move<0x140>(v));   // row_mirror: every lane of a 16-lane row holds the row minimum
+    v = min(v, (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x401F));   // lane ^ 16 within 32
+    uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)v, 0);
+    uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)v, 32);
+    return min(lo, hi);
+}
+
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v, uint32_t lane) {
+#pragma unroll
+    for (uint32_t d = 1; d < kWave; d <<= 1) {
+        uint32_t t = (uint32_t)__shfl_up((int)v, d);
+        if (lane >= d) v += t;
+    }
+    return v;
+}
+
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
+#pragma unroll
+    for (uint32_t d = 32; d >= 1; d >>= 1) v += (uint32_t)__shfl_xor((int)v, d);
+    return v;
+}
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+#pragma unroll
+    for (uint32_t d = 32; d >= 1; d >>= 1) v = max(v, (uint32_t)__shfl_xor((int)v, d));
+    return v;
+}
+
+__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v) {
+#pragma unroll
+    for (uint32_t d = 32; d >= 1; d >>= 1) v += (unsigned long long)__shfl_xor((long long)v, d);
+    return v;
+}
+
+// 4096-bin log-linear histogram map for values below 2^32.
+__device__ __forceinline__ uint32_t hist_bin_u32(uint32_t v) {
+    uint32_t e = 31u - (uint32_t)__clz((int)(v | 1u));
+    uint32_t wide = ((e - 6u) << 7) | ((v >> (e - 7u)) & 127u);
+    return v < 128u ? v : wide;
+}
+
+__device__ __forceinline__ unsigned long long hist_lower_edge(uint32_t bin) {
+    if (bin < 128u) return bin;
+    return (unsigned long long)(128u | (bin & 127u)) << ((bin >> 7) - 1u);
+}
+
+// ----------------------------------------------------------------------------------
+// the evaluation kernel
+// ----------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, const uint16_t* __restrict__ assign,
+                                                              ap_metrics* __restrict__ out, uint32_t C) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    uint32_t* hist = reinterpret_cast<uint32_t*>(lds);                        // [3][kBins]
+    uint32_t* slots = reinterpret_cast<uint32_t*>(lds + p.off_slots);         // [M][B] slot-free times
+    uint32_t* cnt = reinterpret_cast<uint32_t*>(lds + p.off_cnt);             // [kWaves][M+1]
+    uint32_t* qstart = reinterpret_cast<uint32_t*>(lds + p.off_qstart);       // [M+2]
+    uint16_t* list = reinterpret_cast<uint16_t*>(lds + p.off_list);           // [chunk] indices by replica
+    uint32_t* c_arr = reinterpret_cast<uint32_t*>(lds + p.off_arr);           // [chunk] staged trace
+    uint32_t* c_prompt = reinterpret_cast<uint32_t*>(lds + p.off_prompt);
+    uint32_t* c_out = reinterpret_cast<uint32_t*>(lds + p.off_out);
+    unsigned long long* acc64 = reinterpret_cast<unsigned long long*>(lds + p.off_misc);   // e2e, ttft, tpot
+    uint32_t* acc32 = reinterpret_cast<uint32_t*>(lds + p.off_misc + 24);     // makespan, slo_ok, n_rej, p99 bins[3]
+    uint32_t* wtot = reinterpret_cast<uint32_t*>(lds + p.off_misc + 64);      // [3][kWaves] scan carries
+
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, w = tid >> 6;
+    const uint32_t R = p.R, M = p.M, B = p.B, M1 = p.M + 1u;
+    const uint32_t per_wave = p.chunk / kWaves;       // multiple of 64
+    const uint32_t groups = per_wave / kWave;         // <= kMaxGroups
+    const unsigned long long lanes_below = (1ull << lane) - 1ull;
+
+    for (uint32_t c = blockIdx.x; c < C; c += gridDim.x) {
+        const uint16_t* row = assign + (size_t)c * R;
+
+        for (uint32_t i = tid; i < 3u * kBins; i += kThreads) hist[i] = 0u;
+        for (uint32_t i = tid; i < M * B; i += kThreads) slots[i] = 0u;
+        if (tid < 16u) reinterpret_cast<uint32_t*>(acc64)[tid] = 0u;
+        unsigned long long s_e2e = 0, s_ttft = 0, s_tpot = 0;
+        uint32_t last_fin = 0, n_ok = 0, n_rej = 0;
+        __syncthreads();
+
+        for (uint32_t r0 = 0; r0 < R; r0 += p.chunk) {
+            const uint32_t n = min(p.chunk, R - r0);
+
+            // ---- stage the chunk of the trace; read this wavefront's assignments -----------
+            for (uint32_t i = tid; i < n; i += kThreads) {
+                c_arr[i] = p.arrival[r0 + i];
+                c_prompt[i] = p.prompt[r0 + i];
+                c_out[i] = p.outlen[r0 + i];
+            }
+            for (uint32_t i = tid; i < kWaves * M1; i += kThreads) cnt[i] = 0u;
+            uint32_t key[kMaxGroups];
+#pragma unroll
+            for (uint32_t g = 0; g < kMaxGroups; ++g) {
+                uint32_t idx = w * per_wave + g * kWave + lane;
+                key[g] = (g < groups && idx < n) ? min((uint32_t)row[r0 + idx], M) : kNoKey;
+            }
+            __syncthreads();
+
+            // ---- (1) per-wavefront replica histogram ---------------------------------------
+#pragma unroll
+            for (uint32_t g = 0; g < kMaxGroups; ++g)
+                if (key[g] != kNoKey) atomicAdd(&cnt[w * M1 + key[g]], 1u);
+            __syncthreads();
+
+            // ---- (2) offsets: down the wavefronts per replica, then across replicas --------
+            for (uint32_t m = tid; m <= M; m += kThreads) {
+                uint32_t run = 0;
+                for (uint32_t ww = 0; ww < kWaves; ++ww) {
+                    uint32_t t = cnt[ww * M1 + m];
+                    cnt[ww * M1 + m] = run;
+                    run += t;
+                }
+                qstart[m] = run;
+            }
+            __syncthreads();
+            if (w == 0) {
+                uint32_t carry = 0;
+                for (uint32_t base = 0; base <= M; base += kWave) {
+                    uint32_t m = base + lane;
+                    uint32_t v = m <= M ? qstart[m] : 0u;
+                    uint32_t incl = wave_inclusive_scan(v, lane);
+                    if (m <= M) qstart[m] = carry + incl - v;
+                    carry += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+                }
+                if (lane == 0) qstart[M1] = carry;
+            }
+            __syncthreads();
+
+            // ---- (3) stable scatter: rank among equal keys of the group by ballots ---------
+#pragma unroll
+            for (uint32_t g = 0; g < kMaxGroups; ++g) {
+                if (g >= groups) break;
+                const uint32_t k = key[g];
+                unsigned long long peers = ~0ull;
+                for (uint32_t b = 0; b < p.key_bits; ++b) {
+                    bool bit = (k >> b) & 1u;
+                    unsigned long long s = __ballot(bit);
+                    peers &= bit ? s : ~s;
+                }
+                if (k < M) {
+                    uint32_t rank = __popcll(peers & lanes_below);
+                    uint32_t total = __popcll(peers);
+                    uint32_t base = qstart[k] + cnt[w * M1 + k];
+                    list[base + rank] = (uint16_t)(w * per_wave + g * kWave + lane);
+                    if (rank + 1u == total) cnt[w * M1 + k] += total;
+                } else if (k == M) {
+                    n_rej += 1u;        // replica id outside the table
+                }
+            }
+            __syncthreads();
+
+            // ---- (4)+(5) replay: one wavefront per replica, lanes = slots / requests ------
+            for (uint32_t m = w; m < M; m += kWaves) {
+                const uint32_t qs = qstart[m];
+                const uint32_t qn = qstart[m + 1] - qs;
+                if (qn == 0) continue;
+                const DevReplica rp = p.rep[m];
+                uint32_t S = lane < B ? slots[m * B + lane] : kNever;
+                for (uint32_t sb = 0; sb < qn; sb += kWave) {
+                    const uint32_t nb = min(kWave, qn - sb);
+                    const bool valid = lane < nb;
+                    const uint32_t li = valid ? (uint32_t)list[qs + sb + lane] : 0u;
+                    const uint32_t arr = c_arr[li], prm = c_prompt[li], ol = c_out[li];
+                    const uint32_t now = max(arr, rp.t_on);
+                    const uint32_t prefill = rp.a + rp.b * prm;
+                    const uint32_t tpot = rp.c + rp.d * ((prm + 1023u) >> 10);
+                    const uint32_t dec = ol * tpot;
+                    const uint32_t svc = prefill + dec;
+                    // requests are in arrival order, so those arriving inside the window are a prefix
+                    const uint32_t n_open = __popcll(__ballot(valid && now < rp.t_off));
+                    uint32_t start = now;
+                    uint32_t j = 0;
+                    while (j < n_open) {
+                        const uint32_t now_j = (uint32_t)__builtin_amdgcn_readlane((int)now, (int)j);
+                        const unsigned long long idle = __ballot(S <= now_j);
+                        const uint32_t n_idle = __popcll(idle);
+                        if (n_idle == 0) {
+                            // every slot busy: the request takes the earliest-free one
+                            const uint32_t u = wave_min_u32(S);
+                            if (u >= rp.t_off) break;
+                            const uint32_t fin_j = u + (uint32_t)__builtin_amdgcn_readlane((int)svc, (int)j);
+                            const uint32_t sl = (uint32_t)__ffsll((long long)__ballot(S == u)) - 1u;
+                            if (lane == sl) S = fin_j;
+                            if (lane == j) start = u;
+                            j += 1u;
+                        } else {
+                            // n_idle slots are free now and stay free: the next n_idle requests start on arrival
+                            const uint32_t g = min(n_idle, n_open - j);
+                            const uint32_t ri = __popcll(idle & lanes_below);
+                            const uint32_t fin = now + svc;
+                            const uint32_t take = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(((j + ri) & 63u) << 2), (int)fin);
+                            if (((idle >> lane) & 1ull) && ri < g) S = take;
+                            j += g;
+                        }
+                    }
+                    const bool served = lane < j;
+                    if (served) {
+                        const uint32_t ttft = start - arr + prefill;
+                        const uint32_t e2e = ttft + dec;
+                        atomicAdd(&hist[hist_bin_u32(ttft)], 1u);
+                        atomicAdd(&hist[kBins + hist_bin_u32(tpot)], 1u);
+                        atomicAdd(&hist[2u * kBins + hist_bin_u32(e2e)], 1u);
+                        s_ttft += ttft;
+                        s_e2e += e2e;
+                        s_tpot += tpot;
+                        last_fin = max(last_fin, start + svc);
+                        n_ok += (ttft <= p.slo_ttft && tpot <= p.slo_tpot) ? 1u : 0u;
+                    } else if (valid) {
+                        n_rej += 1u;    // replica gone before the request could start
+                    }
+                }
+                if (lane < B) slots[m * B + lane] = S;
+            }
+            __syncthreads();
+        }
+
+        // ---- per-candidate reductions -------------------------------------------------------
+        s_e2e = wave_sum_u64(s_e2e);
+        s_ttft = wave_sum_u64(s_ttft);
+        s_tpot = wave_sum_u64(s_tpot);
+        last_fin = wave_max_u32(last_fin);
+        n_ok = wave_sum_u32(n_ok);
+        n_rej = wave_sum_u32(n_rej);
+        if (lane == 0) {
+            atomicAdd(&acc64[0], s_e2e);
+            atomicAdd(&acc64[1], s_ttft);
+            atomicAdd(&acc64[2], s_tpot);
+            atomicMax(&acc32[0], last_fin);
+            atomicAdd(&acc32[1], n_ok);
+            atomicAdd(&acc32[2], n_rej);
+        }
+        __syncthreads();
+        const uint32_t rejected = acc32[2];
+        if (tid < 3u && rejected) hist[tid * kBins + p.penalty_bin] += rejected;
+        __syncthreads();
+
+        // p99: block-wide prefix sum over the bins, 4 bins per thread, three histograms at once
+        uint32_t part[3], incl[3];
+#pragma unroll
+        for (uint32_t h = 0; h < 3u; ++h) {
+            const uint32_t* hb = hist + h * kBins + 4u * tid;
+            part[h] = hb[0] + hb[1] + hb[2] + hb[3];
+            incl[h] = wave_inclusive_scan(part[h], lane);
+            if (lane == 63u) wtot[h * kWaves + w] = incl[h];
+        }
+        __syncthreads();
+#pragma unroll
+        for (uint32_t h = 0; h < 3u; ++h) {
+            uint32_t before = 0;
+            for (uint32_t ww = 0; ww < w; ++ww) before += wtot[h * kWaves + ww];
+            uint32_t hi = before + incl[h], lo = hi - part[h];
+            if (lo < p.k99 && p.k99 <= hi) {
+                const uint32_t* hb = hist + h * kBins + 4u * tid;
+                uint32_t run = lo, b = 0;
+                for (; b < 3u; ++b) {
+                    run += hb[b];
+                    if (run >= p.k99) break;
+                }
+                acc32[3 + h] = 4u * tid + b;
+            }
+        }
+        __syncthreads();
+        if (tid == 0) {
+            ap_metrics mt;
+            mt.sum_e2e_us = acc64[0] + (unsigned long long)rejected * p.penalty;
+            mt.sum_ttft_us = acc64[1] + (unsigned long long)rejected * p.penalty;
+            mt.sum_tpot_us = acc64[2] + (unsigned long long)rejected * p.penalty;
+            mt.makespan_us = acc32[0];
+            mt.p99_ttft_us = hist_lower_edge(acc32[3]);
+            mt.p99_tpot_us = hist_lower_edge(acc32[4]);
+            mt.p99_e2e_us = hist_lower_edge(acc32[5]);
+            mt.slo_ok = acc32[1];
+            mt.n_rejected = rejected;
+            out[c] = mt;
+        }
+        __syncthreads();
+    }
+}
+
+// ----------------------------------------------------------------------------------
+// host side
+// ----------------------------------------------------------------------------------
+inline uint32_t align_up(uint32_t v, uint32_t a) { return (v + a - 1u) / a * a; }
+
+// LDS layout for a given chunk size; returns total bytes.
+uint32_t plan_lds(EvalParams& p, uint32_t chunk) {
+    uint32_t off = 3u * kBins * 4u;
+    p.off_slots = off;  off += align_up(p.M * p.B * 4u, 16u);
+    p.off_cnt = off;    off += align_up(kWaves * (p.M + 1u) * 4u, 16u);
+    p.off_qstart = off; off += align_up((p.M + 2u) * 4u, 16u);
+    p.off_list = off;   off += align_up(chunk * 2u, 16u);
+    p.off_arr = off;    off += chunk * 4u;
+    p.off_prompt = off; off += chunk * 4u;
+    p.off_out = off;    off += chunk * 4u;
+    p.off_misc = off;   off += 64u + 3u * kWaves * 4u;
+    p.chunk = chunk;
+    return off;
+}
+
+}  // namespace
+
+struct ap_workload {
+    int device = 0;
+    uint32_t R = 0;
+    uint64_t base_us = 0;             // first arrival
+    uint64_t span_us = 0;             // last arrival - first arrival
+    std::vector<int32_t> h_prompt, h_out;
+    uint32_t* d_arrival = nullptr;
+    uint32_t* d_prompt = nullptr;
+    uint32_t* d_out = nullptr;
+    DevReplica* d_rep = nullptr;      // capacity AP_MAX_REPLICAS
+    bool has_model = false;
+    EvalParams params{};
+    uint32_t lds_bytes = 0;
+    uint32_t max_grid = 0;
+};
+
+extern "C" {
+
+const char* ap_status_str(ap_status s) {
+    switch (s) {
+        case AP_OK: return "ok";
+        case AP_ERR_INVALID: return "invalid argument";
+        case AP_ERR_RANGE: return "capacity of the device path exceeded";
+        case AP_ERR_ALLOC: return "allocation failed";
+        case AP_ERR_DEVICE: return "HIP call failed";
+        case AP_ERR_STATE: return "no cost model set";
+    }
+    return "unknown status";
+}
+
+uint32_t ap_hist_bin(uint64_t v) {
+    if (v < 128u) return (uint32_t)v;
+    uint32_t e = 0;
+    for (uint64_t t = v; t > 1u; t >>= 1) ++e;         // floor(log2 v)
+    if (e > 37u) return kBins - 1u;
+    return ((e - 6u) << 7) | (uint32_t)((v >> (e - 7u)) & 127u);
+}
+
+uint64_t ap_hist_lower(uint32_t bin) {
+    if (bin < 128u) return bin;
+    return (uint64_t)(128u | (bin & 127u)) << ((bin >> 7) - 1u);
+}
+
+ap_status ap_workload_create(const uint64_t* arrival_us, const int32_t* prompt_len, const int32_t* out_len,
+                             uint32_t R, ap_workload** out) {
+    if (!arrival_us || !prompt_len || !out_len || !out || R == 0) return AP_ERR_INVALID;
+    for (uint32_t r = 0; r < R; ++r) {
+        if (prompt_len[r] < 1 || out_len[r] < 1) return AP_ERR_INVALID;
+        if (r && arrival_us[r] < arrival_us[r - 1]) return AP_ERR_INVALID;
+    }
+    ap_workload* w = new (std::nothrow) ap_workload;
+    if (!w) return AP_ERR_ALLOC;
+    std::vector<uint32_t> rel;
+    try {
+        w->h_prompt.assign(prompt_len, prompt_len + R);
+        w->h_out.assign(out_len, out_len + R);
+        rel.resize(R);
+    } catch (const std::bad_alloc&) {
+        delete w;
+        return AP_ERR_ALLOC;
+    }
+    w->R = R;
+    w->base_us = arrival_us[0];
+    w->span_us = arrival_us[R - 1] - arrival_us[0];
+    // relative 32-bit arrivals; a span that does not fit is refused later by ap_costmodel_set
+    for (uint32_t r = 0; r < R; ++r) rel[r] = (uint32_t)std::min<uint64_t>(arrival_us[r] - w->base_us, kNever);
+
+    ap_status st = AP_OK;
+    if (hipGetDevice(&w->device) != hipSuccess) st = AP_ERR_DEVICE;
+    const size_t bytes = (size_t)R * 4u;
+    if (st == AP_OK && (hipMalloc(&w->d_arrival, bytes) != hipSuccess || hipMalloc(&w->d_prompt, bytes) != hipSuccess ||
+                        hipMalloc(&w->d_out, bytes) != hipSuccess ||
+                        hipMalloc(&w->d_rep, sizeof(DevReplica) * AP_MAX_REPLICAS) != hipSuccess))
+        st = AP_ERR_ALLOC;
+    if (st == AP_OK && (hipMemcpy(w->d_arrival, rel.data(), bytes, hipMemcpyHostToDevice) != hipSuccess ||
+                        hipMemcpy(w->d_prompt, prompt_len, bytes, hipMemcpyHostToDevice) != hipSuccess ||
+                        hipMemcpy(w->d_out, out_len, bytes, hipMemcpyHostToDevice) != hipSuccess))
+        st = AP_ERR_DEVICE;
+    if (st != AP_OK) {
+        (void)hipGetLastError();
+        ap_workload_destroy(w);
+        return st;
+    }
+    *out = w;
+    return AP_OK;
+}
+
+ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t M, uint32_t B, const ap_slo* slo) {
+    if (!w || !replicas || !slo || M == 0 || B == 0) return AP_ERR_INVALID;
+    for (uint32_t m = 0; m < M; ++m)
+        if (replicas[m].t_on_us > replicas[m].t_off_us) return AP_ERR_INVALID;
+    if (M > AP_MAX_REPLICAS || B > AP_MAX_SLOTS) return AP_ERR_RANGE;
+
+    // ---- range proof for 32-bit relative time ------------------------------------------
+    // Every start is at most max(latest arrival, latest t_on of a replica that can serve)
+    // plus the total of all earlier service on that replica; bound the latter by the sum
+    // over requests of their largest service time on any replica.
+    const uint64_t limit = (uint64_t)kNever - 1u;
+    uint64_t latest = w->span_us;
+    for (uint32_t m = 0; m < M; ++m) {
+        const ap_replica& rp = replicas[m];
+        if (rp.t_on_us >= rp.t_off_us || rp.t_on_us <= w->base_us) continue;   // never serves / already on
+        latest = std::max(latest, rp.t_on_us - w->base_us);
+    }
+    if (latest > limit) return AP_ERR_RANGE;
+    // distinct coefficient sets
+    std::vector<const ap_replica*> kinds;
+    for (uint32_t m = 0; m < M; ++m) {
+        bool seen = false;
+        for (const ap_replica* k : kinds)
+            seen = seen || (k->prefill_base_us == replicas[m].prefill_base_us &&
+                            k->prefill_per_tok_us == replicas[m].prefill_per_tok_us &&
+                            k->decode_base_us == replicas[m].decode_base_us &&
+                            k->decode_per_kctx_us == replicas[m].decode_per_kctx_us);
+        if (!seen) kinds.push_back(&replicas[m]);
+    }
+    uint64_t total = latest;
+    for (uint32_t r = 0; r < w->R; ++r) {
+        const uint64_t prompt = (uint64_t)w->h_prompt[r], outl = (uint64_t)w->h_out[r];
+        uint64_t worst = 0;
+        for (const ap_replica* k : kinds) {
+            // each term stays far below 2^64: coefficients < 2^32, lengths < 2^31
+            uint64_t prefill = (uint64_t)k->prefill_base_us + (uint64_t)k->prefill_per_tok_us * prompt;
+            uint64_t tpot = (uint64_t)k->decode_base_us + (uint64_t)k->decode_per_kctx_us * ((prompt + 1023u) >> 10);
+            if (tpot > limit || prefill > limit) return AP_ERR_RANGE;
+            uint64_t svc = prefill + outl * tpot;
+            worst = std::max(worst, svc);
+        }
+        total += worst;
+        if (total > limit) return AP_ERR_RANGE;
+    }
+
+    // ---- LDS plan: the largest chunk that fits ------------------------------------------
+    if (hipSetDevice(w->device) != hipSuccess) return AP_ERR_DEVICE;
+    int lds_cap = 0, n_cu = 0;
+    if (hipDeviceGetAttribute(&lds_cap, hipDeviceAttributeMaxSharedMemoryPerBlock, w->device) != hipSuccess ||
+        hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, w->device) != hipSuccess)
+        return AP_ERR_DEVICE;
+    EvalParams p{};
+    p.M = M;
+    p.B = B;
+    uint32_t bytes = 0, chunk = kMaxChunk;
+    for (; chunk >= kThreads; chunk -= kThreads) {
+        bytes = plan_lds(p, chunk);
+        if (bytes <= (uint32_t)lds_cap) break;
+    }
+    if (chunk < kThreads) return AP_ERR_RANGE;
+
+    std::vector<DevReplica> dev(M);
+    for (uint32_t m = 0; m < M; ++m) {
+        const ap_replica& rp = replicas[m];
+        DevReplica& d = dev[m];
+        d.a = rp.prefill_base_us;
+        d.b = rp.prefill_per_tok_us;
+        d.c = rp.decode_base_us;
+        d.d = rp.decode_per_kctx_us;
+        if (rp.t_on_us >= rp.t_off_us || rp.t_off_us <= w->base_us) {
+            d.t_on = 0;      // the window is empty or closed before the trace: nothing is ever served
+            d.t_off = 0;
+        } else {
+            d.t_on = rp.t_on_us <= w->base_us ? 0u : (uint32_t)(rp.t_on_us - w->base_us);
+            d.t_off = (uint32_t)std::min<uint64_t>(rp.t_off_us - w->base_us, kNever);
+        }
+    }
+    if (hipMemcpy(w->d_rep, dev.data(), sizeof(DevReplica) * M, hipMemcpyHostToDevice) != hipSuccess ||
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&k_eval_candidates),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        w->has_model = false;     // the replica table on the device may be half-written
+        return AP_ERR_DEVICE;
+    }
+
+    p.arrival = w->d_arrival;
+    p.prompt = w->d_prompt;
+    p.outlen = w->d_out;
+    p.rep = w->d_rep;
+    p.R = w->R;
+    p.key_bits = 0;
+    while ((M >> p.key_bits) != 0u) ++p.key_bits;       // bits needed for the values 0..M
+    p.slo_ttft = (uint32_t)std::min<uint64_t>(slo->ttft_us, kNever);
+    p.slo_tpot = (uint32_t)std::min<uint64_t>(slo->tpot_us, kNever);
+    p.penalty = slo->penalty_us;
+    p.penalty_bin = ap_hist_bin(slo->penalty_us);
+    p.k99 = (uint32_t)((99ull * w->R + 99ull) / 100ull);
+    w->params = p;
+    w->lds_bytes = bytes;
+    w->max_grid = (uint32_t)n_cu * 4u;
+    w->has_model = true;
+    return AP_OK;
+}
+
+ap_status ap_eval_candidates(const ap_workload* w, const uint16_t* d_assign, uint32_t C, ap_metrics* d_out,
+                             void* hip_stream) {
+    if (!w) return AP_ERR_INVALID;
+    if (!w->has_model) return AP_ERR_STATE;
+    if (C == 0) return AP_OK;
+    if (!d_assign || !d_out) return AP_ERR_INVALID;
+    const uint32_t grid = std::min(C, w->max_grid);
+    hipLaunchKernelGGL(k_eval_candidates, dim3(grid), dim3(kThreads), w->lds_bytes,
+                       static_cast<hipStream_t>(hip_stream), w->params, d_assign, d_out, C);
+    if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
+    return AP_OK;
+}
+
+ap_status ap_workload_destroy(ap_workload* w) {
+    if (!w) return AP_OK;
+    bool ok = true;
+    if (w->d_arrival) ok = (hipFree(w->d_arrival) == hipSuccess) && ok;
+    if (w->d_prompt) ok = (hipFree(w->d_prompt) == hipSuccess) && ok;
+    if (w->d_out) ok = (hipFree(w->d_out) == hipSuccess) && ok;
+    if (w->d_rep) ok = (hipFree(w->d_rep) == hipSuccess) && ok;
+    delete w;
+    return ok ? AP_OK : AP_ERR_DEVICE;
+}
+
+}  // extern "C"

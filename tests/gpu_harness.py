@@ -1,0 +1,75 @@
+"""Shared plumbing for the GPU parity tests: run rows through the C ABI and through the
+oracle, compare byte for byte.  (Not a test module.)"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import Oracle
+from paper_2604_07144_amd import binding
+
+
+class GpuWorkload:
+    """A workload handle of the HIP library with its cost model set from a Trace."""
+
+    def __init__(self, tr, **override):
+        kw = dict(B=tr.B, slo_ttft_us=tr.slo_ttft_us, slo_tpot_us=tr.slo_tpot_us, penalty_us=tr.penalty_us,
+                  coef=tr.coef, t_on_us=tr.t_on_us, t_off_us=tr.t_off_us)
+        kw.update(override)
+        self.R = tr.R
+        self.handle = binding.ap_workload_create(tr.arrival_us, tr.prompt_len, tr.out_len)
+        try:
+            binding.ap_costmodel_set(self.handle, binding.make_replicas(kw["coef"], kw["t_on_us"], kw["t_off_us"]),
+                                     kw["B"], kw["slo_ttft_us"], kw["slo_tpot_us"], kw["penalty_us"])
+        except Exception:
+            self.close()
+            raise
+
+    def eval_device(self, d_assign: torch.Tensor, d_out: torch.Tensor | None = None) -> torch.Tensor:
+        """d_assign: CUDA tensor [C, R] of 2-byte elements.  Returns the CUDA result tensor [C, 8] int64."""
+        assert d_assign.is_cuda and d_assign.element_size() == 2 and d_assign.is_contiguous()
+        assert d_assign.shape[1] == self.R
+        C = d_assign.shape[0]
+        if d_out is None:
+            d_out = torch.full((C, 8), -1, dtype=torch.int64, device=d_assign.device)
+        binding.ap_eval_candidates(self.handle, d_assign.data_ptr(), C, d_out.data_ptr(),
+                                   torch.cuda.current_stream().cuda_stream)
+        return d_out
+
+    def eval(self, rows: np.ndarray) -> np.ndarray:
+        rows = np.ascontiguousarray(rows, dtype=np.uint16)
+        d_assign = torch.from_numpy(rows.view(np.int16)).cuda()
+        d_out = self.eval_device(d_assign)
+        torch.cuda.synchronize()
+        return to_records(d_out)
+
+    def close(self):
+        if self.handle is not None:
+            binding.ap_workload_destroy(self.handle)
+            self.handle = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+
+def to_records(d_out: torch.Tensor) -> np.ndarray:
+    return d_out.cpu().numpy().view(binding.METRICS_DTYPE).reshape(-1)
+
+
+def oracle_for(tr, **override) -> Oracle:
+    return Oracle.from_trace(tr, **override)
+
+
+def assert_same(got: np.ndarray, want: np.ndarray, what: str = "") -> None:
+    """Bit-exact comparison of metric records; on failure name the first differing row and fields."""
+    assert got.shape == want.shape, (what, got.shape, want.shape)
+    if got.tobytes() == want.tobytes():
+        return
+    for c in range(got.shape[0]):
+        if got[c] != want[c]:
+            diff = {n: (int(got[c][n]), int(want[c][n])) for n in got.dtype.names if got[c][n] != want[c][n]}
+            raise AssertionError(f"{what}: row {c} differs (gpu, oracle): {diff}")
+    raise AssertionError(f"{what}: records differ in padding only")

@@ -1,0 +1,241 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle, bit for bit.
+
+Integer path, so the bar is byte equality of the 64-byte records.  Small cases compare
+every candidate; the full-size configurations run every candidate on the GPU, in the
+launch configuration the benchmark times, and compare a sample of rows that the oracle
+computes one by one.
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+from paper_2604_07144_amd import binding, traces          # noqa: E402
+from tests.gpu_harness import GpuWorkload, assert_same, oracle_for, to_records   # noqa: E402
+
+U64MAX = 0xFFFFFFFFFFFFFFFF
+STD, FAST, SLOW = traces.COEF_STANDARD, traces.COEF_FAST, traces.COEF_SLOW
+
+
+def both(tr, rows, what, **override):
+    with GpuWorkload(tr, **override) as g:
+        got = g.eval(rows)
+    want = oracle_for(tr, **override).eval_batch(rows, nthreads=8)
+    assert_same(got, want, what)
+    return got
+
+
+# ------------------------------------------------------------------ hand-worked trace
+def test_hand_worked_trace_on_gpu():
+    tr = traces.custom_trace([0, 1000, 1500, 2000], [100, 1024, 1025, 16], [10, 100, 1, 20], [STD], B=2)
+    got = both(tr, np.zeros((1, 4), np.uint16), "hand base")
+    assert (int(got["sum_e2e_us"][0]), int(got["sum_ttft_us"][0]), int(got["makespan_us"][0])) == (25240, 21305, 10358)
+    assert (int(got["p99_ttft_us"][0]), int(got["p99_tpot_us"][0]), int(got["p99_e2e_us"][0])) == (7744, 35, 8320)
+    both(tr, np.zeros((1, 4), np.uint16), "hand B=1", B=1)
+    both(tr, np.zeros((1, 4), np.uint16), "hand t_on", t_on_us=[3000])
+    both(tr, np.zeros((1, 4), np.uint16), "hand t_off", t_off_us=[5000], penalty_us=1_000_000)
+    both(tr, np.zeros((1, 4), np.uint16), "hand tight slo", slo_ttft_us=6000, slo_tpot_us=30)
+
+
+# ------------------------------------------------------------------ brute force, tiny
+@pytest.mark.parametrize("R,M,B", [(8, 3, 1), (8, 3, 2), (7, 2, 3), (6, 3, 8)])
+def test_all_assignments_of_tiny_instances(R, M, B):
+    rng = np.random.default_rng(100 + R + M + B)
+    arrival = np.cumsum(rng.integers(0, 3000, R)).astype(np.uint64)
+    tr = traces.custom_trace(arrival, rng.integers(1, 3000, R), rng.integers(1, 200, R), [STD, FAST, SLOW][:M],
+                             [0, 4000, 0][:M], [U64MAX, U64MAX, 9000][:M], B=B, penalty_us=5_000_000)
+    rows = np.array(list(itertools.product(range(M), repeat=R)), dtype=np.uint16)
+    both(tr, rows, f"brute R={R} M={M} B={B}")
+
+
+# ------------------------------------------------------------------ crafted edge traces
+def _mk(n, M, B, gap, seed, coef=None, t_on=None, t_off=None, ties=False, **kw):
+    rng = np.random.default_rng(seed)
+    gaps = rng.integers(0, gap + 1, n)
+    if ties:
+        gaps[rng.random(n) < 0.5] = 0                       # many equal arrival times
+    arrival = (np.cumsum(gaps) + 1_000_000_007).astype(np.uint64)   # first arrival is not 0
+    coef = coef or [[STD, FAST, SLOW][m % 3] for m in range(M)]
+    return traces.custom_trace(arrival, rng.integers(1, 6000, n), rng.integers(1, 500, n), coef, t_on, t_off, B=B, **kw)
+
+
+def _rows(C, R, hi, seed):
+    return np.random.default_rng(seed).integers(0, hi, size=(C, R)).astype(np.uint16)
+
+
+@pytest.mark.parametrize("name,n,M,B,gap,C", [
+    ("saturated_b1", 3000, 3, 1, 500, 12),            # single slot, long queues
+    ("saturated_b8", 5000, 4, 8, 300, 12),            # spans two time chunks, ragged tail
+    ("saturated_b64", 9000, 2, 64, 40, 8),            # every slot busy, state carried over three chunks
+    ("saturated_b33", 4500, 5, 33, 100, 8),           # B neither a power of two nor a row multiple
+    ("light_b64", 6000, 64, 64, 4000, 8),             # nobody waits
+    ("ties", 2500, 6, 4, 800, 10),
+    ("one_request", 1, 1, 1, 10, 3),
+    ("b_exceeds_r", 40, 3, 64, 100, 6),
+    ("m512_b8", 4200, 512, 8, 50, 4),                 # many replicas: most queues empty
+    ("exact_chunk", 4096, 7, 16, 600, 6),             # R equal to one full chunk
+    ("chunk_plus_one", 4097, 7, 16, 600, 6),
+])
+def test_crafted_traces(name, n, M, B, gap, C):
+    tr = _mk(n, M, B, gap, seed=len(name) * 7 + n, ties=(name == "ties"))
+    both(tr, _rows(C, n, M, seed=n + M), name)
+
+
+def test_all_requests_on_one_replica_and_empty_replicas():
+    tr = _mk(5000, 9, 16, 200, seed=3)
+    rows = np.zeros((4, 5000), np.uint16)
+    rows[1] = 8
+    rows[2, ::2] = 4
+    rows[3] = np.random.default_rng(0).integers(0, 2, 5000) * 7
+    both(tr, rows, "one replica")
+
+
+def test_invalid_replica_ids_are_rejected():
+    tr = _mk(3000, 5, 4, 400, seed=9, penalty_us=12_345_678)
+    rows = _rows(6, 3000, 9, seed=4)                  # ids 5..8 do not exist
+    rows[5] = 65535
+    got = both(tr, rows, "invalid ids")
+    assert int(got["n_rejected"][5]) == 3000 and int(got["makespan_us"][5]) == 0
+
+
+def test_availability_windows():
+    n, M = 6000, 12
+    base = _mk(n, M, 8, 300, seed=21)
+    span = int(base.arrival_us[-1] - base.arrival_us[0])
+    a0 = int(base.arrival_us[0])
+    rng = np.random.default_rng(8)
+    xy = rng.integers(0, span + 1, size=(M, 2)) + a0
+    t_on, t_off = xy.min(1).astype(np.uint64), xy.max(1).astype(np.uint64)
+    t_on[0], t_off[0] = 0, a0                                      # closed before the trace starts
+    t_on[1], t_off[1] = a0 + span + 5, U64MAX                      # opens after the last arrival: all wait
+    t_on[2], t_off[2] = a0 + span // 2, a0 + span // 2             # empty window
+    t_on[3], t_off[3] = 0, U64MAX
+    t_on[4], t_off[4] = a0 + 10, a0 + 11                           # one microsecond
+    tr = _mk(n, M, 8, 300, seed=21, t_on=t_on, t_off=t_off, penalty_us=900_000_000)
+    both(tr, _rows(10, n, M, seed=5), "windows")
+    both(tr, _rows(4, n, M, seed=6), "windows B=64", B=64)
+
+
+def test_slo_variants_and_small_penalty():
+    tr = _mk(4000, 4, 6, 900, seed=33)
+    rows = _rows(6, 4000, 5, seed=2)
+    both(tr, rows, "tight tpot", slo_tpot_us=30)
+    both(tr, rows, "tight ttft", slo_ttft_us=2500)
+    both(tr, rows, "huge slo", slo_ttft_us=2**40, slo_tpot_us=2**40)
+    both(tr, rows, "zero slo", slo_ttft_us=0, slo_tpot_us=0)
+    both(tr, rows, "small penalty", penalty_us=5)
+    both(tr, rows, "huge penalty", penalty_us=2**40 + 12345)
+
+
+def test_results_do_not_depend_on_batch_composition():
+    tr = traces.make_trace(1, C=40, R=4096, rate_scale=60.0)
+    rows = tr.assignment_rows(0, 40)
+    with GpuWorkload(tr, B=4) as g:
+        whole = g.eval(rows)
+        perm = np.random.default_rng(0).permutation(40)
+        assert_same(g.eval(rows[perm]), whole[perm], "permuted batch")
+        assert_same(g.eval(rows[7:8]), whole[7:8], "single row")
+        assert_same(g.eval(rows), whole, "second call on the same workload")
+    assert_same(whole, oracle_for(tr, B=4).eval_batch(rows, nthreads=8), "cfg1 saturated")
+
+
+def test_cost_model_can_be_replaced():
+    tr = _mk(3000, 3, 4, 500, seed=77)
+    rows = _rows(5, 3000, 3, seed=1)
+    with GpuWorkload(tr) as g:
+        first = g.eval(rows)
+        binding.ap_costmodel_set(g.handle, binding.make_replicas([SLOW, SLOW, FAST], [0] * 3, [U64MAX] * 3), 2,
+                                 400_000, 40, 1_000_000)
+        second = g.eval(rows)
+    assert_same(first, oracle_for(tr).eval_batch(rows), "before swap")
+    assert_same(second, oracle_for(tr, coef=[SLOW, SLOW, FAST], B=2, slo_ttft_us=400_000, slo_tpot_us=40,
+                                   penalty_us=1_000_000).eval_batch(rows), "after swap")
+
+
+def test_error_paths():
+    tr = _mk(100, 2, 2, 100, seed=1)
+    with pytest.raises(binding.ApError) as e:
+        binding.ap_workload_create(tr.arrival_us[::-1].copy(), tr.prompt_len, tr.out_len)      # unsorted
+    assert e.value.status == binding.AP_ERR_INVALID
+    with pytest.raises(binding.ApError) as e:
+        binding.ap_workload_create(tr.arrival_us, np.zeros(100, np.int32), tr.out_len)         # prompt 0
+    assert e.value.status == binding.AP_ERR_INVALID
+    h = binding.ap_workload_create(tr.arrival_us, tr.prompt_len, tr.out_len)
+    try:
+        d = torch.zeros((1, 100), dtype=torch.int16, device="cuda")
+        o = torch.zeros((1, 8), dtype=torch.int64, device="cuda")
+        with pytest.raises(binding.ApError) as e:
+            binding.ap_eval_candidates(h, d.data_ptr(), 1, o.data_ptr(), 0)                    # no cost model yet
+        assert e.value.status == binding.AP_ERR_STATE
+        rep = binding.make_replicas([STD, STD], [0, 0], [U64MAX, U64MAX])
+        for bad_B in (0, 65):
+            with pytest.raises(binding.ApError):
+                binding.ap_costmodel_set(h, rep, bad_B, 1, 1, 1)
+        with pytest.raises(binding.ApError) as e:                                              # t_on > t_off
+            binding.ap_costmodel_set(h, binding.make_replicas([STD], [5], [4]), 2, 1, 1, 1)
+        assert e.value.status == binding.AP_ERR_INVALID
+        with pytest.raises(binding.ApError) as e:                                              # 32-bit horizon
+            binding.ap_costmodel_set(h, binding.make_replicas([(4_000_000_000, 3, 25, 5)], [0], [U64MAX]), 2, 1, 1, 1)
+        assert e.value.status == binding.AP_ERR_RANGE
+        with pytest.raises(binding.ApError) as e:                                              # slot state > LDS
+            binding.ap_costmodel_set(h, binding.make_replicas([STD] * 1024, [0] * 1024, [U64MAX] * 1024), 64, 1, 1, 1)
+        assert e.value.status == binding.AP_ERR_RANGE
+        binding.ap_costmodel_set(h, rep, 2, 500_000, 50_000, 1_000_000)
+        binding.ap_eval_candidates(h, d.data_ptr(), 0, o.data_ptr(), 0)                        # C == 0: no-op
+        with pytest.raises(binding.ApError) as e:
+            binding.ap_eval_candidates(h, 0, 1, o.data_ptr(), 0)
+        assert e.value.status == binding.AP_ERR_INVALID
+        binding.ap_eval_candidates(h, d.data_ptr(), 1, o.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert_same(to_records(o), oracle_for(tr).eval_batch(np.zeros((1, 100), np.uint16)), "after errors")
+    finally:
+        binding.ap_workload_destroy(h)
+
+
+# ------------------------------------------------------------------ the five configurations
+@pytest.mark.parametrize("cfg", [0, 1])
+def test_small_configurations_every_row(cfg):
+    tr = traces.make_trace(cfg)
+    rows = tr.assignment_rows(0, tr.C)
+    both(tr, rows, tr.spec.name)
+
+
+@pytest.mark.parametrize("cfg,n_check", [(2, 192), (3, 128), (4, 48)])
+def test_full_size_configurations_sampled_rows(cfg, n_check):
+    """All C rows run on the GPU at full size (rows uploaded in slabs); the oracle scores a
+    spread of them one by one."""
+    tr = traces.make_trace(cfg)
+    C, R = tr.C, tr.R
+    d_assign = torch.empty((C, R), dtype=torch.int16, device="cuda")
+    slab = 512
+    for lo in range(0, C, slab):
+        hi = min(C, lo + slab)
+        d_assign[lo:hi] = torch.from_numpy(tr.assignment_rows(lo, hi).view(np.int16)).cuda()
+    with GpuWorkload(tr) as g:
+        d_out = g.eval_device(d_assign)
+        torch.cuda.synchronize()
+        got = to_records(d_out)
+    pick = np.unique(np.concatenate([[0, 1, C // 2 - 1, C // 2, C - 2, C - 1],
+                                     np.random.default_rng(cfg).integers(0, C, n_check)]))
+    rows = np.stack([tr.assignment_row(int(c)) for c in pick])
+    want = oracle_for(tr).eval_batch(rows, nthreads=16)
+    assert_same(got[pick], want, tr.spec.name)
+    # properties that hold for every row at any size
+    assert ((got["n_rejected"] <= R) & (got["slo_ok"] <= R - got["n_rejected"])).all()
+    assert (got["sum_e2e_us"] >= got["sum_ttft_us"]).all()
+    assert (got["p99_e2e_us"] >= got["p99_ttft_us"]).all()
+    if cfg != 3:
+        assert (got["n_rejected"] == 0).all()
+
+
+@pytest.mark.parametrize("cfg", [3, 4])
+def test_saturated_variants_reduced(cfg):
+    """Arrival rate x100 on a reduced number of candidates: queues really form."""
+    tr = traces.make_trace(cfg, C=24, rate_scale=100.0)
+    rows = tr.assignment_rows(0, 24)
+    got = both(tr, rows, tr.spec.name + " x100")
+    nominal = oracle_for(tr, B=64).eval_batch(rows[:1])            # sanity: the variant does queue
+    assert int(got["sum_ttft_us"][0]) >= int(nominal["sum_ttft_us"][0])
