@@ -117,11 +117,230 @@ __device__ __forceinline__ unsigned long long hist_lower_edge(uint32_t bin) {
     return (unsigned long long)(128u | (bin & 127u)) << ((bin >> 7) - 1u);
 }
 
+// Block-wide end of one candidate: fold the per-lane sums, add the rejected requests at the
+// penalty value, find the three p99 bins by a prefix sum over the histograms and write the
+// record.  Called by all kThreads threads; `hist` holds the served requests' counts.
+__device__ __forceinline__ void finish_candidate(const EvalParams& p, uint32_t* hist, unsigned long long* acc64,
+                                                 uint32_t* acc32, uint32_t* wtot, unsigned long long s_e2e,
+                                                 unsigned long long s_ttft, unsigned long long s_tpot,
+                                                 uint32_t last_fin, uint32_t n_ok, uint32_t n_rej,
+                                                 ap_metrics* __restrict__ dst) {
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, w = tid >> 6;
+    s_e2e = wave_sum_u64(s_e2e);
+    s_ttft = wave_sum_u64(s_ttft);
+    s_tpot = wave_sum_u64(s_tpot);
+    last_fin = wave_max_u32(last_fin);
+    n_ok = wave_sum_u32(n_ok);
+    n_rej = wave_sum_u32(n_rej);
+    if (lane == 0) {
+        atomicAdd(&acc64[0], s_e2e);
+        atomicAdd(&acc64[1], s_ttft);
+        atomicAdd(&acc64[2], s_tpot);
+        atomicMax(&acc32[0], last_fin);
+        atomicAdd(&acc32[1], n_ok);
+        atomicAdd(&acc32[2], n_rej);
+    }
+    __syncthreads();
+    const uint32_t rejected = acc32[2];
+    if (tid < 3u && rejected) hist[tid * kBins + p.penalty_bin] += rejected;
+    __syncthreads();
+
+    // p99: block-wide prefix sum over the bins, 4 bins per thread, three histograms at once
+    uint32_t part[3], incl[3];
+#pragma unroll
+    for (uint32_t h = 0; h < 3u; ++h) {
+        const uint32_t* hb = hist + h * kBins + 4u * tid;
+        part[h] = hb[0] + hb[1] + hb[2] + hb[3];
+        incl[h] = wave_inclusive_scan(part[h], lane);
+        if (lane == 63u) wtot[h * kWaves + w] = incl[h];
+    }
+    __syncthreads();
+#pragma unroll
+    for (uint32_t h = 0; h < 3u; ++h) {
+        uint32_t before = 0;
+        for (uint32_t ww = 0; ww < w; ++ww) before += wtot[h * kWaves + ww];
+        uint32_t hi = before + incl[h], lo = hi - part[h];
+        if (lo < p.k99 && p.k99 <= hi) {
+            const uint32_t* hb = hist + h * kBins + 4u * tid;
+            uint32_t run = lo, b = 0;
+            for (; b < 3u; ++b) {
+                run += hb[b];
+                if (run >= p.k99) break;
+            }
+            acc32[3 + h] = 4u * tid + b;
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        ap_metrics mt;
+        mt.sum_e2e_us = acc64[0] + (unsigned long long)rejected * p.penalty;
+        mt.sum_ttft_us = acc64[1] + (unsigned long long)rejected * p.penalty;
+        mt.sum_tpot_us = acc64[2] + (unsigned long long)rejected * p.penalty;
+        mt.makespan_us = acc32[0];
+        mt.p99_ttft_us = hist_lower_edge(acc32[3]);
+        mt.p99_tpot_us = hist_lower_edge(acc32[4]);
+        mt.p99_e2e_us = hist_lower_edge(acc32[5]);
+        mt.slo_ok = acc32[1];
+        mt.n_rejected = rejected;
+        *dst = mt;
+    }
+}
+
+// A record no evaluation can produce (slo_ok <= R - n_rejected always): "not scored yet".
+__device__ __forceinline__ bool is_pending(const ap_metrics& m) {
+    return m.slo_ok == 0xFFFFFFFFu && m.n_rejected == 0xFFFFFFFFu;
+}
+
+// ----------------------------------------------------------------------------------
+// cost tables -> metrics of the contention-free replay (one-time, at ap_costmodel_set)
+// ----------------------------------------------------------------------------------
+// When every replica has the same coefficients and is available for the whole trace, a
+// request that never waits has ttft = prefill, e2e = prefill + decode and the same tpot
+// whichever replica it is on.  This kernel evaluates the cost model for every request
+// (prefill, tpot, decode of the serve-latency equation's integer stand-in), stores the
+// service-time table the screening kernel reads, and reduces the values to the record
+// every contention-free candidate shares.  One workgroup.
+__global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint32_t* __restrict__ service,
+                                                              ap_metrics* __restrict__ nominal) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    uint32_t* hist = reinterpret_cast<uint32_t*>(lds);
+    unsigned long long* acc64 = reinterpret_cast<unsigned long long*>(lds + p.off_misc);
+    uint32_t* acc32 = reinterpret_cast<uint32_t*>(lds + p.off_misc + 24);
+    uint32_t* wtot = reinterpret_cast<uint32_t*>(lds + p.off_misc + 64);
+    const uint32_t tid = threadIdx.x;
+    for (uint32_t i = tid; i < 3u * kBins; i += kThreads) hist[i] = 0u;
+    if (tid < 16u) reinterpret_cast<uint32_t*>(acc64)[tid] = 0u;
+    __syncthreads();
+    const DevReplica rp = p.rep[0];
+    unsigned long long s_e2e = 0, s_ttft = 0, s_tpot = 0;
+    uint32_t last_fin = 0, n_ok = 0;
+    for (uint32_t r = tid; r < p.R; r += kThreads) {
+        const uint32_t prm = p.prompt[r];
+        const uint32_t prefill = rp.a + rp.b * prm;
+        const uint32_t tpot = rp.c + rp.d * ((prm + 1023u) >> 10);
+        const uint32_t e2e = prefill + p.outlen[r] * tpot;
+        service[r] = e2e;
+        atomicAdd(&hist[hist_bin_u32(prefill)], 1u);
+        atomicAdd(&hist[kBins + hist_bin_u32(tpot)], 1u);
+        atomicAdd(&hist[2u * kBins + hist_bin_u32(e2e)], 1u);
+        s_ttft += prefill;
+        s_e2e += e2e;
+        s_tpot += tpot;
+        last_fin = max(last_fin, p.arrival[r] + e2e);
+        n_ok += (prefill <= p.slo_ttft && tpot <= p.slo_tpot) ? 1u : 0u;
+    }
+    finish_candidate(p, hist, acc64, acc32, wtot, s_e2e, s_ttft, s_tpot, last_fin, n_ok, 0u, nominal);
+}
+
+// ----------------------------------------------------------------------------------
+// screening: prove that a candidate is contention-free without ordering its requests
+// ----------------------------------------------------------------------------------
+// Applies when every replica has the same coefficients and is available throughout, so a
+// request that does not wait occupies a slot during [arrival, arrival + service).
+// Each replica gets S <= B screening slots in LDS, all 0.  Every request, in any order,
+// probes its replica's slots with an atomic max of its finish time: a probe whose old
+// value is <= the request's arrival has claimed a slot that no request still in service
+// at that instant holds; any other probe only raises the slot's value.  Slot values never
+// decrease, so a slot can look busy when it is not (a failed probe leaves a finish time
+// behind) but never free when it is busy.  Hence, if every request of the candidate
+// claims a slot, the contention-free schedule keeps at most S <= B requests in service
+// per replica at any time, nobody waits in the B-slot queue, and the candidate's record is
+// the nominal one.  The test is sufficient, not necessary: a candidate with a request that
+// finds no slot, or that names a replica outside the table, is marked pending and is
+// replayed exactly by k_eval_candidates.
+//
+// One wavefront per candidate; order does not matter, so each lane takes 8 consecutive
+// requests per step (one 16-byte load of assignments, 32-byte loads of the tables).
+struct ScreenParams {
+    const uint32_t* arrival;      // [R]
+    const uint32_t* service;      // [R] prefill + decode
+    const ap_metrics* nominal;
+    uint32_t R, M;
+    uint32_t slots;               // S, a power of two
+};
+
+constexpr uint32_t kScreenWaves = 4;
+constexpr uint32_t kScreenThreads = kScreenWaves * kWave;
+constexpr uint32_t kScreenMaxSlots = 16;
+constexpr uint32_t kScreenLdsPerWave = 8192;      // bytes of slot state per candidate in flight
+
+template <bool kVector>
+__global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenParams p, const uint16_t* __restrict__ assign,
+                                                                       ap_metrics* __restrict__ out, uint32_t C) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    const uint32_t lane = threadIdx.x & 63u, w = threadIdx.x >> 6;
+    const uint32_t M = p.M, S = p.slots, R = p.R;
+    uint32_t* slot = reinterpret_cast<uint32_t*>(lds) + w * M * S;     // [M][S], this wavefront's own
+
+    for (uint32_t c = blockIdx.x * kScreenWaves + w; c < C; c += gridDim.x * kScreenWaves) {
+        const uint16_t* row = assign + (size_t)c * R;
+        for (uint32_t i = lane; i < M * S; i += kWave) slot[i] = 0u;
+        bool bad = false;
+        for (uint32_t i0 = 0; i0 < R && !bad; i0 += kWave * 8u) {
+            const uint32_t i = i0 + lane * 8u;
+            uint32_t id[8], arr[8], svc[8];
+            if (i + 8u <= R) {
+                if (kVector) {
+                    const uint4 v = *reinterpret_cast<const uint4*>(row + i);
+                    id[0] = v.x & 0xFFFFu; id[1] = v.x >> 16; id[2] = v.y & 0xFFFFu; id[3] = v.y >> 16;
+                    id[4] = v.z & 0xFFFFu; id[5] = v.z >> 16; id[6] = v.w & 0xFFFFu; id[7] = v.w >> 16;
+                } else {
+#pragma unroll
+                    for (uint32_t q = 0; q < 8u; ++q) id[q] = row[i + q];
+                }
+                const uint4 a0 = *reinterpret_cast<const uint4*>(p.arrival + i);
+                const uint4 a1 = *reinterpret_cast<const uint4*>(p.arrival + i + 4u);
+                const uint4 s0 = *reinterpret_cast<const uint4*>(p.service + i);
+                const uint4 s1 = *reinterpret_cast<const uint4*>(p.service + i + 4u);
+                arr[0] = a0.x; arr[1] = a0.y; arr[2] = a0.z; arr[3] = a0.w;
+                arr[4] = a1.x; arr[5] = a1.y; arr[6] = a1.z; arr[7] = a1.w;
+                svc[0] = s0.x; svc[1] = s0.y; svc[2] = s0.z; svc[3] = s0.w;
+                svc[4] = s1.x; svc[5] = s1.y; svc[6] = s1.z; svc[7] = s1.w;
+            } else {
+#pragma unroll
+                for (uint32_t q = 0; q < 8u; ++q) {
+                    const bool in = i + q < R;
+                    id[q] = in ? (uint32_t)row[i + q] : 0xFFFFFFFFu;       // marks "no request"
+                    arr[q] = in ? p.arrival[i + q] : 0u;
+                    svc[q] = in ? p.service[i + q] : 0u;
+                }
+            }
+            bool lane_bad = false;
+#pragma unroll
+            for (uint32_t q = 0; q < 8u; ++q) {
+                const uint32_t m = id[q];
+                if (m == 0xFFFFFFFFu) continue;
+                if (m >= M) {
+                    lane_bad = true;              // unknown replica: the request is rejected, not nominal
+                    continue;
+                }
+                const uint32_t fin = arr[q] + svc[q];
+                uint32_t* mine = slot + m * S;
+                const uint32_t first = (i + q) & (S - 1u);
+                bool placed = atomicMax(&mine[first], fin) <= arr[q];
+                for (uint32_t t = 1; t < S && !placed; ++t)
+                    placed = atomicMax(&mine[(first + t) & (S - 1u)], fin) <= arr[q];
+                lane_bad = lane_bad || !placed;
+            }
+            bad = __ballot(lane_bad) != 0ull;
+        }
+        // 64-byte record: nominal, or the pending mark
+        if (lane < 8u) {
+            const unsigned long long* src = reinterpret_cast<const unsigned long long*>(p.nominal);
+            const unsigned long long v = bad ? ~0ull : src[lane];
+            reinterpret_cast<unsigned long long*>(&out[c])[lane] = v;
+        }
+    }
+}
+
 // ----------------------------------------------------------------------------------
 // the evaluation kernel
 // ----------------------------------------------------------------------------------
+//
+// only_pending != 0: score just the candidates whose record carries the "still to do" mark
+// left by the screening kernel; every other record is final and is not touched.
 __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, const uint16_t* __restrict__ assign,
-                                                              ap_metrics* __restrict__ out, uint32_t C) {
+                                                              ap_metrics* out, uint32_t C, uint32_t only_pending) {
     extern __shared__ __align__(16) unsigned char lds[];
     uint32_t* hist = reinterpret_cast<uint32_t*>(lds);                        // [3][kBins]
     uint32_t* slots = reinterpret_cast<uint32_t*>(lds + p.off_slots);         // [M][B] slot-free times
@@ -142,6 +361,7 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
     const unsigned long long lanes_below = (1ull << lane) - 1ull;
 
     for (uint32_t c = blockIdx.x; c < C; c += gridDim.x) {
+        if (only_pending && !is_pending(out[c])) continue;      // same record for every thread: uniform
         const uint16_t* row = assign + (size_t)c * R;
 
         for (uint32_t i = tid; i < 3u * kBins; i += kThreads) hist[i] = 0u;
@@ -287,65 +507,7 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
             __syncthreads();
         }
 
-        // ---- per-candidate reductions -------------------------------------------------------
-        s_e2e = wave_sum_u64(s_e2e);
-        s_ttft = wave_sum_u64(s_ttft);
-        s_tpot = wave_sum_u64(s_tpot);
-        last_fin = wave_max_u32(last_fin);
-        n_ok = wave_sum_u32(n_ok);
-        n_rej = wave_sum_u32(n_rej);
-        if (lane == 0) {
-            atomicAdd(&acc64[0], s_e2e);
-            atomicAdd(&acc64[1], s_ttft);
-            atomicAdd(&acc64[2], s_tpot);
-            atomicMax(&acc32[0], last_fin);
-            atomicAdd(&acc32[1], n_ok);
-            atomicAdd(&acc32[2], n_rej);
-        }
-        __syncthreads();
-        const uint32_t rejected = acc32[2];
-        if (tid < 3u && rejected) hist[tid * kBins + p.penalty_bin] += rejected;
-        __syncthreads();
-
-        // p99: block-wide prefix sum over the bins, 4 bins per thread, three histograms at once
-        uint32_t part[3], incl[3];
-#pragma unroll
-        for (uint32_t h = 0; h < 3u; ++h) {
-            const uint32_t* hb = hist + h * kBins + 4u * tid;
-            part[h] = hb[0] + hb[1] + hb[2] + hb[3];
-            incl[h] = wave_inclusive_scan(part[h], lane);
-            if (lane == 63u) wtot[h * kWaves + w] = incl[h];
-        }
-        __syncthreads();
-#pragma unroll
-        for (uint32_t h = 0; h < 3u; ++h) {
-            uint32_t before = 0;
-            for (uint32_t ww = 0; ww < w; ++ww) before += wtot[h * kWaves + ww];
-            uint32_t hi = before + incl[h], lo = hi - part[h];
-            if (lo < p.k99 && p.k99 <= hi) {
-                const uint32_t* hb = hist + h * kBins + 4u * tid;
-                uint32_t run = lo, b = 0;
-                for (; b < 3u; ++b) {
-                    run += hb[b];
-                    if (run >= p.k99) break;
-                }
-                acc32[3 + h] = 4u * tid + b;
-            }
-        }
-        __syncthreads();
-        if (tid == 0) {
-            ap_metrics mt;
-            mt.sum_e2e_us = acc64[0] + (unsigned long long)rejected * p.penalty;
-            mt.sum_ttft_us = acc64[1] + (unsigned long long)rejected * p.penalty;
-            mt.sum_tpot_us = acc64[2] + (unsigned long long)rejected * p.penalty;
-            mt.makespan_us = acc32[0];
-            mt.p99_ttft_us = hist_lower_edge(acc32[3]);
-            mt.p99_tpot_us = hist_lower_edge(acc32[4]);
-            mt.p99_e2e_us = hist_lower_edge(acc32[5]);
-            mt.slo_ok = acc32[1];
-            mt.n_rejected = rejected;
-            out[c] = mt;
-        }
+        finish_candidate(p, hist, acc64, acc32, wtot, s_e2e, s_ttft, s_tpot, last_fin, n_ok, n_rej, &out[c]);
         __syncthreads();
     }
 }
@@ -382,10 +544,16 @@ struct ap_workload {
     uint32_t* d_prompt = nullptr;
     uint32_t* d_out = nullptr;
     DevReplica* d_rep = nullptr;      // capacity AP_MAX_REPLICAS
+    uint32_t* d_service = nullptr;    // [R] prefill + decode, valid when screen is set
+    ap_metrics* d_nominal = nullptr;  // record shared by all contention-free candidates
     bool has_model = false;
+    bool screen = false;              // homogeneous, always-on replicas: screening applies
     EvalParams params{};
+    ScreenParams screen_params{};
     uint32_t lds_bytes = 0;
+    uint32_t screen_lds_bytes = 0;
     uint32_t max_grid = 0;
+    uint32_t n_cu = 0;
 };
 
 extern "C" {
@@ -444,7 +612,9 @@ ap_status ap_workload_create(const uint64_t* arrival_us, const int32_t* prompt_l
     const size_t bytes = (size_t)R * 4u;
     if (st == AP_OK && (hipMalloc(&w->d_arrival, bytes) != hipSuccess || hipMalloc(&w->d_prompt, bytes) != hipSuccess ||
                         hipMalloc(&w->d_out, bytes) != hipSuccess ||
-                        hipMalloc(&w->d_rep, sizeof(DevReplica) * AP_MAX_REPLICAS) != hipSuccess))
+                        hipMalloc(&w->d_rep, sizeof(DevReplica) * AP_MAX_REPLICAS) != hipSuccess ||
+                        hipMalloc(&w->d_service, bytes) != hipSuccess ||
+                        hipMalloc(&w->d_nominal, sizeof(ap_metrics)) != hipSuccess))
         st = AP_ERR_ALLOC;
     if (st == AP_OK && (hipMemcpy(w->d_arrival, rel.data(), bytes, hipMemcpyHostToDevice) != hipSuccess ||
                         hipMemcpy(w->d_prompt, prompt_len, bytes, hipMemcpyHostToDevice) != hipSuccess ||
@@ -538,6 +708,8 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
     }
     if (hipMemcpy(w->d_rep, dev.data(), sizeof(DevReplica) * M, hipMemcpyHostToDevice) != hipSuccess ||
         hipFuncSetAttribute(reinterpret_cast<const void*>(&k_eval_candidates),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess ||
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&k_nominal_metrics),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) {
         (void)hipGetLastError();
         w->has_model = false;     // the replica table on the device may be half-written
@@ -556,9 +728,36 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
     p.penalty = slo->penalty_us;
     p.penalty_bin = ap_hist_bin(slo->penalty_us);
     p.k99 = (uint32_t)((99ull * w->R + 99ull) / 100ull);
+    w->has_model = false;
     w->params = p;
     w->lds_bytes = bytes;
+    w->n_cu = (uint32_t)n_cu;
     w->max_grid = (uint32_t)n_cu * 4u;
+
+    // ---- screening plan: only for identical replicas that are available throughout ------
+    bool always_on = true;
+    for (const DevReplica& d : dev) always_on = always_on && d.t_on == 0u && d.t_off == kNever;
+    w->screen = always_on && kinds.size() == 1;
+    if (w->screen) {
+        // screening slots per replica: a power of two, at most B, sized so that one
+        // candidate's slot state stays within kScreenLdsPerWave bytes of LDS
+        uint32_t S = 1;
+        while (S * 2u <= std::min(B, kScreenMaxSlots) && M * S * 2u * 4u <= kScreenLdsPerWave) S *= 2u;
+        ScreenParams sp{};
+        sp.arrival = w->d_arrival;
+        sp.service = w->d_service;
+        sp.nominal = w->d_nominal;
+        sp.R = w->R;
+        sp.M = M;
+        sp.slots = S;
+        w->screen_params = sp;
+        w->screen_lds_bytes = kScreenWaves * M * S * 4u;
+        hipLaunchKernelGGL(k_nominal_metrics, dim3(1), dim3(kThreads), bytes, nullptr, p, w->d_service, w->d_nominal);
+        if (hipGetLastError() != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+            (void)hipGetLastError();
+            return AP_ERR_DEVICE;
+        }
+    }
     w->has_model = true;
     return AP_OK;
 }
@@ -569,9 +768,21 @@ ap_status ap_eval_candidates(const ap_workload* w, const uint16_t* d_assign, uin
     if (!w->has_model) return AP_ERR_STATE;
     if (C == 0) return AP_OK;
     if (!d_assign || !d_out) return AP_ERR_INVALID;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (w->screen) {
+        const uint32_t blocks = std::min((C + kScreenWaves - 1u) / kScreenWaves, w->n_cu * 8u);
+        const bool vec = (w->R % 8u == 0u) && (reinterpret_cast<uintptr_t>(d_assign) % 16u == 0u);
+        if (vec)
+            hipLaunchKernelGGL(k_screen_candidates<true>, dim3(blocks), dim3(kScreenThreads), w->screen_lds_bytes,
+                               stream, w->screen_params, d_assign, d_out, C);
+        else
+            hipLaunchKernelGGL(k_screen_candidates<false>, dim3(blocks), dim3(kScreenThreads), w->screen_lds_bytes,
+                               stream, w->screen_params, d_assign, d_out, C);
+        if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
+    }
     const uint32_t grid = std::min(C, w->max_grid);
-    hipLaunchKernelGGL(k_eval_candidates, dim3(grid), dim3(kThreads), w->lds_bytes,
-                       static_cast<hipStream_t>(hip_stream), w->params, d_assign, d_out, C);
+    hipLaunchKernelGGL(k_eval_candidates, dim3(grid), dim3(kThreads), w->lds_bytes, stream, w->params, d_assign,
+                       d_out, C, w->screen ? 1u : 0u);
     if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
     return AP_OK;
 }
@@ -583,6 +794,8 @@ ap_status ap_workload_destroy(ap_workload* w) {
     if (w->d_prompt) ok = (hipFree(w->d_prompt) == hipSuccess) && ok;
     if (w->d_out) ok = (hipFree(w->d_out) == hipSuccess) && ok;
     if (w->d_rep) ok = (hipFree(w->d_rep) == hipSuccess) && ok;
+    if (w->d_service) ok = (hipFree(w->d_service) == hipSuccess) && ok;
+    if (w->d_nominal) ok = (hipFree(w->d_nominal) == hipSuccess) && ok;
     delete w;
     return ok ? AP_OK : AP_ERR_DEVICE;
 }

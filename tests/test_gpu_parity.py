@@ -84,6 +84,39 @@ def test_crafted_traces(name, n, M, B, gap, C):
     both(tr, _rows(C, n, M, seed=n + M), name)
 
 
+@pytest.mark.parametrize("name,n,M,B,gap,C", [
+    ("light_vector_rows", 8192, 16, 16, 9000, 16),     # R % 8 == 0: 16-byte loads; nobody waits
+    ("light_scalar_rows", 8191, 16, 16, 9000, 16),     # R % 8 != 0: rows are not 16-byte aligned
+    ("borderline", 8192, 16, 8, 1500, 32),             # some candidates pass the screen, some do not
+    ("saturated", 6000, 8, 8, 100, 8),                 # every candidate fails the screen
+    ("tiny_segments", 3000, 2, 2, 30000, 8),
+    ("m1000", 40000, 1000, 4, 40, 4),
+])
+def test_homogeneous_always_on_traces_take_the_screening_path(name, n, M, B, gap, C):
+    tr = _mk(n, M, B, gap, seed=n + 13, coef=[STD] * M)
+    rows = _rows(C, n, M, seed=n)
+    rows[0] = np.arange(n) % M                           # round robin: the most even candidate
+    both(tr, rows, name)
+
+
+def test_screening_with_invalid_ids_and_unaligned_batch_pointer():
+    n, M = 4096, 8
+    tr = _mk(n, M, 16, 9000, seed=5, coef=[FAST] * M, penalty_us=4_000_000)
+    rows = _rows(9, n, M, seed=3)
+    rows[2, 100] = M                                     # one unknown replica id: that request is rejected
+    rows[4, -1] = 65535
+    want = oracle_for(tr).eval_batch(rows)
+    assert int(want["n_rejected"][2]) == 1 and int(want["n_rejected"][0]) == 0
+    with GpuWorkload(tr) as g:
+        assert_same(g.eval(rows), want, "invalid ids under screening")
+        # a batch that starts 2 bytes into an allocation: rows are not 16-byte aligned
+        flat = torch.zeros(9 * n + 1, dtype=torch.int16, device="cuda")
+        flat[1:] = torch.from_numpy(rows.view(np.int16).reshape(-1)).cuda()
+        d_out = g.eval_device(flat[1:].view(9, n))
+        torch.cuda.synchronize()
+        assert_same(to_records(d_out), want, "unaligned batch")
+
+
 def test_all_requests_on_one_replica_and_empty_replicas():
     tr = _mk(5000, 9, 16, 200, seed=3)
     rows = np.zeros((4, 5000), np.uint16)
