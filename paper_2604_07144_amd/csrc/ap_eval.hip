@@ -191,6 +191,20 @@ __device__ __forceinline__ bool is_pending(const ap_metrics& m) {
     return m.slo_ok == 0xFFFFFFFFu && m.n_rejected == 0xFFFFFFFFu;
 }
 
+// Screening kernel geometry (the tables written below use its lane-major layout).
+constexpr uint32_t kScreenWaves = 4;
+constexpr uint32_t kScreenThreads = kScreenWaves * kWave;
+constexpr uint32_t kScreenBlock = kWave * 8u;     // requests per wavefront per block
+constexpr uint32_t kScreenMaxSlots = 32;
+constexpr uint32_t kScreenLdsPerWave = 16384;     // bytes of slot state per candidate in flight
+
+// Position of request r in the lane-major tables: in its block of 512, request
+// 128k + 2l + h is element 2k + h of lane l.
+__host__ __device__ inline uint32_t screen_table_index(uint32_t r) {
+    const uint32_t x = r % kScreenBlock, k = x / 128u, l = (x % 128u) / 2u, h = x % 2u;
+    return (r - x) + l * 8u + 2u * k + h;
+}
+
 // ----------------------------------------------------------------------------------
 // cost tables -> metrics of the contention-free replay (one-time, at ap_costmodel_set)
 // ----------------------------------------------------------------------------------
@@ -198,9 +212,11 @@ __device__ __forceinline__ bool is_pending(const ap_metrics& m) {
 // request that never waits has ttft = prefill, e2e = prefill + decode and the same tpot
 // whichever replica it is on.  This kernel evaluates the cost model for every request
 // (prefill, tpot, decode of the serve-latency equation's integer stand-in), stores the
-// service-time table the screening kernel reads, and reduces the values to the record
-// every contention-free candidate shares.  One workgroup.
-__global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint32_t* __restrict__ service,
+// arrival / contention-free-finish tables the screening kernel reads (in its lane-major
+// layout), and reduces the values to the record every contention-free candidate shares.
+// One workgroup.
+__global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint32_t* __restrict__ arrival_t,
+                                                              uint32_t* __restrict__ finish_t,
                                                               ap_metrics* __restrict__ nominal) {
     extern __shared__ __align__(16) unsigned char lds[];
     uint32_t* hist = reinterpret_cast<uint32_t*>(lds);
@@ -219,7 +235,8 @@ __global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint
         const uint32_t prefill = rp.a + rp.b * prm;
         const uint32_t tpot = rp.c + rp.d * ((prm + 1023u) >> 10);
         const uint32_t e2e = prefill + p.outlen[r] * tpot;
-        service[r] = e2e;
+        arrival_t[screen_table_index(r)] = p.arrival[r];
+        finish_t[screen_table_index(r)] = p.arrival[r] + e2e;
         atomicAdd(&hist[hist_bin_u32(prefill)], 1u);
         atomicAdd(&hist[kBins + hist_bin_u32(tpot)], 1u);
         atomicAdd(&hist[2u * kBins + hist_bin_u32(e2e)], 1u);
@@ -233,97 +250,174 @@ __global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint
 }
 
 // ----------------------------------------------------------------------------------
-// screening: prove that a candidate is contention-free without ordering its requests
+// screening: prove that a candidate is contention-free without queueing its requests
 // ----------------------------------------------------------------------------------
 // Applies when every replica has the same coefficients and is available throughout, so a
 // request that does not wait occupies a slot during [arrival, arrival + service).
-// Each replica gets S <= B screening slots in LDS, all 0.  Every request, in any order,
-// probes its replica's slots with an atomic max of its finish time: a probe whose old
-// value is <= the request's arrival has claimed a slot that no request still in service
-// at that instant holds; any other probe only raises the slot's value.  Slot values never
-// decrease, so a slot can look busy when it is not (a failed probe leaves a finish time
-// behind) but never free when it is busy.  Hence, if every request of the candidate
-// claims a slot, the contention-free schedule keeps at most S <= B requests in service
-// per replica at any time, nobody waits in the B-slot queue, and the candidate's record is
-// the nominal one.  The test is sufficient, not necessary: a candidate with a request that
-// finds no slot, or that names a replica outside the table, is marked pending and is
-// replayed exactly by k_eval_candidates.
+// Each replica gets S <= B screening slots in LDS, all 0.  Every request probes its
+// replica's slots with an atomic max of its finish time: a probe whose old value is <= the
+// request's arrival has claimed a slot that no request still in service at that instant
+// holds; any other probe only raises the slot's value.  Slot values never decrease, so a
+// slot can look busy when it is not but never free when it is busy: two requests that
+// claimed the same slot have disjoint service intervals, in whatever order they were
+// processed.  Hence, if every request of the candidate claims a slot, the contention-free
+// schedule keeps at most S <= B requests in service per replica at any time, nobody waits
+// in the B-slot queue, and the candidate's record is the nominal one.  The test is
+// sufficient, not necessary: a candidate with a request that finds no slot, or that names
+// a replica outside the table, is marked pending and is replayed exactly by
+// k_eval_candidates.  Requests are taken 64 at a time in arrival order, which keeps the
+// number of slots a replica needs close to its true concurrency.
 //
-// One wavefront per candidate; order does not matter, so each lane takes 8 consecutive
-// requests per step (one 16-byte load of assignments, 32-byte loads of the tables).
+// One wavefront per candidate.  A block is 512 consecutive requests; lane l holds the eight
+// requests i0 + 128k + 2l + h (k = 0..3, h = 0..1): four 4-byte loads of assignment pairs.
+// Step e = 2k + h therefore covers every other request of a 128-request window, close
+// enough to arrival order.  The arrival / finish tables are stored lane-major so that a
+// lane's eight values are contiguous (two 16-byte loads each).
 struct ScreenParams {
-    const uint32_t* arrival;      // [R]
-    const uint32_t* service;      // [R] prefill + decode
+    const uint32_t* arrival_t;    // [ceil(R/512)*512] in the order given by screen_table_index
+    const uint32_t* finish_t;     // same layout: arrival + prefill + decode
     const ap_metrics* nominal;
     uint32_t R, M;
-    uint32_t slots;               // S, a power of two
+    uint32_t slots_log2;          // S = 1 << slots_log2
 };
 
-constexpr uint32_t kScreenWaves = 4;
-constexpr uint32_t kScreenThreads = kScreenWaves * kWave;
-constexpr uint32_t kScreenMaxSlots = 16;
-constexpr uint32_t kScreenLdsPerWave = 8192;      // bytes of slot state per candidate in flight
+struct ScreenRegs {
+    uint32_t pair[4];             // two replica ids per word, as stored in the candidate's row
+    uint32_t arr[8], fin[8];
+};
 
-template <bool kVector>
+template <bool kAligned>
+__device__ __forceinline__ void screen_fetch(ScreenRegs& g, const ScreenParams& p, const uint16_t* __restrict__ row,
+                                             uint32_t i0, uint32_t lane) {
+#pragma unroll
+    for (uint32_t k = 0; k < 4u; ++k) {
+        const uint16_t* at = row + i0 + 128u * k + 2u * lane;
+        // assignments are read once: stream them past the caches that hold the tables
+        if (kAligned) {
+            g.pair[k] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(at));
+        } else {
+            g.pair[k] = (uint32_t)__builtin_nontemporal_load(at) | ((uint32_t)__builtin_nontemporal_load(at + 1) << 16);
+        }
+    }
+    const uint4 a0 = *reinterpret_cast<const uint4*>(p.arrival_t + i0 + lane * 8u);
+    const uint4 a1 = *reinterpret_cast<const uint4*>(p.arrival_t + i0 + lane * 8u + 4u);
+    const uint4 f0 = *reinterpret_cast<const uint4*>(p.finish_t + i0 + lane * 8u);
+    const uint4 f1 = *reinterpret_cast<const uint4*>(p.finish_t + i0 + lane * 8u + 4u);
+    g.arr[0] = a0.x; g.arr[1] = a0.y; g.arr[2] = a0.z; g.arr[3] = a0.w;
+    g.arr[4] = a1.x; g.arr[5] = a1.y; g.arr[6] = a1.z; g.arr[7] = a1.w;
+    g.fin[0] = f0.x; g.fin[1] = f0.y; g.fin[2] = f0.z; g.fin[3] = f0.w;
+    g.fin[4] = f1.x; g.fin[5] = f1.y; g.fin[6] = f1.z; g.fin[7] = f1.w;
+}
+
+// Claim a slot for each of the lane's eight requests.  `slot_bytes` is the byte address
+// of this lane's first-choice slot in replica 0's ring; replica m's ring is m << ring_shift
+// bytes further on, and ring M is a spare one that absorbs unknown replica ids.
+// The eight steps are taken in groups of kGroup: within a group all first probes are issued
+// back to back (LDS executes them in order, so the steps still see each other's claims),
+// then the second probes (half a ring away) of the few that lost, then the rest of the ring
+// for those that lost twice.  A larger group hides more LDS latency but lets a retry see
+// claims of up to kGroup * 64 later requests; the host picks kGroup from M and S.
+// Returns true if some request of this lane found no slot or named an unknown replica.
+template <uint32_t kGroup>
+__device__ __forceinline__ bool screen_claim(const uint32_t id[8], const uint32_t arr[8], const uint32_t fin[8],
+                                             unsigned char* lds, uint32_t slot_bytes, uint32_t ring_base_bytes,
+                                             uint32_t ring_shift, uint32_t M, uint32_t S, uint32_t my_first) {
+    uint32_t top = 0;
+    bool lane_bad = false;
+#pragma unroll
+    for (uint32_t g = 0; g < 8u; g += kGroup) {
+        uint32_t at[kGroup], old[kGroup], old2[kGroup];
+#pragma unroll
+        for (uint32_t j = 0; j < kGroup; ++j) {
+            const uint32_t e = g + j;
+            top = max(top, id[e]);
+            at[j] = (min(id[e], M) << ring_shift) + slot_bytes;
+            old[j] = atomicMax(reinterpret_cast<uint32_t*>(lds + at[j]), fin[e]);
+        }
+#pragma unroll
+        for (uint32_t j = 0; j < kGroup; ++j) {
+            const uint32_t e = g + j;
+            old2[j] = 0u;
+            if (old[j] > arr[e])
+                old2[j] = atomicMax(reinterpret_cast<uint32_t*>(lds + (at[j] ^ ((S >> 1) << 2))), fin[e]);
+        }
+#pragma unroll
+        for (uint32_t j = 0; j < kGroup; ++j) {
+            const uint32_t e = g + j;
+            if (old2[j] > arr[e] && id[e] < M) {
+                uint32_t* ring = reinterpret_cast<uint32_t*>(lds + ring_base_bytes + (id[e] << ring_shift));
+                bool placed = false;
+                for (uint32_t t = 1; t < S && !placed; ++t) {
+                    uint32_t* other = &ring[(my_first + t) & (S - 1u)];
+                    if (*other <= arr[e]) placed = atomicMax(other, fin[e]) <= arr[e];
+                }
+                lane_bad = lane_bad || !placed;
+            }
+        }
+    }
+    return lane_bad || top >= M;                     // unknown replica: rejected, so not nominal
+}
+
+template <bool kAligned, uint32_t kGroup>
 __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenParams p, const uint16_t* __restrict__ assign,
                                                                        ap_metrics* __restrict__ out, uint32_t C) {
     extern __shared__ __align__(16) unsigned char lds[];
     const uint32_t lane = threadIdx.x & 63u, w = threadIdx.x >> 6;
-    const uint32_t M = p.M, S = p.slots, R = p.R;
-    uint32_t* slot = reinterpret_cast<uint32_t*>(lds) + w * M * S;     // [M][S], this wavefront's own
+    const uint32_t M = p.M, R = p.R, S = 1u << p.slots_log2;
+    const uint32_t ring_shift = p.slots_log2 + 2u;                           // bytes per ring, log2
+    const uint32_t ring_base_bytes = w * ((M + 1u) << ring_shift);          // this wavefront's M + 1 rings
+    uint32_t* slot = reinterpret_cast<uint32_t*>(lds + ring_base_bytes);
+    const uint32_t my_first = lane & (S - 1u);
+    const uint32_t slot_bytes = ring_base_bytes + my_first * 4u;
+    const uint32_t n_full = R / kScreenBlock;
 
     for (uint32_t c = blockIdx.x * kScreenWaves + w; c < C; c += gridDim.x * kScreenWaves) {
         const uint16_t* row = assign + (size_t)c * R;
-        for (uint32_t i = lane; i < M * S; i += kWave) slot[i] = 0u;
+        for (uint32_t i = lane; i < ((M + 1u) << p.slots_log2); i += kWave) slot[i] = 0u;
         bool bad = false;
-        for (uint32_t i0 = 0; i0 < R && !bad; i0 += kWave * 8u) {
-            const uint32_t i = i0 + lane * 8u;
-            uint32_t id[8], arr[8], svc[8];
-            if (i + 8u <= R) {
-                if (kVector) {
-                    const uint4 v = *reinterpret_cast<const uint4*>(row + i);
-                    id[0] = v.x & 0xFFFFu; id[1] = v.x >> 16; id[2] = v.y & 0xFFFFu; id[3] = v.y >> 16;
-                    id[4] = v.z & 0xFFFFu; id[5] = v.z >> 16; id[6] = v.w & 0xFFFFu; id[7] = v.w >> 16;
-                } else {
-#pragma unroll
-                    for (uint32_t q = 0; q < 8u; ++q) id[q] = row[i + q];
-                }
-                const uint4 a0 = *reinterpret_cast<const uint4*>(p.arrival + i);
-                const uint4 a1 = *reinterpret_cast<const uint4*>(p.arrival + i + 4u);
-                const uint4 s0 = *reinterpret_cast<const uint4*>(p.service + i);
-                const uint4 s1 = *reinterpret_cast<const uint4*>(p.service + i + 4u);
-                arr[0] = a0.x; arr[1] = a0.y; arr[2] = a0.z; arr[3] = a0.w;
-                arr[4] = a1.x; arr[5] = a1.y; arr[6] = a1.z; arr[7] = a1.w;
-                svc[0] = s0.x; svc[1] = s0.y; svc[2] = s0.z; svc[3] = s0.w;
-                svc[4] = s1.x; svc[5] = s1.y; svc[6] = s1.z; svc[7] = s1.w;
-            } else {
-#pragma unroll
-                for (uint32_t q = 0; q < 8u; ++q) {
-                    const bool in = i + q < R;
-                    id[q] = in ? (uint32_t)row[i + q] : 0xFFFFFFFFu;       // marks "no request"
-                    arr[q] = in ? p.arrival[i + q] : 0u;
-                    svc[q] = in ? p.service[i + q] : 0u;
-                }
+
+        // full blocks, two register sets: one is processed while the other is being loaded
+        ScreenRegs ga, gb;
+        if (n_full > 0u) screen_fetch<kAligned>(ga, p, row, 0u, lane);
+        for (uint32_t b = 0; b < n_full; b += 2u) {
+            if (b + 1u < n_full) screen_fetch<kAligned>(gb, p, row, (b + 1u) * kScreenBlock, lane);
+            {
+                const uint32_t id[8] = {ga.pair[0] & 0xFFFFu, ga.pair[0] >> 16, ga.pair[1] & 0xFFFFu, ga.pair[1] >> 16,
+                                        ga.pair[2] & 0xFFFFu, ga.pair[2] >> 16, ga.pair[3] & 0xFFFFu, ga.pair[3] >> 16};
+                bad = __ballot(screen_claim<kGroup>(id, ga.arr, ga.fin, lds, slot_bytes, ring_base_bytes, ring_shift, M, S,
+                                            my_first)) != 0ull;
             }
-            bool lane_bad = false;
-#pragma unroll
-            for (uint32_t q = 0; q < 8u; ++q) {
-                const uint32_t m = id[q];
-                if (m == 0xFFFFFFFFu) continue;
-                if (m >= M) {
-                    lane_bad = true;              // unknown replica: the request is rejected, not nominal
-                    continue;
-                }
-                const uint32_t fin = arr[q] + svc[q];
-                uint32_t* mine = slot + m * S;
-                const uint32_t first = (i + q) & (S - 1u);
-                bool placed = atomicMax(&mine[first], fin) <= arr[q];
-                for (uint32_t t = 1; t < S && !placed; ++t)
-                    placed = atomicMax(&mine[(first + t) & (S - 1u)], fin) <= arr[q];
-                lane_bad = lane_bad || !placed;
+            if (bad || b + 1u >= n_full) break;
+            if (b + 2u < n_full) screen_fetch<kAligned>(ga, p, row, (b + 2u) * kScreenBlock, lane);
+            {
+                const uint32_t id[8] = {gb.pair[0] & 0xFFFFu, gb.pair[0] >> 16, gb.pair[1] & 0xFFFFu, gb.pair[1] >> 16,
+                                        gb.pair[2] & 0xFFFFu, gb.pair[2] >> 16, gb.pair[3] & 0xFFFFu, gb.pair[3] >> 16};
+                bad = __ballot(screen_claim<kGroup>(id, gb.arr, gb.fin, lds, slot_bytes, ring_base_bytes, ring_shift, M, S,
+                                            my_first)) != 0ull;
             }
-            bad = __ballot(lane_bad) != 0ull;
+            if (bad) break;
         }
+
+        // ragged tail: the same steps with every access guarded; absent requests go to the spare ring
+        const uint32_t i0 = n_full * kScreenBlock;
+        if (!bad && i0 < R) {
+            uint32_t id[8], arr[8], fin[8];
+            bool unknown = false;
+#pragma unroll
+            for (uint32_t e = 0; e < 8u; ++e) {
+                const uint32_t r = i0 + 128u * (e >> 1) + 2u * lane + (e & 1u);
+                const bool in = r < R;
+                const uint32_t m = in ? (uint32_t)row[r] : 0u;
+                unknown = unknown || m >= M;
+                id[e] = in ? min(m, M) : M;
+                arr[e] = in ? p.arrival_t[i0 + lane * 8u + e] : kNever;      // an absent request never loses a probe
+                fin[e] = in ? p.finish_t[i0 + lane * 8u + e] : 0u;
+            }
+            // ids were clamped to the spare ring, so screen_claim itself reports only lost requests
+            bool lane_bad = screen_claim<kGroup>(id, arr, fin, lds, slot_bytes, ring_base_bytes, ring_shift, M + 1u, S, my_first);
+            bad = __ballot(lane_bad || unknown) != 0ull;
+        }
+
         // 64-byte record: nominal, or the pending mark
         if (lane < 8u) {
             const unsigned long long* src = reinterpret_cast<const unsigned long long*>(p.nominal);
@@ -544,7 +638,8 @@ struct ap_workload {
     uint32_t* d_prompt = nullptr;
     uint32_t* d_out = nullptr;
     DevReplica* d_rep = nullptr;      // capacity AP_MAX_REPLICAS
-    uint32_t* d_service = nullptr;    // [R] prefill + decode, valid when screen is set
+    uint32_t* d_arrival_t = nullptr;  // lane-major arrival / finish tables, valid when screen is set
+    uint32_t* d_finish_t = nullptr;
     ap_metrics* d_nominal = nullptr;  // record shared by all contention-free candidates
     bool has_model = false;
     bool screen = false;              // homogeneous, always-on replicas: screening applies
@@ -552,6 +647,7 @@ struct ap_workload {
     ScreenParams screen_params{};
     uint32_t lds_bytes = 0;
     uint32_t screen_lds_bytes = 0;
+    uint32_t screen_group = 1;        // steps whose first probes are issued together: 1, 2, 4 or 8
     uint32_t max_grid = 0;
     uint32_t n_cu = 0;
 };
@@ -610,10 +706,12 @@ ap_status ap_workload_create(const uint64_t* arrival_us, const int32_t* prompt_l
     ap_status st = AP_OK;
     if (hipGetDevice(&w->device) != hipSuccess) st = AP_ERR_DEVICE;
     const size_t bytes = (size_t)R * 4u;
+    const size_t padded = ((size_t)R + kScreenBlock - 1u) / kScreenBlock * kScreenBlock * 4u;
     if (st == AP_OK && (hipMalloc(&w->d_arrival, bytes) != hipSuccess || hipMalloc(&w->d_prompt, bytes) != hipSuccess ||
                         hipMalloc(&w->d_out, bytes) != hipSuccess ||
                         hipMalloc(&w->d_rep, sizeof(DevReplica) * AP_MAX_REPLICAS) != hipSuccess ||
-                        hipMalloc(&w->d_service, bytes) != hipSuccess ||
+                        hipMalloc(&w->d_arrival_t, padded) != hipSuccess ||
+                        hipMalloc(&w->d_finish_t, padded) != hipSuccess ||
                         hipMalloc(&w->d_nominal, sizeof(ap_metrics)) != hipSuccess))
         st = AP_ERR_ALLOC;
     if (st == AP_OK && (hipMemcpy(w->d_arrival, rel.data(), bytes, hipMemcpyHostToDevice) != hipSuccess ||
@@ -741,18 +839,23 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
     if (w->screen) {
         // screening slots per replica: a power of two, at most B, sized so that one
         // candidate's slot state stays within kScreenLdsPerWave bytes of LDS
-        uint32_t S = 1;
-        while (S * 2u <= std::min(B, kScreenMaxSlots) && M * S * 2u * 4u <= kScreenLdsPerWave) S *= 2u;
+        uint32_t S_log2 = 0;
+        while ((2u << S_log2) <= std::min(B, kScreenMaxSlots) && M * (2u << S_log2) * 4u <= kScreenLdsPerWave) ++S_log2;
         ScreenParams sp{};
-        sp.arrival = w->d_arrival;
-        sp.service = w->d_service;
+        sp.arrival_t = w->d_arrival_t;
+        sp.finish_t = w->d_finish_t;
         sp.nominal = w->d_nominal;
         sp.R = w->R;
         sp.M = M;
-        sp.slots = S;
+        sp.slots_log2 = S_log2;
         w->screen_params = sp;
-        w->screen_lds_bytes = kScreenWaves * M * S * 4u;
-        hipLaunchKernelGGL(k_nominal_metrics, dim3(1), dim3(kThreads), bytes, nullptr, p, w->d_service, w->d_nominal);
+        // a group of g steps sends about 64 g / M requests to each replica before any retry;
+        // keep that within a quarter of the ring
+        w->screen_group = 1;
+        while (w->screen_group < 8u && 64u * (w->screen_group * 2u) * 4u <= M << S_log2) w->screen_group *= 2u;
+        w->screen_lds_bytes = kScreenWaves * ((M + 1u) << S_log2) * 4u;      // M rings and a spare one per wavefront
+        hipLaunchKernelGGL(k_nominal_metrics, dim3(1), dim3(kThreads), bytes, nullptr, p, w->d_arrival_t,
+                           w->d_finish_t, w->d_nominal);
         if (hipGetLastError() != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
             (void)hipGetLastError();
             return AP_ERR_DEVICE;
@@ -771,13 +874,17 @@ ap_status ap_eval_candidates(const ap_workload* w, const uint16_t* d_assign, uin
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (w->screen) {
         const uint32_t blocks = std::min((C + kScreenWaves - 1u) / kScreenWaves, w->n_cu * 8u);
-        const bool vec = (w->R % 8u == 0u) && (reinterpret_cast<uintptr_t>(d_assign) % 16u == 0u);
-        if (vec)
-            hipLaunchKernelGGL(k_screen_candidates<true>, dim3(blocks), dim3(kScreenThreads), w->screen_lds_bytes,
-                               stream, w->screen_params, d_assign, d_out, C);
-        else
-            hipLaunchKernelGGL(k_screen_candidates<false>, dim3(blocks), dim3(kScreenThreads), w->screen_lds_bytes,
-                               stream, w->screen_params, d_assign, d_out, C);
+        // rows start on 4-byte boundaries when R is even and the batch itself does
+        const bool aligned = (w->R % 2u == 0u) && (reinterpret_cast<uintptr_t>(d_assign) % 4u == 0u);
+        void (*kernel)(ScreenParams, const uint16_t*, ap_metrics*, uint32_t) = nullptr;
+        switch (w->screen_group) {
+            case 8: kernel = aligned ? k_screen_candidates<true, 8> : k_screen_candidates<false, 8>; break;
+            case 4: kernel = aligned ? k_screen_candidates<true, 4> : k_screen_candidates<false, 4>; break;
+            case 2: kernel = aligned ? k_screen_candidates<true, 2> : k_screen_candidates<false, 2>; break;
+            default: kernel = aligned ? k_screen_candidates<true, 1> : k_screen_candidates<false, 1>; break;
+        }
+        hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kScreenThreads), w->screen_lds_bytes, stream, w->screen_params,
+                           d_assign, d_out, C);
         if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
     }
     const uint32_t grid = std::min(C, w->max_grid);
@@ -794,7 +901,8 @@ ap_status ap_workload_destroy(ap_workload* w) {
     if (w->d_prompt) ok = (hipFree(w->d_prompt) == hipSuccess) && ok;
     if (w->d_out) ok = (hipFree(w->d_out) == hipSuccess) && ok;
     if (w->d_rep) ok = (hipFree(w->d_rep) == hipSuccess) && ok;
-    if (w->d_service) ok = (hipFree(w->d_service) == hipSuccess) && ok;
+    if (w->d_arrival_t) ok = (hipFree(w->d_arrival_t) == hipSuccess) && ok;
+    if (w->d_finish_t) ok = (hipFree(w->d_finish_t) == hipSuccess) && ok;
     if (w->d_nominal) ok = (hipFree(w->d_nominal) == hipSuccess) && ok;
     delete w;
     return ok ? AP_OK : AP_ERR_DEVICE;
