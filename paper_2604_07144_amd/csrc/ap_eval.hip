@@ -212,10 +212,12 @@ __host__ __device__ inline uint32_t screen_table_index(uint32_t r) {
 // request that never waits has ttft = prefill, e2e = prefill + decode and the same tpot
 // whichever replica it is on.  This kernel evaluates the cost model for every request
 // (prefill, tpot, decode of the serve-latency equation's integer stand-in), stores the
-// arrival / contention-free-finish tables the screening kernel reads (in its lane-major
-// layout), and reduces the values to the record every contention-free candidate shares.
+// contention-free finish times the screening kernels read (in request order and in the
+// lane-major layout), and reduces the values to the record every contention-free candidate
+// shares.
 // One workgroup.
-__global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint32_t* __restrict__ arrival_t,
+__global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint32_t* __restrict__ finish,
+                                                              uint32_t* __restrict__ arrival_t,
                                                               uint32_t* __restrict__ finish_t,
                                                               ap_metrics* __restrict__ nominal) {
     extern __shared__ __align__(16) unsigned char lds[];
@@ -235,6 +237,7 @@ __global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint
         const uint32_t prefill = rp.a + rp.b * prm;
         const uint32_t tpot = rp.c + rp.d * ((prm + 1023u) >> 10);
         const uint32_t e2e = prefill + p.outlen[r] * tpot;
+        finish[r] = p.arrival[r] + e2e;
         arrival_t[screen_table_index(r)] = p.arrival[r];
         finish_t[screen_table_index(r)] = p.arrival[r] + e2e;
         atomicAdd(&hist[hist_bin_u32(prefill)], 1u);
@@ -274,8 +277,10 @@ __global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint
 // enough to arrival order.  The arrival / finish tables are stored lane-major so that a
 // lane's eight values are contiguous (two 16-byte loads each).
 struct ScreenParams {
+    const uint32_t* arrival;      // [R] in request order
+    const uint32_t* finish;       // [R] arrival + prefill + decode, in request order
     const uint32_t* arrival_t;    // [ceil(R/512)*512] in the order given by screen_table_index
-    const uint32_t* finish_t;     // same layout: arrival + prefill + decode
+    const uint32_t* finish_t;     // same layout
     const ap_metrics* nominal;
     uint32_t R, M;
     uint32_t slots_log2;          // S = 1 << slots_log2
@@ -309,23 +314,23 @@ __device__ __forceinline__ void screen_fetch(ScreenRegs& g, const ScreenParams& 
     g.fin[4] = f1.x; g.fin[5] = f1.y; g.fin[6] = f1.z; g.fin[7] = f1.w;
 }
 
-// Claim a slot for each of the lane's eight requests.  `slot_bytes` is the byte address
+// Claim a slot for each of the lane's kCount requests.  `slot_bytes` is the byte address
 // of this lane's first-choice slot in replica 0's ring; replica m's ring is m << ring_shift
 // bytes further on, and ring M is a spare one that absorbs unknown replica ids.
-// The eight steps are taken in groups of kGroup: within a group all first probes are issued
+// The steps are taken in groups of kGroup: within a group all first probes are issued
 // back to back (LDS executes them in order, so the steps still see each other's claims),
 // then the second probes (half a ring away) of the few that lost, then the rest of the ring
 // for those that lost twice.  A larger group hides more LDS latency but lets a retry see
 // claims of up to kGroup * 64 later requests; the host picks kGroup from M and S.
 // Returns true if some request of this lane found no slot or named an unknown replica.
-template <uint32_t kGroup>
-__device__ __forceinline__ bool screen_claim(const uint32_t id[8], const uint32_t arr[8], const uint32_t fin[8],
+template <uint32_t kCount, uint32_t kGroup>
+__device__ __forceinline__ bool screen_claim(const uint32_t* id, const uint32_t* arr, const uint32_t* fin,
                                              unsigned char* lds, uint32_t slot_bytes, uint32_t ring_base_bytes,
                                              uint32_t ring_shift, uint32_t M, uint32_t S, uint32_t my_first) {
     uint32_t top = 0;
     bool lane_bad = false;
 #pragma unroll
-    for (uint32_t g = 0; g < 8u; g += kGroup) {
+    for (uint32_t g = 0; g < kCount; g += kGroup) {
         uint32_t at[kGroup], old[kGroup], old2[kGroup];
 #pragma unroll
         for (uint32_t j = 0; j < kGroup; ++j) {
@@ -384,7 +389,7 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenPara
             {
                 const uint32_t id[8] = {ga.pair[0] & 0xFFFFu, ga.pair[0] >> 16, ga.pair[1] & 0xFFFFu, ga.pair[1] >> 16,
                                         ga.pair[2] & 0xFFFFu, ga.pair[2] >> 16, ga.pair[3] & 0xFFFFu, ga.pair[3] >> 16};
-                bad = __ballot(screen_claim<kGroup>(id, ga.arr, ga.fin, lds, slot_bytes, ring_base_bytes, ring_shift, M, S,
+                bad = __ballot(screen_claim<8, kGroup>(id, ga.arr, ga.fin, lds, slot_bytes, ring_base_bytes, ring_shift, M, S,
                                             my_first)) != 0ull;
             }
             if (bad || b + 1u >= n_full) break;
@@ -392,7 +397,7 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenPara
             {
                 const uint32_t id[8] = {gb.pair[0] & 0xFFFFu, gb.pair[0] >> 16, gb.pair[1] & 0xFFFFu, gb.pair[1] >> 16,
                                         gb.pair[2] & 0xFFFFu, gb.pair[2] >> 16, gb.pair[3] & 0xFFFFu, gb.pair[3] >> 16};
-                bad = __ballot(screen_claim<kGroup>(id, gb.arr, gb.fin, lds, slot_bytes, ring_base_bytes, ring_shift, M, S,
+                bad = __ballot(screen_claim<8, kGroup>(id, gb.arr, gb.fin, lds, slot_bytes, ring_base_bytes, ring_shift, M, S,
                                             my_first)) != 0ull;
             }
             if (bad) break;
@@ -414,7 +419,7 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenPara
                 fin[e] = in ? p.finish_t[i0 + lane * 8u + e] : 0u;
             }
             // ids were clamped to the spare ring, so screen_claim itself reports only lost requests
-            bool lane_bad = screen_claim<kGroup>(id, arr, fin, lds, slot_bytes, ring_base_bytes, ring_shift, M + 1u, S, my_first);
+            bool lane_bad = screen_claim<8, kGroup>(id, arr, fin, lds, slot_bytes, ring_base_bytes, ring_shift, M + 1u, S, my_first);
             bad = __ballot(lane_bad || unknown) != 0ull;
         }
 
@@ -424,6 +429,113 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenPara
             const unsigned long long v = bad ? ~0ull : src[lane];
             reinterpret_cast<unsigned long long*>(&out[c])[lane] = v;
         }
+    }
+}
+
+// The same test with the four wavefronts of a workgroup sharing one candidate: wavefront j
+// takes the two steps 128j + 2l + h of every block (one 4-byte load of an assignment pair
+// and two 8-byte table loads per lane), all four claim from one set of rings, and a
+// barrier per block keeps them within the same 512 requests.  Used when the rings of one
+// candidate are large (M * S >= 2048 words): it quarters the LDS held per wavefront, so that
+// enough wavefronts are resident to hide the LDS and memory latency.
+template <bool kAligned>
+__global__ __launch_bounds__(kScreenThreads) void k_screen_candidates_wide(ScreenParams p,
+                                                                            const uint16_t* __restrict__ assign,
+                                                                            ap_metrics* __restrict__ out, uint32_t C) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, j = tid >> 6;
+    const uint32_t M = p.M, R = p.R, S = 1u << p.slots_log2;
+    const uint32_t ring_shift = p.slots_log2 + 2u;
+    const uint32_t n_words = (M + 1u) << p.slots_log2;                       // M rings and the spare one
+    uint32_t* slot = reinterpret_cast<uint32_t*>(lds);
+    uint32_t* flag = slot + n_words;
+    const uint32_t my_first = lane & (S - 1u);
+    const uint32_t slot_bytes = my_first * 4u;
+    const uint32_t n_full = R / kScreenBlock;
+    const uint32_t mine = 128u * j + 2u * lane;                              // offset of this lane's pair in a block
+
+    for (uint32_t c = blockIdx.x; c < C; c += gridDim.x) {
+        const uint16_t* row = assign + (size_t)c * R;
+        for (uint32_t i = tid; i < n_words; i += kScreenThreads) slot[i] = 0u;
+        if (tid < 2u) flag[tid] = 0u;
+        __syncthreads();
+
+        // Full blocks go in groups of kDepth.  While a group is processed the loads of the next
+        // group are issued, one register set per block, so kDepth blocks stay in flight per
+        // wavefront; the body is straight-line (the prefetch index is clamped instead of
+        // guarded) so the register sets never have to be copied.  A barrier after every block
+        // keeps the four wavefronts within the same 512 requests.  The verdict is exchanged once
+        // per group: group g reports in flag[g & 1], and a wavefront already in the next group
+        // writes the other word, so all wavefronts read the same verdict and leave together.
+        constexpr uint32_t kDepth = 2;
+        uint32_t pair[kDepth];
+        uint2 arr[kDepth], fin[kDepth];
+        auto fetch = [&](uint32_t d, uint32_t blk) {
+            const uint32_t i0 = blk * kScreenBlock;
+            const uint16_t* at = row + i0 + mine;
+            if (kAligned) {
+                pair[d] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(at));
+            } else {
+                pair[d] = (uint32_t)__builtin_nontemporal_load(at) | ((uint32_t)__builtin_nontemporal_load(at + 1) << 16);
+            }
+            arr[d] = *reinterpret_cast<const uint2*>(p.arrival + i0 + mine);
+            fin[d] = *reinterpret_cast<const uint2*>(p.finish + i0 + mine);
+        };
+        auto claim = [&](uint32_t d) {
+            const uint32_t id[2] = {pair[d] & 0xFFFFu, pair[d] >> 16};
+            const uint32_t a[2] = {arr[d].x, arr[d].y}, f[2] = {fin[d].x, fin[d].y};
+            return screen_claim<2, 2>(id, a, f, lds, slot_bytes, 0u, ring_shift, M, S, my_first);
+        };
+        const uint32_t n_groups = n_full / kDepth;
+        bool bad = false;
+        uint32_t turn = 0;                                                   // which flag word the next verdict uses
+        if (n_groups > 0u) {
+#pragma unroll
+            for (uint32_t d = 0; d < kDepth; ++d) fetch(d, d);
+        }
+        for (uint32_t g = 0; g < n_groups && !bad; ++g, ++turn) {
+            bool lane_bad = false;
+#pragma unroll
+            for (uint32_t d = 0; d < kDepth; ++d) {
+                const uint32_t id[2] = {pair[d] & 0xFFFFu, pair[d] >> 16};
+                const uint32_t a[2] = {arr[d].x, arr[d].y}, f[2] = {fin[d].x, fin[d].y};
+                fetch(d, min((g + 1u) * kDepth + d, n_full - 1u));           // refill (redundant in the last group)
+                lane_bad = screen_claim<2, 2>(id, a, f, lds, slot_bytes, 0u, ring_shift, M, S, my_first) || lane_bad;
+                if (d + 1u == kDepth && __ballot(lane_bad) != 0ull && lane == 0) flag[turn & 1u] = 1u;
+                __syncthreads();
+            }
+            bad = flag[turn & 1u] != 0u;
+        }
+        for (uint32_t blk = n_groups * kDepth; blk < n_full && !bad; ++blk, ++turn) {    // fewer than kDepth blocks left
+            fetch(0u, blk);
+            if (__ballot(claim(0u)) != 0ull && lane == 0) flag[turn & 1u] = 1u;
+            __syncthreads();
+            bad = flag[turn & 1u] != 0u;
+        }
+        const uint32_t i0 = n_full * kScreenBlock;
+        if (!bad && i0 < R) {                                                // ragged tail, every access guarded
+            uint32_t id[2], a[2], f[2];
+            bool unknown = false;
+#pragma unroll
+            for (uint32_t h = 0; h < 2u; ++h) {
+                const uint32_t r = i0 + mine + h;
+                const bool in = r < R;
+                const uint32_t m = in ? (uint32_t)row[r] : 0u;
+                unknown = unknown || m >= M;
+                id[h] = in ? min(m, M) : M;
+                a[h] = in ? p.arrival[r] : kNever;                           // an absent request never loses a probe
+                f[h] = in ? p.finish[r] : 0u;
+            }
+            const bool lane_bad = screen_claim<2, 2>(id, a, f, lds, slot_bytes, 0u, ring_shift, M + 1u, S, my_first);
+            if (__ballot(lane_bad || unknown) != 0ull && lane == 0) flag[turn & 1u] = 1u;
+        }
+        __syncthreads();
+        bad = (flag[0] | flag[1]) != 0u;
+        if (tid < 8u) {
+            const unsigned long long* src = reinterpret_cast<const unsigned long long*>(p.nominal);
+            reinterpret_cast<unsigned long long*>(&out[c])[tid] = bad ? ~0ull : src[tid];
+        }
+        __syncthreads();
     }
 }
 
@@ -638,6 +750,7 @@ struct ap_workload {
     uint32_t* d_prompt = nullptr;
     uint32_t* d_out = nullptr;
     DevReplica* d_rep = nullptr;      // capacity AP_MAX_REPLICAS
+    uint32_t* d_finish = nullptr;     // [R] contention-free finish times, valid when screen is set
     uint32_t* d_arrival_t = nullptr;  // lane-major arrival / finish tables, valid when screen is set
     uint32_t* d_finish_t = nullptr;
     ap_metrics* d_nominal = nullptr;  // record shared by all contention-free candidates
@@ -648,6 +761,8 @@ struct ap_workload {
     uint32_t lds_bytes = 0;
     uint32_t screen_lds_bytes = 0;
     uint32_t screen_group = 1;        // steps whose first probes are issued together: 1, 2, 4 or 8
+    bool screen_wide = false;         // four wavefronts per candidate
+    uint32_t screen_wide_lds_bytes = 0;
     uint32_t max_grid = 0;
     uint32_t n_cu = 0;
 };
@@ -710,6 +825,7 @@ ap_status ap_workload_create(const uint64_t* arrival_us, const int32_t* prompt_l
     if (st == AP_OK && (hipMalloc(&w->d_arrival, bytes) != hipSuccess || hipMalloc(&w->d_prompt, bytes) != hipSuccess ||
                         hipMalloc(&w->d_out, bytes) != hipSuccess ||
                         hipMalloc(&w->d_rep, sizeof(DevReplica) * AP_MAX_REPLICAS) != hipSuccess ||
+                        hipMalloc(&w->d_finish, bytes) != hipSuccess ||
                         hipMalloc(&w->d_arrival_t, padded) != hipSuccess ||
                         hipMalloc(&w->d_finish_t, padded) != hipSuccess ||
                         hipMalloc(&w->d_nominal, sizeof(ap_metrics)) != hipSuccess))
@@ -842,6 +958,8 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
         uint32_t S_log2 = 0;
         while ((2u << S_log2) <= std::min(B, kScreenMaxSlots) && M * (2u << S_log2) * 4u <= kScreenLdsPerWave) ++S_log2;
         ScreenParams sp{};
+        sp.arrival = w->d_arrival;
+        sp.finish = w->d_finish;
         sp.arrival_t = w->d_arrival_t;
         sp.finish_t = w->d_finish_t;
         sp.nominal = w->d_nominal;
@@ -853,8 +971,10 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
         // keep that within a quarter of the ring
         w->screen_group = 1;
         while (w->screen_group < 8u && 64u * (w->screen_group * 2u) * 4u <= M << S_log2) w->screen_group *= 2u;
+        w->screen_wide = w->screen_group == 8u;          // exactly the candidates with large rings
+        w->screen_wide_lds_bytes = (((M + 1u) << S_log2) + 4u) * 4u;
         w->screen_lds_bytes = kScreenWaves * ((M + 1u) << S_log2) * 4u;      // M rings and a spare one per wavefront
-        hipLaunchKernelGGL(k_nominal_metrics, dim3(1), dim3(kThreads), bytes, nullptr, p, w->d_arrival_t,
+        hipLaunchKernelGGL(k_nominal_metrics, dim3(1), dim3(kThreads), bytes, nullptr, p, w->d_finish, w->d_arrival_t,
                            w->d_finish_t, w->d_nominal);
         if (hipGetLastError() != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
             (void)hipGetLastError();
@@ -877,6 +997,11 @@ ap_status ap_eval_candidates(const ap_workload* w, const uint16_t* d_assign, uin
         // rows start on 4-byte boundaries when R is even and the batch itself does
         const bool aligned = (w->R % 2u == 0u) && (reinterpret_cast<uintptr_t>(d_assign) % 4u == 0u);
         void (*kernel)(ScreenParams, const uint16_t*, ap_metrics*, uint32_t) = nullptr;
+        if (w->screen_wide) {
+            kernel = aligned ? k_screen_candidates_wide<true> : k_screen_candidates_wide<false>;
+            hipLaunchKernelGGL(kernel, dim3(std::min(C, w->n_cu * 8u)), dim3(kScreenThreads), w->screen_wide_lds_bytes,
+                               stream, w->screen_params, d_assign, d_out, C);
+        } else {
         switch (w->screen_group) {
             case 8: kernel = aligned ? k_screen_candidates<true, 8> : k_screen_candidates<false, 8>; break;
             case 4: kernel = aligned ? k_screen_candidates<true, 4> : k_screen_candidates<false, 4>; break;
@@ -885,6 +1010,7 @@ ap_status ap_eval_candidates(const ap_workload* w, const uint16_t* d_assign, uin
         }
         hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kScreenThreads), w->screen_lds_bytes, stream, w->screen_params,
                            d_assign, d_out, C);
+        }
         if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
     }
     const uint32_t grid = std::min(C, w->max_grid);
@@ -901,6 +1027,7 @@ ap_status ap_workload_destroy(ap_workload* w) {
     if (w->d_prompt) ok = (hipFree(w->d_prompt) == hipSuccess) && ok;
     if (w->d_out) ok = (hipFree(w->d_out) == hipSuccess) && ok;
     if (w->d_rep) ok = (hipFree(w->d_rep) == hipSuccess) && ok;
+    if (w->d_finish) ok = (hipFree(w->d_finish) == hipSuccess) && ok;
     if (w->d_arrival_t) ok = (hipFree(w->d_arrival_t) == hipSuccess) && ok;
     if (w->d_finish_t) ok = (hipFree(w->d_finish_t) == hipSuccess) && ok;
     if (w->d_nominal) ok = (hipFree(w->d_nominal) == hipSuccess) && ok;
