@@ -26,6 +26,41 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 TABLE_BYTES_PER_REQUEST = 16   # arrival + prefill/decode/tpot-class inputs, per replica type
 
+KERNEL_SOURCE = os.path.join(ROOT, "paper_2604_07144_amd", "csrc", "ap_eval.hip")
+# HBM bytes per ap_eval_candidates call from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch, summed over
+# the call's kernels, scaled by what the same counters read for a device copy of known size; see profiles/).
+# Keyed by configuration; valid only for the kernel source whose hash is recorded with it.
+MEASURED_TRAFFIC = {
+    # cfg: (sha256 of the kernel source when measured, bytes per call)
+}
+
+
+def kernel_source_hash() -> str:
+    import hashlib
+    with open(KERNEL_SOURCE, "rb") as f:
+        return hashlib.sha256(f.read()).hexdigest()
+
+
+def measured_traffic(cfg: int):
+    """Recorded HBM traffic for this configuration, or None once the kernels have changed since."""
+    rec = MEASURED_TRAFFIC.get(cfg)
+    if rec is None or rec[0] != kernel_source_hash():
+        return None
+    return rec[1]
+
+
+def copy_calibration(n_bytes: int = 1 << 30, repeats: int = 5) -> int:
+    """A plain device-to-device copy of known size, for scaling the FETCH_SIZE / WRITE_SIZE counters."""
+    import torch
+    src = torch.empty(n_bytes, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    for _ in range(repeats):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_calibration_bytes": n_bytes, "repeats": repeats}))
+    return 0
+
 
 def algorithmic_bytes(C: int, R: int, n_types: int) -> int:
     """Bytes the method itself must move per call: every uint16 assignment once, one 64-byte
@@ -43,7 +78,11 @@ def main() -> int:
     ap.add_argument("--rows", type=int, default=0, help="use only the first ROWS candidates (0 = all)")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the oracle sample (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a 1 GiB device copy (reference dispatch for the HBM byte counters)")
     args = ap.parse_args()
+    if args.calibrate_copy:
+        return copy_calibration()
     if args.gpus != 1:
         print("bench.py: this path runs on one GPU; candidates are independent, so more GPUs would only "
               "split the rows. Run with --gpus 1.", file=sys.stderr)
@@ -93,6 +132,7 @@ def main() -> int:
         binding.ap_workload_destroy(h)
 
     sims = C * R
+    full_batch = (C == tr.C and args.rate_scale == 1.0)
     ms_per_step = wall * 1e3 / args.steps
     avg_kernel_s = float(np.mean(kernel_ms)) * 1e-3
     alg = algorithmic_bytes(C, R, n_types)
@@ -115,8 +155,9 @@ def main() -> int:
                                + (f" arrival rate x{args.rate_scale:g}" if args.rate_scale != 1.0 else ""),
                    "candidates": C, "requests": R, "replicas": M, "slots": tr.B, "replica_types": n_types},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "k_eval_candidates", "kernel_ms_avg": avg_kernel_s * 1e3,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.config) if full_batch else None,
+                     "kernel": "one ap_eval_candidates call (screening kernel + replay of pending candidates)",
+                     "kernel_ms_avg": avg_kernel_s * 1e3,
                      "kernel_ms_min": float(np.min(kernel_ms)), "algorithmic_bytes": alg},
         "mean_ttft_us_row0": int(got["sum_ttft_us"][0]) / R,
         "rejected_row0": int(got["n_rejected"][0]),
@@ -125,10 +166,18 @@ def main() -> int:
     if not args.no_cpu:
         import oracle
         threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")), 16)
-        n_cpu = args.cpu_rows or max(threads, min(C, int(6e8 // max(1, R * M))))
+        orc = oracle.Oracle.from_trace(tr)
+        if args.cpu_rows:
+            n_cpu = args.cpu_rows
+        else:
+            # size the sample for about 15 s of CPU work: time one row per thread first
+            probe = np.stack([tr.assignment_row(int(c)) for c in range(min(C, threads))])
+            t0 = time.perf_counter()
+            orc.eval_batch(probe, nthreads=threads)
+            per_row_cpu_s = max(1e-6, (time.perf_counter() - t0) * threads / probe.shape[0])
+            n_cpu = int(min(C, max(threads, 15.0 / per_row_cpu_s)))
         pick = np.unique(np.linspace(0, C - 1, n_cpu).astype(np.int64))
         rows = np.stack([tr.assignment_row(int(c)) for c in pick])
-        orc = oracle.Oracle.from_trace(tr)
         t0 = time.perf_counter()
         want = orc.eval_batch(rows, nthreads=threads)
         cpu_s = time.perf_counter() - t0
