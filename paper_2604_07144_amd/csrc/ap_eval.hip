@@ -31,9 +31,10 @@
 namespace {
 
 constexpr uint32_t kWave = 64;
-constexpr uint32_t kWaves = 16;                 // wavefronts per workgroup
-constexpr uint32_t kThreads = kWave * kWaves;   // 1024
+constexpr uint32_t kWaves = 8;                  // wavefronts per workgroup
+constexpr uint32_t kThreads = kWave * kWaves;   // 512
 constexpr uint32_t kBins = 4096;
+constexpr uint32_t kBinsPerThread = kBins / kThreads;
 constexpr uint32_t kMaxGroups = 4;              // 64-request groups per wavefront per chunk
 constexpr uint32_t kMaxChunk = kThreads * kMaxGroups;
 constexpr uint32_t kNever = 0xFFFFFFFFu;        // "no such time": larger than every reachable time
@@ -54,7 +55,7 @@ struct EvalParams {
     uint32_t penalty_bin, k99;
     uint64_t penalty;
     // byte offsets into dynamic LDS
-    uint32_t off_slots, off_cnt, off_qstart, off_list, off_arr, off_prompt, off_out, off_misc;
+    uint32_t off_slots, off_sorted, off_cnt, off_qstart, off_list, off_arr, off_prompt, off_out, off_misc;
 };
 
 // ----------------------------------------------------------------------------------
@@ -117,9 +118,48 @@ __device__ __forceinline__ unsigned long long hist_lower_edge(uint32_t bin) {
     return (unsigned long long)(128u | (bin & 127u)) << ((bin >> 7) - 1u);
 }
 
+// Ascending bitonic sort of one value per lane across the wavefront.
+__device__ __forceinline__ uint32_t wave_sort_ascending(uint32_t v, uint32_t lane) {
+#pragma unroll
+    for (uint32_t k = 2; k <= kWave; k <<= 1) {
+#pragma unroll
+        for (uint32_t j = k >> 1; j > 0; j >>= 1) {
+            const uint32_t other = (uint32_t)__shfl_xor((int)v, (int)j);
+            const bool keep_min = ((lane & j) == 0u) == ((lane & k) == 0u);
+            v = keep_min ? min(v, other) : max(v, other);
+        }
+    }
+    return v;
+}
+
+// Lane i receives lane i + 1's value; lane 63 receives `last`.
+__device__ __forceinline__ uint32_t wave_shift_down(uint32_t v, uint32_t last) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)last, (int)v, 0x130 /* wave_shl:1 */, 0xF, 0xF, false);
+}
+
+// The three 4096-bin histograms of a candidate in LDS.  When R < 65536 no count can exceed 16
+// bits, so two bins share a 32-bit word (half the LDS, half the clearing and scanning).
+template <bool kHist16>
+__device__ __forceinline__ void hist_add(uint32_t* hist, uint32_t which, uint32_t bin, uint32_t count) {
+    if (kHist16) atomicAdd(&hist[which * (kBins / 2u) + (bin >> 1)], count << ((bin & 1u) << 4));
+    else atomicAdd(&hist[which * kBins + bin], count);
+}
+
+template <bool kHist16>
+__device__ __forceinline__ uint32_t hist_get(const uint32_t* hist, uint32_t which, uint32_t bin) {
+    if (kHist16) return (hist[which * (kBins / 2u) + (bin >> 1)] >> ((bin & 1u) << 4)) & 0xFFFFu;
+    return hist[which * kBins + bin];
+}
+
+template <bool kHist16>
+__device__ __forceinline__ void hist_clear(uint32_t* hist) {
+    for (uint32_t i = threadIdx.x; i < (kHist16 ? 3u * kBins / 2u : 3u * kBins); i += kThreads) hist[i] = 0u;
+}
+
 // Block-wide end of one candidate: fold the per-lane sums, add the rejected requests at the
 // penalty value, find the three p99 bins by a prefix sum over the histograms and write the
 // record.  Called by all kThreads threads; `hist` holds the served requests' counts.
+template <bool kHist16>
 __device__ __forceinline__ void finish_candidate(const EvalParams& p, uint32_t* hist, unsigned long long* acc64,
                                                  uint32_t* acc32, uint32_t* wtot, unsigned long long s_e2e,
                                                  unsigned long long s_ttft, unsigned long long s_tpot,
@@ -142,15 +182,16 @@ __device__ __forceinline__ void finish_candidate(const EvalParams& p, uint32_t* 
     }
     __syncthreads();
     const uint32_t rejected = acc32[2];
-    if (tid < 3u && rejected) hist[tid * kBins + p.penalty_bin] += rejected;
+    if (tid < 3u && rejected) hist_add<kHist16>(hist, tid, p.penalty_bin, rejected);
     __syncthreads();
 
-    // p99: block-wide prefix sum over the bins, 4 bins per thread, three histograms at once
+    // p99: block-wide prefix sum over the bins, kBinsPerThread bins per thread, three histograms at once
     uint32_t part[3], incl[3];
 #pragma unroll
     for (uint32_t h = 0; h < 3u; ++h) {
-        const uint32_t* hb = hist + h * kBins + 4u * tid;
-        part[h] = hb[0] + hb[1] + hb[2] + hb[3];
+        part[h] = 0;
+#pragma unroll
+        for (uint32_t i = 0; i < kBinsPerThread; ++i) part[h] += hist_get<kHist16>(hist, h, kBinsPerThread * tid + i);
         incl[h] = wave_inclusive_scan(part[h], lane);
         if (lane == 63u) wtot[h * kWaves + w] = incl[h];
     }
@@ -159,15 +200,14 @@ __device__ __forceinline__ void finish_candidate(const EvalParams& p, uint32_t* 
     for (uint32_t h = 0; h < 3u; ++h) {
         uint32_t before = 0;
         for (uint32_t ww = 0; ww < w; ++ww) before += wtot[h * kWaves + ww];
-        uint32_t hi = before + incl[h], lo = hi - part[h];
+        const uint32_t hi = before + incl[h], lo = hi - part[h];
         if (lo < p.k99 && p.k99 <= hi) {
-            const uint32_t* hb = hist + h * kBins + 4u * tid;
             uint32_t run = lo, b = 0;
-            for (; b < 3u; ++b) {
-                run += hb[b];
+            for (; b + 1u < kBinsPerThread; ++b) {
+                run += hist_get<kHist16>(hist, h, kBinsPerThread * tid + b);
                 if (run >= p.k99) break;
             }
-            acc32[3 + h] = 4u * tid + b;
+            acc32[3 + h] = kBinsPerThread * tid + b;
         }
     }
     __syncthreads();
@@ -216,6 +256,7 @@ __host__ __device__ inline uint32_t screen_table_index(uint32_t r) {
 // lane-major layout), and reduces the values to the record every contention-free candidate
 // shares.
 // One workgroup.
+template <bool kHist16>
 __global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint32_t* __restrict__ finish,
                                                               uint32_t* __restrict__ arrival_t,
                                                               uint32_t* __restrict__ finish_t,
@@ -226,7 +267,7 @@ __global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint
     uint32_t* acc32 = reinterpret_cast<uint32_t*>(lds + p.off_misc + 24);
     uint32_t* wtot = reinterpret_cast<uint32_t*>(lds + p.off_misc + 64);
     const uint32_t tid = threadIdx.x;
-    for (uint32_t i = tid; i < 3u * kBins; i += kThreads) hist[i] = 0u;
+    hist_clear<kHist16>(hist);
     if (tid < 16u) reinterpret_cast<uint32_t*>(acc64)[tid] = 0u;
     __syncthreads();
     const DevReplica rp = p.rep[0];
@@ -240,16 +281,16 @@ __global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint
         finish[r] = p.arrival[r] + e2e;
         arrival_t[screen_table_index(r)] = p.arrival[r];
         finish_t[screen_table_index(r)] = p.arrival[r] + e2e;
-        atomicAdd(&hist[hist_bin_u32(prefill)], 1u);
-        atomicAdd(&hist[kBins + hist_bin_u32(tpot)], 1u);
-        atomicAdd(&hist[2u * kBins + hist_bin_u32(e2e)], 1u);
+        hist_add<kHist16>(hist, 0u, hist_bin_u32(prefill), 1u);
+        hist_add<kHist16>(hist, 1u, hist_bin_u32(tpot), 1u);
+        hist_add<kHist16>(hist, 2u, hist_bin_u32(e2e), 1u);
         s_ttft += prefill;
         s_e2e += e2e;
         s_tpot += tpot;
         last_fin = max(last_fin, p.arrival[r] + e2e);
         n_ok += (prefill <= p.slo_ttft && tpot <= p.slo_tpot) ? 1u : 0u;
     }
-    finish_candidate(p, hist, acc64, acc32, wtot, s_e2e, s_ttft, s_tpot, last_fin, n_ok, 0u, nominal);
+    finish_candidate<kHist16>(p, hist, acc64, acc32, wtot, s_e2e, s_ttft, s_tpot, last_fin, n_ok, 0u, nominal);
 }
 
 // ----------------------------------------------------------------------------------
@@ -540,16 +581,29 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates_wide(Scree
 }
 
 // ----------------------------------------------------------------------------------
-// the evaluation kernel
+// the evaluation kernel (exact replay)
 // ----------------------------------------------------------------------------------
-//
 // only_pending != 0: score just the candidates whose record carries the "still to do" mark
 // left by the screening kernel; every other record is final and is not touched.
+//
+// Replay of one replica's queue segment, 64 requests at a time (one per lane), with the B
+// slot-free times one per lane:
+//  * if at least as many slots are free at the first request's ready time as there are
+//    requests, every request starts when it is ready (free slots stay free for later
+//    requests because ready times do not decrease) and the finish times are routed to the
+//    free lanes in one permute;
+//  * otherwise the requests are taken one by one with the slot times kept sorted across the
+//    lanes: lane 0 holds the earliest-free slot, start = max(ready, lane 0), and the new
+//    finish time is inserted by one shift-and-compare (new[i] = min(S[i+1], max(S[i], f))).
+//    The slots are sorted (bitonic, across lanes) when this mode is entered after a
+//    permute-mode update.
+template <bool kHist16>
 __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, const uint16_t* __restrict__ assign,
                                                               ap_metrics* out, uint32_t C, uint32_t only_pending) {
     extern __shared__ __align__(16) unsigned char lds[];
-    uint32_t* hist = reinterpret_cast<uint32_t*>(lds);                        // [3][kBins]
+    uint32_t* hist = reinterpret_cast<uint32_t*>(lds);                        // three histograms
     uint32_t* slots = reinterpret_cast<uint32_t*>(lds + p.off_slots);         // [M][B] slot-free times
+    uint32_t* sorted = reinterpret_cast<uint32_t*>(lds + p.off_sorted);       // [M] slots ascending across lanes?
     uint32_t* cnt = reinterpret_cast<uint32_t*>(lds + p.off_cnt);             // [kWaves][M+1]
     uint32_t* qstart = reinterpret_cast<uint32_t*>(lds + p.off_qstart);       // [M+2]
     uint16_t* list = reinterpret_cast<uint16_t*>(lds + p.off_list);           // [chunk] indices by replica
@@ -570,8 +624,9 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
         if (only_pending && !is_pending(out[c])) continue;      // same record for every thread: uniform
         const uint16_t* row = assign + (size_t)c * R;
 
-        for (uint32_t i = tid; i < 3u * kBins; i += kThreads) hist[i] = 0u;
+        hist_clear<kHist16>(hist);
         for (uint32_t i = tid; i < M * B; i += kThreads) slots[i] = 0u;
+        for (uint32_t i = tid; i < M; i += kThreads) sorted[i] = 1u;       // all zero is sorted
         if (tid < 16u) reinterpret_cast<uint32_t*>(acc64)[tid] = 0u;
         unsigned long long s_e2e = 0, s_ttft = 0, s_tpot = 0;
         uint32_t last_fin = 0, n_ok = 0, n_rej = 0;
@@ -655,50 +710,52 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
                 if (qn == 0) continue;
                 const DevReplica rp = p.rep[m];
                 uint32_t S = lane < B ? slots[m * B + lane] : kNever;
+                bool in_order = sorted[m] != 0u;
                 for (uint32_t sb = 0; sb < qn; sb += kWave) {
                     const uint32_t nb = min(kWave, qn - sb);
                     const bool valid = lane < nb;
                     const uint32_t li = valid ? (uint32_t)list[qs + sb + lane] : 0u;
                     const uint32_t arr = c_arr[li], prm = c_prompt[li], ol = c_out[li];
-                    const uint32_t now = max(arr, rp.t_on);
+                    const uint32_t ready = max(arr, rp.t_on);
                     const uint32_t prefill = rp.a + rp.b * prm;
                     const uint32_t tpot = rp.c + rp.d * ((prm + 1023u) >> 10);
                     const uint32_t dec = ol * tpot;
                     const uint32_t svc = prefill + dec;
                     // requests are in arrival order, so those arriving inside the window are a prefix
-                    const uint32_t n_open = __popcll(__ballot(valid && now < rp.t_off));
-                    uint32_t start = now;
-                    uint32_t j = 0;
-                    while (j < n_open) {
-                        const uint32_t now_j = (uint32_t)__builtin_amdgcn_readlane((int)now, (int)j);
-                        const unsigned long long idle = __ballot(S <= now_j);
-                        const uint32_t n_idle = __popcll(idle);
-                        if (n_idle == 0) {
-                            // every slot busy: the request takes the earliest-free one
-                            const uint32_t u = wave_min_u32(S);
-                            if (u >= rp.t_off) break;
-                            const uint32_t fin_j = u + (uint32_t)__builtin_amdgcn_readlane((int)svc, (int)j);
-                            const uint32_t sl = (uint32_t)__ffsll((long long)__ballot(S == u)) - 1u;
-                            if (lane == sl) S = fin_j;
-                            if (lane == j) start = u;
-                            j += 1u;
-                        } else {
-                            // n_idle slots are free now and stay free: the next n_idle requests start on arrival
-                            const uint32_t g = min(n_idle, n_open - j);
+                    const uint32_t n_open = __popcll(__ballot(valid && ready < rp.t_off));
+                    uint32_t start = ready;
+                    uint32_t n_served = n_open;
+                    if (n_open > 0u) {
+                        const uint32_t ready0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)ready);
+                        const unsigned long long idle = __ballot(S <= ready0);
+                        if ((uint32_t)__popcll(idle) >= n_open) {
+                            // enough free slots for the whole block: request i takes the i-th free lane
                             const uint32_t ri = __popcll(idle & lanes_below);
-                            const uint32_t fin = now + svc;
-                            const uint32_t take = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(((j + ri) & 63u) << 2), (int)fin);
-                            if (((idle >> lane) & 1ull) && ri < g) S = take;
-                            j += g;
+                            const uint32_t fin = ready + svc;
+                            const uint32_t take = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(ri << 2), (int)fin);
+                            if (((idle >> lane) & 1ull) && ri < n_open) S = take;
+                            in_order = false;
+                        } else {
+                            if (!in_order) S = wave_sort_ascending(S, lane);
+                            in_order = true;
+                            uint32_t j = 0;
+                            for (; j < n_open; ++j) {
+                                const uint32_t u = (uint32_t)__builtin_amdgcn_readfirstlane((int)S);
+                                const uint32_t st = max((uint32_t)__builtin_amdgcn_readlane((int)ready, (int)j), u);
+                                if (st >= rp.t_off) break;
+                                const uint32_t fj = st + (uint32_t)__builtin_amdgcn_readlane((int)svc, (int)j);
+                                S = min(wave_shift_down(S, kNever), max(S, fj));
+                                if (lane == j) start = st;
+                            }
+                            n_served = j;
                         }
                     }
-                    const bool served = lane < j;
-                    if (served) {
+                    if (lane < n_served) {
                         const uint32_t ttft = start - arr + prefill;
                         const uint32_t e2e = ttft + dec;
-                        atomicAdd(&hist[hist_bin_u32(ttft)], 1u);
-                        atomicAdd(&hist[kBins + hist_bin_u32(tpot)], 1u);
-                        atomicAdd(&hist[2u * kBins + hist_bin_u32(e2e)], 1u);
+                        hist_add<kHist16>(hist, 0u, hist_bin_u32(ttft), 1u);
+                        hist_add<kHist16>(hist, 1u, hist_bin_u32(tpot), 1u);
+                        hist_add<kHist16>(hist, 2u, hist_bin_u32(e2e), 1u);
                         s_ttft += ttft;
                         s_e2e += e2e;
                         s_tpot += tpot;
@@ -709,11 +766,12 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
                     }
                 }
                 if (lane < B) slots[m * B + lane] = S;
+                if (lane == 0) sorted[m] = in_order ? 1u : 0u;
             }
             __syncthreads();
         }
 
-        finish_candidate(p, hist, acc64, acc32, wtot, s_e2e, s_ttft, s_tpot, last_fin, n_ok, n_rej, &out[c]);
+        finish_candidate<kHist16>(p, hist, acc64, acc32, wtot, s_e2e, s_ttft, s_tpot, last_fin, n_ok, n_rej, &out[c]);
         __syncthreads();
     }
 }
@@ -724,9 +782,10 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
 inline uint32_t align_up(uint32_t v, uint32_t a) { return (v + a - 1u) / a * a; }
 
 // LDS layout for a given chunk size; returns total bytes.
-uint32_t plan_lds(EvalParams& p, uint32_t chunk) {
-    uint32_t off = 3u * kBins * 4u;
+uint32_t plan_lds(EvalParams& p, uint32_t chunk, bool hist16) {
+    uint32_t off = 3u * kBins * (hist16 ? 2u : 4u);
     p.off_slots = off;  off += align_up(p.M * p.B * 4u, 16u);
+    p.off_sorted = off; off += align_up(p.M * 4u, 16u);
     p.off_cnt = off;    off += align_up(kWaves * (p.M + 1u) * 4u, 16u);
     p.off_qstart = off; off += align_up((p.M + 2u) * 4u, 16u);
     p.off_list = off;   off += align_up(chunk * 2u, 16u);
@@ -756,6 +815,7 @@ struct ap_workload {
     ap_metrics* d_nominal = nullptr;  // record shared by all contention-free candidates
     bool has_model = false;
     bool screen = false;              // homogeneous, always-on replicas: screening applies
+    bool hist16 = false;              // R < 65536: 16-bit histogram counters
     EvalParams params{};
     ScreenParams screen_params{};
     uint32_t lds_bytes = 0;
@@ -897,12 +957,21 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
     EvalParams p{};
     p.M = M;
     p.B = B;
-    uint32_t bytes = 0, chunk = kMaxChunk;
-    for (; chunk >= kThreads; chunk -= kThreads) {
-        bytes = plan_lds(p, chunk);
-        if (bytes <= (uint32_t)lds_cap) break;
+    // No bin can count more than R requests, so below 65536 requests two bins share a word.
+    const bool hist16 = w->R < 65536u;
+    // Prefer a layout that lets two workgroups share a compute unit (they cover each other's
+    // barriers), as long as the chunk stays at least half the largest one.
+    uint32_t bytes = 0, chunk = 0;
+    for (uint32_t budget : {(uint32_t)lds_cap / 2u, (uint32_t)lds_cap}) {
+        const uint32_t smallest = budget == (uint32_t)lds_cap ? kThreads : kMaxChunk / 2u;
+        for (chunk = kMaxChunk; chunk >= smallest; chunk -= kThreads) {
+            bytes = plan_lds(p, chunk, hist16);
+            if (bytes <= budget) break;
+        }
+        if (chunk >= smallest) break;
+        chunk = 0;
     }
-    if (chunk < kThreads) return AP_ERR_RANGE;
+    if (chunk == 0) return AP_ERR_RANGE;
 
     std::vector<DevReplica> dev(M);
     for (uint32_t m = 0; m < M; ++m) {
@@ -921,9 +990,11 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
         }
     }
     if (hipMemcpy(w->d_rep, dev.data(), sizeof(DevReplica) * M, hipMemcpyHostToDevice) != hipSuccess ||
-        hipFuncSetAttribute(reinterpret_cast<const void*>(&k_eval_candidates),
+        hipFuncSetAttribute(hist16 ? reinterpret_cast<const void*>(&k_eval_candidates<true>)
+                                   : reinterpret_cast<const void*>(&k_eval_candidates<false>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess ||
-        hipFuncSetAttribute(reinterpret_cast<const void*>(&k_nominal_metrics),
+        hipFuncSetAttribute(hist16 ? reinterpret_cast<const void*>(&k_nominal_metrics<true>)
+                                   : reinterpret_cast<const void*>(&k_nominal_metrics<false>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) {
         (void)hipGetLastError();
         w->has_model = false;     // the replica table on the device may be half-written
@@ -945,8 +1016,9 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
     w->has_model = false;
     w->params = p;
     w->lds_bytes = bytes;
+    w->hist16 = hist16;
     w->n_cu = (uint32_t)n_cu;
-    w->max_grid = (uint32_t)n_cu * 4u;
+    w->max_grid = (uint32_t)n_cu * 8u;
 
     // ---- screening plan: only for identical replicas that are available throughout ------
     bool always_on = true;
@@ -974,8 +1046,8 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
         w->screen_wide = w->screen_group == 8u;          // exactly the candidates with large rings
         w->screen_wide_lds_bytes = (((M + 1u) << S_log2) + 4u) * 4u;
         w->screen_lds_bytes = kScreenWaves * ((M + 1u) << S_log2) * 4u;      // M rings and a spare one per wavefront
-        hipLaunchKernelGGL(k_nominal_metrics, dim3(1), dim3(kThreads), bytes, nullptr, p, w->d_finish, w->d_arrival_t,
-                           w->d_finish_t, w->d_nominal);
+        hipLaunchKernelGGL(hist16 ? k_nominal_metrics<true> : k_nominal_metrics<false>, dim3(1), dim3(kThreads), bytes,
+                           nullptr, p, w->d_finish, w->d_arrival_t, w->d_finish_t, w->d_nominal);
         if (hipGetLastError() != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
             (void)hipGetLastError();
             return AP_ERR_DEVICE;
@@ -1014,8 +1086,8 @@ ap_status ap_eval_candidates(const ap_workload* w, const uint16_t* d_assign, uin
         if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
     }
     const uint32_t grid = std::min(C, w->max_grid);
-    hipLaunchKernelGGL(k_eval_candidates, dim3(grid), dim3(kThreads), w->lds_bytes, stream, w->params, d_assign,
-                       d_out, C, w->screen ? 1u : 0u);
+    hipLaunchKernelGGL(w->hist16 ? k_eval_candidates<true> : k_eval_candidates<false>, dim3(grid), dim3(kThreads),
+                       w->lds_bytes, stream, w->params, d_assign, d_out, C, w->screen ? 1u : 0u);
     if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
     return AP_OK;
 }
