@@ -24,6 +24,7 @@
 #include <cstdint>
 #include <cstring>
 #include <new>
+#include <type_traits>
 #include <vector>
 
 #include "autopoiesis_eval.h"
@@ -35,7 +36,7 @@ constexpr uint32_t kWaves = 8;                  // wavefronts per workgroup
 constexpr uint32_t kThreads = kWave * kWaves;   // 512
 constexpr uint32_t kBins = 4096;
 constexpr uint32_t kBinsPerThread = kBins / kThreads;
-constexpr uint32_t kMaxGroups = 4;              // 64-request groups per wavefront per chunk
+constexpr uint32_t kMaxGroups = 8;              // 64-request groups per wavefront per chunk
 constexpr uint32_t kMaxChunk = kThreads * kMaxGroups;
 constexpr uint32_t kNever = 0xFFFFFFFFu;        // "no such time": larger than every reachable time
 constexpr uint32_t kNoKey = 0xFFFFFFFFu;
@@ -55,28 +56,16 @@ struct EvalParams {
     uint32_t penalty_bin, k99;
     uint64_t penalty;
     // byte offsets into dynamic LDS
-    uint32_t off_slots, off_sorted, off_cnt, off_qstart, off_list, off_arr, off_prompt, off_out, off_misc;
+    uint32_t off_slots, off_sorted, off_close, off_cnt, off_qstart, off_list, off_arr, off_prompt, off_out, off_misc;
 };
 
 // ----------------------------------------------------------------------------------
 // wavefront helpers (64 lanes)
 // ----------------------------------------------------------------------------------
-template <int kCtrl>
-__device__ __forceinline__ uint32_t dpp_move(uint32_t v) {
-    // lanes whose source is outside the row keep their own value
-    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, kCtrl, 0xF, 0xF, false);
-}
-
-// Minimum over the 64 lanes, returned as a wave-uniform value.
-__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
-    v = min(v, dpp_move<0xB1>(v));    // quad_perm [1,0,3,2]
-    v = min(v, dpp_move<0x4E>(v));    // quad_perm [2,3,0,1]
-    v = min(v, dpp_move<0x141>(v));   // row_half_mirror
-    v = min(v, dpp_move<0x140>(v));   // row_mirror: every lane of a 16-lane row holds the row minimum
-    v = min(v, (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x401F));   // lane ^ 16 within 32
-    uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)v, 0);
-    uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)v, 32);
-    return min(lo, hi);
+// Index of this wavefront in its workgroup, as a wave-uniform (scalar) value: loops and
+// table lookups that depend on it then stay on the scalar unit.
+__device__ __forceinline__ uint32_t wave_index() {
+    return (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
 }
 
 __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v, uint32_t lane) {
@@ -165,7 +154,8 @@ __device__ __forceinline__ void finish_candidate(const EvalParams& p, uint32_t* 
                                                  unsigned long long s_ttft, unsigned long long s_tpot,
                                                  uint32_t last_fin, uint32_t n_ok, uint32_t n_rej,
                                                  ap_metrics* __restrict__ dst) {
-    const uint32_t tid = threadIdx.x, lane = tid & 63u, w = tid >> 6;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t w = wave_index();
     s_e2e = wave_sum_u64(s_e2e);
     s_ttft = wave_sum_u64(s_ttft);
     s_tpot = wave_sum_u64(s_tpot);
@@ -408,7 +398,7 @@ template <bool kAligned, uint32_t kGroup>
 __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenParams p, const uint16_t* __restrict__ assign,
                                                                        ap_metrics* __restrict__ out, uint32_t C) {
     extern __shared__ __align__(16) unsigned char lds[];
-    const uint32_t lane = threadIdx.x & 63u, w = threadIdx.x >> 6;
+    const uint32_t lane = threadIdx.x & 63u, w = wave_index();
     const uint32_t M = p.M, R = p.R, S = 1u << p.slots_log2;
     const uint32_t ring_shift = p.slots_log2 + 2u;                           // bytes per ring, log2
     const uint32_t ring_base_bytes = w * ((M + 1u) << ring_shift);          // this wavefront's M + 1 rings
@@ -484,7 +474,7 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates_wide(Scree
                                                                             const uint16_t* __restrict__ assign,
                                                                             ap_metrics* __restrict__ out, uint32_t C) {
     extern __shared__ __align__(16) unsigned char lds[];
-    const uint32_t tid = threadIdx.x, lane = tid & 63u, j = tid >> 6;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, j = wave_index();
     const uint32_t M = p.M, R = p.R, S = 1u << p.slots_log2;
     const uint32_t ring_shift = p.slots_log2 + 2u;
     const uint32_t n_words = (M + 1u) << p.slots_log2;                       // M rings and the spare one
@@ -597,9 +587,12 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates_wide(Scree
 //    finish time is inserted by one shift-and-compare (new[i] = min(S[i+1], max(S[i], f))).
 //    The slots are sorted (bitonic, across lanes) when this mode is entered after a
 //    permute-mode update.
-template <bool kHist16>
+//
+// kLen16: every prompt and output length is below 65536, so the staged copies are 16-bit.
+template <bool kHist16, bool kLen16>
 __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, const uint16_t* __restrict__ assign,
                                                               ap_metrics* out, uint32_t C, uint32_t only_pending) {
+    using len_t = typename std::conditional<kLen16, uint16_t, uint32_t>::type;
     extern __shared__ __align__(16) unsigned char lds[];
     uint32_t* hist = reinterpret_cast<uint32_t*>(lds);                        // three histograms
     uint32_t* slots = reinterpret_cast<uint32_t*>(lds + p.off_slots);         // [M][B] slot-free times
@@ -608,14 +601,17 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
     uint32_t* qstart = reinterpret_cast<uint32_t*>(lds + p.off_qstart);       // [M+2]
     uint16_t* list = reinterpret_cast<uint16_t*>(lds + p.off_list);           // [chunk] indices by replica
     uint32_t* c_arr = reinterpret_cast<uint32_t*>(lds + p.off_arr);           // [chunk] staged trace
-    uint32_t* c_prompt = reinterpret_cast<uint32_t*>(lds + p.off_prompt);
-    uint32_t* c_out = reinterpret_cast<uint32_t*>(lds + p.off_out);
+    len_t* c_prompt = reinterpret_cast<len_t*>(lds + p.off_prompt);
+    len_t* c_out = reinterpret_cast<len_t*>(lds + p.off_out);
+    uint32_t* t_close = reinterpret_cast<uint32_t*>(lds + p.off_close);       // [M+1] t_off per replica, 0 for "no replica"
     unsigned long long* acc64 = reinterpret_cast<unsigned long long*>(lds + p.off_misc);   // e2e, ttft, tpot
     uint32_t* acc32 = reinterpret_cast<uint32_t*>(lds + p.off_misc + 24);     // makespan, slo_ok, n_rej, p99 bins[3]
     uint32_t* wtot = reinterpret_cast<uint32_t*>(lds + p.off_misc + 64);      // [3][kWaves] scan carries
 
-    const uint32_t tid = threadIdx.x, lane = tid & 63u, w = tid >> 6;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t w = wave_index();
     const uint32_t R = p.R, M = p.M, B = p.B, M1 = p.M + 1u;
+    for (uint32_t m = tid; m <= M; m += kThreads) t_close[m] = m < M ? p.rep[m].t_off : 0u;
     const uint32_t per_wave = p.chunk / kWaves;       // multiple of 64
     const uint32_t groups = per_wave / kWave;         // <= kMaxGroups
     const unsigned long long lanes_below = (1ull << lane) - 1ull;
@@ -638,8 +634,8 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
             // ---- stage the chunk of the trace; read this wavefront's assignments -----------
             for (uint32_t i = tid; i < n; i += kThreads) {
                 c_arr[i] = p.arrival[r0 + i];
-                c_prompt[i] = p.prompt[r0 + i];
-                c_out[i] = p.outlen[r0 + i];
+                c_prompt[i] = (len_t)p.prompt[r0 + i];
+                c_out[i] = (len_t)p.outlen[r0 + i];
             }
             for (uint32_t i = tid; i < kWaves * M1; i += kThreads) cnt[i] = 0u;
             uint32_t key[kMaxGroups];
@@ -649,6 +645,14 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
                 key[g] = (g < groups && idx < n) ? min((uint32_t)row[r0 + idx], M) : kNoKey;
             }
             __syncthreads();
+            // a request that arrives when its replica is already gone can never start: reject it
+            // here (key M, like an unknown replica) instead of queueing it
+#pragma unroll
+            for (uint32_t g = 0; g < kMaxGroups; ++g) {
+                if (key[g] == kNoKey) continue;
+                const uint32_t idx = w * per_wave + g * kWave + lane;
+                if (c_arr[idx] >= t_close[key[g]]) key[g] = M;
+            }
 
             // ---- (1) per-wavefront replica histogram ---------------------------------------
 #pragma unroll
@@ -698,7 +702,7 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
                     list[base + rank] = (uint16_t)(w * per_wave + g * kWave + lane);
                     if (rank + 1u == total) cnt[w * M1 + k] += total;
                 } else if (k == M) {
-                    n_rej += 1u;        // replica id outside the table
+                    n_rej += 1u;        // no such replica, or it left before the request arrived
                 }
             }
             __syncthreads();
@@ -708,14 +712,21 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
                 const uint32_t qs = qstart[m];
                 const uint32_t qn = qstart[m + 1] - qs;
                 if (qn == 0) continue;
-                const DevReplica rp = p.rep[m];
+                // the replica's parameters are the same for every lane: keep them on the scalar unit
+                DevReplica rp = p.rep[m];
+                rp.a = (uint32_t)__builtin_amdgcn_readfirstlane((int)rp.a);
+                rp.b = (uint32_t)__builtin_amdgcn_readfirstlane((int)rp.b);
+                rp.c = (uint32_t)__builtin_amdgcn_readfirstlane((int)rp.c);
+                rp.d = (uint32_t)__builtin_amdgcn_readfirstlane((int)rp.d);
+                rp.t_on = (uint32_t)__builtin_amdgcn_readfirstlane((int)rp.t_on);
+                rp.t_off = (uint32_t)__builtin_amdgcn_readfirstlane((int)rp.t_off);
                 uint32_t S = lane < B ? slots[m * B + lane] : kNever;
-                bool in_order = sorted[m] != 0u;
+                bool in_order = __builtin_amdgcn_readfirstlane((int)sorted[m]) != 0;
                 for (uint32_t sb = 0; sb < qn; sb += kWave) {
                     const uint32_t nb = min(kWave, qn - sb);
                     const bool valid = lane < nb;
                     const uint32_t li = valid ? (uint32_t)list[qs + sb + lane] : 0u;
-                    const uint32_t arr = c_arr[li], prm = c_prompt[li], ol = c_out[li];
+                    const uint32_t arr = c_arr[li], prm = c_prompt[li], ol = c_out[li];     // widened to 32 bits
                     const uint32_t ready = max(arr, rp.t_on);
                     const uint32_t prefill = rp.a + rp.b * prm;
                     const uint32_t tpot = rp.c + rp.d * ((prm + 1023u) >> 10);
@@ -782,19 +793,27 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
 inline uint32_t align_up(uint32_t v, uint32_t a) { return (v + a - 1u) / a * a; }
 
 // LDS layout for a given chunk size; returns total bytes.
-uint32_t plan_lds(EvalParams& p, uint32_t chunk, bool hist16) {
+uint32_t plan_lds(EvalParams& p, uint32_t chunk, bool hist16, bool len16) {
     uint32_t off = 3u * kBins * (hist16 ? 2u : 4u);
     p.off_slots = off;  off += align_up(p.M * p.B * 4u, 16u);
     p.off_sorted = off; off += align_up(p.M * 4u, 16u);
+    p.off_close = off;  off += align_up((p.M + 1u) * 4u, 16u);
     p.off_cnt = off;    off += align_up(kWaves * (p.M + 1u) * 4u, 16u);
     p.off_qstart = off; off += align_up((p.M + 2u) * 4u, 16u);
     p.off_list = off;   off += align_up(chunk * 2u, 16u);
     p.off_arr = off;    off += chunk * 4u;
-    p.off_prompt = off; off += chunk * 4u;
-    p.off_out = off;    off += chunk * 4u;
+    p.off_prompt = off; off += align_up(chunk * (len16 ? 2u : 4u), 16u);
+    p.off_out = off;    off += align_up(chunk * (len16 ? 2u : 4u), 16u);
     p.off_misc = off;   off += 64u + 3u * kWaves * 4u;
     p.chunk = chunk;
     return off;
+}
+
+using EvalKernel = void (*)(EvalParams, const uint16_t*, ap_metrics*, uint32_t, uint32_t);
+
+EvalKernel eval_kernel(bool hist16, bool len16) {
+    if (hist16) return len16 ? k_eval_candidates<true, true> : k_eval_candidates<true, false>;
+    return len16 ? k_eval_candidates<false, true> : k_eval_candidates<false, false>;
 }
 
 }  // namespace
@@ -816,6 +835,7 @@ struct ap_workload {
     bool has_model = false;
     bool screen = false;              // homogeneous, always-on replicas: screening applies
     bool hist16 = false;              // R < 65536: 16-bit histogram counters
+    bool len16 = false;               // every prompt and output length < 65536: 16-bit staging
     EvalParams params{};
     ScreenParams screen_params{};
     uint32_t lds_bytes = 0;
@@ -873,6 +893,8 @@ ap_status ap_workload_create(const uint64_t* arrival_us, const int32_t* prompt_l
         return AP_ERR_ALLOC;
     }
     w->R = R;
+    w->len16 = true;
+    for (uint32_t r = 0; r < R; ++r) w->len16 = w->len16 && prompt_len[r] < 65536 && out_len[r] < 65536;
     w->base_us = arrival_us[0];
     w->span_us = arrival_us[R - 1] - arrival_us[0];
     // relative 32-bit arrivals; a span that does not fit is refused later by ap_costmodel_set
@@ -959,13 +981,16 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
     p.B = B;
     // No bin can count more than R requests, so below 65536 requests two bins share a word.
     const bool hist16 = w->R < 65536u;
-    // Prefer a layout that lets two workgroups share a compute unit (they cover each other's
-    // barriers), as long as the chunk stays at least half the largest one.
+    // A chunk should hand each replica about 48 requests, so that the 64-lane blocks of the
+    // replay are mostly full and rarely spill into a second block; more than that only costs
+    // LDS.  Prefer a size that lets two workgroups share a compute unit (they cover each
+    // other's barriers); otherwise take the largest chunk one workgroup can hold.
+    const uint32_t want = std::min(kMaxChunk, std::max(2u * kThreads, align_up(48u * M, kThreads)));
     uint32_t bytes = 0, chunk = 0;
     for (uint32_t budget : {(uint32_t)lds_cap / 2u, (uint32_t)lds_cap}) {
-        const uint32_t smallest = budget == (uint32_t)lds_cap ? kThreads : kMaxChunk / 2u;
-        for (chunk = kMaxChunk; chunk >= smallest; chunk -= kThreads) {
-            bytes = plan_lds(p, chunk, hist16);
+        const uint32_t smallest = budget == (uint32_t)lds_cap ? kThreads : std::max(kThreads, want / 2u);
+        for (chunk = want; chunk >= smallest; chunk -= kThreads) {
+            bytes = plan_lds(p, chunk, hist16, w->len16);
             if (bytes <= budget) break;
         }
         if (chunk >= smallest) break;
@@ -990,8 +1015,7 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
         }
     }
     if (hipMemcpy(w->d_rep, dev.data(), sizeof(DevReplica) * M, hipMemcpyHostToDevice) != hipSuccess ||
-        hipFuncSetAttribute(hist16 ? reinterpret_cast<const void*>(&k_eval_candidates<true>)
-                                   : reinterpret_cast<const void*>(&k_eval_candidates<false>),
+        hipFuncSetAttribute(reinterpret_cast<const void*>(eval_kernel(hist16, w->len16)),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess ||
         hipFuncSetAttribute(hist16 ? reinterpret_cast<const void*>(&k_nominal_metrics<true>)
                                    : reinterpret_cast<const void*>(&k_nominal_metrics<false>),
@@ -1086,8 +1110,8 @@ ap_status ap_eval_candidates(const ap_workload* w, const uint16_t* d_assign, uin
         if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
     }
     const uint32_t grid = std::min(C, w->max_grid);
-    hipLaunchKernelGGL(w->hist16 ? k_eval_candidates<true> : k_eval_candidates<false>, dim3(grid), dim3(kThreads),
-                       w->lds_bytes, stream, w->params, d_assign, d_out, C, w->screen ? 1u : 0u);
+    hipLaunchKernelGGL(eval_kernel(w->hist16, w->len16), dim3(grid), dim3(kThreads), w->lds_bytes, stream, w->params,
+                       d_assign, d_out, C, w->screen ? 1u : 0u);
     if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
     return AP_OK;
 }
