@@ -32,6 +32,8 @@ KERNEL_SOURCE = os.path.join(ROOT, "paper_2604_07144_amd", "csrc", "ap_eval.hip"
 # Keyed by configuration; valid only for the kernel source whose hash is recorded with it.
 MEASURED_TRAFFIC = {
     # cfg: (sha256 of the kernel source when measured, bytes per call)
+    4: ("01f1f3f15d01d9b87642bc358784ea01f45b2e0831c14e5139ab69544d75d2d0", 4316862435),
+    3: ("01f1f3f15d01d9b87642bc358784ea01f45b2e0831c14e5139ab69544d75d2d0", 546267392),
 }
 
 
