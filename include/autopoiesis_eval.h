@@ -90,7 +90,7 @@ typedef struct {
 
 /* Capacities of the device path (exceeding one gives AP_ERR_RANGE, never a wrong result). */
 #define AP_MAX_SLOTS 64u      /* B */
-#define AP_MAX_REPLICAS 1024u /* M; additionally M*B*4 bytes of slot state must fit in LDS, see ap_costmodel_set */
+#define AP_MAX_REPLICAS 1024u /* M */
 
 /* Take a trace snapshot (Section 4: a sliding window of request arrivals).
  *   arrival_us, prompt_len, out_len : HOST arrays of R elements, copied; the caller keeps its buffers.
@@ -105,10 +105,12 @@ ap_status ap_workload_create(const uint64_t *arrival_us, const int32_t *prompt_l
  *              t_on_us <= t_off_us for every replica (AP_ERR_INVALID otherwise).
  * The device keeps time as 32-bit microseconds relative to the first arrival.  The call
  * proves that no finish time can leave that range (latest arrival or t_on, plus the sum
- * of every request's largest service time, must be below 2^32 - 1 us, about 71 minutes)
- * and that the per-candidate working set fits in the 160 KiB of LDS; otherwise it
- * returns AP_ERR_RANGE and the workload keeps its previous cost model, if any.
- * Synchronous (small host-to-device copies). */
+ * of every request's largest service time, must be below 2^32 - 1 us, about 71 minutes);
+ * otherwise it returns AP_ERR_RANGE and the workload keeps its previous cost model, if any.
+ * It also sizes every device buffer later evaluations need: when M*B slot times of one
+ * candidate do not fit in LDS next to the histograms, evaluations go through a three-kernel
+ * path and the call allocates its scratch area (about 1 GiB) here.
+ * Synchronous (small host-to-device copies, one small kernel). */
 ap_status ap_costmodel_set(ap_workload *w, const ap_replica *replicas, uint32_t M, uint32_t B, const ap_slo *slo);
 
 /* Score C candidates.

@@ -788,6 +788,280 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
 }
 
 // ----------------------------------------------------------------------------------
+// exact replay as three kernels: group -> replay -> reduce
+// ----------------------------------------------------------------------------------
+// The candidates of a batch are scored by three kernels that hand their intermediates over
+// in a device scratch area sized once by ap_costmodel_set (the batch is cut so that the
+// area stays within the last-level cache):
+//   k_group_requests    per candidate and time chunk: replica histogram, scans, ballot-ranked
+//                       stable scatter -> per-replica index lists (queue order = arrival order)
+//   k_replay_queues     one LANE per (candidate, replica) queue; the B slot-free times of a
+//                       queue are a binary min-heap in LDS (one column per lane, so lanes never
+//                       collide on a bank); per request: start = max(ready, heap root), replace
+//                       the root by the finish time, sift down.  64 queues advance per wavefront
+//                       instruction, which is what makes saturated queues affordable.
+//   k_reduce_candidates per candidate: LDS histograms of the per-request bins, p99s, sums.
+// only_pending != 0 restricts all three to the candidates still marked pending.
+struct QueuePartial {                  // what one queue contributes to its candidate's record
+    unsigned long long sum_e2e, sum_ttft, sum_tpot;
+    uint32_t last_fin, n_ok, n_rej, pad;
+};
+
+struct GroupParams {
+    uint32_t R, M, chunk, n_chunks, key_bits;
+    uint32_t qs_stride;                // uint16 entries per (candidate, chunk) in `qs`: M + 2, padded even
+    uint16_t* qs;                      // [batch][n_chunks][qs_stride]: qs[m] = first list position of replica m
+                                       //   in the chunk; qs[M] = number of listed requests; qs[M+1] unused
+    uint16_t* list;                    // [batch][n_chunks * chunk] chunk-local request indices, by replica
+    uint32_t* unknown;                 // [batch] requests naming no replica
+};
+
+constexpr uint32_t kGroupThreads = 512;
+constexpr uint32_t kGroupWaves = kGroupThreads / kWave;
+constexpr uint32_t kGroupMaxPerThread = 8;      // chunk <= 4096
+
+__global__ __launch_bounds__(kGroupThreads) void k_group_requests(GroupParams p, const uint16_t* __restrict__ assign,
+                                                                  const ap_metrics* __restrict__ out, uint32_t c0,
+                                                                  uint32_t n_cand, uint32_t only_pending) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    const uint32_t M = p.M, M1 = p.M + 1u;
+    uint32_t* cnt = reinterpret_cast<uint32_t*>(lds);                    // [kGroupWaves][M+1]
+    uint32_t* qstart = cnt + kGroupWaves * M1;                           // [M+2]
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t w = wave_index();
+    const uint32_t per_wave = p.chunk / kGroupWaves;                     // multiple of 64
+    const uint32_t groups = per_wave / kWave;
+    const unsigned long long lanes_below = (1ull << lane) - 1ull;
+
+    for (uint32_t cb = blockIdx.x; cb < n_cand; cb += gridDim.x) {
+        const uint32_t c = c0 + cb;
+        if (only_pending && !is_pending(out[c])) continue;
+        const uint16_t* row = assign + (size_t)c * p.R;
+        uint32_t n_unknown = 0;
+        for (uint32_t j = 0; j < p.n_chunks; ++j) {
+            const uint32_t r0 = j * p.chunk, n = min(p.chunk, p.R - r0);
+            uint32_t key[kGroupMaxPerThread];
+#pragma unroll
+            for (uint32_t g = 0; g < kGroupMaxPerThread; ++g) {
+                const uint32_t idx = w * per_wave + g * kWave + lane;
+                key[g] = (g < groups && idx < n) ? min((uint32_t)__builtin_nontemporal_load(row + r0 + idx), M) : kNoKey;
+            }
+            for (uint32_t i = tid; i < kGroupWaves * M1; i += kGroupThreads) cnt[i] = 0u;
+            __syncthreads();
+            // (1) per-wavefront replica histogram
+#pragma unroll
+            for (uint32_t g = 0; g < kGroupMaxPerThread; ++g)
+                if (key[g] != kNoKey) atomicAdd(&cnt[w * M1 + key[g]], 1u);
+            __syncthreads();
+            // (2) offsets: down the wavefronts per replica, then across replicas
+            for (uint32_t m = tid; m <= M; m += kGroupThreads) {
+                uint32_t run = 0;
+                for (uint32_t ww = 0; ww < kGroupWaves; ++ww) {
+                    const uint32_t t = cnt[ww * M1 + m];
+                    cnt[ww * M1 + m] = run;
+                    run += t;
+                }
+                qstart[m] = run;
+            }
+            __syncthreads();
+            if (w == 0) {
+                uint32_t carry = 0;
+                for (uint32_t base = 0; base <= M; base += kWave) {
+                    const uint32_t m = base + lane;
+                    const uint32_t v = m <= M ? qstart[m] : 0u;
+                    const uint32_t incl = wave_inclusive_scan(v, lane);
+                    if (m <= M) qstart[m] = carry + incl - v;
+                    carry += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+                }
+            }
+            __syncthreads();
+            // (3) stable scatter: rank among equal keys of a 64-request group by ballots
+            uint16_t* lst = p.list + ((size_t)cb * p.n_chunks + j) * p.chunk;
+#pragma unroll
+            for (uint32_t g = 0; g < kGroupMaxPerThread; ++g) {
+                if (g >= groups) break;
+                const uint32_t k = key[g];
+                unsigned long long peers = ~0ull;
+                for (uint32_t b = 0; b < p.key_bits; ++b) {
+                    const bool bit = (k >> b) & 1u;
+                    const unsigned long long sset = __ballot(bit);
+                    peers &= bit ? sset : ~sset;
+                }
+                if (k < M) {
+                    const uint32_t rank = __popcll(peers & lanes_below);
+                    const uint32_t total = __popcll(peers);
+                    const uint32_t base = qstart[k] + cnt[w * M1 + k];
+                    lst[base + rank] = (uint16_t)(w * per_wave + g * kWave + lane);
+                    if (rank + 1u == total) cnt[w * M1 + k] += total;
+                } else if (k == M) {
+                    n_unknown += 1u;
+                }
+            }
+            uint16_t* qs = p.qs + ((size_t)cb * p.n_chunks + j) * p.qs_stride;
+            for (uint32_t m = tid; m <= M; m += kGroupThreads) qs[m] = (uint16_t)qstart[m];
+            __syncthreads();
+        }
+        n_unknown = wave_sum_u32(n_unknown);
+        if (lane == 0 && n_unknown) atomicAdd(&p.unknown[cb], n_unknown);
+    }
+}
+
+struct ReplayParams {
+    const uint4* req;                  // [R] {arrival (relative us), prompt_len, out_len, 0}
+    const DevReplica* rep;             // [M]
+    const uint16_t* qs;
+    const uint16_t* list;
+    uint32_t* bins_te;                 // [batch][n_chunks * chunk] ttft bin | e2e bin << 16; 0xFFFFFFFF = rejected
+    uint16_t* bins_p;                  // [batch][n_chunks * chunk] tpot bin
+    QueuePartial* partial;             // [batch][M]
+    uint32_t R, M, B, chunk, n_chunks, qs_stride;
+    uint32_t slo_ttft, slo_tpot;
+};
+
+constexpr uint32_t kReplayWaves = 2;
+constexpr uint32_t kReplayThreads = kReplayWaves * kWave;
+
+__global__ __launch_bounds__(kReplayThreads) void k_replay_queues(ReplayParams p, const ap_metrics* __restrict__ out,
+                                                                  uint32_t c0, uint32_t n_cand, uint32_t only_pending) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t w = wave_index();
+    const uint32_t B = p.B, M = p.M;
+    uint32_t* heap = reinterpret_cast<uint32_t*>(lds) + w * B * kWave + lane;      // node i of this lane: heap[i * 64]
+    const uint32_t n_queues = n_cand * M;
+
+    for (uint32_t q0 = (blockIdx.x * kReplayWaves + w) * kWave; q0 < n_queues; q0 += gridDim.x * kReplayThreads) {
+        const uint32_t q = q0 + lane;
+        const uint32_t cb = min(q, n_queues - 1u) / M, m = min(q, n_queues - 1u) % M;
+        bool live = q < n_queues;
+        if (live && only_pending && !is_pending(out[c0 + cb])) live = false;
+        if (__ballot(live) == 0ull) continue;
+        const DevReplica rp = p.rep[m];
+        for (uint32_t i = 0; i < B; ++i) heap[i * kWave] = 0u;            // all slots free at time 0
+
+        const uint16_t* qs = p.qs + (size_t)cb * p.n_chunks * p.qs_stride;
+        const size_t cand_base = (size_t)cb * p.n_chunks * p.chunk;
+        unsigned long long s_e2e = 0, s_ttft = 0, s_tpot = 0;
+        uint32_t last_fin = 0, n_ok = 0, n_rej = 0;
+        bool closed = false;                                              // the replica is gone for good
+        uint32_t j = 0, k = 0, e = 0;
+        if (live) { k = qs[m]; e = qs[m + 1]; }
+        while (true) {
+            // advance to the lane's next listed request (chunks in time order)
+            while (live && k == e) {
+                if (++j >= p.n_chunks) { live = false; break; }
+                k = qs[j * p.qs_stride + m];
+                e = qs[j * p.qs_stride + m + 1u];
+            }
+            if (__ballot(live) == 0ull) break;
+            if (live) {
+                const size_t pos = cand_base + (size_t)j * p.chunk + k;
+                const uint32_t r = j * p.chunk + p.list[pos];
+                ++k;
+                const uint4 rq = p.req[r];
+                const uint32_t ready = max(rq.x, rp.t_on);
+                uint32_t te = 0xFFFFFFFFu, tp = 0xFFFFu;
+                if (!closed) {
+                    const uint32_t root = heap[0];
+                    const uint32_t start = max(ready, root);
+                    if (start >= rp.t_off) {
+                        closed = true;            // starts never decrease along a queue: the rest is rejected too
+                    } else {
+                        const uint32_t prefill = rp.a + rp.b * rq.y;
+                        const uint32_t tpot = rp.c + rp.d * ((rq.y + 1023u) >> 10);
+                        const uint32_t dec = rq.z * tpot;
+                        const uint32_t fin = start + prefill + dec;
+                        // replace the root by `fin` and restore the heap order
+                        uint32_t i = 0;
+                        while (true) {
+                            const uint32_t l = 2u * i + 1u;
+                            if (l >= B) break;
+                            const uint32_t cl = heap[l * kWave];
+                            const uint32_t cr = l + 1u < B ? heap[(l + 1u) * kWave] : kNever;
+                            const uint32_t cm = min(cl, cr);
+                            if (fin <= cm) break;
+                            heap[i * kWave] = cm;
+                            i = cr < cl ? l + 1u : l;
+                        }
+                        heap[i * kWave] = fin;
+                        const uint32_t ttft = start - rq.x + prefill;
+                        const uint32_t e2e = ttft + dec;
+                        te = hist_bin_u32(ttft) | (hist_bin_u32(e2e) << 16);
+                        tp = hist_bin_u32(tpot);
+                        s_ttft += ttft;
+                        s_e2e += e2e;
+                        s_tpot += tpot;
+                        last_fin = max(last_fin, fin);
+                        n_ok += (ttft <= p.slo_ttft && tpot <= p.slo_tpot) ? 1u : 0u;
+                    }
+                }
+                if (closed) n_rej += 1u;
+                p.bins_te[pos] = te;
+                p.bins_p[pos] = (uint16_t)tp;
+            }
+        }
+        if (q < n_queues && !(only_pending && !is_pending(out[c0 + cb]))) {
+            QueuePartial qp;
+            qp.sum_e2e = s_e2e; qp.sum_ttft = s_ttft; qp.sum_tpot = s_tpot;
+            qp.last_fin = last_fin; qp.n_ok = n_ok; qp.n_rej = n_rej; qp.pad = 0u;
+            p.partial[(size_t)cb * M + m] = qp;
+        }
+    }
+}
+
+struct ReduceParams {
+    const uint16_t* qs;
+    const uint32_t* bins_te;
+    const uint16_t* bins_p;
+    const QueuePartial* partial;
+    uint32_t* unknown;                 // read, then cleared for the next batch
+    uint32_t M, chunk, n_chunks, qs_stride;
+};
+
+template <bool kHist16>
+__global__ __launch_bounds__(kThreads) void k_reduce_candidates(EvalParams p, ReduceParams rp, ap_metrics* out,
+                                                                uint32_t c0, uint32_t n_cand, uint32_t only_pending) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    uint32_t* hist = reinterpret_cast<uint32_t*>(lds);
+    unsigned long long* acc64 = reinterpret_cast<unsigned long long*>(lds + p.off_misc);
+    uint32_t* acc32 = reinterpret_cast<uint32_t*>(lds + p.off_misc + 24);
+    uint32_t* wtot = reinterpret_cast<uint32_t*>(lds + p.off_misc + 64);
+    const uint32_t tid = threadIdx.x;
+    for (uint32_t cb = blockIdx.x; cb < n_cand; cb += gridDim.x) {
+        const uint32_t c = c0 + cb;
+        if (only_pending && !is_pending(out[c])) continue;
+        hist_clear<kHist16>(hist);
+        if (tid < 16u) reinterpret_cast<uint32_t*>(acc64)[tid] = 0u;
+        __syncthreads();
+        for (uint32_t j = 0; j < rp.n_chunks; ++j) {
+            const uint32_t n_listed = rp.qs[((size_t)cb * rp.n_chunks + j) * rp.qs_stride + rp.M];
+            const size_t base = ((size_t)cb * rp.n_chunks + j) * rp.chunk;
+            for (uint32_t i = tid; i < n_listed; i += kThreads) {
+                const uint32_t te = rp.bins_te[base + i];
+                if (te != 0xFFFFFFFFu) {
+                    hist_add<kHist16>(hist, 0u, te & 0xFFFFu, 1u);
+                    hist_add<kHist16>(hist, 1u, rp.bins_p[base + i], 1u);
+                    hist_add<kHist16>(hist, 2u, te >> 16, 1u);
+                }
+            }
+        }
+        unsigned long long s_e2e = 0, s_ttft = 0, s_tpot = 0;
+        uint32_t last_fin = 0, n_ok = 0, n_rej = 0;
+        for (uint32_t m = tid; m < rp.M; m += kThreads) {
+            const QueuePartial qp = rp.partial[(size_t)cb * rp.M + m];
+            s_e2e += qp.sum_e2e; s_ttft += qp.sum_ttft; s_tpot += qp.sum_tpot;
+            last_fin = max(last_fin, qp.last_fin); n_ok += qp.n_ok; n_rej += qp.n_rej;
+        }
+        if (tid == 0) {
+            n_rej += rp.unknown[cb];
+            rp.unknown[cb] = 0u;
+        }
+        finish_candidate<kHist16>(p, hist, acc64, acc32, wtot, s_e2e, s_ttft, s_tpot, last_fin, n_ok, n_rej, &out[c]);
+        __syncthreads();
+    }
+}
+
+// ----------------------------------------------------------------------------------
 // host side
 // ----------------------------------------------------------------------------------
 inline uint32_t align_up(uint32_t v, uint32_t a) { return (v + a - 1u) / a * a; }
@@ -845,6 +1119,17 @@ struct ap_workload {
     uint32_t screen_wide_lds_bytes = 0;
     uint32_t max_grid = 0;
     uint32_t n_cu = 0;
+    // three-kernel replay: request records, scratch for one batch of candidates, launch parameters
+    uint4* d_req = nullptr;           // [R] {arrival, prompt_len, out_len, 0}
+    unsigned char* d_scratch = nullptr;
+    size_t scratch_bytes = 0;
+    uint32_t batch = 0;               // candidates per batch
+    GroupParams group_params{};
+    ReplayParams replay_params{};
+    ReduceParams reduce_params{};
+    EvalParams reduce_eval{};
+    uint32_t group_lds_bytes = 0, replay_lds_bytes = 0, reduce_lds_bytes = 0;
+    bool pipeline = false;
 };
 
 extern "C" {
@@ -912,6 +1197,20 @@ ap_status ap_workload_create(const uint64_t* arrival_us, const int32_t* prompt_l
                         hipMalloc(&w->d_finish_t, padded) != hipSuccess ||
                         hipMalloc(&w->d_nominal, sizeof(ap_metrics)) != hipSuccess))
         st = AP_ERR_ALLOC;
+    std::vector<uint4> recs;
+    if (st == AP_OK) {
+        try {
+            recs.resize(R);
+        } catch (const std::bad_alloc&) {
+            st = AP_ERR_ALLOC;
+        }
+    }
+    if (st == AP_OK) {
+        for (uint32_t r = 0; r < R; ++r) recs[r] = make_uint4(rel[r], (uint32_t)prompt_len[r], (uint32_t)out_len[r], 0u);
+        if (hipMalloc(&w->d_req, sizeof(uint4) * (size_t)R) != hipSuccess) st = AP_ERR_ALLOC;
+        else if (hipMemcpy(w->d_req, recs.data(), sizeof(uint4) * (size_t)R, hipMemcpyHostToDevice) != hipSuccess)
+            st = AP_ERR_DEVICE;
+    }
     if (st == AP_OK && (hipMemcpy(w->d_arrival, rel.data(), bytes, hipMemcpyHostToDevice) != hipSuccess ||
                         hipMemcpy(w->d_prompt, prompt_len, bytes, hipMemcpyHostToDevice) != hipSuccess ||
                         hipMemcpy(w->d_out, out_len, bytes, hipMemcpyHostToDevice) != hipSuccess))
@@ -996,7 +1295,14 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
         if (chunk >= smallest) break;
         chunk = 0;
     }
-    if (chunk == 0) return AP_ERR_RANGE;
+    // When even the smallest chunk does not fit (large M * B), candidates are scored by the
+    // three-kernel pipeline instead, whose slot state is per queue rather than per candidate.
+    const bool use_pipeline = chunk == 0;
+    if (use_pipeline) bytes = 0;
+
+    // LDS of the kernels that only need the histograms and the accumulators behind them
+    const uint32_t hist_bytes = 3u * kBins * (hist16 ? 2u : 4u);
+    const uint32_t reduce_lds = hist_bytes + 64u + 3u * kWaves * 4u;
 
     std::vector<DevReplica> dev(M);
     for (uint32_t m = 0; m < M; ++m) {
@@ -1015,11 +1321,11 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
         }
     }
     if (hipMemcpy(w->d_rep, dev.data(), sizeof(DevReplica) * M, hipMemcpyHostToDevice) != hipSuccess ||
-        hipFuncSetAttribute(reinterpret_cast<const void*>(eval_kernel(hist16, w->len16)),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess ||
+        (!use_pipeline && hipFuncSetAttribute(reinterpret_cast<const void*>(eval_kernel(hist16, w->len16)),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) ||
         hipFuncSetAttribute(hist16 ? reinterpret_cast<const void*>(&k_nominal_metrics<true>)
                                    : reinterpret_cast<const void*>(&k_nominal_metrics<false>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) {
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)reduce_lds) != hipSuccess) {
         (void)hipGetLastError();
         w->has_model = false;     // the replica table on the device may be half-written
         return AP_ERR_DEVICE;
@@ -1043,6 +1349,66 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
     w->hist16 = hist16;
     w->n_cu = (uint32_t)n_cu;
     w->max_grid = (uint32_t)n_cu * 8u;
+
+    // ---- three-kernel replay: scratch for one batch of candidates -------------------------
+    w->reduce_eval = p;
+    w->reduce_eval.off_misc = hist_bytes;                              // histograms, then the accumulators
+    w->reduce_lds_bytes = reduce_lds;
+    w->pipeline = use_pipeline;
+    if (use_pipeline) {
+        const uint32_t R = w->R;
+        const uint32_t chunk_g = std::min(kGroupThreads * kGroupMaxPerThread, align_up(R, kGroupThreads));
+        const uint32_t n_chunks = (R + chunk_g - 1u) / chunk_g;
+        const uint32_t qs_stride = align_up(M + 2u, 8u);
+        const size_t slots = (size_t)n_chunks * chunk_g;               // list positions per candidate
+        const size_t per_cand = (size_t)n_chunks * qs_stride * 2u + slots * (2u + 4u + 2u) + (size_t)M * sizeof(QueuePartial) + 4u;
+        const size_t target = (size_t)1 << 30;                         // enough candidates per batch to fill the GPU
+        uint32_t batch = (uint32_t)std::min<size_t>(65535u, std::max<size_t>(1u, target / per_cand));
+        auto carve = [](size_t& off, size_t bytes) { const size_t at = off; off = (off + bytes + 255u) / 256u * 256u; return at; };
+        size_t off = 0;
+        const size_t o_qs = carve(off, (size_t)batch * n_chunks * qs_stride * 2u);
+        const size_t o_list = carve(off, (size_t)batch * slots * 2u);
+        const size_t o_te = carve(off, (size_t)batch * slots * 4u);
+        const size_t o_p = carve(off, (size_t)batch * slots * 2u);
+        const size_t o_part = carve(off, (size_t)batch * M * sizeof(QueuePartial));
+        const size_t o_unk = carve(off, (size_t)batch * 4u);
+        if (off > w->scratch_bytes) {
+            if (w->d_scratch && hipFree(w->d_scratch) != hipSuccess) return AP_ERR_DEVICE;
+            w->d_scratch = nullptr;
+            w->scratch_bytes = 0;
+            if (hipMalloc(&w->d_scratch, off) != hipSuccess) {
+                (void)hipGetLastError();
+                return AP_ERR_ALLOC;
+            }
+            w->scratch_bytes = off;
+        }
+        if (hipMemset(w->d_scratch + o_unk, 0, (size_t)batch * 4u) != hipSuccess) return AP_ERR_DEVICE;
+        w->batch = batch;
+        GroupParams gp{};
+        gp.R = R; gp.M = M; gp.chunk = chunk_g; gp.n_chunks = n_chunks; gp.key_bits = p.key_bits; gp.qs_stride = qs_stride;
+        gp.qs = reinterpret_cast<uint16_t*>(w->d_scratch + o_qs);
+        gp.list = reinterpret_cast<uint16_t*>(w->d_scratch + o_list);
+        gp.unknown = reinterpret_cast<uint32_t*>(w->d_scratch + o_unk);
+        w->group_params = gp;
+        w->group_lds_bytes = (kGroupWaves * (M + 1u) + M + 2u) * 4u;
+        ReplayParams qp{};
+        qp.req = w->d_req; qp.rep = w->d_rep; qp.qs = gp.qs; qp.list = gp.list;
+        qp.bins_te = reinterpret_cast<uint32_t*>(w->d_scratch + o_te);
+        qp.bins_p = reinterpret_cast<uint16_t*>(w->d_scratch + o_p);
+        qp.partial = reinterpret_cast<QueuePartial*>(w->d_scratch + o_part);
+        qp.R = R; qp.M = M; qp.B = B; qp.chunk = chunk_g; qp.n_chunks = n_chunks; qp.qs_stride = qs_stride;
+        qp.slo_ttft = p.slo_ttft; qp.slo_tpot = p.slo_tpot;
+        w->replay_params = qp;
+        w->replay_lds_bytes = kReplayWaves * B * kWave * 4u;
+        ReduceParams rd{};
+        rd.qs = gp.qs; rd.bins_te = qp.bins_te; rd.bins_p = qp.bins_p; rd.partial = qp.partial; rd.unknown = gp.unknown;
+        rd.M = M; rd.chunk = chunk_g; rd.n_chunks = n_chunks; rd.qs_stride = qs_stride;
+        w->reduce_params = rd;
+        if (hipFuncSetAttribute(hist16 ? reinterpret_cast<const void*>(&k_reduce_candidates<true>)
+                                       : reinterpret_cast<const void*>(&k_reduce_candidates<false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)w->reduce_lds_bytes) != hipSuccess)
+            return AP_ERR_DEVICE;
+    }
 
     // ---- screening plan: only for identical replicas that are available throughout ------
     bool always_on = true;
@@ -1070,8 +1436,8 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
         w->screen_wide = w->screen_group == 8u;          // exactly the candidates with large rings
         w->screen_wide_lds_bytes = (((M + 1u) << S_log2) + 4u) * 4u;
         w->screen_lds_bytes = kScreenWaves * ((M + 1u) << S_log2) * 4u;      // M rings and a spare one per wavefront
-        hipLaunchKernelGGL(hist16 ? k_nominal_metrics<true> : k_nominal_metrics<false>, dim3(1), dim3(kThreads), bytes,
-                           nullptr, p, w->d_finish, w->d_arrival_t, w->d_finish_t, w->d_nominal);
+        hipLaunchKernelGGL(hist16 ? k_nominal_metrics<true> : k_nominal_metrics<false>, dim3(1), dim3(kThreads),
+                           reduce_lds, nullptr, w->reduce_eval, w->d_finish, w->d_arrival_t, w->d_finish_t, w->d_nominal);
         if (hipGetLastError() != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
             (void)hipGetLastError();
             return AP_ERR_DEVICE;
@@ -1109,9 +1475,24 @@ ap_status ap_eval_candidates(const ap_workload* w, const uint16_t* d_assign, uin
         }
         if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
     }
+    const uint32_t pending_only = w->screen ? 1u : 0u;
+    if (w->pipeline) {
+        for (uint32_t c0 = 0; c0 < C; c0 += w->batch) {
+            const uint32_t n = std::min(w->batch, C - c0);
+            hipLaunchKernelGGL(k_group_requests, dim3(n), dim3(kGroupThreads), w->group_lds_bytes, stream, w->group_params,
+                               d_assign, d_out, c0, n, pending_only);
+            const uint32_t n_wg = (n * w->params.M + kReplayThreads - 1u) / kReplayThreads;
+            hipLaunchKernelGGL(k_replay_queues, dim3(n_wg), dim3(kReplayThreads), w->replay_lds_bytes, stream,
+                               w->replay_params, d_out, c0, n, pending_only);
+            hipLaunchKernelGGL(w->hist16 ? k_reduce_candidates<true> : k_reduce_candidates<false>, dim3(n), dim3(kThreads),
+                               w->reduce_lds_bytes, stream, w->reduce_eval, w->reduce_params, d_out, c0, n, pending_only);
+        }
+        if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
+        return AP_OK;
+    }
     const uint32_t grid = std::min(C, w->max_grid);
     hipLaunchKernelGGL(eval_kernel(w->hist16, w->len16), dim3(grid), dim3(kThreads), w->lds_bytes, stream, w->params,
-                       d_assign, d_out, C, w->screen ? 1u : 0u);
+                       d_assign, d_out, C, pending_only);
     if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
     return AP_OK;
 }
@@ -1123,6 +1504,8 @@ ap_status ap_workload_destroy(ap_workload* w) {
     if (w->d_prompt) ok = (hipFree(w->d_prompt) == hipSuccess) && ok;
     if (w->d_out) ok = (hipFree(w->d_out) == hipSuccess) && ok;
     if (w->d_rep) ok = (hipFree(w->d_rep) == hipSuccess) && ok;
+    if (w->d_req) ok = (hipFree(w->d_req) == hipSuccess) && ok;
+    if (w->d_scratch) ok = (hipFree(w->d_scratch) == hipSuccess) && ok;
     if (w->d_finish) ok = (hipFree(w->d_finish) == hipSuccess) && ok;
     if (w->d_arrival_t) ok = (hipFree(w->d_arrival_t) == hipSuccess) && ok;
     if (w->d_finish_t) ok = (hipFree(w->d_finish_t) == hipSuccess) && ok;

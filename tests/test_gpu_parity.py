@@ -117,6 +117,29 @@ def test_screening_with_invalid_ids_and_unaligned_batch_pointer():
         assert_same(to_records(d_out), want, "unaligned batch")
 
 
+@pytest.mark.parametrize("name,n,M,B,gap,C,homogeneous,windows", [
+    ("max_table_light", 30000, 1024, 64, 60, 6, False, False),      # the largest replica table and slot count
+    ("max_table_homogeneous_saturated", 40000, 1024, 64, 1, 5, True, False),   # screening first, then the pipeline
+    ("m700_saturated", 50000, 700, 64, 1, 4, False, False),
+    ("m1000_b48_windows", 45000, 1000, 48, 2, 4, False, True),
+    ("m600_b40_long_trace", 70000, 600, 40, 3, 3, False, True),      # R >= 65536: 32-bit histogram counters
+])
+def test_large_replica_tables_take_the_queue_per_lane_path(name, n, M, B, gap, C, homogeneous, windows):
+    """M * B slot times of one candidate no longer fit in LDS: grouping, replay (one lane per queue)
+    and reduction run as three kernels."""
+    rng = np.random.default_rng(n + M)
+    t_on = t_off = None
+    if windows:
+        span = n * gap // 2
+        xy = rng.integers(0, span + 1, size=(M, 2)) + 1_000_000_007
+        t_on, t_off = xy.min(1).astype(np.uint64), xy.max(1).astype(np.uint64)
+    tr = _mk(n, M, B, gap, seed=n + 1, coef=[STD] * M if homogeneous else None, t_on=t_on, t_off=t_off,
+             penalty_us=2_000_000_000)
+    rows = _rows(C, n, M + (0 if homogeneous else 2), seed=M)           # a few unknown replica ids
+    rows[0] = rng.integers(0, 8, n)                                     # everything on eight replicas: deep queues
+    both(tr, rows, name)
+
+
 def test_all_requests_on_one_replica_and_empty_replicas():
     tr = _mk(5000, 9, 16, 200, seed=3)
     rows = np.zeros((4, 5000), np.uint16)
@@ -213,8 +236,8 @@ def test_error_paths():
         with pytest.raises(binding.ApError) as e:                                              # 32-bit horizon
             binding.ap_costmodel_set(h, binding.make_replicas([(4_000_000_000, 3, 25, 5)], [0], [U64MAX]), 2, 1, 1, 1)
         assert e.value.status == binding.AP_ERR_RANGE
-        with pytest.raises(binding.ApError) as e:                                              # slot state > LDS
-            binding.ap_costmodel_set(h, binding.make_replicas([STD] * 1024, [0] * 1024, [U64MAX] * 1024), 64, 1, 1, 1)
+        with pytest.raises(binding.ApError) as e:                                              # more replicas than supported
+            binding.ap_costmodel_set(h, binding.make_replicas([STD] * 1025, [0] * 1025, [U64MAX] * 1025), 64, 1, 1, 1)
         assert e.value.status == binding.AP_ERR_RANGE
         binding.ap_costmodel_set(h, rep, 2, 500_000, 50_000, 1_000_000)
         binding.ap_eval_candidates(h, d.data_ptr(), 0, o.data_ptr(), 0)                        # C == 0: no-op
