@@ -247,9 +247,8 @@ __host__ __device__ inline uint32_t screen_table_index(uint32_t r) {
 // shares.
 // One workgroup.
 template <bool kHist16>
-__global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint32_t* __restrict__ finish,
-                                                              uint32_t* __restrict__ arrival_t,
-                                                              uint32_t* __restrict__ finish_t,
+__global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint32_t* __restrict__ span,
+                                                              uint32_t* __restrict__ span_t, uint32_t tick_shift,
                                                               ap_metrics* __restrict__ nominal) {
     extern __shared__ __align__(16) unsigned char lds[];
     uint32_t* hist = reinterpret_cast<uint32_t*>(lds);
@@ -268,9 +267,11 @@ __global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint
         const uint32_t prefill = rp.a + rp.b * prm;
         const uint32_t tpot = rp.c + rp.d * ((prm + 1023u) >> 10);
         const uint32_t e2e = prefill + p.outlen[r] * tpot;
-        finish[r] = p.arrival[r] + e2e;
-        arrival_t[screen_table_index(r)] = p.arrival[r];
-        finish_t[screen_table_index(r)] = p.arrival[r] + e2e;
+        // service interval in ticks, rounded outwards (arrival down, finish up), 16 bits each
+        const uint32_t fin_us = p.arrival[r] + e2e;
+        const uint32_t span_v = (p.arrival[r] >> tick_shift) | (((fin_us + (1u << tick_shift) - 1u) >> tick_shift) << 16);
+        span[r] = span_v;
+        span_t[screen_table_index(r)] = span_v;
         hist_add<kHist16>(hist, 0u, hist_bin_u32(prefill), 1u);
         hist_add<kHist16>(hist, 1u, hist_bin_u32(tpot), 1u);
         hist_add<kHist16>(hist, 2u, hist_bin_u32(e2e), 1u);
@@ -302,16 +303,20 @@ __global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint
 // k_eval_candidates.  Requests are taken 64 at a time in arrival order, which keeps the
 // number of slots a replica needs close to its true concurrency.
 //
+// Times here are 16-bit ticks of 2^k microseconds (k chosen so that the whole range fits),
+// with every service interval rounded outwards: arrival down, finish up.  A claim needs
+// old finish tick <= arrival tick, which implies old finish <= arrival in microseconds, so
+// the rounding only makes the test more conservative; it halves the table bytes read per
+// request (one 32-bit word: arrival tick | finish tick << 16).
+//
 // One wavefront per candidate.  A block is 512 consecutive requests; lane l holds the eight
 // requests i0 + 128k + 2l + h (k = 0..3, h = 0..1): four 4-byte loads of assignment pairs.
 // Step e = 2k + h therefore covers every other request of a 128-request window, close
 // enough to arrival order.  The arrival / finish tables are stored lane-major so that a
 // lane's eight values are contiguous (two 16-byte loads each).
 struct ScreenParams {
-    const uint32_t* arrival;      // [R] in request order
-    const uint32_t* finish;       // [R] arrival + prefill + decode, in request order
-    const uint32_t* arrival_t;    // [ceil(R/512)*512] in the order given by screen_table_index
-    const uint32_t* finish_t;     // same layout
+    const uint32_t* span;         // [R] in request order: arrival tick | finish tick << 16 (interval rounded outwards)
+    const uint32_t* span_t;       // [ceil(R/512)*512] the same words in the order given by screen_table_index
     const ap_metrics* nominal;
     uint32_t R, M;
     uint32_t slots_log2;          // S = 1 << slots_log2
@@ -319,7 +324,7 @@ struct ScreenParams {
 
 struct ScreenRegs {
     uint32_t pair[4];             // two replica ids per word, as stored in the candidate's row
-    uint32_t arr[8], fin[8];
+    uint32_t span[8];             // arrival tick | finish tick << 16
 };
 
 template <bool kAligned>
@@ -335,14 +340,10 @@ __device__ __forceinline__ void screen_fetch(ScreenRegs& g, const ScreenParams& 
             g.pair[k] = (uint32_t)__builtin_nontemporal_load(at) | ((uint32_t)__builtin_nontemporal_load(at + 1) << 16);
         }
     }
-    const uint4 a0 = *reinterpret_cast<const uint4*>(p.arrival_t + i0 + lane * 8u);
-    const uint4 a1 = *reinterpret_cast<const uint4*>(p.arrival_t + i0 + lane * 8u + 4u);
-    const uint4 f0 = *reinterpret_cast<const uint4*>(p.finish_t + i0 + lane * 8u);
-    const uint4 f1 = *reinterpret_cast<const uint4*>(p.finish_t + i0 + lane * 8u + 4u);
-    g.arr[0] = a0.x; g.arr[1] = a0.y; g.arr[2] = a0.z; g.arr[3] = a0.w;
-    g.arr[4] = a1.x; g.arr[5] = a1.y; g.arr[6] = a1.z; g.arr[7] = a1.w;
-    g.fin[0] = f0.x; g.fin[1] = f0.y; g.fin[2] = f0.z; g.fin[3] = f0.w;
-    g.fin[4] = f1.x; g.fin[5] = f1.y; g.fin[6] = f1.z; g.fin[7] = f1.w;
+    const uint4 s0 = *reinterpret_cast<const uint4*>(p.span_t + i0 + lane * 8u);
+    const uint4 s1 = *reinterpret_cast<const uint4*>(p.span_t + i0 + lane * 8u + 4u);
+    g.span[0] = s0.x; g.span[1] = s0.y; g.span[2] = s0.z; g.span[3] = s0.w;
+    g.span[4] = s1.x; g.span[5] = s1.y; g.span[6] = s1.z; g.span[7] = s1.w;
 }
 
 // Claim a slot for each of the lane's kCount requests.  `slot_bytes` is the byte address
@@ -355,11 +356,17 @@ __device__ __forceinline__ void screen_fetch(ScreenRegs& g, const ScreenParams& 
 // claims of up to kGroup * 64 later requests; the host picks kGroup from M and S.
 // Returns true if some request of this lane found no slot or named an unknown replica.
 template <uint32_t kCount, uint32_t kGroup>
-__device__ __forceinline__ bool screen_claim(const uint32_t* id, const uint32_t* arr, const uint32_t* fin,
+__device__ __forceinline__ bool screen_claim(const uint32_t* id, const uint32_t* span,
                                              unsigned char* lds, uint32_t slot_bytes, uint32_t ring_base_bytes,
                                              uint32_t ring_shift, uint32_t M, uint32_t S, uint32_t my_first) {
     uint32_t top = 0;
     bool lane_bad = false;
+    uint32_t arr[kCount], fin[kCount];
+#pragma unroll
+    for (uint32_t e = 0; e < kCount; ++e) {
+        arr[e] = span[e] & 0xFFFFu;
+        fin[e] = span[e] >> 16;
+    }
 #pragma unroll
     for (uint32_t g = 0; g < kCount; g += kGroup) {
         uint32_t at[kGroup], old[kGroup], old2[kGroup];
@@ -420,7 +427,7 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenPara
             {
                 const uint32_t id[8] = {ga.pair[0] & 0xFFFFu, ga.pair[0] >> 16, ga.pair[1] & 0xFFFFu, ga.pair[1] >> 16,
                                         ga.pair[2] & 0xFFFFu, ga.pair[2] >> 16, ga.pair[3] & 0xFFFFu, ga.pair[3] >> 16};
-                bad = __ballot(screen_claim<8, kGroup>(id, ga.arr, ga.fin, lds, slot_bytes, ring_base_bytes, ring_shift, M, S,
+                bad = __ballot(screen_claim<8, kGroup>(id, ga.span, lds, slot_bytes, ring_base_bytes, ring_shift, M, S,
                                             my_first)) != 0ull;
             }
             if (bad || b + 1u >= n_full) break;
@@ -428,7 +435,7 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenPara
             {
                 const uint32_t id[8] = {gb.pair[0] & 0xFFFFu, gb.pair[0] >> 16, gb.pair[1] & 0xFFFFu, gb.pair[1] >> 16,
                                         gb.pair[2] & 0xFFFFu, gb.pair[2] >> 16, gb.pair[3] & 0xFFFFu, gb.pair[3] >> 16};
-                bad = __ballot(screen_claim<8, kGroup>(id, gb.arr, gb.fin, lds, slot_bytes, ring_base_bytes, ring_shift, M, S,
+                bad = __ballot(screen_claim<8, kGroup>(id, gb.span, lds, slot_bytes, ring_base_bytes, ring_shift, M, S,
                                             my_first)) != 0ull;
             }
             if (bad) break;
@@ -437,7 +444,7 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenPara
         // ragged tail: the same steps with every access guarded; absent requests go to the spare ring
         const uint32_t i0 = n_full * kScreenBlock;
         if (!bad && i0 < R) {
-            uint32_t id[8], arr[8], fin[8];
+            uint32_t id[8], span[8];
             bool unknown = false;
 #pragma unroll
             for (uint32_t e = 0; e < 8u; ++e) {
@@ -446,11 +453,10 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenPara
                 const uint32_t m = in ? (uint32_t)row[r] : 0u;
                 unknown = unknown || m >= M;
                 id[e] = in ? min(m, M) : M;
-                arr[e] = in ? p.arrival_t[i0 + lane * 8u + e] : kNever;      // an absent request never loses a probe
-                fin[e] = in ? p.finish_t[i0 + lane * 8u + e] : 0u;
+                span[e] = in ? p.span_t[i0 + lane * 8u + e] : 0xFFFFu;       // absent: arrives last, finishes at 0, never loses
             }
             // ids were clamped to the spare ring, so screen_claim itself reports only lost requests
-            bool lane_bad = screen_claim<8, kGroup>(id, arr, fin, lds, slot_bytes, ring_base_bytes, ring_shift, M + 1u, S, my_first);
+            bool lane_bad = screen_claim<8, kGroup>(id, span, lds, slot_bytes, ring_base_bytes, ring_shift, M + 1u, S, my_first);
             bad = __ballot(lane_bad || unknown) != 0ull;
         }
 
@@ -500,7 +506,7 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates_wide(Scree
         // writes the other word, so all wavefronts read the same verdict and leave together.
         constexpr uint32_t kDepth = 2;
         uint32_t pair[kDepth];
-        uint2 arr[kDepth], fin[kDepth];
+        uint2 span[kDepth];
         auto fetch = [&](uint32_t d, uint32_t blk) {
             const uint32_t i0 = blk * kScreenBlock;
             const uint16_t* at = row + i0 + mine;
@@ -509,13 +515,12 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates_wide(Scree
             } else {
                 pair[d] = (uint32_t)__builtin_nontemporal_load(at) | ((uint32_t)__builtin_nontemporal_load(at + 1) << 16);
             }
-            arr[d] = *reinterpret_cast<const uint2*>(p.arrival + i0 + mine);
-            fin[d] = *reinterpret_cast<const uint2*>(p.finish + i0 + mine);
+            span[d] = *reinterpret_cast<const uint2*>(p.span + i0 + mine);
         };
         auto claim = [&](uint32_t d) {
             const uint32_t id[2] = {pair[d] & 0xFFFFu, pair[d] >> 16};
-            const uint32_t a[2] = {arr[d].x, arr[d].y}, f[2] = {fin[d].x, fin[d].y};
-            return screen_claim<2, 2>(id, a, f, lds, slot_bytes, 0u, ring_shift, M, S, my_first);
+            const uint32_t sp[2] = {span[d].x, span[d].y};
+            return screen_claim<2, 2>(id, sp, lds, slot_bytes, 0u, ring_shift, M, S, my_first);
         };
         const uint32_t n_groups = n_full / kDepth;
         bool bad = false;
@@ -529,9 +534,9 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates_wide(Scree
 #pragma unroll
             for (uint32_t d = 0; d < kDepth; ++d) {
                 const uint32_t id[2] = {pair[d] & 0xFFFFu, pair[d] >> 16};
-                const uint32_t a[2] = {arr[d].x, arr[d].y}, f[2] = {fin[d].x, fin[d].y};
+                const uint32_t sp[2] = {span[d].x, span[d].y};
                 fetch(d, min((g + 1u) * kDepth + d, n_full - 1u));           // refill (redundant in the last group)
-                lane_bad = screen_claim<2, 2>(id, a, f, lds, slot_bytes, 0u, ring_shift, M, S, my_first) || lane_bad;
+                lane_bad = screen_claim<2, 2>(id, sp, lds, slot_bytes, 0u, ring_shift, M, S, my_first) || lane_bad;
                 if (d + 1u == kDepth && __ballot(lane_bad) != 0ull && lane == 0) flag[turn & 1u] = 1u;
                 __syncthreads();
             }
@@ -545,7 +550,7 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates_wide(Scree
         }
         const uint32_t i0 = n_full * kScreenBlock;
         if (!bad && i0 < R) {                                                // ragged tail, every access guarded
-            uint32_t id[2], a[2], f[2];
+            uint32_t id[2], sp[2];
             bool unknown = false;
 #pragma unroll
             for (uint32_t h = 0; h < 2u; ++h) {
@@ -554,10 +559,9 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates_wide(Scree
                 const uint32_t m = in ? (uint32_t)row[r] : 0u;
                 unknown = unknown || m >= M;
                 id[h] = in ? min(m, M) : M;
-                a[h] = in ? p.arrival[r] : kNever;                           // an absent request never loses a probe
-                f[h] = in ? p.finish[r] : 0u;
+                sp[h] = in ? p.span[r] : 0xFFFFu;                            // absent: arrives last, finishes at 0, never loses
             }
-            const bool lane_bad = screen_claim<2, 2>(id, a, f, lds, slot_bytes, 0u, ring_shift, M + 1u, S, my_first);
+            const bool lane_bad = screen_claim<2, 2>(id, sp, lds, slot_bytes, 0u, ring_shift, M + 1u, S, my_first);
             if (__ballot(lane_bad || unknown) != 0ull && lane == 0) flag[turn & 1u] = 1u;
         }
         __syncthreads();
@@ -1098,13 +1102,13 @@ struct ap_workload {
     uint64_t base_us = 0;             // first arrival
     uint64_t span_us = 0;             // last arrival - first arrival
     std::vector<int32_t> h_prompt, h_out;
+    std::vector<uint32_t> h_arrival;  // relative to base_us (clamped; a span beyond 32 bits is refused anyway)
     uint32_t* d_arrival = nullptr;
     uint32_t* d_prompt = nullptr;
     uint32_t* d_out = nullptr;
     DevReplica* d_rep = nullptr;      // capacity AP_MAX_REPLICAS
-    uint32_t* d_finish = nullptr;     // [R] contention-free finish times, valid when screen is set
-    uint32_t* d_arrival_t = nullptr;  // lane-major arrival / finish tables, valid when screen is set
-    uint32_t* d_finish_t = nullptr;
+    uint32_t* d_span = nullptr;       // [R] contention-free service intervals in ticks, valid when screen is set
+    uint32_t* d_span_t = nullptr;     // the same, lane-major for the one-wavefront screening kernel
     ap_metrics* d_nominal = nullptr;  // record shared by all contention-free candidates
     bool has_model = false;
     bool screen = false;              // homogeneous, always-on replicas: screening applies
@@ -1184,6 +1188,7 @@ ap_status ap_workload_create(const uint64_t* arrival_us, const int32_t* prompt_l
     w->span_us = arrival_us[R - 1] - arrival_us[0];
     // relative 32-bit arrivals; a span that does not fit is refused later by ap_costmodel_set
     for (uint32_t r = 0; r < R; ++r) rel[r] = (uint32_t)std::min<uint64_t>(arrival_us[r] - w->base_us, kNever);
+    w->h_arrival = rel;
 
     ap_status st = AP_OK;
     if (hipGetDevice(&w->device) != hipSuccess) st = AP_ERR_DEVICE;
@@ -1192,9 +1197,8 @@ ap_status ap_workload_create(const uint64_t* arrival_us, const int32_t* prompt_l
     if (st == AP_OK && (hipMalloc(&w->d_arrival, bytes) != hipSuccess || hipMalloc(&w->d_prompt, bytes) != hipSuccess ||
                         hipMalloc(&w->d_out, bytes) != hipSuccess ||
                         hipMalloc(&w->d_rep, sizeof(DevReplica) * AP_MAX_REPLICAS) != hipSuccess ||
-                        hipMalloc(&w->d_finish, bytes) != hipSuccess ||
-                        hipMalloc(&w->d_arrival_t, padded) != hipSuccess ||
-                        hipMalloc(&w->d_finish_t, padded) != hipSuccess ||
+                        hipMalloc(&w->d_span, bytes) != hipSuccess ||
+                        hipMalloc(&w->d_span_t, padded) != hipSuccess ||
                         hipMalloc(&w->d_nominal, sizeof(ap_metrics)) != hipSuccess))
         st = AP_ERR_ALLOC;
     std::vector<uint4> recs;
@@ -1254,6 +1258,7 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
         if (!seen) kinds.push_back(&replicas[m]);
     }
     uint64_t total = latest;
+    uint64_t latest_unqueued = 0;      // latest finish if nobody ever waited (arrival + service)
     for (uint32_t r = 0; r < w->R; ++r) {
         const uint64_t prompt = (uint64_t)w->h_prompt[r], outl = (uint64_t)w->h_out[r];
         uint64_t worst = 0;
@@ -1266,6 +1271,7 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
             worst = std::max(worst, svc);
         }
         total += worst;
+        latest_unqueued = std::max<uint64_t>(latest_unqueued, (uint64_t)w->h_arrival[r] + worst);
         if (total > limit) return AP_ERR_RANGE;
     }
 
@@ -1420,10 +1426,11 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
         uint32_t S_log2 = 0;
         while ((2u << S_log2) <= std::min(B, kScreenMaxSlots) && M * (2u << S_log2) * 4u <= kScreenLdsPerWave) ++S_log2;
         ScreenParams sp{};
-        sp.arrival = w->d_arrival;
-        sp.finish = w->d_finish;
-        sp.arrival_t = w->d_arrival_t;
-        sp.finish_t = w->d_finish_t;
+        sp.span = w->d_span;
+        sp.span_t = w->d_span_t;
+        // tick = 2^tick_shift us, the smallest that brings every contention-free finish time below 2^16 ticks
+        uint32_t tick_shift = 0;
+        while (((latest_unqueued >> tick_shift) + 2u) > 0xFFFFu) ++tick_shift;
         sp.nominal = w->d_nominal;
         sp.R = w->R;
         sp.M = M;
@@ -1437,7 +1444,7 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
         w->screen_wide_lds_bytes = (((M + 1u) << S_log2) + 4u) * 4u;
         w->screen_lds_bytes = kScreenWaves * ((M + 1u) << S_log2) * 4u;      // M rings and a spare one per wavefront
         hipLaunchKernelGGL(hist16 ? k_nominal_metrics<true> : k_nominal_metrics<false>, dim3(1), dim3(kThreads),
-                           reduce_lds, nullptr, w->reduce_eval, w->d_finish, w->d_arrival_t, w->d_finish_t, w->d_nominal);
+                           reduce_lds, nullptr, w->reduce_eval, w->d_span, w->d_span_t, tick_shift, w->d_nominal);
         if (hipGetLastError() != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
             (void)hipGetLastError();
             return AP_ERR_DEVICE;
@@ -1506,9 +1513,8 @@ ap_status ap_workload_destroy(ap_workload* w) {
     if (w->d_rep) ok = (hipFree(w->d_rep) == hipSuccess) && ok;
     if (w->d_req) ok = (hipFree(w->d_req) == hipSuccess) && ok;
     if (w->d_scratch) ok = (hipFree(w->d_scratch) == hipSuccess) && ok;
-    if (w->d_finish) ok = (hipFree(w->d_finish) == hipSuccess) && ok;
-    if (w->d_arrival_t) ok = (hipFree(w->d_arrival_t) == hipSuccess) && ok;
-    if (w->d_finish_t) ok = (hipFree(w->d_finish_t) == hipSuccess) && ok;
+    if (w->d_span) ok = (hipFree(w->d_span) == hipSuccess) && ok;
+    if (w->d_span_t) ok = (hipFree(w->d_span_t) == hipSuccess) && ok;
     if (w->d_nominal) ok = (hipFree(w->d_nominal) == hipSuccess) && ok;
     delete w;
     return ok ? AP_OK : AP_ERR_DEVICE;
