@@ -346,9 +346,24 @@ __device__ __forceinline__ void screen_fetch(ScreenRegs& g, const ScreenParams& 
     g.span[4] = s1.x; g.span[5] = s1.y; g.span[6] = s1.z; g.span[7] = s1.w;
 }
 
-// Claim a slot for each of the lane's kCount requests.  `slot_bytes` is the byte address
-// of this lane's first-choice slot in replica 0's ring; replica m's ring is m << ring_shift
-// bytes further on, and ring M is a spare one that absorbs unknown replica ids.
+// LDS words addressed by their 32-bit byte address (ring addresses are computed as integers;
+// going through the address keeps the ring base out of every access).
+typedef __attribute__((address_space(3))) uint32_t lds_word;
+__device__ __forceinline__ uint32_t lds_address(const void* p) {
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+__device__ __forceinline__ uint32_t lds_max_rtn(uint32_t byte_address, uint32_t v) {
+    return __hip_atomic_fetch_max((lds_word*)(uintptr_t)byte_address, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+__device__ __forceinline__ uint32_t lds_read(uint32_t byte_address) { return *(lds_word*)(uintptr_t)byte_address; }
+
+// Claim a slot for each of the lane's kCount requests.  `span[e]` = arrival tick | finish
+// tick << 16.  `slot_addr` is the LDS byte address of this lane's first-choice slot in
+// replica 0's ring and `ring0_addr` that of the ring itself; replica m's ring is
+// m << ring_shift bytes further on.  Two more rings follow the M real ones: ring M takes the
+// requests that name an unknown replica and is kept at "never free", so such a request loses
+// both probes and is reported from the rare path; ring M + 1 is a spare that is always free
+// (the ragged tail parks its absent requests there).
 // The steps are taken in groups of kGroup: within a group all first probes are issued
 // back to back (LDS executes them in order, so the steps still see each other's claims),
 // then the second probes (half a ring away) of the few that lost, then the rest of the ring
@@ -356,49 +371,43 @@ __device__ __forceinline__ void screen_fetch(ScreenRegs& g, const ScreenParams& 
 // claims of up to kGroup * 64 later requests; the host picks kGroup from M and S.
 // Returns true if some request of this lane found no slot or named an unknown replica.
 template <uint32_t kCount, uint32_t kGroup>
-__device__ __forceinline__ bool screen_claim(const uint32_t* id, const uint32_t* span,
-                                             unsigned char* lds, uint32_t slot_bytes, uint32_t ring_base_bytes,
-                                             uint32_t ring_shift, uint32_t M, uint32_t S, uint32_t my_first) {
-    uint32_t top = 0;
+__device__ __forceinline__ bool screen_claim(const uint32_t* id, const uint32_t* span, uint32_t slot_addr,
+                                             uint32_t ring0_addr, uint32_t ring_shift, uint32_t M, uint32_t S,
+                                             uint32_t my_first) {
     bool lane_bad = false;
-    uint32_t arr[kCount], fin[kCount];
-#pragma unroll
-    for (uint32_t e = 0; e < kCount; ++e) {
-        arr[e] = span[e] & 0xFFFFu;
-        fin[e] = span[e] >> 16;
-    }
 #pragma unroll
     for (uint32_t g = 0; g < kCount; g += kGroup) {
         uint32_t at[kGroup], old[kGroup], old2[kGroup];
 #pragma unroll
         for (uint32_t j = 0; j < kGroup; ++j) {
             const uint32_t e = g + j;
-            top = max(top, id[e]);
-            at[j] = (min(id[e], M) << ring_shift) + slot_bytes;
-            old[j] = atomicMax(reinterpret_cast<uint32_t*>(lds + at[j]), fin[e]);
+            at[j] = (min(id[e], M + 1u) << ring_shift) + slot_addr;
+            old[j] = lds_max_rtn(at[j], span[e] >> 16);
         }
 #pragma unroll
         for (uint32_t j = 0; j < kGroup; ++j) {
             const uint32_t e = g + j;
-            old2[j] = 0u;
-            if (old[j] > arr[e])
-                old2[j] = atomicMax(reinterpret_cast<uint32_t*>(lds + (at[j] ^ ((S >> 1) << 2))), fin[e]);
+            old2[j] = 0u;                 // results are looked at only after all second probes are issued
+            if (old[j] > (span[e] & 0xFFFFu)) old2[j] = lds_max_rtn(at[j] ^ ((S >> 1) << 2), span[e] >> 16);
         }
 #pragma unroll
         for (uint32_t j = 0; j < kGroup; ++j) {
             const uint32_t e = g + j;
-            if (old2[j] > arr[e] && id[e] < M) {
-                uint32_t* ring = reinterpret_cast<uint32_t*>(lds + ring_base_bytes + (id[e] << ring_shift));
+            if (old2[j] > (span[e] & 0xFFFFu)) {
                 bool placed = false;
-                for (uint32_t t = 1; t < S && !placed; ++t) {
-                    uint32_t* other = &ring[(my_first + t) & (S - 1u)];
-                    if (*other <= arr[e]) placed = atomicMax(other, fin[e]) <= arr[e];
+                if (id[e] < M) {
+                    const uint32_t ring = ring0_addr + (id[e] << ring_shift);
+                    const uint32_t arr = span[e] & 0xFFFFu, fin = span[e] >> 16;
+                    for (uint32_t t = 1; t < S && !placed; ++t) {
+                        const uint32_t other = ring + (((my_first + t) & (S - 1u)) << 2);
+                        if (lds_read(other) <= arr) placed = lds_max_rtn(other, fin) <= arr;
+                    }
                 }
-                lane_bad = lane_bad || !placed;
+                lane_bad = lane_bad || !placed;      // no slot, or an unknown replica (rejected, so not nominal)
             }
         }
     }
-    return lane_bad || top >= M;                     // unknown replica: rejected, so not nominal
+    return lane_bad;
 }
 
 template <bool kAligned, uint32_t kGroup>
@@ -408,15 +417,17 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenPara
     const uint32_t lane = threadIdx.x & 63u, w = wave_index();
     const uint32_t M = p.M, R = p.R, S = 1u << p.slots_log2;
     const uint32_t ring_shift = p.slots_log2 + 2u;                           // bytes per ring, log2
-    const uint32_t ring_base_bytes = w * ((M + 1u) << ring_shift);          // this wavefront's M + 1 rings
+    const uint32_t ring_base_bytes = w * ((M + 2u) << ring_shift);          // this wavefront's M + 2 rings
     uint32_t* slot = reinterpret_cast<uint32_t*>(lds + ring_base_bytes);
     const uint32_t my_first = lane & (S - 1u);
-    const uint32_t slot_bytes = ring_base_bytes + my_first * 4u;
+    const uint32_t ring0_addr = lds_address(slot);
+    const uint32_t slot_addr = ring0_addr + my_first * 4u;
     const uint32_t n_full = R / kScreenBlock;
 
     for (uint32_t c = blockIdx.x * kScreenWaves + w; c < C; c += gridDim.x * kScreenWaves) {
         const uint16_t* row = assign + (size_t)c * R;
-        for (uint32_t i = lane; i < ((M + 1u) << p.slots_log2); i += kWave) slot[i] = 0u;
+        for (uint32_t i = lane; i < ((M + 2u) << p.slots_log2); i += kWave)
+            slot[i] = (i >> p.slots_log2) == M ? kNever : 0u;               // ring M: unknown replicas, never free
         bool bad = false;
 
         // full blocks, two register sets: one is processed while the other is being loaded
@@ -427,16 +438,14 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenPara
             {
                 const uint32_t id[8] = {ga.pair[0] & 0xFFFFu, ga.pair[0] >> 16, ga.pair[1] & 0xFFFFu, ga.pair[1] >> 16,
                                         ga.pair[2] & 0xFFFFu, ga.pair[2] >> 16, ga.pair[3] & 0xFFFFu, ga.pair[3] >> 16};
-                bad = __ballot(screen_claim<8, kGroup>(id, ga.span, lds, slot_bytes, ring_base_bytes, ring_shift, M, S,
-                                            my_first)) != 0ull;
+                bad = __ballot(screen_claim<8, kGroup>(id, ga.span, slot_addr, ring0_addr, ring_shift, M, S, my_first)) != 0ull;
             }
             if (bad || b + 1u >= n_full) break;
             if (b + 2u < n_full) screen_fetch<kAligned>(ga, p, row, (b + 2u) * kScreenBlock, lane);
             {
                 const uint32_t id[8] = {gb.pair[0] & 0xFFFFu, gb.pair[0] >> 16, gb.pair[1] & 0xFFFFu, gb.pair[1] >> 16,
                                         gb.pair[2] & 0xFFFFu, gb.pair[2] >> 16, gb.pair[3] & 0xFFFFu, gb.pair[3] >> 16};
-                bad = __ballot(screen_claim<8, kGroup>(id, gb.span, lds, slot_bytes, ring_base_bytes, ring_shift, M, S,
-                                            my_first)) != 0ull;
+                bad = __ballot(screen_claim<8, kGroup>(id, gb.span, slot_addr, ring0_addr, ring_shift, M, S, my_first)) != 0ull;
             }
             if (bad) break;
         }
@@ -445,19 +454,14 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenPara
         const uint32_t i0 = n_full * kScreenBlock;
         if (!bad && i0 < R) {
             uint32_t id[8], span[8];
-            bool unknown = false;
 #pragma unroll
             for (uint32_t e = 0; e < 8u; ++e) {
                 const uint32_t r = i0 + 128u * (e >> 1) + 2u * lane + (e & 1u);
                 const bool in = r < R;
-                const uint32_t m = in ? (uint32_t)row[r] : 0u;
-                unknown = unknown || m >= M;
-                id[e] = in ? min(m, M) : M;
-                span[e] = in ? p.span_t[i0 + lane * 8u + e] : 0xFFFFu;       // absent: arrives last, finishes at 0, never loses
+                id[e] = in ? min((uint32_t)row[r], M) : M + 1u;
+                span[e] = in ? p.span_t[i0 + lane * 8u + e] : 0xFFFFu;       // absent: arrives last, finishes at 0
             }
-            // ids were clamped to the spare ring, so screen_claim itself reports only lost requests
-            bool lane_bad = screen_claim<8, kGroup>(id, span, lds, slot_bytes, ring_base_bytes, ring_shift, M + 1u, S, my_first);
-            bad = __ballot(lane_bad || unknown) != 0ull;
+            bad = __ballot(screen_claim<8, kGroup>(id, span, slot_addr, ring0_addr, ring_shift, M, S, my_first)) != 0ull;
         }
 
         // 64-byte record: nominal, or the pending mark
@@ -483,17 +487,18 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates_wide(Scree
     const uint32_t tid = threadIdx.x, lane = tid & 63u, j = wave_index();
     const uint32_t M = p.M, R = p.R, S = 1u << p.slots_log2;
     const uint32_t ring_shift = p.slots_log2 + 2u;
-    const uint32_t n_words = (M + 1u) << p.slots_log2;                       // M rings and the spare one
+    const uint32_t n_words = (M + 2u) << p.slots_log2;                       // M rings, the unknown-replica ring, a spare
     uint32_t* slot = reinterpret_cast<uint32_t*>(lds);
     uint32_t* flag = slot + n_words;
     const uint32_t my_first = lane & (S - 1u);
-    const uint32_t slot_bytes = my_first * 4u;
+    const uint32_t ring0_addr = lds_address(slot);
+    const uint32_t slot_addr = ring0_addr + my_first * 4u;
     const uint32_t n_full = R / kScreenBlock;
     const uint32_t mine = 128u * j + 2u * lane;                              // offset of this lane's pair in a block
 
     for (uint32_t c = blockIdx.x; c < C; c += gridDim.x) {
         const uint16_t* row = assign + (size_t)c * R;
-        for (uint32_t i = tid; i < n_words; i += kScreenThreads) slot[i] = 0u;
+        for (uint32_t i = tid; i < n_words; i += kScreenThreads) slot[i] = (i >> p.slots_log2) == M ? kNever : 0u;
         if (tid < 2u) flag[tid] = 0u;
         __syncthreads();
 
@@ -520,7 +525,7 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates_wide(Scree
         auto claim = [&](uint32_t d) {
             const uint32_t id[2] = {pair[d] & 0xFFFFu, pair[d] >> 16};
             const uint32_t sp[2] = {span[d].x, span[d].y};
-            return screen_claim<2, 2>(id, sp, lds, slot_bytes, 0u, ring_shift, M, S, my_first);
+            return screen_claim<2, 2>(id, sp, slot_addr, ring0_addr, ring_shift, M, S, my_first);
         };
         const uint32_t n_groups = n_full / kDepth;
         bool bad = false;
@@ -536,7 +541,7 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates_wide(Scree
                 const uint32_t id[2] = {pair[d] & 0xFFFFu, pair[d] >> 16};
                 const uint32_t sp[2] = {span[d].x, span[d].y};
                 fetch(d, min((g + 1u) * kDepth + d, n_full - 1u));           // refill (redundant in the last group)
-                lane_bad = screen_claim<2, 2>(id, sp, lds, slot_bytes, 0u, ring_shift, M, S, my_first) || lane_bad;
+                lane_bad = screen_claim<2, 2>(id, sp, slot_addr, ring0_addr, ring_shift, M, S, my_first) || lane_bad;
                 if (d + 1u == kDepth && __ballot(lane_bad) != 0ull && lane == 0) flag[turn & 1u] = 1u;
                 __syncthreads();
             }
@@ -551,18 +556,15 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates_wide(Scree
         const uint32_t i0 = n_full * kScreenBlock;
         if (!bad && i0 < R) {                                                // ragged tail, every access guarded
             uint32_t id[2], sp[2];
-            bool unknown = false;
 #pragma unroll
             for (uint32_t h = 0; h < 2u; ++h) {
                 const uint32_t r = i0 + mine + h;
                 const bool in = r < R;
-                const uint32_t m = in ? (uint32_t)row[r] : 0u;
-                unknown = unknown || m >= M;
-                id[h] = in ? min(m, M) : M;
-                sp[h] = in ? p.span[r] : 0xFFFFu;                            // absent: arrives last, finishes at 0, never loses
+                id[h] = in ? min((uint32_t)row[r], M) : M + 1u;
+                sp[h] = in ? p.span[r] : 0xFFFFu;                            // absent: arrives last, finishes at 0
             }
-            const bool lane_bad = screen_claim<2, 2>(id, sp, lds, slot_bytes, 0u, ring_shift, M + 1u, S, my_first);
-            if (__ballot(lane_bad || unknown) != 0ull && lane == 0) flag[turn & 1u] = 1u;
+            const bool lane_bad = screen_claim<2, 2>(id, sp, slot_addr, ring0_addr, ring_shift, M, S, my_first);
+            if (__ballot(lane_bad) != 0ull && lane == 0) flag[turn & 1u] = 1u;
         }
         __syncthreads();
         bad = (flag[0] | flag[1]) != 0u;
@@ -1441,8 +1443,8 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
         w->screen_group = 1;
         while (w->screen_group < 8u && 64u * (w->screen_group * 2u) * 4u <= M << S_log2) w->screen_group *= 2u;
         w->screen_wide = w->screen_group == 8u;          // exactly the candidates with large rings
-        w->screen_wide_lds_bytes = (((M + 1u) << S_log2) + 4u) * 4u;
-        w->screen_lds_bytes = kScreenWaves * ((M + 1u) << S_log2) * 4u;      // M rings and a spare one per wavefront
+        w->screen_wide_lds_bytes = (((M + 2u) << S_log2) + 4u) * 4u;
+        w->screen_lds_bytes = kScreenWaves * ((M + 2u) << S_log2) * 4u;      // M rings, one for unknown ids, a spare
         hipLaunchKernelGGL(hist16 ? k_nominal_metrics<true> : k_nominal_metrics<false>, dim3(1), dim3(kThreads),
                            reduce_lds, nullptr, w->reduce_eval, w->d_span, w->d_span_t, tick_shift, w->d_nominal);
         if (hipGetLastError() != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
