@@ -375,6 +375,7 @@ __device__ __forceinline__ bool screen_claim(const uint32_t* id, const uint32_t*
                                              uint32_t ring0_addr, uint32_t ring_shift, uint32_t M, uint32_t S,
                                              uint32_t my_first) {
     bool lane_bad = false;
+    const uint32_t spare_addr = ((M + 1u) << ring_shift) + slot_addr;        // this lane's word of the always-free ring
 #pragma unroll
     for (uint32_t g = 0; g < kCount; g += kGroup) {
         uint32_t at[kGroup], old[kGroup], old2[kGroup];
@@ -384,26 +385,33 @@ __device__ __forceinline__ bool screen_claim(const uint32_t* id, const uint32_t*
             at[j] = (min(id[e], M + 1u) << ring_shift) + slot_addr;
             old[j] = lds_max_rtn(at[j], span[e] >> 16);
         }
+        // Second probe without a branch: a lane that won its first probe "probes" its word of
+        // the always-free ring with the value 0, which changes nothing and cannot lose.
+        bool lost_any = false;
 #pragma unroll
         for (uint32_t j = 0; j < kGroup; ++j) {
             const uint32_t e = g + j;
-            old2[j] = 0u;                 // results are looked at only after all second probes are issued
-            if (old[j] > (span[e] & 0xFFFFu)) old2[j] = lds_max_rtn(at[j] ^ ((S >> 1) << 2), span[e] >> 16);
+            const bool lost = old[j] > (span[e] & 0xFFFFu);
+            old2[j] = lds_max_rtn(lost ? at[j] ^ ((S >> 1) << 2) : spare_addr, lost ? span[e] >> 16 : 0u);
         }
 #pragma unroll
-        for (uint32_t j = 0; j < kGroup; ++j) {
-            const uint32_t e = g + j;
-            if (old2[j] > (span[e] & 0xFFFFu)) {
-                bool placed = false;
-                if (id[e] < M) {
-                    const uint32_t ring = ring0_addr + (id[e] << ring_shift);
-                    const uint32_t arr = span[e] & 0xFFFFu, fin = span[e] >> 16;
-                    for (uint32_t t = 1; t < S && !placed; ++t) {
-                        const uint32_t other = ring + (((my_first + t) & (S - 1u)) << 2);
-                        if (lds_read(other) <= arr) placed = lds_max_rtn(other, fin) <= arr;
+        for (uint32_t j = 0; j < kGroup; ++j) lost_any = lost_any || old2[j] > (span[g + j] & 0xFFFFu);
+        if (__ballot(lost_any) != 0ull) {            // rare: some request of the group lost both probes
+#pragma unroll
+            for (uint32_t j = 0; j < kGroup; ++j) {
+                const uint32_t e = g + j;
+                if (old2[j] > (span[e] & 0xFFFFu)) {
+                    bool placed = false;
+                    if (id[e] < M) {
+                        const uint32_t ring = ring0_addr + (id[e] << ring_shift);
+                        const uint32_t arr = span[e] & 0xFFFFu, fin = span[e] >> 16;
+                        for (uint32_t t = 1; t < S && !placed; ++t) {
+                            const uint32_t other = ring + (((my_first + t) & (S - 1u)) << 2);
+                            if (lds_read(other) <= arr) placed = lds_max_rtn(other, fin) <= arr;
+                        }
                     }
+                    lane_bad = lane_bad || !placed;  // no slot, or an unknown replica (rejected, so not nominal)
                 }
-                lane_bad = lane_bad || !placed;      // no slot, or an unknown replica (rejected, so not nominal)
             }
         }
     }
