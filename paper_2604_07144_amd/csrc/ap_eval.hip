@@ -362,8 +362,9 @@ __device__ __forceinline__ uint32_t lds_read(uint32_t byte_address) { return *(l
 // replica 0's ring and `ring0_addr` that of the ring itself; replica m's ring is
 // m << ring_shift bytes further on.  Two more rings follow the M real ones: ring M takes the
 // requests that name an unknown replica and is kept at "never free", so such a request loses
-// both probes and is reported from the rare path; ring M + 1 is a spare that is always free
-// (the ragged tail parks its absent requests there).
+// both probes and is reported from the rare path; ring M + 1 is a spare that stays all zero
+// (nothing but zeros is ever written to it).  The ragged tail passes its absent requests as
+// (replica 0, arrival tick 0xFFFF, finish tick 0): a probe that changes nothing and cannot lose.
 // The steps are taken in groups of kGroup: within a group all first probes are issued
 // back to back (LDS executes them in order, so the steps still see each other's claims),
 // then the second probes (half a ring away) of the few that lost, then the rest of the ring
@@ -382,7 +383,7 @@ __device__ __forceinline__ bool screen_claim(const uint32_t* id, const uint32_t*
 #pragma unroll
         for (uint32_t j = 0; j < kGroup; ++j) {
             const uint32_t e = g + j;
-            at[j] = (min(id[e], M + 1u) << ring_shift) + slot_addr;
+            at[j] = (min(id[e], M) << ring_shift) + slot_addr;
             old[j] = lds_max_rtn(at[j], span[e] >> 16);
         }
         // Second probe without a branch: a lane that won its first probe "probes" its word of
@@ -458,7 +459,7 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenPara
             if (bad) break;
         }
 
-        // ragged tail: the same steps with every access guarded; absent requests go to the spare ring
+        // ragged tail: the same steps with every access guarded; absent requests become no-op probes
         const uint32_t i0 = n_full * kScreenBlock;
         if (!bad && i0 < R) {
             uint32_t id[8], span[8];
@@ -466,7 +467,7 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenPara
             for (uint32_t e = 0; e < 8u; ++e) {
                 const uint32_t r = i0 + 128u * (e >> 1) + 2u * lane + (e & 1u);
                 const bool in = r < R;
-                id[e] = in ? min((uint32_t)row[r], M) : M + 1u;
+                id[e] = in ? (uint32_t)row[r] : 0u;
                 span[e] = in ? p.span_t[i0 + lane * 8u + e] : 0xFFFFu;       // absent: arrives last, finishes at 0
             }
             bad = __ballot(screen_claim<8, kGroup>(id, span, slot_addr, ring0_addr, ring_shift, M, S, my_first)) != 0ull;
@@ -481,16 +482,85 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenPara
     }
 }
 
-// The same test with the four wavefronts of a workgroup sharing one candidate: wavefront j
-// takes the two steps 128j + 2l + h of every block (one 4-byte load of an assignment pair
-// and two 8-byte table loads per lane), all four claim from one set of rings, and a
-// barrier per block keeps them within the same 512 requests.  Used when the rings of one
-// candidate are large (M * S >= 2048 words): it quarters the LDS held per wavefront, so that
-// enough wavefronts are resident to hide the LDS and memory latency.
+// The same test with the eight wavefronts of a workgroup sharing one candidate, used when the
+// rings of one candidate are large: it divides the LDS held per wavefront by eight, so that
+// enough wavefronts are resident to hide the LDS and memory latency.  A block is 1024
+// consecutive requests; wavefront j takes the two steps 128j + 2l + h of it (one 4-byte load of
+// an assignment pair and one 8-byte table load per lane), all eight claim from one set of
+// rings, and a barrier per block keeps them within the same 1024 requests.
+//
+// Slot words here hold the whole span word of the last claimant (finish tick << 16 | arrival
+// tick): the maximum is still ordered by finish tick, and the test "old finish <= my arrival"
+// compares two 16-bit halves, so no field has to be extracted.
+//
+// Eight wavefronts work on a block in no particular order, and a request that probes a slot
+// after a later request has claimed it loses although it need not (a few percent do).  Losers
+// are therefore resolved per group of kDepth blocks: every lane sends the last of its requests
+// that lost to the slot half a ring away, in one probe for the whole wavefront (lanes without
+// a loser probe the spare ring, which changes nothing).  What is left - a lane with two losers,
+// or one that lost twice - goes round by round, every such lane trying the next slot of one
+// open request per round, until each has a slot or has tried the whole ring.
+constexpr uint32_t kWideWaves = 8;
+constexpr uint32_t kWideThreads = kWideWaves * kWave;
+constexpr uint32_t kWideBlock = kWideWaves * 128u;
+constexpr uint32_t kWideMaxSlots = 64;
+constexpr uint32_t kWideLdsBytes = 32768;         // slot state of the one candidate a workgroup holds
+
+__device__ __forceinline__ bool span_busy(uint32_t old, uint32_t span) { return (old >> 16) > (span & 0xFFFFu); }
+
+// Resolve the K first probes of a lane (`old[k]` came back from slot `at[k]` for span word
+// `span[k]`).  Returns true if some request found no slot in its whole ring.
+template <uint32_t K>
+__device__ __forceinline__ bool wide_resolve(const uint32_t (&span)[K], const uint32_t (&at)[K],
+                                             const uint32_t (&old)[K], uint32_t spare_addr, uint32_t S,
+                                             uint32_t slots_log2) {
+    uint32_t sel_at = spare_addr, sel_span = 0xFFFFu;                        // default: a probe that changes nothing
+    bool have = false, multi = false;
+#pragma unroll
+    for (uint32_t k = 0; k < K; ++k) {
+        const bool lost = span_busy(old[k], span[k]);
+        multi = multi || (have && lost);
+        have = have || lost;
+        sel_at = lost ? at[k] : sel_at;
+        sel_span = lost ? span[k] : sel_span;
+    }
+    const uint32_t old2 = lds_max_rtn(sel_at ^ ((S >> 1) << 2), sel_span);
+    const bool sel_lost = span_busy(old2, sel_span);
+    bool lane_bad = false;
+    if (__ballot(multi || sel_lost) != 0ull) {
+        uint32_t open = 0;                                                   // bit k: request k has no slot yet
+#pragma unroll
+        for (uint32_t k = 0; k < K; ++k) open |= span_busy(old[k], span[k]) ? 1u << k : 0u;
+        uint32_t t = 2u;                                                     // next alternative of the request in hand
+        if (!sel_lost) {                                                     // the one just probed (the highest) is placed
+            open &= ~(1u << (open ? 31u - (uint32_t)__clz(open) : 0u));
+            t = 1u;
+        }
+        while (__ballot(open != 0u) != 0ull) {
+            if (open != 0u) {
+                const uint32_t k = 31u - (uint32_t)__clz(open);
+                uint32_t cur_at = at[0], cur_span = span[0];
+#pragma unroll
+                for (uint32_t j = 1; j < K; ++j) {
+                    cur_at = k == j ? at[j] : cur_at;
+                    cur_span = k == j ? span[j] : cur_span;
+                }
+                // alternatives in bit-reversed order: half a ring away, a quarter, three quarters, ...
+                const uint32_t hop = ((__builtin_bitreverse32(t) >> 1) >> (31u - slots_log2)) << 2;
+                const bool placed = !span_busy(lds_max_rtn(cur_at ^ hop, cur_span), cur_span);
+                const bool last = t + 1u >= S;                               // that was the last other slot of the ring
+                lane_bad = lane_bad || (!placed && last);
+                if (placed || last) { open &= ~(1u << k); t = 1u; } else { ++t; }
+            }
+        }
+    }
+    return lane_bad;
+}
+
 template <bool kAligned>
-__global__ __launch_bounds__(kScreenThreads) void k_screen_candidates_wide(ScreenParams p,
-                                                                            const uint16_t* __restrict__ assign,
-                                                                            ap_metrics* __restrict__ out, uint32_t C) {
+__global__ __launch_bounds__(kWideThreads) void k_screen_candidates_wide(ScreenParams p,
+                                                                          const uint16_t* __restrict__ assign,
+                                                                          ap_metrics* __restrict__ out, uint32_t C) {
     extern __shared__ __align__(16) unsigned char lds[];
     const uint32_t tid = threadIdx.x, lane = tid & 63u, j = wave_index();
     const uint32_t M = p.M, R = p.R, S = 1u << p.slots_log2;
@@ -498,30 +568,31 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates_wide(Scree
     const uint32_t n_words = (M + 2u) << p.slots_log2;                       // M rings, the unknown-replica ring, a spare
     uint32_t* slot = reinterpret_cast<uint32_t*>(lds);
     uint32_t* flag = slot + n_words;
-    const uint32_t my_first = lane & (S - 1u);
     const uint32_t ring0_addr = lds_address(slot);
-    const uint32_t slot_addr = ring0_addr + my_first * 4u;
-    const uint32_t n_full = R / kScreenBlock;
+    const uint32_t slot_addr = ring0_addr + (lane & (S - 1u)) * 4u;          // this lane's first choice in replica 0's ring
+    const uint32_t spare_addr = ((M + 1u) << ring_shift) + slot_addr;
+    const uint32_t n_full = R / kWideBlock;
     const uint32_t mine = 128u * j + 2u * lane;                              // offset of this lane's pair in a block
+    // alternatives are reached by flipping address bits, which needs the rings aligned to their size
+    const bool rings_aligned = (ring0_addr & ((S << 2) - 1u)) == 0u;
 
     for (uint32_t c = blockIdx.x; c < C; c += gridDim.x) {
         const uint16_t* row = assign + (size_t)c * R;
-        for (uint32_t i = tid; i < n_words; i += kScreenThreads) slot[i] = (i >> p.slots_log2) == M ? kNever : 0u;
-        if (tid < 2u) flag[tid] = 0u;
+        for (uint32_t i = tid; i < n_words; i += kWideThreads) slot[i] = (i >> p.slots_log2) == M ? kNever : 0u;
+        if (tid < 2u) flag[tid] = rings_aligned ? 0u : 1u;
         __syncthreads();
 
         // Full blocks go in groups of kDepth.  While a group is processed the loads of the next
         // group are issued, one register set per block, so kDepth blocks stay in flight per
         // wavefront; the body is straight-line (the prefetch index is clamped instead of
-        // guarded) so the register sets never have to be copied.  A barrier after every block
-        // keeps the four wavefronts within the same 512 requests.  The verdict is exchanged once
+        // guarded) so the register sets never have to be copied.  The verdict is exchanged once
         // per group: group g reports in flag[g & 1], and a wavefront already in the next group
         // writes the other word, so all wavefronts read the same verdict and leave together.
         constexpr uint32_t kDepth = 2;
         uint32_t pair[kDepth];
         uint2 span[kDepth];
         auto fetch = [&](uint32_t d, uint32_t blk) {
-            const uint32_t i0 = blk * kScreenBlock;
+            const uint32_t i0 = blk * kWideBlock;
             const uint16_t* at = row + i0 + mine;
             if (kAligned) {
                 pair[d] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(at));
@@ -530,57 +601,57 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates_wide(Scree
             }
             span[d] = *reinterpret_cast<const uint2*>(p.span + i0 + mine);
         };
-        auto claim = [&](uint32_t d) {
-            const uint32_t id[2] = {pair[d] & 0xFFFFu, pair[d] >> 16};
-            const uint32_t sp[2] = {span[d].x, span[d].y};
-            return screen_claim<2, 2>(id, sp, slot_addr, ring0_addr, ring_shift, M, S, my_first);
+        auto first_probe = [&](uint32_t id, uint32_t sp, uint32_t& at, uint32_t& old) {
+            at = (min(id, M) << ring_shift) + slot_addr;                     // unknown replicas: the never-free ring
+            old = lds_max_rtn(at, sp);
         };
         const uint32_t n_groups = n_full / kDepth;
-        bool bad = false;
+        bool bad = !rings_aligned;
         uint32_t turn = 0;                                                   // which flag word the next verdict uses
-        if (n_groups > 0u) {
+        if (n_groups > 0u && !bad) {
 #pragma unroll
             for (uint32_t d = 0; d < kDepth; ++d) fetch(d, d);
         }
         for (uint32_t g = 0; g < n_groups && !bad; ++g, ++turn) {
-            bool lane_bad = false;
+            uint32_t sp[2 * kDepth], at[2 * kDepth], old[2 * kDepth];
 #pragma unroll
             for (uint32_t d = 0; d < kDepth; ++d) {
-                const uint32_t id[2] = {pair[d] & 0xFFFFu, pair[d] >> 16};
-                const uint32_t sp[2] = {span[d].x, span[d].y};
+                const uint32_t ids = pair[d];
+                sp[2 * d] = span[d].x;
+                sp[2 * d + 1] = span[d].y;
                 fetch(d, min((g + 1u) * kDepth + d, n_full - 1u));           // refill (redundant in the last group)
-                lane_bad = screen_claim<2, 2>(id, sp, slot_addr, ring0_addr, ring_shift, M, S, my_first) || lane_bad;
-                if (d + 1u == kDepth && __ballot(lane_bad) != 0ull && lane == 0) flag[turn & 1u] = 1u;
-                __syncthreads();
+                first_probe(ids & 0xFFFFu, sp[2 * d], at[2 * d], old[2 * d]);
+                first_probe(ids >> 16, sp[2 * d + 1], at[2 * d + 1], old[2 * d + 1]);
+                if (d + 1u < kDepth) __syncthreads();
             }
-            bad = flag[turn & 1u] != 0u;
-        }
-        for (uint32_t blk = n_groups * kDepth; blk < n_full && !bad; ++blk, ++turn) {    // fewer than kDepth blocks left
-            fetch(0u, blk);
-            if (__ballot(claim(0u)) != 0ull && lane == 0) flag[turn & 1u] = 1u;
+            const bool lane_bad = wide_resolve<2 * kDepth>(sp, at, old, spare_addr, S, p.slots_log2);
+            if (__ballot(lane_bad) != 0ull && lane == 0) flag[turn & 1u] = 1u;
             __syncthreads();
             bad = flag[turn & 1u] != 0u;
         }
-        const uint32_t i0 = n_full * kScreenBlock;
-        if (!bad && i0 < R) {                                                // ragged tail, every access guarded
-            uint32_t id[2], sp[2];
+        // fewer than kDepth full blocks left, then the ragged tail with every access guarded
+        // (an absent request is a probe of replica 0 that changes nothing and cannot lose)
+        const uint32_t n_rest = n_full - n_groups * kDepth + (n_full * kWideBlock < R ? 1u : 0u);
+        for (uint32_t k = 0; k < n_rest && !bad; ++k, ++turn) {
+            const uint32_t i0 = (n_groups * kDepth + k) * kWideBlock;
+            uint32_t sp[2], at[2], old[2];
 #pragma unroll
             for (uint32_t h = 0; h < 2u; ++h) {
                 const uint32_t r = i0 + mine + h;
                 const bool in = r < R;
-                id[h] = in ? min((uint32_t)row[r], M) : M + 1u;
-                sp[h] = in ? p.span[r] : 0xFFFFu;                            // absent: arrives last, finishes at 0
+                sp[h] = in ? p.span[r] : 0xFFFFu;
+                first_probe(in ? (uint32_t)row[r] : 0u, sp[h], at[h], old[h]);
             }
-            const bool lane_bad = screen_claim<2, 2>(id, sp, slot_addr, ring0_addr, ring_shift, M, S, my_first);
+            const bool lane_bad = wide_resolve<2>(sp, at, old, spare_addr, S, p.slots_log2);
             if (__ballot(lane_bad) != 0ull && lane == 0) flag[turn & 1u] = 1u;
+            __syncthreads();
+            bad = flag[turn & 1u] != 0u;
         }
-        __syncthreads();
-        bad = (flag[0] | flag[1]) != 0u;
         if (tid < 8u) {
             const unsigned long long* src = reinterpret_cast<const unsigned long long*>(p.nominal);
             reinterpret_cast<unsigned long long*>(&out[c])[tid] = bad ? ~0ull : src[tid];
         }
-        __syncthreads();
+        __syncthreads();                                                     // everyone has read the flags
     }
 }
 
@@ -1451,6 +1522,11 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
         w->screen_group = 1;
         while (w->screen_group < 8u && 64u * (w->screen_group * 2u) * 4u <= M << S_log2) w->screen_group *= 2u;
         w->screen_wide = w->screen_group == 8u;          // exactly the candidates with large rings
+        if (w->screen_wide) {
+            // one candidate per workgroup: room for more slots per replica
+            while ((2u << S_log2) <= std::min(B, kWideMaxSlots) && M * (2u << S_log2) * 4u <= kWideLdsBytes) ++S_log2;
+            w->screen_params.slots_log2 = S_log2;
+        }
         w->screen_wide_lds_bytes = (((M + 2u) << S_log2) + 4u) * 4u;
         w->screen_lds_bytes = kScreenWaves * ((M + 2u) << S_log2) * 4u;      // M rings, one for unknown ids, a spare
         hipLaunchKernelGGL(hist16 ? k_nominal_metrics<true> : k_nominal_metrics<false>, dim3(1), dim3(kThreads),
@@ -1478,7 +1554,7 @@ ap_status ap_eval_candidates(const ap_workload* w, const uint16_t* d_assign, uin
         void (*kernel)(ScreenParams, const uint16_t*, ap_metrics*, uint32_t) = nullptr;
         if (w->screen_wide) {
             kernel = aligned ? k_screen_candidates_wide<true> : k_screen_candidates_wide<false>;
-            hipLaunchKernelGGL(kernel, dim3(std::min(C, w->n_cu * 8u)), dim3(kScreenThreads), w->screen_wide_lds_bytes,
+            hipLaunchKernelGGL(kernel, dim3(std::min(C, w->n_cu * 8u)), dim3(kWideThreads), w->screen_wide_lds_bytes,
                                stream, w->screen_params, d_assign, d_out, C);
         } else {
         switch (w->screen_group) {

@@ -117,6 +117,24 @@ def test_screening_with_invalid_ids_and_unaligned_batch_pointer():
         assert_same(to_records(d_out), want, "unaligned batch")
 
 
+@pytest.mark.parametrize("n,M,B", [(4096 + 700, 8, 16), (8192 + 300, 128, 64)])
+def test_unknown_ids_in_otherwise_contention_free_candidates(n, M, B):
+    """Light load, identical replicas: nobody waits, so the shortcut for contention-free candidates decides
+    every row; a single unknown replica id anywhere in a row (first block, middle, ragged tail; the id just
+    past the table, a few further on, the largest) must still be seen.  Both forms of that kernel
+    (small and large replica tables)."""
+    tr = _mk(n, M, B, 60_000, seed=n, coef=[STD] * M, penalty_us=7_000_000)
+    rows = _rows(12, n, M, seed=B)
+    for c, (pos, bad_id) in enumerate([(0, M), (1, M + 1), (700, M + 2), (2047, 65535), (4095, M + 1), (n - 1, M),
+                                       (n - 1, M + 1), (n - 300, 65535), (n // 2, M + 7)]):
+        rows[c, pos] = bad_id
+    want = oracle_for(tr).eval_batch(rows, nthreads=8)
+    assert want["n_rejected"].tolist() == [1] * 9 + [0] * 3
+    assert len(set(want["sum_ttft_us"][9:].tolist())) == 1                # the valid rows are contention-free
+    with GpuWorkload(tr) as g:
+        assert_same(g.eval(rows), want, "unknown ids, light load")
+
+
 @pytest.mark.parametrize("name,n,M,B,gap,C,homogeneous,windows", [
     ("max_table_light", 30000, 1024, 64, 60, 6, False, False),      # the largest replica table and slot count
     ("max_table_homogeneous_saturated", 40000, 1024, 64, 1, 5, True, False),   # screening first, then the pipeline
@@ -138,6 +156,26 @@ def test_large_replica_tables_take_the_queue_per_lane_path(name, n, M, B, gap, C
     rows = _rows(C, n, M + (0 if homogeneous else 2), seed=M)           # a few unknown replica ids
     rows[0] = rng.integers(0, 8, n)                                     # everything on eight replicas: deep queues
     both(tr, rows, name)
+
+
+def test_lengths_beyond_16_bits_and_coarse_ticks():
+    """Prompt / output lengths >= 65536 (32-bit staging in the replay kernel) and a trace long enough that the
+    screening kernel's 16-bit ticks are coarser than a microsecond."""
+    rng = np.random.default_rng(77)
+    n, M = 6000, 6
+    arrival = (np.cumsum(rng.integers(0, 40_000, n)) + 5).astype(np.uint64)           # two minutes of trace: 2 ms ticks
+    prompt = rng.integers(1, 3000, n)
+    out = rng.integers(1, 300, n)
+    prompt[::97] = rng.integers(65536, 200_000, len(prompt[::97]))                    # a few very long prompts
+    out[::89] = rng.integers(65536, 90_000, len(out[::89]))
+    coef = [(50, 1, 2, 1)] * M                                                         # small coefficients keep times in range
+    tr = traces.custom_trace(arrival, prompt, out, coef, B=3, slo_ttft_us=200_000, slo_tpot_us=40)
+    rows = _rows(12, n, M, seed=5)
+    rows[0] = 0                                                                        # one replica takes everything: queueing
+    got = both(tr, rows, "long lengths, homogeneous (screened)")
+    assert len(set(got["sum_ttft_us"].tolist())) > 1                                   # screened and replayed rows both occur
+    mixed = traces.custom_trace(arrival, prompt, out, [(50, 1, 2, 1), (80, 2, 3, 1)] * 3, B=3)
+    both(mixed, rows, "long lengths, two replica types (replayed)")
 
 
 def test_all_requests_on_one_replica_and_empty_replicas():
