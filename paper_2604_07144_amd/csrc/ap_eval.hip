@@ -494,12 +494,12 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenPara
 // compares two 16-bit halves, so no field has to be extracted.
 //
 // Eight wavefronts work on a block in no particular order, and a request that probes a slot
-// after a later request has claimed it loses although it need not (a few percent do).  Losers
-// are therefore resolved per group of kDepth blocks: every lane sends the last of its requests
-// that lost to the slot half a ring away, in one probe for the whole wavefront (lanes without
-// a loser probe the spare ring, which changes nothing).  What is left - a lane with two losers,
-// or one that lost twice - goes round by round, every such lane trying the next slot of one
-// open request per round, until each has a slot or has tried the whole ring.
+// after a later request has claimed it loses although it need not (a few percent do).  A
+// request that lost goes straight to the slot half a ring away, in the same instruction in
+// which the lanes that won "probe" the spare ring with a zero (which changes nothing and cannot
+// lose), so the common case has no branch.  What is left - requests that lost twice - goes
+// round by round, every such lane trying the next slot of one open request per round, until
+// each has a slot or has tried the whole ring.
 constexpr uint32_t kWideWaves = 8;
 constexpr uint32_t kWideThreads = kWideWaves * kWave;
 constexpr uint32_t kWideBlock = kWideWaves * 128u;
@@ -509,33 +509,28 @@ constexpr uint32_t kWideLdsBytes = 32768;         // slot state of the one candi
 __device__ __forceinline__ bool span_busy(uint32_t old, uint32_t span) { return (old >> 16) > (span & 0xFFFFu); }
 
 // Resolve the K first probes of a lane (`old[k]` came back from slot `at[k]` for span word
-// `span[k]`).  Returns true if some request found no slot in its whole ring.
+// `span[k]`): second probe half a ring away for those that lost, then the rounds.  Returns
+// true if some request found no slot in its whole ring.
 template <uint32_t K>
 __device__ __forceinline__ bool wide_resolve(const uint32_t (&span)[K], const uint32_t (&at)[K],
                                              const uint32_t (&old)[K], uint32_t spare_addr, uint32_t S,
                                              uint32_t slots_log2) {
-    uint32_t sel_at = spare_addr, sel_span = 0xFFFFu;                        // default: a probe that changes nothing
-    bool have = false, multi = false;
+    const uint32_t half = (S >> 1) << 2;
+    uint32_t o2[K];
 #pragma unroll
     for (uint32_t k = 0; k < K; ++k) {
         const bool lost = span_busy(old[k], span[k]);
-        multi = multi || (have && lost);
-        have = have || lost;
-        sel_at = lost ? at[k] : sel_at;
-        sel_span = lost ? span[k] : sel_span;
+        o2[k] = lds_max_rtn(lost ? at[k] ^ half : spare_addr, lost ? span[k] : 0u);
     }
-    const uint32_t old2 = lds_max_rtn(sel_at ^ ((S >> 1) << 2), sel_span);
-    const bool sel_lost = span_busy(old2, sel_span);
-    bool lane_bad = false;
-    if (__ballot(multi || sel_lost) != 0ull) {
-        uint32_t open = 0;                                                   // bit k: request k has no slot yet
+    bool any = false;
 #pragma unroll
-        for (uint32_t k = 0; k < K; ++k) open |= span_busy(old[k], span[k]) ? 1u << k : 0u;
+    for (uint32_t k = 0; k < K; ++k) any = any || span_busy(o2[k], span[k]);
+    bool lane_bad = false;
+    if (__ballot(any) != 0ull) {
+        uint32_t open = 0;
+#pragma unroll
+        for (uint32_t k = 0; k < K; ++k) open |= span_busy(o2[k], span[k]) ? 1u << k : 0u;
         uint32_t t = 2u;                                                     // next alternative of the request in hand
-        if (!sel_lost) {                                                     // the one just probed (the highest) is placed
-            open &= ~(1u << (open ? 31u - (uint32_t)__clz(open) : 0u));
-            t = 1u;
-        }
         while (__ballot(open != 0u) != 0ull) {
             if (open != 0u) {
                 const uint32_t k = 31u - (uint32_t)__clz(open);
@@ -545,12 +540,12 @@ __device__ __forceinline__ bool wide_resolve(const uint32_t (&span)[K], const ui
                     cur_at = k == j ? at[j] : cur_at;
                     cur_span = k == j ? span[j] : cur_span;
                 }
-                // alternatives in bit-reversed order: half a ring away, a quarter, three quarters, ...
+                // alternatives in bit-reversed order: half a ring away (done), a quarter, three quarters, ...
                 const uint32_t hop = ((__builtin_bitreverse32(t) >> 1) >> (31u - slots_log2)) << 2;
                 const bool placed = !span_busy(lds_max_rtn(cur_at ^ hop, cur_span), cur_span);
                 const bool last = t + 1u >= S;                               // that was the last other slot of the ring
                 lane_bad = lane_bad || (!placed && last);
-                if (placed || last) { open &= ~(1u << k); t = 1u; } else { ++t; }
+                if (placed || last) { open &= ~(1u << k); t = 2u; } else { ++t; }
             }
         }
     }
@@ -613,18 +608,19 @@ __global__ __launch_bounds__(kWideThreads) void k_screen_candidates_wide(ScreenP
             for (uint32_t d = 0; d < kDepth; ++d) fetch(d, d);
         }
         for (uint32_t g = 0; g < n_groups && !bad; ++g, ++turn) {
-            uint32_t sp[2 * kDepth], at[2 * kDepth], old[2 * kDepth];
+            bool lane_bad = false;
 #pragma unroll
             for (uint32_t d = 0; d < kDepth; ++d) {
+                uint32_t sp[2], at[2], old[2];
                 const uint32_t ids = pair[d];
-                sp[2 * d] = span[d].x;
-                sp[2 * d + 1] = span[d].y;
+                sp[0] = span[d].x;
+                sp[1] = span[d].y;
                 fetch(d, min((g + 1u) * kDepth + d, n_full - 1u));           // refill (redundant in the last group)
-                first_probe(ids & 0xFFFFu, sp[2 * d], at[2 * d], old[2 * d]);
-                first_probe(ids >> 16, sp[2 * d + 1], at[2 * d + 1], old[2 * d + 1]);
+                first_probe(ids & 0xFFFFu, sp[0], at[0], old[0]);
+                first_probe(ids >> 16, sp[1], at[1], old[1]);
+                lane_bad = wide_resolve<2>(sp, at, old, spare_addr, S, p.slots_log2) || lane_bad;
                 if (d + 1u < kDepth) __syncthreads();
             }
-            const bool lane_bad = wide_resolve<2 * kDepth>(sp, at, old, spare_addr, S, p.slots_log2);
             if (__ballot(lane_bad) != 0ull && lane == 0) flag[turn & 1u] = 1u;
             __syncthreads();
             bad = flag[turn & 1u] != 0u;
