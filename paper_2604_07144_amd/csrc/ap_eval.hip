@@ -583,7 +583,7 @@ __global__ __launch_bounds__(kWideThreads) void k_screen_candidates_wide(ScreenP
         // guarded) so the register sets never have to be copied.  The verdict is exchanged once
         // per group: group g reports in flag[g & 1], and a wavefront already in the next group
         // writes the other word, so all wavefronts read the same verdict and leave together.
-        constexpr uint32_t kDepth = 2;
+        constexpr uint32_t kDepth = 4;
         uint32_t pair[kDepth];
         uint2 span[kDepth];
         auto fetch = [&](uint32_t d, uint32_t blk) {
