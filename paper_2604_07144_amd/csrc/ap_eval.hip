@@ -225,8 +225,9 @@ __device__ __forceinline__ bool is_pending(const ap_metrics& m) {
 constexpr uint32_t kScreenWaves = 4;
 constexpr uint32_t kScreenThreads = kScreenWaves * kWave;
 constexpr uint32_t kScreenBlock = kWave * 8u;     // requests per wavefront per block
-constexpr uint32_t kScreenMaxSlots = 32;
-constexpr uint32_t kScreenLdsPerWave = 16384;     // bytes of slot state per candidate in flight
+constexpr uint32_t kScreenMaxSlots = 64;          // slots per replica worth having
+constexpr uint32_t kScreenMinSlots = 32;          // fewer (with B allowing more) and the one-wavefront kernel is not used
+constexpr uint32_t kScreenLdsPerWave = 9216;      // bytes of slot state one wavefront may hold
 
 // Position of request r in the lane-major tables: in its block of 512, request
 // 128k + 2l + h is element 2k + h of lane l.
@@ -289,37 +290,40 @@ __global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint
 // ----------------------------------------------------------------------------------
 // Applies when every replica has the same coefficients and is available throughout, so a
 // request that does not wait occupies a slot during [arrival, arrival + service).
-// Each replica gets S <= B screening slots in LDS, all 0.  Every request probes its
-// replica's slots with an atomic max of its finish time: a probe whose old value is <= the
-// request's arrival has claimed a slot that no request still in service at that instant
-// holds; any other probe only raises the slot's value.  Slot values never decrease, so a
-// slot can look busy when it is not but never free when it is busy: two requests that
+// Each replica gets S <= B screening slots in LDS, all 0.  Every request probes slots of its
+// replica with an atomic max of its service interval: a probe whose old value ends at or
+// before the request's arrival has claimed a slot that no request still in service at that
+// instant holds; any other probe only raises the slot's value.  Slot values never decrease, so
+// a slot can look busy when it is not but never free when it is busy: two requests that
 // claimed the same slot have disjoint service intervals, in whatever order they were
-// processed.  Hence, if every request of the candidate claims a slot, the contention-free
-// schedule keeps at most S <= B requests in service per replica at any time, nobody waits
-// in the B-slot queue, and the candidate's record is the nominal one.  The test is
-// sufficient, not necessary: a candidate with a request that finds no slot, or that names
-// a replica outside the table, is marked pending and is replayed exactly by
-// k_eval_candidates.  Requests are taken 64 at a time in arrival order, which keeps the
-// number of slots a replica needs close to its true concurrency.
+// processed and whichever slots they tried.  Hence, if every request of the candidate claims a
+// slot, the contention-free schedule keeps at most S <= B requests in service per replica at
+// any time, nobody waits in the B-slot queue, and the candidate's record is the nominal one.
+// The test is sufficient, not necessary: a candidate with a request that finds no slot, or that
+// names a replica outside the table, is marked pending and is replayed exactly by
+// k_eval_candidates.  Requests are taken roughly in arrival order, which keeps the number of
+// slots a replica needs close to its true concurrency.
 //
 // Times here are 16-bit ticks of 2^k microseconds (k chosen so that the whole range fits),
 // with every service interval rounded outwards: arrival down, finish up.  A claim needs
 // old finish tick <= arrival tick, which implies old finish <= arrival in microseconds, so
 // the rounding only makes the test more conservative; it halves the table bytes read per
-// request (one 32-bit word: arrival tick | finish tick << 16).
+// request (one 32-bit span word: arrival tick | finish tick << 16).  A slot holds the whole
+// span word of its last claimant: the maximum is still ordered by finish tick, and the test
+// compares two 16-bit halves, so no field has to be extracted.
 //
-// One wavefront per candidate.  A block is 512 consecutive requests; lane l holds the eight
-// requests i0 + 128k + 2l + h (k = 0..3, h = 0..1): four 4-byte loads of assignment pairs.
-// Step e = 2k + h therefore covers every other request of a 128-request window, close
-// enough to arrival order.  The arrival / finish tables are stored lane-major so that a
-// lane's eight values are contiguous (two 16-byte loads each).
+// Two more rings follow the M real ones in a candidate's slot state: ring M takes the requests
+// that name an unknown replica and is kept at "never free", so such a request loses every
+// probe and the candidate ends up pending; ring M + 1 (large tables only) is a spare that
+// stays all zero.  The ragged tail passes its absent requests as (replica 0, arrival tick
+// 0xFFFF, finish tick 0): a probe that cannot lose and leaves every finish tick as it was.
 struct ScreenParams {
     const uint32_t* span;         // [R] in request order: arrival tick | finish tick << 16 (interval rounded outwards)
     const uint32_t* span_t;       // [ceil(R/512)*512] the same words in the order given by screen_table_index
     const ap_metrics* nominal;
     uint32_t R, M;
     uint32_t slots_log2;          // S = 1 << slots_log2
+    uint32_t wave_bytes;          // small tables: LDS bytes of one wavefront's slot state (a multiple of 4 S)
 };
 
 struct ScreenRegs {
@@ -355,111 +359,122 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
 __device__ __forceinline__ uint32_t lds_max_rtn(uint32_t byte_address, uint32_t v) {
     return __hip_atomic_fetch_max((lds_word*)(uintptr_t)byte_address, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
-__device__ __forceinline__ uint32_t lds_read(uint32_t byte_address) { return *(lds_word*)(uintptr_t)byte_address; }
+__device__ __forceinline__ uint32_t lds_add_rtn(uint32_t byte_address, uint32_t v) {
+    return __hip_atomic_fetch_add((lds_word*)(uintptr_t)byte_address, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
 
-// Claim a slot for each of the lane's kCount requests.  `span[e]` = arrival tick | finish
-// tick << 16.  `slot_addr` is the LDS byte address of this lane's first-choice slot in
-// replica 0's ring and `ring0_addr` that of the ring itself; replica m's ring is
-// m << ring_shift bytes further on.  Two more rings follow the M real ones: ring M takes the
-// requests that name an unknown replica and is kept at "never free", so such a request loses
-// both probes and is reported from the rare path; ring M + 1 is a spare that stays all zero
-// (nothing but zeros is ever written to it).  The ragged tail passes its absent requests as
-// (replica 0, arrival tick 0xFFFF, finish tick 0): a probe that changes nothing and cannot lose.
-// The steps are taken in groups of kGroup: within a group all first probes are issued
-// back to back (LDS executes them in order, so the steps still see each other's claims),
-// then the second probes (half a ring away) of the few that lost, then the rest of the ring
-// for those that lost twice.  A larger group hides more LDS latency but lets a retry see
-// claims of up to kGroup * 64 later requests; the host picks kGroup from M and S.
-// Returns true if some request of this lane found no slot or named an unknown replica.
-template <uint32_t kCount, uint32_t kGroup>
-__device__ __forceinline__ bool screen_claim(const uint32_t* id, const uint32_t* span, uint32_t slot_addr,
-                                             uint32_t ring0_addr, uint32_t ring_shift, uint32_t M, uint32_t S,
-                                             uint32_t my_first) {
+// does the interval whose span word is `old` end after the one of `span` begins?
+__device__ __forceinline__ bool span_busy(uint32_t old, uint32_t span) { return (old >> 16) > (span & 0xFFFFu); }
+
+// The slow part shared by both kernels: bit k of `open` says that request k of this lane
+// (first tried at LDS address `at[k]`, span word `span[k]`) still has no slot, having tried
+// the first `tried` alternatives of its ring.  Round by round, every such lane tries the next
+// slot of one open request, until each request has a slot or has tried the whole ring.
+// Alternatives are reached by flipping address bits in bit-reversed order (half a ring away, a
+// quarter, three quarters, ...), which needs the rings aligned to their size.
+// Returns true if some request of this lane found no slot.
+template <uint32_t K>
+__device__ __forceinline__ bool screen_search(const uint32_t (&span)[K], const uint32_t (&at)[K], uint32_t open,
+                                              uint32_t tried, uint32_t S, uint32_t slots_log2) {
     bool lane_bad = false;
-    const uint32_t spare_addr = ((M + 1u) << ring_shift) + slot_addr;        // this lane's word of the always-free ring
+    uint32_t t = tried + 1u;                                                 // next alternative of the request in hand
+    while (__ballot(open != 0u) != 0ull) {
+        if (open != 0u) {
+            const uint32_t k = 31u - (uint32_t)__clz(open);
+            uint32_t cur_at = at[0], cur_span = span[0];
 #pragma unroll
-    for (uint32_t g = 0; g < kCount; g += kGroup) {
-        uint32_t at[kGroup], old[kGroup], old2[kGroup];
-#pragma unroll
-        for (uint32_t j = 0; j < kGroup; ++j) {
-            const uint32_t e = g + j;
-            at[j] = (min(id[e], M) << ring_shift) + slot_addr;
-            old[j] = lds_max_rtn(at[j], span[e] >> 16);
-        }
-        // Second probe without a branch: a lane that won its first probe "probes" its word of
-        // the always-free ring with the value 0, which changes nothing and cannot lose.
-        bool lost_any = false;
-#pragma unroll
-        for (uint32_t j = 0; j < kGroup; ++j) {
-            const uint32_t e = g + j;
-            const bool lost = old[j] > (span[e] & 0xFFFFu);
-            old2[j] = lds_max_rtn(lost ? at[j] ^ ((S >> 1) << 2) : spare_addr, lost ? span[e] >> 16 : 0u);
-        }
-#pragma unroll
-        for (uint32_t j = 0; j < kGroup; ++j) lost_any = lost_any || old2[j] > (span[g + j] & 0xFFFFu);
-        if (__ballot(lost_any) != 0ull) {            // rare: some request of the group lost both probes
-#pragma unroll
-            for (uint32_t j = 0; j < kGroup; ++j) {
-                const uint32_t e = g + j;
-                if (old2[j] > (span[e] & 0xFFFFu)) {
-                    bool placed = false;
-                    if (id[e] < M) {
-                        const uint32_t ring = ring0_addr + (id[e] << ring_shift);
-                        const uint32_t arr = span[e] & 0xFFFFu, fin = span[e] >> 16;
-                        for (uint32_t t = 1; t < S && !placed; ++t) {
-                            const uint32_t other = ring + (((my_first + t) & (S - 1u)) << 2);
-                            if (lds_read(other) <= arr) placed = lds_max_rtn(other, fin) <= arr;
-                        }
-                    }
-                    lane_bad = lane_bad || !placed;  // no slot, or an unknown replica (rejected, so not nominal)
-                }
+            for (uint32_t j = 1; j < K; ++j) {
+                cur_at = k == j ? at[j] : cur_at;
+                cur_span = k == j ? span[j] : cur_span;
             }
+            bool placed = false;
+            if (t < S) {
+                const uint32_t hop = ((__builtin_bitreverse32(t) >> 1) >> (31u - slots_log2)) << 2;
+                placed = !span_busy(lds_max_rtn(cur_at ^ hop, cur_span), cur_span);
+            }
+            const bool last = t + 1u >= S;                                   // no other slot of the ring is left
+            lane_bad = lane_bad || (!placed && last);
+            if (placed || last) { open &= ~(1u << k); t = tried + 1u; } else { ++t; }
         }
     }
     return lane_bad;
 }
 
-template <bool kAligned, uint32_t kGroup>
+// Small replica tables: one wavefront per candidate, nothing shared, no barriers.  A block is
+// 512 consecutive requests; lane l holds the eight requests i0 + 128k + 2l + h (k = 0..3,
+// h = 0..1): four 4-byte loads of assignment pairs, and two 16-byte loads from the table
+// stored lane-major.  Step e = 2k + h therefore covers every other request of a 128-request
+// window, close enough to arrival order.
+// The slot a request tries first is the next one of its replica's ring in turn: a counter per
+// replica (LDS, after the rings) is bumped with a returning atomic add, so the requests of
+// one replica within a step get different slots and a slot comes up again only after S more
+// requests of that replica.  The eight counter bumps of a block are issued back to back, then
+// the eight claims (LDS executes them in order, so the steps still see each other's claims).
+template <uint32_t K>
+__device__ __forceinline__ bool cursor_claim(const uint32_t (&id)[K], const uint32_t (&span)[K], uint32_t ring0_addr,
+                                             uint32_t cursor0_addr, uint32_t ring_shift, uint32_t M, uint32_t S,
+                                             uint32_t slots_log2) {
+    uint32_t key[K], turn[K], at[K], old[K];
+#pragma unroll
+    for (uint32_t e = 0; e < K; ++e) {
+        key[e] = min(id[e], M);                                              // unknown replicas: the never-free ring
+        turn[e] = lds_add_rtn(cursor0_addr + (key[e] << 2), 1u);
+    }
+#pragma unroll
+    for (uint32_t e = 0; e < K; ++e) {
+        at[e] = ring0_addr + (key[e] << ring_shift) + ((turn[e] & (S - 1u)) << 2);
+        old[e] = lds_max_rtn(at[e], span[e]);
+    }
+    bool any = false;
+#pragma unroll
+    for (uint32_t e = 0; e < K; ++e) any = any || span_busy(old[e], span[e]);
+    if (__ballot(any) == 0ull) return false;
+    uint32_t open = 0;                                                       // rare: somebody's slot was still taken
+#pragma unroll
+    for (uint32_t e = 0; e < K; ++e) open |= span_busy(old[e], span[e]) ? 1u << e : 0u;
+    return screen_search<K>(span, at, open, 0u, S, slots_log2);
+}
+
+template <bool kAligned>
 __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenParams p, const uint16_t* __restrict__ assign,
                                                                        ap_metrics* __restrict__ out, uint32_t C) {
     extern __shared__ __align__(16) unsigned char lds[];
     const uint32_t lane = threadIdx.x & 63u, w = wave_index();
     const uint32_t M = p.M, R = p.R, S = 1u << p.slots_log2;
     const uint32_t ring_shift = p.slots_log2 + 2u;                           // bytes per ring, log2
-    const uint32_t ring_base_bytes = w * ((M + 2u) << ring_shift);          // this wavefront's M + 2 rings
-    uint32_t* slot = reinterpret_cast<uint32_t*>(lds + ring_base_bytes);
-    const uint32_t my_first = lane & (S - 1u);
-    const uint32_t ring0_addr = lds_address(slot);
-    const uint32_t slot_addr = ring0_addr + my_first * 4u;
+    uint32_t* mine = reinterpret_cast<uint32_t*>(lds + w * p.wave_bytes);    // M + 1 rings, then M + 1 counters
+    const uint32_t n_ring_words = (M + 1u) << p.slots_log2;
+    const uint32_t ring0_addr = lds_address(mine);
+    const uint32_t cursor0_addr = ring0_addr + n_ring_words * 4u;
     const uint32_t n_full = R / kScreenBlock;
+    const bool rings_aligned = (ring0_addr & ((S << 2) - 1u)) == 0u;
 
     for (uint32_t c = blockIdx.x * kScreenWaves + w; c < C; c += gridDim.x * kScreenWaves) {
         const uint16_t* row = assign + (size_t)c * R;
-        for (uint32_t i = lane; i < ((M + 2u) << p.slots_log2); i += kWave)
-            slot[i] = (i >> p.slots_log2) == M ? kNever : 0u;               // ring M: unknown replicas, never free
-        bool bad = false;
+        for (uint32_t i = lane; i < n_ring_words + M + 1u; i += kWave)
+            mine[i] = (i < n_ring_words && (i >> p.slots_log2) == M) ? kNever : 0u;
+        bool bad = !rings_aligned;
 
         // full blocks, two register sets: one is processed while the other is being loaded
         ScreenRegs ga, gb;
-        if (n_full > 0u) screen_fetch<kAligned>(ga, p, row, 0u, lane);
-        for (uint32_t b = 0; b < n_full; b += 2u) {
+        if (n_full > 0u && !bad) screen_fetch<kAligned>(ga, p, row, 0u, lane);
+        for (uint32_t b = 0; b < n_full && !bad; b += 2u) {
             if (b + 1u < n_full) screen_fetch<kAligned>(gb, p, row, (b + 1u) * kScreenBlock, lane);
             {
                 const uint32_t id[8] = {ga.pair[0] & 0xFFFFu, ga.pair[0] >> 16, ga.pair[1] & 0xFFFFu, ga.pair[1] >> 16,
                                         ga.pair[2] & 0xFFFFu, ga.pair[2] >> 16, ga.pair[3] & 0xFFFFu, ga.pair[3] >> 16};
-                bad = __ballot(screen_claim<8, kGroup>(id, ga.span, slot_addr, ring0_addr, ring_shift, M, S, my_first)) != 0ull;
+                bad = __ballot(cursor_claim<8>(id, ga.span, ring0_addr, cursor0_addr, ring_shift, M, S, p.slots_log2)) != 0ull;
             }
             if (bad || b + 1u >= n_full) break;
             if (b + 2u < n_full) screen_fetch<kAligned>(ga, p, row, (b + 2u) * kScreenBlock, lane);
             {
                 const uint32_t id[8] = {gb.pair[0] & 0xFFFFu, gb.pair[0] >> 16, gb.pair[1] & 0xFFFFu, gb.pair[1] >> 16,
                                         gb.pair[2] & 0xFFFFu, gb.pair[2] >> 16, gb.pair[3] & 0xFFFFu, gb.pair[3] >> 16};
-                bad = __ballot(screen_claim<8, kGroup>(id, gb.span, slot_addr, ring0_addr, ring_shift, M, S, my_first)) != 0ull;
+                bad = __ballot(cursor_claim<8>(id, gb.span, ring0_addr, cursor0_addr, ring_shift, M, S, p.slots_log2)) != 0ull;
             }
-            if (bad) break;
         }
 
-        // ragged tail: the same steps with every access guarded; absent requests become no-op probes
+        // ragged tail: the same steps with every access guarded
         const uint32_t i0 = n_full * kScreenBlock;
         if (!bad && i0 < R) {
             uint32_t id[8], span[8];
@@ -470,7 +485,7 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenPara
                 id[e] = in ? (uint32_t)row[r] : 0u;
                 span[e] = in ? p.span_t[i0 + lane * 8u + e] : 0xFFFFu;       // absent: arrives last, finishes at 0
             }
-            bad = __ballot(screen_claim<8, kGroup>(id, span, slot_addr, ring0_addr, ring_shift, M, S, my_first)) != 0ull;
+            bad = __ballot(cursor_claim<8>(id, span, ring0_addr, cursor0_addr, ring_shift, M, S, p.slots_log2)) != 0ull;
         }
 
         // 64-byte record: nominal, or the pending mark
@@ -482,74 +497,48 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenPara
     }
 }
 
-// The same test with the eight wavefronts of a workgroup sharing one candidate, used when the
-// rings of one candidate are large: it divides the LDS held per wavefront by eight, so that
-// enough wavefronts are resident to hide the LDS and memory latency.  A block is 1024
-// consecutive requests; wavefront j takes the two steps 128j + 2l + h of it (one 4-byte load of
-// an assignment pair and one 8-byte table load per lane), all eight claim from one set of
-// rings, and a barrier per block keeps them within the same 1024 requests.
-//
-// Slot words here hold the whole span word of the last claimant (finish tick << 16 | arrival
-// tick): the maximum is still ordered by finish tick, and the test "old finish <= my arrival"
-// compares two 16-bit halves, so no field has to be extracted.
+// Large replica tables: the eight wavefronts of a workgroup share one candidate, which divides
+// the LDS held per wavefront by eight, so that enough wavefronts are resident to hide the LDS
+// and memory latency.  A block is 1024 consecutive requests; wavefront j takes the two steps
+// 128j + 2l + h of it (one 4-byte load of an assignment pair and one 8-byte table load per
+// lane), all eight claim from one set of rings, and a barrier per block keeps them within the
+// same 1024 requests.  Here lane l tries slot l mod S of the ring first (no counters: with
+// eight wavefronts taking turns at random a counter would not keep neighbours apart).
 //
 // Eight wavefronts work on a block in no particular order, and a request that probes a slot
 // after a later request has claimed it loses although it need not (a few percent do).  A
 // request that lost goes straight to the slot half a ring away, in the same instruction in
 // which the lanes that won "probe" the spare ring with a zero (which changes nothing and cannot
 // lose), so the common case has no branch.  What is left - requests that lost twice - goes
-// round by round, every such lane trying the next slot of one open request per round, until
-// each has a slot or has tried the whole ring.
+// through screen_search.
 constexpr uint32_t kWideWaves = 8;
 constexpr uint32_t kWideThreads = kWideWaves * kWave;
 constexpr uint32_t kWideBlock = kWideWaves * 128u;
 constexpr uint32_t kWideMaxSlots = 64;
-constexpr uint32_t kWideLdsBytes = 32768;         // slot state of the one candidate a workgroup holds
-
-__device__ __forceinline__ bool span_busy(uint32_t old, uint32_t span) { return (old >> 16) > (span & 0xFFFFu); }
+constexpr uint32_t kWideLdsBytes = 32768;         // rings of the M real replicas of the one candidate a workgroup holds
 
 // Resolve the K first probes of a lane (`old[k]` came back from slot `at[k]` for span word
-// `span[k]`): second probe half a ring away for those that lost, then the rounds.  Returns
+// `span[k]`): second probe half a ring away for those that lost, then the search.  Returns
 // true if some request found no slot in its whole ring.
 template <uint32_t K>
 __device__ __forceinline__ bool wide_resolve(const uint32_t (&span)[K], const uint32_t (&at)[K],
                                              const uint32_t (&old)[K], uint32_t spare_addr, uint32_t S,
                                              uint32_t slots_log2) {
     const uint32_t half = (S >> 1) << 2;
-    uint32_t o2[K];
+    uint32_t old2[K];
 #pragma unroll
     for (uint32_t k = 0; k < K; ++k) {
         const bool lost = span_busy(old[k], span[k]);
-        o2[k] = lds_max_rtn(lost ? at[k] ^ half : spare_addr, lost ? span[k] : 0u);
+        old2[k] = lds_max_rtn(lost ? at[k] ^ half : spare_addr, lost ? span[k] : 0u);
     }
     bool any = false;
 #pragma unroll
-    for (uint32_t k = 0; k < K; ++k) any = any || span_busy(o2[k], span[k]);
-    bool lane_bad = false;
-    if (__ballot(any) != 0ull) {
-        uint32_t open = 0;
+    for (uint32_t k = 0; k < K; ++k) any = any || span_busy(old2[k], span[k]);
+    if (__ballot(any) == 0ull) return false;
+    uint32_t open = 0;                                                       // rare: somebody lost twice
 #pragma unroll
-        for (uint32_t k = 0; k < K; ++k) open |= span_busy(o2[k], span[k]) ? 1u << k : 0u;
-        uint32_t t = 2u;                                                     // next alternative of the request in hand
-        while (__ballot(open != 0u) != 0ull) {
-            if (open != 0u) {
-                const uint32_t k = 31u - (uint32_t)__clz(open);
-                uint32_t cur_at = at[0], cur_span = span[0];
-#pragma unroll
-                for (uint32_t j = 1; j < K; ++j) {
-                    cur_at = k == j ? at[j] : cur_at;
-                    cur_span = k == j ? span[j] : cur_span;
-                }
-                // alternatives in bit-reversed order: half a ring away (done), a quarter, three quarters, ...
-                const uint32_t hop = ((__builtin_bitreverse32(t) >> 1) >> (31u - slots_log2)) << 2;
-                const bool placed = !span_busy(lds_max_rtn(cur_at ^ hop, cur_span), cur_span);
-                const bool last = t + 1u >= S;                               // that was the last other slot of the ring
-                lane_bad = lane_bad || (!placed && last);
-                if (placed || last) { open &= ~(1u << k); t = 2u; } else { ++t; }
-            }
-        }
-    }
-    return lane_bad;
+    for (uint32_t k = 0; k < K; ++k) open |= span_busy(old2[k], span[k]) ? 1u << k : 0u;
+    return screen_search<K>(span, at, open, 1u, S, slots_log2);
 }
 
 template <bool kAligned>
@@ -1195,8 +1184,7 @@ struct ap_workload {
     ScreenParams screen_params{};
     uint32_t lds_bytes = 0;
     uint32_t screen_lds_bytes = 0;
-    uint32_t screen_group = 1;        // steps whose first probes are issued together: 1, 2, 4 or 8
-    bool screen_wide = false;         // four wavefronts per candidate
+    bool screen_wide = false;         // eight wavefronts per candidate (large replica tables)
     uint32_t screen_wide_lds_bytes = 0;
     uint32_t max_grid = 0;
     uint32_t n_cu = 0;
@@ -1498,10 +1486,6 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
     for (const DevReplica& d : dev) always_on = always_on && d.t_on == 0u && d.t_off == kNever;
     w->screen = always_on && kinds.size() == 1;
     if (w->screen) {
-        // screening slots per replica: a power of two, at most B, sized so that one
-        // candidate's slot state stays within kScreenLdsPerWave bytes of LDS
-        uint32_t S_log2 = 0;
-        while ((2u << S_log2) <= std::min(B, kScreenMaxSlots) && M * (2u << S_log2) * 4u <= kScreenLdsPerWave) ++S_log2;
         ScreenParams sp{};
         sp.span = w->d_span;
         sp.span_t = w->d_span_t;
@@ -1511,20 +1495,24 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
         sp.nominal = w->d_nominal;
         sp.R = w->R;
         sp.M = M;
-        sp.slots_log2 = S_log2;
-        w->screen_params = sp;
-        // a group of g steps sends about 64 g / M requests to each replica before any retry;
-        // keep that within a quarter of the ring
-        w->screen_group = 1;
-        while (w->screen_group < 8u && 64u * (w->screen_group * 2u) * 4u <= M << S_log2) w->screen_group *= 2u;
-        w->screen_wide = w->screen_group == 8u;          // exactly the candidates with large rings
+        // Screening slots per replica: a power of two, at most B.  One wavefront per candidate as
+        // long as that wavefront's slot state (rings and counters of M + 1 replicas) stays small
+        // enough for many wavefronts per compute unit with a useful number of slots; otherwise
+        // the eight-wavefront kernel, whose workgroup holds one candidate's rings.
+        const uint32_t want = std::min(B, kScreenMaxSlots);
+        uint32_t S_log2 = 0;
+        while ((2u << S_log2) <= want && (M + 1u) * ((2u << S_log2) + 1u) * 4u <= kScreenLdsPerWave) ++S_log2;
+        w->screen_wide = (1u << S_log2) < std::min(want, kScreenMinSlots);
         if (w->screen_wide) {
-            // one candidate per workgroup: room for more slots per replica
+            S_log2 = 0;
             while ((2u << S_log2) <= std::min(B, kWideMaxSlots) && M * (2u << S_log2) * 4u <= kWideLdsBytes) ++S_log2;
-            w->screen_params.slots_log2 = S_log2;
         }
+        sp.slots_log2 = S_log2;
+        const uint32_t ring_bytes = 4u << S_log2;
+        sp.wave_bytes = ((M + 1u) * (ring_bytes + 4u) + ring_bytes - 1u) / ring_bytes * ring_bytes;
+        w->screen_params = sp;
         w->screen_wide_lds_bytes = (((M + 2u) << S_log2) + 4u) * 4u;
-        w->screen_lds_bytes = kScreenWaves * ((M + 2u) << S_log2) * 4u;      // M rings, one for unknown ids, a spare
+        w->screen_lds_bytes = kScreenWaves * sp.wave_bytes;
         hipLaunchKernelGGL(hist16 ? k_nominal_metrics<true> : k_nominal_metrics<false>, dim3(1), dim3(kThreads),
                            reduce_lds, nullptr, w->reduce_eval, w->d_span, w->d_span_t, tick_shift, w->d_nominal);
         if (hipGetLastError() != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
@@ -1547,20 +1535,13 @@ ap_status ap_eval_candidates(const ap_workload* w, const uint16_t* d_assign, uin
         const uint32_t blocks = std::min((C + kScreenWaves - 1u) / kScreenWaves, w->n_cu * 8u);
         // rows start on 4-byte boundaries when R is even and the batch itself does
         const bool aligned = (w->R % 2u == 0u) && (reinterpret_cast<uintptr_t>(d_assign) % 4u == 0u);
-        void (*kernel)(ScreenParams, const uint16_t*, ap_metrics*, uint32_t) = nullptr;
         if (w->screen_wide) {
-            kernel = aligned ? k_screen_candidates_wide<true> : k_screen_candidates_wide<false>;
-            hipLaunchKernelGGL(kernel, dim3(std::min(C, w->n_cu * 8u)), dim3(kWideThreads), w->screen_wide_lds_bytes,
-                               stream, w->screen_params, d_assign, d_out, C);
+            hipLaunchKernelGGL(aligned ? k_screen_candidates_wide<true> : k_screen_candidates_wide<false>,
+                               dim3(std::min(C, w->n_cu * 8u)), dim3(kWideThreads), w->screen_wide_lds_bytes, stream,
+                               w->screen_params, d_assign, d_out, C);
         } else {
-        switch (w->screen_group) {
-            case 8: kernel = aligned ? k_screen_candidates<true, 8> : k_screen_candidates<false, 8>; break;
-            case 4: kernel = aligned ? k_screen_candidates<true, 4> : k_screen_candidates<false, 4>; break;
-            case 2: kernel = aligned ? k_screen_candidates<true, 2> : k_screen_candidates<false, 2>; break;
-            default: kernel = aligned ? k_screen_candidates<true, 1> : k_screen_candidates<false, 1>; break;
-        }
-        hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kScreenThreads), w->screen_lds_bytes, stream, w->screen_params,
-                           d_assign, d_out, C);
+            hipLaunchKernelGGL(aligned ? k_screen_candidates<true> : k_screen_candidates<false>, dim3(blocks),
+                               dim3(kScreenThreads), w->screen_lds_bytes, stream, w->screen_params, d_assign, d_out, C);
         }
         if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
     }
