@@ -91,6 +91,10 @@ def test_crafted_traces(name, n, M, B, gap, C):
     ("saturated", 6000, 8, 8, 100, 8),                 # every candidate fails the screen
     ("tiny_segments", 3000, 2, 2, 30000, 8),
     ("m1000", 40000, 1000, 4, 40, 4),
+    ("b1_light", 5000, 40, 1, 40000, 8),               # a single screening slot per replica
+    ("m1024_b2", 6000, 1024, 2, 300, 6),               # large table, two slots per replica
+    ("m256_b64", 30000, 256, 64, 60, 6),               # large table, 32 slots per replica
+    ("m100_b64", 20000, 100, 64, 30, 6),               # large table, 64 slots per replica, ragged tail
 ])
 def test_homogeneous_always_on_traces_take_the_screening_path(name, n, M, B, gap, C):
     tr = _mk(n, M, B, gap, seed=n + 13, coef=[STD] * M)
@@ -117,7 +121,8 @@ def test_screening_with_invalid_ids_and_unaligned_batch_pointer():
         assert_same(to_records(d_out), want, "unaligned batch")
 
 
-@pytest.mark.parametrize("n,M,B", [(4096 + 700, 8, 16), (8192 + 300, 128, 64)])
+@pytest.mark.parametrize("n,M,B", [(4096 + 700, 8, 16), (8192 + 300, 128, 64), (5000, 1024, 2), (6000, 64, 64),
+                                   (5000, 200, 64)])
 def test_unknown_ids_in_otherwise_contention_free_candidates(n, M, B):
     """Light load, identical replicas: nobody waits, so the shortcut for contention-free candidates decides
     every row; a single unknown replica id anywhere in a row (first block, middle, ragged tail; the id just
