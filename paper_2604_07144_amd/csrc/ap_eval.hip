@@ -677,10 +677,12 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
     unsigned long long* acc64 = reinterpret_cast<unsigned long long*>(lds + p.off_misc);   // e2e, ttft, tpot
     uint32_t* acc32 = reinterpret_cast<uint32_t*>(lds + p.off_misc + 24);     // makespan, slo_ok, n_rej, p99 bins[3]
     uint32_t* wtot = reinterpret_cast<uint32_t*>(lds + p.off_misc + 64);      // [3][kWaves] scan carries
+    uint32_t* next_m = reinterpret_cast<uint32_t*>(lds + p.off_misc + 48);    // next replica nobody has replayed yet
 
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
     const uint32_t w = wave_index();
     const uint32_t R = p.R, M = p.M, B = p.B, M1 = p.M + 1u;
+    const uint32_t grab = max(1u, M / (8u * kWaves));  // replicas a wavefront takes at a time
     for (uint32_t m = tid; m <= M; m += kThreads) t_close[m] = m < M ? p.rep[m].t_off : 0u;
     const uint32_t per_wave = p.chunk / kWaves;       // multiple of 64
     const uint32_t groups = per_wave / kWave;         // <= kMaxGroups
@@ -775,10 +777,19 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
                     n_rej += 1u;        // no such replica, or it left before the request arrived
                 }
             }
+            if (tid == 0) *next_m = 0u;
             __syncthreads();
 
             // ---- (4)+(5) replay: one wavefront per replica, lanes = slots / requests ------
-            for (uint32_t m = w; m < M; m += kWaves) {
+            // Queue lengths differ a lot between replicas (a replica that has just come up has
+            // its whole backlog to serve one by one), so the wavefronts take replicas from a
+            // shared counter instead of a fixed share.
+            for (;;) {
+                uint32_t m_first = 0;
+                if (lane == 0) m_first = atomicAdd(next_m, grab);
+                m_first = (uint32_t)__builtin_amdgcn_readfirstlane((int)m_first);
+                if (m_first >= M) break;
+            for (uint32_t m = m_first; m < min(m_first + grab, M); ++m) {
                 const uint32_t qs = qstart[m];
                 const uint32_t qn = qstart[m + 1] - qs;
                 if (qn == 0) continue;
@@ -848,6 +859,7 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
                 }
                 if (lane < B) slots[m * B + lane] = S;
                 if (lane == 0) sorted[m] = in_order ? 1u : 0u;
+            }
             }
             __syncthreads();
         }
