@@ -830,16 +830,27 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
                         } else {
                             if (!in_order) S = wave_sort_ascending(S, lane);
                             in_order = true;
-                            uint32_t j = 0;
-                            for (; j < n_open; ++j) {
-                                const uint32_t u = (uint32_t)__builtin_amdgcn_readfirstlane((int)S);
-                                const uint32_t st = max((uint32_t)__builtin_amdgcn_readlane((int)ready, (int)j), u);
-                                if (st >= rp.t_off) break;
-                                const uint32_t fj = st + (uint32_t)__builtin_amdgcn_readlane((int)svc, (int)j);
-                                S = min(wave_shift_down(S, kNever), max(S, fj));
-                                if (lane == j) start = st;
+                            // The loop itself does not look at t_off.  Starts do not decrease along
+                            // a queue, so the requests that would start at or after t_off are a
+                            // suffix of the block: if there are any (at most once per replica, when
+                            // its window closes), the slot times are put back and only the served
+                            // prefix is run again.
+                            const uint32_t S_before = S;
+                            uint32_t n_run = n_open;
+                            for (;;) {
+                                for (uint32_t j = 0; j < n_run; ++j) {
+                                    const uint32_t u = (uint32_t)__builtin_amdgcn_readfirstlane((int)S);
+                                    const uint32_t st = max((uint32_t)__builtin_amdgcn_readlane((int)ready, (int)j), u);
+                                    const uint32_t fj = st + (uint32_t)__builtin_amdgcn_readlane((int)svc, (int)j);
+                                    S = min(wave_shift_down(S, kNever), max(S, fj));
+                                    if (lane == j) start = st;
+                                }
+                                const uint32_t n_in_time = __popcll(__ballot(lane < n_run && start < rp.t_off));
+                                if (n_in_time == n_run) break;
+                                S = S_before;
+                                n_run = n_in_time;
                             }
-                            n_served = j;
+                            n_served = n_run;
                         }
                     }
                     if (lane < n_served) {
