@@ -126,6 +126,11 @@ __device__ __forceinline__ uint32_t wave_shift_down(uint32_t v, uint32_t last) {
     return (uint32_t)__builtin_amdgcn_update_dpp((int)last, (int)v, 0x130 /* wave_shl:1 */, 0xF, 0xF, false);
 }
 
+// lane i takes lane i - 1's value; lane 0 takes `first`
+__device__ __forceinline__ uint32_t wave_shift_up(uint32_t v, uint32_t first) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)first, (int)v, 0x138 /* wave_shr:1 */, 0xF, 0xF, false);
+}
+
 // The three 4096-bin histograms of a candidate in LDS.  When R < 65536 no count can exceed 16
 // bits, so two bins share a 32-bit word (half the LDS, half the clearing and scanning).
 template <bool kHist16>
@@ -835,16 +840,27 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
                             // suffix of the block: if there are any (at most once per replica, when
                             // its window closes), the slot times are put back and only the served
                             // prefix is run again.
+                            // Start times are pushed into a vector from lane 0 (cheaper than writing
+                            // lane j), so they come out in reverse order and are turned round after.
                             const uint32_t S_before = S;
                             uint32_t n_run = n_open;
                             for (;;) {
-                                for (uint32_t j = 0; j < n_run; ++j) {
+                                uint32_t pushed = 0;
+                                auto step = [&](uint32_t j) {
                                     const uint32_t u = (uint32_t)__builtin_amdgcn_readfirstlane((int)S);
                                     const uint32_t st = max((uint32_t)__builtin_amdgcn_readlane((int)ready, (int)j), u);
                                     const uint32_t fj = st + (uint32_t)__builtin_amdgcn_readlane((int)svc, (int)j);
                                     S = min(wave_shift_down(S, kNever), max(S, fj));
-                                    if (lane == j) start = st;
+                                    pushed = wave_shift_up(pushed, st);
+                                };
+                                uint32_t j = 0;
+                                for (; j + 2u <= n_run; j += 2u) {
+                                    step(j);
+                                    step(j + 1u);
                                 }
+                                if (j < n_run) step(j);
+                                const uint32_t mine = (uint32_t)__builtin_amdgcn_ds_bpermute((int)((n_run - 1u - lane) << 2), (int)pushed);
+                                if (lane < n_run) start = mine;
                                 const uint32_t n_in_time = __popcll(__ballot(lane < n_run && start < rp.t_off));
                                 if (n_in_time == n_run) break;
                                 S = S_before;
