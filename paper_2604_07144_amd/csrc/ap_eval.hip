@@ -1390,11 +1390,11 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
     p.B = B;
     // No bin can count more than R requests, so below 65536 requests two bins share a word.
     const bool hist16 = w->R < 65536u;
-    // A chunk should hand each replica about 48 requests, so that the 64-lane blocks of the
+    // A chunk should hand each replica about 56 requests, so that the 64-lane blocks of the
     // replay are mostly full and rarely spill into a second block; more than that only costs
     // LDS.  Prefer a size that lets two workgroups share a compute unit (they cover each
     // other's barriers); otherwise take the largest chunk one workgroup can hold.
-    const uint32_t want = std::min(kMaxChunk, std::max(2u * kThreads, align_up(48u * M, kThreads)));
+    const uint32_t want = std::min(kMaxChunk, std::max(2u * kThreads, align_up(56u * M, kThreads)));
     uint32_t bytes = 0, chunk = 0;
     for (uint32_t budget : {(uint32_t)lds_cap / 2u, (uint32_t)lds_cap}) {
         const uint32_t smallest = budget == (uint32_t)lds_cap ? kThreads : std::max(kThreads, want / 2u);
