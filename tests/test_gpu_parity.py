@@ -183,6 +183,32 @@ def test_lengths_beyond_16_bits_and_coarse_ticks():
     both(mixed, rows, "long lengths, two replica types (replayed)")
 
 
+@pytest.mark.parametrize("seed", range(40))
+def test_random_shapes_against_the_oracle(seed):
+    """Shapes, loads and replica tables drawn at random within the documented limits: whichever kernels the
+    library's plan picks for them, every record must equal the oracle's."""
+    rng = np.random.default_rng(1000 + seed)
+    n = int(rng.choice([1, 7, 63, 64, 65, 500, 511, 513, 1023, 1025, 3000, 4097, 9000]))
+    M = int(rng.choice([1, 2, 3, 5, 8, 13, 20, 33, 64, 100, 128, 257, 600, 1024]))
+    B = int(rng.choice([1, 2, 3, 7, 8, 16, 31, 32, 33, 48, 64]))
+    gap = int(10 ** rng.uniform(0.5, 4.7))                      # 3 us .. 50 ms between arrivals
+    homogeneous = bool(rng.integers(0, 2))
+    windows = (not homogeneous) and bool(rng.integers(0, 2))
+    t_on = t_off = None
+    if windows:
+        span = max(1, n * gap // 2)
+        xy = rng.integers(0, span + 1, size=(M, 2)) + 1_000_000_007
+        t_on, t_off = xy.min(1).astype(np.uint64), xy.max(1).astype(np.uint64)
+    tr = _mk(n, M, B, gap, seed=seed, coef=[FAST] * M if homogeneous else None, t_on=t_on, t_off=t_off,
+             ties=bool(rng.integers(0, 2)), penalty_us=int(rng.choice([1, 5_000_000, 3_600_000_000])),
+             slo_ttft_us=int(rng.choice([3_000, 500_000])), slo_tpot_us=int(rng.choice([20, 50_000])))
+    C = int(rng.integers(1, 7))
+    rows = _rows(C, n, M + int(rng.integers(0, 3)), seed=seed + 7)       # sometimes a few unknown ids
+    if C > 1:
+        rows[1] = np.arange(n) % M                                      # the most even candidate
+    both(tr, rows, f"random shape n={n} M={M} B={B} gap={gap} homogeneous={homogeneous} windows={windows}")
+
+
 def test_all_requests_on_one_replica_and_empty_replicas():
     tr = _mk(5000, 9, 16, 200, seed=3)
     rows = np.zeros((4, 5000), np.uint16)
