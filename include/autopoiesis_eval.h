@@ -119,8 +119,10 @@ ap_status ap_costmodel_set(ap_workload *w, const ap_replica *replicas, uint32_t 
  *   d_out    : DEVICE pointer to C ap_metrics records (8-byte aligned); only these are written.
  *   hip_stream : a hipStream_t passed as void* (NULL = the default stream).
  * Asynchronous: kernels are enqueued on hip_stream and the call returns without waiting.
- * It allocates nothing.  One evaluation per workload may be in flight at a time.
- * C == 0 is a no-op.  Errors: AP_ERR_INVALID (null pointers), AP_ERR_STATE, AP_ERR_DEVICE. */
+ * It allocates nothing, copies nothing and clears nothing outside its kernels, so the call may be
+ * captured into a HIP graph (stream capture on hip_stream) and replayed as long as the workload,
+ * its cost model and both buffers stay as they were.  One evaluation per workload may be in
+ * flight at a time.  C == 0 is a no-op.  Errors: AP_ERR_INVALID (null pointers), AP_ERR_STATE, AP_ERR_DEVICE. */
 ap_status ap_eval_candidates(const ap_workload *w, const uint16_t *d_assign, uint32_t C, ap_metrics *d_out,
                              void *hip_stream);
 

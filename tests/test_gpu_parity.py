@@ -320,6 +320,39 @@ def test_error_paths():
         binding.ap_workload_destroy(h)
 
 
+# ------------------------------------------------------------------ stream capture
+@pytest.mark.parametrize("name,n,M,B,gap,homogeneous", [
+    ("screen_then_replay", 8192, 16, 8, 1500, True),      # some candidates pass the screen, the others are replayed
+    ("replay", 5000, 12, 8, 300, False),
+    ("three_kernels", 20000, 1024, 64, 20, False),        # the large-table path: several launches per call
+])
+def test_eval_captured_in_a_graph_and_replayed(name, n, M, B, gap, homogeneous):
+    """ap_eval_candidates allocates nothing and only launches kernels on the caller's stream, so a caller may
+    capture it in a graph.  The graph is replayed several times with new assignments written into the same
+    buffers in between (ordinary eager copies and synchronisations); every replay must equal the oracle."""
+    tr = _mk(n, M, B, gap, seed=n + 3, coef=[STD] * M if homogeneous else None)
+    C = 10
+    orc = oracle_for(tr)
+    with GpuWorkload(tr) as g:
+        d_assign = torch.zeros((C, n), dtype=torch.int16, device="cuda")
+        d_out = torch.full((C, 8), -1, dtype=torch.int64, device="cuda")
+        g.eval_device(d_assign, d_out)                                   # eager warm-up call
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):                                    # capture on torch's capture stream
+            g.eval_device(d_assign, d_out)
+        for it in range(4):
+            rows = _rows(C, n, M + (it % 2), seed=100 * it + M)          # odd rounds carry a few unknown ids
+            rows[0] = np.arange(n) % M
+            d_assign.copy_(torch.from_numpy(rows.view(np.int16)).cuda())
+            d_out.fill_(-1)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert_same(to_records(d_out), orc.eval_batch(rows, nthreads=8), f"{name}: replay {it}")
+            assert_same(g.eval(rows), to_records(d_out), f"{name}: eager call after replay {it}")
+
+
 # ------------------------------------------------------------------ the five configurations
 @pytest.mark.parametrize("cfg", [0, 1])
 def test_small_configurations_every_row(cfg):
