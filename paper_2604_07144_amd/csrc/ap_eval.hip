@@ -700,64 +700,91 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
         hist_clear<kHist16>(hist);
         for (uint32_t i = tid; i < M * B; i += kThreads) slots[i] = 0u;
         for (uint32_t i = tid; i < M; i += kThreads) sorted[i] = 1u;       // all zero is sorted
+        for (uint32_t i = tid; i < kWaves * M1; i += kThreads) cnt[i] = 0u;
         if (tid < 16u) reinterpret_cast<uint32_t*>(acc64)[tid] = 0u;
         unsigned long long s_e2e = 0, s_ttft = 0, s_tpot = 0;
         uint32_t last_fin = 0, n_ok = 0, n_rej = 0;
         __syncthreads();
 
-        for (uint32_t r0 = 0; r0 < R; r0 += p.chunk) {
-            const uint32_t n = min(p.chunk, R - r0);
-
-            // ---- stage the chunk of the trace; read this wavefront's assignments -----------
-            for (uint32_t i = tid; i < n; i += kThreads) {
-                c_arr[i] = p.arrival[r0 + i];
-                c_prompt[i] = (len_t)p.prompt[r0 + i];
-                c_out[i] = (len_t)p.outlen[r0 + i];
-            }
-            for (uint32_t i = tid; i < kWaves * M1; i += kThreads) cnt[i] = 0u;
-            uint32_t key[kMaxGroups];
+        // Each thread owns the same positions of every chunk: position w * per_wave + 64 g + lane
+        // for g < groups.  Their assignment ids and arrival times are loaded one chunk ahead.
+        uint32_t key[kMaxGroups], karr[kMaxGroups];
+        auto load_keys = [&](uint32_t r0) {
+            const uint32_t n = r0 < R ? min(p.chunk, R - r0) : 0u;
 #pragma unroll
             for (uint32_t g = 0; g < kMaxGroups; ++g) {
-                uint32_t idx = w * per_wave + g * kWave + lane;
-                key[g] = (g < groups && idx < n) ? min((uint32_t)row[r0 + idx], M) : kNoKey;
+                const uint32_t idx = w * per_wave + g * kWave + lane;
+                const bool in = g < groups && idx < n;
+                key[g] = in ? (uint32_t)row[r0 + idx] : kNoKey;
+                karr[g] = in ? p.arrival[r0 + idx] : 0u;
             }
-            __syncthreads();
-            // a request that arrives when its replica is already gone can never start: reject it
-            // here (key M, like an unknown replica) instead of queueing it
+        };
+        load_keys(0u);
+
+        for (uint32_t r0 = 0; r0 < R; r0 += p.chunk) {
+            // ---- stage the chunk of the trace (lengths are written to LDS after the scatter) -
+            uint32_t kprompt[kMaxGroups], kout[kMaxGroups];
 #pragma unroll
             for (uint32_t g = 0; g < kMaxGroups; ++g) {
                 if (key[g] == kNoKey) continue;
                 const uint32_t idx = w * per_wave + g * kWave + lane;
-                if (c_arr[idx] >= t_close[key[g]]) key[g] = M;
+                kprompt[g] = p.prompt[r0 + idx];
+                kout[g] = p.outlen[r0 + idx];
+                c_arr[idx] = karr[g];
+                // a request that arrives when its replica is already gone can never start: reject it
+                // here (key M, like an unknown replica) instead of queueing it
+                const uint32_t k = min(key[g], M);
+                key[g] = karr[g] >= t_close[k] ? M : k;
             }
 
-            // ---- (1) per-wavefront replica histogram ---------------------------------------
+            // ---- (1) per-wavefront replica histogram (cnt was cleared during the last replay) --
 #pragma unroll
             for (uint32_t g = 0; g < kMaxGroups; ++g)
                 if (key[g] != kNoKey) atomicAdd(&cnt[w * M1 + key[g]], 1u);
             __syncthreads();
 
             // ---- (2) offsets: down the wavefronts per replica, then across replicas --------
-            for (uint32_t m = tid; m <= M; m += kThreads) {
-                uint32_t run = 0;
-                for (uint32_t ww = 0; ww < kWaves; ++ww) {
-                    uint32_t t = cnt[ww * M1 + m];
-                    cnt[ww * M1 + m] = run;
-                    run += t;
+            if (M1 <= 2u * kWave) {                   // few replicas: one wavefront does both
+                if (w == 0) {
+                    uint32_t carry = 0;
+                    for (uint32_t base = 0; base <= M; base += kWave) {
+                        const uint32_t m = base + lane;
+                        uint32_t run = 0;
+                        if (m <= M) {
+                            for (uint32_t ww = 0; ww < kWaves; ++ww) {
+                                const uint32_t t = cnt[ww * M1 + m];
+                                cnt[ww * M1 + m] = run;
+                                run += t;
+                            }
+                        }
+                        const uint32_t incl = wave_inclusive_scan(run, lane);
+                        if (m <= M) qstart[m] = carry + incl - run;
+                        carry += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+                    }
+                    if (lane == 0) qstart[M1] = carry;
                 }
-                qstart[m] = run;
-            }
-            __syncthreads();
-            if (w == 0) {
-                uint32_t carry = 0;
-                for (uint32_t base = 0; base <= M; base += kWave) {
-                    uint32_t m = base + lane;
-                    uint32_t v = m <= M ? qstart[m] : 0u;
-                    uint32_t incl = wave_inclusive_scan(v, lane);
-                    if (m <= M) qstart[m] = carry + incl - v;
-                    carry += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+            } else {
+                for (uint32_t m = tid; m <= M; m += kThreads) {
+                    uint32_t run = 0;
+                    for (uint32_t ww = 0; ww < kWaves; ++ww) {
+                        uint32_t t = cnt[ww * M1 + m];
+                        cnt[ww * M1 + m] = run;
+                        run += t;
+                    }
+                    qstart[m] = run;
                 }
-                if (lane == 0) qstart[M1] = carry;
+                __syncthreads();
+                if (w == 0) {
+                    uint32_t carry = 0;
+                    for (uint32_t base = 0; base <= M; base += kWave) {
+                        uint32_t m = base + lane;
+                        uint32_t v = m <= M ? qstart[m] : 0u;
+                        uint32_t incl = wave_inclusive_scan(v, lane);
+                        if (m <= M) qstart[m] = carry + incl - v;
+                        carry += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+                    }
+                    if (lane == 0) qstart[M1] = carry;
+                }
             }
             __syncthreads();
 
@@ -781,9 +808,17 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
                 } else if (k == M) {
                     n_rej += 1u;        // no such replica, or it left before the request arrived
                 }
+                if (k != kNoKey) {
+                    const uint32_t idx = w * per_wave + g * kWave + lane;
+                    c_prompt[idx] = (len_t)kprompt[g];
+                    c_out[idx] = (len_t)kout[g];
+                }
             }
             if (tid == 0) *next_m = 0u;
             __syncthreads();
+            // the next chunk's assignments and arrival times arrive while this one is replayed
+            load_keys(r0 + p.chunk);
+            for (uint32_t i = tid; i < kWaves * M1; i += kThreads) cnt[i] = 0u;
 
             // ---- (4)+(5) replay: one wavefront per replica, lanes = slots / requests ------
             // Queue lengths differ a lot between replicas (a replica that has just come up has
