@@ -32,8 +32,8 @@ KERNEL_SOURCE = os.path.join(ROOT, "paper_2604_07144_amd", "csrc", "ap_eval.hip"
 # Keyed by configuration; valid only for the kernel source whose hash is recorded with it.
 MEASURED_TRAFFIC = {
     # cfg: (sha256 of the kernel source when measured, bytes per call)
-    4: ("ecacc661b372a80cc19cda0bb7053f79b00e14e40f77982caa36c5a6f248da4d", 4338613701),
-    3: ("ecacc661b372a80cc19cda0bb7053f79b00e14e40f77982caa36c5a6f248da4d", 546254169),
+    4: ("0d021da5b75f5b40890a9c3288ba0673381670a0c0dc9f871e9b7ef10d812c7b", 4338931271),
+    3: ("0d021da5b75f5b40890a9c3288ba0673381670a0c0dc9f871e9b7ef10d812c7b", 548484719),
 }
 
 
