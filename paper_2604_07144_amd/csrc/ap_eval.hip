@@ -693,6 +693,16 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
     const uint32_t groups = per_wave / kWave;         // <= kMaxGroups
     const unsigned long long lanes_below = (1ull << lane) - 1ull;
 
+    // After screening, most workgroups have nothing left to do: look at all of this workgroup's
+    // records at once (one per thread) and leave if none carries the mark.
+    if (only_pending) {
+        int any = 0;
+        for (unsigned long long c = (unsigned long long)blockIdx.x + (unsigned long long)tid * gridDim.x; c < C;
+             c += (unsigned long long)kThreads * gridDim.x)
+            any |= is_pending(out[c]) ? 1 : 0;
+        if (__syncthreads_or(any) == 0) return;
+    }
+
     for (uint32_t c = blockIdx.x; c < C; c += gridDim.x) {
         if (only_pending && !is_pending(out[c])) continue;      // same record for every thread: uniform
         const uint16_t* row = assign + (size_t)c * R;
@@ -1261,6 +1271,7 @@ struct ap_workload {
     bool screen_wide = false;         // eight wavefronts per candidate (large replica tables)
     uint32_t screen_wide_lds_bytes = 0;
     uint32_t max_grid = 0;
+    uint32_t resident_grid = 0;       // workgroups of the replay kernel that fit on the device at once
     uint32_t n_cu = 0;
     // three-kernel replay: request records, scratch for one batch of candidates, launch parameters
     uint4* d_req = nullptr;           // [R] {arrival, prompt_len, out_len, 0}
@@ -1494,6 +1505,7 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
     w->hist16 = hist16;
     w->n_cu = (uint32_t)n_cu;
     w->max_grid = (uint32_t)n_cu * 8u;
+    w->resident_grid = (uint32_t)n_cu * std::max(1u, std::min(4u, bytes ? (uint32_t)lds_cap / bytes : 1u));
 
     // ---- three-kernel replay: scratch for one batch of candidates -------------------------
     w->reduce_eval = p;
@@ -1634,7 +1646,9 @@ ap_status ap_eval_candidates(const ap_workload* w, const uint16_t* d_assign, uin
         if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
         return AP_OK;
     }
-    const uint32_t grid = std::min(C, w->max_grid);
+    // After screening, most workgroups only find out that nothing is left for them: as many as can be
+    // resident at once look at all the records together.
+    const uint32_t grid = std::min(C, pending_only ? w->resident_grid : w->max_grid);
     hipLaunchKernelGGL(eval_kernel(w->hist16, w->len16), dim3(grid), dim3(kThreads), w->lds_bytes, stream, w->params,
                        d_assign, d_out, C, pending_only);
     if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
