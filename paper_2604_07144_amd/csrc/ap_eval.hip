@@ -317,11 +317,11 @@ __global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint
 // span word of its last claimant: the maximum is still ordered by finish tick, and the test
 // compares two 16-bit halves, so no field has to be extracted.
 //
-// Two more rings follow the M real ones in a candidate's slot state: ring M takes the requests
+// One more ring follows the M real ones in a candidate's slot state: ring M takes the requests
 // that name an unknown replica and is kept at "never free", so such a request loses every
-// probe and the candidate ends up pending; ring M + 1 (large tables only) is a spare that
-// stays all zero.  The ragged tail passes its absent requests as (replica 0, arrival tick
-// 0xFFFF, finish tick 0): a probe that cannot lose and leaves every finish tick as it was.
+// probe and the candidate ends up pending.  The ragged tail passes its absent requests as
+// (replica 0, arrival tick 0xFFFF, finish tick 0): a probe that cannot lose and leaves every
+// finish tick as it was.
 struct ScreenParams {
     const uint32_t* span;         // [R] in request order: arrival tick | finish tick << 16 (interval rounded outwards)
     const uint32_t* span_t;       // [ceil(R/512)*512] the same words in the order given by screen_table_index
@@ -513,9 +513,8 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenPara
 // Eight wavefronts work on a block in no particular order, and a request that probes a slot
 // after a later request has claimed it loses although it need not (a few percent do).  A
 // request that lost goes straight to the slot half a ring away, in the same instruction in
-// which the lanes that won "probe" the spare ring with a zero (which changes nothing and cannot
-// lose), so the common case has no branch.  What is left - requests that lost twice - goes
-// through screen_search.
+// which the lanes that won send a zero there (which changes nothing), so the common case has
+// no branch.  What is left - requests that lost twice - goes through screen_search.
 constexpr uint32_t kWideWaves = 8;
 constexpr uint32_t kWideThreads = kWideWaves * kWave;
 constexpr uint32_t kWideBlock = kWideWaves * 128u;
@@ -527,22 +526,22 @@ constexpr uint32_t kWideLdsBytes = 32768;         // rings of the M real replica
 // true if some request found no slot in its whole ring.
 template <uint32_t K>
 __device__ __forceinline__ bool wide_resolve(const uint32_t (&span)[K], const uint32_t (&at)[K],
-                                             const uint32_t (&old)[K], uint32_t spare_addr, uint32_t S,
-                                             uint32_t slots_log2) {
+                                             const uint32_t (&old)[K], uint32_t S, uint32_t slots_log2) {
     const uint32_t half = (S >> 1) << 2;
     uint32_t old2[K];
 #pragma unroll
     for (uint32_t k = 0; k < K; ++k) {
         const bool lost = span_busy(old[k], span[k]);
-        old2[k] = lds_max_rtn(lost ? at[k] ^ half : spare_addr, lost ? span[k] : 0u);
+        old2[k] = lds_max_rtn(at[k] ^ half, lost ? span[k] : 0u);             // a zero changes nothing
     }
     bool any = false;
 #pragma unroll
-    for (uint32_t k = 0; k < K; ++k) any = any || span_busy(old2[k], span[k]);
+    for (uint32_t k = 0; k < K; ++k) any = any || (span_busy(old[k], span[k]) && span_busy(old2[k], span[k]));
     if (__ballot(any) == 0ull) return false;
     uint32_t open = 0;                                                       // rare: somebody lost twice
 #pragma unroll
-    for (uint32_t k = 0; k < K; ++k) open |= span_busy(old2[k], span[k]) ? 1u << k : 0u;
+    for (uint32_t k = 0; k < K; ++k)
+        open |= (span_busy(old[k], span[k]) && span_busy(old2[k], span[k])) ? 1u << k : 0u;
     return screen_search<K>(span, at, open, 1u, S, slots_log2);
 }
 
@@ -554,12 +553,11 @@ __global__ __launch_bounds__(kWideThreads) void k_screen_candidates_wide(ScreenP
     const uint32_t tid = threadIdx.x, lane = tid & 63u, j = wave_index();
     const uint32_t M = p.M, R = p.R, S = 1u << p.slots_log2;
     const uint32_t ring_shift = p.slots_log2 + 2u;
-    const uint32_t n_words = (M + 2u) << p.slots_log2;                       // M rings, the unknown-replica ring, a spare
+    const uint32_t n_words = (M + 1u) << p.slots_log2;                       // M rings and the unknown-replica ring
     uint32_t* slot = reinterpret_cast<uint32_t*>(lds);
     uint32_t* flag = slot + n_words;
     const uint32_t ring0_addr = lds_address(slot);
     const uint32_t slot_addr = ring0_addr + (lane & (S - 1u)) * 4u;          // this lane's first choice in replica 0's ring
-    const uint32_t spare_addr = ((M + 1u) << ring_shift) + slot_addr;
     const uint32_t n_full = R / kWideBlock;
     const uint32_t mine = 128u * j + 2u * lane;                              // offset of this lane's pair in a block
     // alternatives are reached by flipping address bits, which needs the rings aligned to their size
@@ -612,7 +610,7 @@ __global__ __launch_bounds__(kWideThreads) void k_screen_candidates_wide(ScreenP
                 fetch(d, min((g + 1u) * kDepth + d, n_full - 1u));           // refill (redundant in the last group)
                 first_probe(ids & 0xFFFFu, sp[0], at[0], old[0]);
                 first_probe(ids >> 16, sp[1], at[1], old[1]);
-                lane_bad = wide_resolve<2>(sp, at, old, spare_addr, S, p.slots_log2) || lane_bad;
+                lane_bad = wide_resolve<2>(sp, at, old, S, p.slots_log2) || lane_bad;
                 if (d + 1u < kDepth) __syncthreads();
             }
             if (__ballot(lane_bad) != 0ull && lane == 0) flag[turn & 1u] = 1u;
@@ -632,7 +630,7 @@ __global__ __launch_bounds__(kWideThreads) void k_screen_candidates_wide(ScreenP
                 sp[h] = in ? p.span[r] : 0xFFFFu;
                 first_probe(in ? (uint32_t)row[r] : 0u, sp[h], at[h], old[h]);
             }
-            const bool lane_bad = wide_resolve<2>(sp, at, old, spare_addr, S, p.slots_log2);
+            const bool lane_bad = wide_resolve<2>(sp, at, old, S, p.slots_log2);
             if (__ballot(lane_bad) != 0ull && lane == 0) flag[turn & 1u] = 1u;
             __syncthreads();
             bad = flag[turn & 1u] != 0u;
@@ -1597,7 +1595,7 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
         const uint32_t ring_bytes = 4u << S_log2;
         sp.wave_bytes = ((M + 1u) * (ring_bytes + 4u) + ring_bytes - 1u) / ring_bytes * ring_bytes;
         w->screen_params = sp;
-        w->screen_wide_lds_bytes = (((M + 2u) << S_log2) + 4u) * 4u;
+        w->screen_wide_lds_bytes = (((M + 1u) << S_log2) + 4u) * 4u;
         w->screen_lds_bytes = kScreenWaves * sp.wave_bytes;
         hipLaunchKernelGGL(hist16 ? k_nominal_metrics<true> : k_nominal_metrics<false>, dim3(1), dim3(kThreads),
                            reduce_lds, nullptr, w->reduce_eval, w->d_span, w->d_span_t, tick_shift, w->d_nominal);
