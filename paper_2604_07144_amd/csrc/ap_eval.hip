@@ -507,7 +507,7 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenPara
 // and memory latency.  A block is 1024 consecutive requests; wavefront j takes the two steps
 // 128j + 2l + h of it (one 4-byte load of an assignment pair and one 8-byte table load per
 // lane), all eight claim from one set of rings, and a barrier per block keeps them within the
-// same 1024 requests.  Here lane l tries slot l mod S of the ring first (no counters: with
+// same 1024 requests.  Here lane l tries slot l mod S/2 of the ring first (no counters: with
 // eight wavefronts taking turns at random a counter would not keep neighbours apart).
 //
 // Eight wavefronts work on a block in no particular order, and a request that probes a slot
@@ -557,7 +557,9 @@ __global__ __launch_bounds__(kWideThreads) void k_screen_candidates_wide(ScreenP
     uint32_t* slot = reinterpret_cast<uint32_t*>(lds);
     uint32_t* flag = slot + n_words;
     const uint32_t ring0_addr = lds_address(slot);
-    const uint32_t slot_addr = ring0_addr + (lane & (S - 1u)) * 4u;          // this lane's first choice in replica 0's ring
+    // first choices come from the lower half of a ring only, which leaves the upper half (where the
+    // second probe goes) to the few requests that lost: they rarely lose there again
+    const uint32_t slot_addr = ring0_addr + (lane & ((S > 1u ? S >> 1 : 1u) - 1u)) * 4u;
     const uint32_t n_full = R / kWideBlock;
     const uint32_t mine = 128u * j + 2u * lane;                              // offset of this lane's pair in a block
     // alternatives are reached by flipping address bits, which needs the rings aligned to their size
