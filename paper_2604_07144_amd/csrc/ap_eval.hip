@@ -253,8 +253,8 @@ __host__ __device__ inline uint32_t screen_table_index(uint32_t r) {
 // shares.
 // One workgroup.
 template <bool kHist16>
-__global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint32_t* __restrict__ span,
-                                                              uint32_t* __restrict__ span_t, uint32_t tick_shift,
+__global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint32_t* span, uint32_t* __restrict__ span_t,
+                                                              uint32_t* __restrict__ pair, uint32_t tick_us,
                                                               ap_metrics* __restrict__ nominal) {
     extern __shared__ __align__(16) unsigned char lds[];
     uint32_t* hist = reinterpret_cast<uint32_t*>(lds);
@@ -275,7 +275,7 @@ __global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint
         const uint32_t e2e = prefill + p.outlen[r] * tpot;
         // service interval in ticks, rounded outwards (arrival down, finish up), 16 bits each
         const uint32_t fin_us = p.arrival[r] + e2e;
-        const uint32_t span_v = (p.arrival[r] >> tick_shift) | (((fin_us + (1u << tick_shift) - 1u) >> tick_shift) << 16);
+        const uint32_t span_v = (p.arrival[r] / tick_us) | ((fin_us ? (fin_us - 1u) / tick_us + 1u : 0u) << 16);
         span[r] = span_v;
         span_t[screen_table_index(r)] = span_v;
         hist_add<kHist16>(hist, 0u, hist_bin_u32(prefill), 1u);
@@ -288,6 +288,18 @@ __global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint
         n_ok += (prefill <= p.slo_ttft && tpot <= p.slo_tpot) ? 1u : 0u;
     }
     finish_candidate<kHist16>(p, hist, acc64, acc32, wtot, s_e2e, s_ttft, s_tpot, last_fin, n_ok, 0u, nominal);
+    // One word per pair of consecutive requests: arrival tick of the first | (finish tick of the
+    // first - that arrival) << 16 | (finish tick of the second - that arrival) << 24.  The host
+    // asks for this table only with a tick for which both differences are below 256.
+    if (pair != nullptr) {
+        __syncthreads();                              // the span words written above, by this workgroup
+        for (uint32_t q = tid; 2u * q < p.R; q += kThreads) {
+            const uint32_t s0 = span[2u * q];
+            const uint32_t s1 = 2u * q + 1u < p.R ? span[2u * q + 1u] : s0;
+            const uint32_t arr = s0 & 0xFFFFu;
+            pair[q] = arr | (((s0 >> 16) - arr) << 16) | (((s1 >> 16) - arr) << 24);
+        }
+    }
 }
 
 // ----------------------------------------------------------------------------------
@@ -325,6 +337,7 @@ __global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint
 struct ScreenParams {
     const uint32_t* span;         // [R] in request order: arrival tick | finish tick << 16 (interval rounded outwards)
     const uint32_t* span_t;       // [ceil(R/512)*512] the same words in the order given by screen_table_index
+    const uint32_t* pair;         // [ceil(R/2)] one word per two requests: arrival tick | two 8-bit tick counts
     const ap_metrics* nominal;
     uint32_t R, M;
     uint32_t slots_log2;          // S = 1 << slots_log2
@@ -512,9 +525,10 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenPara
 //
 // Eight wavefronts work on a block in no particular order, and a request that probes a slot
 // after a later request has claimed it loses although it need not (a few percent do).  A
-// request that lost goes straight to the slot half a ring away, in the same instruction in
-// which the lanes that won send a zero there (which changes nothing), so the common case has
-// no branch.  What is left - requests that lost twice - goes through screen_search.
+// request that lost goes straight to a slot in the other half of the ring, in the same
+// instruction in which the lanes that won send a zero there (which changes nothing), so the
+// common case has no branch.  What is left - requests that lost twice - goes through
+// screen_search.
 constexpr uint32_t kWideWaves = 8;
 constexpr uint32_t kWideThreads = kWideWaves * kWave;
 constexpr uint32_t kWideBlock = kWideWaves * 128u;
@@ -522,17 +536,17 @@ constexpr uint32_t kWideMaxSlots = 64;
 constexpr uint32_t kWideLdsBytes = 32768;         // rings of the M real replicas of the one candidate a workgroup holds
 
 // Resolve the K first probes of a lane (`old[k]` came back from slot `at[k]` for span word
-// `span[k]`): second probe half a ring away for those that lost, then the search.  Returns
-// true if some request found no slot in its whole ring.
+// `span[k]`): second probe `second[k]` bytes further on for those that lost, then the search.
+// Returns true if some request found no slot in its whole ring.
 template <uint32_t K>
 __device__ __forceinline__ bool wide_resolve(const uint32_t (&span)[K], const uint32_t (&at)[K],
-                                             const uint32_t (&old)[K], uint32_t S, uint32_t slots_log2) {
-    const uint32_t half = (S >> 1) << 2;
+                                             const uint32_t (&old)[K], const uint32_t (&second)[K], uint32_t S,
+                                             uint32_t slots_log2) {
     uint32_t old2[K];
 #pragma unroll
     for (uint32_t k = 0; k < K; ++k) {
         const bool lost = span_busy(old[k], span[k]);
-        old2[k] = lds_max_rtn(at[k] ^ half, lost ? span[k] : 0u);             // a zero changes nothing
+        old2[k] = lds_max_rtn(at[k] + second[k], lost ? span[k] : 0u);       // a zero changes nothing
     }
     bool any = false;
 #pragma unroll
@@ -542,10 +556,20 @@ __device__ __forceinline__ bool wide_resolve(const uint32_t (&span)[K], const ui
 #pragma unroll
     for (uint32_t k = 0; k < K; ++k)
         open |= (span_busy(old[k], span[k]) && span_busy(old2[k], span[k])) ? 1u << k : 0u;
-    return screen_search<K>(span, at, open, 1u, S, slots_log2);
+    return screen_search<K>(span, at, open, 0u, S, slots_log2);       // all other slots of the ring, in its usual order
 }
 
-template <bool kAligned>
+// kPacked: the table is read one word per pair of requests (half the bytes of two span words).  The
+// second request of a pair is then treated as arriving with the first, which only widens its
+// interval.  The host allows it when the tick that makes the 8-bit counts fit is not much
+// coarser than the tick the 16-bit fields need.
+__device__ __forceinline__ void unpack_pair(uint32_t word, uint32_t& span0, uint32_t& span1) {
+    const uint32_t arr = word & 0xFFFFu;
+    span0 = ((arr + ((word >> 16) & 0xFFu)) << 16) | arr;
+    span1 = ((arr + (word >> 24)) << 16) | arr;
+}
+
+template <bool kAligned, bool kPacked>
 __global__ __launch_bounds__(kWideThreads) void k_screen_candidates_wide(ScreenParams p,
                                                                           const uint16_t* __restrict__ assign,
                                                                           ap_metrics* __restrict__ out, uint32_t C) {
@@ -557,9 +581,17 @@ __global__ __launch_bounds__(kWideThreads) void k_screen_candidates_wide(ScreenP
     uint32_t* slot = reinterpret_cast<uint32_t*>(lds);
     uint32_t* flag = slot + n_words;
     const uint32_t ring0_addr = lds_address(slot);
-    // first choices come from the lower half of a ring only, which leaves the upper half (where the
-    // second probe goes) to the few requests that lost: they rarely lose there again
-    const uint32_t slot_addr = ring0_addr + (lane & ((S > 1u ? S >> 1 : 1u) - 1u)) * 4u;
+    // First choices come from the lower half of a ring only, which leaves the upper half (where the
+    // second probe goes) to the few requests that lost.  The requests of a block that share a first
+    // choice (same lane modulo S/2: two lanes, eight wavefronts, two steps) are sent to different
+    // slots of the upper half, so that those of them that go to one replica - the likely losers - do
+    // not meet again.
+    const uint32_t lower = (S > 1u ? S >> 1 : 1u) - 1u;                      // mask of a slot index in the lower half
+    const uint32_t slot_addr = ring0_addr + (lane & lower) * 4u;
+    uint32_t second[2];                                                      // from a request's first slot to its second, bytes
+#pragma unroll
+    for (uint32_t h = 0; h < 2u; ++h)
+        second[h] = ((S >> 1) + ((lane + (lane >> 5) + 2u * j + 16u * h) & lower) - (lane & lower)) * 4u;
     const uint32_t n_full = R / kWideBlock;
     const uint32_t mine = 128u * j + 2u * lane;                              // offset of this lane's pair in a block
     // alternatives are reached by flipping address bits, which needs the rings aligned to their size
@@ -588,7 +620,11 @@ __global__ __launch_bounds__(kWideThreads) void k_screen_candidates_wide(ScreenP
             } else {
                 pair[d] = (uint32_t)__builtin_nontemporal_load(at) | ((uint32_t)__builtin_nontemporal_load(at + 1) << 16);
             }
-            span[d] = *reinterpret_cast<const uint2*>(p.span + i0 + mine);
+            if (kPacked) {
+                span[d].x = p.pair[(i0 + mine) >> 1];
+            } else {
+                span[d] = *reinterpret_cast<const uint2*>(p.span + i0 + mine);
+            }
         };
         auto first_probe = [&](uint32_t id, uint32_t sp, uint32_t& at, uint32_t& old) {
             at = (min(id, M) << ring_shift) + slot_addr;                     // unknown replicas: the never-free ring
@@ -607,12 +643,16 @@ __global__ __launch_bounds__(kWideThreads) void k_screen_candidates_wide(ScreenP
             for (uint32_t d = 0; d < kDepth; ++d) {
                 uint32_t sp[2], at[2], old[2];
                 const uint32_t ids = pair[d];
-                sp[0] = span[d].x;
-                sp[1] = span[d].y;
+                if (kPacked) {
+                    unpack_pair(span[d].x, sp[0], sp[1]);
+                } else {
+                    sp[0] = span[d].x;
+                    sp[1] = span[d].y;
+                }
                 fetch(d, min((g + 1u) * kDepth + d, n_full - 1u));           // refill (redundant in the last group)
                 first_probe(ids & 0xFFFFu, sp[0], at[0], old[0]);
                 first_probe(ids >> 16, sp[1], at[1], old[1]);
-                lane_bad = wide_resolve<2>(sp, at, old, S, p.slots_log2) || lane_bad;
+                lane_bad = wide_resolve<2>(sp, at, old, second, S, p.slots_log2) || lane_bad;
                 if (d + 1u < kDepth) __syncthreads();
             }
             if (__ballot(lane_bad) != 0ull && lane == 0) flag[turn & 1u] = 1u;
@@ -629,10 +669,17 @@ __global__ __launch_bounds__(kWideThreads) void k_screen_candidates_wide(ScreenP
             for (uint32_t h = 0; h < 2u; ++h) {
                 const uint32_t r = i0 + mine + h;
                 const bool in = r < R;
-                sp[h] = in ? p.span[r] : 0xFFFFu;
+                sp[h] = 0xFFFFu;
+                if (in && kPacked) {
+                    uint32_t both[2];
+                    unpack_pair(p.pair[r >> 1], both[0], both[1]);
+                    sp[h] = both[h];
+                } else if (in) {
+                    sp[h] = p.span[r];
+                }
                 first_probe(in ? (uint32_t)row[r] : 0u, sp[h], at[h], old[h]);
             }
-            const bool lane_bad = wide_resolve<2>(sp, at, old, S, p.slots_log2);
+            const bool lane_bad = wide_resolve<2>(sp, at, old, second, S, p.slots_log2);
             if (__ballot(lane_bad) != 0ull && lane == 0) flag[turn & 1u] = 1u;
             __syncthreads();
             bad = flag[turn & 1u] != 0u;
@@ -1259,6 +1306,8 @@ struct ap_workload {
     DevReplica* d_rep = nullptr;      // capacity AP_MAX_REPLICAS
     uint32_t* d_span = nullptr;       // [R] contention-free service intervals in ticks, valid when screen is set
     uint32_t* d_span_t = nullptr;     // the same, lane-major for the one-wavefront screening kernel
+    uint32_t* d_pair = nullptr;       // one word per two requests (eight-wavefront screening kernel, when it fits)
+    bool screen_packed = false;       // that kernel reads d_pair instead of d_span
     ap_metrics* d_nominal = nullptr;  // record shared by all contention-free candidates
     bool has_model = false;
     bool screen = false;              // homogeneous, always-on replicas: screening applies
@@ -1349,6 +1398,7 @@ ap_status ap_workload_create(const uint64_t* arrival_us, const int32_t* prompt_l
                         hipMalloc(&w->d_rep, sizeof(DevReplica) * AP_MAX_REPLICAS) != hipSuccess ||
                         hipMalloc(&w->d_span, bytes) != hipSuccess ||
                         hipMalloc(&w->d_span_t, padded) != hipSuccess ||
+                        hipMalloc(&w->d_pair, ((size_t)R + 1u) / 2u * 4u) != hipSuccess ||
                         hipMalloc(&w->d_nominal, sizeof(ap_metrics)) != hipSuccess))
         st = AP_ERR_ALLOC;
     std::vector<uint4> recs;
@@ -1409,6 +1459,8 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
     }
     uint64_t total = latest;
     uint64_t latest_unqueued = 0;      // latest finish if nobody ever waited (arrival + service)
+    uint64_t longest_pair = 0;         // longest time from the arrival of request 2q to the unqueued finish of 2q or 2q+1
+    uint64_t service_sum = 0;
     for (uint32_t r = 0; r < w->R; ++r) {
         const uint64_t prompt = (uint64_t)w->h_prompt[r], outl = (uint64_t)w->h_out[r];
         uint64_t worst = 0;
@@ -1421,7 +1473,9 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
             worst = std::max(worst, svc);
         }
         total += worst;
+        service_sum += worst;
         latest_unqueued = std::max<uint64_t>(latest_unqueued, (uint64_t)w->h_arrival[r] + worst);
+        longest_pair = std::max<uint64_t>(longest_pair, (uint64_t)w->h_arrival[r] + worst - w->h_arrival[r & ~1u]);
         if (total > limit) return AP_ERR_RANGE;
     }
 
@@ -1575,9 +1629,10 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
         ScreenParams sp{};
         sp.span = w->d_span;
         sp.span_t = w->d_span_t;
-        // tick = 2^tick_shift us, the smallest that brings every contention-free finish time below 2^16 ticks
-        uint32_t tick_shift = 0;
-        while (((latest_unqueued >> tick_shift) + 2u) > 0xFFFFu) ++tick_shift;
+        sp.pair = w->d_pair;
+        // the smallest tick that brings every contention-free finish time below 2^16 ticks
+        uint64_t tick_us = std::max<uint64_t>(1u, latest_unqueued / 0xFFFDu);
+        while (latest_unqueued / tick_us + 2u > 0xFFFFu) ++tick_us;
         sp.nominal = w->d_nominal;
         sp.R = w->R;
         sp.M = M;
@@ -1593,6 +1648,14 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
             S_log2 = 0;
             while ((2u << S_log2) <= std::min(B, kWideMaxSlots) && M * (2u << S_log2) * 4u <= kWideLdsBytes) ++S_log2;
         }
+        // The eight-wavefront kernel can read one word per pair of requests if the tick is coarse
+        // enough for the pair's two tick counts to fit 8 bits (count <= longest_pair / tick + 2).
+        // Take that tick when it is not out of proportion: at most twice the other one, or at
+        // most an eighth of the mean service time.
+        const uint64_t tick_packed = std::max<uint64_t>(tick_us, (longest_pair + 252u) / 253u);
+        w->screen_packed = w->screen_wide &&
+                           (tick_packed <= 2u * tick_us || tick_packed * 8u <= service_sum / w->R);
+        if (w->screen_packed) tick_us = tick_packed;
         sp.slots_log2 = S_log2;
         const uint32_t ring_bytes = 4u << S_log2;
         sp.wave_bytes = ((M + 1u) * (ring_bytes + 4u) + ring_bytes - 1u) / ring_bytes * ring_bytes;
@@ -1600,7 +1663,8 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
         w->screen_wide_lds_bytes = (((M + 1u) << S_log2) + 4u) * 4u;
         w->screen_lds_bytes = kScreenWaves * sp.wave_bytes;
         hipLaunchKernelGGL(hist16 ? k_nominal_metrics<true> : k_nominal_metrics<false>, dim3(1), dim3(kThreads),
-                           reduce_lds, nullptr, w->reduce_eval, w->d_span, w->d_span_t, tick_shift, w->d_nominal);
+                           reduce_lds, nullptr, w->reduce_eval, w->d_span, w->d_span_t,
+                           w->screen_packed ? w->d_pair : nullptr, (uint32_t)tick_us, w->d_nominal);
         if (hipGetLastError() != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
             (void)hipGetLastError();
             return AP_ERR_DEVICE;
@@ -1622,9 +1686,11 @@ ap_status ap_eval_candidates(const ap_workload* w, const uint16_t* d_assign, uin
         // rows start on 4-byte boundaries when R is even and the batch itself does
         const bool aligned = (w->R % 2u == 0u) && (reinterpret_cast<uintptr_t>(d_assign) % 4u == 0u);
         if (w->screen_wide) {
-            hipLaunchKernelGGL(aligned ? k_screen_candidates_wide<true> : k_screen_candidates_wide<false>,
-                               dim3(std::min(C, w->n_cu * 8u)), dim3(kWideThreads), w->screen_wide_lds_bytes, stream,
-                               w->screen_params, d_assign, d_out, C);
+            void (*kernel)(ScreenParams, const uint16_t*, ap_metrics*, uint32_t) =
+                w->screen_packed ? (aligned ? k_screen_candidates_wide<true, true> : k_screen_candidates_wide<false, true>)
+                                 : (aligned ? k_screen_candidates_wide<true, false> : k_screen_candidates_wide<false, false>);
+            hipLaunchKernelGGL(kernel, dim3(std::min(C, w->n_cu * 8u)), dim3(kWideThreads), w->screen_wide_lds_bytes,
+                               stream, w->screen_params, d_assign, d_out, C);
         } else {
             hipLaunchKernelGGL(aligned ? k_screen_candidates<true> : k_screen_candidates<false>, dim3(blocks),
                                dim3(kScreenThreads), w->screen_lds_bytes, stream, w->screen_params, d_assign, d_out, C);
@@ -1666,6 +1732,7 @@ ap_status ap_workload_destroy(ap_workload* w) {
     if (w->d_scratch) ok = (hipFree(w->d_scratch) == hipSuccess) && ok;
     if (w->d_span) ok = (hipFree(w->d_span) == hipSuccess) && ok;
     if (w->d_span_t) ok = (hipFree(w->d_span_t) == hipSuccess) && ok;
+    if (w->d_pair) ok = (hipFree(w->d_pair) == hipSuccess) && ok;
     if (w->d_nominal) ok = (hipFree(w->d_nominal) == hipSuccess) && ok;
     delete w;
     return ok ? AP_OK : AP_ERR_DEVICE;
