@@ -535,38 +535,42 @@ constexpr uint32_t kWideBlock = kWideWaves * 128u;
 constexpr uint32_t kWideMaxSlots = 64;
 constexpr uint32_t kWideLdsBytes = 32768;         // rings of the M real replicas of the one candidate a workgroup holds
 
-// Resolve the K first probes of a lane (`old[k]` came back from slot `at[k]` for span word
-// `span[k]`): second probe `second[k]` bytes further on for those that lost, then the search.
-// Returns true if some request found no slot in its whole ring.
+// Resolve the K first probes of a lane: `old[k]` came back from slot `at[k]`, where the request
+// offered `value[k]` (its finish tick in the upper half; the lower half does not matter);
+// `arrival[k]` is any word whose lower half is the request's arrival tick.  Second probe
+// `second[k]` bytes further on for those that lost, then the search.  Returns true if some
+// request found no slot in its whole ring.
 template <uint32_t K>
-__device__ __forceinline__ bool wide_resolve(const uint32_t (&span)[K], const uint32_t (&at)[K],
-                                             const uint32_t (&old)[K], const uint32_t (&second)[K], uint32_t S,
-                                             uint32_t slots_log2) {
+__device__ __forceinline__ bool wide_resolve(const uint32_t (&value)[K], const uint32_t (&arrival)[K],
+                                             const uint32_t (&at)[K], const uint32_t (&old)[K],
+                                             const uint32_t (&second)[K], uint32_t S, uint32_t slots_log2) {
     uint32_t old2[K];
 #pragma unroll
     for (uint32_t k = 0; k < K; ++k) {
-        const bool lost = span_busy(old[k], span[k]);
-        old2[k] = lds_max_rtn(at[k] + second[k], lost ? span[k] : 0u);       // a zero changes nothing
+        const bool lost = span_busy(old[k], arrival[k]);
+        old2[k] = lds_max_rtn(at[k] + second[k], lost ? value[k] : 0u);      // a zero changes nothing
     }
     bool any = false;
 #pragma unroll
-    for (uint32_t k = 0; k < K; ++k) any = any || (span_busy(old[k], span[k]) && span_busy(old2[k], span[k]));
+    for (uint32_t k = 0; k < K; ++k) any = any || (span_busy(old[k], arrival[k]) && span_busy(old2[k], arrival[k]));
     if (__ballot(any) == 0ull) return false;
     uint32_t open = 0;                                                       // rare: somebody lost twice
+    uint32_t span[K];
 #pragma unroll
-    for (uint32_t k = 0; k < K; ++k)
-        open |= (span_busy(old[k], span[k]) && span_busy(old2[k], span[k])) ? 1u << k : 0u;
-    return screen_search<K>(span, at, open, 0u, S, slots_log2);       // all other slots of the ring, in its usual order
+    for (uint32_t k = 0; k < K; ++k) {
+        open |= (span_busy(old[k], arrival[k]) && span_busy(old2[k], arrival[k])) ? 1u << k : 0u;
+        span[k] = (value[k] & 0xFFFF0000u) | (arrival[k] & 0xFFFFu);
+    }
+    return screen_search<K>(span, at, open, 0u, S, slots_log2);              // all other slots of the ring, in its usual order
 }
 
 // kPacked: the table is read one word per pair of requests (half the bytes of two span words).  The
 // second request of a pair is then treated as arriving with the first, which only widens its
 // interval.  The host allows it when the tick that makes the 8-bit counts fit is not much
 // coarser than the tick the 16-bit fields need.
-__device__ __forceinline__ void unpack_pair(uint32_t word, uint32_t& span0, uint32_t& span1) {
-    const uint32_t arr = word & 0xFFFFu;
-    span0 = ((arr + ((word >> 16) & 0xFFu)) << 16) | arr;
-    span1 = ((arr + (word >> 24)) << 16) | arr;
+__device__ __forceinline__ void unpack_pair(uint32_t word, uint32_t& value0, uint32_t& value1) {
+    value0 = (word << 16) + (word & 0x00FF0000u);                           // (arrival + first count) << 16
+    value1 = ((word & 0xFFFFu) + (word >> 24)) << 16;                       // (arrival + second count) << 16
 }
 
 template <bool kAligned, bool kPacked>
@@ -621,7 +625,7 @@ __global__ __launch_bounds__(kWideThreads) void k_screen_candidates_wide(ScreenP
                 pair[d] = (uint32_t)__builtin_nontemporal_load(at) | ((uint32_t)__builtin_nontemporal_load(at + 1) << 16);
             }
             if (kPacked) {
-                span[d].x = p.pair[(i0 + mine) >> 1];
+                span[d].x = (p.pair + (i0 >> 1))[mine >> 1];
             } else {
                 span[d] = *reinterpret_cast<const uint2*>(p.span + i0 + mine);
             }
@@ -641,18 +645,19 @@ __global__ __launch_bounds__(kWideThreads) void k_screen_candidates_wide(ScreenP
             bool lane_bad = false;
 #pragma unroll
             for (uint32_t d = 0; d < kDepth; ++d) {
-                uint32_t sp[2], at[2], old[2];
+                uint32_t value[2], arrival[2], at[2], old[2];
                 const uint32_t ids = pair[d];
                 if (kPacked) {
-                    unpack_pair(span[d].x, sp[0], sp[1]);
+                    unpack_pair(span[d].x, value[0], value[1]);
+                    arrival[0] = arrival[1] = span[d].x;                     // the pair's arrival tick is its lower half
                 } else {
-                    sp[0] = span[d].x;
-                    sp[1] = span[d].y;
+                    value[0] = arrival[0] = span[d].x;
+                    value[1] = arrival[1] = span[d].y;
                 }
                 fetch(d, min((g + 1u) * kDepth + d, n_full - 1u));           // refill (redundant in the last group)
-                first_probe(ids & 0xFFFFu, sp[0], at[0], old[0]);
-                first_probe(ids >> 16, sp[1], at[1], old[1]);
-                lane_bad = wide_resolve<2>(sp, at, old, second, S, p.slots_log2) || lane_bad;
+                first_probe(ids & 0xFFFFu, value[0], at[0], old[0]);
+                first_probe(ids >> 16, value[1], at[1], old[1]);
+                lane_bad = wide_resolve<2>(value, arrival, at, old, second, S, p.slots_log2) || lane_bad;
                 if (d + 1u < kDepth) __syncthreads();
             }
             if (__ballot(lane_bad) != 0ull && lane == 0) flag[turn & 1u] = 1u;
@@ -671,15 +676,16 @@ __global__ __launch_bounds__(kWideThreads) void k_screen_candidates_wide(ScreenP
                 const bool in = r < R;
                 sp[h] = 0xFFFFu;
                 if (in && kPacked) {
+                    const uint32_t word = p.pair[r >> 1];
                     uint32_t both[2];
-                    unpack_pair(p.pair[r >> 1], both[0], both[1]);
-                    sp[h] = both[h];
+                    unpack_pair(word, both[0], both[1]);
+                    sp[h] = both[h] | (word & 0xFFFFu);
                 } else if (in) {
                     sp[h] = p.span[r];
                 }
                 first_probe(in ? (uint32_t)row[r] : 0u, sp[h], at[h], old[h]);
             }
-            const bool lane_bad = wide_resolve<2>(sp, at, old, second, S, p.slots_log2);
+            const bool lane_bad = wide_resolve<2>(sp, sp, at, old, second, S, p.slots_log2);
             if (__ballot(lane_bad) != 0ull && lane == 0) flag[turn & 1u] = 1u;
             __syncthreads();
             bad = flag[turn & 1u] != 0u;
