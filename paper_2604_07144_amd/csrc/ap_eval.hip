@@ -325,9 +325,10 @@ __global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint
 // with every service interval rounded outwards: arrival down, finish up.  A claim needs
 // old finish tick <= arrival tick, which implies old finish <= arrival in microseconds, so
 // the rounding only makes the test more conservative; it halves the table bytes read per
-// request (one 32-bit span word: arrival tick | finish tick << 16).  A slot holds the whole
-// span word of its last claimant: the maximum is still ordered by finish tick, and the test
-// compares two 16-bit halves, so no field has to be extracted.
+// request (one 32-bit span word: arrival tick | finish tick << 16).  In the one-wavefront
+// kernel a slot holds the whole span word of its last claimant (the maximum is still ordered
+// by finish tick, and the test compares two 16-bit halves, so no field has to be extracted);
+// in the eight-wavefront kernel it holds the bare finish tick.
 //
 // One more ring follows the M real ones in a candidate's slot state: ring M takes the requests
 // that name an unknown replica and is kept at "never free", so such a request loses every
@@ -391,7 +392,8 @@ __device__ __forceinline__ bool span_busy(uint32_t old, uint32_t span) { return 
 // Alternatives are reached by flipping address bits in bit-reversed order (half a ring away, a
 // quarter, three quarters, ...), which needs the rings aligned to their size.
 // Returns true if some request of this lane found no slot.
-template <uint32_t K>
+// kPlain: the slots hold bare finish ticks instead of span words.
+template <uint32_t K, bool kPlain>
 __device__ __forceinline__ bool screen_search(const uint32_t (&span)[K], const uint32_t (&at)[K], uint32_t open,
                                               uint32_t tried, uint32_t S, uint32_t slots_log2) {
     bool lane_bad = false;
@@ -408,7 +410,8 @@ __device__ __forceinline__ bool screen_search(const uint32_t (&span)[K], const u
             bool placed = false;
             if (t < S) {
                 const uint32_t hop = ((__builtin_bitreverse32(t) >> 1) >> (31u - slots_log2)) << 2;
-                placed = !span_busy(lds_max_rtn(cur_at ^ hop, cur_span), cur_span);
+                const uint32_t was = lds_max_rtn(cur_at ^ hop, kPlain ? cur_span >> 16 : cur_span);
+                placed = kPlain ? was <= (cur_span & 0xFFFFu) : !span_busy(was, cur_span);
             }
             const bool last = t + 1u >= S;                                   // no other slot of the ring is left
             lane_bad = lane_bad || (!placed && last);
@@ -450,7 +453,7 @@ __device__ __forceinline__ bool cursor_claim(const uint32_t (&id)[K], const uint
     uint32_t open = 0;                                                       // rare: somebody's slot was still taken
 #pragma unroll
     for (uint32_t e = 0; e < K; ++e) open |= span_busy(old[e], span[e]) ? 1u << e : 0u;
-    return screen_search<K>(span, at, open, 0u, S, slots_log2);
+    return screen_search<K, false>(span, at, open, 0u, S, slots_log2);
 }
 
 template <bool kAligned>
@@ -535,42 +538,45 @@ constexpr uint32_t kWideBlock = kWideWaves * 128u;
 constexpr uint32_t kWideMaxSlots = 64;
 constexpr uint32_t kWideLdsBytes = 32768;         // rings of the M real replicas of the one candidate a workgroup holds
 
+// Slots of this kernel hold bare finish ticks.  Is the slot whose old content is `old` still
+// taken when the request whose arrival tick is the lower half of `arrival` comes in?
+__device__ __forceinline__ bool wide_busy(uint32_t old, uint32_t arrival) { return old > (arrival & 0xFFFFu); }
+
 // Resolve the K first probes of a lane: `old[k]` came back from slot `at[k]`, where the request
-// offered `value[k]` (its finish tick in the upper half; the lower half does not matter);
-// `arrival[k]` is any word whose lower half is the request's arrival tick.  Second probe
-// `second[k]` bytes further on for those that lost, then the search.  Returns true if some
-// request found no slot in its whole ring.
+// offered its finish tick `finish[k]`; `arrival[k]` is any word whose lower half is the
+// request's arrival tick.  Second probe `second[k]` bytes further on for those that lost, then
+// the search.  Returns true if some request found no slot in its whole ring.
 template <uint32_t K>
-__device__ __forceinline__ bool wide_resolve(const uint32_t (&value)[K], const uint32_t (&arrival)[K],
+__device__ __forceinline__ bool wide_resolve(const uint32_t (&finish)[K], const uint32_t (&arrival)[K],
                                              const uint32_t (&at)[K], const uint32_t (&old)[K],
                                              const uint32_t (&second)[K], uint32_t S, uint32_t slots_log2) {
     uint32_t old2[K];
 #pragma unroll
     for (uint32_t k = 0; k < K; ++k) {
-        const bool lost = span_busy(old[k], arrival[k]);
-        old2[k] = lds_max_rtn(at[k] + second[k], lost ? value[k] : 0u);      // a zero changes nothing
+        const bool lost = wide_busy(old[k], arrival[k]);
+        old2[k] = lds_max_rtn(at[k] + second[k], lost ? finish[k] : 0u);     // a zero changes nothing
     }
     bool any = false;
 #pragma unroll
-    for (uint32_t k = 0; k < K; ++k) any = any || (span_busy(old[k], arrival[k]) && span_busy(old2[k], arrival[k]));
+    for (uint32_t k = 0; k < K; ++k) any = any || (wide_busy(old[k], arrival[k]) && wide_busy(old2[k], arrival[k]));
     if (__ballot(any) == 0ull) return false;
     uint32_t open = 0;                                                       // rare: somebody lost twice
     uint32_t span[K];
 #pragma unroll
     for (uint32_t k = 0; k < K; ++k) {
-        open |= (span_busy(old[k], arrival[k]) && span_busy(old2[k], arrival[k])) ? 1u << k : 0u;
-        span[k] = (value[k] & 0xFFFF0000u) | (arrival[k] & 0xFFFFu);
+        open |= (wide_busy(old[k], arrival[k]) && wide_busy(old2[k], arrival[k])) ? 1u << k : 0u;
+        span[k] = (finish[k] << 16) | (arrival[k] & 0xFFFFu);
     }
-    return screen_search<K>(span, at, open, 0u, S, slots_log2);              // all other slots of the ring, in its usual order
+    return screen_search<K, true>(span, at, open, 0u, S, slots_log2);        // all other slots of the ring, in its usual order
 }
 
 // kPacked: the table is read one word per pair of requests (half the bytes of two span words).  The
 // second request of a pair is then treated as arriving with the first, which only widens its
 // interval.  The host allows it when the tick that makes the 8-bit counts fit is not much
 // coarser than the tick the 16-bit fields need.
-__device__ __forceinline__ void unpack_pair(uint32_t word, uint32_t& value0, uint32_t& value1) {
-    value0 = (word << 16) + (word & 0x00FF0000u);                           // (arrival + first count) << 16
-    value1 = ((word & 0xFFFFu) + (word >> 24)) << 16;                       // (arrival + second count) << 16
+__device__ __forceinline__ void unpack_pair(uint32_t word, uint32_t& finish0, uint32_t& finish1) {
+    finish0 = (word & 0xFFFFu) + ((word >> 16) & 0xFFu);
+    finish1 = (word & 0xFFFFu) + (word >> 24);
 }
 
 template <bool kAligned, bool kPacked>
@@ -651,8 +657,10 @@ __global__ __launch_bounds__(kWideThreads) void k_screen_candidates_wide(ScreenP
                     unpack_pair(span[d].x, value[0], value[1]);
                     arrival[0] = arrival[1] = span[d].x;                     // the pair's arrival tick is its lower half
                 } else {
-                    value[0] = arrival[0] = span[d].x;
-                    value[1] = arrival[1] = span[d].y;
+                    arrival[0] = span[d].x;
+                    arrival[1] = span[d].y;
+                    value[0] = arrival[0] >> 16;
+                    value[1] = arrival[1] >> 16;
                 }
                 fetch(d, min((g + 1u) * kDepth + d, n_full - 1u));           // refill (redundant in the last group)
                 first_probe(ids & 0xFFFFu, value[0], at[0], old[0]);
@@ -669,23 +677,26 @@ __global__ __launch_bounds__(kWideThreads) void k_screen_candidates_wide(ScreenP
         const uint32_t n_rest = n_full - n_groups * kDepth + (n_full * kWideBlock < R ? 1u : 0u);
         for (uint32_t k = 0; k < n_rest && !bad; ++k, ++turn) {
             const uint32_t i0 = (n_groups * kDepth + k) * kWideBlock;
-            uint32_t sp[2], at[2], old[2];
+            uint32_t sp[2], fin[2], at[2], old[2];
 #pragma unroll
             for (uint32_t h = 0; h < 2u; ++h) {
                 const uint32_t r = i0 + mine + h;
                 const bool in = r < R;
-                sp[h] = 0xFFFFu;
+                sp[h] = 0xFFFFu;                                             // absent: arrives last, finishes at 0
+                fin[h] = 0u;
                 if (in && kPacked) {
                     const uint32_t word = p.pair[r >> 1];
                     uint32_t both[2];
                     unpack_pair(word, both[0], both[1]);
-                    sp[h] = both[h] | (word & 0xFFFFu);
+                    sp[h] = word;
+                    fin[h] = both[h];
                 } else if (in) {
                     sp[h] = p.span[r];
+                    fin[h] = sp[h] >> 16;
                 }
-                first_probe(in ? (uint32_t)row[r] : 0u, sp[h], at[h], old[h]);
+                first_probe(in ? (uint32_t)row[r] : 0u, fin[h], at[h], old[h]);
             }
-            const bool lane_bad = wide_resolve<2>(sp, sp, at, old, second, S, p.slots_log2);
+            const bool lane_bad = wide_resolve<2>(fin, sp, at, old, second, S, p.slots_log2);
             if (__ballot(lane_bad) != 0ull && lane == 0) flag[turn & 1u] = 1u;
             __syncthreads();
             bad = flag[turn & 1u] != 0u;
