@@ -32,8 +32,8 @@ KERNEL_SOURCE = os.path.join(ROOT, "paper_2604_07144_amd", "csrc", "ap_eval.hip"
 # Keyed by configuration; valid only for the kernel source whose hash is recorded with it.
 MEASURED_TRAFFIC = {
     # cfg: (sha256 of the kernel source when measured, bytes per call)
-    4: ("0d021da5b75f5b40890a9c3288ba0673381670a0c0dc9f871e9b7ef10d812c7b", 4338931271),
-    3: ("0d021da5b75f5b40890a9c3288ba0673381670a0c0dc9f871e9b7ef10d812c7b", 548484719),
+    4: ("86163911b0fbaf880a0d8be70f5ba812b410b1d142a17191689515586a9b134a", 4321503863),
+    3: ("86163911b0fbaf880a0d8be70f5ba812b410b1d142a17191689515586a9b134a", 548767052),
 }
 
 
