@@ -163,6 +163,31 @@ def test_large_replica_tables_take_the_queue_per_lane_path(name, n, M, B, gap, C
     both(tr, rows, name)
 
 
+@pytest.mark.parametrize("one_very_long_request", [False, True])
+def test_large_table_screening_with_both_table_forms(one_very_long_request):
+    """128 identical replicas, light load: the eight-wavefront form of the contention-free shortcut.  Its table
+    is read one word per two requests when the tick that needs is in proportion; a single request that runs for
+    seconds in a trace of milliseconds-long ones makes that tick far too coarse, and the library falls back to
+    one word per request.  Both must agree with the oracle, unknown ids and ragged tail included."""
+    n, M, B = 20000 + 333, 128, 64
+    rng = np.random.default_rng(5)
+    arrival = (np.cumsum(rng.integers(0, 600, n)) + 77).astype(np.uint64)
+    prompt = rng.integers(1, 6000, n)
+    out = rng.integers(1, 500, n)
+    if one_very_long_request:
+        out[n // 3] = 200_000
+    tr = traces.custom_trace(arrival, prompt, out, [STD] * M, B=B, penalty_us=9_000_000)
+    rows = _rows(10, n, M, seed=2)
+    rows[0] = np.arange(n) % M
+    rows[1, 5] = M + 3                                   # unknown ids: first block, ragged tail
+    rows[2, n - 1] = 65535
+    rows[3, : n // 2] = 7                                # half the trace on one replica: queueing, replayed
+    want = oracle_for(tr).eval_batch(rows, nthreads=8)
+    assert len(set(want["sum_ttft_us"][4:].tolist())) == 1 and want["sum_ttft_us"][3] > want["sum_ttft_us"][4]
+    with GpuWorkload(tr) as g:
+        assert_same(g.eval(rows), want, f"large table, one_very_long_request={one_very_long_request}")
+
+
 def test_lengths_beyond_16_bits_and_coarse_ticks():
     """Prompt / output lengths >= 65536 (32-bit staging in the replay kernel) and a trace long enough that the
     screening kernel's 16-bit ticks are coarser than a microsecond."""
