@@ -1706,7 +1706,9 @@ ap_status ap_eval_candidates(const ap_workload* w, const uint16_t* d_assign, uin
             void (*kernel)(ScreenParams, const uint16_t*, ap_metrics*, uint32_t) =
                 w->screen_packed ? (aligned ? k_screen_candidates_wide<true, true> : k_screen_candidates_wide<false, true>)
                                  : (aligned ? k_screen_candidates_wide<true, false> : k_screen_candidates_wide<false, false>);
-            hipLaunchKernelGGL(kernel, dim3(std::min(C, w->n_cu * 8u)), dim3(kWideThreads), w->screen_wide_lds_bytes,
+            // one candidate per workgroup while the grid stays moderate: workgroups finish at different
+            // times, and the hardware's queue of waiting workgroups balances that better than fixed shares
+            hipLaunchKernelGGL(kernel, dim3(std::min(C, w->n_cu * 64u)), dim3(kWideThreads), w->screen_wide_lds_bytes,
                                stream, w->screen_params, d_assign, d_out, C);
         } else {
             hipLaunchKernelGGL(aligned ? k_screen_candidates<true> : k_screen_candidates<false>, dim3(blocks),
