@@ -1575,7 +1575,7 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
     w->lds_bytes = bytes;
     w->hist16 = hist16;
     w->n_cu = (uint32_t)n_cu;
-    w->max_grid = (uint32_t)n_cu * 8u;
+    w->max_grid = (uint32_t)n_cu * 64u;    // few candidates per workgroup: the hardware balances uneven finish times
     w->resident_grid = (uint32_t)n_cu * std::max(1u, std::min(4u, bytes ? (uint32_t)lds_cap / bytes : 1u));
 
     // ---- three-kernel replay: scratch for one batch of candidates -------------------------
