@@ -32,8 +32,8 @@ KERNEL_SOURCE = os.path.join(ROOT, "paper_2604_07144_amd", "csrc", "ap_eval.hip"
 # Keyed by configuration; valid only for the kernel source whose hash is recorded with it.
 MEASURED_TRAFFIC = {
     # cfg: (sha256 of the kernel source when measured, bytes per call)
-    4: ("86163911b0fbaf880a0d8be70f5ba812b410b1d142a17191689515586a9b134a", 4321503863),
-    3: ("86163911b0fbaf880a0d8be70f5ba812b410b1d142a17191689515586a9b134a", 548767052),
+    4: ("7f5c79ab5aa10df63849b9a68564c91d09c8341f1dfb983d194d06cbdd624e81", 4318124407),
+    3: ("7f5c79ab5aa10df63849b9a68564c91d09c8341f1dfb983d194d06cbdd624e81", 543276028),
 }
 
 

@@ -1699,7 +1699,7 @@ ap_status ap_eval_candidates(const ap_workload* w, const uint16_t* d_assign, uin
     if (!d_assign || !d_out) return AP_ERR_INVALID;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (w->screen) {
-        const uint32_t blocks = std::min((C + kScreenWaves - 1u) / kScreenWaves, w->n_cu * 8u);
+        const uint32_t blocks = std::min((C + kScreenWaves - 1u) / kScreenWaves, w->n_cu * 64u);
         // rows start on 4-byte boundaries when R is even and the batch itself does
         const bool aligned = (w->R % 2u == 0u) && (reinterpret_cast<uintptr_t>(d_assign) % 4u == 0u);
         if (w->screen_wide) {
