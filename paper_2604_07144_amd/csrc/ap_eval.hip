@@ -126,6 +126,20 @@ __device__ __forceinline__ uint32_t wave_shift_down(uint32_t v, uint32_t last) {
     return (uint32_t)__builtin_amdgcn_update_dpp((int)last, (int)v, 0x130 /* wave_shl:1 */, 0xF, 0xF, false);
 }
 
+// The lanes of this wavefront whose key equals mine, as the two halves of a 64-bit mask: one
+// ballot per key bit; a lane keeps the lanes that agree with it on that bit.
+__device__ __forceinline__ void wave_peers(uint32_t key, uint32_t key_bits, uint32_t& lo, uint32_t& hi) {
+    lo = 0xFFFFFFFFu;
+    hi = 0xFFFFFFFFu;
+    for (uint32_t b = 0; b < key_bits; ++b) {
+        const uint32_t bit = (key >> b) & 1u;
+        const unsigned long long set = __ballot(bit != 0u);
+        const uint32_t flip = bit - 1u;               // all ones where my bit is clear: then the agreeing lanes are ~set
+        lo &= (uint32_t)set ^ flip;
+        hi &= (uint32_t)(set >> 32) ^ flip;
+    }
+}
+
 // lane i takes lane i - 1's value; lane 0 takes `first`
 __device__ __forceinline__ uint32_t wave_shift_up(uint32_t v, uint32_t first) {
     return (uint32_t)__builtin_amdgcn_update_dpp((int)first, (int)v, 0x138 /* wave_shr:1 */, 0xF, 0xF, false);
@@ -867,15 +881,11 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
             for (uint32_t g = 0; g < kMaxGroups; ++g) {
                 if (g >= groups) break;
                 const uint32_t k = key[g];
-                unsigned long long peers = ~0ull;
-                for (uint32_t b = 0; b < p.key_bits; ++b) {
-                    bool bit = (k >> b) & 1u;
-                    unsigned long long s = __ballot(bit);
-                    peers &= bit ? s : ~s;
-                }
+                uint32_t peers_lo, peers_hi;
+                wave_peers(k, p.key_bits, peers_lo, peers_hi);
                 if (k < M) {
-                    uint32_t rank = __popcll(peers & lanes_below);
-                    uint32_t total = __popcll(peers);
+                    const uint32_t rank = __builtin_amdgcn_mbcnt_hi(peers_hi, __builtin_amdgcn_mbcnt_lo(peers_lo, 0u));
+                    const uint32_t total = __popc(peers_lo) + __popc(peers_hi);
                     uint32_t base = qstart[k] + cnt[w * M1 + k];
                     list[base + rank] = (uint16_t)(w * per_wave + g * kWave + lane);
                     if (rank + 1u == total) cnt[w * M1 + k] += total;
@@ -1049,7 +1059,6 @@ __global__ __launch_bounds__(kGroupThreads) void k_group_requests(GroupParams p,
     const uint32_t w = wave_index();
     const uint32_t per_wave = p.chunk / kGroupWaves;                     // multiple of 64
     const uint32_t groups = per_wave / kWave;
-    const unsigned long long lanes_below = (1ull << lane) - 1ull;
 
     for (uint32_t cb = blockIdx.x; cb < n_cand; cb += gridDim.x) {
         const uint32_t c = c0 + cb;
@@ -1099,15 +1108,11 @@ __global__ __launch_bounds__(kGroupThreads) void k_group_requests(GroupParams p,
             for (uint32_t g = 0; g < kGroupMaxPerThread; ++g) {
                 if (g >= groups) break;
                 const uint32_t k = key[g];
-                unsigned long long peers = ~0ull;
-                for (uint32_t b = 0; b < p.key_bits; ++b) {
-                    const bool bit = (k >> b) & 1u;
-                    const unsigned long long sset = __ballot(bit);
-                    peers &= bit ? sset : ~sset;
-                }
+                uint32_t peers_lo, peers_hi;
+                wave_peers(k, p.key_bits, peers_lo, peers_hi);
                 if (k < M) {
-                    const uint32_t rank = __popcll(peers & lanes_below);
-                    const uint32_t total = __popcll(peers);
+                    const uint32_t rank = __builtin_amdgcn_mbcnt_hi(peers_hi, __builtin_amdgcn_mbcnt_lo(peers_lo, 0u));
+                    const uint32_t total = __popc(peers_lo) + __popc(peers_hi);
                     const uint32_t base = qstart[k] + cnt[w * M1 + k];
                     lst[base + rank] = (uint16_t)(w * per_wave + g * kWave + lane);
                     if (rank + 1u == total) cnt[w * M1 + k] += total;
