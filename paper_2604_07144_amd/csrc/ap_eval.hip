@@ -132,11 +132,10 @@ __device__ __forceinline__ void wave_peers(uint32_t key, uint32_t key_bits, uint
     lo = 0xFFFFFFFFu;
     hi = 0xFFFFFFFFu;
     for (uint32_t b = 0; b < key_bits; ++b) {
-        const uint32_t bit = (key >> b) & 1u;
-        const unsigned long long set = __ballot(bit != 0u);
-        const uint32_t flip = bit - 1u;               // all ones where my bit is clear: then the agreeing lanes are ~set
-        lo &= (uint32_t)set ^ flip;
-        hi &= (uint32_t)(set >> 32) ^ flip;
+        const uint32_t mine = (uint32_t)__builtin_amdgcn_sbfe((int)key, b, 1u);  // all ones if my bit b is set, else 0
+        const unsigned long long set = __ballot(mine != 0u);
+        lo &= ~((uint32_t)set ^ mine);                                         // lanes whose bit equals mine
+        hi &= ~((uint32_t)(set >> 32) ^ mine);
     }
 }
 
