@@ -97,9 +97,10 @@ __device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v)
 
 // 4096-bin log-linear histogram map for values below 2^32.
 __device__ __forceinline__ uint32_t hist_bin_u32(uint32_t v) {
-    uint32_t e = 31u - (uint32_t)__clz((int)(v | 1u));
-    uint32_t wide = ((e - 6u) << 7) | ((v >> (e - 7u)) & 127u);
-    return v < 128u ? v : wide;
+    // With s = max(floor(log2 v), 7) - 7 the bin is (s << 7) + (v >> s): below 128 that is v itself, above it
+    // v >> s lies in [128, 256), which supplies both the sub-bin and the +1 of the octave number.
+    const uint32_t s = 24u - min((uint32_t)__clz((int)v), 24u);             // __clz(0) is 32
+    return (s << 7) + (v >> s);
 }
 
 __device__ __forceinline__ unsigned long long hist_lower_edge(uint32_t bin) {
