@@ -127,11 +127,13 @@ __device__ __forceinline__ uint32_t wave_shift_down(uint32_t v, uint32_t last) {
     return (uint32_t)__builtin_amdgcn_update_dpp((int)last, (int)v, 0x130 /* wave_shl:1 */, 0xF, 0xF, false);
 }
 
-// The lanes of this wavefront whose key equals mine, as the two halves of a 64-bit mask: one
-// ballot per key bit; a lane keeps the lanes that agree with it on that bit.
-__device__ __forceinline__ void wave_peers(uint32_t key, uint32_t key_bits, uint32_t& lo, uint32_t& hi) {
-    lo = 0xFFFFFFFFu;
-    hi = 0xFFFFFFFFu;
+// The lanes of this wavefront whose key equals mine, as the two halves of a 64-bit mask, for
+// the lanes whose key is below `n_keys` (the others get a meaningless mask): one ballot per bit
+// of n_keys - 1; a lane keeps the lanes that agree with it on that bit.
+__device__ __forceinline__ void wave_peers(uint32_t key, uint32_t n_keys, uint32_t key_bits, uint32_t& lo, uint32_t& hi) {
+    const unsigned long long ranked = __ballot(key < n_keys);
+    lo = (uint32_t)ranked;
+    hi = (uint32_t)(ranked >> 32);
     for (uint32_t b = 0; b < key_bits; ++b) {
         const uint32_t mine = (uint32_t)__builtin_amdgcn_sbfe((int)key, b, 1u);  // all ones if my bit b is set, else 0
         const unsigned long long set = __ballot(mine != 0u);
@@ -882,7 +884,7 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
                 if (g >= groups) break;
                 const uint32_t k = key[g];
                 uint32_t peers_lo, peers_hi;
-                wave_peers(k, p.key_bits, peers_lo, peers_hi);
+                wave_peers(k, M, p.key_bits, peers_lo, peers_hi);
                 if (k < M) {
                     const uint32_t rank = __builtin_amdgcn_mbcnt_hi(peers_hi, __builtin_amdgcn_mbcnt_lo(peers_lo, 0u));
                     const uint32_t total = __popc(peers_lo) + __popc(peers_hi);
@@ -1109,7 +1111,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group_requests(GroupParams p,
                 if (g >= groups) break;
                 const uint32_t k = key[g];
                 uint32_t peers_lo, peers_hi;
-                wave_peers(k, p.key_bits, peers_lo, peers_hi);
+                wave_peers(k, M, p.key_bits, peers_lo, peers_hi);
                 if (k < M) {
                     const uint32_t rank = __builtin_amdgcn_mbcnt_hi(peers_hi, __builtin_amdgcn_mbcnt_lo(peers_lo, 0u));
                     const uint32_t total = __popc(peers_lo) + __popc(peers_hi);
@@ -1569,7 +1571,7 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
     p.rep = w->d_rep;
     p.R = w->R;
     p.key_bits = 0;
-    while ((M >> p.key_bits) != 0u) ++p.key_bits;       // bits needed for the values 0..M
+    while (((M - 1u) >> p.key_bits) != 0u) ++p.key_bits;       // bits needed for the replica ids 0..M-1
     p.slo_ttft = (uint32_t)std::min<uint64_t>(slo->ttft_us, kNever);
     p.slo_tpot = (uint32_t)std::min<uint64_t>(slo->tpot_us, kNever);
     p.penalty = slo->penalty_us;
