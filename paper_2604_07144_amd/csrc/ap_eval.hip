@@ -946,14 +946,22 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
                     if (n_open > 0u) {
                         const uint32_t ready0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)ready);
                         const unsigned long long idle = __ballot(S <= ready0);
-                        if ((uint32_t)__popcll(idle) >= n_open) {
-                            // enough free slots for the whole block: request i takes the i-th free lane
+                        const uint32_t n_idle = __popcll(idle);
+                        // The first n_idle requests find a free slot whatever the earlier ones of the block
+                        // did (a slot free at the first ready time stays free for them), so they start when
+                        // ready and their finish times replace the idle slots' times in one permute.  It pays
+                        // when that covers the whole block, or enough of it to be worth sorting afterwards.
+                        uint32_t n_first = 0;
+                        if (n_idle >= n_open || (in_order ? n_idle >= 16u : n_idle > 0u)) {
+                            n_first = min(n_idle, n_open);
                             const uint32_t ri = __popcll(idle & lanes_below);
                             const uint32_t fin = ready + svc;
                             const uint32_t take = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(ri << 2), (int)fin);
-                            if (((idle >> lane) & 1ull) && ri < n_open) S = take;
+                            if (((idle >> lane) & 1ull) && ri < n_first) S = take;
                             in_order = false;
-                        } else {
+                        }
+                        if (n_first < n_open) {
+                            // the rest one by one, slot times sorted across the lanes
                             if (!in_order) S = wave_sort_ascending(S, lane);
                             in_order = true;
                             // The loop itself does not look at t_off.  Starts do not decrease along
@@ -974,18 +982,18 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
                                     S = min(wave_shift_down(S, kNever), max(S, fj));
                                     pushed = wave_shift_up(pushed, st);
                                 };
-                                uint32_t j = 0;
+                                uint32_t j = n_first;
                                 for (; j + 2u <= n_run; j += 2u) {
                                     step(j);
                                     step(j + 1u);
                                 }
                                 if (j < n_run) step(j);
                                 const uint32_t mine = (uint32_t)__builtin_amdgcn_ds_bpermute((int)((n_run - 1u - lane) << 2), (int)pushed);
-                                if (lane < n_run) start = mine;
+                                if (lane >= n_first && lane < n_run) start = mine;
                                 const uint32_t n_in_time = __popcll(__ballot(lane < n_run && start < rp.t_off));
                                 if (n_in_time == n_run) break;
                                 S = S_before;
-                                n_run = n_in_time;
+                                n_run = n_in_time;      // not below n_first: those start when ready, before t_off
                             }
                             n_served = n_run;
                         }
