@@ -32,8 +32,8 @@ KERNEL_SOURCE = os.path.join(ROOT, "paper_2604_07144_amd", "csrc", "ap_eval.hip"
 # Keyed by configuration; valid only for the kernel source whose hash is recorded with it.
 MEASURED_TRAFFIC = {
     # cfg: (sha256 of the kernel source when measured, bytes per call)
-    4: ("3ad7224f0f5ebe06b0bb6c145a5eb08be6611605a4f8fadaa5c1b0314e2adfb6", 4317771672),
-    3: ("3ad7224f0f5ebe06b0bb6c145a5eb08be6611605a4f8fadaa5c1b0314e2adfb6", 543286574),
+    4: ("2bdf9d4a7e03e2e3478224654c2fea553c9d1371f8060d962030dd161330c5d0", 4319063187),
+    3: ("2bdf9d4a7e03e2e3478224654c2fea553c9d1371f8060d962030dd161330c5d0", 543720066),
 }
 
 
