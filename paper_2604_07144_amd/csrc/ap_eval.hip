@@ -630,55 +630,55 @@ __global__ __launch_bounds__(kWideThreads) void k_screen_candidates_wide(ScreenP
         __syncthreads();
 
         // Full blocks go in groups of kDepth.  While a group is processed the loads of the next
-        // group are issued, one register set per block, so kDepth blocks stay in flight per
+        // group are issued, one register per block and stream, so kDepth blocks stay in flight per
         // wavefront; the body is straight-line (the prefetch index is clamped instead of
-        // guarded) so the register sets never have to be copied.  The verdict is exchanged once
-        // per group: group g reports in flag[g & 1], and a wavefront already in the next group
-        // writes the other word, so all wavefronts read the same verdict and leave together.
+        // guarded), and two register sets take turns (a group loads into the set it does not
+        // read), so nothing has to be copied, or waited for, between groups.  The verdict is
+        // exchanged once per group: group g reports in flag[g & 1], and a wavefront already in
+        // the next group writes the other word, so all wavefronts read the same verdict and
+        // leave together.
         constexpr uint32_t kDepth = 4;
-        uint32_t pair[kDepth];
-        uint2 span[kDepth];
-        auto fetch = [&](uint32_t d, uint32_t blk) {
+        struct Loaded {
+            uint32_t pair[kDepth];    // two replica ids
+            uint2 span[kDepth];       // their table words (.x only when packed)
+        };
+        auto fetch = [&](Loaded& into, uint32_t d, uint32_t blk) {
             const uint32_t i0 = blk * kWideBlock;
             const uint16_t* at = row + i0 + mine;
             if (kAligned) {
-                pair[d] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(at));
+                into.pair[d] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(at));
             } else {
-                pair[d] = (uint32_t)__builtin_nontemporal_load(at) | ((uint32_t)__builtin_nontemporal_load(at + 1) << 16);
+                into.pair[d] = (uint32_t)__builtin_nontemporal_load(at) | ((uint32_t)__builtin_nontemporal_load(at + 1) << 16);
             }
             if (kPacked) {
-                span[d].x = (p.pair + (i0 >> 1))[mine >> 1];
+                into.span[d].x = (p.pair + (i0 >> 1))[mine >> 1];
             } else {
-                span[d] = *reinterpret_cast<const uint2*>(p.span + i0 + mine);
+                into.span[d] = *reinterpret_cast<const uint2*>(p.span + i0 + mine);
             }
         };
-        auto first_probe = [&](uint32_t id, uint32_t sp, uint32_t& at, uint32_t& old) {
+        auto first_probe = [&](uint32_t id, uint32_t finish, uint32_t& at, uint32_t& old) {
             at = (min(id, M) << ring_shift) + slot_addr;                     // unknown replicas: the never-free ring
-            old = lds_max_rtn(at, sp);
+            old = lds_max_rtn(at, finish);
         };
         const uint32_t n_groups = n_full / kDepth;
         bool bad = !rings_aligned;
         uint32_t turn = 0;                                                   // which flag word the next verdict uses
-        if (n_groups > 0u && !bad) {
-#pragma unroll
-            for (uint32_t d = 0; d < kDepth; ++d) fetch(d, d);
-        }
-        for (uint32_t g = 0; g < n_groups && !bad; ++g, ++turn) {
+        auto run_group = [&](const Loaded& now, Loaded& next, uint32_t g) {
             bool lane_bad = false;
 #pragma unroll
             for (uint32_t d = 0; d < kDepth; ++d) {
                 uint32_t value[2], arrival[2], at[2], old[2];
-                const uint32_t ids = pair[d];
+                const uint32_t ids = now.pair[d];
                 if (kPacked) {
-                    unpack_pair(span[d].x, value[0], value[1]);
-                    arrival[0] = arrival[1] = span[d].x;                     // the pair's arrival tick is its lower half
+                    unpack_pair(now.span[d].x, value[0], value[1]);
+                    arrival[0] = arrival[1] = now.span[d].x;                 // the pair's arrival tick is its lower half
                 } else {
-                    arrival[0] = span[d].x;
-                    arrival[1] = span[d].y;
+                    arrival[0] = now.span[d].x;
+                    arrival[1] = now.span[d].y;
                     value[0] = arrival[0] >> 16;
                     value[1] = arrival[1] >> 16;
                 }
-                fetch(d, min((g + 1u) * kDepth + d, n_full - 1u));           // refill (redundant in the last group)
+                fetch(next, d, min((g + 1u) * kDepth + d, n_full - 1u));     // redundant in the last group
                 first_probe(ids & 0xFFFFu, value[0], at[0], old[0]);
                 first_probe(ids >> 16, value[1], at[1], old[1]);
                 lane_bad = wide_resolve<2>(value, arrival, at, old, second, S, p.slots_log2) || lane_bad;
@@ -687,6 +687,17 @@ __global__ __launch_bounds__(kWideThreads) void k_screen_candidates_wide(ScreenP
             if (__ballot(lane_bad) != 0ull && lane == 0) flag[turn & 1u] = 1u;
             __syncthreads();
             bad = flag[turn & 1u] != 0u;
+            ++turn;
+        };
+        Loaded set_a, set_b;
+        if (n_groups > 0u && !bad) {
+#pragma unroll
+            for (uint32_t d = 0; d < kDepth; ++d) fetch(set_a, d, d);
+        }
+        for (uint32_t g = 0; g < n_groups && !bad; g += 2u) {
+            run_group(set_a, set_b, g);
+            if (bad || g + 1u >= n_groups) break;
+            run_group(set_b, set_a, g + 1u);
         }
         // fewer than kDepth full blocks left, then the ragged tail with every access guarded
         // (an absent request is a probe of replica 0 that changes nothing and cannot lose)
