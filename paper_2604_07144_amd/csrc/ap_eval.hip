@@ -694,11 +694,12 @@ __global__ __launch_bounds__(kWideThreads) void k_screen_candidates_wide(ScreenP
 #pragma unroll
             for (uint32_t d = 0; d < kDepth; ++d) fetch(set_a, d, d);
         }
-        for (uint32_t g = 0; g < n_groups && !bad; g += 2u) {
+        uint32_t g = 0;
+        for (; g + 2u <= n_groups && !bad; g += 2u) {
             run_group(set_a, set_b, g);
-            if (bad || g + 1u >= n_groups) break;
-            run_group(set_b, set_a, g + 1u);
+            if (!bad) run_group(set_b, set_a, g + 1u);
         }
+        if (g < n_groups && !bad) run_group(set_a, set_b, g);               // an odd number of groups
         // fewer than kDepth full blocks left, then the ragged tail with every access guarded
         // (an absent request is a probe of replica 0 that changes nothing and cannot lose)
         const uint32_t n_rest = n_full - n_groups * kDepth + (n_full * kWideBlock < R ? 1u : 0u);
