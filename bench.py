@@ -32,8 +32,8 @@ KERNEL_SOURCE = os.path.join(ROOT, "paper_2604_07144_amd", "csrc", "ap_eval.hip"
 # Keyed by configuration; valid only for the kernel source whose hash is recorded with it.
 MEASURED_TRAFFIC = {
     # cfg: (sha256 of the kernel source when measured, bytes per call)
-    4: ("2bdf9d4a7e03e2e3478224654c2fea553c9d1371f8060d962030dd161330c5d0", 4319063187),
-    3: ("2bdf9d4a7e03e2e3478224654c2fea553c9d1371f8060d962030dd161330c5d0", 543720066),
+    4: ("6ca87f1619036eddd7d3494d7b7e238bf85be6437375379466566691dfd73df0", 4310758110),
+    3: ("6ca87f1619036eddd7d3494d7b7e238bf85be6437375379466566691dfd73df0", 543731148),
 }
 
 
