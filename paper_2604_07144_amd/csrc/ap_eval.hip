@@ -788,11 +788,15 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
     // After screening, most workgroups have nothing left to do: look at all of this workgroup's
     // records at once (one per thread) and leave if none carries the mark.
     if (only_pending) {
-        int any = 0;
+        bool any = false;
         for (unsigned long long c = (unsigned long long)blockIdx.x + (unsigned long long)tid * gridDim.x; c < C;
              c += (unsigned long long)kThreads * gridDim.x)
-            any |= is_pending(out[c]) ? 1 : 0;
-        if (__syncthreads_or(any) == 0) return;
+            any = any || is_pending(out[c]);
+        if (tid == 0) *next_m = 0u;                   // borrowed as the workgroup's "something to do" word
+        __syncthreads();
+        if (any) *next_m = 1u;
+        __syncthreads();
+        if (*next_m == 0u) return;                    // the same word for every thread: all leave or none
     }
 
     for (uint32_t c = blockIdx.x; c < C; c += gridDim.x) {
@@ -1540,6 +1544,12 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
     // other's barriers); otherwise take the largest chunk one workgroup can hold.
     const uint32_t want = std::min(kMaxChunk, std::max(2u * kThreads, align_up(56u * M, kThreads)));
     uint32_t bytes = 0, chunk = 0;
+    {   // what the kernel itself declares (nothing today) comes off the dynamic part
+        hipFuncAttributes attr;
+        if (hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(eval_kernel(hist16, w->len16))) != hipSuccess)
+            return AP_ERR_DEVICE;
+        lds_cap -= (int)std::min<size_t>(attr.sharedSizeBytes, (size_t)lds_cap);
+    }
     for (uint32_t budget : {(uint32_t)lds_cap / 2u, (uint32_t)lds_cap}) {
         const uint32_t smallest = budget == (uint32_t)lds_cap ? kThreads : std::max(kThreads, want / 2u);
         for (chunk = want; chunk >= smallest; chunk -= kThreads) {

@@ -78,6 +78,7 @@ def _rows(C, R, hi, seed):
     ("m512_b8", 4200, 512, 8, 50, 4),                 # many replicas: most queues empty
     ("exact_chunk", 4096, 7, 16, 600, 6),             # R equal to one full chunk
     ("chunk_plus_one", 4097, 7, 16, 600, 6),
+    ("m600_b32_lds_limit", 9000, 600, 32, 248, 4),    # the replay kernel's LDS plan lands exactly on the device limit
 ])
 def test_crafted_traces(name, n, M, B, gap, C):
     tr = _mk(n, M, B, gap, seed=len(name) * 7 + n, ties=(name == "ties"))
