@@ -209,7 +209,7 @@ def test_lengths_beyond_16_bits_and_coarse_ticks():
     both(mixed, rows, "long lengths, two replica types (replayed)")
 
 
-@pytest.mark.parametrize("seed", range(40))
+@pytest.mark.parametrize("seed", range(160))
 def test_random_shapes_against_the_oracle(seed):
     """Shapes, loads and replica tables drawn at random within the documented limits: whichever kernels the
     library's plan picks for them, every record must equal the oracle's."""
