@@ -387,30 +387,27 @@ def test_small_configurations_every_row(cfg):
     both(tr, rows, tr.spec.name)
 
 
-@pytest.mark.parametrize("cfg,n_check", [(2, 192), (3, 128), (4, 48)])
-def test_full_size_configurations_sampled_rows(cfg, n_check):
-    """All C rows run on the GPU at full size (rows uploaded in slabs); the oracle scores a
-    spread of them one by one."""
+@pytest.mark.parametrize("cfg", [2, 3, 4])
+def test_full_size_configurations_every_row(cfg):
+    """All C rows run on the GPU at full size, in the launch configuration the benchmark times (one call over
+    the whole batch; rows drawn and uploaded in slabs), and the oracle scores every one of them (sixteen threads,
+    slab by slab: configs[4] is 2.1e9 request simulations, about twenty seconds of host time)."""
     tr = traces.make_trace(cfg)
     C, R = tr.C, tr.R
+    orc = oracle_for(tr)
     d_assign = torch.empty((C, R), dtype=torch.int16, device="cuda")
+    want = np.empty(C, dtype=binding.METRICS_DTYPE)
     slab = 512
     for lo in range(0, C, slab):
         hi = min(C, lo + slab)
-        d_assign[lo:hi] = torch.from_numpy(tr.assignment_rows(lo, hi).view(np.int16)).cuda()
+        rows = tr.assignment_rows(lo, hi)
+        d_assign[lo:hi] = torch.from_numpy(rows.view(np.int16)).cuda()
+        want[lo:hi] = orc.eval_batch(rows, nthreads=16)
     with GpuWorkload(tr) as g:
         d_out = g.eval_device(d_assign)
         torch.cuda.synchronize()
         got = to_records(d_out)
-    pick = np.unique(np.concatenate([[0, 1, C // 2 - 1, C // 2, C - 2, C - 1],
-                                     np.random.default_rng(cfg).integers(0, C, n_check)]))
-    rows = np.stack([tr.assignment_row(int(c)) for c in pick])
-    want = oracle_for(tr).eval_batch(rows, nthreads=16)
-    assert_same(got[pick], want, tr.spec.name)
-    # properties that hold for every row at any size
-    assert ((got["n_rejected"] <= R) & (got["slo_ok"] <= R - got["n_rejected"])).all()
-    assert (got["sum_e2e_us"] >= got["sum_ttft_us"]).all()
-    assert (got["p99_e2e_us"] >= got["p99_ttft_us"]).all()
+    assert_same(got, want, tr.spec.name)
     if cfg != 3:
         assert (got["n_rejected"] == 0).all()
 
