@@ -32,8 +32,8 @@ KERNEL_SOURCE = os.path.join(ROOT, "paper_2604_07144_amd", "csrc", "ap_eval.hip"
 # Keyed by configuration; valid only for the kernel source whose hash is recorded with it.
 MEASURED_TRAFFIC = {
     # cfg: (sha256 of the kernel source when measured, bytes per call)
-    4: ("6ca87f1619036eddd7d3494d7b7e238bf85be6437375379466566691dfd73df0", 4310758110),
-    3: ("6ca87f1619036eddd7d3494d7b7e238bf85be6437375379466566691dfd73df0", 543731148),
+    4: ("cf0ac7fe2799b79139138f7d20e9c35a12f1198469b1bafe5fb31f0d58beab97", 4311175191),
+    3: ("cf0ac7fe2799b79139138f7d20e9c35a12f1198469b1bafe5fb31f0d58beab97", 543642513),
 }
 
 
