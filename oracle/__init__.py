@@ -72,6 +72,8 @@ def lib():
         L.orc_eval_row.restype = C.c_int
         L.orc_eval_batch.argtypes = [C.POINTER(OrcProblem), C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p]
         L.orc_eval_batch.restype = C.c_int
+        L.orc_child_row.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
+        L.orc_child_row.restype = None
         _lib = L
     return _lib
 
@@ -140,6 +142,29 @@ class Oracle:
         if rc:
             raise RuntimeError(f"orc_eval_batch failed: {rc}")
         return out
+
+    def eval_children(self, parent, edit_first, edit_request, edit_replica, nthreads: int = 1) -> np.ndarray:
+        """Children of ``parent`` given as edit lists: their rows by the child-row rule, then ``eval_batch``."""
+        return self.eval_batch(child_rows(parent, edit_first, edit_request, edit_replica), nthreads)
+
+
+def child_rows(parent, edit_first, edit_request, edit_replica) -> np.ndarray:
+    """Rows of the children of ``parent``: child c applies edits ``edit_first[c] .. edit_first[c+1]``
+    (none when that range is empty or reversed) front to back."""
+    parent = np.ascontiguousarray(parent, dtype=np.uint16)
+    first = np.ascontiguousarray(edit_first, dtype=np.uint32)
+    request = np.ascontiguousarray(edit_request, dtype=np.uint32)
+    replica = np.ascontiguousarray(edit_replica, dtype=np.uint16)
+    assert first.ndim == 1 and first.shape[0] >= 1 and request.shape == replica.shape
+    n_children, R = first.shape[0] - 1, parent.shape[0]
+    rows = np.empty((n_children, R), dtype=np.uint16)
+    for c in range(n_children):
+        lo, hi = int(first[c]), int(first[c + 1])
+        n = max(0, hi - lo)
+        assert n == 0 or hi <= request.shape[0]
+        lib().orc_child_row(parent.ctypes.data, R, request.ctypes.data + 4 * lo, replica.ctypes.data + 2 * lo,
+                            n, rows[c].ctypes.data)
+    return rows
 
 
 def _metrics_to_record(m: OrcMetrics) -> np.ndarray:

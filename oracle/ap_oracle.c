@@ -54,7 +54,8 @@
  * Pins (tests that run without a GPU): hand-worked traces, the single-slot Lindley
  * closed form, the order-statistic definition of the B-slot queue, sweep-line
  * invariants, brute force over all assignments of tiny instances, numpy reductions
- * for the no-wait case.  Nothing in this file is "parity unpinned".
+ * for the no-wait case; the child-row rule against numpy's indexed assignment (last
+ * write wins) and hand-made lists.  Nothing in this file is "parity unpinned".
  *
  * All times are unsigned 64-bit microseconds.
  */
@@ -247,6 +248,24 @@ int orc_eval_row(const orc_problem *p, const uint16_t *row, orc_metrics *out, co
     free(ttft); free(tpot); free(e2e); free(fin); free(sta); free(rej); free(queue);
     free(slot_free); free(hist);
     return 0;
+}
+
+/* ---- sparse candidates: a parent assignment plus per-child edit lists ------------
+ * A child candidate is a small modification of a parent (Section 5.4 "Synthesis
+ * Configuration", trade-off-aware mutation: children are diff-based modifications of a
+ * high-performing parent; Section 6.1 "Warm-start re-evolution": a population holds top
+ * candidates along with their mutations).  For the workload-assignment dimension the
+ * diff is a list of (request, replica) pairs.  The child's row is the parent's row with
+ * the list applied front to back: a later edit of the same request replaces an earlier
+ * one, and an edit that names a request outside the trace changes nothing.  A replica id
+ * outside the table is kept as it is (the replay rejects that request, as for any row).
+ * The child's metrics are those of orc_eval_row on this row: nothing else is defined. */
+void orc_child_row(const uint16_t *parent, uint32_t R, const uint32_t *request, const uint16_t *replica,
+                   uint64_t n_edits, uint16_t *row)
+{
+    for (uint32_t r = 0; r < R; ++r) row[r] = parent[r];
+    for (uint64_t e = 0; e < n_edits; ++e)
+        if (request[e] < R) row[request[e]] = replica[e];
 }
 
 /* ---- many rows: threads over candidate rows, nothing else --------------------- */

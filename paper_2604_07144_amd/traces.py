@@ -30,7 +30,7 @@ COEF_STANDARD = (2000, 3, 25, 5)
 COEF_FAST = (1200, 2, 15, 3)
 COEF_SLOW = (3500, 5, 40, 8)
 
-_STREAM_ARRIVAL, _STREAM_PROMPT, _STREAM_OUT, _STREAM_REPLICA, _STREAM_ASSIGN = 1, 2, 3, 4, 5
+_STREAM_ARRIVAL, _STREAM_PROMPT, _STREAM_OUT, _STREAM_REPLICA, _STREAM_ASSIGN, _STREAM_EDITS = 1, 2, 3, 4, 5, 6
 
 
 def _rng(seed: int, stream: int, row: int = 0) -> np.random.Generator:
@@ -111,18 +111,72 @@ class Trace:
         rng = _rng(spec.seed, _STREAM_ASSIGN, c)
         if spec.assign == "uniform" or (spec.assign == "half_jsq5" and c < spec.C // 2):
             return rng.integers(0, M, size=R, dtype=np.uint16)
-        frac = 0.05 if spec.assign == "half_jsq5" else 0.01
         row = self.jsq_base().copy()
-        n = max(1, int(round(frac * R)))
-        pos = rng.integers(0, R, size=n)
-        row[pos] = rng.integers(0, M, size=n, dtype=np.uint16)
+        pos, val = self._mutation_draws(rng)
+        row[pos] = val
         return row
+
+    def _mutation_draws(self, rng: np.random.Generator):
+        """The (request, replica) pairs a mutated row draws, in draw order (requests may repeat)."""
+        frac = 0.05 if self.spec.assign == "half_jsq5" else 0.01
+        n = max(1, int(round(frac * self.R)))
+        pos = rng.integers(0, self.R, size=n)
+        return pos, rng.integers(0, self.M, size=n, dtype=np.uint16)
+
+    def is_mutated_row(self, c: int) -> bool:
+        """True when row ``c`` is the join-shortest-queue parent plus a list of reassignments."""
+        return self.spec.assign == "jsq1" or (self.spec.assign == "half_jsq5" and c >= self.spec.C // 2)
+
+    def mutation_lists(self, lo: int, hi: int, *, tidy: bool = False):
+        """Rows ``lo..hi`` of a mutation sweep as edit lists against ``jsq_base()``.
+
+        Returns ``(edit_first uint32[hi-lo+1], edit_request uint32[E], edit_replica uint16[E])``: the very
+        pairs ``assignment_row`` draws, in draw order, so a request can occur more than once in a list.
+        ``tidy=True`` lists every request once, in increasing order, keeping the pair drawn last.
+        """
+        first, reqs, reps = [0], [], []
+        for c in range(lo, hi):
+            if not self.is_mutated_row(c):
+                raise ValueError(f"row {c} of {self.spec.name} is not drawn as a mutation of the parent")
+            pos, val = self._mutation_draws(_rng(self.spec.seed, _STREAM_ASSIGN, c))
+            if tidy:
+                # last occurrence of every request: first occurrence in the reversed list
+                uniq, idx = np.unique(pos[::-1], return_index=True)
+                pos, val = uniq, val[::-1][idx]
+            reqs.append(pos.astype(np.uint32))
+            reps.append(val.astype(np.uint16))
+            first.append(first[-1] + pos.shape[0])
+        return (np.asarray(first, dtype=np.uint32), np.concatenate(reqs) if reqs else np.zeros(0, np.uint32),
+                np.concatenate(reps) if reps else np.zeros(0, np.uint16))
 
     def assignment_rows(self, lo: int, hi: int) -> np.ndarray:
         out = np.empty((hi - lo, self.R), dtype=np.uint16)
         for i, c in enumerate(range(lo, hi)):
             out[i] = self.assignment_row(c)
         return out
+
+
+def draw_edit_lists(seed: int, n_children: int, R: int, M: int, mean_edits: float, *,
+                    request_range: Optional[int] = None, replica_range: Optional[int] = None,
+                    sorted_lists: bool = False):
+    """Edit lists for ``n_children`` children of some parent row: per child a Poisson(``mean_edits``) number
+    of (request, replica) pairs (so some lists are empty), requests uniform below ``request_range``
+    (default R; larger values produce edits that name no request), replicas uniform below ``replica_range``
+    (default M; larger values produce unknown replica ids).  ``sorted_lists`` orders each list by request
+    (stable: equal requests keep their draw order).  Returns ``(edit_first, edit_request, edit_replica)``."""
+    rng = _rng(seed, _STREAM_EDITS)
+    counts = rng.poisson(mean_edits, size=n_children)
+    first = np.zeros(n_children + 1, dtype=np.uint32)
+    np.cumsum(counts, out=first[1:])
+    total = int(first[-1])
+    request = rng.integers(0, request_range or R, size=total).astype(np.uint32)
+    replica = rng.integers(0, replica_range or M, size=total).astype(np.uint16)
+    if sorted_lists:
+        for c in range(n_children):
+            lo, hi = int(first[c]), int(first[c + 1])
+            order = np.argsort(request[lo:hi], kind="stable")
+            request[lo:hi], replica[lo:hi] = request[lo:hi][order], replica[lo:hi][order]
+    return first, request, replica
 
 
 def _arrivals(spec: TraceSpec, R: int, rate_scale: float) -> np.ndarray:

@@ -3,7 +3,8 @@
 Each test ties the oracle to something other than itself: hand-worked values
 (tests/golden/hand_trace.txt), closed forms from queueing theory, a second definition
 of the B-slot queue as an order statistic, sweep-line invariants, exhaustive
-enumeration of tiny instances, and numpy reductions for the no-wait case.
+enumeration of tiny instances, and numpy reductions for the no-wait case.  The child-row
+rule of sparse candidates is tied to numpy's indexed assignment and to hand-made lists.
 """
 import itertools
 import os
@@ -340,3 +341,58 @@ def test_window_edge_cases():
     assert int(m["slo_ok"]) == 0
     m = make(arrival, prompt, out, B=4, slo=(2300, 29)).eval_row(row)
     assert int(m["slo_ok"]) == 0
+
+
+# ----------------------------------------------------------------------------- sparse candidates
+def test_child_row_hand_made_lists():
+    """Section 5.4 (children are diffs of a parent): front-to-back application, last edit of a request
+    wins, an edit outside the trace changes nothing, ids outside the table are kept."""
+    parent = np.array([0, 1, 2, 3, 0, 1], dtype=np.uint16)
+    #            child 0: none | child 1: two requests | child 2: request 4 three times | child 3: outside + unknown id
+    request = np.array([2, 5, 4, 4, 4, 6, 0xFFFFFFFF, 1], dtype=np.uint32)
+    replica = np.array([7, 0, 1, 2, 3, 9, 9, 0xFFFF], dtype=np.uint16)
+    first = np.array([0, 0, 2, 5, 8], dtype=np.uint32)
+    rows = oracle.child_rows(parent, first, request, replica)
+    assert rows.tolist() == [[0, 1, 2, 3, 0, 1],
+                             [0, 1, 7, 3, 0, 0],
+                             [0, 1, 2, 3, 3, 1],
+                             [0, 0xFFFF, 2, 3, 0, 1]]
+    # an empty and a reversed range both mean "no edits"
+    rows = oracle.child_rows(parent, np.array([3, 3, 1], dtype=np.uint32), request, replica)
+    assert rows.tolist() == [parent.tolist(), parent.tolist()]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_child_row_matches_numpy_indexed_assignment(seed):
+    """numpy documents that an indexed assignment with repeated indices keeps the value assigned last;
+    that is the child-row rule for in-range requests."""
+    R, M = 500, 7
+    rng = np.random.default_rng(seed)
+    parent = rng.integers(0, M, size=R, dtype=np.uint16)
+    first, request, replica = traces.draw_edit_lists(seed, 40, R, M, 60.0, request_range=R + 50,
+                                                     replica_range=M + 2, sorted_lists=bool(seed % 2))
+    rows = oracle.child_rows(parent, first, request, replica)
+    for c in range(40):
+        lo, hi = int(first[c]), int(first[c + 1])
+        inside = request[lo:hi] < R
+        expect = parent.copy()
+        expect[request[lo:hi][inside]] = replica[lo:hi][inside]
+        assert (rows[c] == expect).all(), c
+
+
+def test_mutation_sweep_rows_are_children_of_the_jsq_parent():
+    """The dense rows of a mutation sweep and its edit lists (raw draws, or one pair per request in
+    increasing order) describe the same candidates, so their metrics agree row by row."""
+    tr = traces.make_trace(4, C=12, R=3000, M=8, B=4)
+    dense = tr.assignment_rows(0, 12)
+    orc = Oracle.from_trace(tr)
+    want = orc.eval_batch(dense)
+    for tidy in (False, True):
+        first, request, replica = tr.mutation_lists(0, 12, tidy=tidy)
+        assert (oracle.child_rows(tr.jsq_base(), first, request, replica) == dense).all()
+        assert (orc.eval_children(tr.jsq_base(), first, request, replica) == want).all()
+        if tidy:
+            for c in range(12):
+                lst = request[first[c]:first[c + 1]].astype(np.int64)
+                assert (np.diff(lst) > 0).all()
+    assert len({tuple(r) for r in want.tolist()}) > 1        # the children really differ in their metrics
