@@ -91,6 +91,7 @@ def main() -> int:
     ap.add_argument("--rows", type=int, default=0, help="use only the first ROWS candidates (0 = all)")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the oracle sample (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-children", action="store_true", help="skip the sparse (edit-list) leg of a mutation sweep")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a 1 GiB device copy (reference dispatch for the HBM byte counters)")
     args = ap.parse_args()
@@ -141,6 +142,65 @@ def main() -> int:
         wall = time.perf_counter() - t0
         kernel_ms = [a.elapsed_time(b) for a, b in ev]
         got = d_out.cpu().numpy().view(binding.METRICS_DTYPE).reshape(-1)
+
+        # The same candidates in their sparse form, where the configuration is a mutation sweep: every row is
+        # the join-shortest-queue parent plus a short list of reassignments, so a caller that holds the parent
+        # passes the lists instead of the rows (ap_parent_set + ap_eval_children).  Reported beside `value`,
+        # never as `value`: the metric above is defined on dense rows.
+        children = None
+        if not args.no_children and all(tr.is_mutated_row(c) for c in (0, C // 2, C - 1)):
+            parent = tr.jsq_base()
+            d_parent = torch.from_numpy(parent.view(np.int16)).cuda()
+            counts, reqs, reps = [], [], []
+            for lo in range(0, C, slab):                      # the lists: where a row differs from the parent
+                hi = min(C, lo + slab)
+                differs = d_assign[lo:hi] != d_parent[None, :]
+                counts.append(differs.sum(dim=1))
+                where = differs.nonzero()                     # row-major: per row, requests in increasing order
+                reqs.append(where[:, 1].to(torch.int32))
+                reps.append(d_assign[lo:hi][where[:, 0], where[:, 1]])
+                del differs, where
+            d_first = torch.zeros(C + 1, dtype=torch.int64, device="cuda")
+            d_first[1:] = torch.cat(counts).cumsum(0)
+            n_edits = int(d_first[-1])
+            d_first = d_first.to(torch.int32)
+            d_request = torch.cat(reqs + [torch.zeros(1, dtype=torch.int32, device="cuda")])
+            d_replica = torch.cat(reps + [torch.zeros(1, dtype=torch.int16, device="cuda")])
+            d_out2 = torch.zeros((C, 8), dtype=torch.int64, device="cuda")
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            binding.ap_parent_set(h, parent, C)
+            parent_set_ms = (time.perf_counter() - t0) * 1e3
+
+            def child_step():
+                binding.ap_eval_children(h, d_first.data_ptr(), d_request.data_ptr(), d_replica.data_ptr(), C,
+                                         d_out2.data_ptr(), stream.cuda_stream)
+
+            for _ in range(args.warmup):
+                child_step()
+            torch.cuda.synchronize()
+            ev2 = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+            t0 = time.perf_counter()
+            for a, b in ev2:
+                a.record(stream)
+                child_step()
+                b.record(stream)
+            torch.cuda.synchronize()
+            child_wall = time.perf_counter() - t0
+            child_ms = [a.elapsed_time(b) for a, b in ev2]
+            got2 = d_out2.cpu().numpy().view(binding.METRICS_DTYPE).reshape(-1)
+            # bytes this form must move: the lists (4 + 2 per edit, 4 per child), one record per child,
+            # the parent row and the per-request tables once
+            child_alg = 6 * n_edits + 4 * (C + 1) + 64 * C + 2 * R + TABLE_BYTES_PER_REQUEST * n_types * R
+            child_s = float(np.mean(child_ms)) * 1e-3
+            children = {"value": C * R / (child_wall / args.steps), "unit": "sims/s (same candidates, passed as edit lists)",
+                        "ms_per_step": child_wall * 1e3 / args.steps, "kernel_ms_avg": child_s * 1e3,
+                        "kernel_ms_median": float(np.median(child_ms)), "kernel_ms_min": float(np.min(child_ms)),
+                        "edits": n_edits, "algorithmic_bytes": child_alg,
+                        "roofline": {"bound": "hbm", "achieved": child_alg / child_s / 1e9, "peak": HBM_PEAK_GBS,
+                                     "unit": "GB/s", "frac": child_alg / child_s / 1e9 / HBM_PEAK_GBS, "traffic": None},
+                        "ap_parent_set_ms": parent_set_ms,
+                        "matches_dense": bool(got2.tobytes() == got.tobytes())}
     finally:
         binding.ap_workload_destroy(h)
 
@@ -175,6 +235,9 @@ def main() -> int:
         "mean_ttft_us_row0": int(got["sum_ttft_us"][0]) / R,
         "rejected_row0": int(got["n_rejected"][0]),
     }
+
+    if children is not None:
+        result["sparse_children"] = children
 
     if not args.no_cpu:
         import oracle

@@ -40,7 +40,7 @@ typedef enum {
     AP_ERR_RANGE = 2,   /* a documented capacity of the device path is exceeded */
     AP_ERR_ALLOC = 3,   /* host or device allocation failed */
     AP_ERR_DEVICE = 4,  /* a HIP call failed */
-    AP_ERR_STATE = 5    /* evaluation requested before a cost model was set */
+    AP_ERR_STATE = 5    /* evaluation requested before a cost model (for children: a parent) was set */
 } ap_status;
 
 /* One replica (Section 4, data plane: the snapshot carries cluster resource
@@ -125,6 +125,37 @@ ap_status ap_costmodel_set(ap_workload *w, const ap_replica *replicas, uint32_t 
  * flight at a time.  C == 0 is a no-op.  Errors: AP_ERR_INVALID (null pointers), AP_ERR_STATE, AP_ERR_DEVICE. */
 ap_status ap_eval_candidates(const ap_workload *w, const uint16_t *d_assign, uint32_t C, ap_metrics *d_out,
                              void *hip_stream);
+
+/* Sparse candidates: children of one parent assignment (Section 5.4 "Synthesis Configuration",
+ * trade-off-aware mutation: children are diff-based modifications of a high-performing parent;
+ * Section 6.1 "Warm-start re-evolution": a population holds top candidates along with their
+ * mutations).  For the workload-assignment dimension a child is the parent row plus a list of
+ * (request, replica) edits.
+ *
+ * ap_parent_set fixes the parent for later ap_eval_children calls.
+ *   parent       : HOST array, uint16 [R], copied.  Values >= M are allowed (those requests are rejected).
+ *   max_children : the largest C a later ap_eval_children may pass (>= 1).  The call allocates
+ *                  max_children * R * 2 bytes of device memory for the rows of children that need the
+ *                  dense path (kept, and reused by later calls that ask for no more).
+ * Needs a cost model (AP_ERR_STATE otherwise); a later ap_costmodel_set discards the parent.
+ * Synchronous (one copy, one small kernel).  Errors: AP_ERR_INVALID, AP_ERR_STATE, AP_ERR_ALLOC, AP_ERR_DEVICE. */
+ap_status ap_parent_set(ap_workload *w, const uint16_t *parent, uint32_t max_children);
+
+/* Score C children of the parent.  Child c owns the edits e = d_edit_first[c] .. d_edit_first[c+1]-1
+ * (none if that range is empty or reversed); its row is the parent's with
+ * row[d_edit_request[e]] = d_edit_replica[e] applied in that order: a later edit of the same request
+ * replaces an earlier one, an edit whose request is >= R changes nothing, a replica >= M is not an error
+ * (that request is rejected).  d_out[c] is exactly what ap_eval_candidates returns for that row.
+ *   d_edit_first   : DEVICE pointer, uint32 [C + 1].
+ *   d_edit_request : DEVICE pointer, uint32 [E], E >= every index used by d_edit_first (must be a valid
+ *   d_edit_replica : DEVICE pointer, uint16 [E]   pointer even when every list is empty).
+ *   d_out          : DEVICE pointer to C ap_metrics records; only these are written.
+ * Asynchronous on hip_stream, allocates nothing, launches kernels only (may be captured into a HIP
+ * graph).  One evaluation per workload, of either kind, may be in flight at a time.  C == 0 is a no-op.
+ * Errors: AP_ERR_INVALID (null pointers), AP_ERR_STATE (no cost model or no parent), AP_ERR_RANGE
+ * (C > max_children), AP_ERR_DEVICE. */
+ap_status ap_eval_children(const ap_workload *w, const uint32_t *d_edit_first, const uint32_t *d_edit_request,
+                           const uint16_t *d_edit_replica, uint32_t C, ap_metrics *d_out, void *hip_stream);
 
 /* Release the workload and its device memory.  NULL is accepted. */
 ap_status ap_workload_destroy(ap_workload *w);

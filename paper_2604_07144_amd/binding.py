@@ -53,6 +53,11 @@ def lib() -> C.CDLL:
         L.ap_costmodel_set.restype = C.c_int
         L.ap_eval_candidates.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p]
         L.ap_eval_candidates.restype = C.c_int
+        L.ap_parent_set.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32]
+        L.ap_parent_set.restype = C.c_int
+        L.ap_eval_children.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p,
+                                       C.c_void_p]
+        L.ap_eval_children.restype = C.c_int
         L.ap_workload_destroy.argtypes = [C.c_void_p]
         L.ap_workload_destroy.restype = C.c_int
         L.ap_status_str.argtypes = [C.c_int]
@@ -118,6 +123,22 @@ def ap_eval_candidates(workload: int, d_assign_ptr: int, n_candidates: int, d_ou
     """Device pointers (ints) in; asynchronous on ``stream`` (a hipStream_t as int, 0 = default)."""
     _check(lib().ap_eval_candidates(workload, C.c_void_p(d_assign_ptr), int(n_candidates), C.c_void_p(d_out_ptr),
                                     C.c_void_p(stream)), "ap_eval_candidates")
+
+
+def ap_parent_set(workload: int, parent, max_children: int) -> None:
+    """Host uint16[R] parent row in; sizes the device rows for up to ``max_children`` children."""
+    parent = np.ascontiguousarray(parent, dtype=np.uint16)
+    if parent.ndim != 1:
+        raise ValueError("parent must be a 1-D array of replica ids")
+    _check(lib().ap_parent_set(workload, parent.ctypes.data, int(max_children)), "ap_parent_set")
+
+
+def ap_eval_children(workload: int, d_edit_first_ptr: int, d_edit_request_ptr: int, d_edit_replica_ptr: int,
+                     n_children: int, d_out_ptr: int, stream: int = 0) -> None:
+    """Device pointers (ints) in; asynchronous on ``stream`` (a hipStream_t as int, 0 = default)."""
+    _check(lib().ap_eval_children(workload, C.c_void_p(d_edit_first_ptr), C.c_void_p(d_edit_request_ptr),
+                                  C.c_void_p(d_edit_replica_ptr), int(n_children), C.c_void_p(d_out_ptr),
+                                  C.c_void_p(stream)), "ap_eval_children")
 
 
 def ap_workload_destroy(workload: int) -> None:

@@ -472,7 +472,9 @@ __device__ __forceinline__ bool cursor_claim(const uint32_t (&id)[K], const uint
     return screen_search<K, false>(span, at, open, 0u, S, slots_log2);
 }
 
-template <bool kAligned>
+// kMarked: look only at the candidates whose record already carries the pending mark (the rows
+// written for the children that k_certify_children could not settle); every other record is final.
+template <bool kAligned, bool kMarked>
 __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenParams p, const uint16_t* __restrict__ assign,
                                                                        ap_metrics* __restrict__ out, uint32_t C) {
     extern __shared__ __align__(16) unsigned char lds[];
@@ -487,6 +489,7 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenPara
     const bool rings_aligned = (ring0_addr & ((S << 2) - 1u)) == 0u;
 
     for (uint32_t c = blockIdx.x * kScreenWaves + w; c < C; c += gridDim.x * kScreenWaves) {
+        if (kMarked && !is_pending(out[c])) continue;
         const uint16_t* row = assign + (size_t)c * R;
         for (uint32_t i = lane; i < n_ring_words + M + 1u; i += kWave)
             mine[i] = (i < n_ring_words && (i >> p.slots_log2) == M) ? kNever : 0u;
@@ -595,7 +598,7 @@ __device__ __forceinline__ void unpack_pair(uint32_t word, uint32_t& finish0, ui
     finish1 = (word & 0xFFFFu) + (word >> 24);
 }
 
-template <bool kAligned, bool kPacked>
+template <bool kAligned, bool kPacked, bool kMarked>
 __global__ __launch_bounds__(kWideThreads) void k_screen_candidates_wide(ScreenParams p,
                                                                           const uint16_t* __restrict__ assign,
                                                                           ap_metrics* __restrict__ out, uint32_t C) {
@@ -624,6 +627,7 @@ __global__ __launch_bounds__(kWideThreads) void k_screen_candidates_wide(ScreenP
     const bool rings_aligned = (ring0_addr & ((S << 2) - 1u)) == 0u;
 
     for (uint32_t c = blockIdx.x; c < C; c += gridDim.x) {
+        if (kMarked && !is_pending(out[c])) continue;                        // the same for the whole workgroup
         const uint16_t* row = assign + (size_t)c * R;
         for (uint32_t i = tid; i < n_words; i += kWideThreads) slot[i] = (i >> p.slots_log2) == M ? kNever : 0u;
         if (tid < 2u) flag[tid] = rings_aligned ? 0u : 1u;
@@ -1339,6 +1343,154 @@ EvalKernel eval_kernel(bool hist16, bool len16) {
     return len16 ? k_eval_candidates<false, true> : k_eval_candidates<false, false>;
 }
 
+
+// ----------------------------------------------------------------------------------
+// sparse candidates: children of one parent row, given as lists of (request, replica) edits
+// ----------------------------------------------------------------------------------
+// Children are small modifications of a parent (Section 5.4 "Synthesis Configuration",
+// trade-off-aware mutation; Section 6.1 "Warm-start re-evolution": top candidates along with
+// their mutations).  A child's row is the parent's with its edits applied front to back; a later
+// edit of a request replaces an earlier one and an edit naming a request >= R changes nothing.
+//
+// With identical, always-available replicas the parent is analysed once (k_parent_occupancy):
+// peak[m] is the largest number of the parent's requests replica m has in service at the same
+// moment when nobody waits, i.e. the depth of the intervals [arrival, arrival + service).  A
+// child's requests on replica m are a subset of the parent's there plus the requests its edits
+// send to m, so their depth is at most peak[m] + (edits naming m).  Where that stays within B for
+// every replica no request of the child ever finds the B slots taken, nobody waits, and the
+// child's record is the nominal one - decided from the edit list alone, without its row.  Every
+// other child gets its row written out and goes through the dense path (screening, then replay).
+struct ChildParams {
+    const uint16_t* parent;       // [R]
+    const uint32_t* room;         // [M] B - peak[m], or 0 where the parent already exceeds B
+    const ap_metrics* nominal;
+    uint16_t* rows;               // [max_children][R] rows of the children the dense path has to look at
+    uint32_t R, M, key_bits;      // key_bits: bits of R - 1
+    uint32_t certify;             // 0: no shortcut (replicas differ, windows, parent not contention-free): rows for all
+};
+
+constexpr uint32_t kChildWaves = 4;
+constexpr uint32_t kChildThreads = kChildWaves * kWave;
+constexpr uint32_t kOccupancyBlock = kWave * 8u;  // parent ids per step of k_parent_occupancy
+
+// One wavefront per replica walks the parent row in arrival order.  Lane l holds the finish time
+// of the request that last used "slot" l; a request takes the lowest lane that is free at its
+// arrival (finish <= arrival), and the number of busy lanes plus one is the depth at that moment.
+// More than 64 at once is reported as 65 (B never exceeds 64).  peak[M] counts the parent's
+// requests that name no replica of the table.
+__global__ __launch_bounds__(kWave) void k_parent_occupancy(EvalParams p, const uint16_t* __restrict__ parent,
+                                                            uint32_t* __restrict__ peak, uint32_t* __restrict__ room) {
+    const uint32_t lane = threadIdx.x, m = blockIdx.x;
+    const DevReplica rp = p.rep[0];
+    uint32_t slot_finish = 0u, deepest = 0u, unknown = 0u;
+    uint32_t id[8], next_id[8];
+    auto fetch = [&](uint32_t (&into)[8], uint32_t r0) {
+#pragma unroll
+        for (uint32_t k = 0; k < 8u; ++k) {
+            const uint32_t r = r0 + k * kWave + lane;
+            into[k] = r < p.R ? (uint32_t)parent[r] : kNoKey;
+        }
+    };
+    fetch(next_id, 0u);
+    for (uint32_t r0 = 0; r0 < p.R; r0 += kOccupancyBlock) {
+#pragma unroll
+        for (uint32_t k = 0; k < 8u; ++k) id[k] = next_id[k];
+        if (r0 + kOccupancyBlock < p.R) fetch(next_id, r0 + kOccupancyBlock);
+        uint32_t arrival[8], finish[8];
+#pragma unroll
+        for (uint32_t k = 0; k < 8u; ++k) {
+            const uint32_t r = r0 + k * kWave + lane;
+            arrival[k] = finish[k] = 0u;
+            unknown += (id[k] != kNoKey && id[k] >= p.M) ? 1u : 0u;
+            if (id[k] == m) {
+                const uint32_t prm = p.prompt[r];
+                const uint32_t tpot = rp.c + rp.d * ((prm + 1023u) >> 10);
+                arrival[k] = p.arrival[r];
+                finish[k] = arrival[k] + rp.a + rp.b * prm + p.outlen[r] * tpot;
+            }
+        }
+#pragma unroll
+        for (uint32_t k = 0; k < 8u; ++k) {
+            unsigned long long todo = __ballot(id[k] == m);
+            while (todo != 0ull) {
+                const uint32_t from = (uint32_t)__ffsll((long long)todo) - 1u;
+                todo &= todo - 1ull;
+                const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)arrival[k], (int)from);
+                const uint32_t f = (uint32_t)__builtin_amdgcn_readlane((int)finish[k], (int)from);
+                const unsigned long long busy = __ballot(slot_finish > a);
+                deepest = max(deepest, (uint32_t)__popcll(busy) + 1u);
+                if (~busy != 0ull && lane == (uint32_t)__ffsll((long long)~busy) - 1u) slot_finish = f;
+            }
+        }
+    }
+    if (lane == 0u) {
+        peak[m] = deepest;
+        room[m] = deepest <= p.B ? p.B - deepest : 0u;
+    }
+    if (m == 0u) {
+        unknown = wave_sum_u32(unknown);
+        if (lane == 0u) peak[p.M] = unknown;
+    }
+}
+
+// One wavefront per child.  certify: count the child's edits per replica in LDS and compare with
+// the room the parent leaves; a child that passes gets the nominal record.  A child that does not
+// pass (too many edits for some replica, or an edit naming a replica outside the table) gets the
+// pending mark and its row: the parent's, then its edits in batches of 64, the lanes of a batch
+// that name the same request settled in favour of the highest lane, batches in list order.
+__global__ __launch_bounds__(kChildThreads) void k_certify_children(ChildParams p, const uint32_t* __restrict__ first,
+                                                                    const uint32_t* __restrict__ request,
+                                                                    const uint16_t* __restrict__ replica,
+                                                                    ap_metrics* __restrict__ out, uint32_t C) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    const uint32_t lane = threadIdx.x & 63u, w = wave_index();
+    uint32_t* count = reinterpret_cast<uint32_t*>(lds) + w * p.M;            // this wavefront's: edits per replica
+    for (uint32_t m = lane; m < p.M; m += kWave) count[m] = 0u;
+    for (uint32_t c = blockIdx.x * kChildWaves + w; c < C; c += gridDim.x * kChildWaves) {
+        const unsigned long long e0 = first[c], e1 = first[c + 1u];          // empty or reversed: no edits
+        bool dense = p.certify == 0u;
+        if (!dense) {
+            bool fail = false;
+#pragma unroll 4
+            for (unsigned long long e = e0 + lane; e < e1; e += kWave) {
+                const uint32_t r = request[e], m = replica[e];
+                if (r < p.R) {
+                    if (m < p.M) atomicAdd(&count[m], 1u);
+                    else fail = true;
+                }
+            }
+            for (uint32_t m = lane; m < p.M; m += kWave) {
+                fail = fail || count[m] > p.room[m];
+                count[m] = 0u;
+            }
+            dense = __ballot(fail) != 0ull;
+            if (lane < 8u) {
+                const unsigned long long* src = reinterpret_cast<const unsigned long long*>(p.nominal);
+                reinterpret_cast<unsigned long long*>(&out[c])[lane] = dense ? ~0ull : src[lane];
+            }
+        }
+        if (!dense) continue;
+        uint16_t* row = p.rows + (size_t)c * p.R;
+        if (p.R % 8u == 0u) {                                                // rows are then 16-byte aligned
+            const uint4* src = reinterpret_cast<const uint4*>(p.parent);
+            uint4* dst = reinterpret_cast<uint4*>(row);
+            for (uint32_t i = lane; i < p.R / 8u; i += kWave) dst[i] = src[i];
+        } else {
+            for (uint32_t i = lane; i < p.R; i += kWave) row[i] = p.parent[i];
+        }
+        for (unsigned long long b = e0; b < e1; b += kWave) {
+            __threadfence();                                                 // the copy, or the batch before, has landed
+            const unsigned long long e = b + lane;
+            const uint32_t r = e < e1 ? request[e] : kNoKey;
+            const uint16_t m = e < e1 ? replica[e] : (uint16_t)0;
+            uint32_t lo, hi;
+            wave_peers(r, p.R, p.key_bits, lo, hi);                          // lanes of this batch naming my request
+            const unsigned long long peers = ((unsigned long long)hi << 32) | lo;
+            if (e < e1 && r < p.R && ((peers >> lane) >> 1) == 0ull) row[r] = m;
+        }
+    }
+}
+
 }  // namespace
 
 struct ap_workload {
@@ -1381,7 +1533,68 @@ struct ap_workload {
     EvalParams reduce_eval{};
     uint32_t group_lds_bytes = 0, replay_lds_bytes = 0, reduce_lds_bytes = 0;
     bool pipeline = false;
+    // sparse candidates (ap_parent_set / ap_eval_children)
+    uint16_t* d_parent = nullptr;     // [R]
+    uint32_t* d_peak = nullptr;       // [AP_MAX_REPLICAS + 1] depth of the parent per replica, then its unknown ids
+    uint32_t* d_room = nullptr;       // [AP_MAX_REPLICAS]
+    uint16_t* d_rows = nullptr;       // [max_children][R]
+    size_t rows_bytes = 0;
+    uint32_t max_children = 0;
+    bool has_parent = false;
+    ChildParams child_params{};
 };
+
+// The dense path on C rows: screening where it applies, then the exact replay of what is left.
+// marked: only rows whose record carries the pending mark are looked at (screening applies).
+static ap_status launch_dense(const ap_workload* w, const uint16_t* d_assign, uint32_t C, ap_metrics* d_out,
+                              hipStream_t stream, bool marked) {
+    if (w->screen) {
+        const uint32_t blocks = std::min((C + kScreenWaves - 1u) / kScreenWaves, w->n_cu * 64u);
+        // rows start on 4-byte boundaries when R is even and the batch itself does
+        const bool aligned = (w->R % 2u == 0u) && (reinterpret_cast<uintptr_t>(d_assign) % 4u == 0u);
+        typedef void (*screen_fn)(ScreenParams, const uint16_t*, ap_metrics*, uint32_t);
+        if (w->screen_wide) {
+            static const screen_fn wide[8] = {
+                k_screen_candidates_wide<false, false, false>, k_screen_candidates_wide<true, false, false>,
+                k_screen_candidates_wide<false, true, false>,  k_screen_candidates_wide<true, true, false>,
+                k_screen_candidates_wide<false, false, true>,  k_screen_candidates_wide<true, false, true>,
+                k_screen_candidates_wide<false, true, true>,   k_screen_candidates_wide<true, true, true>};
+            // one candidate per workgroup while the grid stays moderate: workgroups finish at different
+            // times, and the hardware's queue of waiting workgroups balances that better than fixed shares
+            hipLaunchKernelGGL(wide[(aligned ? 1 : 0) + (w->screen_packed ? 2 : 0) + (marked ? 4 : 0)],
+                               dim3(std::min(C, w->n_cu * 64u)), dim3(kWideThreads), w->screen_wide_lds_bytes, stream,
+                               w->screen_params, d_assign, d_out, C);
+        } else {
+            static const screen_fn narrow[4] = {k_screen_candidates<false, false>, k_screen_candidates<true, false>,
+                                                k_screen_candidates<false, true>, k_screen_candidates<true, true>};
+            hipLaunchKernelGGL(narrow[(aligned ? 1 : 0) + (marked ? 2 : 0)], dim3(blocks), dim3(kScreenThreads),
+                               w->screen_lds_bytes, stream, w->screen_params, d_assign, d_out, C);
+        }
+        if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
+    }
+    const uint32_t pending_only = w->screen ? 1u : 0u;
+    if (w->pipeline) {
+        for (uint32_t c0 = 0; c0 < C; c0 += w->batch) {
+            const uint32_t n = std::min(w->batch, C - c0);
+            hipLaunchKernelGGL(k_group_requests, dim3(n), dim3(kGroupThreads), w->group_lds_bytes, stream, w->group_params,
+                               d_assign, d_out, c0, n, pending_only);
+            const uint32_t n_wg = (n * w->params.M + kReplayThreads - 1u) / kReplayThreads;
+            hipLaunchKernelGGL(k_replay_queues, dim3(n_wg), dim3(kReplayThreads), w->replay_lds_bytes, stream,
+                               w->replay_params, d_out, c0, n, pending_only);
+            hipLaunchKernelGGL(w->hist16 ? k_reduce_candidates<true> : k_reduce_candidates<false>, dim3(n), dim3(kThreads),
+                               w->reduce_lds_bytes, stream, w->reduce_eval, w->reduce_params, d_out, c0, n, pending_only);
+        }
+        if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
+        return AP_OK;
+    }
+    // After screening, most workgroups only find out that nothing is left for them: as many as can be
+    // resident at once look at all the records together.
+    const uint32_t grid = std::min(C, pending_only ? w->resident_grid : w->max_grid);
+    hipLaunchKernelGGL(eval_kernel(w->hist16, w->len16), dim3(grid), dim3(kThreads), w->lds_bytes, stream, w->params,
+                       d_assign, d_out, C, pending_only);
+    if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
+    return AP_OK;
+}
 
 extern "C" {
 
@@ -1392,7 +1605,7 @@ const char* ap_status_str(ap_status s) {
         case AP_ERR_RANGE: return "capacity of the device path exceeded";
         case AP_ERR_ALLOC: return "allocation failed";
         case AP_ERR_DEVICE: return "HIP call failed";
-        case AP_ERR_STATE: return "no cost model set";
+        case AP_ERR_STATE: return "no cost model (or, for children, no parent) set";
     }
     return "unknown status";
 }
@@ -1608,6 +1821,7 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
     p.penalty_bin = ap_hist_bin(slo->penalty_us);
     p.k99 = (uint32_t)((99ull * w->R + 99ull) / 100ull);
     w->has_model = false;
+    w->has_parent = false;    // its analysis belonged to the previous cost model
     w->params = p;
     w->lds_bytes = bytes;
     w->hist16 = hist16;
@@ -1734,47 +1948,77 @@ ap_status ap_eval_candidates(const ap_workload* w, const uint16_t* d_assign, uin
     if (!w->has_model) return AP_ERR_STATE;
     if (C == 0) return AP_OK;
     if (!d_assign || !d_out) return AP_ERR_INVALID;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    return launch_dense(w, d_assign, C, d_out, static_cast<hipStream_t>(hip_stream), false);
+}
+
+ap_status ap_parent_set(ap_workload* w, const uint16_t* parent, uint32_t max_children) {
+    if (!w || !parent || max_children == 0) return AP_ERR_INVALID;
+    if (!w->has_model) return AP_ERR_STATE;
+    if (hipSetDevice(w->device) != hipSuccess) return AP_ERR_DEVICE;
+    w->has_parent = false;
+    const size_t need = (size_t)max_children * w->R * sizeof(uint16_t);
+    if ((!w->d_parent && hipMalloc(&w->d_parent, (size_t)w->R * sizeof(uint16_t)) != hipSuccess) ||
+        (!w->d_peak && hipMalloc(&w->d_peak, sizeof(uint32_t) * (AP_MAX_REPLICAS + 1u)) != hipSuccess) ||
+        (!w->d_room && hipMalloc(&w->d_room, sizeof(uint32_t) * AP_MAX_REPLICAS) != hipSuccess)) {
+        (void)hipGetLastError();
+        return AP_ERR_ALLOC;
+    }
+    if (need > w->rows_bytes) {
+        if (w->d_rows && hipFree(w->d_rows) != hipSuccess) return AP_ERR_DEVICE;
+        w->d_rows = nullptr;
+        w->rows_bytes = 0;
+        if (hipMalloc(&w->d_rows, need) != hipSuccess) {
+            (void)hipGetLastError();
+            return AP_ERR_ALLOC;
+        }
+        w->rows_bytes = need;
+    }
+    if (hipMemcpy(w->d_parent, parent, (size_t)w->R * sizeof(uint16_t), hipMemcpyHostToDevice) != hipSuccess)
+        return AP_ERR_DEVICE;
+    const uint32_t M = w->params.M;
+    bool certify = false;
     if (w->screen) {
-        const uint32_t blocks = std::min((C + kScreenWaves - 1u) / kScreenWaves, w->n_cu * 64u);
-        // rows start on 4-byte boundaries when R is even and the batch itself does
-        const bool aligned = (w->R % 2u == 0u) && (reinterpret_cast<uintptr_t>(d_assign) % 4u == 0u);
-        if (w->screen_wide) {
-            void (*kernel)(ScreenParams, const uint16_t*, ap_metrics*, uint32_t) =
-                w->screen_packed ? (aligned ? k_screen_candidates_wide<true, true> : k_screen_candidates_wide<false, true>)
-                                 : (aligned ? k_screen_candidates_wide<true, false> : k_screen_candidates_wide<false, false>);
-            // one candidate per workgroup while the grid stays moderate: workgroups finish at different
-            // times, and the hardware's queue of waiting workgroups balances that better than fixed shares
-            hipLaunchKernelGGL(kernel, dim3(std::min(C, w->n_cu * 64u)), dim3(kWideThreads), w->screen_wide_lds_bytes,
-                               stream, w->screen_params, d_assign, d_out, C);
-        } else {
-            hipLaunchKernelGGL(aligned ? k_screen_candidates<true> : k_screen_candidates<false>, dim3(blocks),
-                               dim3(kScreenThreads), w->screen_lds_bytes, stream, w->screen_params, d_assign, d_out, C);
+        // the shortcut needs the nominal record, i.e. identical replicas that are always available
+        hipLaunchKernelGGL(k_parent_occupancy, dim3(M), dim3(kWave), 0, nullptr, w->params, w->d_parent, w->d_peak, w->d_room);
+        std::vector<uint32_t> peak(M + 1u);
+        if (hipGetLastError() != hipSuccess ||
+            hipMemcpy(peak.data(), w->d_peak, sizeof(uint32_t) * (M + 1u), hipMemcpyDeviceToHost) != hipSuccess) {
+            (void)hipGetLastError();
+            return AP_ERR_DEVICE;
         }
-        if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
+        // ... and a parent that is contention-free itself and names only replicas of the table
+        certify = peak[M] == 0u;
+        for (uint32_t m = 0; m < M; ++m) certify = certify && peak[m] <= w->params.B;
     }
-    const uint32_t pending_only = w->screen ? 1u : 0u;
-    if (w->pipeline) {
-        for (uint32_t c0 = 0; c0 < C; c0 += w->batch) {
-            const uint32_t n = std::min(w->batch, C - c0);
-            hipLaunchKernelGGL(k_group_requests, dim3(n), dim3(kGroupThreads), w->group_lds_bytes, stream, w->group_params,
-                               d_assign, d_out, c0, n, pending_only);
-            const uint32_t n_wg = (n * w->params.M + kReplayThreads - 1u) / kReplayThreads;
-            hipLaunchKernelGGL(k_replay_queues, dim3(n_wg), dim3(kReplayThreads), w->replay_lds_bytes, stream,
-                               w->replay_params, d_out, c0, n, pending_only);
-            hipLaunchKernelGGL(w->hist16 ? k_reduce_candidates<true> : k_reduce_candidates<false>, dim3(n), dim3(kThreads),
-                               w->reduce_lds_bytes, stream, w->reduce_eval, w->reduce_params, d_out, c0, n, pending_only);
-        }
-        if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
-        return AP_OK;
-    }
-    // After screening, most workgroups only find out that nothing is left for them: as many as can be
-    // resident at once look at all the records together.
-    const uint32_t grid = std::min(C, pending_only ? w->resident_grid : w->max_grid);
-    hipLaunchKernelGGL(eval_kernel(w->hist16, w->len16), dim3(grid), dim3(kThreads), w->lds_bytes, stream, w->params,
-                       d_assign, d_out, C, pending_only);
-    if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
+    ChildParams cp{};
+    cp.parent = w->d_parent;
+    cp.room = w->d_room;
+    cp.nominal = w->d_nominal;
+    cp.rows = w->d_rows;
+    cp.R = w->R;
+    cp.M = M;
+    cp.key_bits = 0;
+    while (((w->R - 1u) >> cp.key_bits) != 0u) ++cp.key_bits;
+    cp.certify = certify ? 1u : 0u;
+    w->child_params = cp;
+    w->max_children = max_children;
+    w->has_parent = true;
     return AP_OK;
+}
+
+ap_status ap_eval_children(const ap_workload* w, const uint32_t* d_edit_first, const uint32_t* d_edit_request,
+                           const uint16_t* d_edit_replica, uint32_t C, ap_metrics* d_out, void* hip_stream) {
+    if (!w) return AP_ERR_INVALID;
+    if (!w->has_model || !w->has_parent) return AP_ERR_STATE;
+    if (C == 0) return AP_OK;
+    if (!d_edit_first || !d_edit_request || !d_edit_replica || !d_out) return AP_ERR_INVALID;
+    if (C > w->max_children) return AP_ERR_RANGE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const uint32_t blocks = std::min((C + kChildWaves - 1u) / kChildWaves, w->n_cu * 64u);
+    hipLaunchKernelGGL(k_certify_children, dim3(blocks), dim3(kChildThreads), kChildWaves * w->child_params.M * 4u, stream,
+                       w->child_params, d_edit_first, d_edit_request, d_edit_replica, d_out, C);
+    if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
+    return launch_dense(w, w->d_rows, C, d_out, stream, w->child_params.certify != 0u);
 }
 
 ap_status ap_workload_destroy(ap_workload* w) {
@@ -1790,6 +2034,10 @@ ap_status ap_workload_destroy(ap_workload* w) {
     if (w->d_span_t) ok = (hipFree(w->d_span_t) == hipSuccess) && ok;
     if (w->d_pair) ok = (hipFree(w->d_pair) == hipSuccess) && ok;
     if (w->d_nominal) ok = (hipFree(w->d_nominal) == hipSuccess) && ok;
+    if (w->d_parent) ok = (hipFree(w->d_parent) == hipSuccess) && ok;
+    if (w->d_peak) ok = (hipFree(w->d_peak) == hipSuccess) && ok;
+    if (w->d_room) ok = (hipFree(w->d_room) == hipSuccess) && ok;
+    if (w->d_rows) ok = (hipFree(w->d_rows) == hipSuccess) && ok;
     delete w;
     return ok ? AP_OK : AP_ERR_DEVICE;
 }

@@ -43,6 +43,26 @@ class GpuWorkload:
         torch.cuda.synchronize()
         return to_records(d_out)
 
+    def set_parent(self, parent: np.ndarray, max_children: int) -> None:
+        binding.ap_parent_set(self.handle, parent, max_children)
+
+    def eval_children_device(self, d_first: torch.Tensor, d_request: torch.Tensor, d_replica: torch.Tensor,
+                             d_out: torch.Tensor | None = None) -> torch.Tensor:
+        """Edit lists as CUDA tensors (int32 [C+1], int32 [E], int16 [E]); returns the CUDA result tensor."""
+        assert d_first.is_cuda and d_first.element_size() == 4 and d_request.element_size() == 4
+        assert d_replica.element_size() == 2 and d_request.shape == d_replica.shape
+        C = d_first.shape[0] - 1
+        if d_out is None:
+            d_out = torch.full((C, 8), -1, dtype=torch.int64, device=d_first.device)
+        binding.ap_eval_children(self.handle, d_first.data_ptr(), d_request.data_ptr(), d_replica.data_ptr(), C,
+                                 d_out.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        return d_out
+
+    def eval_children(self, first: np.ndarray, request: np.ndarray, replica: np.ndarray) -> np.ndarray:
+        d_out = self.eval_children_device(*edit_lists_to_device(first, request, replica))
+        torch.cuda.synchronize()
+        return to_records(d_out)
+
     def close(self):
         if self.handle is not None:
             binding.ap_workload_destroy(self.handle)
@@ -53,6 +73,15 @@ class GpuWorkload:
 
     def __exit__(self, *exc):
         self.close()
+
+
+def edit_lists_to_device(first, request, replica):
+    """Upload edit lists; the two edit arrays get one spare element so that their pointers are valid when empty."""
+    first = np.ascontiguousarray(first, dtype=np.uint32)
+    request = np.concatenate([np.ascontiguousarray(request, dtype=np.uint32), np.zeros(1, np.uint32)])
+    replica = np.concatenate([np.ascontiguousarray(replica, dtype=np.uint16), np.zeros(1, np.uint16)])
+    return (torch.from_numpy(first.view(np.int32)).cuda(), torch.from_numpy(request.view(np.int32)).cuda(),
+            torch.from_numpy(replica.view(np.int16)).cuda())
 
 
 def to_records(d_out: torch.Tensor) -> np.ndarray:
