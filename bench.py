@@ -5,7 +5,9 @@ One step = one ap_eval_candidates call over the whole candidate batch of the cho
 configuration (all stages of the path), with trace, cost model and assignments already
 resident in HBM.  Prints ONE JSON line with the throughput, the HBM roofline of the
 evaluation kernel (algorithmic bytes / measured kernel time) and the CPU oracle timed on
-this host on a bounded sample of the same workload.
+this host on a bounded sample of the same workload.  Where the configuration is a mutation
+sweep the same candidates are also scored from their edit lists (ap_eval_children) and
+reported in a `sparse_children` object beside the dense figures.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 0..4] [--rate-scale S]
 """
@@ -32,9 +34,11 @@ KERNEL_SOURCE = os.path.join(ROOT, "paper_2604_07144_amd", "csrc", "ap_eval.hip"
 # Keyed by configuration; valid only for the kernel source whose hash is recorded with it.
 MEASURED_TRAFFIC = {
     # cfg: (sha256 of the kernel source when measured, bytes per call)
-    4: ("cf0ac7fe2799b79139138f7d20e9c35a12f1198469b1bafe5fb31f0d58beab97", 4311175191),
-    3: ("cf0ac7fe2799b79139138f7d20e9c35a12f1198469b1bafe5fb31f0d58beab97", 543642513),
+    4: ("5fbc304d0d75da8fe9b80ab675e0b06a45ed674adf54bde74de9bffa371913fc", 4312060765),
+    3: ("5fbc304d0d75da8fe9b80ab675e0b06a45ed674adf54bde74de9bffa371913fc", 543538571),
 }
+# the same for one ap_eval_children call on the sparse form of configs[4]
+MEASURED_TRAFFIC_CHILDREN = {4: ("5fbc304d0d75da8fe9b80ab675e0b06a45ed674adf54bde74de9bffa371913fc", 134367648)}
 
 
 def kernel_source_hash() -> str:
@@ -43,9 +47,9 @@ def kernel_source_hash() -> str:
         return hashlib.sha256(f.read()).hexdigest()
 
 
-def measured_traffic(cfg: int):
+def measured_traffic(cfg: int, table=None):
     """Recorded HBM traffic for this configuration, or None once the kernels have changed since."""
-    rec = MEASURED_TRAFFIC.get(cfg)
+    rec = (MEASURED_TRAFFIC if table is None else table).get(cfg)
     if rec is None or rec[0] != kernel_source_hash():
         return None
     return rec[1]
@@ -198,7 +202,9 @@ def main() -> int:
                         "kernel_ms_median": float(np.median(child_ms)), "kernel_ms_min": float(np.min(child_ms)),
                         "edits": n_edits, "algorithmic_bytes": child_alg,
                         "roofline": {"bound": "hbm", "achieved": child_alg / child_s / 1e9, "peak": HBM_PEAK_GBS,
-                                     "unit": "GB/s", "frac": child_alg / child_s / 1e9 / HBM_PEAK_GBS, "traffic": None},
+                                     "unit": "GB/s", "frac": child_alg / child_s / 1e9 / HBM_PEAK_GBS,
+                                     "traffic": measured_traffic(args.config, MEASURED_TRAFFIC_CHILDREN)
+                                     if C == tr.C and args.rate_scale == 1.0 else None},
                         "ap_parent_set_ms": parent_set_ms,
                         "matches_dense": bool(got2.tobytes() == got.tobytes())}
     finally:

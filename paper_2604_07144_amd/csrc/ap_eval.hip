@@ -488,7 +488,18 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenPara
     const uint32_t n_full = R / kScreenBlock;
     const bool rings_aligned = (ring0_addr & ((S << 2) - 1u)) == 0u;
 
-    for (uint32_t c = blockIdx.x * kScreenWaves + w; c < C; c += gridDim.x * kScreenWaves) {
+    // kMarked: a workgroup owns a run of consecutive candidates (at most one per thread), looks at all
+    // their records at once and leaves when none is marked - the usual case
+    uint32_t c_first = blockIdx.x * kScreenWaves, c_end = C, c_step = gridDim.x * kScreenWaves;
+    if (kMarked) {
+        const uint32_t per = (C + gridDim.x - 1u) / gridDim.x;
+        c_first = blockIdx.x * per;
+        c_end = min(C, c_first + per);
+        c_step = kScreenWaves;
+        const uint32_t mine = c_first + threadIdx.x;
+        if (__syncthreads_or(threadIdx.x < per && mine < c_end && is_pending(out[mine]) ? 1 : 0) == 0) return;
+    }
+    for (uint32_t c = c_first + w; c < c_end; c += c_step) {
         if (kMarked && !is_pending(out[c])) continue;
         const uint16_t* row = assign + (size_t)c * R;
         for (uint32_t i = lane; i < n_ring_words + M + 1u; i += kWave)
@@ -626,7 +637,17 @@ __global__ __launch_bounds__(kWideThreads) void k_screen_candidates_wide(ScreenP
     // alternatives are reached by flipping address bits, which needs the rings aligned to their size
     const bool rings_aligned = (ring0_addr & ((S << 2) - 1u)) == 0u;
 
-    for (uint32_t c = blockIdx.x; c < C; c += gridDim.x) {
+    // kMarked: a workgroup owns a run of consecutive candidates (at most one per thread), looks at all
+    // their records at once and leaves when none is marked - the usual case
+    uint32_t c_first = blockIdx.x, c_end = C, c_step = gridDim.x;
+    if (kMarked) {
+        const uint32_t per = (C + gridDim.x - 1u) / gridDim.x;
+        c_first = blockIdx.x * per;
+        c_end = min(C, c_first + per);
+        c_step = 1u;
+        if (__syncthreads_or(tid < per && c_first + tid < c_end && is_pending(out[c_first + tid]) ? 1 : 0) == 0) return;
+    }
+    for (uint32_t c = c_first; c < c_end; c += c_step) {
         if (kMarked && !is_pending(out[c])) continue;                        // the same for the whole workgroup
         const uint16_t* row = assign + (size_t)c * R;
         for (uint32_t i = tid; i < n_words; i += kWideThreads) slot[i] = (i >> p.slots_log2) == M ? kNever : 0u;
@@ -1445,29 +1466,53 @@ __global__ __launch_bounds__(kChildThreads) void k_certify_children(ChildParams 
     extern __shared__ __align__(16) unsigned char lds[];
     const uint32_t lane = threadIdx.x & 63u, w = wave_index();
     uint32_t* count = reinterpret_cast<uint32_t*>(lds) + w * p.M;            // this wavefront's: edits per replica
+    uint32_t* room = reinterpret_cast<uint32_t*>(lds) + kChildWaves * p.M;   // the workgroup's copy of p.room
     for (uint32_t m = lane; m < p.M; m += kWave) count[m] = 0u;
+    unsigned long long nominal_word = 0ull;                                  // lanes 0..7: the record of a child that passes
+    if (p.certify != 0u) {
+        for (uint32_t m = threadIdx.x; m < p.M; m += kChildThreads) room[m] = p.room[m];
+        if (lane < 8u) nominal_word = reinterpret_cast<const unsigned long long*>(p.nominal)[lane];
+    }
+    __syncthreads();
     for (uint32_t c = blockIdx.x * kChildWaves + w; c < C; c += gridDim.x * kChildWaves) {
         const unsigned long long e0 = first[c], e1 = first[c + 1u];          // empty or reversed: no edits
         bool dense = p.certify == 0u;
         if (!dense) {
             bool fail = false;
-#pragma unroll 4
-            for (unsigned long long e = e0 + lane; e < e1; e += kWave) {
-                const uint32_t r = request[e], m = replica[e];
-                if (r < p.R) {
-                    if (m < p.M) atomicAdd(&count[m], 1u);
-                    else fail = true;
+            // rounds of kInFlight loads of both arrays per lane; the next round is requested before the
+            // current one is counted, so the lists stream in without a pause between rounds
+            constexpr uint32_t kInFlight = 8;
+            uint32_t r[kInFlight], m[kInFlight], r_next[kInFlight], m_next[kInFlight];
+            auto fetch = [&](uint32_t (&rq)[kInFlight], uint32_t (&rp)[kInFlight], unsigned long long b) {
+#pragma unroll
+                for (uint32_t k = 0; k < kInFlight; ++k) {
+                    const unsigned long long e = b + k * kWave + lane;
+                    rq[k] = e < e1 ? request[e] : kNoKey;                    // past the end: names no request
+                    rp[k] = e < e1 ? (uint32_t)replica[e] : 0u;
+                }
+            };
+            if (e0 < e1) fetch(r_next, m_next, e0);
+            for (unsigned long long b = e0; b < e1; b += kInFlight * kWave) {
+#pragma unroll
+                for (uint32_t k = 0; k < kInFlight; ++k) {
+                    r[k] = r_next[k];
+                    m[k] = m_next[k];
+                }
+                if (b + kInFlight * kWave < e1) fetch(r_next, m_next, b + kInFlight * kWave);
+#pragma unroll
+                for (uint32_t k = 0; k < kInFlight; ++k) {
+                    if (r[k] < p.R) {
+                        if (m[k] < p.M) atomicAdd(&count[m[k]], 1u);
+                        else fail = true;
+                    }
                 }
             }
             for (uint32_t m = lane; m < p.M; m += kWave) {
-                fail = fail || count[m] > p.room[m];
+                fail = fail || count[m] > room[m];
                 count[m] = 0u;
             }
             dense = __ballot(fail) != 0ull;
-            if (lane < 8u) {
-                const unsigned long long* src = reinterpret_cast<const unsigned long long*>(p.nominal);
-                reinterpret_cast<unsigned long long*>(&out[c])[lane] = dense ? ~0ull : src[lane];
-            }
+            if (lane < 8u) reinterpret_cast<unsigned long long*>(&out[c])[lane] = dense ? ~0ull : nominal_word;
         }
         if (!dense) continue;
         uint16_t* row = p.rows + (size_t)c * p.R;
@@ -1561,13 +1606,17 @@ static ap_status launch_dense(const ap_workload* w, const uint16_t* d_assign, ui
                 k_screen_candidates_wide<false, true, true>,   k_screen_candidates_wide<true, true, true>};
             // one candidate per workgroup while the grid stays moderate: workgroups finish at different
             // times, and the hardware's queue of waiting workgroups balances that better than fixed shares
-            hipLaunchKernelGGL(wide[(aligned ? 1 : 0) + (w->screen_packed ? 2 : 0) + (marked ? 4 : 0)],
-                               dim3(std::min(C, w->n_cu * 64u)), dim3(kWideThreads), w->screen_wide_lds_bytes, stream,
-                               w->screen_params, d_assign, d_out, C);
+            // marked: runs of candidates per workgroup (at most one per thread), few workgroups
+            const uint32_t grid = marked ? std::max((C + kWideThreads - 1u) / kWideThreads, std::min(C, w->n_cu * 4u))
+                                         : std::min(C, w->n_cu * 64u);
+            hipLaunchKernelGGL(wide[(aligned ? 1 : 0) + (w->screen_packed ? 2 : 0) + (marked ? 4 : 0)], dim3(grid),
+                               dim3(kWideThreads), w->screen_wide_lds_bytes, stream, w->screen_params, d_assign, d_out, C);
         } else {
             static const screen_fn narrow[4] = {k_screen_candidates<false, false>, k_screen_candidates<true, false>,
                                                 k_screen_candidates<false, true>, k_screen_candidates<true, true>};
-            hipLaunchKernelGGL(narrow[(aligned ? 1 : 0) + (marked ? 2 : 0)], dim3(blocks), dim3(kScreenThreads),
+            const uint32_t grid = marked ? std::max((C + kScreenThreads - 1u) / kScreenThreads, std::min(blocks, w->n_cu * 8u))
+                                         : blocks;
+            hipLaunchKernelGGL(narrow[(aligned ? 1 : 0) + (marked ? 2 : 0)], dim3(grid), dim3(kScreenThreads),
                                w->screen_lds_bytes, stream, w->screen_params, d_assign, d_out, C);
         }
         if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
@@ -2015,7 +2064,7 @@ ap_status ap_eval_children(const ap_workload* w, const uint32_t* d_edit_first, c
     if (C > w->max_children) return AP_ERR_RANGE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const uint32_t blocks = std::min((C + kChildWaves - 1u) / kChildWaves, w->n_cu * 64u);
-    hipLaunchKernelGGL(k_certify_children, dim3(blocks), dim3(kChildThreads), kChildWaves * w->child_params.M * 4u, stream,
+    hipLaunchKernelGGL(k_certify_children, dim3(blocks), dim3(kChildThreads), (kChildWaves + 1u) * w->child_params.M * 4u, stream,
                        w->child_params, d_edit_first, d_edit_request, d_edit_replica, d_out, C);
     if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
     return launch_dense(w, w->d_rows, C, d_out, stream, w->child_params.certify != 0u);
