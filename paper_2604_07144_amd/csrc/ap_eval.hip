@@ -1392,65 +1392,109 @@ struct ChildParams {
 
 constexpr uint32_t kChildWaves = 4;
 constexpr uint32_t kChildThreads = kChildWaves * kWave;
-constexpr uint32_t kOccupancyBlock = kWave * 8u;  // parent ids per step of k_parent_occupancy
+constexpr uint32_t kOccupancyThreads = 256;
+constexpr uint32_t kOccupancyWaves = kOccupancyThreads / kWave;
+constexpr uint32_t kOccupancyPerThread = 16;      // parent ids per thread and step
+constexpr uint32_t kOccupancyStep = kOccupancyThreads * kOccupancyPerThread;
 
-// One wavefront per replica walks the parent row in arrival order.  Lane l holds the finish time
-// of the request that last used "slot" l; a request takes the lowest lane that is free at its
-// arrival (finish <= arrival), and the number of busy lanes plus one is the depth at that moment.
-// More than 64 at once is reported as 65 (B never exceeds 64).  peak[M] counts the parent's
-// requests that name no replica of the table.
-__global__ __launch_bounds__(kWave) void k_parent_occupancy(EvalParams p, const uint16_t* __restrict__ parent,
-                                                            uint32_t* __restrict__ peak, uint32_t* __restrict__ room) {
-    const uint32_t lane = threadIdx.x, m = blockIdx.x;
+// One workgroup per replica walks the parent row in steps of 4096 ids.  All its threads pick out
+// the replica's requests of the step (each thread 16 consecutive ids; counts scanned across the
+// workgroup; request indices written to an LDS list in arrival order), then the first wavefront
+// takes the list through the queue-free schedule: lane l holds the finish time of the request
+// that last used "slot" l, a request takes the lowest lane that is free at its arrival (finish
+// <= arrival), and the number of busy lanes plus one is the depth at that moment.  More than 64
+// at once is reported as 65 (B never exceeds 64).  peak[M] counts the parent's requests that
+// name no replica of the table.
+__global__ __launch_bounds__(kOccupancyThreads) void k_parent_occupancy(EvalParams p, const uint16_t* __restrict__ parent,
+                                                                        uint32_t* __restrict__ peak,
+                                                                        uint32_t* __restrict__ room) {
+    __shared__ uint32_t list[kOccupancyStep];     // requests of this replica in the current step
+    __shared__ uint32_t wave_total[kOccupancyWaves];
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wv = wave_index(), m = blockIdx.x;
     const DevReplica rp = p.rep[0];
     uint32_t slot_finish = 0u, deepest = 0u, unknown = 0u;
-    uint32_t id[8], next_id[8];
-    auto fetch = [&](uint32_t (&into)[8], uint32_t r0) {
+    // my 16 ids of a step: two 16-byte loads where the row has them all (the parent buffer is 16-byte
+    // aligned and a thread's run starts at a multiple of 16 ids), one by one at the ragged end
+    auto fetch = [&](uint4 (&into)[2], uint32_t r0) {
+        const uint32_t at = r0 + tid * kOccupancyPerThread;
+        if (at + kOccupancyPerThread <= p.R) {
+            into[0] = reinterpret_cast<const uint4*>(parent + at)[0];
+            into[1] = reinterpret_cast<const uint4*>(parent + at)[1];
+        } else {
+            uint32_t w[8];
 #pragma unroll
-        for (uint32_t k = 0; k < 8u; ++k) {
-            const uint32_t r = r0 + k * kWave + lane;
-            into[k] = r < p.R ? (uint32_t)parent[r] : kNoKey;
+            for (uint32_t k = 0; k < 8u; ++k) {
+                const uint32_t lo = at + 2u * k < p.R ? (uint32_t)parent[at + 2u * k] : 0xFFFFu;
+                const uint32_t hi = at + 2u * k + 1u < p.R ? (uint32_t)parent[at + 2u * k + 1u] : 0xFFFFu;
+                w[k] = lo | (hi << 16);
+            }
+            into[0] = make_uint4(w[0], w[1], w[2], w[3]);
+            into[1] = make_uint4(w[4], w[5], w[6], w[7]);
         }
     };
-    fetch(next_id, 0u);
-    for (uint32_t r0 = 0; r0 < p.R; r0 += kOccupancyBlock) {
+    uint4 ids_next[2];
+    fetch(ids_next, 0u);
+    for (uint32_t r0 = 0; r0 < p.R; r0 += kOccupancyStep) {
+        // as a bit mask: which of my 16 ids name this replica (absent ones read as 0xFFFF and are skipped below)
+        const uint32_t mine = r0 + tid * kOccupancyPerThread;
+        const uint32_t w[8] = {ids_next[0].x, ids_next[0].y, ids_next[0].z, ids_next[0].w,
+                               ids_next[1].x, ids_next[1].y, ids_next[1].z, ids_next[1].w};
+        if (r0 + kOccupancyStep < p.R) fetch(ids_next, r0 + kOccupancyStep);   // in flight during the rest of this step
+        uint32_t hits = 0u;
 #pragma unroll
-        for (uint32_t k = 0; k < 8u; ++k) id[k] = next_id[k];
-        if (r0 + kOccupancyBlock < p.R) fetch(next_id, r0 + kOccupancyBlock);
-        uint32_t arrival[8], finish[8];
+        for (uint32_t k = 0; k < kOccupancyPerThread; ++k) {
+            const uint32_t id = (w[k >> 1] >> ((k & 1u) << 4)) & 0xFFFFu;
+            const bool present = mine + k < p.R;
+            hits |= (present && id == m ? 1u : 0u) << k;
+            unknown += (present && id >= p.M) ? 1u : 0u;
+        }
+        const uint32_t n_mine = (uint32_t)__popc(hits);
+        const uint32_t upto = wave_inclusive_scan(n_mine, lane);
+        if (lane == 63u) wave_total[wv] = upto;
+        __syncthreads();
+        uint32_t before = upto - n_mine, n_list = 0u;
 #pragma unroll
-        for (uint32_t k = 0; k < 8u; ++k) {
-            const uint32_t r = r0 + k * kWave + lane;
-            arrival[k] = finish[k] = 0u;
-            unknown += (id[k] != kNoKey && id[k] >= p.M) ? 1u : 0u;
-            if (id[k] == m) {
-                const uint32_t prm = p.prompt[r];
-                const uint32_t tpot = rp.c + rp.d * ((prm + 1023u) >> 10);
-                arrival[k] = p.arrival[r];
-                finish[k] = arrival[k] + rp.a + rp.b * prm + p.outlen[r] * tpot;
+        for (uint32_t j = 0; j < kOccupancyWaves; ++j) {
+            before += j < wv ? wave_total[j] : 0u;
+            n_list += wave_total[j];
+        }
+        for (uint32_t h = hits; h != 0u; h &= h - 1u) list[before++] = mine + (uint32_t)__ffs((int)h) - 1u;
+        __syncthreads();
+        if (wv == 0u) {
+            for (uint32_t i0 = 0; i0 < n_list; i0 += kWave) {
+                uint32_t arrival = 0u, finish = 0u;
+                if (i0 + lane < n_list) {
+                    const uint32_t r = list[i0 + lane];
+                    const uint32_t prm = p.prompt[r];
+                    arrival = p.arrival[r];
+                    finish = arrival + rp.a + rp.b * prm + p.outlen[r] * (rp.c + rp.d * ((prm + 1023u) >> 10));
+                }
+                const uint32_t n_here = min(kWave, n_list - i0);
+                for (uint32_t k = 0; k < n_here; ++k) {
+                    const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)arrival, (int)k);
+                    const uint32_t f = (uint32_t)__builtin_amdgcn_readlane((int)finish, (int)k);
+                    const unsigned long long busy = __ballot(slot_finish > a);
+                    deepest = max(deepest, (uint32_t)__popcll(busy) + 1u);
+                    if (~busy != 0ull && lane == (uint32_t)__ffsll((long long)~busy) - 1u) slot_finish = f;
+                }
             }
         }
-#pragma unroll
-        for (uint32_t k = 0; k < 8u; ++k) {
-            unsigned long long todo = __ballot(id[k] == m);
-            while (todo != 0ull) {
-                const uint32_t from = (uint32_t)__ffsll((long long)todo) - 1u;
-                todo &= todo - 1ull;
-                const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)arrival[k], (int)from);
-                const uint32_t f = (uint32_t)__builtin_amdgcn_readlane((int)finish[k], (int)from);
-                const unsigned long long busy = __ballot(slot_finish > a);
-                deepest = max(deepest, (uint32_t)__popcll(busy) + 1u);
-                if (~busy != 0ull && lane == (uint32_t)__ffsll((long long)~busy) - 1u) slot_finish = f;
-            }
-        }
+        // the next step's scan may overwrite wave_total and list only after everyone is done with them
+        __syncthreads();
     }
-    if (lane == 0u) {
+    if (tid == 0u) {
         peak[m] = deepest;
         room[m] = deepest <= p.B ? p.B - deepest : 0u;
     }
     if (m == 0u) {
         unknown = wave_sum_u32(unknown);
-        if (lane == 0u) peak[p.M] = unknown;
+        if (lane == 0u) wave_total[wv] = unknown;
+        __syncthreads();
+        if (tid == 0u) {
+            uint32_t total = 0u;
+            for (uint32_t j = 0; j < kOccupancyWaves; ++j) total += wave_total[j];
+            peak[p.M] = total;
+        }
     }
 }
 
@@ -2005,6 +2049,7 @@ ap_status ap_parent_set(ap_workload* w, const uint16_t* parent, uint32_t max_chi
     if (!w->has_model) return AP_ERR_STATE;
     if (hipSetDevice(w->device) != hipSuccess) return AP_ERR_DEVICE;
     w->has_parent = false;
+    if ((uint64_t)max_children > (UINT64_MAX / sizeof(uint16_t)) / w->R) return AP_ERR_ALLOC;     // the rows cannot exist
     const size_t need = (size_t)max_children * w->R * sizeof(uint16_t);
     if ((!w->d_parent && hipMalloc(&w->d_parent, (size_t)w->R * sizeof(uint16_t)) != hipSuccess) ||
         (!w->d_peak && hipMalloc(&w->d_peak, sizeof(uint32_t) * (AP_MAX_REPLICAS + 1u)) != hipSuccess) ||
@@ -2028,7 +2073,8 @@ ap_status ap_parent_set(ap_workload* w, const uint16_t* parent, uint32_t max_chi
     bool certify = false;
     if (w->screen) {
         // the shortcut needs the nominal record, i.e. identical replicas that are always available
-        hipLaunchKernelGGL(k_parent_occupancy, dim3(M), dim3(kWave), 0, nullptr, w->params, w->d_parent, w->d_peak, w->d_room);
+        hipLaunchKernelGGL(k_parent_occupancy, dim3(M), dim3(kOccupancyThreads), 0, nullptr, w->params, w->d_parent, w->d_peak,
+                           w->d_room);
         std::vector<uint32_t> peak(M + 1u);
         if (hipGetLastError() != hipSuccess ||
             hipMemcpy(peak.data(), w->d_peak, sizeof(uint32_t) * (M + 1u), hipMemcpyDeviceToHost) != hipSuccess) {
