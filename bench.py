@@ -28,23 +28,27 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 TABLE_BYTES_PER_REQUEST = 16   # arrival + prefill/decode/tpot-class inputs, per replica type
 
-KERNEL_SOURCE = os.path.join(ROOT, "paper_2604_07144_amd", "csrc", "ap_eval.hip")
+KERNEL_SOURCE_DIR = os.path.join(ROOT, "paper_2604_07144_amd", "csrc")
 # HBM bytes per ap_eval_candidates call from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch, summed over
 # the call's kernels, scaled by what the same counters read for a device copy of known size; see profiles/).
-# Keyed by configuration; valid only for the kernel source whose hash is recorded with it.
+# Keyed by configuration; valid only for the library source (all of csrc/) whose hash is recorded with it.
 MEASURED_TRAFFIC = {
     # cfg: (sha256 of the kernel source when measured, bytes per call)
-    4: ("43fb2478160aa0a23111167082a6479cf8899aa4bc0a21bbcdf7addd86290d7b", 4312770589),
-    3: ("43fb2478160aa0a23111167082a6479cf8899aa4bc0a21bbcdf7addd86290d7b", 543682157),
+    4: ("45993df7eff3811e4fe9d2f783a94b182536819b6bb11b03cfc655476b206411", 4311362228),
+    3: ("45993df7eff3811e4fe9d2f783a94b182536819b6bb11b03cfc655476b206411", 543783591),
 }
 # the same for one ap_eval_children call on the sparse form of configs[4]
-MEASURED_TRAFFIC_CHILDREN = {4: ("43fb2478160aa0a23111167082a6479cf8899aa4bc0a21bbcdf7addd86290d7b", 134331835)}
+MEASURED_TRAFFIC_CHILDREN = {4: ("45993df7eff3811e4fe9d2f783a94b182536819b6bb11b03cfc655476b206411", 134357920)}
 
 
 def kernel_source_hash() -> str:
+    """sha256 over every file of the library's source directory, in name order."""
     import hashlib
-    with open(KERNEL_SOURCE, "rb") as f:
-        return hashlib.sha256(f.read()).hexdigest()
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(KERNEL_SOURCE_DIR)):
+        with open(os.path.join(KERNEL_SOURCE_DIR, name), "rb") as f:
+            h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()
 
 
 def measured_traffic(cfg: int, table=None):

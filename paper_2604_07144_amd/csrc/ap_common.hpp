@@ -1,0 +1,226 @@
+// Constants, kernel parameter blocks and wavefront / histogram helpers shared by all kernels.
+#ifndef AP_COMMON_HPP
+#define AP_COMMON_HPP
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <cstring>
+#include <new>
+#include <type_traits>
+#include <vector>
+
+#include "autopoiesis_eval.h"
+
+namespace {
+
+constexpr uint32_t kWave = 64;
+constexpr uint32_t kWaves = 8;                  // wavefronts per workgroup
+constexpr uint32_t kThreads = kWave * kWaves;   // 512
+constexpr uint32_t kBins = 4096;
+constexpr uint32_t kBinsPerThread = kBins / kThreads;
+constexpr uint32_t kMaxGroups = 8;              // 64-request groups per wavefront per chunk
+constexpr uint32_t kMaxChunk = kThreads * kMaxGroups;
+constexpr uint32_t kNever = 0xFFFFFFFFu;        // "no such time": larger than every reachable time
+constexpr uint32_t kNoKey = 0xFFFFFFFFu;
+
+struct DevReplica {
+    uint32_t a, b, c, d;      // cost coefficients
+    uint32_t t_on, t_off;     // window, relative microseconds (t_off == kNever: never leaves)
+};
+
+struct EvalParams {
+    const uint32_t* arrival;  // [R] relative microseconds
+    const uint32_t* prompt;   // [R]
+    const uint32_t* outlen;   // [R]
+    const DevReplica* rep;    // [M]
+    uint32_t R, M, B, chunk, key_bits;
+    uint32_t slo_ttft, slo_tpot;
+    uint32_t penalty_bin, k99;
+    uint64_t penalty;
+    // byte offsets into dynamic LDS
+    uint32_t off_slots, off_sorted, off_close, off_cnt, off_qstart, off_list, off_arr, off_prompt, off_out, off_misc;
+};
+
+// ----------------------------------------------------------------------------------
+// wavefront helpers (64 lanes)
+// ----------------------------------------------------------------------------------
+// Index of this wavefront in its workgroup, as a wave-uniform (scalar) value: loops and
+// table lookups that depend on it then stay on the scalar unit.
+__device__ __forceinline__ uint32_t wave_index() {
+    return (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+}
+
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v, uint32_t lane) {
+#pragma unroll
+    for (uint32_t d = 1; d < kWave; d <<= 1) {
+        uint32_t t = (uint32_t)__shfl_up((int)v, d);
+        if (lane >= d) v += t;
+    }
+    return v;
+}
+
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
+#pragma unroll
+    for (uint32_t d = 32; d >= 1; d >>= 1) v += (uint32_t)__shfl_xor((int)v, d);
+    return v;
+}
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+#pragma unroll
+    for (uint32_t d = 32; d >= 1; d >>= 1) v = max(v, (uint32_t)__shfl_xor((int)v, d));
+    return v;
+}
+
+__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v) {
+#pragma unroll
+    for (uint32_t d = 32; d >= 1; d >>= 1) v += (unsigned long long)__shfl_xor((long long)v, d);
+    return v;
+}
+
+// 4096-bin log-linear histogram map for values below 2^32.
+__device__ __forceinline__ uint32_t hist_bin_u32(uint32_t v) {
+    // With s = max(floor(log2 v), 7) - 7 the bin is (s << 7) + (v >> s): below 128 that is v itself, above it
+    // v >> s lies in [128, 256), which supplies both the sub-bin and the +1 of the octave number.
+    const uint32_t s = 24u - min((uint32_t)__clz((int)v), 24u);             // __clz(0) is 32
+    return (s << 7) + (v >> s);
+}
+
+__device__ __forceinline__ unsigned long long hist_lower_edge(uint32_t bin) {
+    if (bin < 128u) return bin;
+    return (unsigned long long)(128u | (bin & 127u)) << ((bin >> 7) - 1u);
+}
+
+// Ascending bitonic sort of one value per lane across the wavefront.
+__device__ __forceinline__ uint32_t wave_sort_ascending(uint32_t v, uint32_t lane) {
+#pragma unroll
+    for (uint32_t k = 2; k <= kWave; k <<= 1) {
+#pragma unroll
+        for (uint32_t j = k >> 1; j > 0; j >>= 1) {
+            const uint32_t other = (uint32_t)__shfl_xor((int)v, (int)j);
+            const bool keep_min = ((lane & j) == 0u) == ((lane & k) == 0u);
+            v = keep_min ? min(v, other) : max(v, other);
+        }
+    }
+    return v;
+}
+
+// Lane i receives lane i + 1's value; lane 63 receives `last`.
+__device__ __forceinline__ uint32_t wave_shift_down(uint32_t v, uint32_t last) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)last, (int)v, 0x130 /* wave_shl:1 */, 0xF, 0xF, false);
+}
+
+// The lanes of this wavefront whose key equals mine, as the two halves of a 64-bit mask, for
+// the lanes whose key is below `n_keys` (the others get a meaningless mask): one ballot per bit
+// of n_keys - 1; a lane keeps the lanes that agree with it on that bit.
+__device__ __forceinline__ void wave_peers(uint32_t key, uint32_t n_keys, uint32_t key_bits, uint32_t& lo, uint32_t& hi) {
+    const unsigned long long ranked = __ballot(key < n_keys);
+    lo = (uint32_t)ranked;
+    hi = (uint32_t)(ranked >> 32);
+    for (uint32_t b = 0; b < key_bits; ++b) {
+        const uint32_t mine = (uint32_t)__builtin_amdgcn_sbfe((int)key, b, 1u);  // all ones if my bit b is set, else 0
+        const unsigned long long set = __ballot(mine != 0u);
+        lo &= ~((uint32_t)set ^ mine);                                         // lanes whose bit equals mine
+        hi &= ~((uint32_t)(set >> 32) ^ mine);
+    }
+}
+
+// lane i takes lane i - 1's value; lane 0 takes `first`
+__device__ __forceinline__ uint32_t wave_shift_up(uint32_t v, uint32_t first) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)first, (int)v, 0x138 /* wave_shr:1 */, 0xF, 0xF, false);
+}
+
+// The three 4096-bin histograms of a candidate in LDS.  When R < 65536 no count can exceed 16
+// bits, so two bins share a 32-bit word (half the LDS, half the clearing and scanning).
+template <bool kHist16>
+__device__ __forceinline__ void hist_add(uint32_t* hist, uint32_t which, uint32_t bin, uint32_t count) {
+    if (kHist16) atomicAdd(&hist[which * (kBins / 2u) + (bin >> 1)], count << ((bin & 1u) << 4));
+    else atomicAdd(&hist[which * kBins + bin], count);
+}
+
+template <bool kHist16>
+__device__ __forceinline__ uint32_t hist_get(const uint32_t* hist, uint32_t which, uint32_t bin) {
+    if (kHist16) return (hist[which * (kBins / 2u) + (bin >> 1)] >> ((bin & 1u) << 4)) & 0xFFFFu;
+    return hist[which * kBins + bin];
+}
+
+template <bool kHist16>
+__device__ __forceinline__ void hist_clear(uint32_t* hist) {
+    for (uint32_t i = threadIdx.x; i < (kHist16 ? 3u * kBins / 2u : 3u * kBins); i += kThreads) hist[i] = 0u;
+}
+
+// Block-wide end of one candidate: fold the per-lane sums, add the rejected requests at the
+// penalty value, find the three p99 bins by a prefix sum over the histograms and write the
+// record.  Called by all kThreads threads; `hist` holds the served requests' counts.
+template <bool kHist16>
+__device__ __forceinline__ void finish_candidate(const EvalParams& p, uint32_t* hist, unsigned long long* acc64,
+                                                 uint32_t* acc32, uint32_t* wtot, unsigned long long s_e2e,
+                                                 unsigned long long s_ttft, unsigned long long s_tpot,
+                                                 uint32_t last_fin, uint32_t n_ok, uint32_t n_rej,
+                                                 ap_metrics* __restrict__ dst) {
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t w = wave_index();
+    s_e2e = wave_sum_u64(s_e2e);
+    s_ttft = wave_sum_u64(s_ttft);
+    s_tpot = wave_sum_u64(s_tpot);
+    last_fin = wave_max_u32(last_fin);
+    n_ok = wave_sum_u32(n_ok);
+    n_rej = wave_sum_u32(n_rej);
+    if (lane == 0) {
+        atomicAdd(&acc64[0], s_e2e);
+        atomicAdd(&acc64[1], s_ttft);
+        atomicAdd(&acc64[2], s_tpot);
+        atomicMax(&acc32[0], last_fin);
+        atomicAdd(&acc32[1], n_ok);
+        atomicAdd(&acc32[2], n_rej);
+    }
+    __syncthreads();
+    const uint32_t rejected = acc32[2];
+    if (tid < 3u && rejected) hist_add<kHist16>(hist, tid, p.penalty_bin, rejected);
+    __syncthreads();
+
+    // p99: block-wide prefix sum over the bins, kBinsPerThread bins per thread, three histograms at once
+    uint32_t part[3], incl[3];
+#pragma unroll
+    for (uint32_t h = 0; h < 3u; ++h) {
+        part[h] = 0;
+#pragma unroll
+        for (uint32_t i = 0; i < kBinsPerThread; ++i) part[h] += hist_get<kHist16>(hist, h, kBinsPerThread * tid + i);
+        incl[h] = wave_inclusive_scan(part[h], lane);
+        if (lane == 63u) wtot[h * kWaves + w] = incl[h];
+    }
+    __syncthreads();
+#pragma unroll
+    for (uint32_t h = 0; h < 3u; ++h) {
+        uint32_t before = 0;
+        for (uint32_t ww = 0; ww < w; ++ww) before += wtot[h * kWaves + ww];
+        const uint32_t hi = before + incl[h], lo = hi - part[h];
+        if (lo < p.k99 && p.k99 <= hi) {
+            uint32_t run = lo, b = 0;
+            for (; b + 1u < kBinsPerThread; ++b) {
+                run += hist_get<kHist16>(hist, h, kBinsPerThread * tid + b);
+                if (run >= p.k99) break;
+            }
+            acc32[3 + h] = kBinsPerThread * tid + b;
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        ap_metrics mt;
+        mt.sum_e2e_us = acc64[0] + (unsigned long long)rejected * p.penalty;
+        mt.sum_ttft_us = acc64[1] + (unsigned long long)rejected * p.penalty;
+        mt.sum_tpot_us = acc64[2] + (unsigned long long)rejected * p.penalty;
+        mt.makespan_us = acc32[0];
+        mt.p99_ttft_us = hist_lower_edge(acc32[3]);
+        mt.p99_tpot_us = hist_lower_edge(acc32[4]);
+        mt.p99_e2e_us = hist_lower_edge(acc32[5]);
+        mt.slo_ok = acc32[1];
+        mt.n_rejected = rejected;
+        *dst = mt;
+    }
+}
+
+}  // namespace
+
+#endif  // AP_COMMON_HPP
