@@ -35,7 +35,9 @@ class OrcMetrics(C.Structure):
 class OrcProblem(C.Structure):
     _fields_ = [("R", C.c_uint32), ("arrival_us", C.c_void_p), ("prompt_len", C.c_void_p),
                 ("out_len", C.c_void_p), ("M", C.c_uint32), ("replicas", C.c_void_p), ("B", C.c_uint32),
-                ("slo_ttft_us", C.c_uint64), ("slo_tpot_us", C.c_uint64), ("penalty_us", C.c_uint64)]
+                ("slo_ttft_us", C.c_uint64), ("slo_tpot_us", C.c_uint64), ("penalty_us", C.c_uint64),
+                ("n_types", C.c_uint32), ("rep_type", C.c_void_p), ("prefill_tab", C.c_void_p),
+                ("tpot_tab", C.c_void_p)]
 
 
 class OrcDetail(C.Structure):
@@ -104,7 +106,22 @@ class Oracle:
         self.problem = OrcProblem(self.R, self.arrival.ctypes.data, self.prompt.ctypes.data,
                                   self.out.ctypes.data, self.M,
                                   C.cast(self.replicas, C.c_void_p).value, int(B),
-                                  int(slo_ttft_us), int(slo_tpot_us), int(penalty_us))
+                                  int(slo_ttft_us), int(slo_tpot_us), int(penalty_us), 0, None, None, None)
+
+    def set_cost_tables(self, rep_type, prefill_us, tpot_us) -> "Oracle":
+        """Switch to the tabulated cost model: ``rep_type`` uint32[M], tables uint32[T][R] (microseconds of
+        prefill, microseconds per output token).  The windows of the replica table stay in force."""
+        self.rep_type = np.ascontiguousarray(rep_type, dtype=np.uint32)
+        self.prefill_tab = np.ascontiguousarray(prefill_us, dtype=np.uint32)
+        self.tpot_tab = np.ascontiguousarray(tpot_us, dtype=np.uint32)
+        assert self.rep_type.shape == (self.M,) and self.prefill_tab.ndim == 2
+        assert self.prefill_tab.shape == self.tpot_tab.shape and self.prefill_tab.shape[1] == self.R
+        assert int(self.rep_type.max()) < self.prefill_tab.shape[0]
+        self.problem.n_types = self.prefill_tab.shape[0]
+        self.problem.rep_type = self.rep_type.ctypes.data
+        self.problem.prefill_tab = self.prefill_tab.ctypes.data
+        self.problem.tpot_tab = self.tpot_tab.ctypes.data
+        return self
 
     @classmethod
     def from_trace(cls, tr, **override):

@@ -98,6 +98,17 @@ typedef struct {
     uint64_t slo_ttft_us;
     uint64_t slo_tpot_us;
     uint64_t penalty_us;
+    /* Tabulated cost model (optional; all three NULL = the linear stand-in above).  The serving
+     * simulator's estimate of a request's prefill time and of its time per output token on a
+     * given kind of replica can come from any model - the paper's own is the roofline sum of
+     * Appendix "Serving Simulator" - so here it is an input: replica m is of type rep_type[m]
+     * (< n_types) and request r costs prefill_tab[type * R + r] microseconds of prefill and
+     * tpot_tab[type * R + r] microseconds per output token there; decode = out_len * tpot as
+     * before.  The coefficients of `replicas` are then unused; the windows still apply. */
+    uint32_t n_types;
+    const uint32_t *rep_type;
+    const uint32_t *prefill_tab;
+    const uint32_t *tpot_tab;
 } orc_problem;
 
 /* Optional per-request record of one replay, for the invariant tests. */
@@ -181,6 +192,11 @@ int orc_eval_row(const orc_problem *p, const uint16_t *row, orc_metrics *out, co
             uint64_t prefill = (uint64_t)rep->prefill_base_us + (uint64_t)rep->prefill_per_tok_us * prompt;
             uint64_t kctx = (prompt + 1023u) / 1024u;
             uint64_t per_tok = (uint64_t)rep->decode_base_us + (uint64_t)rep->decode_per_kctx_us * kctx;
+            if (p->prefill_tab) {                   /* tabulated cost model */
+                size_t at = (size_t)p->rep_type[m] * R + r;
+                prefill = p->prefill_tab[at];
+                per_tok = p->tpot_tab[at];
+            }
             uint64_t decode = (uint64_t)p->out_len[r] * per_tok;
 
             uint32_t best = 0;

@@ -396,3 +396,45 @@ def test_mutation_sweep_rows_are_children_of_the_jsq_parent():
                 lst = request[first[c]:first[c + 1]].astype(np.int64)
                 assert (np.diff(lst) > 0).all()
     assert len({tuple(r) for r in want.tolist()}) > 1        # the children really differ in their metrics
+
+
+# ----------------------------------------------------------------------------- tabulated cost model
+def test_cost_tables_hand_worked():
+    """Three requests on one single-slot replica with arbitrary table values, worked by hand:
+    r0 starts at 0 (ttft 100, decode 2*10, finish 120); r1 arrives at 50, starts at 120 (ttft 70+200,
+    decode 1*20, finish 340); r2 arrives at 60, starts at 340 (ttft 280+300, decode 3*30, finish 730)."""
+    orc = make([0, 50, 60], [7, 7, 7], [2, 1, 3], B=1).set_cost_tables([0], [[100, 200, 300]], [[10, 20, 30]])
+    m, d = orc.eval_row(np.zeros(3, np.uint16), detail=True)
+    assert d["start_us"].tolist() == [0, 120, 340] and d["finish_us"].tolist() == [120, 340, 730]
+    assert d["ttft_us"].tolist() == [100, 270, 580] and d["tpot_us"].tolist() == [10, 20, 30]
+    assert (int(m["sum_ttft_us"]), int(m["sum_e2e_us"]), int(m["sum_tpot_us"]), int(m["makespan_us"])) == (950, 1080, 60, 730)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_cost_tables_filled_from_the_linear_model_change_nothing(seed):
+    """The tabulated branch fed with the linear stand-in's own values (one table row per coefficient set,
+    replica -> row through rep_type) must reproduce the linear branch, which the pins above hold in place:
+    catches a transposed table, a wrong type lookup, a table that is read but not used."""
+    rng = np.random.default_rng(300 + seed)
+    n, M, B = 400, 6, 3
+    arrival = np.cumsum(rng.integers(0, 900, n)).astype(np.uint64)
+    prompt, out = rng.integers(1, 5000, n), rng.integers(1, 300, n)
+    kinds = [traces.COEF_STANDARD, traces.COEF_FAST, traces.COEF_SLOW]
+    rep_type = rng.integers(0, 3, M)
+    coef = [kinds[t] for t in rep_type]
+    t_on = rng.integers(0, int(arrival[-1]) // 2, M).tolist()
+    t_off = [int(arrival[-1]) // 2 + int(x) for x in rng.integers(1, int(arrival[-1]), M)]
+    rows = rng.integers(0, M + 1, size=(8, n)).astype(np.uint16)
+    want = make(arrival, prompt, out, coef, t_on, t_off, B=B).eval_batch(rows)
+    prefill = np.stack([a + b * prompt for a, b, _, _ in kinds])
+    tpot = np.stack([c + d * ((prompt + 1023) // 1024) for _, _, c, d in kinds])
+    # the coefficients of the replica table are ignored once tables are set: give it nonsense ones
+    tabled = make(arrival, prompt, out, [(1, 1, 1, 1)] * M, t_on, t_off, B=B).set_cost_tables(rep_type, prefill, tpot)
+    assert (tabled.eval_batch(rows) == want).all()
+    # relabelling the types (rows of both tables permuted, rep_type mapped) changes nothing
+    perm = np.array([2, 0, 1])
+    inv = np.argsort(perm)
+    relabelled = make(arrival, prompt, out, [(1, 1, 1, 1)] * M, t_on, t_off, B=B).set_cost_tables(
+        inv[rep_type], prefill[perm], tpot[perm])
+    assert (relabelled.eval_batch(rows) == want).all()
+    assert len({tuple(r) for r in want.tolist()}) > 1
