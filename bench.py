@@ -100,6 +100,8 @@ def main() -> int:
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the oracle sample (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-children", action="store_true", help="skip the sparse (edit-list) leg of a mutation sweep")
+    ap.add_argument("--cost-tables", action="store_true",
+                    help="pass the configuration's cost model as per-type tables (ap_costtable_set) instead of coefficients")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a 1 GiB device copy (reference dispatch for the HBM byte counters)")
     args = ap.parse_args()
@@ -129,8 +131,18 @@ def main() -> int:
 
     h = binding.ap_workload_create(tr.arrival_us, tr.prompt_len, tr.out_len)
     try:
-        binding.ap_costmodel_set(h, binding.make_replicas(tr.coef, tr.t_on_us, tr.t_off_us), tr.B,
-                                 tr.slo_ttft_us, tr.slo_tpot_us, tr.penalty_us)
+        if args.cost_tables:
+            # the same cost model, evaluated here once per replica type and request and handed over as tables
+            kinds = sorted({tuple(int(x) for x in row) for row in tr.coef})
+            rep_type = np.array([kinds.index(tuple(int(x) for x in row)) for row in tr.coef], dtype=np.uint32)
+            prompt = tr.prompt_len.astype(np.int64)
+            prefill = np.stack([a + b * prompt for a, b, _, _ in kinds]).astype(np.uint32)
+            tpot = np.stack([c + d * ((prompt + 1023) // 1024) for _, _, c, d in kinds]).astype(np.uint32)
+            binding.ap_costtable_set(h, rep_type, tr.t_on_us, tr.t_off_us, tr.B, tr.slo_ttft_us, tr.slo_tpot_us,
+                                     tr.penalty_us, prefill, tpot)
+        else:
+            binding.ap_costmodel_set(h, binding.make_replicas(tr.coef, tr.t_on_us, tr.t_off_us), tr.B,
+                                     tr.slo_ttft_us, tr.slo_tpot_us, tr.penalty_us)
         stream = torch.cuda.current_stream()
 
         def step():
@@ -219,7 +231,7 @@ def main() -> int:
         binding.ap_workload_destroy(h)
 
     sims = C * R
-    full_batch = (C == tr.C and args.rate_scale == 1.0)
+    full_batch = (C == tr.C and args.rate_scale == 1.0 and not args.cost_tables)
     ms_per_step = wall * 1e3 / args.steps
     avg_kernel_s = float(np.mean(kernel_ms)) * 1e-3
     alg = algorithmic_bytes(C, R, n_types)
@@ -239,7 +251,8 @@ def main() -> int:
         "dtype": "u32",
         "data": "synthetic",
         "config": {"workload": f"configs[{args.config}] {tr.spec.name}: C={C} R={R} M={M} B={tr.B}"
-                               + (f" arrival rate x{args.rate_scale:g}" if args.rate_scale != 1.0 else ""),
+                               + (f" arrival rate x{args.rate_scale:g}" if args.rate_scale != 1.0 else "")
+                               + (" (cost model passed as tables)" if args.cost_tables else ""),
                    "candidates": C, "requests": R, "replicas": M, "slots": tr.B, "replica_types": n_types},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.config) if full_batch else None,

@@ -113,6 +113,28 @@ ap_status ap_workload_create(const uint64_t *arrival_us, const int32_t *prompt_l
  * Synchronous (small host-to-device copies, one small kernel). */
 ap_status ap_costmodel_set(ap_workload *w, const ap_replica *replicas, uint32_t M, uint32_t B, const ap_slo *slo);
 
+/* A replica whose service times come from tables: its type selects the table row, its window
+ * is as in ap_replica. */
+typedef struct {
+    uint32_t type;
+    uint64_t t_on_us;
+    uint64_t t_off_us;
+} ap_typed_replica;
+
+/* Attach (or replace) a tabulated cost model: the serving simulator's estimate of every request's
+ * prefill time and time per output token on every kind of replica is an input, so any cost model
+ * can be plugged in - the paper's own is the roofline sum of Appendix "Serving Simulator"
+ * (serve-latency equation: T_prefill(s^p) plus the decode steps).  Service time of request r on a
+ * replica of type t, in microseconds:
+ *     prefill = prefill_us[t * R + r],   tpot = tpot_us[t * R + r],   decode = out_len[r] * tpot
+ * Everything else (B slots, windows, SLOs, penalty, metrics) is as for ap_costmodel_set, and so are
+ * the range proof (AP_ERR_RANGE, previous model kept), the sizing of device buffers and the errors.
+ *   replicas            : HOST array of M entries, copied; type < n_types (AP_ERR_INVALID otherwise).
+ *   prefill_us, tpot_us : HOST arrays, uint32 [n_types][R], copied.  n_types * R must be below 2^32.
+ * Synchronous.  Replaces a model set by ap_costmodel_set and vice versa; discards the parent, if any. */
+ap_status ap_costtable_set(ap_workload *w, const ap_typed_replica *replicas, uint32_t M, uint32_t B, const ap_slo *slo,
+                           const uint32_t *prefill_us, const uint32_t *tpot_us, uint32_t n_types);
+
 /* Score C candidates.
  *   d_assign : DEVICE pointer, uint16 [C][R] row-major; d_assign[c*R + r] is the replica of request r
  *              under candidate c.  A value >= M is not an error: that request is rejected.

@@ -23,6 +23,8 @@ REPLICA_DTYPE = np.dtype([("prefill_base_us", "<u4"), ("prefill_per_tok_us", "<u
 METRICS_DTYPE = np.dtype([("sum_e2e_us", "<u8"), ("sum_ttft_us", "<u8"), ("sum_tpot_us", "<u8"),
                           ("makespan_us", "<u8"), ("p99_ttft_us", "<u8"), ("p99_tpot_us", "<u8"),
                           ("p99_e2e_us", "<u8"), ("slo_ok", "<u4"), ("n_rejected", "<u4")])
+TYPED_REPLICA_DTYPE = np.dtype({"names": ["type", "t_on_us", "t_off_us"], "formats": ["<u4", "<u8", "<u8"],
+                                "offsets": [0, 8, 16], "itemsize": 24})
 assert REPLICA_DTYPE.itemsize == 32 and METRICS_DTYPE.itemsize == 64
 
 
@@ -51,6 +53,9 @@ def lib() -> C.CDLL:
         L.ap_workload_create.restype = C.c_int
         L.ap_costmodel_set.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.POINTER(ApSlo)]
         L.ap_costmodel_set.restype = C.c_int
+        L.ap_costtable_set.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.POINTER(ApSlo), C.c_void_p,
+                                       C.c_void_p, C.c_uint32]
+        L.ap_costtable_set.restype = C.c_int
         L.ap_eval_candidates.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p]
         L.ap_eval_candidates.restype = C.c_int
         L.ap_parent_set.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32]
@@ -117,6 +122,22 @@ def ap_costmodel_set(workload: int, replicas: np.ndarray, B: int, slo_ttft_us: i
     slo = ApSlo(int(slo_ttft_us), int(slo_tpot_us), int(penalty_us))
     _check(lib().ap_costmodel_set(workload, replicas.ctypes.data, replicas.shape[0], int(B), C.byref(slo)),
            "ap_costmodel_set")
+
+
+def ap_costtable_set(workload: int, rep_type, t_on_us, t_off_us, B: int, slo_ttft_us: int, slo_tpot_us: int,
+                     penalty_us: int, prefill_us, tpot_us) -> None:
+    """Host arrays in: replica types and windows (length M), cost tables uint32[T][R]."""
+    rep = np.zeros(len(rep_type), dtype=TYPED_REPLICA_DTYPE)
+    rep["type"] = np.asarray(rep_type, dtype=np.uint32)
+    rep["t_on_us"] = np.asarray(t_on_us, dtype=np.uint64)
+    rep["t_off_us"] = np.asarray(t_off_us, dtype=np.uint64)
+    prefill = np.ascontiguousarray(prefill_us, dtype=np.uint32)
+    tpot = np.ascontiguousarray(tpot_us, dtype=np.uint32)
+    if prefill.ndim != 2 or prefill.shape != tpot.shape:
+        raise ValueError("prefill_us and tpot_us must be 2-D arrays [n_types][R] of one shape")
+    slo = ApSlo(int(slo_ttft_us), int(slo_tpot_us), int(penalty_us))
+    _check(lib().ap_costtable_set(workload, rep.ctypes.data, rep.shape[0], int(B), C.byref(slo), prefill.ctypes.data,
+                                  tpot.ctypes.data, prefill.shape[0]), "ap_costtable_set")
 
 
 def ap_eval_candidates(workload: int, d_assign_ptr: int, n_candidates: int, d_out_ptr: int, stream: int = 0) -> None:

@@ -106,9 +106,10 @@ __global__ __launch_bounds__(kOccupancyThreads) void k_parent_occupancy(EvalPara
                 uint32_t arrival = 0u, finish = 0u;
                 if (i0 + lane < n_list) {
                     const uint32_t r = list[i0 + lane];
-                    const uint32_t prm = p.prompt[r];
+                    uint32_t prefill, tpot;
+                    request_cost(p.tab_prefill, p.tab_tpot, rp, r, p.prompt[r], prefill, tpot);
                     arrival = p.arrival[r];
-                    finish = arrival + rp.a + rp.b * prm + p.outlen[r] * (rp.c + rp.d * ((prm + 1023u) >> 10));
+                    finish = arrival + prefill + p.outlen[r] * tpot;
                 }
                 const uint32_t n_here = min(kWave, n_list - i0);
                 for (uint32_t k = 0; k < n_here; ++k) {

@@ -26,7 +26,7 @@ constexpr uint32_t kNever = 0xFFFFFFFFu;        // "no such time": larger than e
 constexpr uint32_t kNoKey = 0xFFFFFFFFu;
 
 struct DevReplica {
-    uint32_t a, b, c, d;      // cost coefficients
+    uint32_t a, b, c, d;      // cost coefficients; with cost tables: a = first entry of the replica's type (type * R)
     uint32_t t_on, t_off;     // window, relative microseconds (t_off == kNever: never leaves)
 };
 
@@ -35,6 +35,8 @@ struct EvalParams {
     const uint32_t* prompt;   // [R]
     const uint32_t* outlen;   // [R]
     const DevReplica* rep;    // [M]
+    const uint32_t* tab_prefill;  // [T][R] microseconds of prefill per replica type and request, or null:
+    const uint32_t* tab_tpot;     // [T][R] microseconds per output token       the linear stand-in applies
     uint32_t R, M, B, chunk, key_bits;
     uint32_t slo_ttft, slo_tpot;
     uint32_t penalty_bin, k99;
@@ -42,6 +44,27 @@ struct EvalParams {
     // byte offsets into dynamic LDS
     uint32_t off_slots, off_sorted, off_close, off_cnt, off_qstart, off_list, off_arr, off_prompt, off_out, off_misc;
 };
+
+// Prefill time and time per output token of request r (prompt length `prompt`) on a replica:
+// the linear stand-in for the serve-latency equation, or the caller's tables (any cost model
+// evaluated beforehand, e.g. the roofline sums of Appendix "Serving Simulator").
+template <bool kTabled>
+__device__ __forceinline__ void request_cost(const uint32_t* __restrict__ tab_prefill, const uint32_t* __restrict__ tab_tpot,
+                                             const DevReplica& rp, uint32_t r, uint32_t prompt, uint32_t& prefill,
+                                             uint32_t& tpot) {
+    if (kTabled) {
+        prefill = tab_prefill[rp.a + r];
+        tpot = tab_tpot[rp.a + r];
+    } else {
+        prefill = rp.a + rp.b * prompt;
+        tpot = rp.c + rp.d * ((prompt + 1023u) >> 10);
+    }
+}
+__device__ __forceinline__ void request_cost(const uint32_t* tab_prefill, const uint32_t* tab_tpot, const DevReplica& rp,
+                                             uint32_t r, uint32_t prompt, uint32_t& prefill, uint32_t& tpot) {
+    if (tab_prefill != nullptr) request_cost<true>(tab_prefill, tab_tpot, rp, r, prompt, prefill, tpot);
+    else request_cost<false>(tab_prefill, tab_tpot, rp, r, prompt, prefill, tpot);
+}
 
 // ----------------------------------------------------------------------------------
 // wavefront helpers (64 lanes)

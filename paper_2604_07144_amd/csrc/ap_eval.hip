@@ -54,9 +54,13 @@ uint32_t plan_lds(EvalParams& p, uint32_t chunk, bool hist16, bool len16) {
 
 using EvalKernel = void (*)(EvalParams, const uint16_t*, ap_metrics*, uint32_t, uint32_t);
 
-EvalKernel eval_kernel(bool hist16, bool len16) {
-    if (hist16) return len16 ? k_eval_candidates<true, true> : k_eval_candidates<true, false>;
-    return len16 ? k_eval_candidates<false, true> : k_eval_candidates<false, false>;
+EvalKernel eval_kernel(bool hist16, bool len16, bool tabled) {
+    static const EvalKernel variants[8] = {
+        k_eval_candidates<false, false, false>, k_eval_candidates<true, false, false>,
+        k_eval_candidates<false, true, false>,  k_eval_candidates<true, true, false>,
+        k_eval_candidates<false, false, true>,  k_eval_candidates<true, false, true>,
+        k_eval_candidates<false, true, true>,   k_eval_candidates<true, true, true>};
+    return variants[(hist16 ? 1 : 0) + (len16 ? 2 : 0) + (tabled ? 4 : 0)];
 }
 
 }  // namespace
@@ -72,6 +76,10 @@ struct ap_workload {
     uint32_t* d_prompt = nullptr;
     uint32_t* d_out = nullptr;
     DevReplica* d_rep = nullptr;      // capacity AP_MAX_REPLICAS
+    uint32_t* d_tab_prefill = nullptr;  // [T][R] cost tables (ap_costtable_set), kept for the largest T seen
+    uint32_t* d_tab_tpot = nullptr;
+    size_t tab_entries = 0;
+    bool tabled = false;              // the current cost model reads the tables
     uint32_t* d_span = nullptr;       // [R] contention-free service intervals in ticks, valid when screen is set
     uint32_t* d_span_t = nullptr;     // the same, lane-major for the one-wavefront screening kernel
     uint32_t* d_pair = nullptr;       // one word per two requests (eight-wavefront screening kernel, when it fits)
@@ -162,7 +170,7 @@ static ap_status launch_dense(const ap_workload* w, const uint16_t* d_assign, ui
     // After screening, most workgroups only find out that nothing is left for them: as many as can be
     // resident at once look at all the records together.
     const uint32_t grid = std::min(C, pending_only ? w->resident_grid : w->max_grid);
-    hipLaunchKernelGGL(eval_kernel(w->hist16, w->len16), dim3(grid), dim3(kThreads), w->lds_bytes, stream, w->params,
+    hipLaunchKernelGGL(eval_kernel(w->hist16, w->len16, w->tabled), dim3(grid), dim3(kThreads), w->lds_bytes, stream, w->params,
                        d_assign, d_out, C, pending_only);
     if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
     return AP_OK;
@@ -261,8 +269,13 @@ ap_status ap_workload_create(const uint64_t* arrival_us, const int32_t* prompt_l
     return AP_OK;
 }
 
-ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t M, uint32_t B, const ap_slo* slo) {
+// Shared by ap_costmodel_set (rep_type == nullptr: the coefficients of `replicas` apply) and
+// ap_costtable_set (replica m is of type rep_type[m] < T and the HOST tables [T][R] apply; the
+// coefficients are ignored).
+static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint32_t M, uint32_t B, const ap_slo* slo,
+                                const uint32_t* rep_type, const uint32_t* tab_prefill, const uint32_t* tab_tpot, uint32_t T) {
     if (!w || !replicas || !slo || M == 0 || B == 0) return AP_ERR_INVALID;
+    const bool tabled = rep_type != nullptr;
     for (uint32_t m = 0; m < M; ++m)
         if (replicas[m].t_on_us > replicas[m].t_off_us) return AP_ERR_INVALID;
     if (M > AP_MAX_REPLICAS || B > AP_MAX_SLOTS) return AP_ERR_RANGE;
@@ -279,28 +292,40 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
         latest = std::max(latest, rp.t_on_us - w->base_us);
     }
     if (latest > limit) return AP_ERR_RANGE;
-    // distinct coefficient sets
-    std::vector<const ap_replica*> kinds;
+    // distinct kinds of replica (coefficient sets, or types with tables), each by its first replica
+    std::vector<uint32_t> kinds;
     for (uint32_t m = 0; m < M; ++m) {
         bool seen = false;
-        for (const ap_replica* k : kinds)
-            seen = seen || (k->prefill_base_us == replicas[m].prefill_base_us &&
-                            k->prefill_per_tok_us == replicas[m].prefill_per_tok_us &&
-                            k->decode_base_us == replicas[m].decode_base_us &&
-                            k->decode_per_kctx_us == replicas[m].decode_per_kctx_us);
-        if (!seen) kinds.push_back(&replicas[m]);
+        for (uint32_t k : kinds)
+            seen = seen || (tabled ? rep_type[k] == rep_type[m]
+                                   : (replicas[k].prefill_base_us == replicas[m].prefill_base_us &&
+                                      replicas[k].prefill_per_tok_us == replicas[m].prefill_per_tok_us &&
+                                      replicas[k].decode_base_us == replicas[m].decode_base_us &&
+                                      replicas[k].decode_per_kctx_us == replicas[m].decode_per_kctx_us));
+        if (!seen) kinds.push_back(m);
     }
+    // prefill time and time per token of request r on the kind whose first replica is k
+    auto host_cost = [&](uint32_t k, uint32_t r, uint64_t& prefill, uint64_t& tpot) {
+        if (tabled) {
+            prefill = tab_prefill[(size_t)rep_type[k] * w->R + r];
+            tpot = tab_tpot[(size_t)rep_type[k] * w->R + r];
+        } else {
+            // each term stays far below 2^64: coefficients < 2^32, lengths < 2^31
+            const uint64_t prompt = (uint64_t)w->h_prompt[r];
+            prefill = (uint64_t)replicas[k].prefill_base_us + (uint64_t)replicas[k].prefill_per_tok_us * prompt;
+            tpot = (uint64_t)replicas[k].decode_base_us + (uint64_t)replicas[k].decode_per_kctx_us * ((prompt + 1023u) >> 10);
+        }
+    };
     uint64_t total = latest;
     uint64_t latest_unqueued = 0;      // latest finish if nobody ever waited (arrival + service)
     uint64_t longest_pair = 0;         // longest time from the arrival of request 2q to the unqueued finish of 2q or 2q+1
     uint64_t service_sum = 0;
     for (uint32_t r = 0; r < w->R; ++r) {
-        const uint64_t prompt = (uint64_t)w->h_prompt[r], outl = (uint64_t)w->h_out[r];
+        const uint64_t outl = (uint64_t)w->h_out[r];
         uint64_t worst = 0;
-        for (const ap_replica* k : kinds) {
-            // each term stays far below 2^64: coefficients < 2^32, lengths < 2^31
-            uint64_t prefill = (uint64_t)k->prefill_base_us + (uint64_t)k->prefill_per_tok_us * prompt;
-            uint64_t tpot = (uint64_t)k->decode_base_us + (uint64_t)k->decode_per_kctx_us * ((prompt + 1023u) >> 10);
+        for (uint32_t k : kinds) {
+            uint64_t prefill, tpot;
+            host_cost(k, r, prefill, tpot);
             if (tpot > limit || prefill > limit) return AP_ERR_RANGE;
             uint64_t svc = prefill + outl * tpot;
             worst = std::max(worst, svc);
@@ -331,7 +356,7 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
     uint32_t bytes = 0, chunk = 0;
     {   // what the kernel itself declares (nothing today) comes off the dynamic part
         hipFuncAttributes attr;
-        if (hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(eval_kernel(hist16, w->len16))) != hipSuccess)
+        if (hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(eval_kernel(hist16, w->len16, tabled))) != hipSuccess)
             return AP_ERR_DEVICE;
         lds_cap -= (int)std::min<size_t>(attr.sharedSizeBytes, (size_t)lds_cap);
     }
@@ -357,10 +382,10 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
     for (uint32_t m = 0; m < M; ++m) {
         const ap_replica& rp = replicas[m];
         DevReplica& d = dev[m];
-        d.a = rp.prefill_base_us;
-        d.b = rp.prefill_per_tok_us;
-        d.c = rp.decode_base_us;
-        d.d = rp.decode_per_kctx_us;
+        d.a = tabled ? rep_type[m] * w->R : rp.prefill_base_us;     // T * R < 2^32 was checked by the caller
+        d.b = tabled ? 0u : rp.prefill_per_tok_us;
+        d.c = tabled ? 0u : rp.decode_base_us;
+        d.d = tabled ? 0u : rp.decode_per_kctx_us;
         if (rp.t_on_us >= rp.t_off_us || rp.t_off_us <= w->base_us) {
             d.t_on = 0;      // the window is empty or closed before the trace: nothing is ever served
             d.t_off = 0;
@@ -369,8 +394,30 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
             d.t_off = (uint32_t)std::min<uint64_t>(rp.t_off_us - w->base_us, kNever);
         }
     }
+    if (tabled) {
+        const size_t entries = (size_t)T * w->R;
+        if (entries > w->tab_entries) {
+            if ((w->d_tab_prefill && hipFree(w->d_tab_prefill) != hipSuccess) ||
+                (w->d_tab_tpot && hipFree(w->d_tab_tpot) != hipSuccess))
+                return AP_ERR_DEVICE;
+            w->d_tab_prefill = w->d_tab_tpot = nullptr;
+            w->tab_entries = 0;
+            w->has_model = false;     // the previous model may have pointed at the freed tables
+            if (hipMalloc(&w->d_tab_prefill, entries * 4u) != hipSuccess || hipMalloc(&w->d_tab_tpot, entries * 4u) != hipSuccess) {
+                (void)hipGetLastError();
+                return AP_ERR_ALLOC;
+            }
+            w->tab_entries = entries;
+        }
+        if (hipMemcpy(w->d_tab_prefill, tab_prefill, entries * 4u, hipMemcpyHostToDevice) != hipSuccess ||
+            hipMemcpy(w->d_tab_tpot, tab_tpot, entries * 4u, hipMemcpyHostToDevice) != hipSuccess) {
+            (void)hipGetLastError();
+            w->has_model = false;
+            return AP_ERR_DEVICE;
+        }
+    }
     if (hipMemcpy(w->d_rep, dev.data(), sizeof(DevReplica) * M, hipMemcpyHostToDevice) != hipSuccess ||
-        (!use_pipeline && hipFuncSetAttribute(reinterpret_cast<const void*>(eval_kernel(hist16, w->len16)),
+        (!use_pipeline && hipFuncSetAttribute(reinterpret_cast<const void*>(eval_kernel(hist16, w->len16, tabled)),
                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) ||
         hipFuncSetAttribute(hist16 ? reinterpret_cast<const void*>(&k_nominal_metrics<true>)
                                    : reinterpret_cast<const void*>(&k_nominal_metrics<false>),
@@ -384,6 +431,8 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
     p.prompt = w->d_prompt;
     p.outlen = w->d_out;
     p.rep = w->d_rep;
+    p.tab_prefill = tabled ? w->d_tab_prefill : nullptr;
+    p.tab_tpot = tabled ? w->d_tab_tpot : nullptr;
     p.R = w->R;
     p.key_bits = 0;
     while (((M - 1u) >> p.key_bits) != 0u) ++p.key_bits;       // bits needed for the replica ids 0..M-1
@@ -394,6 +443,7 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
     p.k99 = (uint32_t)((99ull * w->R + 99ull) / 100ull);
     w->has_model = false;
     w->has_parent = false;    // its analysis belonged to the previous cost model
+    w->tabled = tabled;
     w->params = p;
     w->lds_bytes = bytes;
     w->hist16 = hist16;
@@ -444,6 +494,7 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
         w->group_lds_bytes = (kGroupWaves * (M + 1u) + M + 2u) * 4u;
         ReplayParams qp{};
         qp.req = w->d_req; qp.rep = w->d_rep; qp.qs = gp.qs; qp.list = gp.list;
+        qp.tab_prefill = p.tab_prefill; qp.tab_tpot = p.tab_tpot;
         qp.bins_te = reinterpret_cast<uint32_t*>(w->d_scratch + o_te);
         qp.bins_p = reinterpret_cast<uint16_t*>(w->d_scratch + o_p);
         qp.partial = reinterpret_cast<QueuePartial*>(w->d_scratch + o_part);
@@ -512,6 +563,31 @@ ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t 
     }
     w->has_model = true;
     return AP_OK;
+}
+
+ap_status ap_costmodel_set(ap_workload* w, const ap_replica* replicas, uint32_t M, uint32_t B, const ap_slo* slo) {
+    return set_cost_model(w, replicas, M, B, slo, nullptr, nullptr, nullptr, 0u);
+}
+
+ap_status ap_costtable_set(ap_workload* w, const ap_typed_replica* replicas, uint32_t M, uint32_t B, const ap_slo* slo,
+                           const uint32_t* prefill_us, const uint32_t* tpot_us, uint32_t n_types) {
+    if (!w || !replicas || !slo || !prefill_us || !tpot_us || M == 0 || B == 0 || n_types == 0) return AP_ERR_INVALID;
+    if (M > AP_MAX_REPLICAS) return AP_ERR_RANGE;
+    if ((uint64_t)n_types * w->R > 0xFFFFFFFFull) return AP_ERR_RANGE;      // table offsets are 32-bit on the device
+    std::vector<ap_replica> plain;
+    std::vector<uint32_t> types;
+    try {
+        plain.resize(M);
+        types.resize(M);
+    } catch (const std::bad_alloc&) {
+        return AP_ERR_ALLOC;
+    }
+    for (uint32_t m = 0; m < M; ++m) {
+        if (replicas[m].type >= n_types) return AP_ERR_INVALID;
+        types[m] = replicas[m].type;
+        plain[m] = ap_replica{0u, 0u, 0u, 0u, replicas[m].t_on_us, replicas[m].t_off_us};
+    }
+    return set_cost_model(w, plain.data(), M, B, slo, types.data(), prefill_us, tpot_us, n_types);
 }
 
 ap_status ap_eval_candidates(const ap_workload* w, const uint16_t* d_assign, uint32_t C, ap_metrics* d_out,
@@ -602,6 +678,8 @@ ap_status ap_workload_destroy(ap_workload* w) {
     if (w->d_prompt) ok = (hipFree(w->d_prompt) == hipSuccess) && ok;
     if (w->d_out) ok = (hipFree(w->d_out) == hipSuccess) && ok;
     if (w->d_rep) ok = (hipFree(w->d_rep) == hipSuccess) && ok;
+    if (w->d_tab_prefill) ok = (hipFree(w->d_tab_prefill) == hipSuccess) && ok;
+    if (w->d_tab_tpot) ok = (hipFree(w->d_tab_tpot) == hipSuccess) && ok;
     if (w->d_req) ok = (hipFree(w->d_req) == hipSuccess) && ok;
     if (w->d_scratch) ok = (hipFree(w->d_scratch) == hipSuccess) && ok;
     if (w->d_span) ok = (hipFree(w->d_span) == hipSuccess) && ok;

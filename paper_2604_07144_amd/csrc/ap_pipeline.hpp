@@ -123,6 +123,8 @@ __global__ __launch_bounds__(kGroupThreads) void k_group_requests(GroupParams p,
 struct ReplayParams {
     const uint4* req;                  // [R] {arrival (relative us), prompt_len, out_len, 0}
     const DevReplica* rep;             // [M]
+    const uint32_t* tab_prefill;       // cost tables, or null (see EvalParams)
+    const uint32_t* tab_tpot;
     const uint16_t* qs;
     const uint16_t* list;
     uint32_t* bins_te;                 // [batch][n_chunks * chunk] ttft bin | e2e bin << 16; 0xFFFFFFFF = rejected
@@ -181,8 +183,8 @@ __global__ __launch_bounds__(kReplayThreads) void k_replay_queues(ReplayParams p
                     if (start >= rp.t_off) {
                         closed = true;            // starts never decrease along a queue: the rest is rejected too
                     } else {
-                        const uint32_t prefill = rp.a + rp.b * rq.y;
-                        const uint32_t tpot = rp.c + rp.d * ((rq.y + 1023u) >> 10);
+                        uint32_t prefill, tpot;
+                        request_cost(p.tab_prefill, p.tab_tpot, rp, r, rq.y, prefill, tpot);
                         const uint32_t dec = rq.z * tpot;
                         const uint32_t fin = start + prefill + dec;
                         // replace the root by `fin` and restore the heap order

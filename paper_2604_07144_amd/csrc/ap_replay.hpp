@@ -25,7 +25,9 @@ namespace {
 //    permute-mode update.
 //
 // kLen16: every prompt and output length is below 65536, so the staged copies are 16-bit.
-template <bool kHist16, bool kLen16>
+// kTabled: prefill time and time per token come from the caller's tables (one pair of loads per
+// request in the replay step) instead of the linear stand-in; prompt lengths are then not staged.
+template <bool kHist16, bool kLen16, bool kTabled>
 __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, const uint16_t* __restrict__ assign,
                                                               ap_metrics* out, uint32_t C, uint32_t only_pending) {
     using len_t = typename std::conditional<kLen16, uint16_t, uint32_t>::type;
@@ -103,7 +105,7 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
             for (uint32_t g = 0; g < kMaxGroups; ++g) {
                 if (key[g] == kNoKey) continue;
                 const uint32_t idx = w * per_wave + g * kWave + lane;
-                kprompt[g] = p.prompt[r0 + idx];
+                kprompt[g] = kTabled ? 0u : p.prompt[r0 + idx];
                 kout[g] = p.outlen[r0 + idx];
                 c_arr[idx] = karr[g];
                 // a request that arrives when its replica is already gone can never start: reject it
@@ -181,7 +183,7 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
                 }
                 if (k != kNoKey) {
                     const uint32_t idx = w * per_wave + g * kWave + lane;
-                    c_prompt[idx] = (len_t)kprompt[g];
+                    if (!kTabled) c_prompt[idx] = (len_t)kprompt[g];
                     c_out[idx] = (len_t)kout[g];
                 }
             }
@@ -218,10 +220,11 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
                     const uint32_t nb = min(kWave, qn - sb);
                     const bool valid = lane < nb;
                     const uint32_t li = valid ? (uint32_t)list[qs + sb + lane] : 0u;
-                    const uint32_t arr = c_arr[li], prm = c_prompt[li], ol = c_out[li];     // widened to 32 bits
+                    const uint32_t arr = c_arr[li], ol = c_out[li];                         // widened to 32 bits
                     const uint32_t ready = max(arr, rp.t_on);
-                    const uint32_t prefill = rp.a + rp.b * prm;
-                    const uint32_t tpot = rp.c + rp.d * ((prm + 1023u) >> 10);
+                    uint32_t prefill, tpot;
+                    request_cost<kTabled>(p.tab_prefill, p.tab_tpot, rp, r0 + li, kTabled ? 0u : (uint32_t)c_prompt[li],
+                                          prefill, tpot);
                     const uint32_t dec = ol * tpot;
                     const uint32_t svc = prefill + dec;
                     // requests are in arrival order, so those arriving inside the window are a prefix

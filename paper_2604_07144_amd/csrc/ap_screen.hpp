@@ -54,9 +54,8 @@ __global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint
     unsigned long long s_e2e = 0, s_ttft = 0, s_tpot = 0;
     uint32_t last_fin = 0, n_ok = 0;
     for (uint32_t r = tid; r < p.R; r += kThreads) {
-        const uint32_t prm = p.prompt[r];
-        const uint32_t prefill = rp.a + rp.b * prm;
-        const uint32_t tpot = rp.c + rp.d * ((prm + 1023u) >> 10);
+        uint32_t prefill, tpot;
+        request_cost(p.tab_prefill, p.tab_tpot, rp, r, p.prompt[r], prefill, tpot);
         const uint32_t e2e = prefill + p.outlen[r] * tpot;
         // service interval in ticks, rounded outwards (arrival down, finish up), 16 bits each
         const uint32_t fin_us = p.arrival[r] + e2e;

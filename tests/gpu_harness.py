@@ -12,15 +12,21 @@ from paper_2604_07144_amd import binding
 class GpuWorkload:
     """A workload handle of the HIP library with its cost model set from a Trace."""
 
-    def __init__(self, tr, **override):
+    def __init__(self, tr, tables=None, **override):
+        """``tables=(rep_type, prefill_us[T][R], tpot_us[T][R])`` selects the tabulated cost model (the trace's
+        coefficients are then unused); otherwise the linear one with the trace's coefficients."""
         kw = dict(B=tr.B, slo_ttft_us=tr.slo_ttft_us, slo_tpot_us=tr.slo_tpot_us, penalty_us=tr.penalty_us,
                   coef=tr.coef, t_on_us=tr.t_on_us, t_off_us=tr.t_off_us)
         kw.update(override)
         self.R = tr.R
         self.handle = binding.ap_workload_create(tr.arrival_us, tr.prompt_len, tr.out_len)
         try:
-            binding.ap_costmodel_set(self.handle, binding.make_replicas(kw["coef"], kw["t_on_us"], kw["t_off_us"]),
-                                     kw["B"], kw["slo_ttft_us"], kw["slo_tpot_us"], kw["penalty_us"])
+            if tables is None:
+                binding.ap_costmodel_set(self.handle, binding.make_replicas(kw["coef"], kw["t_on_us"], kw["t_off_us"]),
+                                         kw["B"], kw["slo_ttft_us"], kw["slo_tpot_us"], kw["penalty_us"])
+            else:
+                binding.ap_costtable_set(self.handle, tables[0], kw["t_on_us"], kw["t_off_us"], kw["B"],
+                                         kw["slo_ttft_us"], kw["slo_tpot_us"], kw["penalty_us"], tables[1], tables[2])
         except Exception:
             self.close()
             raise
