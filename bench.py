@@ -34,11 +34,11 @@ KERNEL_SOURCE_DIR = os.path.join(ROOT, "paper_2604_07144_amd", "csrc")
 # Keyed by configuration; valid only for the library source (all of csrc/) whose hash is recorded with it.
 MEASURED_TRAFFIC = {
     # cfg: (sha256 of the kernel source when measured, bytes per call)
-    4: ("45993df7eff3811e4fe9d2f783a94b182536819b6bb11b03cfc655476b206411", 4311362228),
-    3: ("45993df7eff3811e4fe9d2f783a94b182536819b6bb11b03cfc655476b206411", 543783591),
+    4: ("cdfcf6c09b771448fb4495bb2405e873a4f8d1e555ffe50873f7f9aa755b7770", 4311565539),
+    3: ("cdfcf6c09b771448fb4495bb2405e873a4f8d1e555ffe50873f7f9aa755b7770", 543699962),
 }
 # the same for one ap_eval_children call on the sparse form of configs[4]
-MEASURED_TRAFFIC_CHILDREN = {4: ("45993df7eff3811e4fe9d2f783a94b182536819b6bb11b03cfc655476b206411", 134357920)}
+MEASURED_TRAFFIC_CHILDREN = {4: ("cdfcf6c09b771448fb4495bb2405e873a4f8d1e555ffe50873f7f9aa755b7770", 134397388)}
 
 
 def kernel_source_hash() -> str:

@@ -179,6 +179,52 @@ ap_status ap_parent_set(ap_workload *w, const uint16_t *parent, uint32_t max_chi
 ap_status ap_eval_children(const ap_workload *w, const uint32_t *d_edit_first, const uint32_t *d_edit_request,
                            const uint16_t *d_edit_replica, uint32_t C, ap_metrics *d_out, void *hip_stream);
 
+/* Roofline cost tables (Appendix "Serving Simulator").  A model M_z is described by its layers L,
+ * hidden size H, MLP intermediate size I, vocabulary V, attention heads A, key-value heads K <= A
+ * and weight precision eta in bits (per-head dimension d = H / A); a GPU type g by its memory m_g
+ * (bytes), peak throughput F_g (FLOP/s), HBM bandwidth B_g, PCIe bandwidth P_g, GPUs per node nu_g
+ * and the interconnect bandwidth R inside a node and across nodes (all bytes/s); a replica group by
+ * (z, g, tensor-parallel degree t, per-replica batch b). */
+typedef struct {
+    uint32_t layers, hidden, intermediate, vocab, heads, kv_heads, weight_bits;
+} ap_model;
+
+typedef struct {
+    double mem_bytes, flops, hbm_bytes_per_s, pcie_bytes_per_s, link_intra_bytes_per_s, link_inter_bytes_per_s;
+    uint32_t gpus_per_node;
+} ap_gpu;
+
+typedef struct {
+    uint32_t model, gpu, tp, batch;
+} ap_group;
+
+/* Evaluate the serve-latency equation's two terms for every group and sequence length:
+ *   prefill_ns[g][s], s = 0 .. max_seq       : T_prefill(z,g,t,b,s) in nanoseconds (entry 0 is 0);
+ *   decode_prefix_ns[g][k], k = 0 .. max_seq+1 : sum of T_decode(z,g,t,b,j) over 1 <= j < k, so that the
+ *       decode sum over k = s_p .. s_p + s_d - 1 is decode_prefix_ns[s_p + s_d] - decode_prefix_ns[s_p];
+ *   weight_bytes[g] : W_z of the weight-size equation;  feasible[g] : 0 if W_z / t > 0.8 m_g, else 1.
+ * Each term applies the roofline equations (pi = min(F / A * B_g, F_g), T = F / pi) to the QKV
+ * projection, attention, output projection and MLP of a layer, L times, and to the output head once,
+ * and adds the ring all-reduce time 2(t-1)/t * 2L * H * b * s * eta/8 / R_{g,t} (R: inside a node when
+ * t <= nu_g).  Times are rounded to whole nanoseconds (half to even) before they are summed.
+ * All pointers are HOST pointers; the four outputs must hold n_groups*(max_seq+1), n_groups*(max_seq+2),
+ * n_groups and n_groups elements.  Synchronous; allocates and frees its own device buffers.
+ * Errors: AP_ERR_INVALID (null pointers, empty arrays, an index out of range, a zero field, K > A, a
+ * non-positive rate), AP_ERR_RANGE (more than 65535 groups, max_seq above 2^24), AP_ERR_ALLOC, AP_ERR_DEVICE. */
+ap_status ap_roofline_tables(const ap_model *models, uint32_t n_models, const ap_gpu *gpus, uint32_t n_gpus,
+                             const ap_group *groups, uint32_t n_groups, uint32_t max_seq, uint64_t *prefill_ns,
+                             uint64_t *decode_prefix_ns, double *weight_bytes, uint8_t *feasible);
+
+/* The same tables turned into the inputs of ap_costtable_set for the requests of a workload: for group g
+ * (= replica type g) and request r with prompt length s_p and output length s_d,
+ *   prefill_us[g * R + r] = (prefill_ns[g][s_p] + 500) / 1000
+ *   tpot_us[g * R + r]    = (decode sum in ns + 500 s_d) / (1000 s_d)      (rounded time per output token)
+ *   prefill_us, tpot_us : HOST pointers, uint32 [n_groups][R], written.
+ * Synchronous.  Errors as above, AP_ERR_RANGE also when a request's s_p + s_d exceeds 2^24. */
+ap_status ap_roofline_costs(const ap_workload *w, const ap_model *models, uint32_t n_models, const ap_gpu *gpus,
+                            uint32_t n_gpus, const ap_group *groups, uint32_t n_groups, uint32_t *prefill_us,
+                            uint32_t *tpot_us);
+
 /* Release the workload and its device memory.  NULL is accepted. */
 ap_status ap_workload_destroy(ap_workload *w);
 

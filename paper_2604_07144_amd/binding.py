@@ -25,7 +25,12 @@ METRICS_DTYPE = np.dtype([("sum_e2e_us", "<u8"), ("sum_ttft_us", "<u8"), ("sum_t
                           ("p99_e2e_us", "<u8"), ("slo_ok", "<u4"), ("n_rejected", "<u4")])
 TYPED_REPLICA_DTYPE = np.dtype({"names": ["type", "t_on_us", "t_off_us"], "formats": ["<u4", "<u8", "<u8"],
                                 "offsets": [0, 8, 16], "itemsize": 24})
-assert REPLICA_DTYPE.itemsize == 32 and METRICS_DTYPE.itemsize == 64
+MODEL_DTYPE = np.dtype([(n, "<u4") for n in ("layers", "hidden", "intermediate", "vocab", "heads", "kv_heads", "weight_bits")])
+GPU_DTYPE = np.dtype({"names": ["mem_bytes", "flops", "hbm_bytes_per_s", "pcie_bytes_per_s", "link_intra_bytes_per_s",
+                                "link_inter_bytes_per_s", "gpus_per_node"],
+                      "formats": ["<f8"] * 6 + ["<u4"], "offsets": [0, 8, 16, 24, 32, 40, 48], "itemsize": 56})
+GROUP_DTYPE = np.dtype([(n, "<u4") for n in ("model", "gpu", "tp", "batch")])
+assert REPLICA_DTYPE.itemsize == 32 and METRICS_DTYPE.itemsize == 64 and MODEL_DTYPE.itemsize == 28
 
 
 class ApSlo(C.Structure):
@@ -63,6 +68,12 @@ def lib() -> C.CDLL:
         L.ap_eval_children.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p,
                                        C.c_void_p]
         L.ap_eval_children.restype = C.c_int
+        L.ap_roofline_tables.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_uint32,
+                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.ap_roofline_tables.restype = C.c_int
+        L.ap_roofline_costs.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32,
+                                        C.c_void_p, C.c_void_p]
+        L.ap_roofline_costs.restype = C.c_int
         L.ap_workload_destroy.argtypes = [C.c_void_p]
         L.ap_workload_destroy.restype = C.c_int
         L.ap_status_str.argtypes = [C.c_int]
@@ -160,6 +171,39 @@ def ap_eval_children(workload: int, d_edit_first_ptr: int, d_edit_request_ptr: i
     _check(lib().ap_eval_children(workload, C.c_void_p(d_edit_first_ptr), C.c_void_p(d_edit_request_ptr),
                                   C.c_void_p(d_edit_replica_ptr), int(n_children), C.c_void_p(d_out_ptr),
                                   C.c_void_p(stream)), "ap_eval_children")
+
+
+def _roofline_args(models, gpus, groups):
+    models = np.ascontiguousarray(models, dtype=MODEL_DTYPE)
+    gpus = np.ascontiguousarray(gpus, dtype=GPU_DTYPE)
+    groups = np.ascontiguousarray(groups, dtype=GROUP_DTYPE)
+    return models, gpus, groups
+
+
+def ap_roofline_tables(models, gpus, groups, max_seq: int):
+    """Structured arrays in (MODEL_DTYPE, GPU_DTYPE, GROUP_DTYPE); returns prefill_ns[G][max_seq+1],
+    decode_prefix_ns[G][max_seq+2], weight_bytes[G], feasible[G]."""
+    models, gpus, groups = _roofline_args(models, gpus, groups)
+    G = groups.shape[0]
+    prefill_ns = np.zeros((G, max_seq + 1), dtype=np.uint64)
+    prefix_ns = np.zeros((G, max_seq + 2), dtype=np.uint64)
+    weight = np.zeros(G, dtype=np.float64)
+    feasible = np.zeros(G, dtype=np.uint8)
+    _check(lib().ap_roofline_tables(models.ctypes.data, models.shape[0], gpus.ctypes.data, gpus.shape[0],
+                                    groups.ctypes.data, G, int(max_seq), prefill_ns.ctypes.data, prefix_ns.ctypes.data,
+                                    weight.ctypes.data, feasible.ctypes.data), "ap_roofline_tables")
+    return prefill_ns, prefix_ns, weight, feasible
+
+
+def ap_roofline_costs(workload: int, n_requests: int, models, gpus, groups):
+    """Returns prefill_us[G][R], tpot_us[G][R] (uint32) for the workload's requests."""
+    models, gpus, groups = _roofline_args(models, gpus, groups)
+    G = groups.shape[0]
+    prefill_us = np.zeros((G, n_requests), dtype=np.uint32)
+    tpot_us = np.zeros((G, n_requests), dtype=np.uint32)
+    _check(lib().ap_roofline_costs(workload, models.ctypes.data, models.shape[0], gpus.ctypes.data, gpus.shape[0],
+                                   groups.ctypes.data, G, prefill_us.ctypes.data, tpot_us.ctypes.data), "ap_roofline_costs")
+    return prefill_us, tpot_us
 
 
 def ap_workload_destroy(workload: int) -> None:

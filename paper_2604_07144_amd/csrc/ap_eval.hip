@@ -21,12 +21,13 @@
 //
 // This file holds the host side: planning, the workload object and the C ABI.  The kernels are in
 // ap_screen.hpp (screening), ap_replay.hpp (fused replay), ap_pipeline.hpp (three-kernel replay) and
-// ap_children.hpp (sparse candidates); ap_common.hpp has what they share.
+// ap_children.hpp (sparse candidates) and ap_roofline.hpp (roofline cost tables); ap_common.hpp has what they share.
 #include "ap_common.hpp"
 #include "ap_screen.hpp"
 #include "ap_replay.hpp"
 #include "ap_pipeline.hpp"
 #include "ap_children.hpp"
+#include "ap_roofline.hpp"
 
 namespace {
 
@@ -669,6 +670,130 @@ ap_status ap_eval_children(const ap_workload* w, const uint32_t* d_edit_first, c
                        w->child_params, d_edit_first, d_edit_request, d_edit_replica, d_out, C);
     if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
     return launch_dense(w, w->d_rows, C, d_out, stream, w->child_params.certify != 0u);
+}
+
+// ---- roofline cost tables -------------------------------------------------------------
+namespace {
+
+// Device buffers of one roofline computation; freed when the object goes out of scope.
+struct RoofBuffers {
+    RoofGroup* groups = nullptr;
+    unsigned long long* prefill_ns = nullptr;
+    unsigned long long* step_ns = nullptr;
+    unsigned long long* prefix_ns = nullptr;
+    double* weight_bytes = nullptr;
+    uint32_t* feasible = nullptr;
+    uint32_t* prefill_us = nullptr;
+    uint32_t* tpot_us = nullptr;
+    ~RoofBuffers() {
+        for (void* q : {(void*)groups, (void*)prefill_ns, (void*)step_ns, (void*)prefix_ns, (void*)weight_bytes,
+                        (void*)feasible, (void*)prefill_us, (void*)tpot_us})
+            if (q) (void)hipFree(q);
+    }
+};
+
+// Validate the descriptions and run the table kernels; leaves prefill_ns / prefix_ns / weight_bytes /
+// feasible filled on the device.
+ap_status roofline_tables_on_device(const ap_model* models, uint32_t n_models, const ap_gpu* gpus, uint32_t n_gpus,
+                                    const ap_group* groups, uint32_t n_groups, uint32_t max_seq, RoofBuffers& buf) {
+    if (!models || !gpus || !groups || n_models == 0 || n_gpus == 0 || n_groups == 0 || max_seq == 0) return AP_ERR_INVALID;
+    if (n_groups > 65535u || max_seq > (1u << 24)) return AP_ERR_RANGE;
+    std::vector<RoofGroup> host;
+    try {
+        host.resize(n_groups);
+    } catch (const std::bad_alloc&) {
+        return AP_ERR_ALLOC;
+    }
+    for (uint32_t i = 0; i < n_groups; ++i) {
+        const ap_group& gr = groups[i];
+        if (gr.model >= n_models || gr.gpu >= n_gpus || gr.tp == 0 || gr.batch == 0) return AP_ERR_INVALID;
+        const ap_model& m = models[gr.model];
+        const ap_gpu& g = gpus[gr.gpu];
+        if (m.layers == 0 || m.hidden == 0 || m.intermediate == 0 || m.vocab == 0 || m.heads == 0 || m.kv_heads == 0 ||
+            m.kv_heads > m.heads || m.weight_bits == 0)
+            return AP_ERR_INVALID;
+        if (!(g.flops > 0.0) || !(g.hbm_bytes_per_s > 0.0) || !(g.mem_bytes > 0.0) || g.gpus_per_node == 0 ||
+            !(g.link_intra_bytes_per_s > 0.0) || !(g.link_inter_bytes_per_s > 0.0))
+            return AP_ERR_INVALID;
+        RoofGroup& o = host[i];
+        o.L = m.layers; o.H = m.hidden; o.I = m.intermediate; o.V = m.vocab; o.A = m.heads; o.K = m.kv_heads;
+        o.e = (double)m.weight_bits / 8.0;
+        o.b = gr.batch; o.t = gr.tp;
+        o.flops = g.flops; o.hbm = g.hbm_bytes_per_s;
+        o.link = gr.tp <= g.gpus_per_node ? g.link_intra_bytes_per_s : g.link_inter_bytes_per_s;
+        o.mem = g.mem_bytes;
+    }
+    const size_t per_group = (size_t)max_seq + 1u;
+    if (hipMalloc(&buf.groups, sizeof(RoofGroup) * n_groups) != hipSuccess ||
+        hipMalloc(&buf.prefill_ns, 8u * per_group * n_groups) != hipSuccess ||
+        hipMalloc(&buf.step_ns, 8u * per_group * n_groups) != hipSuccess ||
+        hipMalloc(&buf.prefix_ns, 8u * (per_group + 1u) * n_groups) != hipSuccess ||
+        hipMalloc(&buf.weight_bytes, 8u * n_groups) != hipSuccess || hipMalloc(&buf.feasible, 4u * n_groups) != hipSuccess) {
+        (void)hipGetLastError();
+        return AP_ERR_ALLOC;
+    }
+    if (hipMemcpy(buf.groups, host.data(), sizeof(RoofGroup) * n_groups, hipMemcpyHostToDevice) != hipSuccess)
+        return AP_ERR_DEVICE;
+    hipLaunchKernelGGL(k_roofline_steps, dim3((max_seq + kRoofThreads) / kRoofThreads, n_groups), dim3(kRoofThreads), 0, nullptr,
+                       buf.groups, n_groups, max_seq, buf.prefill_ns, buf.step_ns, buf.weight_bytes, buf.feasible);
+    hipLaunchKernelGGL(k_roofline_prefix, dim3(n_groups), dim3(kRoofThreads), 0, nullptr, buf.step_ns, max_seq, buf.prefix_ns);
+    if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
+    return AP_OK;
+}
+
+}  // namespace
+
+ap_status ap_roofline_tables(const ap_model* models, uint32_t n_models, const ap_gpu* gpus, uint32_t n_gpus,
+                             const ap_group* groups, uint32_t n_groups, uint32_t max_seq, uint64_t* prefill_ns,
+                             uint64_t* decode_prefix_ns, double* weight_bytes, uint8_t* feasible) {
+    if (!prefill_ns || !decode_prefix_ns || !weight_bytes || !feasible) return AP_ERR_INVALID;
+    RoofBuffers buf;
+    const ap_status st = roofline_tables_on_device(models, n_models, gpus, n_gpus, groups, n_groups, max_seq, buf);
+    if (st != AP_OK) return st;
+    std::vector<uint32_t> ok;
+    try {
+        ok.resize(n_groups);
+    } catch (const std::bad_alloc&) {
+        return AP_ERR_ALLOC;
+    }
+    const size_t per_group = (size_t)max_seq + 1u;
+    if (hipMemcpy(prefill_ns, buf.prefill_ns, 8u * per_group * n_groups, hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemcpy(decode_prefix_ns, buf.prefix_ns, 8u * (per_group + 1u) * n_groups, hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemcpy(weight_bytes, buf.weight_bytes, 8u * n_groups, hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemcpy(ok.data(), buf.feasible, 4u * n_groups, hipMemcpyDeviceToHost) != hipSuccess) {
+        (void)hipGetLastError();
+        return AP_ERR_DEVICE;
+    }
+    for (uint32_t i = 0; i < n_groups; ++i) feasible[i] = ok[i] ? 1u : 0u;
+    return AP_OK;
+}
+
+ap_status ap_roofline_costs(const ap_workload* w, const ap_model* models, uint32_t n_models, const ap_gpu* gpus,
+                            uint32_t n_gpus, const ap_group* groups, uint32_t n_groups, uint32_t* prefill_us,
+                            uint32_t* tpot_us) {
+    if (!w || !prefill_us || !tpot_us) return AP_ERR_INVALID;
+    if (hipSetDevice(w->device) != hipSuccess) return AP_ERR_DEVICE;
+    uint64_t longest = 0;                                  // prompt + output of the longest request
+    for (uint32_t r = 0; r < w->R; ++r) longest = std::max<uint64_t>(longest, (uint64_t)w->h_prompt[r] + (uint64_t)w->h_out[r]);
+    if (longest > (1u << 24)) return AP_ERR_RANGE;
+    RoofBuffers buf;
+    const ap_status st = roofline_tables_on_device(models, n_models, gpus, n_gpus, groups, n_groups, (uint32_t)longest, buf);
+    if (st != AP_OK) return st;
+    const size_t entries = (size_t)n_groups * w->R;
+    if (hipMalloc(&buf.prefill_us, 4u * entries) != hipSuccess || hipMalloc(&buf.tpot_us, 4u * entries) != hipSuccess) {
+        (void)hipGetLastError();
+        return AP_ERR_ALLOC;
+    }
+    hipLaunchKernelGGL(k_roofline_request_costs, dim3((w->R + kRoofThreads - 1u) / kRoofThreads, n_groups), dim3(kRoofThreads),
+                       0, nullptr, buf.prefill_ns, buf.prefix_ns, (uint32_t)longest, w->d_prompt, w->d_out, w->R, buf.prefill_us,
+                       buf.tpot_us);
+    if (hipGetLastError() != hipSuccess ||
+        hipMemcpy(prefill_us, buf.prefill_us, 4u * entries, hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemcpy(tpot_us, buf.tpot_us, 4u * entries, hipMemcpyDeviceToHost) != hipSuccess) {
+        (void)hipGetLastError();
+        return AP_ERR_DEVICE;
+    }
+    return AP_OK;
 }
 
 ap_status ap_workload_destroy(ap_workload* w) {

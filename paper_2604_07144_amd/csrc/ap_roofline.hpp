@@ -1,0 +1,147 @@
+// Roofline cost tables: prefill time and decode-step time of every (model, GPU type, tensor-parallel degree,
+// batch) group for every sequence length, and from them the per-request table entries of the tabulated cost
+// model.
+#ifndef AP_ROOFLINE_HPP
+#define AP_ROOFLINE_HPP
+
+#include "ap_common.hpp"
+
+namespace {
+
+// ----------------------------------------------------------------------------------
+// the cost model of Appendix "Serving Simulator", in double precision
+// ----------------------------------------------------------------------------------
+// One group (z, g, t, b) of the serve-latency equation with everything the sublayer formulas
+// need, as doubles.
+struct RoofGroup {
+    double L, H, I, V, A, K;      // layers, hidden, MLP intermediate, vocabulary, heads, key-value heads
+    double e;                     // bytes per weight (eta / 8)
+    double b, t;                  // batch, tensor-parallel degree
+    double flops, hbm;            // F_g, B_g
+    double link;                  // R_{g,t}: intra-node when t <= nu_g, cross-node otherwise
+    double mem;                   // m_g
+};
+
+// Model weight size: W_z = [L (3 H I + 2 A H d + 2 K H d) + 2 H V] * eta / 8.
+__device__ __forceinline__ double roof_weight_bytes(const RoofGroup& g) {
+#pragma clang fp contract(off)
+    const double d = g.H / g.A;
+    const double per_layer = ((((3.0 * g.H) * g.I) + (((2.0 * g.A) * g.H) * d)) + (((2.0 * g.K) * g.H) * d));
+    return ((g.L * per_layer) + ((2.0 * g.H) * g.V)) * g.e;
+}
+
+// Roofline equations: achieved performance pi = min(F / A * B_g, F_g), time F / pi.
+__device__ __forceinline__ double roof_op_time(double flops, double bytes, const RoofGroup& g) {
+#pragma clang fp contract(off)
+    const double perf = fmin((flops / bytes) * g.hbm, g.flops);
+    return flops / perf;
+}
+
+// One forward pass of n new tokens per sequence over a context of c tokens: the four sublayers of a
+// layer (QKV projection, attention, output projection, MLP) L times, the output head once, and the two
+// ring all-reduces per layer of the all-reduce equation.  Operations are written in one fixed order, with
+// no fused multiply-add, so that the same arithmetic in any IEEE double implementation gives the same bits.
+__device__ __forceinline__ double roof_phase_time(const RoofGroup& g, double n, double c) {
+#pragma clang fp contract(off)
+    const double d = g.H / g.A;
+    const double qkv_w = g.A + 2.0 * g.K;
+    const double qkv = roof_op_time(((((((2.0 * g.b) * n) * g.H) * qkv_w) * d) / g.t),
+                                    g.e * (((((g.H * qkv_w) * d) / g.t) + ((g.b * n) * g.H)) + ((((g.b * n) * qkv_w) * d) / g.t)), g);
+    const double att = roof_op_time(((((((4.0 * g.b) * n) * c) * g.A) * d) / g.t),
+                                    g.e * ((((((2.0 * g.b) * n) * g.A) * d) / g.t) + (((((2.0 * g.b) * c) * g.K) * d) / g.t)), g);
+    const double proj = roof_op_time(((((((2.0 * g.b) * n) * g.A) * d) * g.H) / g.t),
+                                     g.e * (((((g.A * d) * g.H) / g.t) + ((((g.b * n) * g.A) * d) / g.t)) + ((g.b * n) * g.H)), g);
+    const double mlp = roof_op_time((((((6.0 * g.b) * n) * g.H) * g.I) / g.t),
+                                    g.e * (((((3.0 * g.H) * g.I) / g.t) + (((2.0 * g.b) * n) * g.H)) + ((((3.0 * g.b) * n) * g.I) / g.t)), g);
+    const double head = roof_op_time(((((2.0 * g.b) * g.H) * g.V) / g.t),
+                                     g.e * ((((g.H * g.V) / g.t) + (g.b * g.H)) + ((g.b * g.V) / g.t)), g);
+    double comm = 0.0;
+    if (g.t != 1.0) comm = (((((((2.0 * (g.t - 1.0)) / g.t) * (2.0 * g.L)) * g.H) * g.b) * n) * g.e) / g.link;
+    return ((g.L * (((qkv + att) + proj) + mlp)) + head) + comm;
+}
+
+__device__ __forceinline__ unsigned long long roof_ns(double seconds) {
+#pragma clang fp contract(off)
+    return (unsigned long long)__double2ll_rn(seconds * 1e9);              // round half to even
+}
+
+constexpr uint32_t kRoofThreads = 256;
+
+// prefill_ns[g][s] for s = 0 .. max_seq (entry 0 is 0) and step_ns[g][k], the decode step at context
+// k (entry 0 is 0: a context holds at least one token).  One thread per (group, length).
+// Also, once per group: its weight size and the memory-feasibility verdict W_z / t <= 0.8 m_g.
+__global__ __launch_bounds__(kRoofThreads) void k_roofline_steps(const RoofGroup* __restrict__ groups, uint32_t n_groups,
+                                                                 uint32_t max_seq, unsigned long long* __restrict__ prefill_ns,
+                                                                 unsigned long long* __restrict__ step_ns,
+                                                                 double* __restrict__ weight_bytes,
+                                                                 uint32_t* __restrict__ feasible) {
+    const uint32_t s = blockIdx.x * kRoofThreads + threadIdx.x, gi = blockIdx.y;
+    if (s > max_seq || gi >= n_groups) return;
+    const RoofGroup g = groups[gi];
+    if (s == 0u) {
+        const double w = roof_weight_bytes(g);
+        weight_bytes[gi] = w;
+        feasible[gi] = (w / g.t > 0.8 * g.mem) ? 0u : 1u;
+    }
+    const size_t at = (size_t)gi * (max_seq + 1u) + s;
+    prefill_ns[at] = s == 0u ? 0ull : roof_ns(roof_phase_time(g, (double)s, (double)s));
+    step_ns[at] = s == 0u ? 0ull : roof_ns(roof_phase_time(g, 1.0, (double)s));
+}
+
+// prefix_ns[g][k] = sum of step_ns[g][j] for j < k, k = 0 .. max_seq + 1: the sum of the serve-latency
+// equation over k = s_p .. s_p + s_d - 1 is then prefix[s_p + s_d] - prefix[s_p].  Integers: the order of
+// the additions does not matter.  One workgroup per group walks its row in tiles.
+__global__ __launch_bounds__(kRoofThreads) void k_roofline_prefix(const unsigned long long* __restrict__ step_ns,
+                                                                  uint32_t max_seq, unsigned long long* __restrict__ prefix_ns) {
+    __shared__ unsigned long long wave_total[kRoofThreads / kWave];
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wv = tid >> 6, gi = blockIdx.x;
+    const unsigned long long* in = step_ns + (size_t)gi * (max_seq + 1u);
+    unsigned long long* out = prefix_ns + (size_t)gi * (max_seq + 2u);
+    unsigned long long carry = 0ull;
+    if (tid == 0u) out[0] = 0ull;
+    for (uint32_t base = 0; base <= max_seq; base += kRoofThreads) {
+        const uint32_t k = base + tid;
+        unsigned long long v = k <= max_seq ? in[k] : 0ull;
+#pragma unroll
+        for (uint32_t dlt = 1; dlt < kWave; dlt <<= 1) {
+            const unsigned long long up = (unsigned long long)__shfl_up((long long)v, dlt);
+            if (lane >= dlt) v += up;
+        }
+        if (lane == 63u) wave_total[wv] = v;
+        __syncthreads();
+        unsigned long long before = carry, total = carry;
+#pragma unroll
+        for (uint32_t j = 0; j < kRoofThreads / kWave; ++j) {
+            before += j < wv ? wave_total[j] : 0ull;
+            total += wave_total[j];
+        }
+        if (k <= max_seq) out[k + 1u] = before + v;                            // inclusive sum up to k = prefix of k + 1
+        carry = total;
+        __syncthreads();
+    }
+}
+
+// Table entries of the tabulated cost model for a trace: per group and request,
+// prefill_us = T_prefill(s_p) rounded to microseconds, tpot_us = the decode sum of the serve-latency
+// equation divided by the number of output tokens, rounded.
+__global__ __launch_bounds__(kRoofThreads) void k_roofline_request_costs(const unsigned long long* __restrict__ prefill_ns,
+                                                                         const unsigned long long* __restrict__ prefix_ns,
+                                                                         uint32_t max_seq, const uint32_t* __restrict__ prompt,
+                                                                         const uint32_t* __restrict__ outlen, uint32_t R,
+                                                                         uint32_t* __restrict__ prefill_us,
+                                                                         uint32_t* __restrict__ tpot_us) {
+    const uint32_t r = blockIdx.x * kRoofThreads + threadIdx.x, gi = blockIdx.y;
+    if (r >= R) return;
+    const uint32_t sp = prompt[r], sd = outlen[r];                            // the host checked sp + sd <= max_seq
+    const unsigned long long pre = prefill_ns[(size_t)gi * (max_seq + 1u) + sp];
+    const unsigned long long* prefix = prefix_ns + (size_t)gi * (max_seq + 2u);
+    const unsigned long long decode = prefix[sp + sd] - prefix[sp];
+    const unsigned long long pre_us = (pre + 500ull) / 1000ull;
+    const unsigned long long per_tok = (decode + 500ull * sd) / (1000ull * sd);
+    prefill_us[(size_t)gi * R + r] = (uint32_t)min(pre_us, 0xFFFFFFFFull);
+    tpot_us[(size_t)gi * R + r] = (uint32_t)min(per_tok, 0xFFFFFFFFull);
+}
+
+}  // namespace
+
+#endif  // AP_ROOFLINE_HPP
