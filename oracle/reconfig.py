@@ -1,0 +1,77 @@
+"""CPU oracle for the reconfiguration cost and the end-to-end trace time (numpy, float64 / integers).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``; the product never imports it and it shares no code
+with the HIP path.  The weight-size equation is taken from ``oracle/roofline.py`` (another oracle).
+
+What is computed, and which passage of the paper each step follows:
+
+* ``transfer_ns``: the weight transfer time of Appendix "Serving Simulator", Reconfiguration Cost,
+  ``tau(z, g) = W_z / P_g * c_z`` (``c_z``: the model-size-dependent PCIe utilisation coefficient, an
+  input), rounded to whole nanoseconds.
+* ``reconfig_ns``: ``Reconfig-Cost(sigma_{i-1}, sigma_i) = T_term + T_load``.  A plan says, for every model
+  and GPU type, with which tensor-parallel degree and how many replicas the model is deployed there (count
+  0: not at all).  ``Delta M_i`` is the set of models whose (GPU type, TP, count) tuples differ between the
+  two plans.  ``T_term`` = the largest ``tau(z, g)`` over the changed models ``z`` and the GPU types ``g``
+  on which the *previous* plan deploys ``z`` (different GPU types terminate concurrently: the slowest
+  decides); ``T_load`` = the largest ``tau(z, g)`` over the GPU types ``g`` and the models ``z`` the *new*
+  plan deploys there.  Both are zero when the plans are equal.
+* ``trace_time``: the execution model of Section 5.1,
+  ``T_total = t_sched(1) + t_serve(1) + sum_{i=2}^{N} [t_stale(i) + t_reconfig(i) + t_serve(i)]``, with the
+  per-interval scheduling, stale-serving and serving times as inputs (they come from the policy's
+  wall-clock time and from the serving simulator), and the breakdown the evaluator reports as artifact
+  feedback (Section 5.3, Table 1: N, the three sums, T_total).
+
+Reading: the loading-cost equation as printed ranges over every model the new plan deploys; together
+with "both costs are zero if the plans are equal" and "the time to transfer *new* model weights" it is
+taken over the changed models only.  Times are integer nanoseconds, so sums and maxima are exact.
+
+Pins (tests/test_reconfig_pins.py): the worked numbers of the system prompt's Example C (13 GB over 64 GB/s
+and 32 GB/s: 0.20 s + 0.41 s = 0.61 s) and Examples A and B (0.25 + 0.25, 0.51 + 0.25), the three rows of
+Table 1 (44.8 s, 33.5 s, 50.0 s), equal plans, and brute force over tiny plan pairs.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from oracle import roofline as rf
+
+
+def transfer_ns(models, pcie_coef, gpus) -> np.ndarray:
+    """tau[z][g] in nanoseconds."""
+    tau = np.zeros((len(models), len(gpus)), dtype=np.uint64)
+    for z, m in enumerate(models):
+        for g, gpu in enumerate(gpus):
+            tau[z, g] = np.uint64(np.rint(rf.weight_bytes(m) / gpu.pcie_bytes_per_s * pcie_coef[z] * 1e9))
+    return tau
+
+
+def reconfig_ns(tau, prev, new):
+    """prev, new: integer arrays [Z][G][2] of (tp, count).  Returns (T_term, T_load) in nanoseconds."""
+    prev = np.asarray(prev).reshape(tau.shape + (2,))
+    new = np.asarray(new).reshape(tau.shape + (2,))
+    term = load = 0
+    for z in range(tau.shape[0]):
+        deployed_prev = [(g, int(prev[z, g, 0])) if prev[z, g, 1] else None for g in range(tau.shape[1])]
+        deployed_new = [(g, int(new[z, g, 0])) if new[z, g, 1] else None for g in range(tau.shape[1])]
+        counts_differ = [int(prev[z, g, 1]) != int(new[z, g, 1]) for g in range(tau.shape[1])]
+        if deployed_prev == deployed_new and not any(counts_differ):
+            continue                                       # the model's (GPU type, TP, count) tuples are unchanged
+        for g in range(tau.shape[1]):
+            if prev[z, g, 1]:
+                term = max(term, int(tau[z, g]))
+            if new[z, g, 1]:
+                load = max(load, int(tau[z, g]))
+    return term, load
+
+
+def trace_time(tau, plans, n_intervals, sched_ns, stale_ns, serve_ns):
+    """One candidate: plans [N_max][Z][G][2]; returns (N, sum_stale, sum_reconfig, sum_serve, T_total) in ns."""
+    n = int(n_intervals)
+    total_stale = total_reconfig = 0
+    total_serve = int(serve_ns[0])
+    for i in range(1, n):
+        term, load = reconfig_ns(tau, plans[i - 1], plans[i])
+        total_stale += int(stale_ns[i])
+        total_reconfig += term + load
+        total_serve += int(serve_ns[i])
+    return n, total_stale, total_reconfig, total_serve, int(sched_ns) + total_stale + total_reconfig + total_serve
