@@ -34,11 +34,11 @@ KERNEL_SOURCE_DIR = os.path.join(ROOT, "paper_2604_07144_amd", "csrc")
 # Keyed by configuration; valid only for the library source (all of csrc/) whose hash is recorded with it.
 MEASURED_TRAFFIC = {
     # cfg: (sha256 of the kernel source when measured, bytes per call)
-    4: ("cdfcf6c09b771448fb4495bb2405e873a4f8d1e555ffe50873f7f9aa755b7770", 4311565539),
-    3: ("cdfcf6c09b771448fb4495bb2405e873a4f8d1e555ffe50873f7f9aa755b7770", 543699962),
+    4: ("847895a926f18957f773a02c6d2f0942c8ff3f5b0e901e1a9c6d9f36e2584858", 4311255009),
+    3: ("847895a926f18957f773a02c6d2f0942c8ff3f5b0e901e1a9c6d9f36e2584858", 543742688),
 }
 # the same for one ap_eval_children call on the sparse form of configs[4]
-MEASURED_TRAFFIC_CHILDREN = {4: ("cdfcf6c09b771448fb4495bb2405e873a4f8d1e555ffe50873f7f9aa755b7770", 134397388)}
+MEASURED_TRAFFIC_CHILDREN = {4: ("847895a926f18957f773a02c6d2f0942c8ff3f5b0e901e1a9c6d9f36e2584858", 134397078)}
 
 
 def kernel_source_hash() -> str:

@@ -225,6 +225,45 @@ ap_status ap_roofline_costs(const ap_workload *w, const ap_model *models, uint32
                             uint32_t n_gpus, const ap_group *groups, uint32_t n_groups, uint32_t *prefill_us,
                             uint32_t *tpot_us);
 
+/* End-to-end trace time of candidate plan sequences (Section 5.1, execution model):
+ *   T_total = t_sched(1) + t_serve(1) + sum_{i=2}^{N} [ t_stale(i) + t_reconfig(i) + t_serve(i) ]
+ * with t_reconfig(i) = Reconfig-Cost(sigma_{i-1}, sigma_i) = T_term + T_load of Appendix "Serving
+ * Simulator": tau(z, g) = W_z / P_g * c_z is the weight transfer time of model z on GPU type g (W_z by
+ * the weight-size equation, c_z = pcie_coef[z]); over the models whose (GPU type, TP, count) tuples
+ * differ between the two plans, T_term is the largest tau on a GPU type the previous plan deploys them
+ * on and T_load the largest on a GPU type the new plan deploys them on; equal plans cost nothing.  The
+ * record is the evaluator's artifact feedback (Section 5.3, Table 1; the table's N counts reschedulings,
+ * n_intervals here counts intervals including the cold start). */
+typedef struct {
+    uint32_t tp;    /* tensor-parallel degree of the model's replicas on this GPU type */
+    uint32_t count; /* number of replicas; 0 = the model is not deployed on this GPU type */
+} ap_placement;
+
+typedef struct {
+    uint64_t total_ns;
+    uint64_t sum_stale_ns;
+    uint64_t sum_reconfig_ns;
+    uint64_t sum_serve_ns;
+    uint64_t sched_ns;
+    uint32_t n_intervals;
+    uint32_t reserved;
+} ap_breakdown;
+
+/*   models, pcie_coef, gpus : HOST arrays (n_models, n_models, n_gpus entries); of ap_gpu only
+ *                             pcie_bytes_per_s is used.
+ *   d_plans       : DEVICE, ap_placement [C][N_max][n_models][n_gpus]; plan i of candidate c is sigma_{i+1}.
+ *   d_n_intervals : DEVICE, uint32 [C]; N of each candidate, taken as at least 1 and at most N_max.
+ *   d_sched_ns    : DEVICE, uint64 [C]; t_sched(1).
+ *   d_stale_ns, d_serve_ns : DEVICE, uint64 [C][N_max]; t_stale(i+1), t_serve(i+1) at index i (stale[0] unused).
+ *   d_out         : DEVICE, ap_breakdown [C], written.
+ * All times are nanoseconds.  Synchronous (default stream; small temporary buffers).  C == 0 is a no-op.
+ * Errors: AP_ERR_INVALID (null pointers, empty arrays, a zero model field, a non-positive coefficient or
+ * bandwidth), AP_ERR_RANGE (n_models * n_gpus above 2^20), AP_ERR_ALLOC, AP_ERR_DEVICE. */
+ap_status ap_trace_time(const ap_model *models, const double *pcie_coef, uint32_t n_models, const ap_gpu *gpus,
+                        uint32_t n_gpus, const ap_placement *d_plans, const uint32_t *d_n_intervals,
+                        const uint64_t *d_sched_ns, const uint64_t *d_stale_ns, const uint64_t *d_serve_ns, uint32_t C,
+                        uint32_t N_max, ap_breakdown *d_out);
+
 /* Release the workload and its device memory.  NULL is accepted. */
 ap_status ap_workload_destroy(ap_workload *w);
 

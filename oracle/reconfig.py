@@ -66,7 +66,7 @@ def reconfig_ns(tau, prev, new):
 
 def trace_time(tau, plans, n_intervals, sched_ns, stale_ns, serve_ns):
     """One candidate: plans [N_max][Z][G][2]; returns (N, sum_stale, sum_reconfig, sum_serve, T_total) in ns."""
-    n = int(n_intervals)
+    n = min(max(int(n_intervals), 1), len(plans))          # at least the cold start, at most the plans given
     total_stale = total_reconfig = 0
     total_serve = int(serve_ns[0])
     for i in range(1, n):

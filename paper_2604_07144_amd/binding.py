@@ -30,6 +30,9 @@ GPU_DTYPE = np.dtype({"names": ["mem_bytes", "flops", "hbm_bytes_per_s", "pcie_b
                                 "link_inter_bytes_per_s", "gpus_per_node"],
                       "formats": ["<f8"] * 6 + ["<u4"], "offsets": [0, 8, 16, 24, 32, 40, 48], "itemsize": 56})
 GROUP_DTYPE = np.dtype([(n, "<u4") for n in ("model", "gpu", "tp", "batch")])
+PLACEMENT_DTYPE = np.dtype([("tp", "<u4"), ("count", "<u4")])
+BREAKDOWN_DTYPE = np.dtype([("total_ns", "<u8"), ("sum_stale_ns", "<u8"), ("sum_reconfig_ns", "<u8"), ("sum_serve_ns", "<u8"),
+                            ("sched_ns", "<u8"), ("n_intervals", "<u4"), ("reserved", "<u4")])
 assert REPLICA_DTYPE.itemsize == 32 and METRICS_DTYPE.itemsize == 64 and MODEL_DTYPE.itemsize == 28
 
 
@@ -74,6 +77,9 @@ def lib() -> C.CDLL:
         L.ap_roofline_costs.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32,
                                         C.c_void_p, C.c_void_p]
         L.ap_roofline_costs.restype = C.c_int
+        L.ap_trace_time.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p,
+                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p]
+        L.ap_trace_time.restype = C.c_int
         L.ap_workload_destroy.argtypes = [C.c_void_p]
         L.ap_workload_destroy.restype = C.c_int
         L.ap_status_str.argtypes = [C.c_int]
@@ -204,6 +210,20 @@ def ap_roofline_costs(workload: int, n_requests: int, models, gpus, groups):
     _check(lib().ap_roofline_costs(workload, models.ctypes.data, models.shape[0], gpus.ctypes.data, gpus.shape[0],
                                    groups.ctypes.data, G, prefill_us.ctypes.data, tpot_us.ctypes.data), "ap_roofline_costs")
     return prefill_us, tpot_us
+
+
+def ap_trace_time(models, pcie_coef, gpus, d_plans_ptr: int, d_n_intervals_ptr: int, d_sched_ns_ptr: int,
+                  d_stale_ns_ptr: int, d_serve_ns_ptr: int, n_candidates: int, n_max: int, d_out_ptr: int) -> None:
+    """Host descriptors (structured arrays, float64 coefficients), device pointers (ints) for the rest."""
+    models = np.ascontiguousarray(models, dtype=MODEL_DTYPE)
+    gpus = np.ascontiguousarray(gpus, dtype=GPU_DTYPE)
+    coef = np.ascontiguousarray(pcie_coef, dtype=np.float64)
+    if coef.shape != (models.shape[0],):
+        raise ValueError("one PCIe coefficient per model")
+    _check(lib().ap_trace_time(models.ctypes.data, coef.ctypes.data, models.shape[0], gpus.ctypes.data, gpus.shape[0],
+                               C.c_void_p(d_plans_ptr), C.c_void_p(d_n_intervals_ptr), C.c_void_p(d_sched_ns_ptr),
+                               C.c_void_p(d_stale_ns_ptr), C.c_void_p(d_serve_ns_ptr), int(n_candidates), int(n_max),
+                               C.c_void_p(d_out_ptr)), "ap_trace_time")
 
 
 def ap_workload_destroy(workload: int) -> None:

@@ -796,6 +796,73 @@ ap_status ap_roofline_costs(const ap_workload* w, const ap_model* models, uint32
     return AP_OK;
 }
 
+ap_status ap_trace_time(const ap_model* models, const double* pcie_coef, uint32_t n_models, const ap_gpu* gpus, uint32_t n_gpus,
+                        const ap_placement* d_plans, const uint32_t* d_n_intervals, const uint64_t* d_sched_ns,
+                        const uint64_t* d_stale_ns, const uint64_t* d_serve_ns, uint32_t C, uint32_t N_max,
+                        ap_breakdown* d_out) {
+    if (!models || !pcie_coef || !gpus || n_models == 0 || n_gpus == 0 || N_max == 0) return AP_ERR_INVALID;
+    if (C == 0) return AP_OK;
+    if (!d_plans || !d_n_intervals || !d_sched_ns || !d_stale_ns || !d_serve_ns || !d_out) return AP_ERR_INVALID;
+    if ((uint64_t)n_models * n_gpus > (1u << 20)) return AP_ERR_RANGE;
+    std::vector<RoofGroup> host;
+    std::vector<double> pcie;
+    try {
+        host.resize(n_models);
+        pcie.resize(n_gpus);
+    } catch (const std::bad_alloc&) {
+        return AP_ERR_ALLOC;
+    }
+    for (uint32_t z = 0; z < n_models; ++z) {
+        const ap_model& m = models[z];
+        if (m.layers == 0 || m.hidden == 0 || m.intermediate == 0 || m.vocab == 0 || m.heads == 0 || m.kv_heads == 0 ||
+            m.kv_heads > m.heads || m.weight_bits == 0 || !(pcie_coef[z] > 0.0))
+            return AP_ERR_INVALID;
+        RoofGroup o{};
+        o.L = m.layers; o.H = m.hidden; o.I = m.intermediate; o.V = m.vocab; o.A = m.heads; o.K = m.kv_heads;
+        o.e = (double)m.weight_bits / 8.0;
+        host[z] = o;
+    }
+    for (uint32_t g = 0; g < n_gpus; ++g) {
+        if (!(gpus[g].pcie_bytes_per_s > 0.0)) return AP_ERR_INVALID;
+        pcie[g] = gpus[g].pcie_bytes_per_s;
+    }
+    struct Temp {
+        RoofGroup* models = nullptr;
+        double* coef = nullptr;
+        double* pcie = nullptr;
+        unsigned long long* tau = nullptr;
+        ~Temp() {
+            for (void* q : {(void*)models, (void*)coef, (void*)pcie, (void*)tau})
+                if (q) (void)hipFree(q);
+        }
+    } tmp;
+    if (hipMalloc(&tmp.models, sizeof(RoofGroup) * n_models) != hipSuccess || hipMalloc(&tmp.coef, 8u * n_models) != hipSuccess ||
+        hipMalloc(&tmp.pcie, 8u * n_gpus) != hipSuccess || hipMalloc(&tmp.tau, 8u * (size_t)n_models * n_gpus) != hipSuccess) {
+        (void)hipGetLastError();
+        return AP_ERR_ALLOC;
+    }
+    if (hipMemcpy(tmp.models, host.data(), sizeof(RoofGroup) * n_models, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(tmp.coef, pcie_coef, 8u * n_models, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(tmp.pcie, pcie.data(), 8u * n_gpus, hipMemcpyHostToDevice) != hipSuccess)
+        return AP_ERR_DEVICE;
+    hipLaunchKernelGGL(k_transfer_times, dim3((n_models * n_gpus + kRoofThreads - 1u) / kRoofThreads), dim3(kRoofThreads), 0, nullptr,
+                       tmp.models, tmp.coef, n_models, tmp.pcie, n_gpus, tmp.tau);
+    TraceTimeParams tp{};
+    tp.tau_ns = tmp.tau;
+    tp.plans = d_plans;
+    tp.n_intervals = d_n_intervals;
+    tp.sched_ns = reinterpret_cast<const unsigned long long*>(d_sched_ns);
+    tp.stale_ns = reinterpret_cast<const unsigned long long*>(d_stale_ns);
+    tp.serve_ns = reinterpret_cast<const unsigned long long*>(d_serve_ns);
+    tp.C = C; tp.N_max = N_max; tp.Z = n_models; tp.G = n_gpus;
+    hipLaunchKernelGGL(k_trace_time, dim3((C + kRoofThreads - 1u) / kRoofThreads), dim3(kRoofThreads), 0, nullptr, tp, d_out);
+    if (hipGetLastError() != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+        (void)hipGetLastError();
+        return AP_ERR_DEVICE;
+    }
+    return AP_OK;
+}
+
 ap_status ap_workload_destroy(ap_workload* w) {
     if (!w) return AP_OK;
     bool ok = true;

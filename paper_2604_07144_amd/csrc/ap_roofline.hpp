@@ -142,6 +142,75 @@ __global__ __launch_bounds__(kRoofThreads) void k_roofline_request_costs(const u
     tpot_us[(size_t)gi * R + r] = (uint32_t)min(per_tok, 0xFFFFFFFFull);
 }
 
+// ----------------------------------------------------------------------------------
+// reconfiguration cost and end-to-end trace time
+// ----------------------------------------------------------------------------------
+// Weight transfer time tau(z, g) = W_z / P_g * c_z (Appendix "Serving Simulator", Reconfiguration Cost),
+// in whole nanoseconds.  `models` are RoofGroups of which only the model fields are used.
+__global__ __launch_bounds__(kRoofThreads) void k_transfer_times(const RoofGroup* __restrict__ models, const double* __restrict__ coef,
+                                                                 uint32_t n_models, const double* __restrict__ pcie,
+                                                                 uint32_t n_gpus, unsigned long long* __restrict__ tau_ns) {
+#pragma clang fp contract(off)
+    const uint32_t i = blockIdx.x * kRoofThreads + threadIdx.x;
+    if (i >= n_models * n_gpus) return;
+    const uint32_t z = i / n_gpus, g = i - z * n_gpus;
+    tau_ns[i] = roof_ns((roof_weight_bytes(models[z]) / pcie[g]) * coef[z]);
+}
+
+struct TraceTimeParams {
+    const unsigned long long* tau_ns;     // [Z][G]
+    const ap_placement* plans;            // [C][N_max][Z][G]
+    const uint32_t* n_intervals;          // [C]
+    const unsigned long long* sched_ns;   // [C]
+    const unsigned long long* stale_ns;   // [C][N_max]
+    const unsigned long long* serve_ns;   // [C][N_max]
+    uint32_t C, N_max, Z, G;
+};
+
+// One thread per candidate: T_total = t_sched(1) + t_serve(1) + sum over i >= 2 of t_stale(i) +
+// Reconfig-Cost(sigma_{i-1}, sigma_i) + t_serve(i) (Section 5.1, execution model), where
+// Reconfig-Cost = T_term + T_load: over the models whose (GPU type, TP, count) tuples changed, the largest
+// transfer time on a GPU type the previous plan had them on, plus the largest on a GPU type the new plan
+// puts them on.  Integers throughout.
+__global__ __launch_bounds__(kRoofThreads) void k_trace_time(TraceTimeParams p, ap_breakdown* __restrict__ out) {
+    const uint32_t c = blockIdx.x * kRoofThreads + threadIdx.x;
+    if (c >= p.C) return;
+    const uint32_t n = min(max(p.n_intervals[c], 1u), p.N_max);
+    const size_t per_plan = (size_t)p.Z * p.G;
+    const ap_placement* plans = p.plans + (size_t)c * p.N_max * per_plan;
+    unsigned long long stale = 0ull, reconfig = 0ull, serve = p.serve_ns[(size_t)c * p.N_max];
+    for (uint32_t i = 1; i < n; ++i) {
+        const ap_placement* prev = plans + (size_t)(i - 1u) * per_plan;
+        const ap_placement* next = plans + (size_t)i * per_plan;
+        unsigned long long term = 0ull, load = 0ull;
+        for (uint32_t z = 0; z < p.Z; ++z) {
+            bool changed = false;
+            for (uint32_t g = 0; g < p.G; ++g) {
+                const ap_placement a = prev[z * p.G + g], b = next[z * p.G + g];
+                changed = changed || a.count != b.count || (a.count != 0u && a.tp != b.tp);
+            }
+            if (!changed) continue;
+            for (uint32_t g = 0; g < p.G; ++g) {
+                const unsigned long long tau = p.tau_ns[z * p.G + g];
+                if (prev[z * p.G + g].count != 0u) term = max(term, tau);
+                if (next[z * p.G + g].count != 0u) load = max(load, tau);
+            }
+        }
+        stale += p.stale_ns[(size_t)c * p.N_max + i];
+        reconfig += term + load;
+        serve += p.serve_ns[(size_t)c * p.N_max + i];
+    }
+    ap_breakdown r;
+    r.sched_ns = p.sched_ns[c];
+    r.sum_stale_ns = stale;
+    r.sum_reconfig_ns = reconfig;
+    r.sum_serve_ns = serve;
+    r.total_ns = r.sched_ns + stale + reconfig + serve;
+    r.n_intervals = n;
+    r.reserved = 0u;
+    out[c] = r;
+}
+
 }  // namespace
 
 #endif  // AP_ROOFLINE_HPP
