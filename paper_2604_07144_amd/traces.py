@@ -30,7 +30,7 @@ COEF_STANDARD = (2000, 3, 25, 5)
 COEF_FAST = (1200, 2, 15, 3)
 COEF_SLOW = (3500, 5, 40, 8)
 
-_STREAM_ARRIVAL, _STREAM_PROMPT, _STREAM_OUT, _STREAM_REPLICA, _STREAM_ASSIGN, _STREAM_EDITS = 1, 2, 3, 4, 5, 6
+_STREAM_ARRIVAL, _STREAM_PROMPT, _STREAM_OUT, _STREAM_REPLICA, _STREAM_ASSIGN, _STREAM_EDITS, _STREAM_AGENTIC = 1, 2, 3, 4, 5, 6, 7
 
 
 def _rng(seed: int, stream: int, row: int = 0) -> np.random.Generator:
@@ -177,6 +177,59 @@ def draw_edit_lists(seed: int, n_children: int, R: int, M: int, mean_edits: floa
             order = np.argsort(request[lo:hi], kind="stable")
             request[lo:hi], replica[lo:hi] = request[lo:hi][order], replica[lo:hi][order]
     return first, request, replica
+
+
+def make_agentic(seed: int, W: int = 64, *, P: int = 4, Q: int = 4, mean_calls: float = 5.0, rate: float = 20.0,
+                 capacity: int = 16384) -> dict:
+    """A slice of multi-call agentic workflows (stands in for the 64-workflow ShareGPT slices of Section 8.3):
+    ``W`` workflows arriving as a Poisson process of ``rate`` per second; each a DAG of 1 + Poisson(mean_calls - 1)
+    calls in which call j depends on call j - 1 with probability 0.7 and on one or two earlier calls otherwise
+    (fan-out / fan-in), lengths log-normal like the request traces; ``P`` prefill and ``Q`` decode instances of three
+    speeds in turn; a committed horizon per workflow proportional to its total token count.  Inputs only: nothing
+    here schedules anything."""
+    rng = _rng(seed, _STREAM_AGENTIC)
+    arrival = np.floor(np.cumsum(rng.exponential(1.0 / rate, size=W)) * 1e6).astype(np.uint64)
+    wf, in_len, out_len, pred_first, pred = [], [], [], [0], []
+    for w in range(W):
+        n = 1 + int(rng.poisson(max(0.0, mean_calls - 1.0)))
+        base = len(wf)
+        for j in range(n):
+            wf.append(w)
+            in_len.append(int(np.clip(np.floor(rng.lognormal(6.0, 1.0)), 16, 8192)))
+            out_len.append(int(np.clip(np.floor(rng.lognormal(5.0, 1.0)), 1, 2048)))
+            if j > 0:
+                if rng.random() < 0.7:
+                    mine = {base + j - 1}
+                else:
+                    mine = {base + int(x) for x in rng.integers(0, j, size=int(rng.integers(1, 3)))}
+                pred.extend(sorted(mine))
+            pred_first.append(len(pred))
+    wf = np.asarray(wf, dtype=np.uint32)
+    in_len, out_len = np.asarray(in_len, dtype=np.uint32), np.asarray(out_len, dtype=np.uint32)
+    tokens = np.bincount(wf, weights=(in_len + out_len).astype(np.float64), minlength=W)
+    slo = np.maximum(1, np.floor(tokens * rng.uniform(20.0, 120.0, size=W))).astype(np.uint64)
+    kinds_p = ((1500, 2), (2500, 3), (900, 1))
+    kinds_q = ((25, 5), (40, 8), (15, 3))
+    return dict(arrival_us=arrival, slo_us=slo, wf=wf, in_len=in_len, out_len=out_len,
+                pred_first=np.asarray(pred_first, dtype=np.uint32), pred=np.asarray(pred, dtype=np.uint32),
+                pa=np.array([kinds_p[i % 3][0] for i in range(P)], dtype=np.uint32),
+                pb=np.array([kinds_p[i % 3][1] for i in range(P)], dtype=np.uint32),
+                qc=np.array([kinds_q[i % 3][0] for i in range(Q)], dtype=np.uint32),
+                qd=np.array([kinds_q[i % 3][1] for i in range(Q)], dtype=np.uint32),
+                cap=np.full(Q, capacity, dtype=np.uint32), penalty_permille=100_000)
+
+
+def draw_agentic_candidates(seed: int, n_candidates: int, K: int, P: int, Q: int, *, key_range: int = 1 << 20,
+                            bad_ids: bool = False):
+    """Candidate plans for ``K`` calls: a prefill instance, a decode instance and a queue key per call, uniform;
+    row 1 (if present) orders every queue by call index.  ``bad_ids`` lets a few ids fall outside the cluster."""
+    rng = _rng(seed, _STREAM_AGENTIC, 1)
+    pre = rng.integers(0, P + (1 if bad_ids else 0), size=(n_candidates, K)).astype(np.uint16)
+    dec = rng.integers(0, Q + (1 if bad_ids else 0), size=(n_candidates, K)).astype(np.uint16)
+    key = rng.integers(0, key_range, size=(n_candidates, K)).astype(np.uint32)
+    if n_candidates > 1:
+        key[1] = 0                                            # all keys equal: ties go to the lower call index
+    return pre, dec, key
 
 
 def _arrivals(spec: TraceSpec, R: int, rate_scale: float) -> np.ndarray:
