@@ -34,11 +34,11 @@ KERNEL_SOURCE_DIR = os.path.join(ROOT, "paper_2604_07144_amd", "csrc")
 # Keyed by configuration; valid only for the library source (all of csrc/) whose hash is recorded with it.
 MEASURED_TRAFFIC = {
     # cfg: (sha256 of the kernel source when measured, bytes per call)
-    4: ("847895a926f18957f773a02c6d2f0942c8ff3f5b0e901e1a9c6d9f36e2584858", 4311255009),
-    3: ("847895a926f18957f773a02c6d2f0942c8ff3f5b0e901e1a9c6d9f36e2584858", 543742688),
+    4: ("ca85b74230c57802bd19ae0a2a9c23f2ec45b927ba906d4146962486e49f19c3", 4310672871),
+    3: ("ca85b74230c57802bd19ae0a2a9c23f2ec45b927ba906d4146962486e49f19c3", 543638184),
 }
 # the same for one ap_eval_children call on the sparse form of configs[4]
-MEASURED_TRAFFIC_CHILDREN = {4: ("847895a926f18957f773a02c6d2f0942c8ff3f5b0e901e1a9c6d9f36e2584858", 134397078)}
+MEASURED_TRAFFIC_CHILDREN = {4: ("ca85b74230c57802bd19ae0a2a9c23f2ec45b927ba906d4146962486e49f19c3", 134398773)}
 
 
 def kernel_source_hash() -> str:
@@ -89,6 +89,60 @@ def algorithmic_bytes(C: int, R: int, n_types: int) -> int:
     return 2 * C * R + 64 * C + TABLE_BYTES_PER_REQUEST * n_types * R
 
 
+def agentic_bench(args) -> int:
+    """Candidate plans per second for one 64-workflow slice (Section 8.3 uses two such slices), plans resident in HBM."""
+    import torch
+    from paper_2604_07144_amd import binding, traces
+    torch.cuda.set_device(0)
+    fields = ("arrival_us", "slo_us", "wf", "in_len", "out_len", "pred_first", "pred", "pa", "pb", "qc", "qd", "cap",
+              "penalty_permille")
+    wl = traces.make_agentic(0, 64, P=4, Q=4, capacity=6000, rate=60.0)
+    K, C = len(wl["wf"]), args.rows if args.rows else 8192
+    pre, dec, key = traces.draw_agentic_candidates(0, C, K, 4, 4)
+    d_pre = torch.from_numpy(pre.view(np.int16)).cuda()
+    d_dec = torch.from_numpy(dec.view(np.int16)).cuda()
+    d_key = torch.from_numpy(key.view(np.int32)).cuda()
+    d_out = torch.zeros((C, 5), dtype=torch.int64, device="cuda")
+    h = binding.ap_agentic_create(*(wl[f] for f in fields))
+    stream = torch.cuda.current_stream()
+    try:
+        def step():
+            binding.ap_agentic_eval(h, d_pre.data_ptr(), d_dec.data_ptr(), d_key.data_ptr(), C, d_out.data_ptr(), stream.cuda_stream)
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        t0 = time.perf_counter()
+        for a, b in ev:
+            a.record(stream)
+            step()
+            b.record(stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        ms = [a.elapsed_time(b) for a, b in ev]
+        got = d_out.cpu().numpy().view(binding.AGENTIC_METRICS_DTYPE).reshape(-1)
+    finally:
+        binding.ap_agentic_destroy(h)
+    result = {"metric": "candidate plans/s (agentic workflows)", "value": C / (wall / args.steps), "unit": "plans/s",
+              "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps,
+              "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32", "data": "synthetic",
+              "config": {"workload": f"one 64-workflow slice: K={K} calls, 4 prefill + 4 decode instances, C={C} plans"},
+              "kernel_ms_avg": float(np.mean(ms)), "kernel_ms_min": float(np.min(ms)),
+              "call_stages_per_s": 2 * K * C / (float(np.mean(ms)) * 1e-3)}
+    if not args.no_cpu:
+        from oracle.agentic import AgenticOracle
+        orc = AgenticOracle.from_workload(wl)
+        n = min(C, 512)
+        t0 = time.perf_counter()
+        want = orc.eval_batch(pre[:n], dec[:n], key[:n])
+        cpu_s = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": n / cpu_s, "unit": "plans/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"the first {n} plans, {cpu_s:.2f} s on one thread",
+                                  "matches_gpu": bool(all(got[c].tolist() == want[c].tolist() for c in range(n)))}
+    print(json.dumps(result))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -104,9 +158,14 @@ def main() -> int:
                     help="pass the configuration's cost model as per-type tables (ap_costtable_set) instead of coefficients")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a 1 GiB device copy (reference dispatch for the HBM byte counters)")
+    ap.add_argument("--agentic", action="store_true",
+                    help="time the agentic-workflow evaluator instead (64-workflow slice, 8192 candidate plans); "
+                         "prints its own JSON line")
     args = ap.parse_args()
     if args.calibrate_copy:
         return copy_calibration()
+    if args.agentic:
+        return agentic_bench(args)
     if args.gpus != 1:
         print("bench.py: this path runs on one GPU; candidates are independent, so more GPUs would only "
               "split the rows. Run with --gpus 1.", file=sys.stderr)

@@ -264,6 +264,71 @@ ap_status ap_trace_time(const ap_model *models, const double *pcie_coef, uint32_
                         const uint64_t *d_sched_ns, const uint64_t *d_stale_ns, const uint64_t *d_serve_ns, uint32_t C,
                         uint32_t N_max, ap_breakdown *d_out);
 
+/* Agentic request scheduling (Section 8.3; Appendix "Scheduling Problem Formulation", Formulation for
+ * Agentic Request): multi-call workflows on a disaggregated cluster of prefill instances (one call at a
+ * time) and decode instances (each with a token-capacity budget).  A call becomes schedulable when its
+ * workflow has arrived and all its predecessor calls have completed.  A candidate plan gives every call
+ * a prefill instance, a decode instance and a queue key; on every instance the waiting call with the
+ * smallest (key, call index) goes first, a decode instance admitting its first waiting call as soon as
+ * in_len + out_len tokens fit the free part of its budget (no overtaking).  Events of one instant are
+ * applied as decode completions, prefill completions, releases, decode admissions, prefill starts.
+ * Prefill of call k on instance p takes base_us + per_tok_us * in_len[k]; decode on instance q takes
+ * out_len[k] * (base_us + per_kctx_us * ceil(in_len[k] / 1024)).  A call naming no prefill instance
+ * fails at its release; one naming no decode instance, or larger than that instance's whole budget,
+ * fails when its prefill ends; a failed call counts as completed then, and its workflow is charged
+ * penalty_permille.  Per workflow: ratio = completion time * 1000 / SLO (the completion ratio C / SLO in
+ * per mille). */
+typedef struct ap_agentic ap_agentic;
+
+typedef struct {
+    uint32_t base_us, per_tok_us;
+} ap_prefill_instance;
+
+typedef struct {
+    uint32_t base_us, per_kctx_us, capacity_tokens;
+} ap_decode_instance;
+
+/* Per candidate, 40 bytes: sum of the W ratios (mean = sum / W), their nearest-rank 95th and 99th
+ * percentiles (rank ceil(q W / 100)), latest completion minus earliest arrival, workflows with C > SLO
+ * (failed ones included), workflows with a failed call. */
+typedef struct {
+    uint64_t sum_ratio_permille;
+    uint64_t p95_permille;
+    uint64_t p99_permille;
+    uint64_t makespan_us;
+    uint32_t n_late;
+    uint32_t n_failed;
+} ap_agentic_metrics;
+
+#define AP_AGENTIC_MAX_CALLS 1024u
+#define AP_AGENTIC_MAX_WORKFLOWS 1024u
+#define AP_AGENTIC_MAX_INSTANCES 64u /* of either kind */
+
+/* All arrays are HOST arrays, copied.
+ *   arrival_us, slo_us : [W]; slo_us > 0.
+ *   wf, in_len, out_len : [K]; wf[k] < W; lengths >= 1.
+ *   pred_first [K + 1], pred : predecessors of call k are pred[pred_first[k] .. pred_first[k+1]); each must be
+ *       smaller than k and belong to the same workflow.
+ *   prefill [P], decode [Q] : base_us + per_tok_us >= 1 resp. base_us + per_kctx_us >= 1 (no stage takes no time).
+ * Errors: AP_ERR_INVALID (any of the above violated, null pointers, W, K, P or Q zero), AP_ERR_RANGE (a
+ * capacity above exceeded, or arrivals plus all stage times could leave 32-bit microseconds), AP_ERR_ALLOC,
+ * AP_ERR_DEVICE. */
+ap_status ap_agentic_create(const uint64_t *arrival_us, const uint64_t *slo_us, uint32_t W, const uint32_t *wf,
+                            const uint32_t *in_len, const uint32_t *out_len, const uint32_t *pred_first,
+                            const uint32_t *pred, uint32_t K, const ap_prefill_instance *prefill, uint32_t P,
+                            const ap_decode_instance *decode, uint32_t Q, uint64_t penalty_permille, ap_agentic **out);
+
+/* Score C candidate plans.
+ *   d_prefill, d_decode : DEVICE, uint16 [C][K]; an id >= P resp. >= Q is not an error (the call fails).
+ *   d_key               : DEVICE, uint32 [C][K].
+ *   d_out               : DEVICE, ap_agentic_metrics [C], written.
+ * Asynchronous on hip_stream; allocates nothing; one kernel.  C == 0 is a no-op.
+ * Errors: AP_ERR_INVALID (null pointers), AP_ERR_DEVICE. */
+ap_status ap_agentic_eval(const ap_agentic *a, const uint16_t *d_prefill, const uint16_t *d_decode, const uint32_t *d_key,
+                          uint32_t C, ap_agentic_metrics *d_out, void *hip_stream);
+
+ap_status ap_agentic_destroy(ap_agentic *a);
+
 /* Release the workload and its device memory.  NULL is accepted. */
 ap_status ap_workload_destroy(ap_workload *w);
 

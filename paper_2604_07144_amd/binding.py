@@ -31,6 +31,8 @@ GPU_DTYPE = np.dtype({"names": ["mem_bytes", "flops", "hbm_bytes_per_s", "pcie_b
                       "formats": ["<f8"] * 6 + ["<u4"], "offsets": [0, 8, 16, 24, 32, 40, 48], "itemsize": 56})
 GROUP_DTYPE = np.dtype([(n, "<u4") for n in ("model", "gpu", "tp", "batch")])
 PLACEMENT_DTYPE = np.dtype([("tp", "<u4"), ("count", "<u4")])
+AGENTIC_METRICS_DTYPE = np.dtype([("sum_ratio_permille", "<u8"), ("p95_permille", "<u8"), ("p99_permille", "<u8"),
+                                  ("makespan_us", "<u8"), ("n_late", "<u4"), ("n_failed", "<u4")])
 BREAKDOWN_DTYPE = np.dtype([("total_ns", "<u8"), ("sum_stale_ns", "<u8"), ("sum_reconfig_ns", "<u8"), ("sum_serve_ns", "<u8"),
                             ("sched_ns", "<u8"), ("n_intervals", "<u4"), ("reserved", "<u4")])
 assert REPLICA_DTYPE.itemsize == 32 and METRICS_DTYPE.itemsize == 64 and MODEL_DTYPE.itemsize == 28
@@ -80,6 +82,14 @@ def lib() -> C.CDLL:
         L.ap_trace_time.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p,
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p]
         L.ap_trace_time.restype = C.c_int
+        L.ap_agentic_create.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_uint64,
+                                        C.POINTER(C.c_void_p)]
+        L.ap_agentic_create.restype = C.c_int
+        L.ap_agentic_eval.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p]
+        L.ap_agentic_eval.restype = C.c_int
+        L.ap_agentic_destroy.argtypes = [C.c_void_p]
+        L.ap_agentic_destroy.restype = C.c_int
         L.ap_workload_destroy.argtypes = [C.c_void_p]
         L.ap_workload_destroy.restype = C.c_int
         L.ap_status_str.argtypes = [C.c_int]
@@ -224,6 +234,36 @@ def ap_trace_time(models, pcie_coef, gpus, d_plans_ptr: int, d_n_intervals_ptr: 
                                C.c_void_p(d_plans_ptr), C.c_void_p(d_n_intervals_ptr), C.c_void_p(d_sched_ns_ptr),
                                C.c_void_p(d_stale_ns_ptr), C.c_void_p(d_serve_ns_ptr), int(n_candidates), int(n_max),
                                C.c_void_p(d_out_ptr)), "ap_trace_time")
+
+
+def ap_agentic_create(arrival_us, slo_us, wf, in_len, out_len, pred_first, pred, pa, pb, qc, qd, cap,
+                      penalty_permille: int) -> int:
+    """Host arrays in (instances as parallel coefficient arrays), opaque handle out."""
+    arrival = np.ascontiguousarray(arrival_us, dtype=np.uint64)
+    slo = np.ascontiguousarray(slo_us, dtype=np.uint64)
+    wf, in_len, out_len = (np.ascontiguousarray(x, dtype=np.uint32) for x in (wf, in_len, out_len))
+    pred_first = np.ascontiguousarray(pred_first, dtype=np.uint32)
+    pred = np.append(np.asarray(pred, dtype=np.uint32), np.uint32(0))          # a valid pointer even when empty
+    prefill = np.ascontiguousarray(np.stack([np.asarray(pa, np.uint32), np.asarray(pb, np.uint32)], axis=1))
+    decode = np.ascontiguousarray(np.stack([np.asarray(qc, np.uint32), np.asarray(qd, np.uint32), np.asarray(cap, np.uint32)], axis=1))
+    if arrival.shape != slo.shape or not (wf.shape == in_len.shape == out_len.shape) or pred_first.shape != (wf.shape[0] + 1,):
+        raise ValueError("array lengths do not fit together")
+    handle = C.c_void_p()
+    _check(lib().ap_agentic_create(arrival.ctypes.data, slo.ctypes.data, arrival.shape[0], wf.ctypes.data, in_len.ctypes.data,
+                                   out_len.ctypes.data, pred_first.ctypes.data, pred.ctypes.data, wf.shape[0],
+                                   prefill.ctypes.data, prefill.shape[0], decode.ctypes.data, decode.shape[0],
+                                   int(penalty_permille), C.byref(handle)), "ap_agentic_create")
+    return handle.value
+
+
+def ap_agentic_eval(handle: int, d_prefill_ptr: int, d_decode_ptr: int, d_key_ptr: int, n_candidates: int, d_out_ptr: int,
+                    stream: int = 0) -> None:
+    _check(lib().ap_agentic_eval(handle, C.c_void_p(d_prefill_ptr), C.c_void_p(d_decode_ptr), C.c_void_p(d_key_ptr),
+                                 int(n_candidates), C.c_void_p(d_out_ptr), C.c_void_p(stream)), "ap_agentic_eval")
+
+
+def ap_agentic_destroy(handle: int) -> None:
+    _check(lib().ap_agentic_destroy(handle), "ap_agentic_destroy")
 
 
 def ap_workload_destroy(workload: int) -> None:

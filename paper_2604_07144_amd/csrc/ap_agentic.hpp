@@ -1,0 +1,272 @@
+// Agentic workflows on a disaggregated prefill/decode cluster: one wavefront replays one candidate plan.
+#ifndef AP_AGENTIC_HPP
+#define AP_AGENTIC_HPP
+
+#include "ap_common.hpp"
+
+namespace {
+
+// ----------------------------------------------------------------------------------
+// candidate plans for multi-call workflows (Section 8.3; Appendix, Formulation for Agentic Request)
+// ----------------------------------------------------------------------------------
+// A call is released when its workflow has arrived and all its predecessors have completed; it is
+// prefilled on its prefill instance (one call at a time, the waiting call with the smallest
+// (key, index) first), then decoded on its decode instance, which admits its first waiting call as
+// soon as the call's in + out tokens fit the free part of the instance's token budget (no
+// overtaking).  Events of one instant are applied as decode completions, prefill completions,
+// releases, decode admissions, prefill starts.  A call that names no prefill instance fails at its
+// release, one that names no decode instance or can never fit fails at the end of its prefill; a
+// failed call completes at that instant and its workflow is charged the penalty ratio.  Per
+// workflow: ratio = completion time * 1000 / SLO; per candidate: their sum, nearest-rank 95th and
+// 99th percentiles, the number of late and of failed workflows, the makespan.
+//
+// The event loop is serial in time, so the parallelism is across candidates (one wavefront each)
+// and, inside a step, across calls: the 64 lanes scan the call table for the next instant, apply the
+// completions and releases of that instant, and find the best waiting call of an instance by a
+// wavefront-wide minimum of (key, index).  Per-call state lives in LDS; the wavefronts of a
+// workgroup run their own loops and never meet at a barrier.
+struct AgenticParams {
+    const uint32_t* arrival;      // [W] microseconds after the earliest arrival
+    const unsigned long long* slo;  // [W]
+    const uint32_t* wf;           // [K]
+    const uint32_t* in_len;       // [K]
+    const uint32_t* out_len;      // [K]
+    const uint32_t* pred_first;   // [K + 1]
+    const uint32_t* pred;
+    const uint32_t* pa;           // [P] prefill: pa + pb * in_len
+    const uint32_t* pb;
+    const uint32_t* qc;           // [Q] decode: out_len * (qc + qd * ceil(in_len / 1024))
+    const uint32_t* qd;
+    const uint32_t* cap;          // [Q]
+    unsigned long long penalty;
+    uint32_t W, K, P, Q;
+    uint32_t wave_bytes;          // LDS per wavefront
+};
+
+constexpr uint32_t kAgenticWaves = 4;
+constexpr uint32_t kAgenticThreads = kAgenticWaves * kWave;
+enum : uint32_t { kBlocked = 0, kWaitPre = 1, kInPre = 2, kWaitDec = 3, kInDec = 4, kDone = 5 };
+
+__device__ __forceinline__ void wave_sync_lds() {
+    // LDS writes of any lane of this wavefront are visible to the lanes' later reads; keeps the compiler
+    // from carrying LDS values across the point
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+}
+
+__device__ __forceinline__ unsigned long long wave_min_u64(unsigned long long v) {
+#pragma unroll
+    for (uint32_t d = 32; d >= 1; d >>= 1) {
+        const unsigned long long o = (unsigned long long)__shfl_xor((long long)v, d);
+        v = o < v ? o : v;
+    }
+    return v;
+}
+
+__device__ __forceinline__ unsigned long long wave_or_u64(unsigned long long v) {
+#pragma unroll
+    for (uint32_t d = 32; d >= 1; d >>= 1) v |= (unsigned long long)__shfl_xor((long long)v, d);
+    return v;
+}
+
+__global__ __launch_bounds__(kAgenticThreads) void k_agentic_eval(AgenticParams p, const uint16_t* __restrict__ pre_inst,
+                                                                  const uint16_t* __restrict__ dec_inst,
+                                                                  const uint32_t* __restrict__ key,
+                                                                  ap_agentic_metrics* __restrict__ out, uint32_t C) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    const uint32_t lane = threadIdx.x & 63u, wv = wave_index();
+    const uint32_t K = p.K, W = p.W;
+    unsigned char* mine = lds + wv * p.wave_bytes;
+    // per call: event time (end of the running stage, or completion time), key, instance ids, phase
+    unsigned long long* ratio = reinterpret_cast<unsigned long long*>(mine);   // [W] (wave_bytes is a multiple of 16)
+    uint32_t* tev = reinterpret_cast<uint32_t*>(ratio + W);
+    uint32_t* ckey = tev + K;
+    uint32_t* comp = ckey + K;                                   // [W] completion time per workflow
+    uint32_t* used = comp + W;                                   // [Q] tokens in use
+    uint16_t* cpre = reinterpret_cast<uint16_t*>(used + p.Q);
+    uint16_t* cdec = cpre + K;
+    unsigned char* phase = reinterpret_cast<unsigned char*>(cdec + K);
+    unsigned char* busy = phase + K;                             // [P]
+    unsigned char* wf_failed = busy + p.P;                       // [W]
+
+    for (uint32_t c = blockIdx.x * kAgenticWaves + wv; c < C; c += gridDim.x * kAgenticWaves) {
+        for (uint32_t k = lane; k < K; k += kWave) {
+            tev[k] = 0u;
+            ckey[k] = key[(size_t)c * K + k];
+            cpre[k] = pre_inst[(size_t)c * K + k];
+            cdec[k] = dec_inst[(size_t)c * K + k];
+            phase[k] = (unsigned char)kBlocked;
+        }
+        for (uint32_t w = lane; w < W; w += kWave) {
+            comp[w] = p.arrival[w];                              // a workflow without calls completes on arrival
+            wf_failed[w] = 0;
+        }
+        for (uint32_t q = lane; q < p.Q; q += kWave) used[q] = 0u;
+        for (uint32_t i = lane; i < p.P; i += kWave) busy[i] = 0;
+        wave_sync_lds();
+
+        for (;;) {
+            // ---- the next instant at which something happens --------------------------------
+            uint32_t t = kNever;
+            for (uint32_t k = lane; k < K; k += kWave) {
+                const uint32_t ph = phase[k];
+                if (ph == kInPre || ph == kInDec) {
+                    t = min(t, tev[k]);
+                } else if (ph == kBlocked) {
+                    uint32_t at = p.arrival[p.wf[k]];
+                    bool ready = true;
+                    for (uint32_t i = p.pred_first[k]; i < p.pred_first[k + 1u]; ++i) {
+                        const uint32_t j = p.pred[i];
+                        ready = ready && phase[j] == kDone;
+                        at = max(at, tev[j]);
+                    }
+                    if (ready) t = min(t, at);
+                }
+            }
+            t = (uint32_t)__builtin_amdgcn_readfirstlane((int)~wave_max_u32(~t));                // wavefront minimum
+            if (t == kNever) break;
+
+            // ---- 1. completions: decode, then prefill ---------------------------------------
+            for (uint32_t k = lane; k < K; k += kWave) {
+                if (phase[k] == kInDec && tev[k] == t) {
+                    phase[k] = (unsigned char)kDone;
+                    atomicSub(&used[cdec[k]], p.in_len[k] + p.out_len[k]);
+                }
+            }
+            wave_sync_lds();
+            for (uint32_t k = lane; k < K; k += kWave) {
+                if (phase[k] == kInPre && tev[k] == t) {
+                    busy[cpre[k]] = 0;
+                    const uint32_t q = cdec[k];
+                    if (q >= p.Q || p.in_len[k] + p.out_len[k] > p.cap[q]) {
+                        phase[k] = (unsigned char)kDone;          // fails here; tev[k] == t is its completion time
+                        wf_failed[p.wf[k]] = 1;
+                    } else {
+                        phase[k] = (unsigned char)kWaitDec;
+                    }
+                }
+            }
+            wave_sync_lds();
+            // ---- 2. releases; a call that fails at its release completes now and may release others
+            for (;;) {
+                bool again = false;
+                for (uint32_t k = lane; k < K; k += kWave) {
+                    if (phase[k] != kBlocked || p.arrival[p.wf[k]] > t) continue;
+                    bool ready = true;
+                    for (uint32_t i = p.pred_first[k]; i < p.pred_first[k + 1u]; ++i) ready = ready && phase[p.pred[i]] == kDone;
+                    if (!ready) continue;
+                    if (cpre[k] >= p.P) {
+                        phase[k] = (unsigned char)kDone;
+                        tev[k] = t;
+                        wf_failed[p.wf[k]] = 1;
+                        again = true;
+                    } else {
+                        phase[k] = (unsigned char)kWaitPre;
+                    }
+                }
+                wave_sync_lds();
+                if (__ballot(again) == 0ull) break;
+            }
+            // ---- which instances have calls waiting -----------------------------------------
+            unsigned long long dec_waiting = 0ull, pre_waiting = 0ull;
+            for (uint32_t k = lane; k < K; k += kWave) {
+                const uint32_t ph = phase[k];
+                if (ph == kWaitDec) dec_waiting |= 1ull << cdec[k];
+                if (ph == kWaitPre) pre_waiting |= 1ull << cpre[k];
+            }
+            dec_waiting = wave_or_u64(dec_waiting);
+            pre_waiting = wave_or_u64(pre_waiting);
+            // ---- 3. decode admissions: the first waiting call of an instance, while it fits --
+            while (dec_waiting != 0ull) {
+                const uint32_t q = (uint32_t)__ffsll((long long)dec_waiting) - 1u;
+                dec_waiting &= dec_waiting - 1ull;
+                for (;;) {
+                    unsigned long long best = ~0ull;
+                    for (uint32_t k = lane; k < K; k += kWave)
+                        if (phase[k] == kWaitDec && cdec[k] == q) best = min(best, ((unsigned long long)ckey[k] << 32) | k);
+                    best = wave_min_u64(best);
+                    if (best == ~0ull) break;
+                    const uint32_t k = (uint32_t)best;            // the same in every lane
+                    const uint32_t need = p.in_len[k] + p.out_len[k];
+                    if (used[q] + need > p.cap[q]) break;
+                    if (lane == 0u) {
+                        used[q] += need;
+                        phase[k] = (unsigned char)kInDec;
+                        tev[k] = t + p.out_len[k] * (p.qc[q] + p.qd[q] * ((p.in_len[k] + 1023u) >> 10));
+                    }
+                    wave_sync_lds();
+                }
+            }
+            // ---- 4. prefill starts on idle instances -------------------------------------------
+            while (pre_waiting != 0ull) {
+                const uint32_t i = (uint32_t)__ffsll((long long)pre_waiting) - 1u;
+                pre_waiting &= pre_waiting - 1ull;
+                if (busy[i] != 0) continue;
+                unsigned long long best = ~0ull;
+                for (uint32_t k = lane; k < K; k += kWave)
+                    if (phase[k] == kWaitPre && cpre[k] == i) best = min(best, ((unsigned long long)ckey[k] << 32) | k);
+                best = wave_min_u64(best);
+                const uint32_t k = (uint32_t)best;
+                if (lane == 0u) {
+                    busy[i] = 1;
+                    phase[k] = (unsigned char)kInPre;
+                    tev[k] = t + p.pa[i] + p.pb[i] * p.in_len[k];
+                }
+                wave_sync_lds();
+            }
+        }
+
+        // ---- workflows -> completion ratios -> metrics --------------------------------------------
+        uint32_t last_done = 0u;
+        for (uint32_t k = lane; k < K; k += kWave) {
+            atomicMax(&comp[p.wf[k]], tev[k]);
+            last_done = max(last_done, tev[k]);
+        }
+        last_done = wave_max_u32(last_done);
+        wave_sync_lds();
+        unsigned long long sum = 0ull;
+        uint32_t n_late = 0u, n_failed = 0u;
+        for (uint32_t w = lane; w < W; w += kWave) {
+            const unsigned long long took = comp[w] - p.arrival[w];
+            const bool failed = wf_failed[w] != 0;
+            const unsigned long long r = failed ? p.penalty : took * 1000ull / p.slo[w];
+            ratio[w] = r;
+            sum += r;
+            n_late += (failed || took > p.slo[w]) ? 1u : 0u;
+            n_failed += failed ? 1u : 0u;
+        }
+        sum = wave_sum_u64(sum);
+        n_late = wave_sum_u32(n_late);
+        n_failed = wave_sum_u32(n_failed);
+        wave_sync_lds();
+        // nearest rank: the value whose rank among all ratios (ties by workflow index) is the wanted one
+        const uint32_t rank95 = (uint32_t)((95ull * W + 99ull) / 100ull) - 1u, rank99 = (uint32_t)((99ull * W + 99ull) / 100ull) - 1u;
+        unsigned long long p95 = 0ull, p99 = 0ull;
+        for (uint32_t w = lane; w < W; w += kWave) {
+            const unsigned long long r = ratio[w];
+            uint32_t rank = 0u;
+            for (uint32_t v = 0; v < W; ++v) {
+                const unsigned long long o = ratio[v];
+                rank += (o < r || (o == r && v < w)) ? 1u : 0u;
+            }
+            if (rank == rank95) p95 = r;
+            if (rank == rank99) p99 = r;
+        }
+        p95 = wave_or_u64(p95);                                  // exactly one lane holds each
+        p99 = wave_or_u64(p99);
+        if (lane == 0u) {
+            ap_agentic_metrics m;
+            m.sum_ratio_permille = sum;
+            m.p95_permille = p95;
+            m.p99_permille = p99;
+            m.makespan_us = last_done;
+            m.n_late = n_late;
+            m.n_failed = n_failed;
+            out[c] = m;
+        }
+        wave_sync_lds();
+    }
+}
+
+}  // namespace
+
+#endif  // AP_AGENTIC_HPP

@@ -21,13 +21,15 @@
 //
 // This file holds the host side: planning, the workload object and the C ABI.  The kernels are in
 // ap_screen.hpp (screening), ap_replay.hpp (fused replay), ap_pipeline.hpp (three-kernel replay) and
-// ap_children.hpp (sparse candidates) and ap_roofline.hpp (roofline cost tables); ap_common.hpp has what they share.
+// ap_children.hpp (sparse candidates), ap_roofline.hpp (roofline cost tables, trace time) and ap_agentic.hpp
+// (agentic workflows); ap_common.hpp has what they share.
 #include "ap_common.hpp"
 #include "ap_screen.hpp"
 #include "ap_replay.hpp"
 #include "ap_pipeline.hpp"
 #include "ap_children.hpp"
 #include "ap_roofline.hpp"
+#include "ap_agentic.hpp"
 
 namespace {
 
@@ -861,6 +863,146 @@ ap_status ap_trace_time(const ap_model* models, const double* pcie_coef, uint32_
         return AP_ERR_DEVICE;
     }
     return AP_OK;
+}
+
+// ---- agentic workflows ------------------------------------------------------------------
+struct ap_agentic {
+    int device = 0;
+    AgenticParams params{};
+    uint32_t lds_bytes = 0;
+    uint32_t n_cu = 0;
+    void* d_block = nullptr;          // one allocation behind all the tables
+};
+
+ap_status ap_agentic_create(const uint64_t* arrival_us, const uint64_t* slo_us, uint32_t W, const uint32_t* wf,
+                            const uint32_t* in_len, const uint32_t* out_len, const uint32_t* pred_first, const uint32_t* pred,
+                            uint32_t K, const ap_prefill_instance* prefill, uint32_t P, const ap_decode_instance* decode,
+                            uint32_t Q, uint64_t penalty_permille, ap_agentic** out) {
+    if (!arrival_us || !slo_us || !wf || !in_len || !out_len || !pred_first || !prefill || !decode || !out || W == 0 || K == 0 ||
+        P == 0 || Q == 0)
+        return AP_ERR_INVALID;
+    if (W > AP_AGENTIC_MAX_WORKFLOWS || K > AP_AGENTIC_MAX_CALLS || P > AP_AGENTIC_MAX_INSTANCES || Q > AP_AGENTIC_MAX_INSTANCES)
+        return AP_ERR_RANGE;
+    if (pred_first[0] != 0u) return AP_ERR_INVALID;
+    for (uint32_t k = 0; k < K; ++k) {
+        if (wf[k] >= W || in_len[k] == 0 || out_len[k] == 0 || pred_first[k + 1u] < pred_first[k]) return AP_ERR_INVALID;
+        if (pred_first[k + 1u] > pred_first[k] && !pred) return AP_ERR_INVALID;
+        for (uint32_t i = pred_first[k]; i < pred_first[k + 1u]; ++i)
+            if (pred[i] >= k || wf[pred[i]] != wf[k]) return AP_ERR_INVALID;
+    }
+    uint64_t first = arrival_us[0], last = arrival_us[0];
+    for (uint32_t w = 0; w < W; ++w) {
+        if (slo_us[w] == 0) return AP_ERR_INVALID;
+        first = std::min(first, arrival_us[w]);
+        last = std::max(last, arrival_us[w]);
+    }
+    for (uint32_t i = 0; i < P; ++i)
+        if ((uint64_t)prefill[i].base_us + prefill[i].per_tok_us == 0) return AP_ERR_INVALID;
+    for (uint32_t i = 0; i < Q; ++i)
+        if ((uint64_t)decode[i].base_us + decode[i].per_kctx_us == 0) return AP_ERR_INVALID;
+    // 32-bit time: no completion can lie beyond the last arrival plus every call's slowest stages in a row
+    const uint64_t limit = (uint64_t)kNever - 1u;
+    uint64_t total = last - first;
+    if (total > limit) return AP_ERR_RANGE;
+    for (uint32_t k = 0; k < K; ++k) {
+        uint64_t slow_pre = 0, slow_dec = 0;
+        for (uint32_t i = 0; i < P; ++i)
+            slow_pre = std::max<uint64_t>(slow_pre, (uint64_t)prefill[i].base_us + (uint64_t)prefill[i].per_tok_us * in_len[k]);
+        for (uint32_t i = 0; i < Q; ++i)
+            slow_dec = std::max<uint64_t>(slow_dec, (uint64_t)out_len[k] * ((uint64_t)decode[i].base_us +
+                                                    (uint64_t)decode[i].per_kctx_us * (((uint64_t)in_len[k] + 1023u) >> 10)));
+        if (slow_pre > limit || slow_dec > limit) return AP_ERR_RANGE;
+        total += slow_pre + slow_dec;
+        if (total > limit) return AP_ERR_RANGE;
+        if ((uint64_t)in_len[k] + out_len[k] > limit) return AP_ERR_RANGE;
+    }
+
+    ap_agentic* a = new (std::nothrow) ap_agentic;
+    if (!a) return AP_ERR_ALLOC;
+    ap_status st = AP_OK;
+    const uint32_t n_pred = pred_first[K];
+    std::vector<uint32_t> rel, pa, pb, qc, qd, cap;
+    try {
+        rel.resize(W); pa.resize(P); pb.resize(P); qc.resize(Q); qd.resize(Q); cap.resize(Q);
+    } catch (const std::bad_alloc&) {
+        delete a;
+        return AP_ERR_ALLOC;
+    }
+    for (uint32_t w = 0; w < W; ++w) rel[w] = (uint32_t)(arrival_us[w] - first);
+    for (uint32_t i = 0; i < P; ++i) { pa[i] = prefill[i].base_us; pb[i] = prefill[i].per_tok_us; }
+    for (uint32_t i = 0; i < Q; ++i) { qc[i] = decode[i].base_us; qd[i] = decode[i].per_kctx_us; cap[i] = decode[i].capacity_tokens; }
+    // one block: slo (8-byte entries) first, then the 4-byte tables
+    const size_t n_words = (size_t)W + 3u * K + (K + 1u) + std::max(1u, n_pred) + 2u * P + 3u * Q;
+    const size_t bytes = 8u * (size_t)W + 4u * n_words;
+    if (hipGetDevice(&a->device) != hipSuccess) st = AP_ERR_DEVICE;
+    if (st == AP_OK && hipMalloc(&a->d_block, bytes) != hipSuccess) st = AP_ERR_ALLOC;
+    int n_cu = 0, lds_cap = 0;
+    if (st == AP_OK && (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, a->device) != hipSuccess ||
+                        hipDeviceGetAttribute(&lds_cap, hipDeviceAttributeMaxSharedMemoryPerBlock, a->device) != hipSuccess))
+        st = AP_ERR_DEVICE;
+    if (st == AP_OK) {
+        unsigned char* base = static_cast<unsigned char*>(a->d_block);
+        unsigned long long* d_slo = reinterpret_cast<unsigned long long*>(base);
+        uint32_t* at = reinterpret_cast<uint32_t*>(base + 8u * (size_t)W);
+        auto put = [&](const uint32_t* src, size_t n) {
+            uint32_t* here = at;
+            if (n && hipMemcpy(here, src, 4u * n, hipMemcpyHostToDevice) != hipSuccess) st = AP_ERR_DEVICE;
+            at += n;
+            return here;
+        };
+        if (hipMemcpy(d_slo, slo_us, 8u * (size_t)W, hipMemcpyHostToDevice) != hipSuccess) st = AP_ERR_DEVICE;
+        AgenticParams& p = a->params;
+        p.slo = d_slo;
+        p.arrival = put(rel.data(), W);
+        p.wf = put(wf, K);
+        p.in_len = put(in_len, K);
+        p.out_len = put(out_len, K);
+        p.pred_first = put(pred_first, K + 1u);
+        p.pred = put(pred, n_pred);
+        at += n_pred ? 0u : 1u;
+        p.pa = put(pa.data(), P);
+        p.pb = put(pb.data(), P);
+        p.qc = put(qc.data(), Q);
+        p.qd = put(qd.data(), Q);
+        p.cap = put(cap.data(), Q);
+        p.penalty = penalty_permille;
+        p.W = W; p.K = K; p.P = P; p.Q = Q;
+        // per wavefront: ratio u64[W] | tev, key u32[K] | comp u32[W] | used u32[Q] | ids u16[2K] | phase u8[K] | busy u8[P] | failed u8[W]
+        const uint32_t wave_bytes = align_up(8u * W + 4u * (2u * K + W + Q) + 2u * 2u * K + K + P + W, 16u);
+        p.wave_bytes = wave_bytes;
+        a->lds_bytes = wave_bytes * kAgenticWaves;
+        a->n_cu = (uint32_t)n_cu;
+        if (a->lds_bytes > (uint32_t)lds_cap) st = AP_ERR_RANGE;
+        else if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_agentic_eval), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)a->lds_bytes) != hipSuccess)
+            st = AP_ERR_DEVICE;
+    }
+    if (st != AP_OK) {
+        (void)hipGetLastError();
+        ap_agentic_destroy(a);
+        return st;
+    }
+    *out = a;
+    return AP_OK;
+}
+
+ap_status ap_agentic_eval(const ap_agentic* a, const uint16_t* d_prefill, const uint16_t* d_decode, const uint32_t* d_key,
+                          uint32_t C, ap_agentic_metrics* d_out, void* hip_stream) {
+    if (!a) return AP_ERR_INVALID;
+    if (C == 0) return AP_OK;
+    if (!d_prefill || !d_decode || !d_key || !d_out) return AP_ERR_INVALID;
+    const uint32_t blocks = std::min((C + kAgenticWaves - 1u) / kAgenticWaves, a->n_cu * 64u);
+    hipLaunchKernelGGL(k_agentic_eval, dim3(blocks), dim3(kAgenticThreads), a->lds_bytes, static_cast<hipStream_t>(hip_stream),
+                       a->params, d_prefill, d_decode, d_key, d_out, C);
+    if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
+    return AP_OK;
+}
+
+ap_status ap_agentic_destroy(ap_agentic* a) {
+    if (!a) return AP_OK;
+    const bool ok = !a->d_block || hipFree(a->d_block) == hipSuccess;
+    delete a;
+    return ok ? AP_OK : AP_ERR_DEVICE;
 }
 
 ap_status ap_workload_destroy(ap_workload* w) {

@@ -1,0 +1,104 @@
+"""GPU parity for candidate plans of agentic workflows (``ap_agentic_*``), through the C ABI, against the
+serial CPU oracle: integer work, so every field of every record must be equal."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+from oracle.agentic import AgenticOracle                   # noqa: E402
+from paper_2604_07144_amd import binding, traces          # noqa: E402
+
+FIELDS = ("arrival_us", "slo_us", "wf", "in_len", "out_len", "pred_first", "pred", "pa", "pb", "qc", "qd", "cap",
+          "penalty_permille")
+
+
+def gpu_eval(wl, pre, dec, key):
+    handle = binding.ap_agentic_create(*(wl[f] for f in FIELDS))
+    try:
+        C = pre.shape[0]
+        d_pre = torch.from_numpy(np.ascontiguousarray(pre, dtype=np.uint16).view(np.int16)).cuda()
+        d_dec = torch.from_numpy(np.ascontiguousarray(dec, dtype=np.uint16).view(np.int16)).cuda()
+        d_key = torch.from_numpy(np.ascontiguousarray(key, dtype=np.uint32).view(np.int32)).cuda()
+        d_out = torch.full((C, 5), -1, dtype=torch.int64, device="cuda")
+        binding.ap_agentic_eval(handle, d_pre.data_ptr(), d_dec.data_ptr(), d_key.data_ptr(), C, d_out.data_ptr(),
+                                torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        return d_out.cpu().numpy().view(binding.AGENTIC_METRICS_DTYPE).reshape(-1)
+    finally:
+        binding.ap_agentic_destroy(handle)
+
+
+def both(wl, pre, dec, key, what):
+    got = gpu_eval(wl, pre, dec, key)
+    want = AgenticOracle.from_workload(wl).eval_batch(pre, dec, key)
+    for c in range(pre.shape[0]):
+        assert got[c].tolist() == want[c].tolist(), (what, c, got[c], want[c])
+    return got
+
+
+def tiny(P=1, cap=300):
+    return dict(arrival_us=[0], slo_us=[10000], wf=[0, 0, 0], in_len=[100, 200, 50], out_len=[10, 5, 20],
+                pred_first=[0, 0, 1, 2], pred=[0, 0], pa=[100] * P, pb=[1] * P, qc=[10], qd=[0], cap=[cap],
+                penalty_permille=77_000)
+
+
+def test_hand_worked_schedules_on_gpu():
+    rows = lambda *r: tuple(np.array([x], dtype=t) for x, t in zip(r, (np.uint16, np.uint16, np.uint32)))
+    got = both(tiny(), *rows([0, 0, 0], [0, 0, 0], [0, 1, 0]), "one prefill instance")
+    assert (int(got["sum_ratio_permille"][0]), int(got["makespan_us"][0])) == (80, 800)
+    got = both(tiny(P=2, cap=250), *rows([0, 0, 1], [0, 0, 0], [0, 0, 0]), "budget blocks admission")
+    assert int(got["makespan_us"][0]) == 700
+    got = both(tiny(P=2, cap=150), *rows([0, 0, 1], [0, 0, 0], [0, 0, 0]), "a call that never fits")
+    assert (int(got["sum_ratio_permille"][0]), int(got["n_failed"][0])) == (77_000, 1)
+    both(tiny(P=2), *rows([9, 0, 1], [0, 0, 9], [0, 0, 0]), "unknown instances")
+
+
+@pytest.mark.parametrize("seed,W,P,Q,capacity,rate,mean_calls", [
+    (0, 64, 4, 4, 16384, 20.0, 5.0),        # the paper-shaped slice, light
+    (1, 64, 2, 2, 3000, 200.0, 5.0),        # contended on both stages, some ids outside the cluster
+    (2, 64, 1, 3, 9000, 80.0, 5.0),
+    (3, 64, 3, 1, 12000, 500.0, 5.0),
+    (4, 1, 1, 1, 20000, 10.0, 1.0),         # one workflow
+    (5, 33, 5, 7, 6000, 300.0, 9.0),        # odd sizes
+    (6, 200, 64, 64, 4000, 2000.0, 5.0),    # as many instances as lanes, about a thousand calls
+    (7, 64, 4, 4, 1200, 50.0, 3.0),         # tiny budgets: many calls can never fit
+])
+def test_random_workloads(seed, W, P, Q, capacity, rate, mean_calls):
+    wl = traces.make_agentic(seed, W, P=P, Q=Q, capacity=capacity, rate=rate, mean_calls=mean_calls)
+    K = len(wl["wf"])
+    assert K <= 1024
+    pre, dec, key = traces.draw_agentic_candidates(seed, 48, K, P, Q, key_range=[1 << 20, 40][seed % 2], bad_ids=seed == 1)
+    got = both(wl, pre, dec, key, f"seed {seed} K={K}")
+    assert len({tuple(r) for r in got.tolist()}) > 1 or W == 1
+
+
+def test_error_paths():
+    torch.cuda.init()
+    wl = traces.make_agentic(0, 8)
+
+    def status(**change):
+        args = dict(wl)
+        args.update(change)
+        with pytest.raises(binding.ApError) as e:
+            binding.ap_agentic_create(*(args[f] for f in FIELDS))
+        return e.value.status
+
+    bad = wl["wf"].copy(); bad[0] = 99
+    assert status(wf=bad) == binding.AP_ERR_INVALID
+    bad = wl["in_len"].copy(); bad[1] = 0
+    assert status(in_len=bad) == binding.AP_ERR_INVALID
+    bad = wl["slo_us"].copy(); bad[2] = 0
+    assert status(slo_us=bad) == binding.AP_ERR_INVALID
+    if len(wl["pred"]):
+        bad = wl["pred"].copy(); bad[0] = len(wl["wf"]) - 1          # a predecessor that is not earlier
+        assert status(pred=bad) == binding.AP_ERR_INVALID
+    assert status(pa=[0] * 4, pb=[0] * 4) == binding.AP_ERR_INVALID          # a stage that takes no time
+    assert status(pa=[0xFFFFFFFF] * 4) == binding.AP_ERR_RANGE               # times beyond 32 bits
+    assert status(pa=[1] * 65, pb=[1] * 65) == binding.AP_ERR_RANGE          # more instances than supported
+    h = binding.ap_agentic_create(*(wl[f] for f in FIELDS))
+    with pytest.raises(binding.ApError) as e:
+        binding.ap_agentic_eval(h, 0, 0, 0, 1, 0)
+    assert e.value.status == binding.AP_ERR_INVALID
+    binding.ap_agentic_eval(h, 0, 0, 0, 0, 0)                                 # C == 0
+    binding.ap_agentic_destroy(h)
