@@ -34,11 +34,11 @@ KERNEL_SOURCE_DIR = os.path.join(ROOT, "paper_2604_07144_amd", "csrc")
 # Keyed by configuration; valid only for the library source (all of csrc/) whose hash is recorded with it.
 MEASURED_TRAFFIC = {
     # cfg: (sha256 of the kernel source when measured, bytes per call)
-    4: ("ca85b74230c57802bd19ae0a2a9c23f2ec45b927ba906d4146962486e49f19c3", 4310672871),
-    3: ("ca85b74230c57802bd19ae0a2a9c23f2ec45b927ba906d4146962486e49f19c3", 543638184),
+    4: ("bd439e74ef6cdc4e0d6be27d4c0079810937e76c21b2b5de904bcff647aca442", 4311304784),
+    3: ("bd439e74ef6cdc4e0d6be27d4c0079810937e76c21b2b5de904bcff647aca442", 543707559),
 }
 # the same for one ap_eval_children call on the sparse form of configs[4]
-MEASURED_TRAFFIC_CHILDREN = {4: ("ca85b74230c57802bd19ae0a2a9c23f2ec45b927ba906d4146962486e49f19c3", 134398773)}
+MEASURED_TRAFFIC_CHILDREN = {4: ("bd439e74ef6cdc4e0d6be27d4c0079810937e76c21b2b5de904bcff647aca442", 134407087)}
 
 
 def kernel_source_hash() -> str:

@@ -31,8 +31,9 @@ struct AgenticParams {
     const uint32_t* wf;           // [K]
     const uint32_t* in_len;       // [K]
     const uint32_t* out_len;      // [K]
-    const uint32_t* pred_first;   // [K + 1]
-    const uint32_t* pred;
+    const uint32_t* n_pred;       // [K] number of predecessors
+    const uint32_t* succ_first;   // [K + 1] successors of call k: succ[succ_first[k] .. succ_first[k + 1])
+    const uint32_t* succ;
     const uint32_t* pa;           // [P] prefill: pa + pb * in_len
     const uint32_t* pb;
     const uint32_t* qc;           // [Q] decode: out_len * (qc + qd * ceil(in_len / 1024))
@@ -68,6 +69,16 @@ __device__ __forceinline__ unsigned long long wave_or_u64(unsigned long long v) 
     return v;
 }
 
+// Call k has completed: each successor has one predecessor less to wait for.  (Byte counters: the
+// decrement goes through the 32-bit word that holds the byte; no borrow can cross into the next
+// byte because a counter is decremented exactly as often as it was set.)
+__device__ __forceinline__ void agentic_notify(const AgenticParams& p, unsigned char* left, uint32_t k) {
+    for (uint32_t i = p.succ_first[k]; i < p.succ_first[k + 1u]; ++i) {
+        const uint32_t s = p.succ[i];
+        atomicSub(reinterpret_cast<uint32_t*>(left + (s & ~3u)), 1u << ((s & 3u) * 8u));
+    }
+}
+
 __global__ __launch_bounds__(kAgenticThreads) void k_agentic_eval(AgenticParams p, const uint16_t* __restrict__ pre_inst,
                                                                   const uint16_t* __restrict__ dec_inst,
                                                                   const uint32_t* __restrict__ key,
@@ -77,14 +88,16 @@ __global__ __launch_bounds__(kAgenticThreads) void k_agentic_eval(AgenticParams 
     const uint32_t K = p.K, W = p.W;
     unsigned char* mine = lds + wv * p.wave_bytes;
     // per call: event time (end of the running stage, or completion time), key, instance ids, phase
-    unsigned long long* ratio = reinterpret_cast<unsigned long long*>(mine);   // [W] (wave_bytes is a multiple of 16)
-    uint32_t* tev = reinterpret_cast<uint32_t*>(ratio + W);
-    uint32_t* ckey = tev + K;
-    uint32_t* comp = ckey + K;                                   // [W] completion time per workflow
+    // (the ratios reuse the key area once the event loop is over; wave_bytes is a multiple of 16)
+    uint32_t* ckey = reinterpret_cast<uint32_t*>(mine);          // [max(K, 2 W)]
+    unsigned long long* ratio = reinterpret_cast<unsigned long long*>(mine);   // [W]
+    uint32_t* tev = ckey + max(K, 2u * W);
+    uint32_t* comp = tev + K;                                    // [W] completion time per workflow
     uint32_t* used = comp + W;                                   // [Q] tokens in use
     uint16_t* cpre = reinterpret_cast<uint16_t*>(used + p.Q);
     uint16_t* cdec = cpre + K;
-    unsigned char* phase = reinterpret_cast<unsigned char*>(cdec + K);
+    unsigned char* left = reinterpret_cast<unsigned char*>(cdec + K);   // [K] predecessors still to complete; 4-byte aligned
+    unsigned char* phase = left + K;
     unsigned char* busy = phase + K;                             // [P]
     unsigned char* wf_failed = busy + p.P;                       // [W]
 
@@ -95,6 +108,7 @@ __global__ __launch_bounds__(kAgenticThreads) void k_agentic_eval(AgenticParams 
             cpre[k] = pre_inst[(size_t)c * K + k];
             cdec[k] = dec_inst[(size_t)c * K + k];
             phase[k] = (unsigned char)kBlocked;
+            left[k] = (unsigned char)p.n_pred[k];
         }
         for (uint32_t w = lane; w < W; w += kWave) {
             comp[w] = p.arrival[w];                              // a workflow without calls completes on arrival
@@ -104,74 +118,66 @@ __global__ __launch_bounds__(kAgenticThreads) void k_agentic_eval(AgenticParams 
         for (uint32_t i = lane; i < p.P; i += kWave) busy[i] = 0;
         wave_sync_lds();
 
+        // Times are relative to the earliest arrival, so the first instant is 0.  Every step applies the
+        // instant's completions (one scan of the call table), then its releases together with the census
+        // of waiting calls and of what happens next (a second scan), then admissions and starts (a scan per
+        // call that starts).  The next instant is the earliest end of a stage in service or arrival of a
+        // workflow whose first calls are still to come.
+        uint32_t t = 0u;
         for (;;) {
-            // ---- the next instant at which something happens --------------------------------
-            uint32_t t = kNever;
+            // ---- 1. completions: decode (frees tokens), prefill (on to the decode queue, or fails) ----
             for (uint32_t k = lane; k < K; k += kWave) {
                 const uint32_t ph = phase[k];
-                if (ph == kInPre || ph == kInDec) {
-                    t = min(t, tev[k]);
-                } else if (ph == kBlocked) {
-                    uint32_t at = p.arrival[p.wf[k]];
-                    bool ready = true;
-                    for (uint32_t i = p.pred_first[k]; i < p.pred_first[k + 1u]; ++i) {
-                        const uint32_t j = p.pred[i];
-                        ready = ready && phase[j] == kDone;
-                        at = max(at, tev[j]);
-                    }
-                    if (ready) t = min(t, at);
-                }
-            }
-            t = (uint32_t)__builtin_amdgcn_readfirstlane((int)~wave_max_u32(~t));                // wavefront minimum
-            if (t == kNever) break;
-
-            // ---- 1. completions: decode, then prefill ---------------------------------------
-            for (uint32_t k = lane; k < K; k += kWave) {
-                if (phase[k] == kInDec && tev[k] == t) {
+                if (ph == kInDec && tev[k] == t) {
                     phase[k] = (unsigned char)kDone;
                     atomicSub(&used[cdec[k]], p.in_len[k] + p.out_len[k]);
-                }
-            }
-            wave_sync_lds();
-            for (uint32_t k = lane; k < K; k += kWave) {
-                if (phase[k] == kInPre && tev[k] == t) {
+                    agentic_notify(p, left, k);
+                } else if (ph == kInPre && tev[k] == t) {
                     busy[cpre[k]] = 0;
                     const uint32_t q = cdec[k];
                     if (q >= p.Q || p.in_len[k] + p.out_len[k] > p.cap[q]) {
                         phase[k] = (unsigned char)kDone;          // fails here; tev[k] == t is its completion time
                         wf_failed[p.wf[k]] = 1;
+                        agentic_notify(p, left, k);
                     } else {
                         phase[k] = (unsigned char)kWaitDec;
                     }
                 }
             }
             wave_sync_lds();
-            // ---- 2. releases; a call that fails at its release completes now and may release others
+            // ---- 2. releases, and in the same scan: who is waiting where, what comes next ------------
+            // (repeated only when a call failed at its release: it has completed now and may release others)
+            unsigned long long dec_waiting, pre_waiting;
+            uint32_t t_next;
             for (;;) {
                 bool again = false;
+                dec_waiting = pre_waiting = 0ull;
+                t_next = kNever;
                 for (uint32_t k = lane; k < K; k += kWave) {
-                    if (phase[k] != kBlocked || p.arrival[p.wf[k]] > t) continue;
-                    bool ready = true;
-                    for (uint32_t i = p.pred_first[k]; i < p.pred_first[k + 1u]; ++i) ready = ready && phase[p.pred[i]] == kDone;
-                    if (!ready) continue;
-                    if (cpre[k] >= p.P) {
-                        phase[k] = (unsigned char)kDone;
-                        tev[k] = t;
-                        wf_failed[p.wf[k]] = 1;
-                        again = true;
-                    } else {
-                        phase[k] = (unsigned char)kWaitPre;
+                    uint32_t ph = phase[k];
+                    if (ph == kBlocked) {
+                        const bool ready = left[k] == 0;
+                        const uint32_t arrives = p.arrival[p.wf[k]];
+                        if (ready && arrives > t) t_next = min(t_next, arrives);
+                        if (ready && arrives <= t) {
+                            if (cpre[k] >= p.P) {
+                                ph = kDone;
+                                tev[k] = t;
+                                wf_failed[p.wf[k]] = 1;
+                                agentic_notify(p, left, k);
+                                again = true;
+                            } else {
+                                ph = kWaitPre;
+                            }
+                            phase[k] = (unsigned char)ph;
+                        }
                     }
+                    if (ph == kWaitDec) dec_waiting |= 1ull << cdec[k];
+                    if (ph == kWaitPre) pre_waiting |= 1ull << cpre[k];
+                    if (ph == kInPre || ph == kInDec) t_next = min(t_next, tev[k]);
                 }
                 wave_sync_lds();
                 if (__ballot(again) == 0ull) break;
-            }
-            // ---- which instances have calls waiting -----------------------------------------
-            unsigned long long dec_waiting = 0ull, pre_waiting = 0ull;
-            for (uint32_t k = lane; k < K; k += kWave) {
-                const uint32_t ph = phase[k];
-                if (ph == kWaitDec) dec_waiting |= 1ull << cdec[k];
-                if (ph == kWaitPre) pre_waiting |= 1ull << cpre[k];
             }
             dec_waiting = wave_or_u64(dec_waiting);
             pre_waiting = wave_or_u64(pre_waiting);
@@ -188,10 +194,12 @@ __global__ __launch_bounds__(kAgenticThreads) void k_agentic_eval(AgenticParams 
                     const uint32_t k = (uint32_t)best;            // the same in every lane
                     const uint32_t need = p.in_len[k] + p.out_len[k];
                     if (used[q] + need > p.cap[q]) break;
+                    const uint32_t ends = t + p.out_len[k] * (p.qc[q] + p.qd[q] * ((p.in_len[k] + 1023u) >> 10));
+                    t_next = min(t_next, ends);
                     if (lane == 0u) {
                         used[q] += need;
                         phase[k] = (unsigned char)kInDec;
-                        tev[k] = t + p.out_len[k] * (p.qc[q] + p.qd[q] * ((p.in_len[k] + 1023u) >> 10));
+                        tev[k] = ends;
                     }
                     wave_sync_lds();
                 }
@@ -206,13 +214,17 @@ __global__ __launch_bounds__(kAgenticThreads) void k_agentic_eval(AgenticParams 
                     if (phase[k] == kWaitPre && cpre[k] == i) best = min(best, ((unsigned long long)ckey[k] << 32) | k);
                 best = wave_min_u64(best);
                 const uint32_t k = (uint32_t)best;
+                const uint32_t ends = t + p.pa[i] + p.pb[i] * p.in_len[k];
+                t_next = min(t_next, ends);
                 if (lane == 0u) {
                     busy[i] = 1;
                     phase[k] = (unsigned char)kInPre;
-                    tev[k] = t + p.pa[i] + p.pb[i] * p.in_len[k];
+                    tev[k] = ends;
                 }
                 wave_sync_lds();
             }
+            t = (uint32_t)__builtin_amdgcn_readfirstlane((int)~wave_max_u32(~t_next));            // wavefront minimum
+            if (t == kNever) break;
         }
 
         // ---- workflows -> completion ratios -> metrics --------------------------------------------

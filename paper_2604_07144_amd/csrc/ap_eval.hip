@@ -929,10 +929,39 @@ ap_status ap_agentic_create(const uint64_t* arrival_us, const uint64_t* slo_us, 
         return AP_ERR_ALLOC;
     }
     for (uint32_t w = 0; w < W; ++w) rel[w] = (uint32_t)(arrival_us[w] - first);
+    // the kernel counts down a call's outstanding predecessors, so it wants the lists the other way round
+    std::vector<uint32_t> n_pred_of, succ_first, succ;
+    try {
+        n_pred_of.assign(K, 0u);
+        succ_first.assign(K + 1u, 0u);
+        succ.assign(std::max(1u, n_pred), 0u);
+    } catch (const std::bad_alloc&) {
+        delete a;
+        return AP_ERR_ALLOC;
+    }
+    for (uint32_t k = 0; k < K; ++k) {
+        // a predecessor listed twice counts once: keep distinct ones
+        std::vector<uint32_t> mine(pred + pred_first[k], pred + pred_first[k + 1u]);
+        std::sort(mine.begin(), mine.end());
+        mine.erase(std::unique(mine.begin(), mine.end()), mine.end());
+        if (mine.size() > 255u) { delete a; return AP_ERR_RANGE; }
+        n_pred_of[k] = (uint32_t)mine.size();
+        for (uint32_t j : mine) ++succ_first[j + 1u];
+    }
+    for (uint32_t k = 0; k < K; ++k) succ_first[k + 1u] += succ_first[k];
+    {
+        std::vector<uint32_t> fill(succ_first.begin(), succ_first.end() - 1);
+        for (uint32_t k = 0; k < K; ++k) {
+            std::vector<uint32_t> mine(pred + pred_first[k], pred + pred_first[k + 1u]);
+            std::sort(mine.begin(), mine.end());
+            mine.erase(std::unique(mine.begin(), mine.end()), mine.end());
+            for (uint32_t j : mine) succ[fill[j]++] = k;
+        }
+    }
     for (uint32_t i = 0; i < P; ++i) { pa[i] = prefill[i].base_us; pb[i] = prefill[i].per_tok_us; }
     for (uint32_t i = 0; i < Q; ++i) { qc[i] = decode[i].base_us; qd[i] = decode[i].per_kctx_us; cap[i] = decode[i].capacity_tokens; }
     // one block: slo (8-byte entries) first, then the 4-byte tables
-    const size_t n_words = (size_t)W + 3u * K + (K + 1u) + std::max(1u, n_pred) + 2u * P + 3u * Q;
+    const size_t n_words = (size_t)W + 4u * K + (K + 1u) + std::max(1u, n_pred) + 2u * P + 3u * Q;
     const size_t bytes = 8u * (size_t)W + 4u * n_words;
     if (hipGetDevice(&a->device) != hipSuccess) st = AP_ERR_DEVICE;
     if (st == AP_OK && hipMalloc(&a->d_block, bytes) != hipSuccess) st = AP_ERR_ALLOC;
@@ -957,9 +986,9 @@ ap_status ap_agentic_create(const uint64_t* arrival_us, const uint64_t* slo_us, 
         p.wf = put(wf, K);
         p.in_len = put(in_len, K);
         p.out_len = put(out_len, K);
-        p.pred_first = put(pred_first, K + 1u);
-        p.pred = put(pred, n_pred);
-        at += n_pred ? 0u : 1u;
+        p.n_pred = put(n_pred_of.data(), K);
+        p.succ_first = put(succ_first.data(), K + 1u);
+        p.succ = put(succ.data(), std::max(1u, n_pred));
         p.pa = put(pa.data(), P);
         p.pb = put(pb.data(), P);
         p.qc = put(qc.data(), Q);
@@ -967,8 +996,9 @@ ap_status ap_agentic_create(const uint64_t* arrival_us, const uint64_t* slo_us, 
         p.cap = put(cap.data(), Q);
         p.penalty = penalty_permille;
         p.W = W; p.K = K; p.P = P; p.Q = Q;
-        // per wavefront: ratio u64[W] | tev, key u32[K] | comp u32[W] | used u32[Q] | ids u16[2K] | phase u8[K] | busy u8[P] | failed u8[W]
-        const uint32_t wave_bytes = align_up(8u * W + 4u * (2u * K + W + Q) + 2u * 2u * K + K + P + W, 16u);
+        // per wavefront: key u32[max(K, 2W)] (later ratio u64[W]) | tev u32[K] | comp u32[W] | used u32[Q] | ids u16[2K] |
+        // phase, left u8[K] each | busy u8[P] | failed u8[W]
+        const uint32_t wave_bytes = align_up(4u * (std::max(K, 2u * W) + K + W + Q) + 2u * 2u * K + 2u * K + P + W, 16u);
         p.wave_bytes = wave_bytes;
         a->lds_bytes = wave_bytes * kAgenticWaves;
         a->n_cu = (uint32_t)n_cu;
