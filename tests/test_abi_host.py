@@ -2,6 +2,7 @@
 symbol the header declares, and its host helpers agree with the oracle's histogram map."""
 import os
 import re
+import subprocess
 
 import numpy as np
 
@@ -50,3 +51,35 @@ def test_host_histogram_helpers_match_oracle():
         assert binding.ap_hist_bin(v) == oracle.hist_bin(v), v
     for b in range(4096):
         assert binding.ap_hist_lower(b) == oracle.hist_lower(b), b
+
+
+def test_struct_layouts_match_the_header_as_gcc_sees_it(tmp_path):
+    """Every struct of the header, compiled by gcc: sizes and field offsets must be the ones the binding's numpy
+    dtypes (and, for the two shared records, the oracle's) assume."""
+    structs = {"ap_replica": binding.REPLICA_DTYPE, "ap_metrics": binding.METRICS_DTYPE,
+               "ap_typed_replica": binding.TYPED_REPLICA_DTYPE, "ap_model": binding.MODEL_DTYPE, "ap_gpu": binding.GPU_DTYPE,
+               "ap_group": binding.GROUP_DTYPE, "ap_placement": binding.PLACEMENT_DTYPE, "ap_breakdown": binding.BREAKDOWN_DTYPE,
+               "ap_agentic_metrics": binding.AGENTIC_METRICS_DTYPE}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "autopoiesis_eval.h"', 'int main(void) {']
+    for name, dt in structs.items():
+        lines.append(f'printf("{name} size %zu\\n", sizeof({name}));')
+        for field in dt.names:
+            lines.append(f'printf("{name} {field} %zu\\n", offsetof({name}, {field}));')
+    lines += ['printf("ap_slo size %zu\\n", sizeof(ap_slo));', 'printf("ap_prefill_instance size %zu\\n", sizeof(ap_prefill_instance));',
+              'printf("ap_decode_instance size %zu\\n", sizeof(ap_decode_instance));', 'return 0; }']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c11", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    seen = {}
+    for line in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines():
+        name, what, value = line.split()
+        seen[(name, what)] = int(value)
+    for name, dt in structs.items():
+        assert seen[(name, "size")] == dt.itemsize, name
+        for field in dt.names:
+            assert seen[(name, field)] == dt.fields[field][1], (name, field)
+    assert seen[("ap_slo", "size")] == 24 and seen[("ap_prefill_instance", "size")] == 8
+    assert seen[("ap_decode_instance", "size")] == 12
+    from oracle import agentic
+    assert agentic.METRICS_DTYPE == binding.AGENTIC_METRICS_DTYPE
