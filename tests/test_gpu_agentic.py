@@ -73,6 +73,24 @@ def test_random_workloads(seed, W, P, Q, capacity, rate, mean_calls):
     assert len({tuple(r) for r in got.tolist()}) > 1 or W == 1
 
 
+def test_largest_supported_sizes():
+    """1024 workflows of one call each on 64 + 64 instances: every documented limit at once."""
+    rng = np.random.default_rng(11)
+    W = K = 1024
+    wl = dict(arrival_us=np.sort(rng.integers(0, 2_000_000, W)).astype(np.uint64), slo_us=rng.integers(1, 10**6, W).astype(np.uint64),
+              wf=np.arange(K, dtype=np.uint32), in_len=rng.integers(1, 4000, K).astype(np.uint32),
+              out_len=rng.integers(1, 300, K).astype(np.uint32), pred_first=np.zeros(K + 1, np.uint32), pred=np.zeros(0, np.uint32),
+              pa=rng.integers(1, 3000, 64).astype(np.uint32), pb=rng.integers(0, 4, 64).astype(np.uint32),
+              qc=rng.integers(1, 50, 64).astype(np.uint32), qd=rng.integers(0, 9, 64).astype(np.uint32),
+              cap=rng.integers(2000, 9000, 64).astype(np.uint32), penalty_permille=5000)
+    pre, dec, key = traces.draw_agentic_candidates(3, 12, K, 64, 64, key_range=7, bad_ids=True)
+    both(wl, pre, dec, key, "1024 workflows, 1024 calls, 64 + 64 instances")
+    # a dependency chain through all 1024 calls of one workflow
+    chain = dict(wl, arrival_us=[5], slo_us=[10**9], wf=np.zeros(K, np.uint32), pred_first=np.concatenate([[0], np.arange(K)]).astype(np.uint32),
+                 pred=np.arange(K - 1, dtype=np.uint32))
+    both(chain, pre, dec, key, "one chain of 1024 calls")
+
+
 def test_error_paths():
     torch.cuda.init()
     wl = traces.make_agentic(0, 8)

@@ -53,6 +53,18 @@ def test_tables_bit_exact(max_seq):
     assert 0 < int(feasible.sum()) < len(groups)                   # both verdicts occur
 
 
+def test_long_tables_bit_exact():
+    """A million sequence lengths for one compute-heavy and one memory-heavy group: the prefix sums run through
+    thousands of tiles and reach 2^47 ns."""
+    torch.cuda.init()
+    groups = [rf.Group(2, 1, 8, 64), rf.Group(3, 2, 1, 1)]
+    max_seq = 1 << 20
+    want_pre, want_prefix = rf.tables(MODELS, GPUS, groups, max_seq)
+    got_pre, got_prefix, _, _ = binding.ap_roofline_tables(*_pack(MODELS, GPUS, groups), max_seq)
+    assert (got_pre == want_pre).all() and (got_prefix == want_prefix).all()
+    assert int(want_prefix[0, -1]) > 1 << 47
+
+
 def test_request_costs_and_the_replay_on_top_of_them():
     """Tables for three replica types of a trace, computed on the device, handed to ap_costtable_set, and the
     replay's records compared with the oracle's tabulated branch fed with the oracle's own tables."""
