@@ -38,8 +38,8 @@
  * Pins (tests/test_agentic_pins.py): a hand-worked three-call example, the critical-path closed form
  * when nothing is contended, the single-server prefix sums in key order, serialisation by the token
  * budget, sweep-line invariants of the per-call record (one prefill at a time per instance, budget
- * never exceeded, precedence, no overtaking of waiting calls).  The dynamics above are this build's
- * reading, not printed values: parity unpinned for the choice of rules themselves.
+ * never exceeded, precedence, no overtaking of waiting calls).  The dynamics above are a reading of
+ * the paper, not printed values: parity unpinned for the choice of rules themselves.
  */
 #include <stdint.h>
 #include <stdlib.h>

@@ -41,8 +41,8 @@ over decode steps are exact integers; a request's table entries are
 Pins (tests/test_roofline_pins.py): published parameter counts of two public model families for the
 weight equation; the compute-bound and memory-bound closed forms and the ridge point for the roofline;
 hand-computed values for the all-reduce term; the linear growth of a memory-bound decode step with its
-context; brute-force summation for the prefix table.  The sublayer FLOP/byte counts themselves are this
-build's reading of "each sublayer" and have no printed value to be checked against: parity unpinned for
+context; brute-force summation for the prefix table.  The sublayer FLOP/byte counts themselves are a
+reading of "each sublayer" and have no printed value to be checked against: parity unpinned for
 those coefficients (their weight parts are pinned through the weight equation).
 """
 from __future__ import annotations
