@@ -83,3 +83,29 @@ def test_struct_layouts_match_the_header_as_gcc_sees_it(tmp_path):
     assert seen[("ap_decode_instance", "size")] == 12
     from oracle import agentic
     assert agentic.METRICS_DTYPE == binding.AGENTIC_METRICS_DTYPE
+
+
+def test_generators_produce_well_formed_inputs():
+    """The seeded generators shared by both sides hold no method arithmetic, but what they draw must be
+    well-formed: sorted arrivals, positive lengths, edit ranges that tile the arrays, DAGs in topological order."""
+    from paper_2604_07144_amd import traces
+    for cfg in (0, 1):
+        tr = traces.make_trace(cfg)
+        assert (np.diff(tr.arrival_us.astype(np.int64)) >= 0).all() and tr.prompt_len.min() >= 1 and tr.out_len.min() >= 1
+        assert tr.assignment_rows(0, 4).shape == (4, tr.R) and int(tr.assignment_rows(0, 4).max()) < tr.M
+    tr = traces.make_trace(1)
+    assert not tr.is_mutated_row(0) and tr.is_mutated_row(tr.C - 1)
+    first, request, replica = tr.mutation_lists(tr.C // 2, tr.C // 2 + 5)
+    assert first[0] == 0 and first[-1] == len(request) == len(replica) and (np.diff(first.astype(np.int64)) > 0).all()
+    first, request, replica = traces.draw_edit_lists(3, 50, 1000, 7, 4.0, request_range=1003, replica_range=8, sorted_lists=True)
+    assert first[-1] == len(request) and int(request.max()) < 1003 and int(replica.max()) < 8
+    assert all((np.diff(request[first[c]:first[c + 1]].astype(np.int64)) >= 0).all() for c in range(50))
+    wl = traces.make_agentic(5, 40)
+    K = len(wl["wf"])
+    assert wl["pred_first"][0] == 0 and wl["pred_first"][-1] == len(wl["pred"]) and len(wl["pred_first"]) == K + 1
+    for k in range(K):
+        for j in wl["pred"][wl["pred_first"][k]:wl["pred_first"][k + 1]]:
+            assert j < k and wl["wf"][j] == wl["wf"][k]
+    assert (np.diff(wl["arrival_us"].astype(np.int64)) >= 0).all() and wl["slo_us"].min() >= 1
+    pre, dec, key = traces.draw_agentic_candidates(5, 3, K, 4, 4)
+    assert pre.shape == dec.shape == key.shape == (3, K) and int(pre.max()) < 4 and int(dec.max()) < 4 and (key[1] == 0).all()
