@@ -19,6 +19,13 @@
  * term that grows with context), and the per-request latencies are reduced to the
  * ap_metrics record below.
  *
+ * Around that call: candidates given as edit lists against a parent assignment
+ * (ap_parent_set, ap_eval_children), cost models given as tables (ap_costtable_set) and the
+ * paper's roofline cost model to fill them (ap_roofline_tables, ap_roofline_costs), the
+ * end-to-end trace time of plan sequences with reconfiguration cost (ap_trace_time), and
+ * candidate plans of multi-call agentic workflows (ap_agentic_*).  Each is documented at
+ * its declaration with the passage of the paper it follows.
+ *
  * All calls return an ap_status and never throw or abort.  Out-parameters are left
  * untouched on error.  Every kernel runs on the device that is current when the
  * workload is created; the evaluation is asynchronous on the caller's stream.
