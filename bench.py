@@ -34,11 +34,11 @@ KERNEL_SOURCE_DIR = os.path.join(ROOT, "paper_2604_07144_amd", "csrc")
 # Keyed by configuration; valid only for the library source (all of csrc/) whose hash is recorded with it.
 MEASURED_TRAFFIC = {
     # cfg: (sha256 of the kernel source when measured, bytes per call)
-    4: ("bd439e74ef6cdc4e0d6be27d4c0079810937e76c21b2b5de904bcff647aca442", 4312359626),
-    3: ("bd439e74ef6cdc4e0d6be27d4c0079810937e76c21b2b5de904bcff647aca442", 543720045),
+    4: ("72edf65638d1d192674b4bfe9065d312b7fa1a0700cc5cf6b7710a8a013cf729", 4310726048),
+    3: ("72edf65638d1d192674b4bfe9065d312b7fa1a0700cc5cf6b7710a8a013cf729", 543759270),
 }
 # the same for one ap_eval_children call on the sparse form of configs[4]
-MEASURED_TRAFFIC_CHILDREN = {4: ("bd439e74ef6cdc4e0d6be27d4c0079810937e76c21b2b5de904bcff647aca442", 134426072)}
+MEASURED_TRAFFIC_CHILDREN = {4: ("72edf65638d1d192674b4bfe9065d312b7fa1a0700cc5cf6b7710a8a013cf729", 134391008)}
 
 
 def kernel_source_hash() -> str:

@@ -518,7 +518,7 @@ static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint
     // ---- screening plan: only for identical replicas that are available throughout ------
     bool always_on = true;
     for (const DevReplica& d : dev) always_on = always_on && d.t_on == 0u && d.t_off == kNever;
-    w->screen = always_on && kinds.size() == 1;
+    w->screen = always_on && kinds.size() == 1 && w->R <= (1u << 30);      // the kernels' byte offsets are 32-bit
     if (w->screen) {
         ScreenParams sp{};
         sp.span = w->d_span;

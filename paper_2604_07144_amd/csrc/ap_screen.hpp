@@ -137,9 +137,12 @@ struct ScreenRegs {
 template <bool kAligned>
 __device__ __forceinline__ void screen_fetch(ScreenRegs& g, const ScreenParams& p, const uint16_t* __restrict__ row,
                                              uint32_t i0, uint32_t lane) {
+    // Addresses are a uniform base plus a 32-bit byte offset per lane (the host keeps R below 2^30), which
+    // costs one 32-bit add per block instead of 64-bit pointer arithmetic per load.
+    const char* row_bytes = reinterpret_cast<const char*>(row) + (i0 + 2u * lane) * 2u;
 #pragma unroll
     for (uint32_t k = 0; k < 4u; ++k) {
-        const uint16_t* at = row + i0 + 128u * k + 2u * lane;
+        const uint16_t* at = reinterpret_cast<const uint16_t*>(row_bytes + 256u * k);
         // assignments are read once: stream them past the caches that hold the tables
         if (kAligned) {
             g.pair[k] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(at));
@@ -147,8 +150,9 @@ __device__ __forceinline__ void screen_fetch(ScreenRegs& g, const ScreenParams& 
             g.pair[k] = (uint32_t)__builtin_nontemporal_load(at) | ((uint32_t)__builtin_nontemporal_load(at + 1) << 16);
         }
     }
-    const uint4 s0 = *reinterpret_cast<const uint4*>(p.span_t + i0 + lane * 8u);
-    const uint4 s1 = *reinterpret_cast<const uint4*>(p.span_t + i0 + lane * 8u + 4u);
+    const char* span_bytes = reinterpret_cast<const char*>(p.span_t) + (i0 + lane * 8u) * 4u;
+    const uint4 s0 = *reinterpret_cast<const uint4*>(span_bytes);
+    const uint4 s1 = *reinterpret_cast<const uint4*>(span_bytes + 16u);
     g.span[0] = s0.x; g.span[1] = s0.y; g.span[2] = s0.z; g.span[3] = s0.w;
     g.span[4] = s1.x; g.span[5] = s1.y; g.span[6] = s1.z; g.span[7] = s1.w;
 }
@@ -436,17 +440,19 @@ __global__ __launch_bounds__(kWideThreads) void k_screen_candidates_wide(ScreenP
             uint2 span[kDepth];       // their table words (.x only when packed)
         };
         auto fetch = [&](Loaded& into, uint32_t d, uint32_t blk) {
-            const uint32_t i0 = blk * kWideBlock;
-            const uint16_t* at = row + i0 + mine;
+            // A uniform base plus a 32-bit byte offset per lane (the host keeps R below 2^30): the pair of
+            // ids and the pair's table word sit at the same offset, so one 32-bit add serves both loads.
+            const uint32_t off = (blk * kWideBlock + mine) * 2u;
+            const uint16_t* at = reinterpret_cast<const uint16_t*>(reinterpret_cast<const char*>(row) + off);
             if (kAligned) {
                 into.pair[d] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(at));
             } else {
                 into.pair[d] = (uint32_t)__builtin_nontemporal_load(at) | ((uint32_t)__builtin_nontemporal_load(at + 1) << 16);
             }
             if (kPacked) {
-                into.span[d].x = (p.pair + (i0 >> 1))[mine >> 1];
+                into.span[d].x = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(p.pair) + off);
             } else {
-                into.span[d] = *reinterpret_cast<const uint2*>(p.span + i0 + mine);
+                into.span[d] = *reinterpret_cast<const uint2*>(reinterpret_cast<const char*>(p.span) + off * 2u);
             }
         };
         auto first_probe = [&](uint32_t id, uint32_t finish, uint32_t& at, uint32_t& old) {
