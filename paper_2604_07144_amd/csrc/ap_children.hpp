@@ -148,8 +148,10 @@ __global__ __launch_bounds__(kOccupancyThreads) void k_parent_occupancy(EvalPara
 __global__ __launch_bounds__(kChildThreads) void k_certify_children(ChildParams p, const uint32_t* __restrict__ first,
                                                                     const uint32_t* __restrict__ request,
                                                                     const uint16_t* __restrict__ replica,
-                                                                    ap_metrics* __restrict__ out, uint32_t C) {
+                                                                    ap_metrics* __restrict__ out, uint32_t C,
+                                                                    PendingWord flags) {
     extern __shared__ __align__(16) unsigned char lds[];
+    pending_clear_next(flags);
     const uint32_t lane = threadIdx.x & 63u, w = wave_index();
     uint32_t* count = reinterpret_cast<uint32_t*>(lds) + w * p.M;            // this wavefront's: edits per replica
     uint32_t* room = reinterpret_cast<uint32_t*>(lds) + kChildWaves * p.M;   // the workgroup's copy of p.room
@@ -199,6 +201,7 @@ __global__ __launch_bounds__(kChildThreads) void k_certify_children(ChildParams 
             }
             dense = __ballot(fail) != 0ull;
             if (lane < 8u) reinterpret_cast<unsigned long long*>(&out[c])[lane] = dense ? ~0ull : nominal_word;
+            if (dense && lane == 0u) pending_raise(flags);
         }
         if (!dense) continue;
         uint16_t* row = p.rows + (size_t)c * p.R;

@@ -55,7 +55,7 @@ uint32_t plan_lds(EvalParams& p, uint32_t chunk, bool hist16, bool len16) {
     return off;
 }
 
-using EvalKernel = void (*)(EvalParams, const uint16_t*, ap_metrics*, uint32_t, uint32_t);
+using EvalKernel = void (*)(EvalParams, const uint16_t*, ap_metrics*, uint32_t, uint32_t, PendingWord);
 
 EvalKernel eval_kernel(bool hist16, bool len16, bool tabled) {
     static const EvalKernel variants[8] = {
@@ -88,6 +88,8 @@ struct ap_workload {
     uint32_t* d_pair = nullptr;       // one word per two requests (eight-wavefront screening kernel, when it fits)
     bool screen_packed = false;       // that kernel reads d_pair instead of d_span
     ap_metrics* d_nominal = nullptr;  // record shared by all contention-free candidates
+    uint32_t* d_pending = nullptr;    // [2] "this call has left pending marks", taken in turn by the calls
+    mutable uint32_t turn = 0;        // which of the two the next call uses
     bool has_model = false;
     bool screen = false;              // homogeneous, always-on replicas: screening applies
     bool hist16 = false;              // R < 65536: 16-bit histogram counters
@@ -125,13 +127,19 @@ struct ap_workload {
 
 // The dense path on C rows: screening where it applies, then the exact replay of what is left.
 // marked: only rows whose record carries the pending mark are looked at (screening applies).
+static PendingWord take_pending_word(const ap_workload* w) {
+    const uint32_t t = w->turn;
+    w->turn = t ^ 1u;
+    return PendingWord{w->d_pending + t, w->d_pending + (t ^ 1u)};
+}
+
 static ap_status launch_dense(const ap_workload* w, const uint16_t* d_assign, uint32_t C, ap_metrics* d_out,
-                              hipStream_t stream, bool marked) {
+                              hipStream_t stream, bool marked, PendingWord flags) {
     if (w->screen) {
         const uint32_t blocks = std::min((C + kScreenWaves - 1u) / kScreenWaves, w->n_cu * 64u);
         // rows start on 4-byte boundaries when R is even and the batch itself does
         const bool aligned = (w->R % 2u == 0u) && (reinterpret_cast<uintptr_t>(d_assign) % 4u == 0u);
-        typedef void (*screen_fn)(ScreenParams, const uint16_t*, ap_metrics*, uint32_t);
+        typedef void (*screen_fn)(ScreenParams, const uint16_t*, ap_metrics*, uint32_t, PendingWord);
         if (w->screen_wide) {
             static const screen_fn wide[8] = {
                 k_screen_candidates_wide<false, false, false>, k_screen_candidates_wide<true, false, false>,
@@ -144,14 +152,14 @@ static ap_status launch_dense(const ap_workload* w, const uint16_t* d_assign, ui
             const uint32_t grid = marked ? std::max((C + kWideThreads - 1u) / kWideThreads, std::min(C, w->n_cu * 4u))
                                          : std::min(C, w->n_cu * 64u);
             hipLaunchKernelGGL(wide[(aligned ? 1 : 0) + (w->screen_packed ? 2 : 0) + (marked ? 4 : 0)], dim3(grid),
-                               dim3(kWideThreads), w->screen_wide_lds_bytes, stream, w->screen_params, d_assign, d_out, C);
+                               dim3(kWideThreads), w->screen_wide_lds_bytes, stream, w->screen_params, d_assign, d_out, C, flags);
         } else {
             static const screen_fn narrow[4] = {k_screen_candidates<false, false>, k_screen_candidates<true, false>,
                                                 k_screen_candidates<false, true>, k_screen_candidates<true, true>};
             const uint32_t grid = marked ? std::max((C + kScreenThreads - 1u) / kScreenThreads, std::min(blocks, w->n_cu * 8u))
                                          : blocks;
             hipLaunchKernelGGL(narrow[(aligned ? 1 : 0) + (marked ? 2 : 0)], dim3(grid), dim3(kScreenThreads),
-                               w->screen_lds_bytes, stream, w->screen_params, d_assign, d_out, C);
+                               w->screen_lds_bytes, stream, w->screen_params, d_assign, d_out, C, flags);
         }
         if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
     }
@@ -174,7 +182,7 @@ static ap_status launch_dense(const ap_workload* w, const uint16_t* d_assign, ui
     // resident at once look at all the records together.
     const uint32_t grid = std::min(C, pending_only ? w->resident_grid : w->max_grid);
     hipLaunchKernelGGL(eval_kernel(w->hist16, w->len16, w->tabled), dim3(grid), dim3(kThreads), w->lds_bytes, stream, w->params,
-                       d_assign, d_out, C, pending_only);
+                       d_assign, d_out, C, pending_only, flags);
     if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
     return AP_OK;
 }
@@ -243,8 +251,10 @@ ap_status ap_workload_create(const uint64_t* arrival_us, const int32_t* prompt_l
                         hipMalloc(&w->d_span, bytes) != hipSuccess ||
                         hipMalloc(&w->d_span_t, padded) != hipSuccess ||
                         hipMalloc(&w->d_pair, ((size_t)R + 1u) / 2u * 4u) != hipSuccess ||
-                        hipMalloc(&w->d_nominal, sizeof(ap_metrics)) != hipSuccess))
+                        hipMalloc(&w->d_nominal, sizeof(ap_metrics)) != hipSuccess ||
+                        hipMalloc(&w->d_pending, 2u * sizeof(uint32_t)) != hipSuccess))
         st = AP_ERR_ALLOC;
+    if (st == AP_OK && hipMemset(w->d_pending, 0, 2u * sizeof(uint32_t)) != hipSuccess) st = AP_ERR_DEVICE;
     std::vector<uint4> recs;
     if (st == AP_OK) {
         try {
@@ -599,7 +609,7 @@ ap_status ap_eval_candidates(const ap_workload* w, const uint16_t* d_assign, uin
     if (!w->has_model) return AP_ERR_STATE;
     if (C == 0) return AP_OK;
     if (!d_assign || !d_out) return AP_ERR_INVALID;
-    return launch_dense(w, d_assign, C, d_out, static_cast<hipStream_t>(hip_stream), false);
+    return launch_dense(w, d_assign, C, d_out, static_cast<hipStream_t>(hip_stream), false, take_pending_word(w));
 }
 
 ap_status ap_parent_set(ap_workload* w, const uint16_t* parent, uint32_t max_children) {
@@ -668,10 +678,11 @@ ap_status ap_eval_children(const ap_workload* w, const uint32_t* d_edit_first, c
     if (C > w->max_children) return AP_ERR_RANGE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const uint32_t blocks = std::min((C + kChildWaves - 1u) / kChildWaves, w->n_cu * 64u);
+    const PendingWord flags = take_pending_word(w);
     hipLaunchKernelGGL(k_certify_children, dim3(blocks), dim3(kChildThreads), (kChildWaves + 1u) * w->child_params.M * 4u, stream,
-                       w->child_params, d_edit_first, d_edit_request, d_edit_replica, d_out, C);
+                       w->child_params, d_edit_first, d_edit_request, d_edit_replica, d_out, C, flags);
     if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
-    return launch_dense(w, w->d_rows, C, d_out, stream, w->child_params.certify != 0u);
+    return launch_dense(w, w->d_rows, C, d_out, stream, w->child_params.certify != 0u, flags);
 }
 
 // ---- roofline cost tables -------------------------------------------------------------
@@ -1050,6 +1061,7 @@ ap_status ap_workload_destroy(ap_workload* w) {
     if (w->d_span_t) ok = (hipFree(w->d_span_t) == hipSuccess) && ok;
     if (w->d_pair) ok = (hipFree(w->d_pair) == hipSuccess) && ok;
     if (w->d_nominal) ok = (hipFree(w->d_nominal) == hipSuccess) && ok;
+    if (w->d_pending) ok = (hipFree(w->d_pending) == hipSuccess) && ok;
     if (w->d_parent) ok = (hipFree(w->d_parent) == hipSuccess) && ok;
     if (w->d_peak) ok = (hipFree(w->d_peak) == hipSuccess) && ok;
     if (w->d_room) ok = (hipFree(w->d_room) == hipSuccess) && ok;

@@ -29,7 +29,9 @@ namespace {
 // request in the replay step) instead of the linear stand-in; prompt lengths are then not staged.
 template <bool kHist16, bool kLen16, bool kTabled>
 __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, const uint16_t* __restrict__ assign,
-                                                              ap_metrics* out, uint32_t C, uint32_t only_pending) {
+                                                              ap_metrics* out, uint32_t C, uint32_t only_pending,
+                                                              PendingWord flags) {
+    if (only_pending && pending_none(flags)) return;  // the kernels before this one have left no mark
     using len_t = typename std::conditional<kLen16, uint16_t, uint32_t>::type;
     extern __shared__ __align__(16) unsigned char lds[];
     uint32_t* hist = reinterpret_cast<uint32_t*>(lds);                        // three histograms

@@ -11,6 +11,26 @@ __device__ __forceinline__ bool is_pending(const ap_metrics& m) {
     return m.slo_ok == 0xFFFFFFFFu && m.n_rejected == 0xFFFFFFFFu;
 }
 
+// Two words in device memory say whether a call has left any pending mark.  A call uses one of
+// them (`mine`): every kernel that writes a pending mark also sets it, and the kernels that only
+// look for marks leave at once while it is zero.  The calls of a workload take the words in turn,
+// and a call's first kernels clear the word of the call after it (`next`), which nothing else
+// touches meanwhile.  A word that was never cleared (a captured call replayed on its own) only
+// costs the look at the records.
+struct PendingWord {
+    uint32_t* mine;
+    uint32_t* next;
+};
+__device__ __forceinline__ void pending_raise(const PendingWord& f) {
+    __hip_atomic_store(f.mine, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ bool pending_none(const PendingWord& f) {
+    return __hip_atomic_load(f.mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u;
+}
+__device__ __forceinline__ void pending_clear_next(const PendingWord& f) {
+    if (blockIdx.x == 0u && threadIdx.x == 0u) __hip_atomic_store(f.next, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // Screening kernel geometry (the tables written below use its lane-major layout).
 constexpr uint32_t kScreenWaves = 4;
 constexpr uint32_t kScreenThreads = kScreenWaves * kWave;
@@ -248,8 +268,11 @@ __device__ __forceinline__ bool cursor_claim(const uint32_t (&id)[K], const uint
 // written for the children that k_certify_children could not settle); every other record is final.
 template <bool kAligned, bool kMarked>
 __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenParams p, const uint16_t* __restrict__ assign,
-                                                                       ap_metrics* __restrict__ out, uint32_t C) {
+                                                                       ap_metrics* __restrict__ out, uint32_t C,
+                                                                       PendingWord flags) {
     extern __shared__ __align__(16) unsigned char lds[];
+    pending_clear_next(flags);
+    if (kMarked && pending_none(flags)) return;                              // nobody has left a mark
     const uint32_t lane = threadIdx.x & 63u, w = wave_index();
     const uint32_t M = p.M, R = p.R, S = 1u << p.slots_log2;
     const uint32_t ring_shift = p.slots_log2 + 2u;                           // bytes per ring, log2
@@ -317,6 +340,7 @@ __global__ __launch_bounds__(kScreenThreads) void k_screen_candidates(ScreenPara
             const unsigned long long v = bad ? ~0ull : src[lane];
             reinterpret_cast<unsigned long long*>(&out[c])[lane] = v;
         }
+        if (bad && lane == 0u) pending_raise(flags);
     }
 }
 
@@ -384,9 +408,12 @@ __device__ __forceinline__ void unpack_pair(uint32_t word, uint32_t& finish0, ui
 template <bool kAligned, bool kPacked, bool kMarked>
 __global__ __launch_bounds__(kWideThreads) void k_screen_candidates_wide(ScreenParams p,
                                                                           const uint16_t* __restrict__ assign,
-                                                                          ap_metrics* __restrict__ out, uint32_t C) {
+                                                                          ap_metrics* __restrict__ out, uint32_t C,
+                                                                          PendingWord flags) {
     extern __shared__ __align__(16) unsigned char lds[];
     const uint32_t tid = threadIdx.x, lane = tid & 63u, j = wave_index();
+    pending_clear_next(flags);
+    if (kMarked && pending_none(flags)) return;                              // nobody has left a mark
     const uint32_t M = p.M, R = p.R, S = 1u << p.slots_log2;
     const uint32_t ring_shift = p.slots_log2 + 2u;
     const uint32_t n_words = (M + 1u) << p.slots_log2;                       // M rings and the unknown-replica ring
@@ -532,6 +559,7 @@ __global__ __launch_bounds__(kWideThreads) void k_screen_candidates_wide(ScreenP
             const unsigned long long* src = reinterpret_cast<const unsigned long long*>(p.nominal);
             reinterpret_cast<unsigned long long*>(&out[c])[tid] = bad ? ~0ull : src[tid];
         }
+        if (bad && tid == 0u) pending_raise(flags);
         __syncthreads();                                                     // everyone has read the flags
     }
 }

@@ -75,6 +75,43 @@ def test_children_that_pass_and_children_that_need_their_row():
     assert int(got[4]["n_rejected"]) == 1
 
 
+@pytest.mark.parametrize("M,B,gap", [(16, 8, 4000), (128, 64, 100)], ids=["one_wavefront_screen", "eight_wavefront_screen"])
+def test_calls_that_leave_work_for_the_replay_alternate_with_calls_that_leave_none(M, B, gap):
+    """The kernels of a call tell each other through a word in device memory whether any candidate is still to
+    be replayed, and consecutive calls on one workload take two such words in turn: every order of calls that
+    do and do not leave such candidates, dense and as children, must give the oracle's records."""
+    n = 5000
+    tr = _mk(n, M, B, gap, seed=11, coef=[STD] * M)
+    parent = (np.arange(n) % M).astype(np.uint16)
+    crowded = parent.copy()
+    crowded[1000:1000 + 6 * B] = 3                                    # more requests at once than replica 3 has slots
+    rows_free = np.stack([parent, np.roll(parent, 1)])
+    rows_wait = np.stack([parent, crowded, np.roll(parent, 2)])
+    # children: none needs its row / the second one does
+    free_lists = (np.array([0, 0, 2], np.uint32), np.array([5, 4000], np.uint32), np.array([1, 2], np.uint16))
+    wait_lists = (np.array([0, 1, 1 + 6 * B, 1 + 6 * B], np.uint32),
+                  np.concatenate([[9], np.arange(1000, 1000 + 6 * B)]).astype(np.uint32),
+                  np.concatenate([[0], np.full(6 * B, 3)]).astype(np.uint16))
+    orc = oracle_for(tr)
+    want = {"free": orc.eval_batch(rows_free, nthreads=4), "wait": orc.eval_batch(rows_wait, nthreads=4),
+            "free_children": orc.eval_children(parent, *free_lists, nthreads=4),
+            "wait_children": orc.eval_children(parent, *wait_lists, nthreads=4)}
+    assert int(want["wait"][1]["sum_ttft_us"]) > int(want["wait"][0]["sum_ttft_us"])          # somebody does wait
+    assert int(want["wait_children"][1]["sum_ttft_us"]) > int(want["wait_children"][0]["sum_ttft_us"])
+    order = ["wait", "free", "free", "wait", "wait", "free_children", "wait_children", "free_children", "free",
+             "wait_children", "wait_children", "free", "wait", "free_children", "free_children", "wait", "free"]
+    with GpuWorkload(tr) as g:
+        g.set_parent(parent, 3)
+        for step, kind in enumerate(order):
+            if kind == "free":
+                got = g.eval(rows_free)
+            elif kind == "wait":
+                got = g.eval(rows_wait)
+            else:
+                got = g.eval_children(*(free_lists if kind == "free_children" else wait_lists))
+            assert_same(got, want[kind], f"call {step} ({kind})")
+
+
 def test_parent_that_queues_or_names_unknown_replicas():
     """No shortcut when the parent itself is not contention-free, or names a replica outside the table."""
     n, M, B = 3000, 4, 2
