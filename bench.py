@@ -34,11 +34,11 @@ KERNEL_SOURCE_DIR = os.path.join(ROOT, "paper_2604_07144_amd", "csrc")
 # Keyed by configuration; valid only for the library source (all of csrc/) whose hash is recorded with it.
 MEASURED_TRAFFIC = {
     # cfg: (sha256 of the kernel source when measured, bytes per call)
-    4: ("a5f6053d85d3169c338b8b5407e6870e7af3d722a56c41971d4905bcd53b0f0b", 4308948485),
-    3: ("a5f6053d85d3169c338b8b5407e6870e7af3d722a56c41971d4905bcd53b0f0b", 543757976),
+    4: ("90a639b5e463cdcd26f5d8c2dad777bd12fae5b412f251d5f8848dc69d486da2", 4307966047),
+    3: ("90a639b5e463cdcd26f5d8c2dad777bd12fae5b412f251d5f8848dc69d486da2", 543689339),
 }
 # the same for one ap_eval_children call on the sparse form of configs[4]
-MEASURED_TRAFFIC_CHILDREN = {4: ("a5f6053d85d3169c338b8b5407e6870e7af3d722a56c41971d4905bcd53b0f0b", 131194878)}
+MEASURED_TRAFFIC_CHILDREN = {4: ("90a639b5e463cdcd26f5d8c2dad777bd12fae5b412f251d5f8848dc69d486da2", 131184941)}
 
 
 def kernel_source_hash() -> str:

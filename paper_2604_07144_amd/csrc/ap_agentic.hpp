@@ -54,19 +54,34 @@ __device__ __forceinline__ void wave_sync_lds() {
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
 }
 
-__device__ __forceinline__ unsigned long long wave_min_u64(unsigned long long v) {
-#pragma unroll
-    for (uint32_t d = 32; d >= 1; d >>= 1) {
-        const unsigned long long o = (unsigned long long)__shfl_xor((long long)v, d);
-        v = o < v ? o : v;
-    }
-    return v;
+// Wavefront-wide reductions on the cross-lane data path of the vector ALU (no trip through LDS, which
+// the per-lane shuffles would take): an inclusive scan inside each row of 16 lanes by shifting the row
+// right by 1, 2, 4 and 8 lanes (a lane with no source keeps the identity), then the last lane of row 0
+// and of row 2 sent to rows 1 and 3, then lane 31 to rows 2 and 3; lane 63 holds the result, which is
+// handed to every lane as a uniform value.
+#define AP_DPP(identity, v, ctrl, rows) \
+    (uint32_t)__builtin_amdgcn_update_dpp((int)(identity), (int)(v), ctrl, rows, 0xF, false)
+__device__ __forceinline__ uint32_t wave_all_or(uint32_t v) {
+    v |= AP_DPP(0u, v, 0x111, 0xF);                                          // row_shr:1
+    v |= AP_DPP(0u, v, 0x112, 0xF);                                          // row_shr:2
+    v |= AP_DPP(0u, v, 0x114, 0xF);                                          // row_shr:4
+    v |= AP_DPP(0u, v, 0x118, 0xF);                                          // row_shr:8
+    v |= AP_DPP(0u, v, 0x142, 0xA);                                          // row_bcast:15 into rows 1 and 3
+    v |= AP_DPP(0u, v, 0x143, 0xC);                                          // row_bcast:31 into rows 2 and 3
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
-
-__device__ __forceinline__ unsigned long long wave_or_u64(unsigned long long v) {
-#pragma unroll
-    for (uint32_t d = 32; d >= 1; d >>= 1) v |= (unsigned long long)__shfl_xor((long long)v, d);
-    return v;
+__device__ __forceinline__ uint32_t wave_all_min(uint32_t v) {
+    v = min(v, AP_DPP(kNever, v, 0x111, 0xF));
+    v = min(v, AP_DPP(kNever, v, 0x112, 0xF));
+    v = min(v, AP_DPP(kNever, v, 0x114, 0xF));
+    v = min(v, AP_DPP(kNever, v, 0x118, 0xF));
+    v = min(v, AP_DPP(kNever, v, 0x142, 0xA));
+    v = min(v, AP_DPP(kNever, v, 0x143, 0xC));
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+#undef AP_DPP
+__device__ __forceinline__ unsigned long long wave_all_or64(unsigned long long v) {
+    return ((unsigned long long)wave_all_or((uint32_t)(v >> 32)) << 32) | wave_all_or((uint32_t)v);
 }
 
 // Call k has completed: each successor has one predecessor less to wait for.  (Byte counters: the
@@ -179,19 +194,23 @@ __global__ __launch_bounds__(kAgenticThreads) void k_agentic_eval(AgenticParams 
                 wave_sync_lds();
                 if (__ballot(again) == 0ull) break;
             }
-            dec_waiting = wave_or_u64(dec_waiting);
-            pre_waiting = wave_or_u64(pre_waiting);
+            dec_waiting = wave_all_or64(dec_waiting);
+            pre_waiting = wave_all_or64(pre_waiting);
             // ---- 3. decode admissions: the first waiting call of an instance, while it fits --
             while (dec_waiting != 0ull) {
                 const uint32_t q = (uint32_t)__ffsll((long long)dec_waiting) - 1u;
                 dec_waiting &= dec_waiting - 1ull;
                 for (;;) {
-                    unsigned long long best = ~0ull;
+                    // smallest (key, index): the smallest key first, then the smallest index among its holders
+                    uint32_t best_key = kNever, best_k = kNever;
                     for (uint32_t k = lane; k < K; k += kWave)
-                        if (phase[k] == kWaitDec && cdec[k] == q) best = min(best, ((unsigned long long)ckey[k] << 32) | k);
-                    best = wave_min_u64(best);
-                    if (best == ~0ull) break;
-                    const uint32_t k = (uint32_t)best;            // the same in every lane
+                        if (phase[k] == kWaitDec && cdec[k] == q && (best_k == kNever || ckey[k] < best_key)) {
+                            best_key = ckey[k];                   // a lane meets its calls in index order: ties keep the first
+                            best_k = k;
+                        }
+                    const uint32_t key_min = wave_all_min(best_key);
+                    const uint32_t k = wave_all_min(best_key == key_min ? best_k : kNever);   // the same in every lane
+                    if (k == kNever) break;
                     const uint32_t need = p.in_len[k] + p.out_len[k];
                     if (used[q] + need > p.cap[q]) break;
                     const uint32_t ends = t + p.out_len[k] * (p.qc[q] + p.qd[q] * ((p.in_len[k] + 1023u) >> 10));
@@ -209,11 +228,14 @@ __global__ __launch_bounds__(kAgenticThreads) void k_agentic_eval(AgenticParams 
                 const uint32_t i = (uint32_t)__ffsll((long long)pre_waiting) - 1u;
                 pre_waiting &= pre_waiting - 1ull;
                 if (busy[i] != 0) continue;
-                unsigned long long best = ~0ull;
+                uint32_t best_key = kNever, best_k = kNever;
                 for (uint32_t k = lane; k < K; k += kWave)
-                    if (phase[k] == kWaitPre && cpre[k] == i) best = min(best, ((unsigned long long)ckey[k] << 32) | k);
-                best = wave_min_u64(best);
-                const uint32_t k = (uint32_t)best;
+                    if (phase[k] == kWaitPre && cpre[k] == i && (best_k == kNever || ckey[k] < best_key)) {
+                        best_key = ckey[k];
+                        best_k = k;
+                    }
+                const uint32_t key_min = wave_all_min(best_key);
+                const uint32_t k = wave_all_min(best_key == key_min ? best_k : kNever);   // a call waits there: k is one
                 const uint32_t ends = t + p.pa[i] + p.pb[i] * p.in_len[k];
                 t_next = min(t_next, ends);
                 if (lane == 0u) {
@@ -223,7 +245,7 @@ __global__ __launch_bounds__(kAgenticThreads) void k_agentic_eval(AgenticParams 
                 }
                 wave_sync_lds();
             }
-            t = (uint32_t)__builtin_amdgcn_readfirstlane((int)~wave_max_u32(~t_next));            // wavefront minimum
+            t = wave_all_min(t_next);
             if (t == kNever) break;
         }
 
@@ -263,8 +285,8 @@ __global__ __launch_bounds__(kAgenticThreads) void k_agentic_eval(AgenticParams 
             if (rank == rank95) p95 = r;
             if (rank == rank99) p99 = r;
         }
-        p95 = wave_or_u64(p95);                                  // exactly one lane holds each
-        p99 = wave_or_u64(p99);
+        p95 = wave_all_or64(p95);                                // exactly one lane holds each
+        p99 = wave_all_or64(p99);
         if (lane == 0u) {
             ap_agentic_metrics m;
             m.sum_ratio_permille = sum;
