@@ -34,11 +34,11 @@ KERNEL_SOURCE_DIR = os.path.join(ROOT, "paper_2604_07144_amd", "csrc")
 # Keyed by configuration; valid only for the library source (all of csrc/) whose hash is recorded with it.
 MEASURED_TRAFFIC = {
     # cfg: (sha256 of the kernel source when measured, bytes per call)
-    4: ("90a639b5e463cdcd26f5d8c2dad777bd12fae5b412f251d5f8848dc69d486da2", 4307966047),
-    3: ("90a639b5e463cdcd26f5d8c2dad777bd12fae5b412f251d5f8848dc69d486da2", 543689339),
+    4: ("7a452141f4b5b16cc5cd8761900db37f5f8d1048f1c2b1e1a151e8f36ac38d10", 4308997956),
+    3: ("7a452141f4b5b16cc5cd8761900db37f5f8d1048f1c2b1e1a151e8f36ac38d10", 543467808),
 }
 # the same for one ap_eval_children call on the sparse form of configs[4]
-MEASURED_TRAFFIC_CHILDREN = {4: ("90a639b5e463cdcd26f5d8c2dad777bd12fae5b412f251d5f8848dc69d486da2", 131184941)}
+MEASURED_TRAFFIC_CHILDREN = {4: ("7a452141f4b5b16cc5cd8761900db37f5f8d1048f1c2b1e1a151e8f36ac38d10", 131208077)}
 
 
 def kernel_source_hash() -> str:

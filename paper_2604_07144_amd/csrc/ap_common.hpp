@@ -75,12 +75,16 @@ __device__ __forceinline__ uint32_t wave_index() {
     return (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
 }
 
-__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v, uint32_t lane) {
-#pragma unroll
-    for (uint32_t d = 1; d < kWave; d <<= 1) {
-        uint32_t t = (uint32_t)__shfl_up((int)v, d);
-        if (lane >= d) v += t;
-    }
+// Inclusive prefix sum over the lanes on the vector ALU's cross-lane path: a scan inside each row of 16
+// lanes (the row shifted right by 1, 2, 4, 8; a lane without a source adds nothing), then the last lane
+// of rows 0 and 2 added to rows 1 and 3, then lane 31 added to rows 2 and 3.
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v, uint32_t /*lane*/) {
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111 /* row_shr:1 */, 0xF, 0xF, false);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112 /* row_shr:2 */, 0xF, 0xF, false);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114 /* row_shr:4 */, 0xF, 0xF, false);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118 /* row_shr:8 */, 0xF, 0xF, false);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142 /* row_bcast:15 */, 0xA, 0xF, false);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143 /* row_bcast:31 */, 0xC, 0xF, false);
     return v;
 }
 
@@ -115,18 +119,48 @@ __device__ __forceinline__ unsigned long long hist_lower_edge(uint32_t bin) {
     return (unsigned long long)(128u | (bin & 127u)) << ((bin >> 7) - 1u);
 }
 
-// Ascending bitonic sort of one value per lane across the wavefront.
-__device__ __forceinline__ uint32_t wave_sort_ascending(uint32_t v, uint32_t lane) {
-#pragma unroll
-    for (uint32_t k = 2; k <= kWave; k <<= 1) {
-#pragma unroll
-        for (uint32_t j = k >> 1; j > 0; j >>= 1) {
-            const uint32_t other = (uint32_t)__shfl_xor((int)v, (int)j);
-            const bool keep_min = ((lane & j) == 0u) == ((lane & k) == 0u);
-            v = keep_min ? min(v, other) : max(v, other);
-        }
+// The value of lane (i ^ J) for every lane i.  J = 1, 2: a permutation inside each group of four lanes;
+// J = 4, 8: the row of 16 lanes shifted left for the lanes whose bit J is clear and right for the
+// others (two moves into one register, each writing the groups of four lanes it is meant for) - all on
+// the vector ALU's cross-lane path.  J = 16, 32 cross rows and take the shuffle through the LDS crossbar.
+template <uint32_t J>
+__device__ __forceinline__ uint32_t lane_xor(uint32_t v) {
+    if (J == 1u) return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0xB1 /* quad_perm:[1,0,3,2] */, 0xF, 0xF, false);
+    if (J == 2u) return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x4E /* quad_perm:[2,3,0,1] */, 0xF, 0xF, false);
+    if (J == 4u) {
+        const int t = __builtin_amdgcn_update_dpp((int)v, (int)v, 0x104 /* row_shl:4 */, 0xF, 0x5, false);
+        return (uint32_t)__builtin_amdgcn_update_dpp(t, (int)v, 0x114 /* row_shr:4 */, 0xF, 0xA, false);
     }
-    return v;
+    if (J == 8u) {
+        const int t = __builtin_amdgcn_update_dpp((int)v, (int)v, 0x108 /* row_shl:8 */, 0xF, 0x3, false);
+        return (uint32_t)__builtin_amdgcn_update_dpp(t, (int)v, 0x118 /* row_shr:8 */, 0xF, 0xC, false);
+    }
+    return (uint32_t)__shfl_xor((int)v, (int)J);
+}
+
+// Ascending bitonic sort of one value per lane across the wavefront.
+template <uint32_t K, uint32_t J>
+__device__ __forceinline__ uint32_t wave_sort_step(uint32_t v, uint32_t lane) {
+    const uint32_t other = lane_xor<J>(v);
+    const bool keep_min = ((lane & J) == 0u) == ((lane & K) == 0u);
+    return keep_min ? min(v, other) : max(v, other);
+}
+template <uint32_t K>
+__device__ __forceinline__ uint32_t wave_sort_merge(uint32_t v, uint32_t lane) {
+    if (K >= 64u) v = wave_sort_step<K, 32u>(v, lane);
+    if (K >= 32u) v = wave_sort_step<K, 16u>(v, lane);
+    if (K >= 16u) v = wave_sort_step<K, 8u>(v, lane);
+    if (K >= 8u) v = wave_sort_step<K, 4u>(v, lane);
+    if (K >= 4u) v = wave_sort_step<K, 2u>(v, lane);
+    return wave_sort_step<K, 1u>(v, lane);
+}
+__device__ __forceinline__ uint32_t wave_sort_ascending(uint32_t v, uint32_t lane) {
+    v = wave_sort_merge<2u>(v, lane);
+    v = wave_sort_merge<4u>(v, lane);
+    v = wave_sort_merge<8u>(v, lane);
+    v = wave_sort_merge<16u>(v, lane);
+    v = wave_sort_merge<32u>(v, lane);
+    return wave_sort_merge<64u>(v, lane);
 }
 
 // Lane i receives lane i + 1's value; lane 63 receives `last`.
