@@ -34,11 +34,11 @@ KERNEL_SOURCE_DIR = os.path.join(ROOT, "paper_2604_07144_amd", "csrc")
 # Keyed by configuration; valid only for the library source (all of csrc/) whose hash is recorded with it.
 MEASURED_TRAFFIC = {
     # cfg: (sha256 of the kernel source when measured, bytes per call)
-    4: ("7a452141f4b5b16cc5cd8761900db37f5f8d1048f1c2b1e1a151e8f36ac38d10", 4308997956),
-    3: ("7a452141f4b5b16cc5cd8761900db37f5f8d1048f1c2b1e1a151e8f36ac38d10", 543467808),
+    4: ("ed38682b033a0914744805a4e5cea8d8155f06f04eec49ae90f12fb9691fa33a", 4308349411),
+    3: ("ed38682b033a0914744805a4e5cea8d8155f06f04eec49ae90f12fb9691fa33a", 543674357),
 }
 # the same for one ap_eval_children call on the sparse form of configs[4]
-MEASURED_TRAFFIC_CHILDREN = {4: ("7a452141f4b5b16cc5cd8761900db37f5f8d1048f1c2b1e1a151e8f36ac38d10", 131208077)}
+MEASURED_TRAFFIC_CHILDREN = {4: ("ed38682b033a0914744805a4e5cea8d8155f06f04eec49ae90f12fb9691fa33a", 131173620)}
 
 
 def kernel_source_hash() -> str:

@@ -134,62 +134,94 @@ __global__ __launch_bounds__(kAgenticThreads) void k_agentic_eval(AgenticParams 
         wave_sync_lds();
 
         // Times are relative to the earliest arrival, so the first instant is 0.  Every step applies the
-        // instant's completions (one scan of the call table), then its releases together with the census
-        // of waiting calls and of what happens next (a second scan), then admissions and starts (a scan per
-        // call that starts).  The next instant is the earliest end of a stage in service or arrival of a
-        // workflow whose first calls are still to come.
+        // instant's completions, then its releases together with the census of waiting calls and of what
+        // happens next, then admissions and starts.  The next instant is the earliest end of a stage in
+        // service or arrival of a workflow whose first calls are still to come.
+        //
+        // Lane l owns the calls l, l + 64, l + 128, ... and keeps three masks over them (bit j: call l + 64 j):
+        // not released yet, waiting for an instance, in service.  Only the owner changes a call's phase, so
+        // the masks stay in registers, and every scan visits just the calls whose mask bit is set (each lane
+        // its own next one per round) instead of the whole table.
+        // A fourth mask holds the calls whose workflow has not arrived yet; they are looked at only when
+        // the earliest of their arrivals (t_wake) is reached.  That instant is taken as an event whether
+        // or not the call is free of predecessors by then; an instant at which nothing can change state
+        // changes no result.
+        const uint32_t n_mine = lane < K ? (K - lane + kWave - 1u) / kWave : 0u;      // <= 16
+        uint32_t m_dormant = (1u << n_mine) - 1u, m_blocked = 0u, m_wait = 0u, m_run = 0u;
+        uint32_t t_wake = 0u;                                     // look at them at the first instant
         uint32_t t = 0u;
         for (;;) {
             // ---- 1. completions: decode (frees tokens), prefill (on to the decode queue, or fails) ----
-            for (uint32_t k = lane; k < K; k += kWave) {
-                const uint32_t ph = phase[k];
-                if (ph == kInDec && tev[k] == t) {
-                    phase[k] = (unsigned char)kDone;
-                    atomicSub(&used[cdec[k]], p.in_len[k] + p.out_len[k]);
-                    agentic_notify(p, left, k);
-                } else if (ph == kInPre && tev[k] == t) {
-                    busy[cpre[k]] = 0;
-                    const uint32_t q = cdec[k];
-                    if (q >= p.Q || p.in_len[k] + p.out_len[k] > p.cap[q]) {
-                        phase[k] = (unsigned char)kDone;          // fails here; tev[k] == t is its completion time
-                        wf_failed[p.wf[k]] = 1;
-                        agentic_notify(p, left, k);
-                    } else {
-                        phase[k] = (unsigned char)kWaitDec;
+            for (uint32_t m = m_run; __ballot(m != 0u) != 0ull; m &= m - 1u) {
+                if (m != 0u) {
+                    const uint32_t j = (uint32_t)__ffs((int)m) - 1u, k = lane + kWave * j;
+                    if (tev[k] == t) {
+                        m_run &= ~(1u << j);
+                        if (phase[k] == kInDec) {
+                            phase[k] = (unsigned char)kDone;
+                            atomicSub(&used[cdec[k]], p.in_len[k] + p.out_len[k]);
+                            agentic_notify(p, left, k);
+                        } else {                                  // end of its prefill
+                            busy[cpre[k]] = 0;
+                            const uint32_t q = cdec[k];
+                            if (q >= p.Q || p.in_len[k] + p.out_len[k] > p.cap[q]) {
+                                phase[k] = (unsigned char)kDone;  // fails here; tev[k] == t is its completion time
+                                wf_failed[p.wf[k]] = 1;
+                                agentic_notify(p, left, k);
+                            } else {
+                                phase[k] = (unsigned char)kWaitDec;
+                                m_wait |= 1u << j;
+                            }
+                        }
                     }
                 }
             }
             wave_sync_lds();
             // ---- 2. releases, and in the same scan: who is waiting where, what comes next ------------
             // (repeated only when a call failed at its release: it has completed now and may release others)
+            if (t_wake <= t) {                                    // workflows of some of my calls have arrived
+                t_wake = kNever;
+                for (uint32_t m = m_dormant; m != 0u; m &= m - 1u) {
+                    const uint32_t j = (uint32_t)__ffs((int)m) - 1u;
+                    const uint32_t arrives = p.arrival[p.wf[lane + kWave * j]];
+                    if (arrives <= t) {
+                        m_dormant &= ~(1u << j);
+                        m_blocked |= 1u << j;
+                    } else {
+                        t_wake = min(t_wake, arrives);
+                    }
+                }
+            }
             unsigned long long dec_waiting, pre_waiting;
             uint32_t t_next;
             for (;;) {
                 bool again = false;
                 dec_waiting = pre_waiting = 0ull;
-                t_next = kNever;
-                for (uint32_t k = lane; k < K; k += kWave) {
-                    uint32_t ph = phase[k];
-                    if (ph == kBlocked) {
-                        const bool ready = left[k] == 0;
-                        const uint32_t arrives = p.arrival[p.wf[k]];
-                        if (ready && arrives > t) t_next = min(t_next, arrives);
-                        if (ready && arrives <= t) {
-                            if (cpre[k] >= p.P) {
-                                ph = kDone;
-                                tev[k] = t;
-                                wf_failed[p.wf[k]] = 1;
-                                agentic_notify(p, left, k);
-                                again = true;
-                            } else {
-                                ph = kWaitPre;
+                t_next = t_wake;
+                for (uint32_t m = m_blocked | m_wait | m_run; __ballot(m != 0u) != 0ull; m &= m - 1u) {
+                    if (m != 0u) {
+                        const uint32_t j = (uint32_t)__ffs((int)m) - 1u, k = lane + kWave * j;
+                        uint32_t ph = phase[k];
+                        if (ph == kBlocked) {
+                            if (left[k] == 0) {                   // its workflow has arrived: released now
+                                m_blocked &= ~(1u << j);
+                                if (cpre[k] >= p.P) {
+                                    ph = kDone;
+                                    tev[k] = t;
+                                    wf_failed[p.wf[k]] = 1;
+                                    agentic_notify(p, left, k);
+                                    again = true;
+                                } else {
+                                    ph = kWaitPre;
+                                    m_wait |= 1u << j;
+                                }
+                                phase[k] = (unsigned char)ph;
                             }
-                            phase[k] = (unsigned char)ph;
                         }
+                        if (ph == kWaitDec) dec_waiting |= 1ull << cdec[k];
+                        if (ph == kWaitPre) pre_waiting |= 1ull << cpre[k];
+                        if (ph == kInPre || ph == kInDec) t_next = min(t_next, tev[k]);
                     }
-                    if (ph == kWaitDec) dec_waiting |= 1ull << cdec[k];
-                    if (ph == kWaitPre) pre_waiting |= 1ull << cpre[k];
-                    if (ph == kInPre || ph == kInDec) t_next = min(t_next, tev[k]);
                 }
                 wave_sync_lds();
                 if (__ballot(again) == 0ull) break;
@@ -203,11 +235,15 @@ __global__ __launch_bounds__(kAgenticThreads) void k_agentic_eval(AgenticParams 
                 for (;;) {
                     // smallest (key, index): the smallest key first, then the smallest index among its holders
                     uint32_t best_key = kNever, best_k = kNever;
-                    for (uint32_t k = lane; k < K; k += kWave)
-                        if (phase[k] == kWaitDec && cdec[k] == q && (best_k == kNever || ckey[k] < best_key)) {
-                            best_key = ckey[k];                   // a lane meets its calls in index order: ties keep the first
-                            best_k = k;
+                    for (uint32_t m = m_wait; __ballot(m != 0u) != 0ull; m &= m - 1u) {
+                        if (m != 0u) {
+                            const uint32_t k = lane + kWave * ((uint32_t)__ffs((int)m) - 1u);
+                            if (phase[k] == kWaitDec && cdec[k] == q && (best_k == kNever || ckey[k] < best_key)) {
+                                best_key = ckey[k];               // a lane meets its calls in index order: ties keep the first
+                                best_k = k;
+                            }
                         }
+                    }
                     const uint32_t key_min = wave_all_min(best_key);
                     const uint32_t k = wave_all_min(best_key == key_min ? best_k : kNever);   // the same in every lane
                     if (k == kNever) break;
@@ -215,10 +251,12 @@ __global__ __launch_bounds__(kAgenticThreads) void k_agentic_eval(AgenticParams 
                     if (used[q] + need > p.cap[q]) break;
                     const uint32_t ends = t + p.out_len[k] * (p.qc[q] + p.qd[q] * ((p.in_len[k] + 1023u) >> 10));
                     t_next = min(t_next, ends);
-                    if (lane == 0u) {
+                    if (lane == (k & 63u)) {                      // its owner
                         used[q] += need;
                         phase[k] = (unsigned char)kInDec;
                         tev[k] = ends;
+                        m_wait &= ~(1u << (k >> 6));
+                        m_run |= 1u << (k >> 6);
                     }
                     wave_sync_lds();
                 }
@@ -229,19 +267,26 @@ __global__ __launch_bounds__(kAgenticThreads) void k_agentic_eval(AgenticParams 
                 pre_waiting &= pre_waiting - 1ull;
                 if (busy[i] != 0) continue;
                 uint32_t best_key = kNever, best_k = kNever;
-                for (uint32_t k = lane; k < K; k += kWave)
-                    if (phase[k] == kWaitPre && cpre[k] == i && (best_k == kNever || ckey[k] < best_key)) {
-                        best_key = ckey[k];
-                        best_k = k;
+                for (uint32_t m = m_wait; __ballot(m != 0u) != 0ull; m &= m - 1u) {
+                    if (m != 0u) {
+                        const uint32_t k = lane + kWave * ((uint32_t)__ffs((int)m) - 1u);
+                        if (phase[k] == kWaitPre && cpre[k] == i && (best_k == kNever || ckey[k] < best_key)) {
+                            best_key = ckey[k];
+                            best_k = k;
+                        }
                     }
+                }
                 const uint32_t key_min = wave_all_min(best_key);
                 const uint32_t k = wave_all_min(best_key == key_min ? best_k : kNever);   // a call waits there: k is one
+                if (k == kNever) continue;
                 const uint32_t ends = t + p.pa[i] + p.pb[i] * p.in_len[k];
                 t_next = min(t_next, ends);
-                if (lane == 0u) {
+                if (lane == (k & 63u)) {                          // its owner
                     busy[i] = 1;
                     phase[k] = (unsigned char)kInPre;
                     tev[k] = ends;
+                    m_wait &= ~(1u << (k >> 6));
+                    m_run |= 1u << (k >> 6);
                 }
                 wave_sync_lds();
             }
