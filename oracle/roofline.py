@@ -40,10 +40,13 @@ over decode steps are exact integers; a request's table entries are
 
 Pins (tests/test_roofline_pins.py): published parameter counts of two public model families for the
 weight equation; the compute-bound and memory-bound closed forms and the ridge point for the roofline;
-hand-computed values for the all-reduce term; the linear growth of a memory-bound decode step with its
-context; brute-force summation for the prefix table.  The sublayer FLOP/byte counts themselves are a
-reading of "each sublayer" and have no printed value to be checked against: parity unpinned for
-those coefficients (their weight parts are pinned through the weight equation).
+hand-computed values for the all-reduce term; brute-force summation for the prefix table.  The sublayer
+counts are a reading of "each sublayer" with no printed value to be checked against; what fixes them
+from outside: every FLOP coefficient by the rule of 2 FLOPs per matrix parameter and token (with the
+published parameter counts) plus 4 s c H per layer for attention, on a device where every operation is
+compute-bound; the weight bytes through the weight equation; the key/value bytes by the linear growth
+of a memory-bound decode step with its context (2 K d e bytes per layer and token).  The bytes of the
+activations read and written per sublayer have no such anchor: parity unpinned for those terms.
 """
 from __future__ import annotations
 

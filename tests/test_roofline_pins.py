@@ -79,6 +79,27 @@ def test_prefill_is_compute_bound_for_long_prompts_and_scales_with_tp():
     assert t4 - comm == pytest.approx(t1 / 4, rel=2e-2)              # a quarter of the work per GPU, plus the all-reduce
 
 
+@pytest.mark.parametrize("model,published_params", [(LLAMA2_7B, 6.74e9), (LLAMA3_8B, 8.03e9)], ids=["llama2_7b", "llama3_8b"])
+def test_flop_counts_follow_two_flops_per_parameter_and_token(model, published_params):
+    """On a device that is compute-bound for every operation the time of a pass is its FLOPs over F_g.  A dense
+    transformer spends 2 FLOPs per matrix parameter and token (one multiply-add per weight), the output head once
+    per pass, plus 4 s c H per layer for the attention scores and their product with the values: with the published
+    parameter counts of the two model families this fixes every FLOP coefficient of the sublayers."""
+    slow = rf.Gpu(mem_bytes=80e9, flops=1e9, hbm_bytes_per_s=1e30, pcie_bytes_per_s=64e9,
+                  link_intra_bytes_per_s=450e9, link_inter_bytes_per_s=50e9, gpus_per_node=8)
+    head = model.hidden * model.vocab
+    per_token = published_params - 2 * head                 # the matrices of the layers (norms are ~1e-4 of them)
+    for s, c in [(1.0, 1.0), (1.0, 700.0), (512.0, 512.0), (3000.0, 3000.0)]:
+        flops = float(rf.phase_time(model, slow, 1, 1, np.array([s]), np.array([c]))[0]) * slow.flops
+        want = 2 * s * per_token + 2 * head + 4 * model.layers * s * c * model.hidden
+        assert flops == pytest.approx(want, rel=5e-3), (s, c)       # the published counts are rounded to 3 digits
+    # batch multiplies everything; tensor parallelism divides it (the all-reduce aside)
+    one = float(rf.phase_time(model, slow, 1, 1, np.array([64.0]), np.array([64.0]))[0])
+    assert float(rf.phase_time(model, slow, 1, 8, np.array([64.0]), np.array([64.0]))[0]) == pytest.approx(8 * one, rel=1e-12)
+    tp4 = float(rf.phase_time(model, slow, 4, 1, np.array([64.0]), np.array([64.0]))[0])
+    assert tp4 - float(rf.comm_time(model, slow, 4, 1, np.array([64.0]))[0]) == pytest.approx(one / 4, rel=1e-12)
+
+
 def test_tables_and_request_costs_against_brute_force():
     models, gpus = [LLAMA2_7B, LLAMA3_8B], [GPU]
     groups = [rf.Group(0, 0, 1, 1), rf.Group(1, 0, 2, 4)]
