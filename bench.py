@@ -34,11 +34,11 @@ KERNEL_SOURCE_DIR = os.path.join(ROOT, "paper_2604_07144_amd", "csrc")
 # Keyed by configuration; valid only for the library source (all of csrc/) whose hash is recorded with it.
 MEASURED_TRAFFIC = {
     # cfg: (sha256 of the kernel source when measured, bytes per call)
-    4: ("ed38682b033a0914744805a4e5cea8d8155f06f04eec49ae90f12fb9691fa33a", 4308349411),
-    3: ("ed38682b033a0914744805a4e5cea8d8155f06f04eec49ae90f12fb9691fa33a", 543674357),
+    4: ("06848ee28e4bf7c75cea0b99b0194dc1286f6c0988ee786daa86df52f0f99389", 4309221147),
+    3: ("06848ee28e4bf7c75cea0b99b0194dc1286f6c0988ee786daa86df52f0f99389", 543892426),
 }
 # the same for one ap_eval_children call on the sparse form of configs[4]
-MEASURED_TRAFFIC_CHILDREN = {4: ("ed38682b033a0914744805a4e5cea8d8155f06f04eec49ae90f12fb9691fa33a", 131173620)}
+MEASURED_TRAFFIC_CHILDREN = {4: ("06848ee28e4bf7c75cea0b99b0194dc1286f6c0988ee786daa86df52f0f99389", 131152203)}
 
 
 def kernel_source_hash() -> str:

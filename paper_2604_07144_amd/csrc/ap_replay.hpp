@@ -272,12 +272,30 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
                                     S = min(wave_shift_down(S, kNever), max(S, fj));
                                     pushed = wave_shift_up(pushed, st);
                                 };
+                                // the same when every request of the run is ready before the first slot frees (a
+                                // backlog): the earliest slot time only grows, so each starts when that slot frees
+                                auto step_backlog = [&](uint32_t j) {
+                                    const uint32_t u = (uint32_t)__builtin_amdgcn_readfirstlane((int)S);
+                                    const uint32_t fj = u + (uint32_t)__builtin_amdgcn_readlane((int)svc, (int)j);
+                                    S = min(wave_shift_down(S, kNever), max(S, fj));
+                                    pushed = wave_shift_up(pushed, u);
+                                };
                                 uint32_t j = n_first;
-                                for (; j + 2u <= n_run; j += 2u) {
-                                    step(j);
-                                    step(j + 1u);
+                                const bool backlog = (uint32_t)__builtin_amdgcn_readlane((int)ready, (int)(n_run - 1u)) <=
+                                                     (uint32_t)__builtin_amdgcn_readfirstlane((int)S);   // ready times do not decrease
+                                if (backlog) {
+                                    for (; j + 2u <= n_run; j += 2u) {
+                                        step_backlog(j);
+                                        step_backlog(j + 1u);
+                                    }
+                                    if (j < n_run) step_backlog(j);
+                                } else {
+                                    for (; j + 2u <= n_run; j += 2u) {
+                                        step(j);
+                                        step(j + 1u);
+                                    }
+                                    if (j < n_run) step(j);
                                 }
-                                if (j < n_run) step(j);
                                 const uint32_t mine = (uint32_t)__builtin_amdgcn_ds_bpermute((int)((n_run - 1u - lane) << 2), (int)pushed);
                                 if (lane >= n_first && lane < n_run) start = mine;
                                 const uint32_t n_in_time = __popcll(__ballot(lane < n_run && start < rp.t_off));
