@@ -34,11 +34,11 @@ KERNEL_SOURCE_DIR = os.path.join(ROOT, "paper_2604_07144_amd", "csrc")
 # Keyed by configuration; valid only for the library source (all of csrc/) whose hash is recorded with it.
 MEASURED_TRAFFIC = {
     # cfg: (sha256 of the kernel source when measured, bytes per call)
-    4: ("06848ee28e4bf7c75cea0b99b0194dc1286f6c0988ee786daa86df52f0f99389", 4309221147),
-    3: ("06848ee28e4bf7c75cea0b99b0194dc1286f6c0988ee786daa86df52f0f99389", 543892426),
+    4: ("382ad49bcaa0aebcaba533620bc77c10a2f76845bf4c37c47a585bdfb30ffdd3", 4309871293),
+    3: ("382ad49bcaa0aebcaba533620bc77c10a2f76845bf4c37c47a585bdfb30ffdd3", 543927151),
 }
 # the same for one ap_eval_children call on the sparse form of configs[4]
-MEASURED_TRAFFIC_CHILDREN = {4: ("06848ee28e4bf7c75cea0b99b0194dc1286f6c0988ee786daa86df52f0f99389", 131152203)}
+MEASURED_TRAFFIC_CHILDREN = {4: ("382ad49bcaa0aebcaba533620bc77c10a2f76845bf4c37c47a585bdfb30ffdd3", 131210995)}
 
 
 def kernel_source_hash() -> str:

@@ -33,53 +33,121 @@ struct ChildParams {
 
 constexpr uint32_t kChildWaves = 4;
 constexpr uint32_t kChildThreads = kChildWaves * kWave;
-constexpr uint32_t kOccupancyThreads = 256;
+constexpr uint32_t kOccupancyThreads = 1024;
 constexpr uint32_t kOccupancyWaves = kOccupancyThreads / kWave;
-constexpr uint32_t kOccupancyPerThread = 16;      // parent ids per thread and step
+constexpr uint32_t kOccupancyPerThread = 8;       // parent ids per thread and step
 constexpr uint32_t kOccupancyStep = kOccupancyThreads * kOccupancyPerThread;
+constexpr uint32_t kOccupancyTile = 2u * kOccupancyThreads;                 // requests whose depths are counted together
+constexpr uint32_t kOccupancyListCap = kOccupancyStep + kOccupancyTile;
 
-// One workgroup per replica walks the parent row in steps of 4096 ids.  All its threads pick out
-// the replica's requests of the step (each thread 16 consecutive ids; counts scanned across the
-// workgroup; request indices written to an LDS list in arrival order), then the first wavefront
-// takes the list through the queue-free schedule: lane l holds the finish time of the request
-// that last used "slot" l, a request takes the lowest lane that is free at its arrival (finish
-// <= arrival), and the number of busy lanes plus one is the depth at that moment.  More than 64
-// at once is reported as 65 (B never exceeds 64).  peak[M] counts the parent's requests that
-// name no replica of the table.
+// One workgroup per replica walks the parent row in steps of 8192 ids.  All its threads pick out
+// the replica's requests of the step (each thread 8 consecutive ids; counts scanned across the
+// workgroup; request indices appended to an LDS list in arrival order).  Whenever the list holds a
+// tile of 2048 requests, and once more at the end, the depths of the tile's requests are counted,
+// two requests per thread: the depth at a request's arrival is one plus the number of earlier
+// requests whose unqueued finish time is later than that arrival.  Earlier requests of the same
+// tile are looked at backwards from the request, as far as an arrival plus the tile's longest
+// service time still reaches past this arrival (arrivals are in order, so nothing before that can
+// still be in service).  Requests of earlier tiles are represented by the 64 latest finish times
+// seen so far (`latest`, ascending across the lanes of the first wavefront, kept by dropping the
+// earliest and inserting the new one where it belongs): if fewer than 64 earlier requests are
+// still in service they are all among those, and 64 or more make the depth exceed every B anyway.
+// A depth above 64 is reported as 65.  peak[M] counts the parent's requests that name no replica
+// of the table.
 __global__ __launch_bounds__(kOccupancyThreads) void k_parent_occupancy(EvalParams p, const uint16_t* __restrict__ parent,
                                                                         uint32_t* __restrict__ peak,
                                                                         uint32_t* __restrict__ room) {
-    __shared__ uint32_t list[kOccupancyStep];     // requests of this replica in the current step
+    __shared__ uint32_t list[kOccupancyListCap];  // this replica's requests not yet counted, in arrival order
+    __shared__ uint32_t tile_arrival[kOccupancyTile], tile_finish[kOccupancyTile];
+    __shared__ uint32_t carry[kWave];             // `latest` as the tile being counted sees it
     __shared__ uint32_t wave_total[kOccupancyWaves];
+    __shared__ uint32_t longest;                  // longest service time of the tile
+    __shared__ uint32_t wg_deepest;
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wv = wave_index(), m = blockIdx.x;
     const DevReplica rp = p.rep[0];
-    uint32_t slot_finish = 0u, deepest = 0u, unknown = 0u;
-    // my 16 ids of a step: two 16-byte loads where the row has them all (the parent buffer is 16-byte
-    // aligned and a thread's run starts at a multiple of 16 ids), one by one at the ragged end
-    auto fetch = [&](uint4 (&into)[2], uint32_t r0) {
+    uint32_t latest = 0u, deepest = 0u, unknown = 0u, n_list = 0u;
+    bool have_carry = false;
+    if (tid == 0u) {
+        longest = 0u;
+        wg_deepest = 0u;
+    }
+
+    // Counts the depths of list[0 .. n_tile) and takes them off the list.  Called by all threads with the same
+    // arguments; more_follow: requests after this tile may exist, so `latest` has to be brought up to date.
+    auto count_tile = [&](uint32_t n_tile, bool more_follow) {
+        uint32_t my_arrival[2] = {0u, 0u};
+#pragma unroll
+        for (uint32_t q = 0; q < 2u; ++q) {
+            const uint32_t i = tid + q * kOccupancyThreads;
+            if (i < n_tile) {
+                const uint32_t r = list[i];
+                uint32_t prefill, tpot;
+                request_cost(p.tab_prefill, p.tab_tpot, rp, r, p.prompt[r], prefill, tpot);
+                const uint32_t service = prefill + p.outlen[r] * tpot;
+                my_arrival[q] = p.arrival[r];
+                tile_arrival[i] = my_arrival[q];
+                tile_finish[i] = my_arrival[q] + service;
+                atomicMax(&longest, service);
+            }
+        }
+        if (wv == 0u) carry[lane] = latest;
+        __syncthreads();
+        const uint32_t reach = longest;
+#pragma unroll
+        for (uint32_t q = 0; q < 2u; ++q) {
+            const uint32_t i = tid + q * kOccupancyThreads;
+            if (i < n_tile) {
+                const uint32_t a = my_arrival[q];
+                uint32_t depth = 1u;
+                if (have_carry)
+                    for (uint32_t l = 0; l < kWave; ++l) depth += carry[l] > a ? 1u : 0u;
+                for (uint32_t j = i; j > 0u && tile_arrival[j - 1u] + reach > a; --j) depth += tile_finish[j - 1u] > a ? 1u : 0u;
+                deepest = max(deepest, min(depth, 65u));
+            }
+        }
+        if (more_follow && wv == 0u) {
+            for (uint32_t i0 = 0; i0 < n_tile; i0 += kWave) {
+                const uint32_t finish = i0 + lane < n_tile ? tile_finish[i0 + lane] : 0u;
+                const uint32_t n_here = min(kWave, n_tile - i0);
+                for (uint32_t k = 0; k < n_here; ++k) {
+                    const uint32_t f = (uint32_t)__builtin_amdgcn_readlane((int)finish, (int)k);
+                    latest = min(wave_shift_down(latest, kNever), max(latest, f));
+                }
+            }
+        }
+        __syncthreads();                          // everyone is done with the tile and with list[0 .. n_tile)
+        // close the gap: a thread only touches the positions congruent to its own index, front to back
+        for (uint32_t d = tid; d + n_tile < n_list; d += kOccupancyThreads) list[d] = list[d + n_tile];
+        if (tid == 0u) longest = 0u;
+        n_list -= n_tile;
+        have_carry = true;
+        __syncthreads();
+    };
+
+    // my 8 ids of a step: one 16-byte load where the row has them all (the parent buffer is 16-byte aligned
+    // and a thread's run starts at a multiple of 8 ids), one by one at the ragged end
+    auto fetch = [&](uint4& into, uint32_t r0) {
         const uint32_t at = r0 + tid * kOccupancyPerThread;
         if (at + kOccupancyPerThread <= p.R) {
-            into[0] = reinterpret_cast<const uint4*>(parent + at)[0];
-            into[1] = reinterpret_cast<const uint4*>(parent + at)[1];
+            into = *reinterpret_cast<const uint4*>(parent + at);
         } else {
-            uint32_t w[8];
+            uint32_t w[4];
 #pragma unroll
-            for (uint32_t k = 0; k < 8u; ++k) {
+            for (uint32_t k = 0; k < 4u; ++k) {
                 const uint32_t lo = at + 2u * k < p.R ? (uint32_t)parent[at + 2u * k] : 0xFFFFu;
                 const uint32_t hi = at + 2u * k + 1u < p.R ? (uint32_t)parent[at + 2u * k + 1u] : 0xFFFFu;
                 w[k] = lo | (hi << 16);
             }
-            into[0] = make_uint4(w[0], w[1], w[2], w[3]);
-            into[1] = make_uint4(w[4], w[5], w[6], w[7]);
+            into = make_uint4(w[0], w[1], w[2], w[3]);
         }
     };
-    uint4 ids_next[2];
+    uint4 ids_next;
     fetch(ids_next, 0u);
+    __syncthreads();                              // longest and wg_deepest are set
     for (uint32_t r0 = 0; r0 < p.R; r0 += kOccupancyStep) {
-        // as a bit mask: which of my 16 ids name this replica (absent ones read as 0xFFFF and are skipped below)
+        // as a bit mask: which of my 8 ids name this replica (absent ones read as 0xFFFF and are skipped below)
         const uint32_t mine = r0 + tid * kOccupancyPerThread;
-        const uint32_t w[8] = {ids_next[0].x, ids_next[0].y, ids_next[0].z, ids_next[0].w,
-                               ids_next[1].x, ids_next[1].y, ids_next[1].z, ids_next[1].w};
+        const uint32_t w[4] = {ids_next.x, ids_next.y, ids_next.z, ids_next.w};
         if (r0 + kOccupancyStep < p.R) fetch(ids_next, r0 + kOccupancyStep);   // in flight during the rest of this step
         uint32_t hits = 0u;
 #pragma unroll
@@ -93,40 +161,26 @@ __global__ __launch_bounds__(kOccupancyThreads) void k_parent_occupancy(EvalPara
         const uint32_t upto = wave_inclusive_scan(n_mine, lane);
         if (lane == 63u) wave_total[wv] = upto;
         __syncthreads();
-        uint32_t before = upto - n_mine, n_list = 0u;
+        uint32_t at = n_list + upto - n_mine, n_step = 0u;
 #pragma unroll
         for (uint32_t j = 0; j < kOccupancyWaves; ++j) {
-            before += j < wv ? wave_total[j] : 0u;
-            n_list += wave_total[j];
+            at += j < wv ? wave_total[j] : 0u;
+            n_step += wave_total[j];
         }
-        for (uint32_t h = hits; h != 0u; h &= h - 1u) list[before++] = mine + (uint32_t)__ffs((int)h) - 1u;
-        __syncthreads();
-        if (wv == 0u) {
-            for (uint32_t i0 = 0; i0 < n_list; i0 += kWave) {
-                uint32_t arrival = 0u, finish = 0u;
-                if (i0 + lane < n_list) {
-                    const uint32_t r = list[i0 + lane];
-                    uint32_t prefill, tpot;
-                    request_cost(p.tab_prefill, p.tab_tpot, rp, r, p.prompt[r], prefill, tpot);
-                    arrival = p.arrival[r];
-                    finish = arrival + prefill + p.outlen[r] * tpot;
-                }
-                const uint32_t n_here = min(kWave, n_list - i0);
-                for (uint32_t k = 0; k < n_here; ++k) {
-                    const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)arrival, (int)k);
-                    const uint32_t f = (uint32_t)__builtin_amdgcn_readlane((int)finish, (int)k);
-                    const unsigned long long busy = __ballot(slot_finish > a);
-                    deepest = max(deepest, (uint32_t)__popcll(busy) + 1u);
-                    if (~busy != 0ull && lane == (uint32_t)__ffsll((long long)~busy) - 1u) slot_finish = f;
-                }
-            }
-        }
-        // the next step's scan may overwrite wave_total and list only after everyone is done with them
-        __syncthreads();
+        for (uint32_t h = hits; h != 0u; h &= h - 1u) list[at++] = mine + (uint32_t)__ffs((int)h) - 1u;
+        n_list += n_step;                         // below kOccupancyListCap: less than a tile was left over
+        __syncthreads();                          // the list is written; wave_total may be rewritten
+        const bool last_step = r0 + kOccupancyStep >= p.R;
+        while (n_list >= kOccupancyTile) count_tile(kOccupancyTile, !(last_step && n_list == kOccupancyTile));
+        if (last_step && n_list > 0u) count_tile(n_list, false);
     }
+    deepest = wave_max_u32(deepest);
+    if (lane == 0u) atomicMax(&wg_deepest, deepest);
+    __syncthreads();
     if (tid == 0u) {
-        peak[m] = deepest;
-        room[m] = deepest <= p.B ? p.B - deepest : 0u;
+        const uint32_t d = wg_deepest;
+        peak[m] = d;
+        room[m] = d <= p.B ? p.B - d : 0u;
     }
     if (m == 0u) {
         unknown = wave_sum_u32(unknown);

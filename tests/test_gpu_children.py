@@ -112,6 +112,27 @@ def test_calls_that_leave_work_for_the_replay_alternate_with_calls_that_leave_no
             assert_same(got, want[kind], f"call {step} ({kind})")
 
 
+@pytest.mark.parametrize("burst_at", [2040, 4090, 5983], ids=["first_tile_boundary", "second_tile_boundary", "end"])
+@pytest.mark.parametrize("B", [16, 17], ids=["burst_overflows", "burst_just_fits"])
+def test_parent_depth_across_the_tiles_of_a_long_replica_list(B, burst_at):
+    """One replica holds 6000 requests, which the parent analysis counts in tiles of 2048; 17 of them arrive in
+    the same microsecond, straddling a tile boundary (or at the very end).  With 17 slots the parent is still
+    contention-free and its children are settled from their lists; with 16 it is not, and every child must go
+    through the dense path: a depth that lost the requests of the earlier tile would certify wrongly."""
+    n, M = 6000, 2
+    arrival = (np.arange(n, dtype=np.uint64) * 3000 + 1_000_000_007)
+    arrival[burst_at:burst_at + 17] = arrival[burst_at]
+    arrival[burst_at + 17:] += 200_000                              # the burst has drained before the next arrival
+    tr = traces.custom_trace(arrival, np.full(n, 16), np.full(n, 1), [STD] * M, B=B)
+    parent = np.zeros(n, np.uint16)
+    first = np.array([0, 0, 1, 3, 4], np.uint32)
+    request = np.array([10, burst_at + 3, burst_at + 20, 100], np.uint32)
+    replica = np.array([1, 1, 1, 0], np.uint16)
+    got = both(tr, parent, (first, request, replica), f"long list B={B} burst at {burst_at}")
+    want_wait = B == 16
+    assert (int(got[0]["sum_ttft_us"]) > n * 2048) == want_wait      # 2048 us of prefill each when nobody waits
+
+
 def test_parent_that_queues_or_names_unknown_replicas():
     """No shortcut when the parent itself is not contention-free, or names a replica outside the table."""
     n, M, B = 3000, 4, 2
