@@ -75,7 +75,7 @@ __global__ __launch_bounds__(kOccupancyThreads) void k_parent_occupancy(EvalPara
     // Counts the depths of list[0 .. n_tile) and takes them off the list.  Called by all threads with the same
     // arguments; more_follow: requests after this tile may exist, so `latest` has to be brought up to date.
     auto count_tile = [&](uint32_t n_tile, bool more_follow) {
-        uint32_t my_arrival[2] = {0u, 0u};
+        uint32_t my_arrival[2] = {0u, 0u}, my_longest = 0u;
 #pragma unroll
         for (uint32_t q = 0; q < 2u; ++q) {
             const uint32_t i = tid + q * kOccupancyThreads;
@@ -87,9 +87,11 @@ __global__ __launch_bounds__(kOccupancyThreads) void k_parent_occupancy(EvalPara
                 my_arrival[q] = p.arrival[r];
                 tile_arrival[i] = my_arrival[q];
                 tile_finish[i] = my_arrival[q] + service;
-                atomicMax(&longest, service);
+                my_longest = max(my_longest, service);
             }
         }
+        my_longest = wave_max_u32(my_longest);
+        if (lane == 0u && my_longest != 0u) atomicMax(&longest, my_longest);
         if (wv == 0u) carry[lane] = latest;
         __syncthreads();
         const uint32_t reach = longest;
