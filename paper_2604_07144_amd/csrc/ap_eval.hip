@@ -118,6 +118,7 @@ struct ap_workload {
     uint16_t* d_parent = nullptr;     // [R]
     uint32_t* d_peak = nullptr;       // [AP_MAX_REPLICAS + 1] depth of the parent per replica, then its unknown ids
     uint32_t* d_room = nullptr;       // [AP_MAX_REPLICAS]
+    unsigned char* h_stage = nullptr; // pinned: the parent row on its way in, then the depths on their way out
     uint16_t* d_rows = nullptr;       // [max_children][R]
     size_t rows_bytes = 0;
     uint32_t max_children = 0;
@@ -619,9 +620,11 @@ ap_status ap_parent_set(ap_workload* w, const uint16_t* parent, uint32_t max_chi
     w->has_parent = false;
     if ((uint64_t)max_children > (UINT64_MAX / sizeof(uint16_t)) / w->R) return AP_ERR_ALLOC;     // the rows cannot exist
     const size_t need = (size_t)max_children * w->R * sizeof(uint16_t);
-    if ((!w->d_parent && hipMalloc(&w->d_parent, (size_t)w->R * sizeof(uint16_t)) != hipSuccess) ||
-        (!w->d_peak && hipMalloc(&w->d_peak, sizeof(uint32_t) * (AP_MAX_REPLICAS + 1u)) != hipSuccess) ||
-        (!w->d_room && hipMalloc(&w->d_room, sizeof(uint32_t) * AP_MAX_REPLICAS) != hipSuccess)) {
+    const size_t row_bytes = (size_t)w->R * sizeof(uint16_t), peak_bytes = sizeof(uint32_t) * (AP_MAX_REPLICAS + 1u);
+    if ((!w->d_parent && hipMalloc(&w->d_parent, row_bytes) != hipSuccess) ||
+        (!w->d_peak && hipMalloc(&w->d_peak, peak_bytes) != hipSuccess) ||
+        (!w->d_room && hipMalloc(&w->d_room, sizeof(uint32_t) * AP_MAX_REPLICAS) != hipSuccess) ||
+        (!w->h_stage && hipHostMalloc(reinterpret_cast<void**>(&w->h_stage), std::max(row_bytes, peak_bytes), hipHostMallocDefault) != hipSuccess)) {
         (void)hipGetLastError();
         return AP_ERR_ALLOC;
     }
@@ -635,23 +638,29 @@ ap_status ap_parent_set(ap_workload* w, const uint16_t* parent, uint32_t max_chi
         }
         w->rows_bytes = need;
     }
-    if (hipMemcpy(w->d_parent, parent, (size_t)w->R * sizeof(uint16_t), hipMemcpyHostToDevice) != hipSuccess)
-        return AP_ERR_DEVICE;
+    // through the pinned buffer: upload, analysis and read-back are queued together and waited for once
+    std::memcpy(w->h_stage, parent, row_bytes);
+    if (hipMemcpyAsync(w->d_parent, w->h_stage, row_bytes, hipMemcpyHostToDevice, nullptr) != hipSuccess) return AP_ERR_DEVICE;
     const uint32_t M = w->params.M;
     bool certify = false;
     if (w->screen) {
         // the shortcut needs the nominal record, i.e. identical replicas that are always available
         hipLaunchKernelGGL(k_parent_occupancy, dim3(M), dim3(kOccupancyThreads), 0, nullptr, w->params, w->d_parent, w->d_peak,
                            w->d_room);
-        std::vector<uint32_t> peak(M + 1u);
+        // (the kernel is queued behind the upload, which has therefore read the pinned buffer before the depths land in it)
         if (hipGetLastError() != hipSuccess ||
-            hipMemcpy(peak.data(), w->d_peak, sizeof(uint32_t) * (M + 1u), hipMemcpyDeviceToHost) != hipSuccess) {
+            hipMemcpyAsync(w->h_stage, w->d_peak, sizeof(uint32_t) * (M + 1u), hipMemcpyDeviceToHost, nullptr) != hipSuccess ||
+            hipStreamSynchronize(nullptr) != hipSuccess) {
             (void)hipGetLastError();
             return AP_ERR_DEVICE;
         }
+        const uint32_t* peak = reinterpret_cast<const uint32_t*>(w->h_stage);
         // ... and a parent that is contention-free itself and names only replicas of the table
         certify = peak[M] == 0u;
         for (uint32_t m = 0; m < M; ++m) certify = certify && peak[m] <= w->params.B;
+    } else if (hipStreamSynchronize(nullptr) != hipSuccess) {
+        (void)hipGetLastError();
+        return AP_ERR_DEVICE;
     }
     ChildParams cp{};
     cp.parent = w->d_parent;
@@ -1062,6 +1071,7 @@ ap_status ap_workload_destroy(ap_workload* w) {
     if (w->d_pair) ok = (hipFree(w->d_pair) == hipSuccess) && ok;
     if (w->d_nominal) ok = (hipFree(w->d_nominal) == hipSuccess) && ok;
     if (w->d_pending) ok = (hipFree(w->d_pending) == hipSuccess) && ok;
+    if (w->h_stage) ok = (hipHostFree(w->h_stage) == hipSuccess) && ok;
     if (w->d_parent) ok = (hipFree(w->d_parent) == hipSuccess) && ok;
     if (w->d_peak) ok = (hipFree(w->d_peak) == hipSuccess) && ok;
     if (w->d_room) ok = (hipFree(w->d_room) == hipSuccess) && ok;
