@@ -34,11 +34,11 @@ KERNEL_SOURCE_DIR = os.path.join(ROOT, "paper_2604_07144_amd", "csrc")
 # Keyed by configuration; valid only for the library source (all of csrc/) whose hash is recorded with it.
 MEASURED_TRAFFIC = {
     # cfg: (sha256 of the kernel source when measured, bytes per call)
-    4: ("1d32ad5f017b00df4e29681181fbc36b393a65f1c8e7083d6c5c9a41a6a2367d", 4307838061),
-    3: ("1d32ad5f017b00df4e29681181fbc36b393a65f1c8e7083d6c5c9a41a6a2367d", 543952685),
+    4: ("866975664060e48ab97bb7c1cbdcb41dd884b6cedbd79379e30c42255bbf46df", 4308109757),
+    3: ("866975664060e48ab97bb7c1cbdcb41dd884b6cedbd79379e30c42255bbf46df", 544024275),
 }
 # the same for one ap_eval_children call on the sparse form of configs[4]
-MEASURED_TRAFFIC_CHILDREN = {4: ("1d32ad5f017b00df4e29681181fbc36b393a65f1c8e7083d6c5c9a41a6a2367d", 131229971)}
+MEASURED_TRAFFIC_CHILDREN = {4: ("866975664060e48ab97bb7c1cbdcb41dd884b6cedbd79379e30c42255bbf46df", 131147374)}
 
 
 def kernel_source_hash() -> str:

@@ -68,6 +68,8 @@ EvalKernel eval_kernel(bool hist16, bool len16, bool tabled) {
 
 }  // namespace
 
+constexpr size_t kNominalSumsBytes = 3u * kBins * sizeof(uint32_t) + 3u * sizeof(unsigned long long) + 4u * sizeof(uint32_t);
+
 struct ap_workload {
     int device = 0;
     uint32_t R = 0;
@@ -88,6 +90,7 @@ struct ap_workload {
     uint32_t* d_pair = nullptr;       // one word per two requests (eight-wavefront screening kernel, when it fits)
     bool screen_packed = false;       // that kernel reads d_pair instead of d_span
     ap_metrics* d_nominal = nullptr;  // record shared by all contention-free candidates
+    unsigned char* d_nominal_sums = nullptr;   // k_nominal_metrics: three histograms of 32-bit counts, then its sums and counters
     uint32_t* d_pending = nullptr;    // [2] "this call has left pending marks", taken in turn by the calls
     mutable uint32_t turn = 0;        // which of the two the next call uses
     bool has_model = false;
@@ -253,6 +256,7 @@ ap_status ap_workload_create(const uint64_t* arrival_us, const int32_t* prompt_l
                         hipMalloc(&w->d_span_t, padded) != hipSuccess ||
                         hipMalloc(&w->d_pair, ((size_t)R + 1u) / 2u * 4u) != hipSuccess ||
                         hipMalloc(&w->d_nominal, sizeof(ap_metrics)) != hipSuccess ||
+                        hipMalloc(&w->d_nominal_sums, kNominalSumsBytes) != hipSuccess ||
                         hipMalloc(&w->d_pending, 2u * sizeof(uint32_t)) != hipSuccess))
         st = AP_ERR_ALLOC;
     if (st == AP_OK && hipMemset(w->d_pending, 0, 2u * sizeof(uint32_t)) != hipSuccess) st = AP_ERR_DEVICE;
@@ -567,9 +571,14 @@ static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint
         w->screen_params = sp;
         w->screen_wide_lds_bytes = (((M + 1u) << S_log2) + 4u) * 4u;
         w->screen_lds_bytes = kScreenWaves * sp.wave_bytes;
-        hipLaunchKernelGGL(hist16 ? k_nominal_metrics<true> : k_nominal_metrics<false>, dim3(1), dim3(kThreads),
+        // a thread takes two requests per turn; enough workgroups for four turns each, at most one per compute unit
+        const uint32_t n_groups = std::max(1u, std::min((uint32_t)n_cu, (w->R + 8u * kThreads - 1u) / (8u * kThreads)));
+        if (hipMemsetAsync(w->d_nominal_sums, 0, kNominalSumsBytes, nullptr) != hipSuccess) return AP_ERR_DEVICE;
+        hipLaunchKernelGGL(hist16 ? k_nominal_metrics<true> : k_nominal_metrics<false>, dim3(n_groups), dim3(kThreads),
                            reduce_lds, nullptr, w->reduce_eval, w->d_span, w->d_span_t,
-                           w->screen_packed ? w->d_pair : nullptr, (uint32_t)tick_us, w->d_nominal);
+                           w->screen_packed ? w->d_pair : nullptr, (uint32_t)tick_us,
+                           reinterpret_cast<uint32_t*>(w->d_nominal_sums),
+                           reinterpret_cast<unsigned long long*>(w->d_nominal_sums + 3u * kBins * sizeof(uint32_t)), w->d_nominal);
         if (hipGetLastError() != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
             (void)hipGetLastError();
             return AP_ERR_DEVICE;
@@ -1070,6 +1079,7 @@ ap_status ap_workload_destroy(ap_workload* w) {
     if (w->d_span_t) ok = (hipFree(w->d_span_t) == hipSuccess) && ok;
     if (w->d_pair) ok = (hipFree(w->d_pair) == hipSuccess) && ok;
     if (w->d_nominal) ok = (hipFree(w->d_nominal) == hipSuccess) && ok;
+    if (w->d_nominal_sums) ok = (hipFree(w->d_nominal_sums) == hipSuccess) && ok;
     if (w->d_pending) ok = (hipFree(w->d_pending) == hipSuccess) && ok;
     if (w->h_stage) ok = (hipHostFree(w->h_stage) == hipSuccess) && ok;
     if (w->d_parent) ok = (hipFree(w->d_parent) == hipSuccess) && ok;

@@ -56,54 +56,107 @@ __host__ __device__ inline uint32_t screen_table_index(uint32_t r) {
 // contention-free finish times the screening kernels read (in request order and in the
 // lane-major layout), and reduces the values to the record every contention-free candidate
 // shares.
-// One workgroup.
+// Several workgroups share the trace, two consecutive requests per thread and turn (a pair's table
+// word needs both).  Each adds its histograms and sums to a copy in device memory that the host has
+// cleared (`g_hist`: three histograms of 32-bit counts; `g_acc`: three 64-bit sums, then the latest
+// finish time, the number of requests within the objectives and a count of the workgroups that are
+// done); the workgroup that finds itself last takes the totals through the usual reduction.
 template <bool kHist16>
-__global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint32_t* span, uint32_t* __restrict__ span_t,
-                                                              uint32_t* __restrict__ pair, uint32_t tick_us,
+__global__ __launch_bounds__(kThreads) void k_nominal_metrics(EvalParams p, uint32_t* __restrict__ span,
+                                                              uint32_t* __restrict__ span_t, uint32_t* __restrict__ pair,
+                                                              uint32_t tick_us, uint32_t* g_hist, unsigned long long* g_acc,
                                                               ap_metrics* __restrict__ nominal) {
     extern __shared__ __align__(16) unsigned char lds[];
+    __shared__ uint32_t finished_before;
     uint32_t* hist = reinterpret_cast<uint32_t*>(lds);
     unsigned long long* acc64 = reinterpret_cast<unsigned long long*>(lds + p.off_misc);
     uint32_t* acc32 = reinterpret_cast<uint32_t*>(lds + p.off_misc + 24);
     uint32_t* wtot = reinterpret_cast<uint32_t*>(lds + p.off_misc + 64);
-    const uint32_t tid = threadIdx.x;
+    uint32_t* g_acc32 = reinterpret_cast<uint32_t*>(g_acc + 3);              // latest finish, within objectives, workgroups done
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
     hist_clear<kHist16>(hist);
     if (tid < 16u) reinterpret_cast<uint32_t*>(acc64)[tid] = 0u;
     __syncthreads();
     const DevReplica rp = p.rep[0];
     unsigned long long s_e2e = 0, s_ttft = 0, s_tpot = 0;
     uint32_t last_fin = 0, n_ok = 0;
-    for (uint32_t r = tid; r < p.R; r += kThreads) {
-        uint32_t prefill, tpot;
-        request_cost(p.tab_prefill, p.tab_tpot, rp, r, p.prompt[r], prefill, tpot);
-        const uint32_t e2e = prefill + p.outlen[r] * tpot;
-        // service interval in ticks, rounded outwards (arrival down, finish up), 16 bits each
-        const uint32_t fin_us = p.arrival[r] + e2e;
-        const uint32_t span_v = (p.arrival[r] / tick_us) | ((fin_us ? (fin_us - 1u) / tick_us + 1u : 0u) << 16);
-        span[r] = span_v;
-        span_t[screen_table_index(r)] = span_v;
-        hist_add<kHist16>(hist, 0u, hist_bin_u32(prefill), 1u);
-        hist_add<kHist16>(hist, 1u, hist_bin_u32(tpot), 1u);
-        hist_add<kHist16>(hist, 2u, hist_bin_u32(e2e), 1u);
-        s_ttft += prefill;
-        s_e2e += e2e;
-        s_tpot += tpot;
-        last_fin = max(last_fin, p.arrival[r] + e2e);
-        n_ok += (prefill <= p.slo_ttft && tpot <= p.slo_tpot) ? 1u : 0u;
-    }
-    finish_candidate<kHist16>(p, hist, acc64, acc32, wtot, s_e2e, s_ttft, s_tpot, last_fin, n_ok, 0u, nominal);
-    // One word per pair of consecutive requests: arrival tick of the first | (finish tick of the
-    // first - that arrival) << 16 | (finish tick of the second - that arrival) << 24.  The host
-    // asks for this table only with a tick for which both differences are below 256.
-    if (pair != nullptr) {
-        __syncthreads();                              // the span words written above, by this workgroup
-        for (uint32_t q = tid; 2u * q < p.R; q += kThreads) {
-            const uint32_t s0 = span[2u * q];
-            const uint32_t s1 = 2u * q + 1u < p.R ? span[2u * q + 1u] : s0;
+    const uint32_t n_pairs = (p.R + 1u) / 2u;
+    for (uint32_t q = blockIdx.x * kThreads + tid; q < n_pairs; q += gridDim.x * kThreads) {
+        uint32_t word[2] = {0u, 0u};
+#pragma unroll
+        for (uint32_t h = 0; h < 2u; ++h) {
+            const uint32_t r = 2u * q + h;
+            if (r < p.R) {
+                uint32_t prefill, tpot;
+                request_cost(p.tab_prefill, p.tab_tpot, rp, r, p.prompt[r], prefill, tpot);
+                const uint32_t e2e = prefill + p.outlen[r] * tpot;
+                // service interval in ticks, rounded outwards (arrival down, finish up), 16 bits each
+                const uint32_t arrival = p.arrival[r], fin_us = arrival + e2e;
+                word[h] = (arrival / tick_us) | ((fin_us ? (fin_us - 1u) / tick_us + 1u : 0u) << 16);
+                span[r] = word[h];
+                span_t[screen_table_index(r)] = word[h];
+                hist_add<kHist16>(hist, 0u, hist_bin_u32(prefill), 1u);
+                hist_add<kHist16>(hist, 1u, hist_bin_u32(tpot), 1u);
+                hist_add<kHist16>(hist, 2u, hist_bin_u32(e2e), 1u);
+                s_ttft += prefill;
+                s_e2e += e2e;
+                s_tpot += tpot;
+                last_fin = max(last_fin, fin_us);
+                n_ok += (prefill <= p.slo_ttft && tpot <= p.slo_tpot) ? 1u : 0u;
+            }
+        }
+        // One word per pair of consecutive requests: arrival tick of the first | (finish tick of the
+        // first - that arrival) << 16 | (finish tick of the second - that arrival) << 24.  The host
+        // asks for this table only with a tick for which both differences are below 256.
+        if (pair != nullptr) {
+            const uint32_t s0 = word[0], s1 = 2u * q + 1u < p.R ? word[1] : s0;
             const uint32_t arr = s0 & 0xFFFFu;
             pair[q] = arr | (((s0 >> 16) - arr) << 16) | (((s1 >> 16) - arr) << 24);
         }
     }
+    // this workgroup's share into the copy in device memory
+    s_e2e = wave_sum_u64(s_e2e);
+    s_ttft = wave_sum_u64(s_ttft);
+    s_tpot = wave_sum_u64(s_tpot);
+    last_fin = wave_max_u32(last_fin);
+    n_ok = wave_sum_u32(n_ok);
+    if (lane == 0u) {
+        atomicAdd(&g_acc[0], s_e2e);
+        atomicAdd(&g_acc[1], s_ttft);
+        atomicAdd(&g_acc[2], s_tpot);
+        atomicMax(&g_acc32[0], last_fin);
+        atomicAdd(&g_acc32[1], n_ok);
+    }
+    __syncthreads();                                  // the histograms in LDS are complete
+    for (uint32_t i = tid; i < 3u * kBins; i += kThreads) {
+        const uint32_t count = hist_get<kHist16>(hist, i / kBins, i % kBins);
+        if (count != 0u) atomicAdd(&g_hist[i], count);
+    }
+    __threadfence();
+    __syncthreads();
+    if (tid == 0u) finished_before = atomicAdd(&g_acc32[2], 1u);
+    __syncthreads();
+    if (finished_before != gridDim.x - 1u) return;    // the same word for every thread
+    // the last one: every other workgroup's additions were made before it counted itself done
+    __threadfence();
+    hist_clear<kHist16>(hist);
+    if (tid < 16u) reinterpret_cast<uint32_t*>(acc64)[tid] = 0u;
+    __syncthreads();
+    for (uint32_t i = tid; i < 3u * kBins; i += kThreads) {
+        const uint32_t count = __hip_atomic_load(&g_hist[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (count != 0u) hist_add<kHist16>(hist, i / kBins, i % kBins, count);
+    }
+    unsigned long long t_e2e = 0, t_ttft = 0, t_tpot = 0;
+    uint32_t t_last = 0, t_ok = 0;
+    if (tid == 0u) {
+        t_e2e = __hip_atomic_load(&g_acc[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        t_ttft = __hip_atomic_load(&g_acc[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        t_tpot = __hip_atomic_load(&g_acc[2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        t_last = __hip_atomic_load(&g_acc32[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        t_ok = __hip_atomic_load(&g_acc32[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    finish_candidate<kHist16>(p, hist, acc64, acc32, wtot, t_e2e, t_ttft, t_tpot, t_last, t_ok, 0u, nominal);
 }
 
 // ----------------------------------------------------------------------------------
