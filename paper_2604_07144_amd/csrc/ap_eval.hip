@@ -21,13 +21,15 @@
 //
 // This file holds the host side: planning, the workload object and the C ABI.  The kernels are in
 // ap_screen.hpp (screening), ap_replay.hpp (fused replay), ap_pipeline.hpp (three-kernel replay) and
-// ap_children.hpp (sparse candidates), ap_roofline.hpp (roofline cost tables, trace time) and ap_agentic.hpp
-// (agentic workflows); ap_common.hpp has what they share.
+// ap_children.hpp (sparse candidates), ap_split.hpp (replicas that differ or come and go: listed and streamed
+// part), ap_roofline.hpp (roofline cost tables, trace time) and ap_agentic.hpp (agentic workflows); ap_common.hpp
+// has what they share.
 #include "ap_common.hpp"
 #include "ap_screen.hpp"
 #include "ap_replay.hpp"
 #include "ap_pipeline.hpp"
 #include "ap_children.hpp"
+#include "ap_split.hpp"
 #include "ap_roofline.hpp"
 #include "ap_agentic.hpp"
 
@@ -127,6 +129,19 @@ struct ap_workload {
     uint32_t max_children = 0;
     bool has_parent = false;
     ChildParams child_params{};
+    // split evaluation (replicas that differ or have windows): listed part replayed, streamed part scored on arrival
+    uint2* d_req8 = nullptr;          // [R] {arrival, prompt | out << 16}; only when every length is below 65536
+    SplitReplica* d_split_rep = nullptr;   // [AP_MAX_REPLICAS + 1]
+    SplitQueue* d_split_queue = nullptr;   // [AP_MAX_REPLICAS]
+    uint32_t* d_split_order = nullptr;     // [AP_MAX_REPLICAS]
+    unsigned char* d_split_scratch = nullptr;
+    size_t split_scratch_bytes = 0;
+    bool split = false;               // the split evaluation runs in front of the general replay
+    bool split_expect_lazy = false;   // stream without histograms first
+    uint32_t split_batch = 0;         // candidates per batch (what the scratch area holds)
+    uint32_t split_lds_bytes = 0, split_lds_bytes_hist = 0;
+    uint32_t split_slots = 0;         // B rounded up to 8, 16, 32 or 64
+    SplitParams split_params{};
 };
 
 // The dense path on C rows: screening where it applies, then the exact replay of what is left.
@@ -167,7 +182,28 @@ static ap_status launch_dense(const ap_workload* w, const uint16_t* d_assign, ui
         }
         if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
     }
-    const uint32_t pending_only = w->screen ? 1u : 0u;
+    if (w->split && !marked) {
+        // the listed / streamed evaluation, a batch of candidates at a time; what it hands back carries the pending mark
+        const SplitParams& sp = w->split_params;
+        typedef void (*replay_fn)(SplitParams, uint32_t);
+        const replay_fn replay = w->split_slots == 8u ? k_replay_lists<8u> : w->split_slots == 16u ? k_replay_lists<16u>
+                                 : w->split_slots == 32u ? k_replay_lists<32u> : k_replay_lists<64u>;
+        for (uint32_t c0 = 0; c0 < C; c0 += w->split_batch) {
+            const uint32_t n = std::min(w->split_batch, C - c0);
+            const uint32_t grid = std::min(n, w->n_cu * 16u);
+            if (w->split_expect_lazy)
+                hipLaunchKernelGGL(k_split_candidates<false>, dim3(grid), dim3(kSplitThreads), w->split_lds_bytes, stream, sp,
+                                   d_assign, c0, n, 0u, flags);
+            hipLaunchKernelGGL(k_split_candidates<true>, dim3(grid), dim3(kSplitThreads), w->split_lds_bytes_hist, stream, sp,
+                               d_assign, c0, n, w->split_expect_lazy ? 1u : 0u, flags);
+            if (sp.n_queues != 0u)
+                hipLaunchKernelGGL(replay, dim3(sp.n_queues * ((n + kWave - 1u) / kWave)), dim3(kWave), 0, stream, sp, n);
+            hipLaunchKernelGGL(k_merge_candidates, dim3(std::min((n + kThreads - 1u) / kThreads, w->n_cu * 4u)), dim3(kThreads),
+                               w->reduce_lds_bytes, stream, w->reduce_eval, sp, d_out, c0, n, flags);
+        }
+        if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
+    }
+    const uint32_t pending_only = (w->screen || (w->split && !marked)) ? 1u : 0u;
     if (w->pipeline) {
         for (uint32_t c0 = 0; c0 < C; c0 += w->batch) {
             const uint32_t n = std::min(w->batch, C - c0);
@@ -274,6 +310,21 @@ ap_status ap_workload_create(const uint64_t* arrival_us, const int32_t* prompt_l
         else if (hipMemcpy(w->d_req, recs.data(), sizeof(uint4) * (size_t)R, hipMemcpyHostToDevice) != hipSuccess)
             st = AP_ERR_DEVICE;
     }
+    if (st == AP_OK && w->len16) {
+        // arrival and both lengths of a request in 8 bytes, for the kernels that read whole records
+        std::vector<uint2> packed;
+        try {
+            packed.resize(R);
+        } catch (const std::bad_alloc&) {
+            st = AP_ERR_ALLOC;
+        }
+        if (st == AP_OK) {
+            for (uint32_t r = 0; r < R; ++r) packed[r] = make_uint2(rel[r], (uint32_t)prompt_len[r] | ((uint32_t)out_len[r] << 16));
+            if (hipMalloc(&w->d_req8, sizeof(uint2) * (size_t)R) != hipSuccess) st = AP_ERR_ALLOC;
+            else if (hipMemcpy(w->d_req8, packed.data(), sizeof(uint2) * (size_t)R, hipMemcpyHostToDevice) != hipSuccess)
+                st = AP_ERR_DEVICE;
+        }
+    }
     if (st == AP_OK && (hipMemcpy(w->d_arrival, rel.data(), bytes, hipMemcpyHostToDevice) != hipSuccess ||
                         hipMemcpy(w->d_prompt, prompt_len, bytes, hipMemcpyHostToDevice) != hipSuccess ||
                         hipMemcpy(w->d_out, out_len, bytes, hipMemcpyHostToDevice) != hipSuccess))
@@ -284,6 +335,170 @@ ap_status ap_workload_create(const uint64_t* arrival_us, const int32_t* prompt_l
         return st;
     }
     *out = w;
+    return AP_OK;
+}
+
+// Plan of the split evaluation (ap_split.hpp) for a linear cost model whose replicas differ or have windows:
+// the index ranges of every replica, the bound D on requests in service that started on arrival, the
+// scratch area for one batch of candidates.  Leaves w->split false where the path does not apply.
+static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, const ap_replica* replicas,
+                            const std::vector<uint32_t>& kinds, const std::vector<uint32_t>& worst_service,
+                            const std::vector<uint64_t>& kind_sum, const std::vector<uint64_t>& kind_longest,
+                            uint64_t latest_finish_bound) {
+    const uint32_t R = w->R, M = w->params.M, B = w->params.B;
+    if (!w->d_req8 || R >= 65536u) return AP_OK;            // 16-bit lengths and 16-bit histogram counts only
+    std::vector<uint32_t> depth_from;                        // depth_from[i] = max over r >= i of D(r); [R] = 0
+    std::vector<SplitReplica> rep;
+    std::vector<SplitQueue> queue;
+    std::vector<uint32_t> order;
+    try {
+        depth_from.assign((size_t)R + 1u, 0u);
+        rep.resize(M + 1u);
+        queue.resize(M);
+        // D(r): sweep in arrival order over a min-heap of the finish times of requests that start on arrival
+        std::vector<uint64_t> heap;
+        heap.reserve(1024);
+        for (uint32_t r = 0; r < R; ++r) {
+            const uint64_t a = w->h_arrival[r];
+            while (!heap.empty() && heap.front() <= a) {
+                std::pop_heap(heap.begin(), heap.end(), std::greater<uint64_t>());
+                heap.pop_back();
+            }
+            heap.push_back(a + worst_service[r]);
+            std::push_heap(heap.begin(), heap.end(), std::greater<uint64_t>());
+            depth_from[r] = (uint32_t)std::min<size_t>(heap.size(), kNever);
+        }
+    } catch (const std::bad_alloc&) {
+        return AP_ERR_ALLOC;
+    }
+    for (uint32_t r = R; r-- > 0u;) depth_from[r] = std::max(depth_from[r], depth_from[r + 1u]);
+
+    // The streamed part of a replica may begin where the bound leaves an eighth of the slots to the listed part.
+    const uint32_t reserve = B / 8u;
+    const uint32_t i_calm = (uint32_t)(std::partition_point(depth_from.begin(), depth_from.end(),
+                                                            [&](uint32_t d) { return d + reserve > B; }) - depth_from.begin());
+    const uint32_t* arr = w->h_arrival.data();
+    uint32_t longest_list = 0;
+    uint64_t expect_rejected = 0;
+    for (uint32_t m = 0; m < M; ++m) {
+        const DevReplica& d = dev[m];
+        const uint32_t i_on = (uint32_t)(std::lower_bound(arr, arr + R, d.t_on) - arr);
+        const uint32_t i_off = (uint32_t)(std::lower_bound(arr, arr + R, d.t_off) - arr);
+        // which kind of replica this is (its service times: mean and longest)
+        size_t ki = 0;
+        for (size_t k = 0; k < kinds.size(); ++k)
+            if (replicas[kinds[k]].prefill_base_us == replicas[m].prefill_base_us &&
+                replicas[kinds[k]].prefill_per_tok_us == replicas[m].prefill_per_tok_us &&
+                replicas[kinds[k]].decode_base_us == replicas[m].decode_base_us &&
+                replicas[kinds[k]].decode_per_kctx_us == replicas[m].decode_per_kctx_us)
+                ki = k;
+        // The backlog a replica finds when it comes up is about its share of the requests so far; served B at a
+        // time it is gone after so many mean service times, and the last of it after one longest service more.
+        // Twice that is where the streamed part begins - a guess that only decides how often the list replay has
+        // to hand a candidate back, never a result.
+        uint32_t i_list = 0;
+        if (i_on > 0u) {
+            const double mean_service = (double)kind_sum[ki] / R;
+            const double drain = 2.0 * (((double)i_on / M) / B + 1.0) * mean_service + (double)kind_longest[ki];
+            const uint64_t t_target = (uint64_t)d.t_on + (uint64_t)std::min(drain, 4.0e9);
+            i_list = (uint32_t)(std::lower_bound(arr, arr + R, (uint32_t)std::min<uint64_t>(t_target, kNever)) - arr);
+        }
+        i_list = std::min(std::max(i_list, i_calm), i_off);
+        rep[m] = SplitReplica{d.a, d.b, d.c, d.d, i_list, i_off, 0u, 0u};
+        SplitQueue q{};
+        q.a = d.a; q.b = d.b; q.c = d.c; q.d = d.d; q.t_on = d.t_on; q.t_off = d.t_off;
+        q.i_list = i_list;
+        q.t_split = i_list < i_off ? arr[i_list] : kNever;
+        q.allow_busy = i_list < i_off ? B - std::min(B, depth_from[i_list]) : 0u;
+        queue[m] = q;
+        longest_list = std::max(longest_list, i_list);
+        expect_rejected += R - i_off;
+    }
+    rep[M] = SplitReplica{0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};  // unknown replica ids: rejected on arrival
+    for (uint32_t m = 0; m < M; ++m)
+        if (queue[m].i_list > 0u) order.push_back(m);
+    std::stable_sort(order.begin(), order.end(), [&](uint32_t x, uint32_t y) { return queue[x].i_list > queue[y].i_list; });
+
+    SplitParams sp{};
+    sp.R = R; sp.M = M; sp.B = B; sp.key_bits = w->params.key_bits;
+    sp.n_tiles = (R + kTile - 1u) / kTile;
+    sp.n_list_tiles = (longest_list + kTile - 1u) / kTile;
+    sp.tile_cap = align_up(std::min(kTile, R) + 7u * std::min(M, std::min(kTile, R)), 8u);
+    sp.n_queues = (uint32_t)order.size();
+    sp.slo_ttft = w->params.slo_ttft;
+    sp.slo_tpot = w->params.slo_tpot;
+    // The p99 values are the penalty latency once R - k99 + 1 requests are rejected, if no served latency can
+    // reach the penalty's bin: all of them lie below the bound on finish times of the range proof.
+    const bool penalty_on_top = w->params.penalty_bin > ap_hist_bin(latest_finish_bound);
+    sp.lazy_from = penalty_on_top ? R - w->params.k99 + 1u : kNever;
+    // LDS of the streaming kernel
+    uint32_t off = 0;
+    const uint32_t hist_bytes = 3u * kBins * 2u;
+    sp.off_table = off; off += align_up((M + 1u) * (uint32_t)sizeof(SplitReplica), 16u);
+    sp.off_acc = off;   off += 64u;
+    sp.off_wave = off;
+    uint32_t wb = 0;
+    wb += align_up(M * 4u, 16u);            sp.w_pos = wb;
+    wb += align_up(M * 4u, 16u);            sp.w_queue = wb;
+    wb += kTile * 4u;                       sp.w_list = wb;
+    wb += align_up(sp.tile_cap * 2u, 16u);
+    sp.wave_bytes = wb;
+    off += kSplitWaves * wb;
+    sp.off_hist = off;
+    if (off + hist_bytes > 64u * 1024u) return AP_OK;       // a replica table that large stays with the general replay
+    w->split_lds_bytes = off;
+    w->split_lds_bytes_hist = off + hist_bytes;
+    w->split_slots = B <= 8u ? 8u : B <= 16u ? 16u : B <= 32u ? 32u : 64u;
+
+    // scratch for one batch of candidates: lists, run descriptors, partial records, histograms
+    const size_t per_cand = (size_t)sp.n_list_tiles * sp.tile_cap * 2u + (size_t)sp.n_list_tiles * M * 4u + sizeof(SplitPartial) +
+                            hist_bytes;
+    uint32_t batch = (uint32_t)std::min<size_t>(16384u, std::max<size_t>(64u, ((size_t)1 << 30) / per_cand));
+    batch = batch / 64u * 64u;
+    auto carve = [](size_t& at, size_t bytes) { const size_t here = at; at = (at + bytes + 255u) / 256u * 256u; return here; };
+    size_t total = 0;
+    const size_t o_lists = carve(total, (size_t)batch * sp.n_list_tiles * sp.tile_cap * 2u);
+    const size_t o_desc = carve(total, (size_t)batch * sp.n_list_tiles * M * 4u);
+    const size_t o_part = carve(total, (size_t)batch * sizeof(SplitPartial));
+    const size_t o_hist = carve(total, (size_t)batch * hist_bytes);
+    if (total > w->split_scratch_bytes) {
+        if (w->d_split_scratch && hipFree(w->d_split_scratch) != hipSuccess) return AP_ERR_DEVICE;
+        w->d_split_scratch = nullptr;
+        w->split_scratch_bytes = 0;
+        if (hipMalloc(&w->d_split_scratch, total) != hipSuccess) {
+            (void)hipGetLastError();
+            return AP_ERR_ALLOC;
+        }
+        w->split_scratch_bytes = total;
+    }
+    if ((!w->d_split_rep && hipMalloc(&w->d_split_rep, sizeof(SplitReplica) * (AP_MAX_REPLICAS + 1u)) != hipSuccess) ||
+        (!w->d_split_queue && hipMalloc(&w->d_split_queue, sizeof(SplitQueue) * AP_MAX_REPLICAS) != hipSuccess) ||
+        (!w->d_split_order && hipMalloc(&w->d_split_order, sizeof(uint32_t) * AP_MAX_REPLICAS) != hipSuccess)) {
+        (void)hipGetLastError();
+        return AP_ERR_ALLOC;
+    }
+    if (hipMemcpy(w->d_split_rep, rep.data(), sizeof(SplitReplica) * (M + 1u), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(w->d_split_queue, queue.data(), sizeof(SplitQueue) * M, hipMemcpyHostToDevice) != hipSuccess ||
+        (!order.empty() &&
+         hipMemcpy(w->d_split_order, order.data(), sizeof(uint32_t) * order.size(), hipMemcpyHostToDevice) != hipSuccess) ||
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&k_merge_candidates), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)w->reduce_lds_bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return AP_ERR_DEVICE;
+    }
+    sp.req8 = w->d_req8;
+    sp.rep = w->d_split_rep;
+    sp.queue = w->d_split_queue;
+    sp.order = w->d_split_order;
+    sp.lists = reinterpret_cast<uint16_t*>(w->d_split_scratch + o_lists);
+    sp.desc = reinterpret_cast<uint32_t*>(w->d_split_scratch + o_desc);
+    sp.part = reinterpret_cast<SplitPartial*>(w->d_split_scratch + o_part);
+    sp.hist = reinterpret_cast<uint32_t*>(w->d_split_scratch + o_hist);
+    w->split_params = sp;
+    w->split_batch = batch;
+    // stream without histograms first when an even spread of the requests over the replicas would reject enough
+    w->split_expect_lazy = penalty_on_top && expect_rejected / M >= sp.lazy_from;
+    w->split = true;
     return AP_OK;
 }
 
@@ -338,16 +553,28 @@ static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint
     uint64_t latest_unqueued = 0;      // latest finish if nobody ever waited (arrival + service)
     uint64_t longest_pair = 0;         // longest time from the arrival of request 2q to the unqueued finish of 2q or 2q+1
     uint64_t service_sum = 0;
+    std::vector<uint32_t> worst_service;            // per request: its longest service time over the kinds of replica
+    std::vector<uint64_t> kind_sum, kind_longest;   // per kind: all service times added up, and the longest
+    try {
+        worst_service.resize(w->R);
+        kind_sum.assign(kinds.size(), 0u);
+        kind_longest.assign(kinds.size(), 0u);
+    } catch (const std::bad_alloc&) {
+        return AP_ERR_ALLOC;
+    }
     for (uint32_t r = 0; r < w->R; ++r) {
         const uint64_t outl = (uint64_t)w->h_out[r];
         uint64_t worst = 0;
-        for (uint32_t k : kinds) {
+        for (size_t ki = 0; ki < kinds.size(); ++ki) {
             uint64_t prefill, tpot;
-            host_cost(k, r, prefill, tpot);
+            host_cost(kinds[ki], r, prefill, tpot);
             if (tpot > limit || prefill > limit) return AP_ERR_RANGE;
             uint64_t svc = prefill + outl * tpot;
             worst = std::max(worst, svc);
+            kind_sum[ki] += std::min(svc, limit);
+            kind_longest[ki] = std::max(kind_longest[ki], std::min(svc, limit));
         }
+        worst_service[r] = (uint32_t)std::min(worst, limit);
         total += worst;
         service_sum += worst;
         latest_unqueued = std::max<uint64_t>(latest_unqueued, (uint64_t)w->h_arrival[r] + worst);
@@ -583,6 +810,12 @@ static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint
             (void)hipGetLastError();
             return AP_ERR_DEVICE;
         }
+    }
+    // ---- split evaluation: replicas that differ or have windows ---------------------------
+    w->split = false;
+    if (!w->screen && !tabled && !use_pipeline) {
+        const ap_status st = plan_split(w, dev, replicas, kinds, worst_service, kind_sum, kind_longest, total);
+        if (st != AP_OK) return st;
     }
     w->has_model = true;
     return AP_OK;
@@ -1086,6 +1319,11 @@ ap_status ap_workload_destroy(ap_workload* w) {
     if (w->d_peak) ok = (hipFree(w->d_peak) == hipSuccess) && ok;
     if (w->d_room) ok = (hipFree(w->d_room) == hipSuccess) && ok;
     if (w->d_rows) ok = (hipFree(w->d_rows) == hipSuccess) && ok;
+    if (w->d_req8) ok = (hipFree(w->d_req8) == hipSuccess) && ok;
+    if (w->d_split_rep) ok = (hipFree(w->d_split_rep) == hipSuccess) && ok;
+    if (w->d_split_queue) ok = (hipFree(w->d_split_queue) == hipSuccess) && ok;
+    if (w->d_split_order) ok = (hipFree(w->d_split_order) == hipSuccess) && ok;
+    if (w->d_split_scratch) ok = (hipFree(w->d_split_scratch) == hipSuccess) && ok;
     delete w;
     return ok ? AP_OK : AP_ERR_DEVICE;
 }

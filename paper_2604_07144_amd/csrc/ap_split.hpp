@@ -1,0 +1,418 @@
+// Exact evaluation for replicas that differ or come and go: the trace of every replica is cut in two.
+#ifndef AP_SPLIT_HPP
+#define AP_SPLIT_HPP
+
+#include "ap_common.hpp"
+#include "ap_screen.hpp"
+
+namespace {
+
+// ----------------------------------------------------------------------------------
+// split evaluation: a listed part that is replayed, a streamed part that provably never waits
+// ----------------------------------------------------------------------------------
+// Replica m serves during [t_on, t_off) (the snapshot holds cluster availability, Section 4; Section 8.2
+// "Elastic Cluster Dynamics").  Requests are in arrival order, so for every replica three index ranges are
+// fixed by the trace alone, whatever the candidate:
+//   r >= i_off[m]             arrives when the replica is gone: rejected on arrival;
+//   r <  i_list[m]            the LISTED part: everything that arrives before the replica is up (its backlog)
+//                             and while that backlog drains.  These requests are grouped by replica and
+//                             replayed exactly through the B-slot queue (k_replay_lists);
+//   i_list[m] <= r < i_off[m] the STREAMED part: scored where the assignment row is read, as requests that
+//                             start on arrival (ttft = prefill), without a queue.
+// Why the streamed part may skip the queue.  Let D(r) be the number of requests r' <= r of the whole trace,
+// on any replica, whose service interval [arrival, arrival + longest service over the replica kinds) holds
+// arrival(r): no candidate can have more requests that started on arrival in service on one replica at that
+// moment.  Let busy(c, m) be the number of slots of replica m that the listed part of candidate c leaves taken
+// beyond t_split[m] = arrival(i_list[m]).  If busy(c, m) + max over r >= i_list[m] of D(r) <= B, then by
+// induction in arrival order every streamed request of (c, m) finds a free slot when it arrives: the requests
+// of m in service at that moment are listed ones still running (at most busy) and earlier streamed ones, which
+// started on arrival by the induction hypothesis and are therefore counted by D(r) - 1.  The host picks
+// i_list[m] so that the bound leaves room (ap_costmodel_set); k_replay_lists counts busy(c, m) at the end of
+// every list and hands the candidate to the general replay if the room is not there.  A trace too dense for
+// any room (D above B) simply has every request listed.
+//
+// Per candidate the record is put together from three parts that add up (sums, counts) or combine by max
+// (latest finish): the streamed part (k_split_candidates), the listed part (k_replay_lists, one atomic update per
+// queue) and the rejected requests at the penalty latency (k_merge_candidates).
+//
+// The p99 fields need the histograms only when fewer than R - k99 + 1 requests are rejected.  Otherwise the
+// k99-th smallest value of each metric is the penalty latency itself (rejected requests are charged it,
+// Appendix "Serving Simulator", Memory Feasibility), provided every served latency falls in a lower bin, which
+// the host checks against its bound on all finish times.  Such a candidate is called settled-by-penalty below
+// and carries kFlagLazy; the others keep 16-bit histograms (in LDS while streaming, then in device memory where
+// the replay adds to them).
+constexpr uint32_t kSplitWaves = 4;
+constexpr uint32_t kSplitThreads = kSplitWaves * kWave;
+constexpr uint32_t kTile = 1024;                  // requests per tile: a list position fits 10 bits
+constexpr uint32_t kFlagNeedHist = 1u;            // streamed without histograms, but they are needed: stream again
+constexpr uint32_t kFlagFallback = 2u;            // the listed part left too many slots taken: general replay
+constexpr uint32_t kFlagLazy = 4u;                // the p99 values are the penalty latency
+
+struct SplitReplica {                             // per replica, for the streaming kernel (LDS copy), 32 bytes
+    uint32_t a, b, c, d;                          // cost coefficients
+    uint32_t i_list, i_off;
+    uint32_t pad0, pad1;
+};
+
+struct SplitQueue {                               // per replica, for the list replay, 48 bytes
+    uint32_t a, b, c, d, t_on, t_off;
+    uint32_t i_list;
+    uint32_t t_split;                             // arrival of request i_list; kNever: nothing is streamed
+    uint32_t allow_busy;                          // slots that may still be taken beyond t_split
+    uint32_t pad0, pad1, pad2;
+};
+
+struct SplitPartial {                             // per candidate of a batch, 64 bytes
+    unsigned long long s_e2e, s_ttft, s_tpot;     // served requests only
+    uint32_t last_fin, n_ok, n_rej, flags;
+    uint32_t pad[6];
+};
+
+struct SplitParams {
+    const uint2* req8;                            // [R] {arrival, prompt | out << 16}
+    const SplitReplica* rep;                      // [M + 1]; entry M takes unknown replica ids: everything rejected
+    const SplitQueue* queue;                      // [M]
+    const uint32_t* order;                        // [n_queues] replicas with a listed part, longest first
+    uint32_t* desc;                               // [batch][n_list_tiles][M] count << 16 | first list position
+    uint16_t* lists;                              // [batch][n_list_tiles][tile_cap] tile-local request indices by replica
+    SplitPartial* part;                           // [batch]
+    uint32_t* hist;                               // [batch][3 * kBins / 2] 16-bit counts, two per word
+    uint32_t R, M, B, key_bits;
+    uint32_t n_tiles, n_list_tiles, tile_cap, n_queues;
+    uint32_t slo_ttft, slo_tpot;
+    uint32_t lazy_from;                           // rejected requests from which the p99 values are the penalty; kNever: never
+    // byte offsets into the streaming kernel's dynamic LDS
+    uint32_t off_table, off_acc, off_wave, wave_bytes, w_pos, w_queue, w_list, off_hist;
+};
+
+// Streaming kernel.  One workgroup per candidate at a time; its wavefronts take the tiles of the row in turn
+// and share nothing but the accumulators (and the histograms), so there is no barrier inside a candidate.
+// Per tile a wavefront classifies its 1024 requests, accumulates the streamed ones, counts the listed ones per
+// replica, queues them in arrival order, ranks them (one ballot per bit of the replica id among 64 queued
+// requests at a time) into per-replica runs that start on multiples of 8 list positions, and writes the runs
+// and their descriptors out.
+// kHist: keep histograms of the streamed requests (needed unless the candidate is settled by penalty).
+// only_flagged: look only at candidates that an earlier launch marked kFlagNeedHist.
+template <bool kHist>
+__global__ __launch_bounds__(kSplitThreads) void k_split_candidates(SplitParams p, const uint16_t* __restrict__ assign,
+                                                                    uint32_t c0, uint32_t n_cand, uint32_t only_flagged,
+                                                                    PendingWord flags) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    pending_clear_next(flags);
+    uint32_t* hist = reinterpret_cast<uint32_t*>(lds + p.off_hist);          // kHist only
+    SplitReplica* table = reinterpret_cast<SplitReplica*>(lds + p.off_table);
+    unsigned long long* acc64 = reinterpret_cast<unsigned long long*>(lds + p.off_acc);
+    uint32_t* acc32 = reinterpret_cast<uint32_t*>(lds + p.off_acc + 24);    // latest finish, within objectives, rejected
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, w = wave_index();
+    unsigned char* mine = lds + p.off_wave + w * p.wave_bytes;
+    uint32_t* cnt = reinterpret_cast<uint32_t*>(mine);                       // [M] listed requests of the tile per replica
+    uint32_t* pos = reinterpret_cast<uint32_t*>(mine + p.w_pos);             // [M] next free position of the replica's run
+    uint32_t* queue = reinterpret_cast<uint32_t*>(mine + p.w_queue);         // [kTile] tile index | replica << 16, arrival order
+    uint16_t* list = reinterpret_cast<uint16_t*>(mine + p.w_list);           // [tile_cap]
+    const uint32_t R = p.R, M = p.M;
+
+    for (uint32_t i = tid; i < (M + 1u) * 8u; i += kSplitThreads)
+        reinterpret_cast<uint32_t*>(table)[i] = reinterpret_cast<const uint32_t*>(p.rep)[i];
+    for (uint32_t m = lane; m < M; m += kWave) cnt[m] = 0u;
+
+    for (uint32_t cb = blockIdx.x; cb < n_cand; cb += gridDim.x) {
+        if (only_flagged && (p.part[cb].flags & kFlagNeedHist) == 0u) continue;     // the same word for every thread
+        __syncthreads();                                                            // the last candidate's totals were read
+        if (kHist)
+            for (uint32_t i = tid; i < 3u * kBins / 2u; i += kSplitThreads) hist[i] = 0u;
+        if (tid < 10u) reinterpret_cast<uint32_t*>(acc64)[tid] = 0u;
+        __syncthreads();
+        const uint16_t* row = assign + (size_t)(c0 + cb) * R;
+        unsigned long long s_e2e = 0, s_ttft = 0, s_tpot = 0;
+        uint32_t last_fin = 0, n_ok = 0, n_rej = 0;
+
+        for (uint32_t j = w; j < p.n_tiles; j += kSplitWaves) {
+            const uint32_t r0 = j * kTile, n = min(kTile, R - r0);
+            const bool grouping = j < p.n_list_tiles;                               // beyond: nothing can be listed
+            uint32_t q_n = 0;                                                       // queued so far (the same in every lane)
+            for (uint32_t g0 = 0; g0 < n; g0 += kWave) {
+                const uint32_t rl = g0 + lane, r = r0 + rl;
+                const bool in = rl < n;
+                const uint32_t k = in ? min((uint32_t)__builtin_nontemporal_load(row + r), M) : M;
+                const uint2 range = *reinterpret_cast<const uint2*>(&table[k].i_list);
+                const bool listed = in && r < range.x;                              // i_list <= i_off
+                const bool rejected = in && r >= range.y;
+                n_rej += (uint32_t)__popcll(__ballot(rejected));
+                if (in && !listed && !rejected) {
+                    // starts on arrival: ttft = prefill
+                    const uint2 rq = p.req8[r];
+                    const uint4 co = *reinterpret_cast<const uint4*>(&table[k]);
+                    const uint32_t prompt = rq.y & 0xFFFFu, out = rq.y >> 16;
+                    const uint32_t prefill = co.x + co.y * prompt;
+                    const uint32_t tpot = co.z + co.w * ((prompt + 1023u) >> 10);
+                    const uint32_t e2e = prefill + out * tpot;
+                    s_ttft += prefill;
+                    s_e2e += e2e;
+                    s_tpot += tpot;
+                    last_fin = max(last_fin, rq.x + e2e);
+                    n_ok += (prefill <= p.slo_ttft && tpot <= p.slo_tpot) ? 1u : 0u;
+                    if (kHist) {
+                        hist_add<true>(hist, 0u, hist_bin_u32(prefill), 1u);
+                        hist_add<true>(hist, 1u, hist_bin_u32(tpot), 1u);
+                        hist_add<true>(hist, 2u, hist_bin_u32(e2e), 1u);
+                    }
+                }
+                const unsigned long long lm = __ballot(listed);
+                if (lm != 0ull) {
+                    if (listed) {
+                        atomicAdd(&cnt[k], 1u);
+                        const uint32_t before = __builtin_amdgcn_mbcnt_hi((uint32_t)(lm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)lm, 0u));
+                        queue[q_n + before] = rl | (k << 16);
+                    }
+                    q_n += (uint32_t)__popcll(lm);
+                }
+            }
+            if (!grouping) continue;                                                // q_n is 0 there
+            // runs: every replica's listed requests of the tile, starting on a multiple of 8 positions
+            const size_t tile_at = (size_t)cb * p.n_list_tiles + j;
+            uint32_t total = 0;
+            for (uint32_t base = 0; base < M; base += kWave) {
+                const uint32_t m = base + lane;
+                const uint32_t c = m < M ? cnt[m] : 0u;
+                const uint32_t room = (c + 7u) & ~7u;
+                const uint32_t upto = wave_inclusive_scan(room, lane);
+                if (m < M) {
+                    pos[m] = total + upto - room;
+                    cnt[m] = 0u;                                                    // for the wavefront's next tile
+                    p.desc[tile_at * M + m] = (c << 16) | (total + upto - room);
+                }
+                total += (uint32_t)__builtin_amdgcn_readlane((int)upto, 63);
+            }
+            for (uint32_t d0 = 0; d0 < q_n; d0 += kWave) {
+                const bool valid = d0 + lane < q_n;
+                const uint32_t pair = valid ? queue[d0 + lane] : 0u;
+                const uint32_t k = valid ? pair >> 16 : kNoKey;
+                uint32_t peers_lo, peers_hi;
+                wave_peers(k, M, p.key_bits, peers_lo, peers_hi);
+                if (valid) {
+                    const uint32_t rank = __builtin_amdgcn_mbcnt_hi(peers_hi, __builtin_amdgcn_mbcnt_lo(peers_lo, 0u));
+                    const uint32_t n_peers = __popc(peers_lo) + __popc(peers_hi);
+                    const uint32_t at = pos[k];
+                    list[at + rank] = (uint16_t)(pair & 0xFFFFu);
+                    if (rank + 1u == n_peers) pos[k] = at + n_peers;
+                }
+            }
+            // 16 bytes (8 positions) at a time; the padding of a run holds whatever the LDS held
+            uint4* dst = reinterpret_cast<uint4*>(p.lists + tile_at * p.tile_cap);
+            for (uint32_t v = lane; v < total / 8u; v += kWave) dst[v] = reinterpret_cast<const uint4*>(list)[v];
+        }
+
+        // the workgroup's totals
+        s_e2e = wave_sum_u64(s_e2e);
+        s_ttft = wave_sum_u64(s_ttft);
+        s_tpot = wave_sum_u64(s_tpot);
+        last_fin = wave_max_u32(last_fin);
+        n_ok = wave_sum_u32(n_ok);
+        if (lane == 0u) {
+            atomicAdd(&acc64[0], s_e2e);
+            atomicAdd(&acc64[1], s_ttft);
+            atomicAdd(&acc64[2], s_tpot);
+            atomicMax(&acc32[0], last_fin);
+            atomicAdd(&acc32[1], n_ok);
+            atomicAdd(&acc32[2], n_rej);                                            // already a wavefront total
+        }
+        __syncthreads();
+        const uint32_t rejected = acc32[2];
+        const bool lazy = rejected >= p.lazy_from;
+        if (tid == 0u) {
+            SplitPartial sp{};
+            sp.s_e2e = acc64[0];
+            sp.s_ttft = acc64[1];
+            sp.s_tpot = acc64[2];
+            sp.last_fin = acc32[0];
+            sp.n_ok = acc32[1];
+            sp.n_rej = rejected;
+            sp.flags = lazy ? kFlagLazy : (kHist ? 0u : kFlagNeedHist);
+            p.part[cb] = sp;
+        }
+        if (kHist && !lazy) {
+            uint32_t* dst = p.hist + (size_t)cb * (3u * kBins / 2u);
+            for (uint32_t i = tid; i < 3u * kBins / 2u; i += kSplitThreads) dst[i] = hist[i];
+        }
+    }
+}
+
+// The median of three: with a <= c it is min(c, max(a, b)), in one instruction.
+__device__ __forceinline__ uint32_t median3(uint32_t a, uint32_t b, uint32_t c) {
+    uint32_t r;
+    asm("v_med3_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+// List replay.  One wavefront per (replica, 64 candidates of the batch): lane l replays the listed part of
+// replica m under candidate 64 * block + l.  All lanes share the replica, hence its cost coefficients and
+// window (scalar registers) and - roughly - the pace at which they move through the trace, so the request
+// records of a tile are staged in LDS once and read by every lane.  A lane keeps its B slot-free times sorted
+// in registers (s[0] the earliest); a request starts at max(ready, s[0]), and its finish time f replaces s[0]
+// by one median per register: s'[i] = med3(s[i], f, s[i+1]), i.e. min(s[i+1], max(s[i], f)).  A lane without a
+// request in a step (or whose request is rejected) inserts 0, which leaves the registers as they are.
+// Starts do not decrease along a queue, so once a start reaches t_off every later request is rejected too.
+// kSlots: B rounded up to a power of two; registers beyond B hold kNever and stay there.
+template <uint32_t kSlots>
+__global__ __launch_bounds__(kWave) void k_replay_lists(SplitParams p, uint32_t n_cand) {
+    __shared__ uint2 recs[kTile];
+    const uint32_t lane = threadIdx.x;
+    const uint32_t n_blocks = (n_cand + kWave - 1u) / kWave;
+    const uint32_t m = p.order[blockIdx.x / n_blocks];
+    const uint32_t cb = (blockIdx.x % n_blocks) * kWave + lane;
+    const bool live = cb < n_cand;
+    SplitQueue q = p.queue[m];
+    q.a = (uint32_t)__builtin_amdgcn_readfirstlane((int)q.a);
+    q.b = (uint32_t)__builtin_amdgcn_readfirstlane((int)q.b);
+    q.c = (uint32_t)__builtin_amdgcn_readfirstlane((int)q.c);
+    q.d = (uint32_t)__builtin_amdgcn_readfirstlane((int)q.d);
+    q.t_on = (uint32_t)__builtin_amdgcn_readfirstlane((int)q.t_on);
+    q.t_off = (uint32_t)__builtin_amdgcn_readfirstlane((int)q.t_off);
+    q.i_list = (uint32_t)__builtin_amdgcn_readfirstlane((int)q.i_list);
+    const bool with_hist = live && (p.part[cb].flags & kFlagLazy) == 0u;
+    uint32_t* hist = p.hist + (size_t)(live ? cb : 0u) * (3u * kBins / 2u);
+
+    uint32_t s[kSlots];
+#pragma unroll
+    for (uint32_t i = 0; i < kSlots; ++i) s[i] = i < p.B ? 0u : kNever;
+    unsigned long long s_e2e = 0, s_ttft = 0, s_tpot = 0;
+    uint32_t last_fin = 0, n_ok = 0, n_rej = 0;
+
+    const uint32_t n_t = (q.i_list + kTile - 1u) / kTile;
+    for (uint32_t j = 0; j < n_t; ++j) {
+        const uint32_t r0 = j * kTile, n = min(kTile, p.R - r0);
+        __syncthreads();                                                            // the last tile's records were read
+        for (uint32_t i = lane; i < n; i += kWave) recs[i] = p.req8[r0 + i];
+        __syncthreads();
+        const size_t tile_at = (size_t)(live ? cb : 0u) * p.n_list_tiles + j;
+        const uint32_t d = live ? p.desc[tile_at * p.M + m] : 0u;
+        uint32_t count = d >> 16;
+        const uint32_t first = d & 0xFFFFu;
+        if ((first & 7u) != 0u || first + ((count + 7u) & ~7u) > p.tile_cap) count = 0u;   // never written that way
+        const uint4* src = reinterpret_cast<const uint4*>(p.lists + tile_at * p.tile_cap + first);
+        for (uint32_t b = 0;; ++b) {
+            const bool more = 8u * b < count;
+            if (__ballot(more) == 0ull) break;
+            uint4 e = make_uint4(0u, 0u, 0u, 0u);
+            if (more) e = src[b];
+            const uint32_t word[4] = {e.x, e.y, e.z, e.w};
+#pragma unroll
+            for (uint32_t k = 0; k < 8u; ++k) {
+                const bool active = 8u * b + k < count;
+                if (k != 0u && __ballot(active) == 0ull) break;
+                const uint32_t rl = ((k & 1u) ? word[k >> 1] >> 16 : word[k >> 1]) & (kTile - 1u);
+                const uint2 rq = recs[rl];
+                const uint32_t prompt = rq.y & 0xFFFFu, out = rq.y >> 16;
+                const uint32_t prefill = q.a + q.b * prompt;
+                const uint32_t tpot = q.c + q.d * ((prompt + 1023u) >> 10);
+                const uint32_t dec = out * tpot;
+                const uint32_t start = max(max(rq.x, q.t_on), s[0]);
+                const bool served = active && start < q.t_off;
+                const uint32_t fin = start + prefill + dec;
+                const uint32_t f = served ? fin : 0u;
+#pragma unroll
+                for (uint32_t i = 0; i + 1u < kSlots; ++i) s[i] = median3(s[i], f, s[i + 1u]);
+                s[kSlots - 1u] = max(s[kSlots - 1u], f);
+                if (served) {
+                    const uint32_t ttft = start - rq.x + prefill;
+                    const uint32_t e2e = ttft + dec;
+                    s_ttft += ttft;
+                    s_e2e += e2e;
+                    s_tpot += tpot;
+                    last_fin = max(last_fin, fin);
+                    n_ok += (ttft <= p.slo_ttft && tpot <= p.slo_tpot) ? 1u : 0u;
+                    if (with_hist) {
+                        const uint32_t bt = hist_bin_u32(ttft), bp = hist_bin_u32(tpot), be = hist_bin_u32(e2e);
+                        atomicAdd(&hist[bt >> 1], 1u << ((bt & 1u) << 4));
+                        atomicAdd(&hist[kBins / 2u + (bp >> 1)], 1u << ((bp & 1u) << 4));
+                        atomicAdd(&hist[kBins + (be >> 1)], 1u << ((be & 1u) << 4));
+                    }
+                } else if (active) {
+                    n_rej += 1u;                                                    // the replica is gone before it could start
+                }
+            }
+        }
+    }
+    if (!live) return;
+    // does the listed part leave the streamed part the room the host counted on?
+    uint32_t flag = 0u;
+    if (q.t_split != kNever) {
+        uint32_t busy = 0u;
+#pragma unroll
+        for (uint32_t i = 0; i < kSlots; ++i) busy += (i < p.B && s[i] > q.t_split) ? 1u : 0u;
+        if (busy > q.allow_busy) flag = kFlagFallback;
+    }
+    SplitPartial* sp = p.part + cb;
+    if (s_e2e) atomicAdd(&sp->s_e2e, s_e2e);
+    if (s_ttft) atomicAdd(&sp->s_ttft, s_ttft);
+    if (s_tpot) atomicAdd(&sp->s_tpot, s_tpot);
+    if (last_fin) atomicMax(&sp->last_fin, last_fin);
+    if (n_ok) atomicAdd(&sp->n_ok, n_ok);
+    if (n_rej) atomicAdd(&sp->n_rej, n_rej);
+    if (flag) atomicOr(&sp->flags, flag);
+}
+
+// Merge: one record per candidate from its partial sums.  A candidate settled by penalty is written by one
+// thread; one that the list replay handed back gets the pending mark (the general replay scores it next); the
+// others take their histograms from device memory through the usual block-wide reduction.
+__global__ __launch_bounds__(kThreads) void k_merge_candidates(EvalParams p, SplitParams sp, ap_metrics* __restrict__ out,
+                                                               uint32_t c0, uint32_t n_cand, PendingWord flags) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    __shared__ uint32_t todo[kThreads];
+    __shared__ uint32_t n_todo;
+    uint32_t* hist = reinterpret_cast<uint32_t*>(lds);
+    unsigned long long* acc64 = reinterpret_cast<unsigned long long*>(lds + p.off_misc);
+    uint32_t* acc32 = reinterpret_cast<uint32_t*>(lds + p.off_misc + 24);
+    uint32_t* wtot = reinterpret_cast<uint32_t*>(lds + p.off_misc + 64);
+    const uint32_t tid = threadIdx.x;
+    for (uint32_t base = blockIdx.x * kThreads; base < n_cand; base += gridDim.x * kThreads) {
+        if (tid == 0u) n_todo = 0u;
+        __syncthreads();
+        const uint32_t cb = base + tid;
+        if (cb < n_cand) {
+            const SplitPartial part = sp.part[cb];
+            unsigned long long* dst = reinterpret_cast<unsigned long long*>(&out[c0 + cb]);
+            if (part.flags & kFlagFallback) {
+#pragma unroll
+                for (uint32_t i = 0; i < 8u; ++i) dst[i] = ~0ull;
+                pending_raise(flags);
+            } else if (part.flags & kFlagLazy) {
+                const unsigned long long penalty = (unsigned long long)part.n_rej * p.penalty;
+                const unsigned long long edge = hist_lower_edge(p.penalty_bin);
+                ap_metrics mt;
+                mt.sum_e2e_us = part.s_e2e + penalty;
+                mt.sum_ttft_us = part.s_ttft + penalty;
+                mt.sum_tpot_us = part.s_tpot + penalty;
+                mt.makespan_us = part.last_fin;
+                mt.p99_ttft_us = edge;
+                mt.p99_tpot_us = edge;
+                mt.p99_e2e_us = edge;
+                mt.slo_ok = part.n_ok;
+                mt.n_rejected = part.n_rej;
+                out[c0 + cb] = mt;
+            } else {
+                todo[atomicAdd(&n_todo, 1u)] = cb;
+            }
+        }
+        __syncthreads();
+        const uint32_t n_here = n_todo;
+        for (uint32_t t = 0; t < n_here; ++t) {
+            const uint32_t c = todo[t];
+            const uint32_t* src = sp.hist + (size_t)c * (3u * kBins / 2u);
+            for (uint32_t i = tid; i < 3u * kBins / 2u; i += kThreads) hist[i] = src[i];
+            if (tid < 16u) reinterpret_cast<uint32_t*>(acc64)[tid] = 0u;
+            __syncthreads();
+            const SplitPartial part = sp.part[c];
+            const bool first = tid == 0u;
+            finish_candidate<true>(p, hist, acc64, acc32, wtot, first ? part.s_e2e : 0ull, first ? part.s_ttft : 0ull,
+                                   first ? part.s_tpot : 0ull, first ? part.last_fin : 0u, first ? part.n_ok : 0u,
+                                   first ? part.n_rej : 0u, &out[c0 + c]);
+            __syncthreads();
+        }
+        __syncthreads();
+    }
+}
+
+}  // namespace
+
+#endif  // AP_SPLIT_HPP
