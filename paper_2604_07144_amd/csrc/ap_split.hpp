@@ -111,6 +111,11 @@ __global__ __launch_bounds__(kSplitThreads) void k_split_candidates(SplitParams 
     uint16_t* list = reinterpret_cast<uint16_t*>(mine + p.w_list);           // [tile_cap]
     const uint32_t R = p.R, M = p.M;
 
+    if (only_flagged) {                                                             // usually nothing is: leave at once
+        bool any = false;
+        for (uint32_t cb = blockIdx.x; cb < n_cand; cb += gridDim.x) any = any || (p.part[cb].flags & kFlagNeedHist) != 0u;
+        if (!any) return;                                                           // the same words for every thread
+    }
     for (uint32_t i = tid; i < (M + 1u) * 8u; i += kSplitThreads)
         reinterpret_cast<uint32_t*>(table)[i] = reinterpret_cast<const uint32_t*>(p.rep)[i];
     for (uint32_t m = lane; m < M; m += kWave) cnt[m] = 0u;
@@ -126,45 +131,69 @@ __global__ __launch_bounds__(kSplitThreads) void k_split_candidates(SplitParams 
         unsigned long long s_e2e = 0, s_ttft = 0, s_tpot = 0;
         uint32_t last_fin = 0, n_ok = 0, n_rej = 0;
 
+        // A wavefront's tiles: the replica ids of its next tile are requested before the current one is worked on,
+        // and the request records of half a tile before that half, so that no group waits for memory by itself.
+        constexpr uint32_t kGroups = kTile / kWave, kHalf = kGroups / 2u;
+        uint32_t key[kGroups], key_next[kGroups];
+        auto fetch_keys = [&](uint32_t (&into)[kGroups], uint32_t j) {
+            const uint32_t r0 = j * kTile, n = j < p.n_tiles ? min(kTile, R - r0) : 0u;
+#pragma unroll
+            for (uint32_t g = 0; g < kGroups; ++g) {
+                const uint32_t rl = g * kWave + lane;
+                into[g] = rl < n ? (uint32_t)__builtin_nontemporal_load(row + r0 + rl) : kNoKey;
+            }
+        };
+        fetch_keys(key_next, w);
         for (uint32_t j = w; j < p.n_tiles; j += kSplitWaves) {
-            const uint32_t r0 = j * kTile, n = min(kTile, R - r0);
+            const uint32_t r0 = j * kTile;
             const bool grouping = j < p.n_list_tiles;                               // beyond: nothing can be listed
             uint32_t q_n = 0;                                                       // queued so far (the same in every lane)
-            for (uint32_t g0 = 0; g0 < n; g0 += kWave) {
-                const uint32_t rl = g0 + lane, r = r0 + rl;
-                const bool in = rl < n;
-                const uint32_t k = in ? min((uint32_t)__builtin_nontemporal_load(row + r), M) : M;
-                const uint2 range = *reinterpret_cast<const uint2*>(&table[k].i_list);
-                const bool listed = in && r < range.x;                              // i_list <= i_off
-                const bool rejected = in && r >= range.y;
-                n_rej += (uint32_t)__popcll(__ballot(rejected));
-                if (in && !listed && !rejected) {
-                    // starts on arrival: ttft = prefill
-                    const uint2 rq = p.req8[r];
-                    const uint4 co = *reinterpret_cast<const uint4*>(&table[k]);
-                    const uint32_t prompt = rq.y & 0xFFFFu, out = rq.y >> 16;
-                    const uint32_t prefill = co.x + co.y * prompt;
-                    const uint32_t tpot = co.z + co.w * ((prompt + 1023u) >> 10);
-                    const uint32_t e2e = prefill + out * tpot;
-                    s_ttft += prefill;
-                    s_e2e += e2e;
-                    s_tpot += tpot;
-                    last_fin = max(last_fin, rq.x + e2e);
-                    n_ok += (prefill <= p.slo_ttft && tpot <= p.slo_tpot) ? 1u : 0u;
-                    if (kHist) {
-                        hist_add<true>(hist, 0u, hist_bin_u32(prefill), 1u);
-                        hist_add<true>(hist, 1u, hist_bin_u32(tpot), 1u);
-                        hist_add<true>(hist, 2u, hist_bin_u32(e2e), 1u);
+#pragma unroll
+            for (uint32_t g = 0; g < kGroups; ++g) key[g] = key_next[g];
+            fetch_keys(key_next, j + kSplitWaves);
+#pragma unroll
+            for (uint32_t h = 0; h < 2u; ++h) {
+                uint2 record[kHalf];
+#pragma unroll
+                for (uint32_t g = 0; g < kHalf; ++g)
+                    record[g] = key[h * kHalf + g] != kNoKey ? p.req8[r0 + (h * kHalf + g) * kWave + lane] : make_uint2(0u, 0u);
+#pragma unroll
+                for (uint32_t g = 0; g < kHalf; ++g) {
+                    const uint32_t rl = (h * kHalf + g) * kWave + lane, r = r0 + rl;
+                    const bool in = key[h * kHalf + g] != kNoKey;
+                    const uint32_t k = min(key[h * kHalf + g], M);
+                    const uint2 range = *reinterpret_cast<const uint2*>(&table[k].i_list);
+                    const bool listed = in && r < range.x;                          // i_list <= i_off
+                    const bool rejected = in && r >= range.y;
+                    n_rej += (uint32_t)__popcll(__ballot(rejected));
+                    if (in && !listed && !rejected) {
+                        // starts on arrival: ttft = prefill
+                        const uint2 rq = record[g];
+                        const uint4 co = *reinterpret_cast<const uint4*>(&table[k]);
+                        const uint32_t prompt = rq.y & 0xFFFFu, out = rq.y >> 16;
+                        const uint32_t prefill = co.x + co.y * prompt;
+                        const uint32_t tpot = co.z + co.w * ((prompt + 1023u) >> 10);
+                        const uint32_t e2e = prefill + out * tpot;
+                        s_ttft += prefill;
+                        s_e2e += e2e;
+                        s_tpot += tpot;
+                        last_fin = max(last_fin, rq.x + e2e);
+                        n_ok += (prefill <= p.slo_ttft && tpot <= p.slo_tpot) ? 1u : 0u;
+                        if (kHist) {
+                            hist_add<true>(hist, 0u, hist_bin_u32(prefill), 1u);
+                            hist_add<true>(hist, 1u, hist_bin_u32(tpot), 1u);
+                            hist_add<true>(hist, 2u, hist_bin_u32(e2e), 1u);
+                        }
                     }
-                }
-                const unsigned long long lm = __ballot(listed);
-                if (lm != 0ull) {
-                    if (listed) {
-                        atomicAdd(&cnt[k], 1u);
-                        const uint32_t before = __builtin_amdgcn_mbcnt_hi((uint32_t)(lm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)lm, 0u));
-                        queue[q_n + before] = rl | (k << 16);
+                    const unsigned long long lm = __ballot(listed);
+                    if (lm != 0ull) {
+                        if (listed) {
+                            atomicAdd(&cnt[k], 1u);
+                            const uint32_t before = __builtin_amdgcn_mbcnt_hi((uint32_t)(lm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)lm, 0u));
+                            queue[q_n + before] = rl | (k << 16);
+                        }
+                        q_n += (uint32_t)__popcll(lm);
                     }
-                    q_n += (uint32_t)__popcll(lm);
                 }
             }
             if (!grouping) continue;                                                // q_n is 0 there
