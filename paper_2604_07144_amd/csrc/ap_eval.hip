@@ -131,7 +131,7 @@ struct ap_workload {
     ChildParams child_params{};
     // split evaluation (replicas that differ or have windows): listed part replayed, streamed part scored on arrival
     uint2* d_req8 = nullptr;          // [R] {arrival, prompt | out << 16}; only when every length is below 65536
-    SplitReplica* d_split_rep = nullptr;   // [AP_MAX_REPLICAS + 1]
+    uint32_t* d_split_tab = nullptr;       // range and kind words [2][AP_MAX_REPLICAS + 1], then the coefficients of every kind
     SplitQueue* d_split_queue = nullptr;   // [AP_MAX_REPLICAS]
     uint32_t* d_split_order = nullptr;     // [AP_MAX_REPLICAS]
     unsigned char* d_split_scratch = nullptr;
@@ -347,13 +347,23 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
                             uint64_t latest_finish_bound) {
     const uint32_t R = w->R, M = w->params.M, B = w->params.B;
     if (!w->d_req8 || R >= 65536u) return AP_OK;            // 16-bit lengths and 16-bit histogram counts only
+    // The kernels multiply with 24-bit factors and add up a tile's sixteen latencies per lane in 32 bits.
+    uint64_t longest_tpot = 0, longest_prefill = 0;
+    for (uint32_t m = 0; m < M; ++m) {
+        if (replicas[m].prefill_per_tok_us >= (1u << 24) || replicas[m].decode_per_kctx_us >= (1u << 24)) return AP_OK;
+        longest_tpot = std::max<uint64_t>(longest_tpot, (uint64_t)replicas[m].decode_base_us + 64ull * replicas[m].decode_per_kctx_us);
+        longest_prefill = std::max<uint64_t>(longest_prefill, (uint64_t)replicas[m].prefill_base_us + 65535ull * replicas[m].prefill_per_tok_us);
+    }
+    if (longest_tpot >= (1u << 24)) return AP_OK;
+    for (uint32_t r = 0; r < R; ++r)
+        if (worst_service[r] >= (1u << 28)) return AP_OK;
     std::vector<uint32_t> depth_from;                        // depth_from[i] = max over r >= i of D(r); [R] = 0
-    std::vector<SplitReplica> rep;
+    std::vector<uint32_t> tab;                               // range words, kind words, coefficients
     std::vector<SplitQueue> queue;
     std::vector<uint32_t> order;
     try {
         depth_from.assign((size_t)R + 1u, 0u);
-        rep.resize(M + 1u);
+        tab.assign(2u * (AP_MAX_REPLICAS + 1u) + 4u * kinds.size(), 0u);
         queue.resize(M);
         // D(r): sweep in arrival order over a min-heap of the finish times of requests that start on arrival
         std::vector<uint64_t> heap;
@@ -404,7 +414,8 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
             i_list = (uint32_t)(std::lower_bound(arr, arr + R, (uint32_t)std::min<uint64_t>(t_target, kNever)) - arr);
         }
         i_list = std::min(std::max(i_list, i_calm), i_off);
-        rep[m] = SplitReplica{d.a, d.b, d.c, d.d, i_list, i_off, 0u, 0u};
+        tab[m] = i_list | (i_off << 16);
+        tab[AP_MAX_REPLICAS + 1u + m] = (uint32_t)ki;
         SplitQueue q{};
         q.a = d.a; q.b = d.b; q.c = d.c; q.d = d.d; q.t_on = d.t_on; q.t_off = d.t_off;
         q.i_list = i_list;
@@ -414,7 +425,12 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
         longest_list = std::max(longest_list, i_list);
         expect_rejected += R - i_off;
     }
-    rep[M] = SplitReplica{0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};  // unknown replica ids: rejected on arrival
+    tab[M] = 0u;                                             // unknown replica ids: rejected on arrival
+    for (size_t k = 0; k < kinds.size(); ++k) {
+        uint32_t* co = &tab[2u * (AP_MAX_REPLICAS + 1u) + 4u * k];
+        co[0] = replicas[kinds[k]].prefill_base_us; co[1] = replicas[kinds[k]].prefill_per_tok_us;
+        co[2] = replicas[kinds[k]].decode_base_us;  co[3] = replicas[kinds[k]].decode_per_kctx_us;
+    }
     for (uint32_t m = 0; m < M; ++m)
         if (queue[m].i_list > 0u) order.push_back(m);
     std::stable_sort(order.begin(), order.end(), [&](uint32_t x, uint32_t y) { return queue[x].i_list > queue[y].i_list; });
@@ -431,17 +447,21 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
     // reach the penalty's bin: all of them lie below the bound on finish times of the range proof.
     const bool penalty_on_top = w->params.penalty_bin > ap_hist_bin(latest_finish_bound);
     sp.lazy_from = penalty_on_top ? R - w->params.k99 + 1u : kNever;
+    sp.all_within = (longest_prefill <= w->params.slo_ttft && longest_tpot <= w->params.slo_tpot) ? 1u : 0u;
     // LDS of the streaming kernel
     uint32_t off = 0;
     const uint32_t hist_bytes = 3u * kBins * 2u;
-    sp.off_table = off; off += align_up((M + 1u) * (uint32_t)sizeof(SplitReplica), 16u);
+    sp.off_range = off; off += align_up((M + 1u) * 4u, 16u);
+    sp.off_kind = off;  off += align_up((M + 1u) * 4u, 16u);
+    sp.off_coef = off;  off += (uint32_t)kinds.size() * 16u;
     sp.off_acc = off;   off += 64u;
     sp.off_wave = off;
     uint32_t wb = 0;
     wb += align_up(M * 4u, 16u);            sp.w_pos = wb;
     wb += align_up(M * 4u, 16u);            sp.w_queue = wb;
     wb += kTile * 4u;                       sp.w_list = wb;
-    wb += align_up(sp.tile_cap * 2u, 16u);
+    wb += align_up(sp.tile_cap * 2u, 16u);  sp.w_same = wb;
+    wb += M * 8u;
     sp.wave_bytes = wb;
     off += kSplitWaves * wb;
     sp.off_hist = off;
@@ -471,13 +491,14 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
         }
         w->split_scratch_bytes = total;
     }
-    if ((!w->d_split_rep && hipMalloc(&w->d_split_rep, sizeof(SplitReplica) * (AP_MAX_REPLICAS + 1u)) != hipSuccess) ||
+    const size_t tab_bytes = 4u * (2u * (AP_MAX_REPLICAS + 1u) + 4u * (size_t)AP_MAX_REPLICAS);
+    if ((!w->d_split_tab && hipMalloc(&w->d_split_tab, tab_bytes) != hipSuccess) ||
         (!w->d_split_queue && hipMalloc(&w->d_split_queue, sizeof(SplitQueue) * AP_MAX_REPLICAS) != hipSuccess) ||
         (!w->d_split_order && hipMalloc(&w->d_split_order, sizeof(uint32_t) * AP_MAX_REPLICAS) != hipSuccess)) {
         (void)hipGetLastError();
         return AP_ERR_ALLOC;
     }
-    if (hipMemcpy(w->d_split_rep, rep.data(), sizeof(SplitReplica) * (M + 1u), hipMemcpyHostToDevice) != hipSuccess ||
+    if (hipMemcpy(w->d_split_tab, tab.data(), 4u * tab.size(), hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(w->d_split_queue, queue.data(), sizeof(SplitQueue) * M, hipMemcpyHostToDevice) != hipSuccess ||
         (!order.empty() &&
          hipMemcpy(w->d_split_order, order.data(), sizeof(uint32_t) * order.size(), hipMemcpyHostToDevice) != hipSuccess) ||
@@ -487,7 +508,10 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
         return AP_ERR_DEVICE;
     }
     sp.req8 = w->d_req8;
-    sp.rep = w->d_split_rep;
+    sp.tab.range = w->d_split_tab;
+    sp.tab.kind = w->d_split_tab + (AP_MAX_REPLICAS + 1u);
+    sp.tab.coef = reinterpret_cast<const uint4*>(w->d_split_tab + 2u * (AP_MAX_REPLICAS + 1u));
+    sp.tab.n_kinds = (uint32_t)kinds.size();
     sp.queue = w->d_split_queue;
     sp.order = w->d_split_order;
     sp.lists = reinterpret_cast<uint16_t*>(w->d_split_scratch + o_lists);
@@ -1320,7 +1344,7 @@ ap_status ap_workload_destroy(ap_workload* w) {
     if (w->d_room) ok = (hipFree(w->d_room) == hipSuccess) && ok;
     if (w->d_rows) ok = (hipFree(w->d_rows) == hipSuccess) && ok;
     if (w->d_req8) ok = (hipFree(w->d_req8) == hipSuccess) && ok;
-    if (w->d_split_rep) ok = (hipFree(w->d_split_rep) == hipSuccess) && ok;
+    if (w->d_split_tab) ok = (hipFree(w->d_split_tab) == hipSuccess) && ok;
     if (w->d_split_queue) ok = (hipFree(w->d_split_queue) == hipSuccess) && ok;
     if (w->d_split_order) ok = (hipFree(w->d_split_order) == hipSuccess) && ok;
     if (w->d_split_scratch) ok = (hipFree(w->d_split_scratch) == hipSuccess) && ok;

@@ -48,10 +48,15 @@ constexpr uint32_t kFlagNeedHist = 1u;            // streamed without histograms
 constexpr uint32_t kFlagFallback = 2u;            // the listed part left too many slots taken: general replay
 constexpr uint32_t kFlagLazy = 4u;                // the p99 values are the penalty latency
 
-struct SplitReplica {                             // per replica, for the streaming kernel (LDS copy), 32 bytes
-    uint32_t a, b, c, d;                          // cost coefficients
-    uint32_t i_list, i_off;
-    uint32_t pad0, pad1;
+// Per replica, for the streaming kernel, as three arrays (copied to LDS; an entry per replica and one more, index
+// M, for unknown replica ids: everything rejected).  Lanes look entries up by replica id, so consecutive ids must
+// fall into different LDS banks: one 32-bit word per replica holds both ranges (R is below 65536 on this path),
+// and the cost coefficients are stored once per kind of replica, which a second word names.
+struct SplitTables {
+    const uint32_t* range;                        // [M + 1] i_list | i_off << 16
+    const uint32_t* kind;                         // [M + 1] index into coef
+    const uint4* coef;                            // [n_kinds] a, b, c, d
+    uint32_t n_kinds;
 };
 
 struct SplitQueue {                               // per replica, for the list replay, 48 bytes
@@ -70,7 +75,7 @@ struct SplitPartial {                             // per candidate of a batch, 6
 
 struct SplitParams {
     const uint2* req8;                            // [R] {arrival, prompt | out << 16}
-    const SplitReplica* rep;                      // [M + 1]; entry M takes unknown replica ids: everything rejected
+    SplitTables tab;
     const SplitQueue* queue;                      // [M]
     const uint32_t* order;                        // [n_queues] replicas with a listed part, longest first
     uint32_t* desc;                               // [batch][n_list_tiles][M] count << 16 | first list position
@@ -81,8 +86,9 @@ struct SplitParams {
     uint32_t n_tiles, n_list_tiles, tile_cap, n_queues;
     uint32_t slo_ttft, slo_tpot;
     uint32_t lazy_from;                           // rejected requests from which the p99 values are the penalty; kNever: never
+    uint32_t all_within;                          // no request's prefill or time per token can exceed the objectives
     // byte offsets into the streaming kernel's dynamic LDS
-    uint32_t off_table, off_acc, off_wave, wave_bytes, w_pos, w_queue, w_list, off_hist;
+    uint32_t off_range, off_kind, off_coef, off_acc, off_wave, wave_bytes, w_pos, w_queue, w_list, w_same, off_hist;
 };
 
 // Streaming kernel.  One workgroup per candidate at a time; its wavefronts take the tiles of the row in turn
@@ -100,7 +106,9 @@ __global__ __launch_bounds__(kSplitThreads) void k_split_candidates(SplitParams 
     extern __shared__ __align__(16) unsigned char lds[];
     pending_clear_next(flags);
     uint32_t* hist = reinterpret_cast<uint32_t*>(lds + p.off_hist);          // kHist only
-    SplitReplica* table = reinterpret_cast<SplitReplica*>(lds + p.off_table);
+    uint32_t* range_of = reinterpret_cast<uint32_t*>(lds + p.off_range);
+    uint32_t* kind_of = reinterpret_cast<uint32_t*>(lds + p.off_kind);
+    uint4* coef_of = reinterpret_cast<uint4*>(lds + p.off_coef);
     unsigned long long* acc64 = reinterpret_cast<unsigned long long*>(lds + p.off_acc);
     uint32_t* acc32 = reinterpret_cast<uint32_t*>(lds + p.off_acc + 24);    // latest finish, within objectives, rejected
     const uint32_t tid = threadIdx.x, lane = tid & 63u, w = wave_index();
@@ -109,6 +117,7 @@ __global__ __launch_bounds__(kSplitThreads) void k_split_candidates(SplitParams 
     uint32_t* pos = reinterpret_cast<uint32_t*>(mine + p.w_pos);             // [M] next free position of the replica's run
     uint32_t* queue = reinterpret_cast<uint32_t*>(mine + p.w_queue);         // [kTile] tile index | replica << 16, arrival order
     uint16_t* list = reinterpret_cast<uint16_t*>(mine + p.w_list);           // [tile_cap]
+    unsigned long long* same = reinterpret_cast<unsigned long long*>(mine + p.w_same);   // [M] lanes naming the replica
     const uint32_t R = p.R, M = p.M;
 
     if (only_flagged) {                                                             // usually nothing is: leave at once
@@ -116,9 +125,15 @@ __global__ __launch_bounds__(kSplitThreads) void k_split_candidates(SplitParams 
         for (uint32_t cb = blockIdx.x; cb < n_cand; cb += gridDim.x) any = any || (p.part[cb].flags & kFlagNeedHist) != 0u;
         if (!any) return;                                                           // the same words for every thread
     }
-    for (uint32_t i = tid; i < (M + 1u) * 8u; i += kSplitThreads)
-        reinterpret_cast<uint32_t*>(table)[i] = reinterpret_cast<const uint32_t*>(p.rep)[i];
-    for (uint32_t m = lane; m < M; m += kWave) cnt[m] = 0u;
+    for (uint32_t i = tid; i <= M; i += kSplitThreads) {
+        range_of[i] = p.tab.range[i];
+        kind_of[i] = p.tab.kind[i];
+    }
+    for (uint32_t i = tid; i < p.tab.n_kinds; i += kSplitThreads) coef_of[i] = p.tab.coef[i];
+    for (uint32_t m = lane; m < M; m += kWave) {
+        cnt[m] = 0u;
+        same[m] = 0ull;
+    }
 
     for (uint32_t cb = blockIdx.x; cb < n_cand; cb += gridDim.x) {
         if (only_flagged && (p.part[cb].flags & kFlagNeedHist) == 0u) continue;     // the same word for every thread
@@ -136,49 +151,58 @@ __global__ __launch_bounds__(kSplitThreads) void k_split_candidates(SplitParams 
         constexpr uint32_t kGroups = kTile / kWave, kHalf = kGroups / 2u;
         uint32_t key[kGroups], key_next[kGroups];
         auto fetch_keys = [&](uint32_t (&into)[kGroups], uint32_t j) {
-            const uint32_t r0 = j * kTile, n = j < p.n_tiles ? min(kTile, R - r0) : 0u;
+            const uint32_t r0 = j * kTile;
+            if (r0 + kTile <= R) {                                                  // a whole tile: no guards
 #pragma unroll
-            for (uint32_t g = 0; g < kGroups; ++g) {
-                const uint32_t rl = g * kWave + lane;
-                into[g] = rl < n ? (uint32_t)__builtin_nontemporal_load(row + r0 + rl) : kNoKey;
+                for (uint32_t g = 0; g < kGroups; ++g) into[g] = (uint32_t)__builtin_nontemporal_load(row + r0 + g * kWave + lane);
+            } else {
+                const uint32_t n = r0 < R ? R - r0 : 0u;
+#pragma unroll
+                for (uint32_t g = 0; g < kGroups; ++g) {
+                    const uint32_t rl = g * kWave + lane;
+                    into[g] = rl < n ? (uint32_t)__builtin_nontemporal_load(row + r0 + rl) : kNoKey;
+                }
             }
         };
-        fetch_keys(key_next, w);
-        for (uint32_t j = w; j < p.n_tiles; j += kSplitWaves) {
+        // one tile; kWhole: all of its 1024 requests exist
+        auto work_tile = [&](auto whole_tag, uint32_t j) {
+            constexpr bool kWhole = decltype(whole_tag)::value;
             const uint32_t r0 = j * kTile;
             const bool grouping = j < p.n_list_tiles;                               // beyond: nothing can be listed
             uint32_t q_n = 0;                                                       // queued so far (the same in every lane)
-#pragma unroll
-            for (uint32_t g = 0; g < kGroups; ++g) key[g] = key_next[g];
-            fetch_keys(key_next, j + kSplitWaves);
+            uint32_t t_e2e = 0, t_ttft = 0, t_tpot = 0;                             // the tile's sums: 16 values below 2^28 each
 #pragma unroll
             for (uint32_t h = 0; h < 2u; ++h) {
                 uint2 record[kHalf];
 #pragma unroll
-                for (uint32_t g = 0; g < kHalf; ++g)
-                    record[g] = key[h * kHalf + g] != kNoKey ? p.req8[r0 + (h * kHalf + g) * kWave + lane] : make_uint2(0u, 0u);
+                for (uint32_t g = 0; g < kHalf; ++g) {
+                    const uint32_t at = r0 + (h * kHalf + g) * kWave + lane;
+                    record[g] = (kWhole || key[h * kHalf + g] != kNoKey) ? p.req8[at] : make_uint2(0u, 0u);
+                }
 #pragma unroll
                 for (uint32_t g = 0; g < kHalf; ++g) {
                     const uint32_t rl = (h * kHalf + g) * kWave + lane, r = r0 + rl;
-                    const bool in = key[h * kHalf + g] != kNoKey;
+                    const bool in = kWhole || key[h * kHalf + g] != kNoKey;
                     const uint32_t k = min(key[h * kHalf + g], M);
-                    const uint2 range = *reinterpret_cast<const uint2*>(&table[k].i_list);
-                    const bool listed = in && r < range.x;                          // i_list <= i_off
-                    const bool rejected = in && r >= range.y;
+                    const uint32_t range = range_of[k];
+                    const bool listed = in && r < (range & 0xFFFFu);                // i_list <= i_off
+                    const bool rejected = in && r >= (range >> 16);
+                    const bool streamed = in && !listed && !rejected;
                     n_rej += (uint32_t)__popcll(__ballot(rejected));
-                    if (in && !listed && !rejected) {
+                    if (p.all_within != 0u) n_ok += (uint32_t)__popcll(__ballot(streamed));   // kept as a wavefront total then
+                    if (streamed) {
                         // starts on arrival: ttft = prefill
                         const uint2 rq = record[g];
-                        const uint4 co = *reinterpret_cast<const uint4*>(&table[k]);
+                        const uint4 co = coef_of[kind_of[k]];
                         const uint32_t prompt = rq.y & 0xFFFFu, out = rq.y >> 16;
-                        const uint32_t prefill = co.x + co.y * prompt;
-                        const uint32_t tpot = co.z + co.w * ((prompt + 1023u) >> 10);
-                        const uint32_t e2e = prefill + out * tpot;
-                        s_ttft += prefill;
-                        s_e2e += e2e;
-                        s_tpot += tpot;
+                        const uint32_t prefill = co.x + __umul24(co.y, prompt);    // the host keeps all factors below 2^24
+                        const uint32_t tpot = co.z + __umul24(co.w, (prompt + 1023u) >> 10);
+                        const uint32_t e2e = prefill + __umul24(out, tpot);
+                        t_ttft += prefill;
+                        t_e2e += e2e;
+                        t_tpot += tpot;
                         last_fin = max(last_fin, rq.x + e2e);
-                        n_ok += (prefill <= p.slo_ttft && tpot <= p.slo_tpot) ? 1u : 0u;
+                        if (p.all_within == 0u) n_ok += (prefill <= p.slo_ttft && tpot <= p.slo_tpot) ? 1u : 0u;
                         if (kHist) {
                             hist_add<true>(hist, 0u, hist_bin_u32(prefill), 1u);
                             hist_add<true>(hist, 1u, hist_bin_u32(tpot), 1u);
@@ -196,7 +220,10 @@ __global__ __launch_bounds__(kSplitThreads) void k_split_candidates(SplitParams 
                     }
                 }
             }
-            if (!grouping) continue;                                                // q_n is 0 there
+            s_ttft += t_ttft;
+            s_e2e += t_e2e;
+            s_tpot += t_tpot;
+            if (!grouping) return;                                                  // q_n is 0 there
             // runs: every replica's listed requests of the tile, starting on a multiple of 8 positions
             const size_t tile_at = (size_t)cb * p.n_list_tiles + j;
             uint32_t total = 0;
@@ -212,23 +239,37 @@ __global__ __launch_bounds__(kSplitThreads) void k_split_candidates(SplitParams 
                 }
                 total += (uint32_t)__builtin_amdgcn_readlane((int)upto, 63);
             }
+            // Rank among the queued requests of one replica, 64 queued requests at a time: every lane sets its bit
+            // in its replica's word and reads the word back (the LDS executes a wavefront's instructions in order),
+            // which tells it how many lanes before it name the same replica; the last of them moves the run's
+            // position on and clears the word.
             for (uint32_t d0 = 0; d0 < q_n; d0 += kWave) {
-                const bool valid = d0 + lane < q_n;
-                const uint32_t pair = valid ? queue[d0 + lane] : 0u;
-                const uint32_t k = valid ? pair >> 16 : kNoKey;
-                uint32_t peers_lo, peers_hi;
-                wave_peers(k, M, p.key_bits, peers_lo, peers_hi);
-                if (valid) {
-                    const uint32_t rank = __builtin_amdgcn_mbcnt_hi(peers_hi, __builtin_amdgcn_mbcnt_lo(peers_lo, 0u));
-                    const uint32_t n_peers = __popc(peers_lo) + __popc(peers_hi);
+                if (d0 + lane < q_n) {
+                    const uint32_t pair = queue[d0 + lane];
+                    const uint32_t k = pair >> 16;
+                    atomicOr(&same[k], 1ull << lane);
+                    const unsigned long long peers = same[k];
+                    const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(peers >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)peers, 0u));
+                    const uint32_t n_peers = (uint32_t)__popcll(peers);
                     const uint32_t at = pos[k];
                     list[at + rank] = (uint16_t)(pair & 0xFFFFu);
-                    if (rank + 1u == n_peers) pos[k] = at + n_peers;
+                    if (rank + 1u == n_peers) {
+                        pos[k] = at + n_peers;
+                        same[k] = 0ull;
+                    }
                 }
             }
             // 16 bytes (8 positions) at a time; the padding of a run holds whatever the LDS held
             uint4* dst = reinterpret_cast<uint4*>(p.lists + tile_at * p.tile_cap);
             for (uint32_t v = lane; v < total / 8u; v += kWave) dst[v] = reinterpret_cast<const uint4*>(list)[v];
+        };
+        fetch_keys(key_next, w);
+        for (uint32_t j = w; j < p.n_tiles; j += kSplitWaves) {
+#pragma unroll
+            for (uint32_t g = 0; g < kGroups; ++g) key[g] = key_next[g];
+            fetch_keys(key_next, j + kSplitWaves);
+            if ((j + 1u) * kTile <= R) work_tile(std::true_type{}, j);
+            else work_tile(std::false_type{}, j);
         }
 
         // the workgroup's totals
@@ -236,7 +277,7 @@ __global__ __launch_bounds__(kSplitThreads) void k_split_candidates(SplitParams 
         s_ttft = wave_sum_u64(s_ttft);
         s_tpot = wave_sum_u64(s_tpot);
         last_fin = wave_max_u32(last_fin);
-        n_ok = wave_sum_u32(n_ok);
+        if (p.all_within == 0u) n_ok = wave_sum_u32(n_ok);                          // else counted per wavefront already
         if (lane == 0u) {
             atomicAdd(&acc64[0], s_e2e);
             atomicAdd(&acc64[1], s_ttft);
@@ -332,9 +373,9 @@ __global__ __launch_bounds__(kWave) void k_replay_lists(SplitParams p, uint32_t 
                 const uint32_t rl = ((k & 1u) ? word[k >> 1] >> 16 : word[k >> 1]) & (kTile - 1u);
                 const uint2 rq = recs[rl];
                 const uint32_t prompt = rq.y & 0xFFFFu, out = rq.y >> 16;
-                const uint32_t prefill = q.a + q.b * prompt;
-                const uint32_t tpot = q.c + q.d * ((prompt + 1023u) >> 10);
-                const uint32_t dec = out * tpot;
+                const uint32_t prefill = q.a + __umul24(q.b, prompt);               // the host keeps all factors below 2^24
+                const uint32_t tpot = q.c + __umul24(q.d, (prompt + 1023u) >> 10);
+                const uint32_t dec = __umul24(out, tpot);
                 const uint32_t start = max(max(rq.x, q.t_on), s[0]);
                 const bool served = active && start < q.t_off;
                 const uint32_t fin = start + prefill + dec;
