@@ -191,11 +191,15 @@ static ap_status launch_dense(const ap_workload* w, const uint16_t* d_assign, ui
         for (uint32_t c0 = 0; c0 < C; c0 += w->split_batch) {
             const uint32_t n = std::min(w->split_batch, C - c0);
             const uint32_t grid = std::min(n, w->n_cu * 16u);
+            typedef void (*split_fn)(SplitParams, const uint16_t*, uint32_t, uint32_t, uint32_t, PendingWord);
+            static const split_fn split[4] = {k_split_candidates<false, false>, k_split_candidates<true, false>,
+                                              k_split_candidates<false, true>, k_split_candidates<true, true>};
+            const int narrow = sp.M <= 64u ? 2 : 0;
             if (w->split_expect_lazy)
-                hipLaunchKernelGGL(k_split_candidates<false>, dim3(grid), dim3(kSplitThreads), w->split_lds_bytes, stream, sp,
-                                   d_assign, c0, n, 0u, flags);
-            hipLaunchKernelGGL(k_split_candidates<true>, dim3(grid), dim3(kSplitThreads), w->split_lds_bytes_hist, stream, sp,
-                               d_assign, c0, n, w->split_expect_lazy ? 1u : 0u, flags);
+                hipLaunchKernelGGL(split[narrow], dim3(grid), dim3(kSplitThreads), w->split_lds_bytes, stream, sp, d_assign, c0, n,
+                                   0u, flags);
+            hipLaunchKernelGGL(split[narrow + 1], dim3(grid), dim3(kSplitThreads), w->split_lds_bytes_hist, stream, sp, d_assign,
+                               c0, n, w->split_expect_lazy ? 1u : 0u, flags);
             if (sp.n_queues != 0u)
                 hipLaunchKernelGGL(replay, dim3(sp.n_queues * ((n + kWave - 1u) / kWave)), dim3(kWave), 0, stream, sp, n);
             hipLaunchKernelGGL(k_merge_candidates, dim3(std::min((n + kThreads - 1u) / kThreads, w->n_cu * 4u)), dim3(kThreads),
@@ -314,14 +318,14 @@ ap_status ap_workload_create(const uint64_t* arrival_us, const int32_t* prompt_l
         // arrival and both lengths of a request in 8 bytes, for the kernels that read whole records
         std::vector<uint2> packed;
         try {
-            packed.resize(R);
+            packed.assign((size_t)R + 1u, make_uint2(0u, 0u));       // one spare record: pairs of records are read at once
         } catch (const std::bad_alloc&) {
             st = AP_ERR_ALLOC;
         }
         if (st == AP_OK) {
             for (uint32_t r = 0; r < R; ++r) packed[r] = make_uint2(rel[r], (uint32_t)prompt_len[r] | ((uint32_t)out_len[r] << 16));
-            if (hipMalloc(&w->d_req8, sizeof(uint2) * (size_t)R) != hipSuccess) st = AP_ERR_ALLOC;
-            else if (hipMemcpy(w->d_req8, packed.data(), sizeof(uint2) * (size_t)R, hipMemcpyHostToDevice) != hipSuccess)
+            if (hipMalloc(&w->d_req8, sizeof(uint2) * ((size_t)R + 1u)) != hipSuccess) st = AP_ERR_ALLOC;
+            else if (hipMemcpy(w->d_req8, packed.data(), sizeof(uint2) * ((size_t)R + 1u), hipMemcpyHostToDevice) != hipSuccess)
                 st = AP_ERR_DEVICE;
         }
     }
@@ -459,7 +463,7 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
     uint32_t wb = 0;
     wb += align_up(M * 4u, 16u);            sp.w_pos = wb;
     wb += align_up(M * 4u, 16u);            sp.w_queue = wb;
-    wb += kTile * 4u;                       sp.w_list = wb;
+    wb += kTile * (M <= 64u ? 2u : 4u);     sp.w_list = wb;
     wb += align_up(sp.tile_cap * 2u, 16u);  sp.w_same = wb;
     wb += M * 8u;
     sp.wave_bytes = wb;

@@ -99,8 +99,9 @@ struct SplitParams {
 // and their descriptors out.
 // kHist: keep histograms of the streamed requests (needed unless the candidate is settled by penalty).
 // only_flagged: look only at candidates that an earlier launch marked kFlagNeedHist.
-template <bool kHist>
-__global__ __launch_bounds__(kSplitThreads) void k_split_candidates(SplitParams p, const uint16_t* __restrict__ assign,
+// kNarrow: at most 64 replicas, so a queued request (tile index and replica) fits 16 bits, which halves the queue.
+template <bool kHist, bool kNarrow>
+__global__ __launch_bounds__(kSplitThreads, 5) void k_split_candidates(SplitParams p, const uint16_t* __restrict__ assign,
                                                                     uint32_t c0, uint32_t n_cand, uint32_t only_flagged,
                                                                     PendingWord flags) {
     extern __shared__ __align__(16) unsigned char lds[];
@@ -115,7 +116,9 @@ __global__ __launch_bounds__(kSplitThreads) void k_split_candidates(SplitParams 
     unsigned char* mine = lds + p.off_wave + w * p.wave_bytes;
     uint32_t* cnt = reinterpret_cast<uint32_t*>(mine);                       // [M] listed requests of the tile per replica
     uint32_t* pos = reinterpret_cast<uint32_t*>(mine + p.w_pos);             // [M] next free position of the replica's run
-    uint32_t* queue = reinterpret_cast<uint32_t*>(mine + p.w_queue);         // [kTile] tile index | replica << 16, arrival order
+    using queued_t = typename std::conditional<kNarrow, uint16_t, uint32_t>::type;
+    constexpr uint32_t kIdShift = kNarrow ? 10u : 16u;
+    queued_t* queue = reinterpret_cast<queued_t*>(mine + p.w_queue);         // [kTile] tile index | replica << kIdShift, arrival order
     uint16_t* list = reinterpret_cast<uint16_t*>(mine + p.w_list);           // [tile_cap]
     unsigned long long* same = reinterpret_cast<unsigned long long*>(mine + p.w_same);   // [M] lanes naming the replica
     const uint32_t R = p.R, M = p.M;
@@ -143,81 +146,103 @@ __global__ __launch_bounds__(kSplitThreads) void k_split_candidates(SplitParams 
         if (tid < 10u) reinterpret_cast<uint32_t*>(acc64)[tid] = 0u;
         __syncthreads();
         const uint16_t* row = assign + (size_t)(c0 + cb) * R;
+        const bool row_aligned = (reinterpret_cast<uintptr_t>(row) & 3u) == 0u;      // pairs of ids as one 4-byte load
         unsigned long long s_e2e = 0, s_ttft = 0, s_tpot = 0;
         uint32_t last_fin = 0, n_ok = 0, n_rej = 0;
 
-        // A wavefront's tiles: the replica ids of its next tile are requested before the current one is worked on,
-        // and the request records of half a tile before that half, so that no group waits for memory by itself.
-        constexpr uint32_t kGroups = kTile / kWave, kHalf = kGroups / 2u;
-        uint32_t key[kGroups], key_next[kGroups];
-        auto fetch_keys = [&](uint32_t (&into)[kGroups], uint32_t j) {
+        // A wavefront's tiles.  A lane holds two consecutive requests of every 128 (one 4-byte load of two replica
+        // ids, one 16-byte load of two request records).  The ids of the next tile are requested before the current
+        // one is worked on and the records of a quarter tile before that quarter; the table look-ups of a quarter are issued
+        // together, so that no request waits for memory or for the LDS by itself.
+        constexpr uint32_t kPairs = kTile / (2u * kWave), kParts = 4u, kHalf = kPairs / kParts;   // pairs per lane and tile; per part
+        uint32_t key[kPairs], key_next[kPairs];
+        auto fetch_keys = [&](uint32_t (&into)[kPairs], uint32_t j) {
             const uint32_t r0 = j * kTile;
-            if (r0 + kTile <= R) {                                                  // a whole tile: no guards
+            if (r0 + kTile <= R && row_aligned) {                                   // a whole tile: no guards
 #pragma unroll
-                for (uint32_t g = 0; g < kGroups; ++g) into[g] = (uint32_t)__builtin_nontemporal_load(row + r0 + g * kWave + lane);
+                for (uint32_t g = 0; g < kPairs; ++g)
+                    into[g] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(row + r0 + g * 2u * kWave + 2u * lane));
             } else {
-                const uint32_t n = r0 < R ? R - r0 : 0u;
+                const uint32_t n = r0 < R ? min(kTile, R - r0) : 0u;
 #pragma unroll
-                for (uint32_t g = 0; g < kGroups; ++g) {
-                    const uint32_t rl = g * kWave + lane;
-                    into[g] = rl < n ? (uint32_t)__builtin_nontemporal_load(row + r0 + rl) : kNoKey;
+                for (uint32_t g = 0; g < kPairs; ++g) {
+                    const uint32_t rl = g * 2u * kWave + 2u * lane;
+                    const uint32_t lo = rl < n ? (uint32_t)__builtin_nontemporal_load(row + r0 + rl) : 0u;
+                    const uint32_t hi = rl + 1u < n ? (uint32_t)__builtin_nontemporal_load(row + r0 + rl + 1u) : 0u;
+                    into[g] = lo | (hi << 16);
                 }
             }
         };
         // one tile; kWhole: all of its 1024 requests exist
         auto work_tile = [&](auto whole_tag, uint32_t j) {
             constexpr bool kWhole = decltype(whole_tag)::value;
-            const uint32_t r0 = j * kTile;
+            const uint32_t r0 = j * kTile, n = min(kTile, R - r0);
             const bool grouping = j < p.n_list_tiles;                               // beyond: nothing can be listed
             uint32_t q_n = 0;                                                       // queued so far (the same in every lane)
             uint32_t t_e2e = 0, t_ttft = 0, t_tpot = 0;                             // the tile's sums: 16 values below 2^28 each
 #pragma unroll
-            for (uint32_t h = 0; h < 2u; ++h) {
-                uint2 record[kHalf];
+            for (uint32_t h = 0; h < kParts; ++h) {
+                uint4 record[kHalf];
+                uint32_t id[2u * kHalf], range[2u * kHalf], kind[2u * kHalf];
 #pragma unroll
                 for (uint32_t g = 0; g < kHalf; ++g) {
-                    const uint32_t at = r0 + (h * kHalf + g) * kWave + lane;
-                    record[g] = (kWhole || key[h * kHalf + g] != kNoKey) ? p.req8[at] : make_uint2(0u, 0u);
+                    const uint32_t rl = (h * kHalf + g) * 2u * kWave + 2u * lane;
+                    record[g] = (kWhole || rl < n) ? *reinterpret_cast<const uint4*>(p.req8 + r0 + rl) : make_uint4(0u, 0u, 0u, 0u);
+                    id[2u * g] = min(key[h * kHalf + g] & 0xFFFFu, M);
+                    id[2u * g + 1u] = min(key[h * kHalf + g] >> 16, M);
+                }
+#pragma unroll
+                for (uint32_t i = 0; i < 2u * kHalf; ++i) {
+                    range[i] = range_of[id[i]];
+                    kind[i] = kind_of[id[i]];
                 }
 #pragma unroll
                 for (uint32_t g = 0; g < kHalf; ++g) {
-                    const uint32_t rl = (h * kHalf + g) * kWave + lane, r = r0 + rl;
-                    const bool in = kWhole || key[h * kHalf + g] != kNoKey;
-                    const uint32_t k = min(key[h * kHalf + g], M);
-                    const uint32_t range = range_of[k];
-                    const bool listed = in && r < (range & 0xFFFFu);                // i_list <= i_off
-                    const bool rejected = in && r >= (range >> 16);
-                    const bool streamed = in && !listed && !rejected;
-                    n_rej += (uint32_t)__popcll(__ballot(rejected));
-                    if (p.all_within != 0u) n_ok += (uint32_t)__popcll(__ballot(streamed));   // kept as a wavefront total then
-                    if (streamed) {
-                        // starts on arrival: ttft = prefill
-                        const uint2 rq = record[g];
-                        const uint4 co = coef_of[kind_of[k]];
-                        const uint32_t prompt = rq.y & 0xFFFFu, out = rq.y >> 16;
-                        const uint32_t prefill = co.x + __umul24(co.y, prompt);    // the host keeps all factors below 2^24
-                        const uint32_t tpot = co.z + __umul24(co.w, (prompt + 1023u) >> 10);
-                        const uint32_t e2e = prefill + __umul24(out, tpot);
-                        t_ttft += prefill;
-                        t_e2e += e2e;
-                        t_tpot += tpot;
-                        last_fin = max(last_fin, rq.x + e2e);
-                        if (p.all_within == 0u) n_ok += (prefill <= p.slo_ttft && tpot <= p.slo_tpot) ? 1u : 0u;
-                        if (kHist) {
-                            hist_add<true>(hist, 0u, hist_bin_u32(prefill), 1u);
-                            hist_add<true>(hist, 1u, hist_bin_u32(tpot), 1u);
-                            hist_add<true>(hist, 2u, hist_bin_u32(e2e), 1u);
+                    bool listed[2];
+#pragma unroll
+                    for (uint32_t e = 0; e < 2u; ++e) {
+                        const uint32_t i = 2u * g + e;
+                        const uint32_t rl = (h * kHalf + g) * 2u * kWave + 2u * lane + e, r = r0 + rl;
+                        const bool in = kWhole || rl < n;
+                        listed[e] = in && r < (range[i] & 0xFFFFu);                 // i_list <= i_off
+                        const bool rejected = in && r >= (range[i] >> 16);
+                        const bool streamed = in && !listed[e] && !rejected;
+                        n_rej += (uint32_t)__popcll(__ballot(rejected));
+                        if (p.all_within != 0u) n_ok += (uint32_t)__popcll(__ballot(streamed));   // a wavefront total then
+                        if (streamed) {
+                            // starts on arrival: ttft = prefill
+                            const uint32_t arrival = e ? record[g].z : record[g].x, lens = e ? record[g].w : record[g].y;
+                            const uint4 co = coef_of[kind[i]];
+                            const uint32_t prompt = lens & 0xFFFFu, out = lens >> 16;
+                            const uint32_t prefill = co.x + __umul24(co.y, prompt);    // the host keeps all factors below 2^24
+                            const uint32_t tpot = co.z + __umul24(co.w, (prompt + 1023u) >> 10);
+                            const uint32_t e2e = prefill + __umul24(out, tpot);
+                            t_ttft += prefill;
+                            t_e2e += e2e;
+                            t_tpot += tpot;
+                            last_fin = max(last_fin, arrival + e2e);
+                            if (p.all_within == 0u) n_ok += (prefill <= p.slo_ttft && tpot <= p.slo_tpot) ? 1u : 0u;
+                            if (kHist) {
+                                hist_add<true>(hist, 0u, hist_bin_u32(prefill), 1u);
+                                hist_add<true>(hist, 1u, hist_bin_u32(tpot), 1u);
+                                hist_add<true>(hist, 2u, hist_bin_u32(e2e), 1u);
+                            }
                         }
                     }
-                    const unsigned long long lm = __ballot(listed);
-                    if (lm != 0ull) {
-                        if (listed) {
-                            atomicAdd(&cnt[k], 1u);
-                            const uint32_t before = __builtin_amdgcn_mbcnt_hi((uint32_t)(lm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)lm, 0u));
-                            queue[q_n + before] = rl | (k << 16);
-                        }
-                        q_n += (uint32_t)__popcll(lm);
+                    // queue the listed ones in arrival order: lanes in order, a lane's first request before its second
+                    const unsigned long long lm0 = __ballot(listed[0]), lm1 = __ballot(listed[1]);
+                    const uint32_t before = __builtin_amdgcn_mbcnt_hi((uint32_t)(lm0 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)lm0, 0u)) +
+                                            __builtin_amdgcn_mbcnt_hi((uint32_t)(lm1 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)lm1, 0u));
+                    const uint32_t rl = (h * kHalf + g) * 2u * kWave + 2u * lane;
+                    if (listed[0]) {
+                        atomicAdd(&cnt[id[2u * g]], 1u);
+                        queue[q_n + before] = (queued_t)(rl | (id[2u * g] << kIdShift));
                     }
+                    if (listed[1]) {
+                        atomicAdd(&cnt[id[2u * g + 1u]], 1u);
+                        queue[q_n + before + (listed[0] ? 1u : 0u)] = (queued_t)((rl + 1u) | (id[2u * g + 1u] << kIdShift));
+                    }
+                    q_n += (uint32_t)__popcll(lm0) + (uint32_t)__popcll(lm1);
                 }
             }
             s_ttft += t_ttft;
@@ -246,13 +271,13 @@ __global__ __launch_bounds__(kSplitThreads) void k_split_candidates(SplitParams 
             for (uint32_t d0 = 0; d0 < q_n; d0 += kWave) {
                 if (d0 + lane < q_n) {
                     const uint32_t pair = queue[d0 + lane];
-                    const uint32_t k = pair >> 16;
+                    const uint32_t k = pair >> kIdShift;
                     atomicOr(&same[k], 1ull << lane);
                     const unsigned long long peers = same[k];
                     const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(peers >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)peers, 0u));
                     const uint32_t n_peers = (uint32_t)__popcll(peers);
                     const uint32_t at = pos[k];
-                    list[at + rank] = (uint16_t)(pair & 0xFFFFu);
+                    list[at + rank] = (uint16_t)(pair & (kTile - 1u));
                     if (rank + 1u == n_peers) {
                         pos[k] = at + n_peers;
                         same[k] = 0ull;
@@ -266,7 +291,7 @@ __global__ __launch_bounds__(kSplitThreads) void k_split_candidates(SplitParams 
         fetch_keys(key_next, w);
         for (uint32_t j = w; j < p.n_tiles; j += kSplitWaves) {
 #pragma unroll
-            for (uint32_t g = 0; g < kGroups; ++g) key[g] = key_next[g];
+            for (uint32_t g = 0; g < kPairs; ++g) key[g] = key_next[g];
             fetch_keys(key_next, j + kSplitWaves);
             if ((j + 1u) * kTile <= R) work_tile(std::true_type{}, j);
             else work_tile(std::false_type{}, j);
