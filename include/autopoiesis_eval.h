@@ -151,9 +151,24 @@ ap_status ap_costtable_set(ap_workload *w, const ap_typed_replica *replicas, uin
  * It allocates nothing, copies nothing and clears nothing outside its kernels, so the call may be
  * captured into a HIP graph (stream capture on hip_stream) and replayed as long as the workload,
  * its cost model and both buffers stay as they were.  One evaluation per workload may be in
- * flight at a time.  C == 0 is a no-op.  Errors: AP_ERR_INVALID (null pointers), AP_ERR_STATE, AP_ERR_DEVICE. */
+ * flight at a time.  C == 0 is a no-op.  Errors: AP_ERR_INVALID (null pointers), AP_ERR_STATE, AP_ERR_DEVICE.
+ * The handle is const because the trace and the cost model are not changed, but the call does update host-side
+ * bookkeeping inside it (which of two device flag words the call uses, the count of candidates scored): calls
+ * on one workload, of this or any other kind, must come from one host thread at a time. */
 ap_status ap_eval_candidates(const ap_workload *w, const uint16_t *d_assign, uint32_t C, ap_metrics *d_out,
                              void *hip_stream);
+
+/* How the candidates scored since the last ap_costmodel_set / ap_costtable_set were settled: all of them, and
+ * those among them that had to go through the request-by-request replay of every replica's queue (the others were
+ * settled by one of the exact shortcuts: proven free of waiting, or split into a replayed backlog and a part that
+ * starts on arrival).  A 32-bit device counter behind `replayed`: it wraps after 2^32 replayed candidates.
+ * Synchronous: waits for the device.  Errors: AP_ERR_INVALID, AP_ERR_STATE, AP_ERR_DEVICE. */
+typedef struct {
+    uint64_t candidates;
+    uint64_t replayed;
+} ap_eval_counts;
+
+ap_status ap_eval_counts_get(const ap_workload *w, ap_eval_counts *out);
 
 /* Sparse candidates: children of one parent assignment (Section 5.4 "Synthesis Configuration",
  * trade-off-aware mutation: children are diff-based modifications of a high-performing parent;
@@ -182,7 +197,8 @@ ap_status ap_parent_set(ap_workload *w, const uint16_t *parent, uint32_t max_chi
  * Asynchronous on hip_stream, allocates nothing, launches kernels only (may be captured into a HIP
  * graph).  One evaluation per workload, of either kind, may be in flight at a time.  C == 0 is a no-op.
  * Errors: AP_ERR_INVALID (null pointers), AP_ERR_STATE (no cost model or no parent), AP_ERR_RANGE
- * (C > max_children), AP_ERR_DEVICE. */
+ * (C > max_children), AP_ERR_DEVICE.  Like ap_eval_candidates the call updates host-side bookkeeping in the
+ * handle: one host thread at a time per workload. */
 ap_status ap_eval_children(const ap_workload *w, const uint32_t *d_edit_first, const uint32_t *d_edit_request,
                            const uint16_t *d_edit_replica, uint32_t C, ap_metrics *d_out, void *hip_stream);
 

@@ -13,21 +13,26 @@ What is computed, and which passage of the paper each step follows:
   0: not at all).  ``Delta M_i`` is the set of models whose (GPU type, TP, count) tuples differ between the
   two plans.  ``T_term`` = the largest ``tau(z, g)`` over the changed models ``z`` and the GPU types ``g``
   on which the *previous* plan deploys ``z`` (different GPU types terminate concurrently: the slowest
-  decides); ``T_load`` = the largest ``tau(z, g)`` over the GPU types ``g`` and the models ``z`` the *new*
-  plan deploys there.  Both are zero when the plans are equal.
+  decides); ``T_load(sigma_i)`` = the largest ``tau(z, g)`` over the GPU types ``g`` and over EVERY model
+  ``z`` the *new* plan deploys there, changed or not (the loading-cost equation takes sigma_i alone and its
+  inner maximum runs over "z in M: sigma_i deploys M_z on g").  Both are zero when the plans are equal,
+  i.e. when no model's tuples changed.
 * ``trace_time``: the execution model of Section 5.1,
   ``T_total = t_sched(1) + t_serve(1) + sum_{i=2}^{N} [t_stale(i) + t_reconfig(i) + t_serve(i)]``, with the
   per-interval scheduling, stale-serving and serving times as inputs (they come from the policy's
   wall-clock time and from the serving simulator), and the breakdown the evaluator reports as artifact
   feedback (Section 5.3, Table 1: N, the three sums, T_total).
 
-Reading: the loading-cost equation as printed ranges over every model the new plan deploys; together
-with "both costs are zero if the plans are equal" and "the time to transfer *new* model weights" it is
-taken over the changed models only.  Times are integer nanoseconds, so sums and maxima are exact.
+``load_scope`` selects the index set of the loading cost: ``"deployed"`` (the default) is the equation as
+printed; ``"changed"`` restricts it to the changed models like the termination cost - a reading of the
+sentence before the equation ("the time to transfer *new* model weights") that this build offers as an
+alternative, not the paper's formula.  The two differ whenever an unchanged model has the largest transfer
+time.  Times are integer nanoseconds, so sums and maxima are exact.
 
 Pins (tests/test_reconfig_pins.py): the worked numbers of the system prompt's Example C (13 GB over 64 GB/s
 and 32 GB/s: 0.20 s + 0.41 s = 0.61 s) and Examples A and B (0.25 + 0.25, 0.51 + 0.25), the three rows of
-Table 1 (44.8 s, 33.5 s, 50.0 s), equal plans, and brute force over tiny plan pairs.
+Table 1 (44.8 s, 33.5 s, 50.0 s), equal plans, a hand-worked two-model case in which the two scopes differ,
+and brute force over tiny plan pairs for both scopes.
 """
 from __future__ import annotations
 
@@ -45,32 +50,40 @@ def transfer_ns(models, pcie_coef, gpus) -> np.ndarray:
     return tau
 
 
-def reconfig_ns(tau, prev, new):
+def reconfig_ns(tau, prev, new, load_scope="deployed"):
     """prev, new: integer arrays [Z][G][2] of (tp, count).  Returns (T_term, T_load) in nanoseconds."""
+    if load_scope not in ("deployed", "changed"):
+        raise ValueError(load_scope)
     prev = np.asarray(prev).reshape(tau.shape + (2,))
     new = np.asarray(new).reshape(tau.shape + (2,))
-    term = load = 0
+    changed = []                                           # Delta M_i
     for z in range(tau.shape[0]):
         deployed_prev = [(g, int(prev[z, g, 0])) if prev[z, g, 1] else None for g in range(tau.shape[1])]
         deployed_new = [(g, int(new[z, g, 0])) if new[z, g, 1] else None for g in range(tau.shape[1])]
         counts_differ = [int(prev[z, g, 1]) != int(new[z, g, 1]) for g in range(tau.shape[1])]
-        if deployed_prev == deployed_new and not any(counts_differ):
-            continue                                       # the model's (GPU type, TP, count) tuples are unchanged
+        if deployed_prev != deployed_new or any(counts_differ):
+            changed.append(z)                              # the model's (GPU type, TP, count) tuples differ
+    if not changed:
+        return 0, 0                                        # sigma_{i-1} = sigma_i: both costs are zero
+    term = load = 0
+    for z in changed:
         for g in range(tau.shape[1]):
             if prev[z, g, 1]:
                 term = max(term, int(tau[z, g]))
+    for z in (changed if load_scope == "changed" else range(tau.shape[0])):
+        for g in range(tau.shape[1]):
             if new[z, g, 1]:
                 load = max(load, int(tau[z, g]))
     return term, load
 
 
-def trace_time(tau, plans, n_intervals, sched_ns, stale_ns, serve_ns):
+def trace_time(tau, plans, n_intervals, sched_ns, stale_ns, serve_ns, load_scope="deployed"):
     """One candidate: plans [N_max][Z][G][2]; returns (N, sum_stale, sum_reconfig, sum_serve, T_total) in ns."""
     n = min(max(int(n_intervals), 1), len(plans))          # at least the cold start, at most the plans given
     total_stale = total_reconfig = 0
     total_serve = int(serve_ns[0])
     for i in range(1, n):
-        term, load = reconfig_ns(tau, plans[i - 1], plans[i])
+        term, load = reconfig_ns(tau, plans[i - 1], plans[i], load_scope)
         total_stale += int(stale_ns[i])
         total_reconfig += term + load
         total_serve += int(serve_ns[i])

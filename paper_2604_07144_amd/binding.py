@@ -68,6 +68,8 @@ def lib() -> C.CDLL:
         L.ap_costtable_set.restype = C.c_int
         L.ap_eval_candidates.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p]
         L.ap_eval_candidates.restype = C.c_int
+        L.ap_eval_counts_get.argtypes = [C.c_void_p, C.c_void_p]
+        L.ap_eval_counts_get.restype = C.c_int
         L.ap_parent_set.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32]
         L.ap_parent_set.restype = C.c_int
         L.ap_eval_children.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p,
@@ -171,6 +173,13 @@ def ap_eval_candidates(workload: int, d_assign_ptr: int, n_candidates: int, d_ou
     """Device pointers (ints) in; asynchronous on ``stream`` (a hipStream_t as int, 0 = default)."""
     _check(lib().ap_eval_candidates(workload, C.c_void_p(d_assign_ptr), int(n_candidates), C.c_void_p(d_out_ptr),
                                     C.c_void_p(stream)), "ap_eval_candidates")
+
+
+def ap_eval_counts_get(workload: int):
+    """Returns (candidates scored since the cost model was set, those that went through the exact replay kernels)."""
+    out = (C.c_uint64 * 2)()
+    _check(lib().ap_eval_counts_get(workload, out), "ap_eval_counts_get")
+    return int(out[0]), int(out[1])
 
 
 def ap_parent_set(workload: int, parent, max_children: int) -> None:

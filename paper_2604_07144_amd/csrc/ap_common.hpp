@@ -41,6 +41,7 @@ struct EvalParams {
     uint32_t slo_ttft, slo_tpot;
     uint32_t penalty_bin, k99;
     uint64_t penalty;
+    uint32_t* replayed;       // device counter: candidates that went through the exact replay kernels
     // byte offsets into dynamic LDS
     uint32_t off_slots, off_sorted, off_close, off_cnt, off_qstart, off_list, off_arr, off_prompt, off_out, off_misc;
 };

@@ -93,8 +93,9 @@ struct ap_workload {
     bool screen_packed = false;       // that kernel reads d_pair instead of d_span
     ap_metrics* d_nominal = nullptr;  // record shared by all contention-free candidates
     unsigned char* d_nominal_sums = nullptr;   // k_nominal_metrics: three histograms of 32-bit counts, then its sums and counters
-    uint32_t* d_pending = nullptr;    // [2] "this call has left pending marks", taken in turn by the calls
+    uint32_t* d_pending = nullptr;    // [2] "this call has left pending marks", taken in turn by the calls; [2] = candidates replayed
     mutable uint32_t turn = 0;        // which of the two the next call uses
+    mutable uint64_t n_scored = 0;    // candidates scored since the cost model was set
     bool has_model = false;
     bool screen = false;              // homogeneous, always-on replicas: screening applies
     bool hist16 = false;              // R < 65536: 16-bit histogram counters
@@ -297,9 +298,9 @@ ap_status ap_workload_create(const uint64_t* arrival_us, const int32_t* prompt_l
                         hipMalloc(&w->d_pair, ((size_t)R + 1u) / 2u * 4u) != hipSuccess ||
                         hipMalloc(&w->d_nominal, sizeof(ap_metrics)) != hipSuccess ||
                         hipMalloc(&w->d_nominal_sums, kNominalSumsBytes) != hipSuccess ||
-                        hipMalloc(&w->d_pending, 2u * sizeof(uint32_t)) != hipSuccess))
+                        hipMalloc(&w->d_pending, 4u * sizeof(uint32_t)) != hipSuccess))
         st = AP_ERR_ALLOC;
-    if (st == AP_OK && hipMemset(w->d_pending, 0, 2u * sizeof(uint32_t)) != hipSuccess) st = AP_ERR_DEVICE;
+    if (st == AP_OK && hipMemset(w->d_pending, 0, 4u * sizeof(uint32_t)) != hipSuccess) st = AP_ERR_DEVICE;
     std::vector<uint4> recs;
     if (st == AP_OK) {
         try {
@@ -714,6 +715,9 @@ static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint
     p.penalty = slo->penalty_us;
     p.penalty_bin = ap_hist_bin(slo->penalty_us);
     p.k99 = (uint32_t)((99ull * w->R + 99ull) / 100ull);
+    p.replayed = w->d_pending + 2;
+    if (hipMemset(p.replayed, 0, sizeof(uint32_t)) != hipSuccess) return AP_ERR_DEVICE;
+    w->n_scored = 0;
     w->has_model = false;
     w->has_parent = false;    // its analysis belonged to the previous cost model
     w->tabled = tabled;
@@ -763,6 +767,7 @@ static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint
         gp.qs = reinterpret_cast<uint16_t*>(w->d_scratch + o_qs);
         gp.list = reinterpret_cast<uint16_t*>(w->d_scratch + o_list);
         gp.unknown = reinterpret_cast<uint32_t*>(w->d_scratch + o_unk);
+        gp.replayed = p.replayed;
         w->group_params = gp;
         w->group_lds_bytes = (kGroupWaves * (M + 1u) + M + 2u) * 4u;
         ReplayParams qp{};
@@ -880,7 +885,22 @@ ap_status ap_eval_candidates(const ap_workload* w, const uint16_t* d_assign, uin
     if (!w->has_model) return AP_ERR_STATE;
     if (C == 0) return AP_OK;
     if (!d_assign || !d_out) return AP_ERR_INVALID;
+    w->n_scored += C;
     return launch_dense(w, d_assign, C, d_out, static_cast<hipStream_t>(hip_stream), false, take_pending_word(w));
+}
+
+ap_status ap_eval_counts_get(const ap_workload* w, ap_eval_counts* out) {
+    if (!w || !out) return AP_ERR_INVALID;
+    if (!w->has_model) return AP_ERR_STATE;
+    uint32_t replayed = 0;
+    if (hipSetDevice(w->device) != hipSuccess || hipDeviceSynchronize() != hipSuccess ||
+        hipMemcpy(&replayed, w->d_pending + 2, sizeof(uint32_t), hipMemcpyDeviceToHost) != hipSuccess) {
+        (void)hipGetLastError();
+        return AP_ERR_DEVICE;
+    }
+    out->candidates = w->n_scored;
+    out->replayed = replayed;
+    return AP_OK;
 }
 
 ap_status ap_parent_set(ap_workload* w, const uint16_t* parent, uint32_t max_children) {
@@ -955,6 +975,7 @@ ap_status ap_eval_children(const ap_workload* w, const uint32_t* d_edit_first, c
     if (C == 0) return AP_OK;
     if (!d_edit_first || !d_edit_request || !d_edit_replica || !d_out) return AP_ERR_INVALID;
     if (C > w->max_children) return AP_ERR_RANGE;
+    w->n_scored += C;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const uint32_t blocks = std::min((C + kChildWaves - 1u) / kChildWaves, w->n_cu * 64u);
     const PendingWord flags = take_pending_word(w);

@@ -33,6 +33,7 @@ struct GroupParams {
                                        //   in the chunk; qs[M] = number of listed requests; qs[M+1] unused
     uint16_t* list;                    // [batch][n_chunks * chunk] chunk-local request indices, by replica
     uint32_t* unknown;                 // [batch] requests naming no replica
+    uint32_t* replayed;                // device counter: candidates that went through the exact replay kernels
 };
 
 constexpr uint32_t kGroupThreads = 512;
@@ -55,6 +56,7 @@ __global__ __launch_bounds__(kGroupThreads) void k_group_requests(GroupParams p,
         const uint32_t c = c0 + cb;
         if (only_pending && !is_pending(out[c])) continue;
         const uint16_t* row = assign + (size_t)c * p.R;
+        if (tid == 0u) atomicAdd(p.replayed, 1u);
         uint32_t n_unknown = 0;
         for (uint32_t j = 0; j < p.n_chunks; ++j) {
             const uint32_t r0 = j * p.chunk, n = min(p.chunk, p.R - r0);

@@ -75,6 +75,7 @@ __global__ __launch_bounds__(kThreads) void k_eval_candidates(EvalParams p, cons
     for (uint32_t c = blockIdx.x; c < C; c += gridDim.x) {
         if (only_pending && !is_pending(out[c])) continue;      // same record for every thread: uniform
         const uint16_t* row = assign + (size_t)c * R;
+        if (tid == 0u) atomicAdd(p.replayed, 1u);
 
         hist_clear<kHist16>(hist);
         for (uint32_t i = tid; i < M * B; i += kThreads) slots[i] = 0u;

@@ -53,19 +53,44 @@ def test_table_1_rows():
         assert [round(x / 1e9, 1) for x in got[1:]] == [stale, reconfig, serve, total]
 
 
-def test_equal_plans_cost_nothing_and_only_changed_models_count():
+def test_loading_cost_ranges_over_every_deployed_model_hand_worked():
+    """Appendix "Serving Simulator", Reconfiguration Cost, worked by hand for two models on one GPU type.
+    tau(0, g) = 3 s, tau(1, g) = 8 s.  Model 0 changes its TP degree, model 1 stays as it is (and has the larger
+    transfer time).  Delta M = {0}.  Termination cost: max over the changed models the previous plan deploys:
+    tau(0, g) = 3 s.  Loading cost as printed: T_load(sigma_i) = max over g, max over EVERY z that sigma_i
+    deploys on g = max(3, 8) = 8 s, so Reconfig-Cost = 3 + 8 = 11 s.  Restricted to the changed models (the
+    alternative scope) the loading cost is 3 s and the sum 6 s."""
+    tau = np.array([[3_000_000_000], [8_000_000_000]], dtype=np.uint64)
+    prev = [[(2, 1)], [(4, 1)]]
+    new = [[(4, 1)], [(4, 1)]]
+    assert rc.reconfig_ns(tau, prev, new) == (3_000_000_000, 8_000_000_000)
+    assert rc.reconfig_ns(tau, prev, new, "deployed") == (3_000_000_000, 8_000_000_000)
+    assert rc.reconfig_ns(tau, prev, new, "changed") == (3_000_000_000, 3_000_000_000)
+    # the same through the execution model: one rescheduling, T_total = 1 + 2 + (0.5 + 11 + 4) s
+    plans = [prev, new]
+    got = rc.trace_time(tau, plans, 2, 10**9, [0, 5 * 10**8], [2 * 10**9, 4 * 10**9])
+    assert got == (2, 5 * 10**8, 11 * 10**9, 6 * 10**9, 185 * 10**8)
+    got = rc.trace_time(tau, plans, 2, 10**9, [0, 5 * 10**8], [2 * 10**9, 4 * 10**9], "changed")
+    assert got == (2, 5 * 10**8, 6 * 10**9, 6 * 10**9, 135 * 10**8)
+
+
+def test_equal_plans_cost_nothing_and_termination_counts_changed_models_only():
     tau = np.array([[5, 7], [11, 13], [17, 19]], dtype=np.uint64)
     plan = [[(2, 1), (0, 0)], [(0, 0), (4, 2)], [(1, 3), (1, 1)]]
-    assert rc.reconfig_ns(tau, plan, plan) == (0, 0)
+    for scope in ("deployed", "changed"):
+        assert rc.reconfig_ns(tau, plan, plan, scope) == (0, 0)
+        # a TP degree written on a GPU type the model is not deployed on is not a change
+        ghost = [[(2, 1), (9, 0)], [(0, 0), (4, 2)], [(1, 3), (1, 1)]]
+        assert rc.reconfig_ns(tau, plan, ghost, scope) == (0, 0)
     moved = [[(2, 1), (0, 0)], [(0, 0), (4, 3)], [(1, 3), (1, 1)]]          # model 1: one more replica
-    assert rc.reconfig_ns(tau, plan, moved) == (13, 13)
+    assert rc.reconfig_ns(tau, plan, moved, "changed") == (13, 13)
+    assert rc.reconfig_ns(tau, plan, moved) == (13, 19)                     # model 2, unchanged, loads slowest
     retp = [[(4, 1), (0, 0)], [(0, 0), (4, 2)], [(1, 3), (1, 1)]]           # model 0: another TP degree
-    assert rc.reconfig_ns(tau, plan, retp) == (5, 5)
-    gone = [[(2, 1), (0, 0)], [(0, 0), (4, 2)], [(0, 0), (0, 0)]]           # model 2 removed: terminated, nothing loaded
-    assert rc.reconfig_ns(tau, plan, gone) == (19, 0)
-    # a TP degree written on a GPU type the model is not deployed on is not a change
-    ghost = [[(2, 1), (9, 0)], [(0, 0), (4, 2)], [(1, 3), (1, 1)]]
-    assert rc.reconfig_ns(tau, plan, ghost) == (0, 0)
+    assert rc.reconfig_ns(tau, plan, retp, "changed") == (5, 5)
+    assert rc.reconfig_ns(tau, plan, retp) == (5, 19)
+    gone = [[(2, 1), (0, 0)], [(0, 0), (4, 2)], [(0, 0), (0, 0)]]           # model 2 removed: terminated, not loaded
+    assert rc.reconfig_ns(tau, plan, gone, "changed") == (19, 0)
+    assert rc.reconfig_ns(tau, plan, gone) == (19, 13)                      # what the new plan still deploys
 
 
 def test_brute_force_over_tiny_plan_pairs():
@@ -81,4 +106,6 @@ def test_brute_force_over_tiny_plan_pairs():
             changed = [z for z in range(2) if key(p, z) != key(q, z)]
             term = max([int(tau[z, g]) for z in changed for g in range(2) if p[z, g, 1]], default=0)
             load = max([int(tau[z, g]) for z in changed for g in range(2) if q[z, g, 1]], default=0)
-            assert rc.reconfig_ns(tau, p, q) == (term, load)
+            assert rc.reconfig_ns(tau, p, q, "changed") == (term, load)
+            every = max([int(tau[z, g]) for z in range(2) for g in range(2) if q[z, g, 1]], default=0)
+            assert rc.reconfig_ns(tau, p, q) == ((term, every) if changed else (0, 0))
