@@ -251,12 +251,19 @@ ap_status ap_roofline_costs(const ap_workload *w, const ap_model *models, uint32
 /* End-to-end trace time of candidate plan sequences (Section 5.1, execution model):
  *   T_total = t_sched(1) + t_serve(1) + sum_{i=2}^{N} [ t_stale(i) + t_reconfig(i) + t_serve(i) ]
  * with t_reconfig(i) = Reconfig-Cost(sigma_{i-1}, sigma_i) = T_term + T_load of Appendix "Serving
- * Simulator": tau(z, g) = W_z / P_g * c_z is the weight transfer time of model z on GPU type g (W_z by
- * the weight-size equation, c_z = pcie_coef[z]); over the models whose (GPU type, TP, count) tuples
- * differ between the two plans, T_term is the largest tau on a GPU type the previous plan deploys them
- * on and T_load the largest on a GPU type the new plan deploys them on; equal plans cost nothing.  The
- * record is the evaluator's artifact feedback (Section 5.3, Table 1; the table's N counts reschedulings,
- * n_intervals here counts intervals including the cold start). */
+ * Simulator", Reconfiguration Cost: tau(z, g) = W_z / P_g * c_z is the weight transfer time of model z on
+ * GPU type g (W_z by the weight-size equation, c_z = pcie_coef[z]).  With Delta M the models whose (GPU
+ * type, TP, count) tuples differ between the two plans, the termination-cost equation gives T_term = the
+ * largest tau(z, g) over z in Delta M and the GPU types g the previous plan deploys z on, and the
+ * loading-cost equation gives T_load(sigma_i) = the largest tau(z, g) over the GPU types g and EVERY model
+ * z the new plan deploys on g, changed or not (AP_LOAD_DEPLOYED, the equation as printed).
+ * AP_LOAD_CHANGED restricts the loading cost to z in Delta M as well - an alternative reading of "the time
+ * to transfer new model weights", not the printed formula.  Equal plans (Delta M empty) cost nothing under
+ * either.  The record is the evaluator's artifact feedback (Section 5.3, Table 1; the table's N counts
+ * reschedulings, n_intervals here counts intervals including the cold start). */
+#define AP_LOAD_DEPLOYED 0u
+#define AP_LOAD_CHANGED 1u
+
 typedef struct {
     uint32_t tp;    /* tensor-parallel degree of the model's replicas on this GPU type */
     uint32_t count; /* number of replicas; 0 = the model is not deployed on this GPU type */
@@ -278,14 +285,19 @@ typedef struct {
  *   d_n_intervals : DEVICE, uint32 [C]; N of each candidate, taken as at least 1 and at most N_max.
  *   d_sched_ns    : DEVICE, uint64 [C]; t_sched(1).
  *   d_stale_ns, d_serve_ns : DEVICE, uint64 [C][N_max]; t_stale(i+1), t_serve(i+1) at index i (stale[0] unused).
+ *   load_scope    : AP_LOAD_DEPLOYED or AP_LOAD_CHANGED (above).
  *   d_out         : DEVICE, ap_breakdown [C], written.
- * All times are nanoseconds.  Synchronous (default stream; small temporary buffers).  C == 0 is a no-op.
+ *   hip_stream    : a hipStream_t passed as void* (NULL = the default stream).  The kernels run on it, i.e.
+ *                   behind whatever produced the device inputs there (e.g. serve times taken from an
+ *                   ap_eval_candidates call on the same stream).
+ * All times are nanoseconds.  The call allocates small temporary device buffers and frees them before it
+ * returns, so it waits for hip_stream: d_out is complete on return.  C == 0 is a no-op.
  * Errors: AP_ERR_INVALID (null pointers, empty arrays, a zero model field, a non-positive coefficient or
- * bandwidth), AP_ERR_RANGE (n_models * n_gpus above 2^20), AP_ERR_ALLOC, AP_ERR_DEVICE. */
+ * bandwidth, an unknown load_scope), AP_ERR_RANGE (n_models * n_gpus above 2^20), AP_ERR_ALLOC, AP_ERR_DEVICE. */
 ap_status ap_trace_time(const ap_model *models, const double *pcie_coef, uint32_t n_models, const ap_gpu *gpus,
                         uint32_t n_gpus, const ap_placement *d_plans, const uint32_t *d_n_intervals,
                         const uint64_t *d_sched_ns, const uint64_t *d_stale_ns, const uint64_t *d_serve_ns, uint32_t C,
-                        uint32_t N_max, ap_breakdown *d_out);
+                        uint32_t N_max, uint32_t load_scope, ap_breakdown *d_out, void *hip_stream);
 
 /* Agentic request scheduling (Section 8.3; Appendix "Scheduling Problem Formulation", Formulation for
  * Agentic Request): multi-call workflows on a disaggregated cluster of prefill instances (one call at a

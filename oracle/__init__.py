@@ -52,7 +52,10 @@ assert METRICS_DTYPE.itemsize == 64 and C.sizeof(OrcMetrics) == 64
 
 
 def build(force: bool = False) -> str:
-    """Compile the oracle with gcc (plain -O2; it is a checker, never tuned)."""
+    """Compile the oracle with gcc (plain -O2; it is a checker, never tuned).  AP_ORACLE_LIB in the environment
+    names a library built elsewhere to be loaded instead (the sanitizer build of tests/test_oracle_sanitizers.py)."""
+    if os.environ.get("AP_ORACLE_LIB"):
+        return os.environ["AP_ORACLE_LIB"]
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.run(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-fPIC", "-shared", "-pthread",
                         _SRC, "-o", _LIB], check=True)

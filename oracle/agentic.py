@@ -29,6 +29,9 @@ assert METRICS_DTYPE.itemsize == 40
 
 
 def build(force: bool = False) -> str:
+    """AP_AGENTIC_ORACLE_LIB in the environment names a library built elsewhere to be loaded instead."""
+    if os.environ.get("AP_AGENTIC_ORACLE_LIB"):
+        return os.environ["AP_AGENTIC_ORACLE_LIB"]
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.run(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-fPIC", "-shared", _SRC, "-o", _LIB], check=True)
     return _LIB

@@ -82,7 +82,8 @@ def lib() -> C.CDLL:
                                         C.c_void_p, C.c_void_p]
         L.ap_roofline_costs.restype = C.c_int
         L.ap_trace_time.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p,
-                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p]
+                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32, C.c_void_p,
+                                    C.c_void_p]
         L.ap_trace_time.restype = C.c_int
         L.ap_agentic_create.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_uint64,
@@ -231,8 +232,12 @@ def ap_roofline_costs(workload: int, n_requests: int, models, gpus, groups):
     return prefill_us, tpot_us
 
 
+AP_LOAD_DEPLOYED, AP_LOAD_CHANGED = 0, 1
+
+
 def ap_trace_time(models, pcie_coef, gpus, d_plans_ptr: int, d_n_intervals_ptr: int, d_sched_ns_ptr: int,
-                  d_stale_ns_ptr: int, d_serve_ns_ptr: int, n_candidates: int, n_max: int, d_out_ptr: int) -> None:
+                  d_stale_ns_ptr: int, d_serve_ns_ptr: int, n_candidates: int, n_max: int, d_out_ptr: int,
+                  load_scope: int = AP_LOAD_DEPLOYED, stream: int = 0) -> None:
     """Host descriptors (structured arrays, float64 coefficients), device pointers (ints) for the rest."""
     models = np.ascontiguousarray(models, dtype=MODEL_DTYPE)
     gpus = np.ascontiguousarray(gpus, dtype=GPU_DTYPE)
@@ -242,7 +247,7 @@ def ap_trace_time(models, pcie_coef, gpus, d_plans_ptr: int, d_n_intervals_ptr: 
     _check(lib().ap_trace_time(models.ctypes.data, coef.ctypes.data, models.shape[0], gpus.ctypes.data, gpus.shape[0],
                                C.c_void_p(d_plans_ptr), C.c_void_p(d_n_intervals_ptr), C.c_void_p(d_sched_ns_ptr),
                                C.c_void_p(d_stale_ns_ptr), C.c_void_p(d_serve_ns_ptr), int(n_candidates), int(n_max),
-                               C.c_void_p(d_out_ptr)), "ap_trace_time")
+                               int(load_scope), C.c_void_p(d_out_ptr), C.c_void_p(stream)), "ap_trace_time")
 
 
 def ap_agentic_create(arrival_us, slo_us, wf, in_len, out_len, pred_first, pred, pa, pb, qc, qd, cap,

@@ -248,7 +248,7 @@ __global__ __launch_bounds__(kAgenticThreads) void k_agentic_eval(AgenticParams 
                     const uint32_t k = wave_all_min(best_key == key_min ? best_k : kNever);   // the same in every lane
                     if (k == kNever) break;
                     const uint32_t need = p.in_len[k] + p.out_len[k];
-                    if (used[q] + need > p.cap[q]) break;
+                    if (need > p.cap[q] - used[q]) break;              // used <= cap always; the sum could leave 32 bits
                     const uint32_t ends = t + p.out_len[k] * (p.qc[q] + p.qd[q] * ((p.in_len[k] + 1023u) >> 10));
                     t_next = min(t_next, ends);
                     if (lane == (k & 63u)) {                      // its owner

@@ -1112,8 +1112,10 @@ ap_status ap_roofline_costs(const ap_workload* w, const ap_model* models, uint32
 ap_status ap_trace_time(const ap_model* models, const double* pcie_coef, uint32_t n_models, const ap_gpu* gpus, uint32_t n_gpus,
                         const ap_placement* d_plans, const uint32_t* d_n_intervals, const uint64_t* d_sched_ns,
                         const uint64_t* d_stale_ns, const uint64_t* d_serve_ns, uint32_t C, uint32_t N_max,
-                        ap_breakdown* d_out) {
+                        uint32_t load_scope, ap_breakdown* d_out, void* hip_stream) {
     if (!models || !pcie_coef || !gpus || n_models == 0 || n_gpus == 0 || N_max == 0) return AP_ERR_INVALID;
+    if (load_scope != AP_LOAD_DEPLOYED && load_scope != AP_LOAD_CHANGED) return AP_ERR_INVALID;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (C == 0) return AP_OK;
     if (!d_plans || !d_n_intervals || !d_sched_ns || !d_stale_ns || !d_serve_ns || !d_out) return AP_ERR_INVALID;
     if ((uint64_t)n_models * n_gpus > (1u << 20)) return AP_ERR_RANGE;
@@ -1154,11 +1156,15 @@ ap_status ap_trace_time(const ap_model* models, const double* pcie_coef, uint32_
         (void)hipGetLastError();
         return AP_ERR_ALLOC;
     }
+    // the descriptions are on the device when these copies return; the kernels then run on the caller's stream,
+    // behind whatever produced the device inputs there
     if (hipMemcpy(tmp.models, host.data(), sizeof(RoofGroup) * n_models, hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(tmp.coef, pcie_coef, 8u * n_models, hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemcpy(tmp.pcie, pcie.data(), 8u * n_gpus, hipMemcpyHostToDevice) != hipSuccess)
+        hipMemcpy(tmp.pcie, pcie.data(), 8u * n_gpus, hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipGetLastError();
         return AP_ERR_DEVICE;
-    hipLaunchKernelGGL(k_transfer_times, dim3((n_models * n_gpus + kRoofThreads - 1u) / kRoofThreads), dim3(kRoofThreads), 0, nullptr,
+    }
+    hipLaunchKernelGGL(k_transfer_times, dim3((n_models * n_gpus + kRoofThreads - 1u) / kRoofThreads), dim3(kRoofThreads), 0, stream,
                        tmp.models, tmp.coef, n_models, tmp.pcie, n_gpus, tmp.tau);
     TraceTimeParams tp{};
     tp.tau_ns = tmp.tau;
@@ -1168,8 +1174,10 @@ ap_status ap_trace_time(const ap_model* models, const double* pcie_coef, uint32_
     tp.stale_ns = reinterpret_cast<const unsigned long long*>(d_stale_ns);
     tp.serve_ns = reinterpret_cast<const unsigned long long*>(d_serve_ns);
     tp.C = C; tp.N_max = N_max; tp.Z = n_models; tp.G = n_gpus;
-    hipLaunchKernelGGL(k_trace_time, dim3((C + kRoofThreads - 1u) / kRoofThreads), dim3(kRoofThreads), 0, nullptr, tp, d_out);
-    if (hipGetLastError() != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+    tp.load_changed_only = load_scope == AP_LOAD_CHANGED ? 1u : 0u;
+    hipLaunchKernelGGL(k_trace_time, dim3((C + kRoofThreads - 1u) / kRoofThreads), dim3(kRoofThreads), 0, stream, tp, d_out);
+    // the temporary tables are freed on return: wait for the stream
+    if (hipGetLastError() != hipSuccess || hipStreamSynchronize(stream) != hipSuccess) {
         (void)hipGetLastError();
         return AP_ERR_DEVICE;
     }

@@ -165,13 +165,16 @@ struct TraceTimeParams {
     const unsigned long long* stale_ns;   // [C][N_max]
     const unsigned long long* serve_ns;   // [C][N_max]
     uint32_t C, N_max, Z, G;
+    uint32_t load_changed_only;           // the loading cost over the changed models only (else: every model the new plan deploys)
 };
 
 // One thread per candidate: T_total = t_sched(1) + t_serve(1) + sum over i >= 2 of t_stale(i) +
 // Reconfig-Cost(sigma_{i-1}, sigma_i) + t_serve(i) (Section 5.1, execution model), where
-// Reconfig-Cost = T_term + T_load: over the models whose (GPU type, TP, count) tuples changed, the largest
-// transfer time on a GPU type the previous plan had them on, plus the largest on a GPU type the new plan
-// puts them on.  Integers throughout.
+// Reconfig-Cost = T_term + T_load (Appendix "Serving Simulator", Reconfiguration Cost): T_term is the largest
+// transfer time, over the models whose (GPU type, TP, count) tuples changed, on a GPU type the previous plan
+// had them on; T_load is the largest transfer time over every model the new plan deploys, on the GPU types it
+// deploys them on (the loading-cost equation takes the new plan alone) - or, with load_changed_only, over the
+// changed models only; both are zero when no model changed.  Integers throughout.
 __global__ __launch_bounds__(kRoofThreads) void k_trace_time(TraceTimeParams p, ap_breakdown* __restrict__ out) {
     const uint32_t c = blockIdx.x * kRoofThreads + threadIdx.x;
     if (c >= p.C) return;
@@ -182,20 +185,25 @@ __global__ __launch_bounds__(kRoofThreads) void k_trace_time(TraceTimeParams p, 
     for (uint32_t i = 1; i < n; ++i) {
         const ap_placement* prev = plans + (size_t)(i - 1u) * per_plan;
         const ap_placement* next = plans + (size_t)i * per_plan;
-        unsigned long long term = 0ull, load = 0ull;
+        unsigned long long term = 0ull, load_changed = 0ull, load_deployed = 0ull;
+        bool any_changed = false;
         for (uint32_t z = 0; z < p.Z; ++z) {
             bool changed = false;
             for (uint32_t g = 0; g < p.G; ++g) {
                 const ap_placement a = prev[z * p.G + g], b = next[z * p.G + g];
                 changed = changed || a.count != b.count || (a.count != 0u && a.tp != b.tp);
             }
-            if (!changed) continue;
+            any_changed = any_changed || changed;
             for (uint32_t g = 0; g < p.G; ++g) {
                 const unsigned long long tau = p.tau_ns[z * p.G + g];
-                if (prev[z * p.G + g].count != 0u) term = max(term, tau);
-                if (next[z * p.G + g].count != 0u) load = max(load, tau);
+                if (changed && prev[z * p.G + g].count != 0u) term = max(term, tau);
+                if (next[z * p.G + g].count != 0u) {
+                    load_deployed = max(load_deployed, tau);
+                    if (changed) load_changed = max(load_changed, tau);
+                }
             }
         }
+        const unsigned long long load = !any_changed ? 0ull : (p.load_changed_only ? load_changed : load_deployed);
         stale += p.stale_ns[(size_t)c * p.N_max + i];
         reconfig += term + load;
         serve += p.serve_ns[(size_t)c * p.N_max + i];

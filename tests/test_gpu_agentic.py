@@ -54,6 +54,17 @@ def test_hand_worked_schedules_on_gpu():
     both(tiny(P=2), *rows([9, 0, 1], [0, 0, 9], [0, 0, 0]), "unknown instances")
 
 
+def test_token_budget_near_the_32_bit_limit():
+    """Two calls of 3e9 tokens each on a decode instance whose budget is 2^32 - 1: together they exceed it (and the
+    32-bit sum of their sizes wraps round), so the second waits for the first to leave."""
+    wl = dict(arrival_us=[0, 0], slo_us=[10**6, 10**6], wf=[0, 1], in_len=[3_000_000_000, 3_000_000_000], out_len=[5, 7],
+              pred_first=[0, 0, 0], pred=[], pa=[10], pb=[0], qc=[1000], qd=[0], cap=[2**32 - 1], penalty_permille=50_000)
+    rows = tuple(np.array([x], dtype=t) for x, t in zip(([0, 0], [0, 0], [0, 1]), (np.uint16, np.uint16, np.uint32)))
+    got = both(wl, *rows, "budget near 2^32")
+    # prefill 10 us each, one at a time: decode of call 0 runs 10..5010, call 1 (ready at 20) is admitted at 5010
+    assert int(got["makespan_us"][0]) == 5010 + 7000 and int(got["n_failed"][0]) == 0
+
+
 @pytest.mark.parametrize("seed,W,P,Q,capacity,rate,mean_calls", [
     (0, 64, 4, 4, 16384, 20.0, 5.0),        # the paper-shaped slice, light
     (1, 64, 2, 2, 3000, 200.0, 5.0),        # contended on both stages, some ids outside the cluster

@@ -12,7 +12,10 @@ from paper_2604_07144_amd import binding                  # noqa: E402
 from tests.test_gpu_roofline import GPUS, MODELS, _pack    # noqa: E402
 
 
-def run(models, coef, gpus, plans, n_intervals, sched, stale, serve):
+SCOPES = {"deployed": binding.AP_LOAD_DEPLOYED, "changed": binding.AP_LOAD_CHANGED}
+
+
+def run(models, coef, gpus, plans, n_intervals, sched, stale, serve, scope="deployed"):
     """plans: uint32 [C][N][Z][G][2]; returns the records as a structured array."""
     C, N = plans.shape[0], plans.shape[1]
     m, g, _ = _pack(models, gpus, [rf.Group(0, 0, 1, 1)])
@@ -23,17 +26,18 @@ def run(models, coef, gpus, plans, n_intervals, sched, stale, serve):
     d_serve = torch.from_numpy(np.ascontiguousarray(serve, dtype=np.uint64).view(np.int64)).cuda()
     d_out = torch.full((C, 6), -1, dtype=torch.int64, device="cuda")
     binding.ap_trace_time(m, coef, g, d_plans.data_ptr(), d_n.data_ptr(), d_sched.data_ptr(), d_stale.data_ptr(),
-                          d_serve.data_ptr(), C, N, d_out.data_ptr())
+                          d_serve.data_ptr(), C, N, d_out.data_ptr(), SCOPES[scope], torch.cuda.current_stream().cuda_stream)
     return d_out.cpu().numpy().view(binding.BREAKDOWN_DTYPE).reshape(-1)
 
 
-def check(models, coef, gpus, plans, n_intervals, sched, stale, serve):
-    got = run(models, coef, gpus, plans, n_intervals, sched, stale, serve)
+def check(models, coef, gpus, plans, n_intervals, sched, stale, serve, scope="deployed"):
+    got = run(models, coef, gpus, plans, n_intervals, sched, stale, serve, scope)
     tau = rc.transfer_ns(models, coef, gpus)
     for c in range(plans.shape[0]):
-        n, s_stale, s_reconfig, s_serve, total = rc.trace_time(tau, plans[c], n_intervals[c], sched[c], stale[c], serve[c])
+        n, s_stale, s_reconfig, s_serve, total = rc.trace_time(tau, plans[c], n_intervals[c], sched[c], stale[c], serve[c],
+                                                               scope)
         want = (total, s_stale, s_reconfig, s_serve, int(sched[c]), n, 0)
-        assert tuple(int(x) for x in got[c]) == want, (c, got[c], want)
+        assert tuple(int(x) for x in got[c]) == want, (scope, c, got[c], want)
     return got
 
 
@@ -51,6 +55,23 @@ def test_random_plan_sequences():
     serve = rng.integers(0, 10**11, size=(C, N)).astype(np.uint64)
     got = check(MODELS, [5.3, 7.0, 11.5, 1.0], GPUS, plans, n_intervals, sched, stale, serve)
     assert (got["sum_reconfig_ns"] == 0).any() and (got["sum_reconfig_ns"] > 0).any()
+    other = check(MODELS, [5.3, 7.0, 11.5, 1.0], GPUS, plans, n_intervals, sched, stale, serve, "changed")
+    assert (other["sum_reconfig_ns"] < got["sum_reconfig_ns"]).any()    # an unchanged model loads slowest somewhere
+    assert (other["sum_reconfig_ns"] <= got["sum_reconfig_ns"]).all()
+
+
+def test_two_models_where_the_scopes_differ_on_gpu():
+    """Model 0 changes its TP degree, model 1 (the larger one) stays: the loading cost as printed is the larger model's
+    transfer time, the changed-only scope gives the smaller model's."""
+    models, gpus = MODELS[:2], GPUS[:1]
+    plans = np.array([[[[(2, 1)], [(4, 1)]], [[(4, 1)], [(4, 1)]]]], dtype=np.uint32)       # [1][2][2][1][2]
+    args = (models, [1.0, 1.0], gpus, plans, np.array([2], np.uint32), np.array([7], np.uint64),
+            np.array([[0, 11]], np.uint64), np.array([[13, 17]], np.uint64))
+    tau = rc.transfer_ns(models, [1.0, 1.0], gpus)
+    both = {scope: int(check(*args, scope)["sum_reconfig_ns"][0]) for scope in SCOPES}
+    assert both["deployed"] == int(tau[0, 0]) + int(max(tau[0, 0], tau[1, 0]))
+    assert both["changed"] == 2 * int(tau[0, 0])
+    assert both["deployed"] != both["changed"]
 
 
 def test_printed_worked_numbers_on_gpu():
@@ -90,8 +111,8 @@ def test_error_paths():
     buf = torch.zeros(64, dtype=torch.int64, device="cuda")
     ptr = buf.data_ptr()
 
-    def status(models, coef, gpus, C=1, N=1, hole=None):
-        args = [models, coef, gpus, ptr, ptr, ptr, ptr, ptr, C, N, ptr]
+    def status(models, coef, gpus, C=1, N=1, hole=None, scope=0):
+        args = [models, coef, gpus, ptr, ptr, ptr, ptr, ptr, C, N, ptr, scope]
         if hole is not None:
             args[hole] = 0
         with pytest.raises(binding.ApError) as e:
@@ -103,6 +124,7 @@ def test_error_paths():
     bad["pcie_bytes_per_s"] = 0.0
     assert status(m, [1.0], bad) == binding.AP_ERR_INVALID
     assert status(m, [1.0], g, N=0) == binding.AP_ERR_INVALID
+    assert status(m, [1.0], g, scope=2) == binding.AP_ERR_INVALID
     for hole in (3, 4, 5, 6, 7, 10):
         assert status(m, [1.0], g, hole=hole) == binding.AP_ERR_INVALID
     binding.ap_trace_time(m, [1.0], g, ptr, ptr, ptr, ptr, ptr, 0, 1, ptr)      # C == 0: nothing to do
