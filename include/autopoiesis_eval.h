@@ -299,6 +299,24 @@ ap_status ap_trace_time(const ap_model *models, const double *pcie_coef, uint32_
                         const uint64_t *d_sched_ns, const uint64_t *d_stale_ns, const uint64_t *d_serve_ns, uint32_t C,
                         uint32_t N_max, uint32_t load_scope, ap_breakdown *d_out, void *hip_stream);
 
+/* ap_trace_time for callers that cannot allocate device memory or wait: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same results as ap_trace_time, but the
+ * transfer-time table tau(z, g) is kept in a fixed array inside the library (8 KiB of device memory per GPU the
+ * library runs on, held until the process ends) and the model / GPU descriptions travel in the kernel arguments,
+ * so the call allocates nothing, frees nothing, copies nothing and does not wait: two kernels are queued on
+ * hip_stream and d_out is complete when the stream reaches the end of them.
+ * Limits: n_models <= AP_STATIC_MAX_MODELS, n_gpus <= AP_STATIC_MAX_GPU_TYPES, else AP_ERR_RANGE.
+ * Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU (different streams, or
+ * different host threads) race on it and must be serialised by the caller; calls on one stream are in order.
+ * The array keeps the last call's table; each call rewrites every entry it reads.
+ * Errors otherwise as ap_trace_time (AP_ERR_ALLOC cannot occur). */
+#define AP_STATIC_MAX_MODELS 64u
+#define AP_STATIC_MAX_GPU_TYPES 16u
+ap_status ap_trace_time_static(const ap_model *models, const double *pcie_coef, uint32_t n_models, const ap_gpu *gpus,
+                               uint32_t n_gpus, const ap_placement *d_plans, const uint32_t *d_n_intervals,
+                               const uint64_t *d_sched_ns, const uint64_t *d_stale_ns, const uint64_t *d_serve_ns,
+                               uint32_t C, uint32_t N_max, uint32_t load_scope, ap_breakdown *d_out, void *hip_stream);
+
 /* Agentic request scheduling (Section 8.3; Appendix "Scheduling Problem Formulation", Formulation for
  * Agentic Request): multi-call workflows on a disaggregated cluster of prefill instances (one call at a
  * time) and decode instances (each with a token-capacity budget).  A call becomes schedulable when its

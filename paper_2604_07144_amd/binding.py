@@ -85,6 +85,8 @@ def lib() -> C.CDLL:
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32, C.c_void_p,
                                     C.c_void_p]
         L.ap_trace_time.restype = C.c_int
+        L.ap_trace_time_static.argtypes = L.ap_trace_time.argtypes
+        L.ap_trace_time_static.restype = C.c_int
         L.ap_agentic_create.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_uint64,
                                         C.POINTER(C.c_void_p)]
@@ -248,6 +250,21 @@ def ap_trace_time(models, pcie_coef, gpus, d_plans_ptr: int, d_n_intervals_ptr: 
                                C.c_void_p(d_plans_ptr), C.c_void_p(d_n_intervals_ptr), C.c_void_p(d_sched_ns_ptr),
                                C.c_void_p(d_stale_ns_ptr), C.c_void_p(d_serve_ns_ptr), int(n_candidates), int(n_max),
                                int(load_scope), C.c_void_p(d_out_ptr), C.c_void_p(stream)), "ap_trace_time")
+
+
+def ap_trace_time_static(models, pcie_coef, gpus, d_plans_ptr: int, d_n_intervals_ptr: int, d_sched_ns_ptr: int,
+                         d_stale_ns_ptr: int, d_serve_ns_ptr: int, n_candidates: int, n_max: int, d_out_ptr: int,
+                         load_scope: int = AP_LOAD_DEPLOYED, stream: int = 0) -> None:
+    """ap_trace_time without allocation or waiting: asynchronous on ``stream``."""
+    models = np.ascontiguousarray(models, dtype=MODEL_DTYPE)
+    gpus = np.ascontiguousarray(gpus, dtype=GPU_DTYPE)
+    coef = np.ascontiguousarray(pcie_coef, dtype=np.float64)
+    if coef.shape != (models.shape[0],):
+        raise ValueError("one PCIe coefficient per model")
+    _check(lib().ap_trace_time_static(models.ctypes.data, coef.ctypes.data, models.shape[0], gpus.ctypes.data, gpus.shape[0],
+                                      C.c_void_p(d_plans_ptr), C.c_void_p(d_n_intervals_ptr), C.c_void_p(d_sched_ns_ptr),
+                                      C.c_void_p(d_stale_ns_ptr), C.c_void_p(d_serve_ns_ptr), int(n_candidates), int(n_max),
+                                      int(load_scope), C.c_void_p(d_out_ptr), C.c_void_p(stream)), "ap_trace_time_static")
 
 
 def ap_agentic_create(arrival_us, slo_us, wf, in_len, out_len, pred_first, pred, pa, pb, qc, qd, cap,

@@ -24,6 +24,8 @@
 // ap_children.hpp (sparse candidates), ap_split.hpp (replicas that differ or come and go: listed and streamed
 // part), ap_roofline.hpp (roofline cost tables, trace time) and ap_agentic.hpp (agentic workflows); ap_common.hpp
 // has what they share.
+#include <mutex>
+
 #include "ap_common.hpp"
 #include "ap_screen.hpp"
 #include "ap_replay.hpp"
@@ -1181,6 +1183,71 @@ ap_status ap_trace_time(const ap_model* models, const double* pcie_coef, uint32_
         (void)hipGetLastError();
         return AP_ERR_DEVICE;
     }
+    return AP_OK;
+}
+
+// ---- trace time for callers that cannot allocate ------------------------------------------
+// The transfer-time table of ap_trace_time_static lives in this array (one copy per device, held until the
+// process ends).  In host code the array's name is only a stand-in for the symbol: its device address is asked
+// for once per device and kept in trace_scratch_at.
+static __device__ __align__(256) unsigned long long scratch[kTransferArgModels * kTransferArgGpus];
+constexpr int kScratchDevices = 64;
+static unsigned long long* trace_scratch_at[kScratchDevices] = {};
+static std::mutex trace_scratch_lock;
+
+ap_status ap_trace_time_static(const ap_model* models, const double* pcie_coef, uint32_t n_models, const ap_gpu* gpus,
+                               uint32_t n_gpus, const ap_placement* d_plans, const uint32_t* d_n_intervals,
+                               const uint64_t* d_sched_ns, const uint64_t* d_stale_ns, const uint64_t* d_serve_ns, uint32_t C,
+                               uint32_t N_max, uint32_t load_scope, ap_breakdown* d_out, void* hip_stream) {
+    if (!models || !pcie_coef || !gpus || n_models == 0 || n_gpus == 0 || N_max == 0) return AP_ERR_INVALID;
+    if (load_scope != AP_LOAD_DEPLOYED && load_scope != AP_LOAD_CHANGED) return AP_ERR_INVALID;
+    if (n_models > AP_STATIC_MAX_MODELS || n_gpus > AP_STATIC_MAX_GPU_TYPES) return AP_ERR_RANGE;
+    if (C == 0) return AP_OK;
+    if (!d_plans || !d_n_intervals || !d_sched_ns || !d_stale_ns || !d_serve_ns || !d_out) return AP_ERR_INVALID;
+    TransferArgs args{};
+    for (uint32_t z = 0; z < n_models; ++z) {
+        const ap_model& m = models[z];
+        if (m.layers == 0 || m.hidden == 0 || m.intermediate == 0 || m.vocab == 0 || m.heads == 0 || m.kv_heads == 0 ||
+            m.kv_heads > m.heads || m.weight_bits == 0 || !(pcie_coef[z] > 0.0))
+            return AP_ERR_INVALID;
+        args.model[z] = m;
+        args.coef[z] = pcie_coef[z];
+    }
+    for (uint32_t g = 0; g < n_gpus; ++g) {
+        if (!(gpus[g].pcie_bytes_per_s > 0.0)) return AP_ERR_INVALID;
+        args.pcie[g] = gpus[g].pcie_bytes_per_s;
+    }
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return AP_ERR_DEVICE;
+    if (device < 0 || device >= kScratchDevices) return AP_ERR_RANGE;
+    unsigned long long* tau = nullptr;
+    {
+        std::lock_guard<std::mutex> hold(trace_scratch_lock);
+        if (!trace_scratch_at[device]) {                      // the first call on this device, which is current
+            void* at = nullptr;
+            if (hipGetSymbolAddress(&at, HIP_SYMBOL(scratch)) != hipSuccess || !at) {
+                (void)hipGetLastError();
+                return AP_ERR_DEVICE;
+            }
+            trace_scratch_at[device] = static_cast<unsigned long long*>(at);
+        }
+        tau = trace_scratch_at[device];
+    }
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    // every entry the second kernel reads is written by the first: nothing of an earlier call is looked at
+    hipLaunchKernelGGL(k_transfer_times_from_args, dim3((n_models * n_gpus + kRoofThreads - 1u) / kRoofThreads), dim3(kRoofThreads), 0,
+                       stream, args, n_models, n_gpus, tau);
+    TraceTimeParams tp{};
+    tp.tau_ns = tau;
+    tp.plans = d_plans;
+    tp.n_intervals = d_n_intervals;
+    tp.sched_ns = reinterpret_cast<const unsigned long long*>(d_sched_ns);
+    tp.stale_ns = reinterpret_cast<const unsigned long long*>(d_stale_ns);
+    tp.serve_ns = reinterpret_cast<const unsigned long long*>(d_serve_ns);
+    tp.C = C; tp.N_max = N_max; tp.Z = n_models; tp.G = n_gpus;
+    tp.load_changed_only = load_scope == AP_LOAD_CHANGED ? 1u : 0u;
+    hipLaunchKernelGGL(k_trace_time, dim3((C + kRoofThreads - 1u) / kRoofThreads), dim3(kRoofThreads), 0, stream, tp, d_out);
+    if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
     return AP_OK;
 }
 

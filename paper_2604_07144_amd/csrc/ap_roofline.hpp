@@ -157,6 +157,27 @@ __global__ __launch_bounds__(kRoofThreads) void k_transfer_times(const RoofGroup
     tau_ns[i] = roof_ns((roof_weight_bytes(models[z]) / pcie[g]) * coef[z]);
 }
 
+// The same with the descriptions passed in the kernel's arguments (no device copy of them has to exist):
+// `a` holds n_models models with their coefficients and the PCIe bandwidth of n_gpus GPU types.
+constexpr uint32_t kTransferArgModels = 64, kTransferArgGpus = 16;
+struct TransferArgs {
+    ap_model model[kTransferArgModels];
+    double coef[kTransferArgModels];
+    double pcie[kTransferArgGpus];
+};
+__global__ __launch_bounds__(kRoofThreads) void k_transfer_times_from_args(TransferArgs a, uint32_t n_models, uint32_t n_gpus,
+                                                                           unsigned long long* __restrict__ tau_ns) {
+#pragma clang fp contract(off)
+    const uint32_t i = blockIdx.x * kRoofThreads + threadIdx.x;
+    if (i >= n_models * n_gpus) return;
+    const uint32_t z = i / n_gpus, g = i - z * n_gpus;
+    const ap_model& m = a.model[z];
+    RoofGroup o{};
+    o.L = m.layers; o.H = m.hidden; o.I = m.intermediate; o.V = m.vocab; o.A = m.heads; o.K = m.kv_heads;
+    o.e = (double)m.weight_bits / 8.0;
+    tau_ns[i] = roof_ns((roof_weight_bytes(o) / a.pcie[g]) * a.coef[z]);
+}
+
 struct TraceTimeParams {
     const unsigned long long* tau_ns;     // [Z][G]
     const ap_placement* plans;            // [C][N_max][Z][G]
