@@ -49,6 +49,10 @@ class GpuWorkload:
         torch.cuda.synchronize()
         return to_records(d_out)
 
+    def counts(self):
+        """(candidates scored, candidates that went through the exact replay kernels) since the cost model was set."""
+        return binding.ap_eval_counts_get(self.handle)
+
     def set_parent(self, parent: np.ndarray, max_children: int) -> None:
         binding.ap_parent_set(self.handle, parent, max_children)
 

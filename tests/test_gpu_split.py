@@ -1,0 +1,122 @@
+"""GPU parity for replicas that differ or have availability windows, where the library cuts every replica's trace
+into a listed part (replayed one queue per lane) and a streamed part (scored on arrival): every branch of that path
+against the CPU oracle, byte for byte, through the C ABI; ``ap_eval_counts_get`` tells which candidates the path
+settled itself and which it handed to the general replay."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+from paper_2604_07144_amd import traces                   # noqa: E402
+from tests.gpu_harness import GpuWorkload, assert_same, oracle_for   # noqa: E402
+
+U64MAX = 0xFFFFFFFFFFFFFFFF
+STD, FAST, SLOW = traces.COEF_STANDARD, traces.COEF_FAST, traces.COEF_SLOW
+
+
+def elastic(n, M, B, rate, seed, *, closing=True, **kw):
+    """Poisson arrivals at `rate` per second, lognormal lengths, three kinds of replica in turn, windows drawn
+    inside the trace (closing=False: replicas come up but never leave)."""
+    rng = np.random.default_rng(seed)
+    arrival = (np.floor(np.cumsum(rng.exponential(1.0 / rate, n)) * 1e6) + 123_456_789).astype(np.uint64)
+    prompt = np.clip(np.floor(rng.lognormal(6.0, 1.0, n)), 16, 4096)
+    out = np.clip(np.floor(rng.lognormal(5.0, 1.0, n)), 1, 1024)
+    xy = rng.integers(int(arrival[0]), int(arrival[-1]) + 1, size=(M, 2)).astype(np.uint64)
+    t_on = xy.min(1)
+    t_off = xy.max(1) if closing else np.full(M, U64MAX, dtype=np.uint64)
+    return traces.custom_trace(arrival, prompt, out, [[STD, FAST, SLOW][m % 3] for m in range(M)], t_on, t_off, B=B, **kw)
+
+
+def rows(C, n, hi, seed):
+    return np.random.default_rng(seed).integers(0, hi, size=(C, n)).astype(np.uint16)
+
+
+def both(tr, r, what, **override):
+    with GpuWorkload(tr, **override) as g:
+        got = g.eval(r)
+        counts = g.counts()
+    assert_same(got, oracle_for(tr, **override).eval_batch(r, nthreads=8), what)
+    assert counts[0] == r.shape[0]
+    return got, counts
+
+
+def test_elastic_cluster_settled_without_the_general_replay():
+    """A calm trace (far fewer requests in service than slots): backlogs behind t_on are replayed from their lists,
+    the rest is scored on arrival, a third of the requests is rejected, so the p99 values are the penalty."""
+    tr = elastic(20000, 48, 64, 1200.0, seed=1)
+    got, (scored, replayed) = both(tr, rows(70, tr.R, 48, seed=2), "elastic, calm")
+    assert replayed == 0 and int(got["n_rejected"].min()) > tr.R // 100
+    got, (_, replayed) = both(tr, rows(5, tr.R, 50, seed=3), "elastic, calm, some unknown replica ids", B=16)
+    assert replayed == 0
+
+
+def test_replicas_that_never_leave_need_the_histograms():
+    """No window closes: nothing is rejected, so the percentiles come from the histograms - streamed requests counted
+    in LDS, listed ones added in device memory."""
+    tr = elastic(15000, 24, 32, 900.0, seed=4, closing=False)
+    got, (_, replayed) = both(tr, rows(40, tr.R, 24, seed=5), "elastic, nobody leaves")
+    assert replayed <= 4 and int(got["n_rejected"].max()) == 0          # the split is a guess: a few may be handed back
+    assert int(got["p99_ttft_us"].min()) > 100_000                      # waiting behind t_on dominates the tail
+
+
+def test_candidates_that_avoid_closed_replicas_among_candidates_that_do_not():
+    """Most rows spread requests over all replicas (many rejections: no histograms needed); two rows use only replicas
+    that are up throughout, so they reject nothing and are streamed a second time with histograms."""
+    tr = elastic(12000, 20, 64, 800.0, seed=6)
+    t_on, t_off = tr.t_on_us.copy(), tr.t_off_us.copy()
+    t_on[[3, 7]], t_off[[3, 7]] = 0, U64MAX
+    r = rows(30, tr.R, 20, seed=7)
+    r[4] = np.where(np.arange(tr.R) % 2 == 0, 3, 7)
+    r[11] = 7
+    got, (_, replayed) = both(tr, r, "mixed need for histograms", t_on_us=t_on, t_off_us=t_off)
+    assert int(got["n_rejected"][4]) == 0 and int(got["n_rejected"][11]) == 0 and int(got["n_rejected"][0]) > 120
+    assert replayed <= 3
+
+
+def test_a_backlog_far_beyond_the_guess_goes_to_the_general_replay():
+    """Every request on one replica that comes up late: its backlog is twenty times what an even spread would give,
+    it has not drained where the streamed part begins, and the candidate is handed to the general replay."""
+    tr = elastic(16000, 20, 64, 600.0, seed=8, closing=False)
+    middle = int(np.argsort(tr.t_on_us)[8])                             # comes up some way into the trace
+    r = rows(12, tr.R, 20, seed=9)
+    r[5] = middle
+    got, (_, replayed) = both(tr, r, "one overloaded replica")
+    assert 1 <= replayed <= 3
+
+
+def test_dense_trace_lists_every_request():
+    """More requests in service than a replica has slots at almost any moment: nothing can be scored on arrival, every
+    request that is not rejected goes through its replica's list."""
+    tr = elastic(9000, 6, 8, 20000.0, seed=10)
+    got, (_, replayed) = both(tr, rows(10, tr.R, 6, seed=11), "dense, windows")
+    assert replayed == 0
+    tr = elastic(9000, 6, 5, 20000.0, seed=12, closing=False, slo_ttft_us=4000, slo_tpot_us=40)
+    both(tr, rows(10, tr.R, 7, seed=13), "dense, no rejections, tight objectives")
+
+
+def test_small_penalty_keeps_the_histograms():
+    """A penalty latency below the served latencies: rejected requests do not sit on top of the histogram, so the
+    percentiles are never read off the penalty."""
+    tr = elastic(10000, 16, 64, 700.0, seed=14, penalty_us=900)
+    both(tr, rows(16, tr.R, 16, seed=15), "penalty below the latencies")
+
+
+def test_more_candidates_than_one_batch_of_scratch():
+    """The scratch area holds a fixed number of candidates' lists (about 1 GiB / 210 KiB here); a call with more
+    candidates is worked off in batches."""
+    tr = elastic(60000, 64, 64, 2500.0, seed=16)
+    C = 5400
+    r = rows(C, tr.R, 64, seed=17)
+    with GpuWorkload(tr) as g:
+        got = g.eval(r)
+    pick = np.unique(np.concatenate([np.arange(0, C, 37), np.arange(C - 450, C)]))
+    assert_same(got[pick], oracle_for(tr).eval_batch(r[pick], nthreads=8), "several batches")
+
+
+@pytest.mark.parametrize("n,M,B", [(1, 3, 2), (63, 5, 64), (1024, 64, 64), (1025, 65, 8), (4097, 100, 33), (2047, 2, 1)])
+def test_tile_and_table_edges(n, M, B):
+    tr = elastic(n, M, B, 2000.0, seed=n + M)
+    both(tr, rows(9, n, M + 1, seed=n), f"edges n={n} M={M} B={B}")
+    still = elastic(n, M, B, 2000.0, seed=n + M + 1, closing=False)
+    both(still, rows(9, n, M, seed=n + 1), f"edges, nobody leaves n={n} M={M} B={B}")
