@@ -37,6 +37,12 @@ MEASURED_TRAFFIC = {
     4: ("866975664060e48ab97bb7c1cbdcb41dd884b6cedbd79379e30c42255bbf46df", 4308109757),
     3: ("866975664060e48ab97bb7c1cbdcb41dd884b6cedbd79379e30c42255bbf46df", 544024275),
 }
+# Wave-instructions per candidate-request of one ap_eval_candidates call (all its kernels), from rocprofv3 --pmc
+# SQ_INSTS_VALU / SQ_INSTS_SALU / SQ_INSTS_LDS; same validity rule.  The chip issues at most 256 CUs x 4 SIMDs x
+# 2.4 GHz / 4 cycles = 6.1e11 64-lane vector instructions per second.
+VALU_PEAK_PER_S = 256 * 4 * 2.4e9 / 4
+MEASURED_ALU = {
+}
 # the same for one ap_eval_children call on the sparse form of configs[4]
 MEASURED_TRAFFIC_CHILDREN = {4: ("866975664060e48ab97bb7c1cbdcb41dd884b6cedbd79379e30c42255bbf46df", 131147374)}
 
@@ -87,6 +93,78 @@ def algorithmic_bytes(C: int, R: int, n_types: int) -> int:
     """Bytes the method itself must move per call: every uint16 assignment once, one 64-byte
     record per candidate, the per-request tables once."""
     return 2 * C * R + 64 * C + TABLE_BYTES_PER_REQUEST * n_types * R
+
+
+def time_calls(step, stream, steps: int, warmup: int, settle_ms: float = 60.0):
+    """`warmup` untimed calls - and as many more as it takes to keep the device busy for `settle_ms`, so that the
+    clocks have settled however short a call is - then exactly `steps` timed calls, each between two HIP events on
+    the stream the kernels are launched on.  Returns (wall seconds of the timed calls, device ms per call)."""
+    import torch
+    t0 = time.perf_counter()
+    done = 0
+    while done < warmup or (time.perf_counter() - t0) * 1e3 < settle_ms:
+        step()
+        done += 1
+        if done % 8 == 0 or done >= warmup:
+            torch.cuda.synchronize()
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    t0 = time.perf_counter()
+    for a, b in ev:
+        a.record(stream)
+        step()
+        b.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return wall, [a.elapsed_time(b) for a, b in ev]
+
+
+def upload_rows(tr, C: int):
+    """Candidate rows 0..C of a trace, drawn and uploaded in slabs; returns the device tensor [C][R] (2-byte elements)."""
+    import torch
+    d_assign = torch.empty((C, tr.R), dtype=torch.int16, device="cuda")
+    slab = max(1, (256 << 20) // (2 * tr.R))
+    for lo in range(0, C, slab):
+        hi = min(C, lo + slab)
+        d_assign[lo:hi] = torch.from_numpy(tr.assignment_rows(lo, hi).view(np.int16)).cuda()
+    return d_assign
+
+
+def side_workload(cfg: int, rate_scale: float, C: int, d_assign, steps: int, warmup: int, label: str) -> dict:
+    """One more workload timed the same way as the main one (same protocol, fewer words): device time per
+    ap_eval_candidates call, throughput, roofline fraction on its own algorithmic bytes, how many candidates went
+    through the exact replay.  `d_assign` may be shared with another workload whose rows are drawn the same way."""
+    import torch
+    from paper_2604_07144_amd import binding, traces
+    tr = traces.make_trace(cfg, rate_scale=rate_scale)
+    n_types = len({tuple(int(x) for x in row) for row in tr.coef})
+    if d_assign is None:
+        d_assign = upload_rows(tr, C)
+    d_out = torch.zeros((C, 8), dtype=torch.int64, device="cuda")
+    stream = torch.cuda.current_stream()
+    h = binding.ap_workload_create(tr.arrival_us, tr.prompt_len, tr.out_len)
+    try:
+        binding.ap_costmodel_set(h, binding.make_replicas(tr.coef, tr.t_on_us, tr.t_off_us), tr.B,
+                                 tr.slo_ttft_us, tr.slo_tpot_us, tr.penalty_us)
+
+        def step():
+            binding.ap_eval_candidates(h, d_assign.data_ptr(), C, d_out.data_ptr(), stream.cuda_stream)
+
+        wall, ms = time_calls(step, stream, steps, warmup)
+        scored, replayed = binding.ap_eval_counts_get(h)
+    finally:
+        binding.ap_workload_destroy(h)
+    alg = algorithmic_bytes(C, tr.R, n_types)
+    avg_s = float(np.mean(ms)) * 1e-3
+    full = C == tr.C and rate_scale == 1.0
+    return {"workload": f"configs[{cfg}] {tr.spec.name}: C={C} R={tr.R} M={tr.M} B={tr.B}"
+                        + (f" arrival rate x{rate_scale:g}" if rate_scale != 1.0 else "") + label,
+            "value": C * tr.R / (wall / steps), "unit": "sims/s", "ms_per_step": wall * 1e3 / steps,
+            "kernel_ms_avg": avg_s * 1e3, "kernel_ms_min": float(np.min(ms)),
+            "roofline": {"bound": "hbm", "achieved": alg / avg_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": alg / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": measured_traffic(cfg) if full else None,
+                         "algorithmic_bytes": alg},
+            "replayed_fraction": replayed / max(1, scored)}, d_assign
 
 
 def agentic_bench(args) -> int:
@@ -155,6 +233,8 @@ def main() -> int:
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the oracle sample (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-children", action="store_true", help="skip the sparse (edit-list) leg of a mutation sweep")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the side workloads of the default run (configs[3], configs[2], the saturated variants)")
     ap.add_argument("--cost-tables", action="store_true",
                     help="pass the configuration's cost model as per-type tables (ap_costtable_set) instead of coefficients")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -182,11 +262,8 @@ def main() -> int:
     n_types = len({tuple(int(x) for x in row) for row in tr.coef})
 
     # inputs resident in HBM before anything is timed (rows drawn and uploaded in slabs)
-    d_assign = torch.empty((C, R), dtype=torch.int16, device="cuda")
+    d_assign = upload_rows(tr, C)
     slab = max(1, (256 << 20) // (2 * R))
-    for lo in range(0, C, slab):
-        hi = min(C, lo + slab)
-        d_assign[lo:hi] = torch.from_numpy(tr.assignment_rows(lo, hi).view(np.int16)).cuda()
     d_out = torch.zeros((C, 8), dtype=torch.int64, device="cuda")
 
     h = binding.ap_workload_create(tr.arrival_us, tr.prompt_len, tr.out_len)
@@ -208,19 +285,10 @@ def main() -> int:
         def step():
             binding.ap_eval_candidates(h, d_assign.data_ptr(), C, d_out.data_ptr(), stream.cuda_stream)
 
-        for _ in range(args.warmup):
-            step()
-        torch.cuda.synchronize()
         # HIP events on the stream the kernels are launched on: per-launch device time
-        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-        t0 = time.perf_counter()
-        for a, b in ev:
-            a.record(stream)
-            step()
-            b.record(stream)
-        torch.cuda.synchronize()
-        wall = time.perf_counter() - t0
-        kernel_ms = [a.elapsed_time(b) for a, b in ev]
+        before = binding.ap_eval_counts_get(h)
+        wall, kernel_ms = time_calls(step, stream, args.steps, args.warmup)
+        after = binding.ap_eval_counts_get(h)
         got = d_out.cpu().numpy().view(binding.METRICS_DTYPE).reshape(-1)
 
         # The same candidates in their sparse form, where the configuration is a mutation sweep: every row is
@@ -260,18 +328,7 @@ def main() -> int:
                 binding.ap_eval_children(h, d_first.data_ptr(), d_request.data_ptr(), d_replica.data_ptr(), C,
                                          d_out2.data_ptr(), stream.cuda_stream)
 
-            for _ in range(args.warmup):
-                child_step()
-            torch.cuda.synchronize()
-            ev2 = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-            t0 = time.perf_counter()
-            for a, b in ev2:
-                a.record(stream)
-                child_step()
-                b.record(stream)
-            torch.cuda.synchronize()
-            child_wall = time.perf_counter() - t0
-            child_ms = [a.elapsed_time(b) for a, b in ev2]
+            child_wall, child_ms = time_calls(child_step, stream, args.steps, args.warmup)
             got2 = d_out2.cpu().numpy().view(binding.METRICS_DTYPE).reshape(-1)
             # bytes this form must move: the lists (4 + 2 per edit, 4 per child), one record per child,
             # the parent row and the per-request tables once
@@ -321,7 +378,34 @@ def main() -> int:
                      "kernel_ms_min": float(np.min(kernel_ms)), "algorithmic_bytes": alg},
         "mean_ttft_us_row0": int(got["sum_ttft_us"][0]) / R,
         "rejected_row0": int(got["n_rejected"][0]),
+        # of the candidates scored by the calls above: how many the exact shortcuts settled, how many went through
+        # the request-by-request replay
+        "screened": {"candidates": after[0] - before[0], "replayed": after[1] - before[1],
+                     "settled_by_shortcut": (after[0] - before[0]) - (after[1] - before[1])},
     }
+    alu = MEASURED_ALU.get(args.config)
+    if full_batch and alu is not None and alu[0] == kernel_source_hash():
+        result["alu"] = dict(alu[1], unit="wave-instructions per candidate-request, rocprofv3 SQ_INSTS_* (see profiles/)",
+                             valu_peak_per_s=VALU_PEAK_PER_S,
+                             valu_per_s=alu[1]["valu"] * sims / avg_kernel_s,
+                             valu_frac=alu[1]["valu"] * sims / avg_kernel_s / VALU_PEAK_PER_S)
+
+    # Side workloads of the default run, each timed like the main one: configs[3] (the other configuration the
+    # target names), configs[2] (the one-wavefront screening kernel at its stated size) and the saturated variants
+    # (arrival rate x100; NOT part of the benchmark spec: the stated traces are lightly loaded).
+    if args.config == 4 and full_batch and not args.no_extras:
+        side = {}
+        side["configs3"], d_rows3 = side_workload(3, 1.0, traces.SPECS[3].C, None, args.steps, args.warmup, "")
+        alu3 = MEASURED_ALU.get(3)
+        if alu3 is not None and alu3[0] == kernel_source_hash():
+            side["configs3"]["alu"] = alu3[1]
+        sat3, _ = side_workload(3, 100.0, traces.SPECS[3].C, d_rows3, args.steps, args.warmup, " (outside BASELINE.json)")
+        del d_rows3
+        side["configs2"], _ = side_workload(2, 1.0, traces.SPECS[2].C, None, args.steps, args.warmup, "")
+        sat4, _ = side_workload(4, 100.0, 2048, d_assign[:2048], max(3, args.steps // 4), min(args.warmup, 2),
+                                " first 2048 rows (outside BASELINE.json)")
+        side["saturated"] = {"configs3_x100": sat3, "configs4_x100": sat4}
+        result.update(side)
 
     if children is not None:
         result["sparse_children"] = children
@@ -338,7 +422,7 @@ def main() -> int:
             t0 = time.perf_counter()
             orc.eval_batch(probe, nthreads=threads)
             per_row_cpu_s = max(1e-6, (time.perf_counter() - t0) * threads / probe.shape[0])
-            n_cpu = int(min(C, max(threads, 15.0 / per_row_cpu_s)))
+            n_cpu = int(min(C, max(1024, 15.0 / per_row_cpu_s)))     # at least 1024 rows whenever a subset is timed
         pick = np.unique(np.linspace(0, C - 1, n_cpu).astype(np.int64))
         rows = np.stack([tr.assignment_row(int(c)) for c in pick])
         t0 = time.perf_counter()
