@@ -147,6 +147,13 @@ struct ap_workload {
     SplitParams split_params{};
 };
 
+typedef void (*split_fn)(SplitParams, const uint16_t*, uint32_t, uint32_t, uint32_t, PendingWord);
+static split_fn split_kernel(uint32_t hist_mode, int narrow) {
+    static const split_fn variants[6] = {k_split_candidates<0u, false>, k_split_candidates<1u, false>, k_split_candidates<2u, false>,
+                                         k_split_candidates<0u, true>,  k_split_candidates<1u, true>,  k_split_candidates<2u, true>};
+    return variants[hist_mode + (narrow ? 3u : 0u)];
+}
+
 // The dense path on C rows: screening where it applies, then the exact replay of what is left.
 // marked: only rows whose record carries the pending mark are looked at (screening applies).
 static PendingWord take_pending_word(const ap_workload* w) {
@@ -194,19 +201,21 @@ static ap_status launch_dense(const ap_workload* w, const uint16_t* d_assign, ui
         for (uint32_t c0 = 0; c0 < C; c0 += w->split_batch) {
             const uint32_t n = std::min(w->split_batch, C - c0);
             const uint32_t grid = std::min(n, w->n_cu * 16u);
-            typedef void (*split_fn)(SplitParams, const uint16_t*, uint32_t, uint32_t, uint32_t, PendingWord);
-            static const split_fn split[4] = {k_split_candidates<false, false>, k_split_candidates<true, false>,
-                                              k_split_candidates<false, true>, k_split_candidates<true, true>};
-            const int narrow = sp.M <= 64u ? 2 : 0;
-            if (w->split_expect_lazy)
-                hipLaunchKernelGGL(split[narrow], dim3(grid), dim3(kSplitThreads), w->split_lds_bytes, stream, sp, d_assign, c0, n,
-                                   0u, flags);
-            hipLaunchKernelGGL(split[narrow + 1], dim3(grid), dim3(kSplitThreads), w->split_lds_bytes_hist, stream, sp, d_assign,
-                               c0, n, w->split_expect_lazy ? 1u : 0u, flags);
+            // First without histograms where the candidates are expected to be settled by penalty, or where nothing is
+            // streamed at all; then with histograms, for every candidate or for those the first pass marked.
+            const int narrow = sp.M <= 64u ? 1 : 0;
+            const bool plain_first = w->split_expect_lazy || sp.any_streamed == 0u;
+            if (plain_first)
+                hipLaunchKernelGGL(split_kernel(0u, narrow), dim3(grid), dim3(kSplitThreads), w->split_lds_bytes, stream, sp,
+                                   d_assign, c0, n, 0u, flags);
+            if (sp.any_streamed != 0u)
+                hipLaunchKernelGGL(split_kernel(sp.wide ? 2u : 1u, narrow), dim3(grid), dim3(kSplitThreads),
+                                   w->split_lds_bytes_hist, stream, sp, d_assign, c0, n, plain_first ? 1u : 0u, flags);
             if (sp.n_queues != 0u)
                 hipLaunchKernelGGL(replay, dim3(sp.n_queues * ((n + kWave - 1u) / kWave)), dim3(kWave), 0, stream, sp, n);
-            hipLaunchKernelGGL(k_merge_candidates, dim3(std::min((n + kThreads - 1u) / kThreads, w->n_cu * 4u)), dim3(kThreads),
-                               w->reduce_lds_bytes, stream, w->reduce_eval, sp, d_out, c0, n, flags);
+            hipLaunchKernelGGL(sp.wide ? k_merge_candidates<false> : k_merge_candidates<true>,
+                               dim3(std::min((n + kThreads - 1u) / kThreads, w->n_cu * 4u)), dim3(kThreads), w->reduce_lds_bytes,
+                               stream, w->reduce_eval, sp, d_out, c0, n, flags);
         }
         if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
     }
@@ -353,7 +362,8 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
                             const std::vector<uint64_t>& kind_sum, const std::vector<uint64_t>& kind_longest,
                             uint64_t latest_finish_bound) {
     const uint32_t R = w->R, M = w->params.M, B = w->params.B;
-    if (!w->d_req8 || R >= 65536u) return AP_OK;            // 16-bit lengths and 16-bit histogram counts only
+    if (!w->d_req8) return AP_OK;                            // request records with 16-bit lengths only
+    const bool wide = R >= 65536u;                           // two range words per replica, 32-bit histogram counts
     // The kernels multiply with 24-bit factors and add up a tile's sixteen latencies per lane in 32 bits.
     uint64_t longest_tpot = 0, longest_prefill = 0;
     for (uint32_t m = 0; m < M; ++m) {
@@ -370,7 +380,7 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
     std::vector<uint32_t> order;
     try {
         depth_from.assign((size_t)R + 1u, 0u);
-        tab.assign(2u * (AP_MAX_REPLICAS + 1u) + 4u * kinds.size(), 0u);
+        tab.assign(3u * (AP_MAX_REPLICAS + 1u) + 4u * kinds.size(), 0u);
         queue.resize(M);
         // D(r): sweep in arrival order over a min-heap of the finish times of requests that start on arrival
         std::vector<uint64_t> heap;
@@ -397,6 +407,7 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
     const uint32_t* arr = w->h_arrival.data();
     uint32_t longest_list = 0;
     uint64_t expect_rejected = 0;
+    bool any_streamed = false;
     for (uint32_t m = 0; m < M; ++m) {
         const DevReplica& d = dev[m];
         const uint32_t i_on = (uint32_t)(std::lower_bound(arr, arr + R, d.t_on) - arr);
@@ -421,8 +432,10 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
             i_list = (uint32_t)(std::lower_bound(arr, arr + R, (uint32_t)std::min<uint64_t>(t_target, kNever)) - arr);
         }
         i_list = std::min(std::max(i_list, i_calm), i_off);
-        tab[m] = i_list | (i_off << 16);
-        tab[AP_MAX_REPLICAS + 1u + m] = (uint32_t)ki;
+        tab[m] = wide ? i_list : (i_list | (i_off << 16));
+        tab[AP_MAX_REPLICAS + 1u + m] = i_off;
+        tab[2u * (AP_MAX_REPLICAS + 1u) + m] = (uint32_t)ki;
+        any_streamed = any_streamed || i_list < i_off;
         SplitQueue q{};
         q.a = d.a; q.b = d.b; q.c = d.c; q.d = d.d; q.t_on = d.t_on; q.t_off = d.t_off;
         q.i_list = i_list;
@@ -433,8 +446,9 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
         expect_rejected += R - i_off;
     }
     tab[M] = 0u;                                             // unknown replica ids: rejected on arrival
+    tab[AP_MAX_REPLICAS + 1u + M] = 0u;
     for (size_t k = 0; k < kinds.size(); ++k) {
-        uint32_t* co = &tab[2u * (AP_MAX_REPLICAS + 1u) + 4u * k];
+        uint32_t* co = &tab[3u * (AP_MAX_REPLICAS + 1u) + 4u * k];
         co[0] = replicas[kinds[k]].prefill_base_us; co[1] = replicas[kinds[k]].prefill_per_tok_us;
         co[2] = replicas[kinds[k]].decode_base_us;  co[3] = replicas[kinds[k]].decode_per_kctx_us;
     }
@@ -455,10 +469,14 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
     const bool penalty_on_top = w->params.penalty_bin > ap_hist_bin(latest_finish_bound);
     sp.lazy_from = penalty_on_top ? R - w->params.k99 + 1u : kNever;
     sp.all_within = (longest_prefill <= w->params.slo_ttft && longest_tpot <= w->params.slo_tpot) ? 1u : 0u;
+    sp.wide = wide ? 1u : 0u;
+    sp.any_streamed = any_streamed ? 1u : 0u;
+    sp.hist_words = wide ? 3u * kBins : 3u * kBins / 2u;
     // LDS of the streaming kernel
     uint32_t off = 0;
-    const uint32_t hist_bytes = 3u * kBins * 2u;
+    const uint32_t hist_bytes = sp.hist_words * 4u;
     sp.off_range = off; off += align_up((M + 1u) * 4u, 16u);
+    sp.off_range_off = off; off += wide ? align_up((M + 1u) * 4u, 16u) : 0u;
     sp.off_kind = off;  off += align_up((M + 1u) * 4u, 16u);
     sp.off_coef = off;  off += (uint32_t)kinds.size() * 16u;
     sp.off_acc = off;   off += 64u;
@@ -472,19 +490,30 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
     sp.wave_bytes = wb;
     off += kSplitWaves * wb;
     sp.off_hist = off;
-    if (off + hist_bytes > 64u * 1024u) return AP_OK;       // a replica table that large stays with the general replay
+    int lds_cap = 0;
+    if (hipDeviceGetAttribute(&lds_cap, hipDeviceAttributeMaxSharedMemoryPerBlock, w->device) != hipSuccess) return AP_ERR_DEVICE;
+    if (off + hist_bytes > (uint32_t)lds_cap) return AP_OK;  // a replica table that large stays with the general replay
     w->split_lds_bytes = off;
     w->split_lds_bytes_hist = off + hist_bytes;
+    const int narrow = M <= 64u ? 1 : 0;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(split_kernel(0u, narrow)), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)off) != hipSuccess ||
+        hipFuncSetAttribute(reinterpret_cast<const void*>(split_kernel(wide ? 2u : 1u, narrow)),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)(off + hist_bytes)) != hipSuccess) {
+        (void)hipGetLastError();
+        return AP_ERR_DEVICE;
+    }
     w->split_slots = B <= 8u ? 8u : B <= 16u ? 16u : B <= 32u ? 32u : 64u;
 
     // scratch for one batch of candidates: lists, run descriptors, partial records, histograms
-    const size_t per_cand = (size_t)sp.n_list_tiles * sp.tile_cap * 2u + (size_t)sp.n_list_tiles * M * 4u + sizeof(SplitPartial) +
-                            hist_bytes;
+    const size_t per_cand = (size_t)sp.n_list_tiles * sp.tile_cap * (2u + 4u) + (size_t)sp.n_list_tiles * M * 4u +
+                            sizeof(SplitPartial) + hist_bytes;
     uint32_t batch = (uint32_t)std::min<size_t>(16384u, std::max<size_t>(64u, ((size_t)1 << 30) / per_cand));
     batch = batch / 64u * 64u;
     auto carve = [](size_t& at, size_t bytes) { const size_t here = at; at = (at + bytes + 255u) / 256u * 256u; return here; };
     size_t total = 0;
     const size_t o_lists = carve(total, (size_t)batch * sp.n_list_tiles * sp.tile_cap * 2u);
+    const size_t o_bins = carve(total, (size_t)batch * sp.n_list_tiles * sp.tile_cap * 4u);
     const size_t o_desc = carve(total, (size_t)batch * sp.n_list_tiles * M * 4u);
     const size_t o_part = carve(total, (size_t)batch * sizeof(SplitPartial));
     const size_t o_hist = carve(total, (size_t)batch * hist_bytes);
@@ -498,7 +527,7 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
         }
         w->split_scratch_bytes = total;
     }
-    const size_t tab_bytes = 4u * (2u * (AP_MAX_REPLICAS + 1u) + 4u * (size_t)AP_MAX_REPLICAS);
+    const size_t tab_bytes = 4u * (3u * (AP_MAX_REPLICAS + 1u) + 4u * (size_t)AP_MAX_REPLICAS + 4u);
     if ((!w->d_split_tab && hipMalloc(&w->d_split_tab, tab_bytes) != hipSuccess) ||
         (!w->d_split_queue && hipMalloc(&w->d_split_queue, sizeof(SplitQueue) * AP_MAX_REPLICAS) != hipSuccess) ||
         (!w->d_split_order && hipMalloc(&w->d_split_order, sizeof(uint32_t) * AP_MAX_REPLICAS) != hipSuccess)) {
@@ -509,19 +538,22 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
         hipMemcpy(w->d_split_queue, queue.data(), sizeof(SplitQueue) * M, hipMemcpyHostToDevice) != hipSuccess ||
         (!order.empty() &&
          hipMemcpy(w->d_split_order, order.data(), sizeof(uint32_t) * order.size(), hipMemcpyHostToDevice) != hipSuccess) ||
-        hipFuncSetAttribute(reinterpret_cast<const void*>(&k_merge_candidates), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)w->reduce_lds_bytes) != hipSuccess) {
+        hipFuncSetAttribute(wide ? reinterpret_cast<const void*>(&k_merge_candidates<false>)
+                                 : reinterpret_cast<const void*>(&k_merge_candidates<true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)w->reduce_lds_bytes) != hipSuccess) {
         (void)hipGetLastError();
         return AP_ERR_DEVICE;
     }
     sp.req8 = w->d_req8;
     sp.tab.range = w->d_split_tab;
-    sp.tab.kind = w->d_split_tab + (AP_MAX_REPLICAS + 1u);
-    sp.tab.coef = reinterpret_cast<const uint4*>(w->d_split_tab + 2u * (AP_MAX_REPLICAS + 1u));
+    sp.tab.range_off = w->d_split_tab + (AP_MAX_REPLICAS + 1u);
+    sp.tab.kind = w->d_split_tab + 2u * (AP_MAX_REPLICAS + 1u);
+    sp.tab.coef = reinterpret_cast<const uint4*>(w->d_split_tab + 3u * (AP_MAX_REPLICAS + 1u));
     sp.tab.n_kinds = (uint32_t)kinds.size();
     sp.queue = w->d_split_queue;
     sp.order = w->d_split_order;
     sp.lists = reinterpret_cast<uint16_t*>(w->d_split_scratch + o_lists);
+    sp.bins = reinterpret_cast<uint32_t*>(w->d_split_scratch + o_bins);
     sp.desc = reinterpret_cast<uint32_t*>(w->d_split_scratch + o_desc);
     sp.part = reinterpret_cast<SplitPartial*>(w->d_split_scratch + o_part);
     sp.hist = reinterpret_cast<uint32_t*>(w->d_split_scratch + o_hist);
@@ -848,7 +880,7 @@ static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint
     }
     // ---- split evaluation: replicas that differ or have windows ---------------------------
     w->split = false;
-    if (!w->screen && !tabled && !use_pipeline) {
+    if (!w->screen && !tabled) {
         const ap_status st = plan_split(w, dev, replicas, kinds, worst_service, kind_sum, kind_longest, total);
         if (st != AP_OK) return st;
     }

@@ -39,21 +39,25 @@ namespace {
 // k99-th smallest value of each metric is the penalty latency itself (rejected requests are charged it,
 // Appendix "Serving Simulator", Memory Feasibility), provided every served latency falls in a lower bin, which
 // the host checks against its bound on all finish times.  Such a candidate is called settled-by-penalty below
-// and carries kFlagLazy; the others keep 16-bit histograms (in LDS while streaming, then in device memory where
-// the replay adds to them).
+// and carries kFlagLazy; the others keep histograms: the streamed requests are counted in LDS while the row is
+// read (and parked in device memory), the list replay leaves the bins of every listed request next to its list
+// entry, and k_merge_candidates adds the two up.
 constexpr uint32_t kSplitWaves = 4;
 constexpr uint32_t kSplitThreads = kSplitWaves * kWave;
 constexpr uint32_t kTile = 1024;                  // requests per tile: a list position fits 10 bits
 constexpr uint32_t kFlagNeedHist = 1u;            // streamed without histograms, but they are needed: stream again
 constexpr uint32_t kFlagFallback = 2u;            // the listed part left too many slots taken: general replay
 constexpr uint32_t kFlagLazy = 4u;                // the p99 values are the penalty latency
+constexpr uint32_t kFlagNoStreamHist = 8u;        // histograms needed, and no request of the candidate was streamed
+constexpr uint32_t kBinServed = 0x80000000u;      // bins word of a listed request: ttft bin | e2e bin << 12 | this if served
 
 // Per replica, for the streaming kernel, as three arrays (copied to LDS; an entry per replica and one more, index
 // M, for unknown replica ids: everything rejected).  Lanes look entries up by replica id, so consecutive ids must
-// fall into different LDS banks: one 32-bit word per replica holds both ranges (R is below 65536 on this path),
-// and the cost coefficients are stored once per kind of replica, which a second word names.
+// fall into different LDS banks: one 32-bit word per replica holds both ranges when R is below 65536 (else one
+// word each), and the cost coefficients are stored once per kind of replica, which another word names.
 struct SplitTables {
-    const uint32_t* range;                        // [M + 1] i_list | i_off << 16
+    const uint32_t* range;                        // [M + 1] i_list | i_off << 16; wide: i_list
+    const uint32_t* range_off;                    // wide only: [M + 1] i_off
     const uint32_t* kind;                         // [M + 1] index into coef
     const uint4* coef;                            // [n_kinds] a, b, c, d
     uint32_t n_kinds;
@@ -81,14 +85,18 @@ struct SplitParams {
     uint32_t* desc;                               // [batch][n_list_tiles][M] count << 16 | first list position
     uint16_t* lists;                              // [batch][n_list_tiles][tile_cap] tile-local request indices by replica
     SplitPartial* part;                           // [batch]
-    uint32_t* hist;                               // [batch][3 * kBins / 2] 16-bit counts, two per word
+    uint32_t* hist;                               // [batch][hist_words] the streamed requests' histograms
+    uint32_t* bins;                               // [batch][n_list_tiles][tile_cap] bins word of every listed request
+    uint32_t hist_words;                          // 3 * kBins / 2 (16-bit counts, R < 65536) or 3 * kBins
+    uint32_t wide;                                // R >= 65536: two range words per replica
+    uint32_t any_streamed;                        // some replica has a streamed part
     uint32_t R, M, B, key_bits;
     uint32_t n_tiles, n_list_tiles, tile_cap, n_queues;
     uint32_t slo_ttft, slo_tpot;
     uint32_t lazy_from;                           // rejected requests from which the p99 values are the penalty; kNever: never
     uint32_t all_within;                          // no request's prefill or time per token can exceed the objectives
     // byte offsets into the streaming kernel's dynamic LDS
-    uint32_t off_range, off_kind, off_coef, off_acc, off_wave, wave_bytes, w_pos, w_queue, w_list, w_same, off_hist;
+    uint32_t off_range, off_range_off, off_kind, off_coef, off_acc, off_wave, wave_bytes, w_pos, w_queue, w_list, w_same, off_hist;
 };
 
 // Streaming kernel.  One workgroup per candidate at a time; its wavefronts take the tiles of the row in turn
@@ -97,17 +105,20 @@ struct SplitParams {
 // replica, queues them in arrival order, ranks them (one ballot per bit of the replica id among 64 queued
 // requests at a time) into per-replica runs that start on multiples of 8 list positions, and writes the runs
 // and their descriptors out.
-// kHist: keep histograms of the streamed requests (needed unless the candidate is settled by penalty).
+// kHistMode: 0 keeps no histograms of the streamed requests (enough when the candidate is settled by penalty, or
+// when nothing is streamed at all), 1 keeps them with 16-bit counts (R < 65536), 2 with 32-bit counts.
 // only_flagged: look only at candidates that an earlier launch marked kFlagNeedHist.
 // kNarrow: at most 64 replicas, so a queued request (tile index and replica) fits 16 bits, which halves the queue.
-template <bool kHist, bool kNarrow>
+template <uint32_t kHistMode, bool kNarrow>
 __global__ __launch_bounds__(kSplitThreads, 5) void k_split_candidates(SplitParams p, const uint16_t* __restrict__ assign,
                                                                     uint32_t c0, uint32_t n_cand, uint32_t only_flagged,
                                                                     PendingWord flags) {
     extern __shared__ __align__(16) unsigned char lds[];
     pending_clear_next(flags);
+    constexpr bool kHist = kHistMode != 0u, kHist16 = kHistMode == 1u;
     uint32_t* hist = reinterpret_cast<uint32_t*>(lds + p.off_hist);          // kHist only
     uint32_t* range_of = reinterpret_cast<uint32_t*>(lds + p.off_range);
+    uint32_t* range_off_of = reinterpret_cast<uint32_t*>(lds + p.off_range_off);   // wide only
     uint32_t* kind_of = reinterpret_cast<uint32_t*>(lds + p.off_kind);
     uint4* coef_of = reinterpret_cast<uint4*>(lds + p.off_coef);
     unsigned long long* acc64 = reinterpret_cast<unsigned long long*>(lds + p.off_acc);
@@ -130,6 +141,7 @@ __global__ __launch_bounds__(kSplitThreads, 5) void k_split_candidates(SplitPara
     }
     for (uint32_t i = tid; i <= M; i += kSplitThreads) {
         range_of[i] = p.tab.range[i];
+        if (p.wide != 0u) range_off_of[i] = p.tab.range_off[i];
         kind_of[i] = p.tab.kind[i];
     }
     for (uint32_t i = tid; i < p.tab.n_kinds; i += kSplitThreads) coef_of[i] = p.tab.coef[i];
@@ -142,7 +154,7 @@ __global__ __launch_bounds__(kSplitThreads, 5) void k_split_candidates(SplitPara
         if (only_flagged && (p.part[cb].flags & kFlagNeedHist) == 0u) continue;     // the same word for every thread
         __syncthreads();                                                            // the last candidate's totals were read
         if (kHist)
-            for (uint32_t i = tid; i < 3u * kBins / 2u; i += kSplitThreads) hist[i] = 0u;
+            for (uint32_t i = tid; i < p.hist_words; i += kSplitThreads) hist[i] = 0u;
         if (tid < 10u) reinterpret_cast<uint32_t*>(acc64)[tid] = 0u;
         __syncthreads();
         const uint16_t* row = assign + (size_t)(c0 + cb) * R;
@@ -183,7 +195,7 @@ __global__ __launch_bounds__(kSplitThreads, 5) void k_split_candidates(SplitPara
 #pragma unroll
             for (uint32_t h = 0; h < kParts; ++h) {
                 uint4 record[kHalf];
-                uint32_t id[2u * kHalf], range[2u * kHalf], kind[2u * kHalf];
+                uint32_t id[2u * kHalf], from[2u * kHalf], upto[2u * kHalf], kind[2u * kHalf];   // listed below `from`, gone from `upto`
 #pragma unroll
                 for (uint32_t g = 0; g < kHalf; ++g) {
                     const uint32_t rl = (h * kHalf + g) * 2u * kWave + 2u * lane;
@@ -193,7 +205,14 @@ __global__ __launch_bounds__(kSplitThreads, 5) void k_split_candidates(SplitPara
                 }
 #pragma unroll
                 for (uint32_t i = 0; i < 2u * kHalf; ++i) {
-                    range[i] = range_of[id[i]];
+                    const uint32_t word = range_of[id[i]];
+                    if (p.wide != 0u) {
+                        from[i] = word;
+                        upto[i] = range_off_of[id[i]];
+                    } else {
+                        from[i] = word & 0xFFFFu;
+                        upto[i] = word >> 16;
+                    }
                     kind[i] = kind_of[id[i]];
                 }
 #pragma unroll
@@ -204,8 +223,8 @@ __global__ __launch_bounds__(kSplitThreads, 5) void k_split_candidates(SplitPara
                         const uint32_t i = 2u * g + e;
                         const uint32_t rl = (h * kHalf + g) * 2u * kWave + 2u * lane + e, r = r0 + rl;
                         const bool in = kWhole || rl < n;
-                        listed[e] = in && r < (range[i] & 0xFFFFu);                 // i_list <= i_off
-                        const bool rejected = in && r >= (range[i] >> 16);
+                        listed[e] = in && r < from[i];                              // i_list <= i_off
+                        const bool rejected = in && r >= upto[i];
                         const bool streamed = in && !listed[e] && !rejected;
                         n_rej += (uint32_t)__popcll(__ballot(rejected));
                         if (p.all_within != 0u) n_ok += (uint32_t)__popcll(__ballot(streamed));   // a wavefront total then
@@ -223,9 +242,9 @@ __global__ __launch_bounds__(kSplitThreads, 5) void k_split_candidates(SplitPara
                             last_fin = max(last_fin, arrival + e2e);
                             if (p.all_within == 0u) n_ok += (prefill <= p.slo_ttft && tpot <= p.slo_tpot) ? 1u : 0u;
                             if (kHist) {
-                                hist_add<true>(hist, 0u, hist_bin_u32(prefill), 1u);
-                                hist_add<true>(hist, 1u, hist_bin_u32(tpot), 1u);
-                                hist_add<true>(hist, 2u, hist_bin_u32(e2e), 1u);
+                                hist_add<kHist16>(hist, 0u, hist_bin_u32(prefill), 1u);
+                                hist_add<kHist16>(hist, 1u, hist_bin_u32(tpot), 1u);
+                                hist_add<kHist16>(hist, 2u, hist_bin_u32(e2e), 1u);
                             }
                         }
                     }
@@ -322,12 +341,12 @@ __global__ __launch_bounds__(kSplitThreads, 5) void k_split_candidates(SplitPara
             sp.last_fin = acc32[0];
             sp.n_ok = acc32[1];
             sp.n_rej = rejected;
-            sp.flags = lazy ? kFlagLazy : (kHist ? 0u : kFlagNeedHist);
+            sp.flags = lazy ? kFlagLazy : (kHist ? 0u : (p.any_streamed != 0u ? kFlagNeedHist : kFlagNoStreamHist));
             p.part[cb] = sp;
         }
         if (kHist && !lazy) {
-            uint32_t* dst = p.hist + (size_t)cb * (3u * kBins / 2u);
-            for (uint32_t i = tid; i < 3u * kBins / 2u; i += kSplitThreads) dst[i] = hist[i];
+            uint32_t* dst = p.hist + (size_t)cb * p.hist_words;
+            for (uint32_t i = tid; i < p.hist_words; i += kSplitThreads) dst[i] = hist[i];
         }
     }
 }
@@ -364,8 +383,7 @@ __global__ __launch_bounds__(kWave) void k_replay_lists(SplitParams p, uint32_t 
     q.t_on = (uint32_t)__builtin_amdgcn_readfirstlane((int)q.t_on);
     q.t_off = (uint32_t)__builtin_amdgcn_readfirstlane((int)q.t_off);
     q.i_list = (uint32_t)__builtin_amdgcn_readfirstlane((int)q.i_list);
-    const bool with_hist = live && (p.part[cb].flags & kFlagLazy) == 0u;
-    uint32_t* hist = p.hist + (size_t)(live ? cb : 0u) * (3u * kBins / 2u);
+    const bool with_hist = live && (p.part[cb].flags & kFlagLazy) == 0u;             // leave the bins of every request
 
     uint32_t s[kSlots];
 #pragma unroll
@@ -385,6 +403,7 @@ __global__ __launch_bounds__(kWave) void k_replay_lists(SplitParams p, uint32_t 
         const uint32_t first = d & 0xFFFFu;
         if ((first & 7u) != 0u || first + ((count + 7u) & ~7u) > p.tile_cap) count = 0u;   // never written that way
         const uint4* src = reinterpret_cast<const uint4*>(p.lists + tile_at * p.tile_cap + first);
+        uint32_t* bins = p.bins + tile_at * p.tile_cap + first;
         for (uint32_t b = 0;; ++b) {
             const bool more = 8u * b < count;
             if (__ballot(more) == 0ull) break;
@@ -416,14 +435,10 @@ __global__ __launch_bounds__(kWave) void k_replay_lists(SplitParams p, uint32_t 
                     s_tpot += tpot;
                     last_fin = max(last_fin, fin);
                     n_ok += (ttft <= p.slo_ttft && tpot <= p.slo_tpot) ? 1u : 0u;
-                    if (with_hist) {
-                        const uint32_t bt = hist_bin_u32(ttft), bp = hist_bin_u32(tpot), be = hist_bin_u32(e2e);
-                        atomicAdd(&hist[bt >> 1], 1u << ((bt & 1u) << 4));
-                        atomicAdd(&hist[kBins / 2u + (bp >> 1)], 1u << ((bp & 1u) << 4));
-                        atomicAdd(&hist[kBins + (be >> 1)], 1u << ((be & 1u) << 4));
-                    }
+                    if (with_hist) bins[8u * b + k] = hist_bin_u32(ttft) | (hist_bin_u32(e2e) << 12) | kBinServed;
                 } else if (active) {
                     n_rej += 1u;                                                    // the replica is gone before it could start
+                    if (with_hist) bins[8u * b + k] = 0u;
                 }
             }
         }
@@ -448,8 +463,11 @@ __global__ __launch_bounds__(kWave) void k_replay_lists(SplitParams p, uint32_t 
 }
 
 // Merge: one record per candidate from its partial sums.  A candidate settled by penalty is written by one
-// thread; one that the list replay handed back gets the pending mark (the general replay scores it next); the
-// others take their histograms from device memory through the usual block-wide reduction.
+// thread; one that the list replay handed back gets the pending mark (the general replay scores it next); for
+// the others the workgroup takes the streamed requests' histograms from device memory, adds the listed requests
+// run by run (a wavefront per run: ttft and e2e bins as the list replay left them, the time per token from the
+// request's record and the run's replica) and goes through the usual block-wide reduction.
+template <bool kHist16>
 __global__ __launch_bounds__(kThreads) void k_merge_candidates(EvalParams p, SplitParams sp, ap_metrics* __restrict__ out,
                                                                uint32_t c0, uint32_t n_cand, PendingWord flags) {
     extern __shared__ __align__(16) unsigned char lds[];
@@ -459,7 +477,7 @@ __global__ __launch_bounds__(kThreads) void k_merge_candidates(EvalParams p, Spl
     unsigned long long* acc64 = reinterpret_cast<unsigned long long*>(lds + p.off_misc);
     uint32_t* acc32 = reinterpret_cast<uint32_t*>(lds + p.off_misc + 24);
     uint32_t* wtot = reinterpret_cast<uint32_t*>(lds + p.off_misc + 64);
-    const uint32_t tid = threadIdx.x;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, w = wave_index();
     for (uint32_t base = blockIdx.x * kThreads; base < n_cand; base += gridDim.x * kThreads) {
         if (tid == 0u) n_todo = 0u;
         __syncthreads();
@@ -493,15 +511,37 @@ __global__ __launch_bounds__(kThreads) void k_merge_candidates(EvalParams p, Spl
         const uint32_t n_here = n_todo;
         for (uint32_t t = 0; t < n_here; ++t) {
             const uint32_t c = todo[t];
-            const uint32_t* src = sp.hist + (size_t)c * (3u * kBins / 2u);
-            for (uint32_t i = tid; i < 3u * kBins / 2u; i += kThreads) hist[i] = src[i];
+            const SplitPartial part = sp.part[c];
+            const uint32_t* src = sp.hist + (size_t)c * sp.hist_words;
+            const bool parked = (part.flags & kFlagNoStreamHist) == 0u;          // the same for every thread
+            for (uint32_t i = tid; i < sp.hist_words; i += kThreads) hist[i] = parked ? src[i] : 0u;
             if (tid < 16u) reinterpret_cast<uint32_t*>(acc64)[tid] = 0u;
             __syncthreads();
-            const SplitPartial part = sp.part[c];
-            const bool first = tid == 0u;
-            finish_candidate<true>(p, hist, acc64, acc32, wtot, first ? part.s_e2e : 0ull, first ? part.s_ttft : 0ull,
-                                   first ? part.s_tpot : 0ull, first ? part.last_fin : 0u, first ? part.n_ok : 0u,
-                                   first ? part.n_rej : 0u, &out[c0 + c]);
+            const size_t tiles_at = (size_t)c * sp.n_list_tiles;
+            for (uint32_t run = w; run < sp.n_list_tiles * sp.M; run += kWaves) {
+                const uint32_t j = run / sp.M, m = run - j * sp.M;
+                const uint32_t d = sp.desc[(tiles_at + j) * sp.M + m];
+                const uint32_t count = min(d >> 16, kTile), first = d & 0xFFFFu;
+                if (count == 0u || first + count > sp.tile_cap) continue;           // the same for the whole wavefront
+                const SplitQueue q = sp.queue[m];
+                const size_t at = (tiles_at + j) * sp.tile_cap + first;
+                for (uint32_t i = lane; i < count; i += kWave) {
+                    const uint32_t word = sp.bins[at + i];
+                    if (word & kBinServed) {
+                        const uint32_t prompt = sp.req8[j * kTile + (sp.lists[at + i] & (kTile - 1u))].y & 0xFFFFu;
+                        const uint32_t tpot = q.c + __umul24(q.d, (prompt + 1023u) >> 10);
+                        hist_add<kHist16>(hist, 0u, word & 0xFFFu, 1u);
+                        hist_add<kHist16>(hist, 1u, hist_bin_u32(tpot), 1u);
+                        hist_add<kHist16>(hist, 2u, (word >> 12) & 0xFFFu, 1u);
+                    }
+                }
+            }
+            __syncthreads();
+            const bool first_thread = tid == 0u;
+            finish_candidate<kHist16>(p, hist, acc64, acc32, wtot, first_thread ? part.s_e2e : 0ull,
+                                      first_thread ? part.s_ttft : 0ull, first_thread ? part.s_tpot : 0ull,
+                                      first_thread ? part.last_fin : 0u, first_thread ? part.n_ok : 0u,
+                                      first_thread ? part.n_rej : 0u, &out[c0 + c]);
             __syncthreads();
         }
         __syncthreads();
