@@ -195,11 +195,20 @@ static ap_status launch_dense(const ap_workload* w, const uint16_t* d_assign, ui
     if (w->split && !marked) {
         // the listed / streamed evaluation, a batch of candidates at a time; what it hands back carries the pending mark
         const SplitParams& sp = w->split_params;
-        typedef void (*replay_fn)(SplitParams, uint32_t);
-        const replay_fn replay = w->split_slots == 8u ? k_replay_lists<8u> : w->split_slots == 16u ? k_replay_lists<16u>
-                                 : w->split_slots == 32u ? k_replay_lists<32u> : k_replay_lists<64u>;
-        for (uint32_t c0 = 0; c0 < C; c0 += w->split_batch) {
-            const uint32_t n = std::min(w->split_batch, C - c0);
+        typedef void (*replay_fn)(SplitParams, uint32_t, uint32_t);
+        const replay_fn replay_lean = w->split_slots == 8u    ? k_replay_lists<8u, false>
+                                      : w->split_slots == 16u ? k_replay_lists<16u, false>
+                                      : w->split_slots == 32u ? k_replay_lists<32u, false>
+                                                              : k_replay_lists<64u, false>;
+        const replay_fn replay_bins = w->split_slots == 8u    ? k_replay_lists<8u, true>
+                                      : w->split_slots == 16u ? k_replay_lists<16u, true>
+                                      : w->split_slots == 32u ? k_replay_lists<32u, true>
+                                                              : k_replay_lists<64u, true>;
+        // batches of equal size (whole wavefronts of the list replay), none above what the scratch area holds
+        const uint32_t n_batches = (C + w->split_batch - 1u) / w->split_batch;
+        const uint32_t per_batch = std::min(w->split_batch, ((C + n_batches - 1u) / n_batches + 63u) / 64u * 64u);
+        for (uint32_t c0 = 0; c0 < C; c0 += per_batch) {
+            const uint32_t n = std::min(per_batch, C - c0);
             const uint32_t grid = std::min(n, w->n_cu * 16u);
             // First without histograms where the candidates are expected to be settled by penalty, or where nothing is
             // streamed at all; then with histograms, for every candidate or for those the first pass marked.
@@ -211,10 +220,16 @@ static ap_status launch_dense(const ap_workload* w, const uint16_t* d_assign, ui
             if (sp.any_streamed != 0u)
                 hipLaunchKernelGGL(split_kernel(sp.wide ? 2u : 1u, narrow), dim3(grid), dim3(kSplitThreads),
                                    w->split_lds_bytes_hist, stream, sp, d_assign, c0, n, plain_first ? 1u : 0u, flags);
-            if (sp.n_queues != 0u)
-                hipLaunchKernelGGL(replay, dim3(sp.n_queues * ((n + kWave - 1u) / kWave)), dim3(kWave), 0, stream, sp, n);
+            // the list replay: where most candidates are settled by penalty, those go through the variant that
+            // leaves no bins, and the wavefronts of the other variant find the few that remain
+            if (sp.n_queues != 0u) {
+                const dim3 waves(sp.n_queues * ((n + kWave - 1u) / kWave));
+                if (w->split_expect_lazy)
+                    hipLaunchKernelGGL(replay_lean, waves, dim3(kWave), 0, stream, sp, n, 1u);
+                hipLaunchKernelGGL(replay_bins, waves, dim3(kWave), 0, stream, sp, n, w->split_expect_lazy ? 2u : 0u);
+            }
             hipLaunchKernelGGL(sp.wide ? k_merge_candidates<false> : k_merge_candidates<true>,
-                               dim3(std::min((n + kThreads - 1u) / kThreads, w->n_cu * 4u)), dim3(kThreads), w->reduce_lds_bytes,
+                               dim3(std::min(n, w->n_cu * 8u)), dim3(kThreads), w->reduce_lds_bytes,
                                stream, w->reduce_eval, sp, d_out, c0, n, flags);
         }
         if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
@@ -506,15 +521,15 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
     w->split_slots = B <= 8u ? 8u : B <= 16u ? 16u : B <= 32u ? 32u : 64u;
 
     // scratch for one batch of candidates: lists, run descriptors, partial records, histograms
-    const size_t per_cand = (size_t)sp.n_list_tiles * sp.tile_cap * (2u + 4u) + (size_t)sp.n_list_tiles * M * 4u +
+    const size_t per_cand = (size_t)sp.n_list_tiles * sp.tile_cap * (2u + 8u) + (size_t)sp.n_list_tiles * (M + 1u) * 4u +
                             sizeof(SplitPartial) + hist_bytes;
-    uint32_t batch = (uint32_t)std::min<size_t>(16384u, std::max<size_t>(64u, ((size_t)1 << 30) / per_cand));
+    uint32_t batch = (uint32_t)std::min<size_t>(16384u, std::max<size_t>(64u, ((size_t)4 << 30) / per_cand));
     batch = batch / 64u * 64u;
     auto carve = [](size_t& at, size_t bytes) { const size_t here = at; at = (at + bytes + 255u) / 256u * 256u; return here; };
     size_t total = 0;
     const size_t o_lists = carve(total, (size_t)batch * sp.n_list_tiles * sp.tile_cap * 2u);
-    const size_t o_bins = carve(total, (size_t)batch * sp.n_list_tiles * sp.tile_cap * 4u);
-    const size_t o_desc = carve(total, (size_t)batch * sp.n_list_tiles * M * 4u);
+    const size_t o_bins = carve(total, (size_t)batch * sp.n_list_tiles * sp.tile_cap * 8u);
+    const size_t o_desc = carve(total, (size_t)batch * sp.n_list_tiles * (M + 1u) * 4u);
     const size_t o_part = carve(total, (size_t)batch * sizeof(SplitPartial));
     const size_t o_hist = carve(total, (size_t)batch * hist_bytes);
     if (total > w->split_scratch_bytes) {
@@ -553,7 +568,7 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
     sp.queue = w->d_split_queue;
     sp.order = w->d_split_order;
     sp.lists = reinterpret_cast<uint16_t*>(w->d_split_scratch + o_lists);
-    sp.bins = reinterpret_cast<uint32_t*>(w->d_split_scratch + o_bins);
+    sp.bins = reinterpret_cast<uint2*>(w->d_split_scratch + o_bins);
     sp.desc = reinterpret_cast<uint32_t*>(w->d_split_scratch + o_desc);
     sp.part = reinterpret_cast<SplitPartial*>(w->d_split_scratch + o_part);
     sp.hist = reinterpret_cast<uint32_t*>(w->d_split_scratch + o_hist);
@@ -828,6 +843,11 @@ static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint
     bool always_on = true;
     for (const DevReplica& d : dev) always_on = always_on && d.t_on == 0u && d.t_off == kNever;
     w->screen = always_on && kinds.size() == 1 && w->R <= (1u << 30);      // the kernels' byte offsets are 32-bit
+    // Screening proves that nobody waits; where the mean number of requests in service per replica (total service time
+    // over the trace's span, by Little's law) is a quarter of the slots or more, hardly any candidate will pass, and
+    // the trace goes straight to the listed evaluation, which replays every queue.
+    const bool crowded = w->span_us == 0 || (double)service_sum / (double)w->span_us / M >= 0.25 * B;
+    if (w->screen && crowded && !tabled && w->d_req8) w->screen = false;
     if (w->screen) {
         ScreenParams sp{};
         sp.span = w->d_span;

@@ -82,11 +82,13 @@ struct SplitParams {
     SplitTables tab;
     const SplitQueue* queue;                      // [M]
     const uint32_t* order;                        // [n_queues] replicas with a listed part, longest first
-    uint32_t* desc;                               // [batch][n_list_tiles][M] count << 16 | first list position
+    uint32_t* desc;                               // [batch][n_list_tiles][M + 1] count << 16 | first list position of
+                                                  //   the replica's run; entry M: list positions the tile uses in all
     uint16_t* lists;                              // [batch][n_list_tiles][tile_cap] tile-local request indices by replica
     SplitPartial* part;                           // [batch]
     uint32_t* hist;                               // [batch][hist_words] the streamed requests' histograms
-    uint32_t* bins;                               // [batch][n_list_tiles][tile_cap] bins word of every listed request
+    uint2* bins;                                  // [batch][n_list_tiles][tile_cap] bins of every listed request:
+                                                  //   x = ttft bin | e2e bin << 12 | kBinServed, y = tpot bin
     uint32_t hist_words;                          // 3 * kBins / 2 (16-bit counts, R < 65536) or 3 * kBins
     uint32_t wide;                                // R >= 65536: two range words per replica
     uint32_t any_streamed;                        // some replica has a streamed part
@@ -279,10 +281,11 @@ __global__ __launch_bounds__(kSplitThreads, 5) void k_split_candidates(SplitPara
                 if (m < M) {
                     pos[m] = total + upto - room;
                     cnt[m] = 0u;                                                    // for the wavefront's next tile
-                    p.desc[tile_at * M + m] = (c << 16) | (total + upto - room);
+                    p.desc[tile_at * (M + 1u) + m] = (c << 16) | (total + upto - room);
                 }
                 total += (uint32_t)__builtin_amdgcn_readlane((int)upto, 63);
             }
+            if (lane == 0u) p.desc[tile_at * (M + 1u) + M] = total;
             // Rank among the queued requests of one replica, 64 queued requests at a time: every lane sets its bit
             // in its replica's word and reads the word back (the LDS executes a wavefront's instructions in order),
             // which tells it how many lanes before it name the same replica; the last of them moves the run's
@@ -367,14 +370,22 @@ __device__ __forceinline__ uint32_t median3(uint32_t a, uint32_t b, uint32_t c) 
 // request in a step (or whose request is rejected) inserts 0, which leaves the registers as they are.
 // Starts do not decrease along a queue, so once a start reaches t_off every later request is rejected too.
 // kSlots: B rounded up to a power of two; registers beyond B hold kNever and stay there.
-template <uint32_t kSlots>
-__global__ __launch_bounds__(kWave) void k_replay_lists(SplitParams p, uint32_t n_cand) {
+// kBinsOut: the variant that leaves the histogram bins of its requests for the merge.  which: 0 every
+// candidate, 1 only those settled by penalty (the lean variant's share), 2 only the others; a wavefront
+// without a lane to work on ends at once.
+template <uint32_t kSlots, bool kBinsOut>
+__global__ __launch_bounds__(kWave) void k_replay_lists(SplitParams p, uint32_t n_cand, uint32_t which) {
     __shared__ uint2 recs[kTile];
     const uint32_t lane = threadIdx.x;
     const uint32_t n_blocks = (n_cand + kWave - 1u) / kWave;
     const uint32_t m = p.order[blockIdx.x / n_blocks];
     const uint32_t cb = (blockIdx.x % n_blocks) * kWave + lane;
-    const bool live = cb < n_cand;
+    bool live = cb < n_cand;
+    const bool lazy = live && (p.part[cb].flags & kFlagLazy) != 0u;
+    if (which == 1u) live = lazy;
+    if (which == 2u) live = live && !lazy;
+    if (__ballot(live) == 0ull) return;
+    const bool with_hist = kBinsOut && live && !lazy;                               // leave the bins of every request
     SplitQueue q = p.queue[m];
     q.a = (uint32_t)__builtin_amdgcn_readfirstlane((int)q.a);
     q.b = (uint32_t)__builtin_amdgcn_readfirstlane((int)q.b);
@@ -383,7 +394,6 @@ __global__ __launch_bounds__(kWave) void k_replay_lists(SplitParams p, uint32_t 
     q.t_on = (uint32_t)__builtin_amdgcn_readfirstlane((int)q.t_on);
     q.t_off = (uint32_t)__builtin_amdgcn_readfirstlane((int)q.t_off);
     q.i_list = (uint32_t)__builtin_amdgcn_readfirstlane((int)q.i_list);
-    const bool with_hist = live && (p.part[cb].flags & kFlagLazy) == 0u;             // leave the bins of every request
 
     uint32_t s[kSlots];
 #pragma unroll
@@ -398,18 +408,23 @@ __global__ __launch_bounds__(kWave) void k_replay_lists(SplitParams p, uint32_t 
         for (uint32_t i = lane; i < n; i += kWave) recs[i] = p.req8[r0 + i];
         __syncthreads();
         const size_t tile_at = (size_t)(live ? cb : 0u) * p.n_list_tiles + j;
-        const uint32_t d = live ? p.desc[tile_at * p.M + m] : 0u;
+        const uint32_t d = live ? p.desc[tile_at * (p.M + 1u) + m] : 0u;
         uint32_t count = d >> 16;
         const uint32_t first = d & 0xFFFFu;
         if ((first & 7u) != 0u || first + ((count + 7u) & ~7u) > p.tile_cap) count = 0u;   // never written that way
         const uint4* src = reinterpret_cast<const uint4*>(p.lists + tile_at * p.tile_cap + first);
-        uint32_t* bins = p.bins + tile_at * p.tile_cap + first;
+        uint2* bins = p.bins + tile_at * p.tile_cap + first;                        // of this run; its padding reads "not served"
         for (uint32_t b = 0;; ++b) {
             const bool more = 8u * b < count;
             if (__ballot(more) == 0ull) break;
             uint4 e = make_uint4(0u, 0u, 0u, 0u);
             if (more) e = src[b];
             const uint32_t word[4] = {e.x, e.y, e.z, e.w};
+            if (kBinsOut && with_hist && more && 8u * b + 8u > count) {                         // the run's last block: its padding
+#pragma unroll
+                for (uint32_t k = 1; k < 8u; ++k)
+                    if (8u * b + k >= count) bins[8u * b + k] = make_uint2(0u, 0u);
+            }
 #pragma unroll
             for (uint32_t k = 0; k < 8u; ++k) {
                 const bool active = 8u * b + k < count;
@@ -435,10 +450,12 @@ __global__ __launch_bounds__(kWave) void k_replay_lists(SplitParams p, uint32_t 
                     s_tpot += tpot;
                     last_fin = max(last_fin, fin);
                     n_ok += (ttft <= p.slo_ttft && tpot <= p.slo_tpot) ? 1u : 0u;
-                    if (with_hist) bins[8u * b + k] = hist_bin_u32(ttft) | (hist_bin_u32(e2e) << 12) | kBinServed;
+                    if (kBinsOut && with_hist)
+                        bins[8u * b + k] = make_uint2(hist_bin_u32(ttft) | (hist_bin_u32(e2e) << 12) | kBinServed,
+                                                      hist_bin_u32(tpot));
                 } else if (active) {
                     n_rej += 1u;                                                    // the replica is gone before it could start
-                    if (with_hist) bins[8u * b + k] = 0u;
+                    if (kBinsOut && with_hist) bins[8u * b + k] = make_uint2(0u, 0u);
                 }
             }
         }
@@ -464,28 +481,26 @@ __global__ __launch_bounds__(kWave) void k_replay_lists(SplitParams p, uint32_t 
 
 // Merge: one record per candidate from its partial sums.  A candidate settled by penalty is written by one
 // thread; one that the list replay handed back gets the pending mark (the general replay scores it next); for
-// the others the workgroup takes the streamed requests' histograms from device memory, adds the listed requests
-// run by run (a wavefront per run: ttft and e2e bins as the list replay left them, the time per token from the
-// request's record and the run's replica) and goes through the usual block-wide reduction.
+// the others a workgroup takes the streamed requests' histograms from device memory, adds the bins the list replay
+// left for every list position of the candidate (padding reads "not served") and goes through the usual
+// block-wide reduction.
 template <bool kHist16>
 __global__ __launch_bounds__(kThreads) void k_merge_candidates(EvalParams p, SplitParams sp, ap_metrics* __restrict__ out,
                                                                uint32_t c0, uint32_t n_cand, PendingWord flags) {
     extern __shared__ __align__(16) unsigned char lds[];
-    __shared__ uint32_t todo[kThreads];
-    __shared__ uint32_t n_todo;
     uint32_t* hist = reinterpret_cast<uint32_t*>(lds);
     unsigned long long* acc64 = reinterpret_cast<unsigned long long*>(lds + p.off_misc);
     uint32_t* acc32 = reinterpret_cast<uint32_t*>(lds + p.off_misc + 24);
     uint32_t* wtot = reinterpret_cast<uint32_t*>(lds + p.off_misc + 64);
-    const uint32_t tid = threadIdx.x, lane = tid & 63u, w = wave_index();
+    const uint32_t tid = threadIdx.x;
+    // One workgroup per candidate that needs its histograms; the others are one thread's work each, so a
+    // workgroup first settles a run of kThreads of them.
     for (uint32_t base = blockIdx.x * kThreads; base < n_cand; base += gridDim.x * kThreads) {
-        if (tid == 0u) n_todo = 0u;
-        __syncthreads();
         const uint32_t cb = base + tid;
         if (cb < n_cand) {
             const SplitPartial part = sp.part[cb];
-            unsigned long long* dst = reinterpret_cast<unsigned long long*>(&out[c0 + cb]);
             if (part.flags & kFlagFallback) {
+                unsigned long long* dst = reinterpret_cast<unsigned long long*>(&out[c0 + cb]);
 #pragma unroll
                 for (uint32_t i = 0; i < 8u; ++i) dst[i] = ~0ull;
                 pending_raise(flags);
@@ -503,47 +518,36 @@ __global__ __launch_bounds__(kThreads) void k_merge_candidates(EvalParams p, Spl
                 mt.slo_ok = part.n_ok;
                 mt.n_rejected = part.n_rej;
                 out[c0 + cb] = mt;
-            } else {
-                todo[atomicAdd(&n_todo, 1u)] = cb;
+            }
+        }
+    }
+    for (uint32_t c = blockIdx.x; c < n_cand; c += gridDim.x) {
+        const SplitPartial part = sp.part[c];                                       // the same for every thread
+        if (part.flags & (kFlagFallback | kFlagLazy)) continue;
+        const uint32_t* src = sp.hist + (size_t)c * sp.hist_words;
+        const bool parked = (part.flags & kFlagNoStreamHist) == 0u;
+        for (uint32_t i = tid; i < sp.hist_words; i += kThreads) hist[i] = parked ? src[i] : 0u;
+        if (tid < 16u) reinterpret_cast<uint32_t*>(acc64)[tid] = 0u;
+        __syncthreads();
+        const size_t tiles_at = (size_t)c * sp.n_list_tiles;
+        for (uint32_t j = 0; j < sp.n_list_tiles; ++j) {
+            const uint32_t used = min(sp.desc[(tiles_at + j) * (sp.M + 1u) + sp.M], sp.tile_cap);
+            const size_t at = (tiles_at + j) * sp.tile_cap;
+            for (uint32_t i = tid; i < used; i += kThreads) {
+                const uint2 word = sp.bins[at + i];
+                if (word.x & kBinServed) {
+                    hist_add<kHist16>(hist, 0u, word.x & 0xFFFu, 1u);
+                    hist_add<kHist16>(hist, 1u, min(word.y, kBins - 1u), 1u);
+                    hist_add<kHist16>(hist, 2u, (word.x >> 12) & 0xFFFu, 1u);
+                }
             }
         }
         __syncthreads();
-        const uint32_t n_here = n_todo;
-        for (uint32_t t = 0; t < n_here; ++t) {
-            const uint32_t c = todo[t];
-            const SplitPartial part = sp.part[c];
-            const uint32_t* src = sp.hist + (size_t)c * sp.hist_words;
-            const bool parked = (part.flags & kFlagNoStreamHist) == 0u;          // the same for every thread
-            for (uint32_t i = tid; i < sp.hist_words; i += kThreads) hist[i] = parked ? src[i] : 0u;
-            if (tid < 16u) reinterpret_cast<uint32_t*>(acc64)[tid] = 0u;
-            __syncthreads();
-            const size_t tiles_at = (size_t)c * sp.n_list_tiles;
-            for (uint32_t run = w; run < sp.n_list_tiles * sp.M; run += kWaves) {
-                const uint32_t j = run / sp.M, m = run - j * sp.M;
-                const uint32_t d = sp.desc[(tiles_at + j) * sp.M + m];
-                const uint32_t count = min(d >> 16, kTile), first = d & 0xFFFFu;
-                if (count == 0u || first + count > sp.tile_cap) continue;           // the same for the whole wavefront
-                const SplitQueue q = sp.queue[m];
-                const size_t at = (tiles_at + j) * sp.tile_cap + first;
-                for (uint32_t i = lane; i < count; i += kWave) {
-                    const uint32_t word = sp.bins[at + i];
-                    if (word & kBinServed) {
-                        const uint32_t prompt = sp.req8[j * kTile + (sp.lists[at + i] & (kTile - 1u))].y & 0xFFFFu;
-                        const uint32_t tpot = q.c + __umul24(q.d, (prompt + 1023u) >> 10);
-                        hist_add<kHist16>(hist, 0u, word & 0xFFFu, 1u);
-                        hist_add<kHist16>(hist, 1u, hist_bin_u32(tpot), 1u);
-                        hist_add<kHist16>(hist, 2u, (word >> 12) & 0xFFFu, 1u);
-                    }
-                }
-            }
-            __syncthreads();
-            const bool first_thread = tid == 0u;
-            finish_candidate<kHist16>(p, hist, acc64, acc32, wtot, first_thread ? part.s_e2e : 0ull,
-                                      first_thread ? part.s_ttft : 0ull, first_thread ? part.s_tpot : 0ull,
-                                      first_thread ? part.last_fin : 0u, first_thread ? part.n_ok : 0u,
-                                      first_thread ? part.n_rej : 0u, &out[c0 + c]);
-            __syncthreads();
-        }
+        const bool first_thread = tid == 0u;
+        finish_candidate<kHist16>(p, hist, acc64, acc32, wtot, first_thread ? part.s_e2e : 0ull,
+                                  first_thread ? part.s_ttft : 0ull, first_thread ? part.s_tpot : 0ull,
+                                  first_thread ? part.last_fin : 0u, first_thread ? part.n_ok : 0u,
+                                  first_thread ? part.n_rej : 0u, &out[c0 + c]);
         __syncthreads();
     }
 }

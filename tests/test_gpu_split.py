@@ -103,7 +103,7 @@ def test_small_penalty_keeps_the_histograms():
 
 
 def test_more_candidates_than_one_batch_of_scratch():
-    """The scratch area holds a fixed number of candidates' lists (about 1 GiB / 210 KiB here); a call with more
+    """The scratch area holds a fixed number of candidates' lists (about 4 GiB / 0.9 MiB here); a call with more
     candidates is worked off in batches."""
     tr = elastic(60000, 64, 64, 2500.0, seed=16)
     C = 5400
