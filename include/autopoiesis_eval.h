@@ -248,6 +248,21 @@ ap_status ap_roofline_costs(const ap_workload *w, const ap_model *models, uint32
                             uint32_t n_gpus, const ap_group *groups, uint32_t n_groups, uint32_t *prefill_us,
                             uint32_t *tpot_us);
 
+/* ap_roofline_costs and ap_costtable_set in one call, without the tables leaving the device: the roofline
+ * terms of Appendix "Serving Simulator" (serve-latency equation) are evaluated for every group, turned into
+ * prefill_us / tpot_us of every request of the workload exactly as ap_roofline_costs does, and written straight
+ * into the workload's own table buffers; group g is replica type g (replicas[m].type < n_groups, AP_ERR_INVALID
+ * otherwise).  The range proof of ap_costmodel_set runs as a reduction over the device tables, and the host
+ * reads back its 32-byte result: no table is copied in either direction.  The roofline buffers and the table
+ * buffers stay with the workload and are reused by later calls that fit (allocation only when they grow).
+ *   replicas, models, gpus, groups : HOST arrays, copied.
+ * Synchronous, like ap_costmodel_set (the host sizes LDS and scratch from the bounds).  Errors as for
+ * ap_roofline_costs and ap_costtable_set; unlike those, a failure after the descriptions were validated leaves the
+ * workload WITHOUT a cost model (the previous tables are overwritten before the proof can run). */
+ap_status ap_costtable_set_roofline(ap_workload *w, const ap_typed_replica *replicas, uint32_t M, uint32_t B,
+                                    const ap_slo *slo, const ap_model *models, uint32_t n_models, const ap_gpu *gpus,
+                                    uint32_t n_gpus, const ap_group *groups, uint32_t n_groups);
+
 /* End-to-end trace time of candidate plan sequences (Section 5.1, execution model):
  *   T_total = t_sched(1) + t_serve(1) + sum_{i=2}^{N} [ t_stale(i) + t_reconfig(i) + t_serve(i) ]
  * with t_reconfig(i) = Reconfig-Cost(sigma_{i-1}, sigma_i) = T_term + T_load of Appendix "Serving

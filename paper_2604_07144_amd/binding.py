@@ -81,6 +81,9 @@ def lib() -> C.CDLL:
         L.ap_roofline_costs.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32,
                                         C.c_void_p, C.c_void_p]
         L.ap_roofline_costs.restype = C.c_int
+        L.ap_costtable_set_roofline.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p,
+                                                C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32]
+        L.ap_costtable_set_roofline.restype = C.c_int
         L.ap_trace_time.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p,
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32, C.c_void_p,
                                     C.c_void_p]
@@ -232,6 +235,21 @@ def ap_roofline_costs(workload: int, n_requests: int, models, gpus, groups):
     _check(lib().ap_roofline_costs(workload, models.ctypes.data, models.shape[0], gpus.ctypes.data, gpus.shape[0],
                                    groups.ctypes.data, G, prefill_us.ctypes.data, tpot_us.ctypes.data), "ap_roofline_costs")
     return prefill_us, tpot_us
+
+
+def ap_costtable_set_roofline(workload: int, rep_type, t_on_us, t_off_us, B: int, slo_ttft_us: int, slo_tpot_us: int,
+                              penalty_us: int, models, gpus, groups) -> None:
+    """Roofline cost tables computed into the workload's own device buffers and attached as its cost model;
+    group g is replica type g."""
+    models, gpus, groups = _roofline_args(models, gpus, groups)
+    rep = np.zeros(len(rep_type), dtype=TYPED_REPLICA_DTYPE)
+    rep["type"] = np.asarray(rep_type, dtype=np.uint32)
+    rep["t_on_us"] = np.asarray(t_on_us, dtype=np.uint64)
+    rep["t_off_us"] = np.asarray(t_off_us, dtype=np.uint64)
+    slo = ApSlo(int(slo_ttft_us), int(slo_tpot_us), int(penalty_us))
+    _check(lib().ap_costtable_set_roofline(workload, rep.ctypes.data, rep.shape[0], int(B), C.byref(slo), models.ctypes.data,
+                                           models.shape[0], gpus.ctypes.data, gpus.shape[0], groups.ctypes.data,
+                                           groups.shape[0]), "ap_costtable_set_roofline")
 
 
 AP_LOAD_DEPLOYED, AP_LOAD_CHANGED = 0, 1

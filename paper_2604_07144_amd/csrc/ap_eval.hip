@@ -74,6 +74,30 @@ EvalKernel eval_kernel(bool hist16, bool len16, bool tabled) {
 
 constexpr size_t kNominalSumsBytes = 3u * kBins * sizeof(uint32_t) + 3u * sizeof(unsigned long long) + 4u * sizeof(uint32_t);
 
+namespace {
+// Device buffers of one roofline computation; freed when the object goes out of scope.
+struct RoofBuffers {
+    RoofGroup* groups = nullptr;
+    unsigned long long* prefill_ns = nullptr;
+    unsigned long long* step_ns = nullptr;
+    unsigned long long* prefix_ns = nullptr;
+    double* weight_bytes = nullptr;
+    uint32_t* feasible = nullptr;
+    uint32_t* prefill_us = nullptr;
+    uint32_t* tpot_us = nullptr;
+    uint32_t cap_groups = 0, cap_seq = 0;       // what the table buffers hold; a later computation that fits reuses them
+    void release() {
+        for (void* q : {(void*)groups, (void*)prefill_ns, (void*)step_ns, (void*)prefix_ns, (void*)weight_bytes,
+                        (void*)feasible, (void*)prefill_us, (void*)tpot_us})
+            if (q) (void)hipFree(q);
+        groups = nullptr; prefill_ns = step_ns = prefix_ns = nullptr; weight_bytes = nullptr; feasible = nullptr;
+        prefill_us = tpot_us = nullptr;
+        cap_groups = cap_seq = 0;
+    }
+    ~RoofBuffers() { release(); }
+};
+}  // namespace
+
 struct ap_workload {
     int device = 0;
     uint32_t R = 0;
@@ -89,6 +113,8 @@ struct ap_workload {
     uint32_t* d_tab_tpot = nullptr;
     size_t tab_entries = 0;
     bool tabled = false;              // the current cost model reads the tables
+    RoofBuffers* roof = nullptr;             // device buffers of ap_costtable_set_roofline, kept for the next call
+    unsigned char* d_bounds = nullptr;       // TableBounds, then the replica types in use [AP_MAX_REPLICAS]
     uint32_t* d_span = nullptr;       // [R] contention-free service intervals in ticks, valid when screen is set
     uint32_t* d_span_t = nullptr;     // the same, lane-major for the one-wavefront screening kernel
     uint32_t* d_pair = nullptr;       // one word per two requests (eight-wavefront screening kernel, when it fits)
@@ -583,10 +609,13 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
 // Shared by ap_costmodel_set (rep_type == nullptr: the coefficients of `replicas` apply) and
 // ap_costtable_set (replica m is of type rep_type[m] < T and the HOST tables [T][R] apply; the
 // coefficients are ignored).
+// tab_prefill == nullptr with rep_type set: the tables are in the workload's device buffers already
+// (ap_costtable_set_roofline) and the bounds come from a reduction over them.
 static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint32_t M, uint32_t B, const ap_slo* slo,
                                 const uint32_t* rep_type, const uint32_t* tab_prefill, const uint32_t* tab_tpot, uint32_t T) {
     if (!w || !replicas || !slo || M == 0 || B == 0) return AP_ERR_INVALID;
     const bool tabled = rep_type != nullptr;
+    const bool on_device = tabled && tab_prefill == nullptr;
     for (uint32_t m = 0; m < M; ++m)
         if (replicas[m].t_on_us > replicas[m].t_off_us) return AP_ERR_INVALID;
     if (M > AP_MAX_REPLICAS || B > AP_MAX_SLOTS) return AP_ERR_RANGE;
@@ -640,7 +669,37 @@ static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint
     } catch (const std::bad_alloc&) {
         return AP_ERR_ALLOC;
     }
-    for (uint32_t r = 0; r < w->R; ++r) {
+    if (on_device) {
+        if (hipSetDevice(w->device) != hipSuccess) return AP_ERR_DEVICE;
+        std::vector<uint32_t> in_use;
+        try {
+            for (uint32_t k : kinds) in_use.push_back(rep_type[k]);
+        } catch (const std::bad_alloc&) {
+            return AP_ERR_ALLOC;
+        }
+        TableBounds bounds{};
+        TableBounds* d_bounds = reinterpret_cast<TableBounds*>(w->d_bounds);
+        uint32_t* d_in_use = reinterpret_cast<uint32_t*>(w->d_bounds + sizeof(TableBounds));
+        if (hipMemcpy(d_bounds, &bounds, sizeof(bounds), hipMemcpyHostToDevice) != hipSuccess ||
+            hipMemcpy(d_in_use, in_use.data(), 4u * in_use.size(), hipMemcpyHostToDevice) != hipSuccess) {
+            (void)hipGetLastError();
+            return AP_ERR_DEVICE;
+        }
+        const uint32_t blocks = std::max(1u, std::min(1024u, (w->R + kRoofThreads - 1u) / kRoofThreads));
+        hipLaunchKernelGGL(k_table_bounds, dim3(blocks), dim3(kRoofThreads), 0, nullptr, w->d_tab_prefill, w->d_tab_tpot, d_in_use,
+                           (uint32_t)in_use.size(), w->d_arrival, w->d_out, w->R, d_bounds);
+        if (hipGetLastError() != hipSuccess ||
+            hipMemcpy(&bounds, d_bounds, sizeof(bounds), hipMemcpyDeviceToHost) != hipSuccess) {
+            (void)hipGetLastError();
+            return AP_ERR_DEVICE;
+        }
+        if (bounds.over_range != 0u || bounds.service_sum > limit - latest) return AP_ERR_RANGE;
+        service_sum = bounds.service_sum;
+        total += bounds.service_sum;
+        latest_unqueued = bounds.latest_unqueued;
+        longest_pair = bounds.longest_pair;
+    }
+    for (uint32_t r = 0; r < (on_device ? 0u : w->R); ++r) {
         const uint64_t outl = (uint64_t)w->h_out[r];
         uint64_t worst = 0;
         for (size_t ki = 0; ki < kinds.size(); ++ki) {
@@ -719,7 +778,7 @@ static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint
     }
     if (tabled) {
         const size_t entries = (size_t)T * w->R;
-        if (entries > w->tab_entries) {
+        if (entries > w->tab_entries && !on_device) {
             if ((w->d_tab_prefill && hipFree(w->d_tab_prefill) != hipSuccess) ||
                 (w->d_tab_tpot && hipFree(w->d_tab_tpot) != hipSuccess))
                 return AP_ERR_DEVICE;
@@ -732,8 +791,10 @@ static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint
             }
             w->tab_entries = entries;
         }
-        if (hipMemcpy(w->d_tab_prefill, tab_prefill, entries * 4u, hipMemcpyHostToDevice) != hipSuccess ||
-            hipMemcpy(w->d_tab_tpot, tab_tpot, entries * 4u, hipMemcpyHostToDevice) != hipSuccess) {
+        if (on_device && entries > w->tab_entries) return AP_ERR_STATE;       // the caller filled them: they exist
+        if (!on_device &&
+            (hipMemcpy(w->d_tab_prefill, tab_prefill, entries * 4u, hipMemcpyHostToDevice) != hipSuccess ||
+             hipMemcpy(w->d_tab_tpot, tab_tpot, entries * 4u, hipMemcpyHostToDevice) != hipSuccess)) {
             (void)hipGetLastError();
             w->has_model = false;
             return AP_ERR_DEVICE;
@@ -1042,23 +1103,6 @@ ap_status ap_eval_children(const ap_workload* w, const uint32_t* d_edit_first, c
 // ---- roofline cost tables -------------------------------------------------------------
 namespace {
 
-// Device buffers of one roofline computation; freed when the object goes out of scope.
-struct RoofBuffers {
-    RoofGroup* groups = nullptr;
-    unsigned long long* prefill_ns = nullptr;
-    unsigned long long* step_ns = nullptr;
-    unsigned long long* prefix_ns = nullptr;
-    double* weight_bytes = nullptr;
-    uint32_t* feasible = nullptr;
-    uint32_t* prefill_us = nullptr;
-    uint32_t* tpot_us = nullptr;
-    ~RoofBuffers() {
-        for (void* q : {(void*)groups, (void*)prefill_ns, (void*)step_ns, (void*)prefix_ns, (void*)weight_bytes,
-                        (void*)feasible, (void*)prefill_us, (void*)tpot_us})
-            if (q) (void)hipFree(q);
-    }
-};
-
 // Validate the descriptions and run the table kernels; leaves prefill_ns / prefix_ns / weight_bytes /
 // feasible filled on the device.
 ap_status roofline_tables_on_device(const ap_model* models, uint32_t n_models, const ap_gpu* gpus, uint32_t n_gpus,
@@ -1091,16 +1135,24 @@ ap_status roofline_tables_on_device(const ap_model* models, uint32_t n_models, c
         o.mem = g.mem_bytes;
     }
     const size_t per_group = (size_t)max_seq + 1u;
-    if (hipMalloc(&buf.groups, sizeof(RoofGroup) * n_groups) != hipSuccess ||
-        hipMalloc(&buf.prefill_ns, 8u * per_group * n_groups) != hipSuccess ||
-        hipMalloc(&buf.step_ns, 8u * per_group * n_groups) != hipSuccess ||
-        hipMalloc(&buf.prefix_ns, 8u * (per_group + 1u) * n_groups) != hipSuccess ||
-        hipMalloc(&buf.weight_bytes, 8u * n_groups) != hipSuccess || hipMalloc(&buf.feasible, 4u * n_groups) != hipSuccess) {
-        (void)hipGetLastError();
-        return AP_ERR_ALLOC;
+    if (n_groups > buf.cap_groups || max_seq > buf.cap_seq) {
+        buf.release();
+        if (hipMalloc(&buf.groups, sizeof(RoofGroup) * n_groups) != hipSuccess ||
+            hipMalloc(&buf.prefill_ns, 8u * per_group * n_groups) != hipSuccess ||
+            hipMalloc(&buf.step_ns, 8u * per_group * n_groups) != hipSuccess ||
+            hipMalloc(&buf.prefix_ns, 8u * (per_group + 1u) * n_groups) != hipSuccess ||
+            hipMalloc(&buf.weight_bytes, 8u * n_groups) != hipSuccess || hipMalloc(&buf.feasible, 4u * n_groups) != hipSuccess) {
+            (void)hipGetLastError();
+            buf.release();
+            return AP_ERR_ALLOC;
+        }
+        buf.cap_groups = n_groups;
+        buf.cap_seq = max_seq;
     }
-    if (hipMemcpy(buf.groups, host.data(), sizeof(RoofGroup) * n_groups, hipMemcpyHostToDevice) != hipSuccess)
+    if (hipMemcpy(buf.groups, host.data(), sizeof(RoofGroup) * n_groups, hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipGetLastError();
         return AP_ERR_DEVICE;
+    }
     hipLaunchKernelGGL(k_roofline_steps, dim3((max_seq + kRoofThreads) / kRoofThreads, n_groups), dim3(kRoofThreads), 0, nullptr,
                        buf.groups, n_groups, max_seq, buf.prefill_ns, buf.step_ns, buf.weight_bytes, buf.feasible);
     hipLaunchKernelGGL(k_roofline_prefix, dim3(n_groups), dim3(kRoofThreads), 0, nullptr, buf.step_ns, max_seq, buf.prefix_ns);
@@ -1109,6 +1161,59 @@ ap_status roofline_tables_on_device(const ap_model* models, uint32_t n_models, c
 }
 
 }  // namespace
+
+ap_status ap_costtable_set_roofline(ap_workload* w, const ap_typed_replica* replicas, uint32_t M, uint32_t B,
+                                    const ap_slo* slo, const ap_model* models, uint32_t n_models, const ap_gpu* gpus,
+                                    uint32_t n_gpus, const ap_group* groups, uint32_t n_groups) {
+    if (!w || !replicas || !slo || M == 0 || B == 0 || n_groups == 0) return AP_ERR_INVALID;
+    if (M > AP_MAX_REPLICAS) return AP_ERR_RANGE;
+    if ((uint64_t)n_groups * w->R > 0xFFFFFFFFull) return AP_ERR_RANGE;     // table offsets are 32-bit on the device
+    if (hipSetDevice(w->device) != hipSuccess) return AP_ERR_DEVICE;
+    std::vector<ap_replica> plain;
+    std::vector<uint32_t> types;
+    try {
+        plain.resize(M);
+        types.resize(M);
+        if (!w->roof) w->roof = new RoofBuffers;
+    } catch (const std::bad_alloc&) {
+        return AP_ERR_ALLOC;
+    }
+    for (uint32_t m = 0; m < M; ++m) {
+        if (replicas[m].type >= n_groups) return AP_ERR_INVALID;
+        types[m] = replicas[m].type;
+        plain[m] = ap_replica{0u, 0u, 0u, 0u, replicas[m].t_on_us, replicas[m].t_off_us};
+    }
+    uint64_t longest = 0;                                  // prompt + output of the longest request
+    for (uint32_t r = 0; r < w->R; ++r) longest = std::max<uint64_t>(longest, (uint64_t)w->h_prompt[r] + (uint64_t)w->h_out[r]);
+    if (longest > (1u << 24)) return AP_ERR_RANGE;
+    const ap_status st = roofline_tables_on_device(models, n_models, gpus, n_gpus, groups, n_groups, (uint32_t)longest, *w->roof);
+    if (st != AP_OK) return st;
+    // from here on the previous cost model is gone: the tables it may have read are overwritten
+    w->has_model = false;
+    const size_t entries = (size_t)n_groups * w->R;
+    if (entries > w->tab_entries) {
+        if ((w->d_tab_prefill && hipFree(w->d_tab_prefill) != hipSuccess) || (w->d_tab_tpot && hipFree(w->d_tab_tpot) != hipSuccess)) {
+            (void)hipGetLastError();
+            return AP_ERR_DEVICE;
+        }
+        w->d_tab_prefill = w->d_tab_tpot = nullptr;
+        w->tab_entries = 0;
+        if (hipMalloc(&w->d_tab_prefill, entries * 4u) != hipSuccess || hipMalloc(&w->d_tab_tpot, entries * 4u) != hipSuccess) {
+            (void)hipGetLastError();
+            return AP_ERR_ALLOC;
+        }
+        w->tab_entries = entries;
+    }
+    if (!w->d_bounds && hipMalloc(&w->d_bounds, sizeof(TableBounds) + 4u * AP_MAX_REPLICAS) != hipSuccess) {
+        (void)hipGetLastError();
+        return AP_ERR_ALLOC;
+    }
+    hipLaunchKernelGGL(k_roofline_request_costs, dim3((w->R + kRoofThreads - 1u) / kRoofThreads, n_groups), dim3(kRoofThreads),
+                       0, nullptr, w->roof->prefill_ns, w->roof->prefix_ns, (uint32_t)longest, w->d_prompt, w->d_out, w->R,
+                       w->d_tab_prefill, w->d_tab_tpot);
+    if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
+    return set_cost_model(w, plain.data(), M, B, slo, types.data(), nullptr, nullptr, n_groups);
+}
 
 ap_status ap_roofline_tables(const ap_model* models, uint32_t n_models, const ap_gpu* gpus, uint32_t n_gpus,
                              const ap_group* groups, uint32_t n_groups, uint32_t max_seq, uint64_t* prefill_ns,
@@ -1500,6 +1605,8 @@ ap_status ap_workload_destroy(ap_workload* w) {
     if (w->d_split_queue) ok = (hipFree(w->d_split_queue) == hipSuccess) && ok;
     if (w->d_split_order) ok = (hipFree(w->d_split_order) == hipSuccess) && ok;
     if (w->d_split_scratch) ok = (hipFree(w->d_split_scratch) == hipSuccess) && ok;
+    if (w->d_bounds) ok = (hipFree(w->d_bounds) == hipSuccess) && ok;
+    delete w->roof;
     delete w;
     return ok ? AP_OK : AP_ERR_DEVICE;
 }

@@ -10,8 +10,9 @@ namespace {
 // exact replay as three kernels: group -> replay -> reduce
 // ----------------------------------------------------------------------------------
 // The candidates of a batch are scored by three kernels that hand their intermediates over
-// in a device scratch area sized once by ap_costmodel_set (the batch is cut so that the
-// area stays within the last-level cache):
+// in a device scratch area sized once by ap_costmodel_set (about 1 GiB, cut into whole
+// candidates: enough of them per launch to fill the device; every intermediate is written once
+// and read once, so the area is not meant to stay in cache):
 //   k_group_requests    per candidate and time chunk: replica histogram, scans, ballot-ranked
 //                       stable scatter -> per-replica index lists (queue order = arrival order)
 //   k_replay_queues     one LANE per (candidate, replica) queue; the B slot-free times of a

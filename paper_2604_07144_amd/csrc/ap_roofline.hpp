@@ -142,6 +142,49 @@ __global__ __launch_bounds__(kRoofThreads) void k_roofline_request_costs(const u
     tpot_us[(size_t)gi * R + r] = (uint32_t)min(per_tok, 0xFFFFFFFFull);
 }
 
+// What the host has to know about cost tables that never leave the device before it accepts them: with the
+// service time of request r taken as its longest over the replica types in use (prefill + out_len * tpot),
+//   service_sum     all of them added up (each clamped to 2^33, far beyond what 32-bit time allows anyway),
+//   latest_unqueued the latest arrival + service time,
+//   longest_pair    the longest time from the arrival of request 2q to the unqueued finish of 2q or 2q + 1,
+//   over_range      how many table entries reach the value reserved for "never".
+struct TableBounds {
+    unsigned long long service_sum, latest_unqueued, longest_pair, over_range;
+};
+
+__global__ __launch_bounds__(kRoofThreads) void k_table_bounds(const uint32_t* __restrict__ tab_prefill,
+                                                               const uint32_t* __restrict__ tab_tpot,
+                                                               const uint32_t* __restrict__ types, uint32_t n_types,
+                                                               const uint32_t* __restrict__ arrival,
+                                                               const uint32_t* __restrict__ outlen, uint32_t R,
+                                                               TableBounds* __restrict__ out) {
+    unsigned long long sum = 0, latest = 0, pair = 0, over = 0;
+    for (uint32_t r = blockIdx.x * kRoofThreads + threadIdx.x; r < R; r += gridDim.x * kRoofThreads) {
+        unsigned long long worst = 0;
+        for (uint32_t i = 0; i < n_types; ++i) {
+            const size_t at = (size_t)types[i] * R + r;
+            const uint32_t prefill = tab_prefill[at], tpot = tab_tpot[at];
+            over += (prefill == 0xFFFFFFFFu || tpot == 0xFFFFFFFFu) ? 1ull : 0ull;
+            worst = max(worst, (unsigned long long)prefill + (unsigned long long)outlen[r] * tpot);
+        }
+        sum += min(worst, 1ull << 33);
+        latest = max(latest, (unsigned long long)arrival[r] + worst);
+        pair = max(pair, (unsigned long long)arrival[r] + worst - arrival[r & ~1u]);
+    }
+    for (uint32_t dlt = 32u; dlt != 0u; dlt >>= 1) {
+        sum += (unsigned long long)__shfl_down((long long)sum, dlt);
+        over += (unsigned long long)__shfl_down((long long)over, dlt);
+        latest = max(latest, (unsigned long long)__shfl_down((long long)latest, dlt));
+        pair = max(pair, (unsigned long long)__shfl_down((long long)pair, dlt));
+    }
+    if ((threadIdx.x & 63u) == 0u) {
+        if (sum) atomicAdd(&out->service_sum, sum);
+        if (over) atomicAdd(&out->over_range, over);
+        atomicMax(&out->latest_unqueued, latest);
+        atomicMax(&out->longest_pair, pair);
+    }
+}
+
 // ----------------------------------------------------------------------------------
 // reconfiguration cost and end-to-end trace time
 // ----------------------------------------------------------------------------------

@@ -84,6 +84,93 @@ def test_request_costs_and_the_replay_on_top_of_them():
     assert_same(got, want, "replay on roofline tables")
 
 
+def test_tables_that_stay_on_the_device_and_the_chain_on_one_stream():
+    """Roofline tables -> replay -> trace time without a table or a record crossing to the host in between:
+    ap_costtable_set_roofline fills the workload's own table buffers, ap_eval_candidates leaves its records on the
+    device, one torch operation on the same stream turns makespans into serving times, and ap_trace_time_static
+    (which neither allocates nor waits) adds them up.  The oracle chain: roofline.request_costs ->
+    Oracle.set_cost_tables / eval_batch -> reconfig.trace_time."""
+    from oracle import reconfig as rc
+    tr = traces.make_trace(3, C=48, R=2000, M=12)
+    groups = [rf.Group(1, 0, 1, 8), rf.Group(1, 1, 2, 8), rf.Group(0, 0, 4, 16)]
+    rep_type = (np.arange(tr.M) % 3).astype(np.uint32)
+    rows = tr.assignment_rows(0, 48)
+    n_cand, N = 16, 3                                        # candidate c serves interval i under row 3 c + i
+    models, gpus = MODELS[:2], GPUS[:2]
+    coef = [5.3, 7.0]
+    rng = np.random.default_rng(11)
+    options = np.array([(0, 0), (1, 1), (2, 1), (4, 2)], dtype=np.uint32)
+    plans = options[rng.integers(0, len(options), size=(n_cand, N, len(models), len(gpus)))]
+    n_intervals = np.full(n_cand, N, dtype=np.uint32)
+    sched = rng.integers(0, 10**9, size=n_cand).astype(np.uint64)
+    stale = rng.integers(0, 10**9, size=(n_cand, N)).astype(np.uint64)
+    m, g, q = _pack(MODELS, GPUS, groups)
+    m2, g2, _ = _pack(models, gpus, [rf.Group(0, 0, 1, 1)])
+
+    handle = binding.ap_workload_create(tr.arrival_us, tr.prompt_len, tr.out_len)
+    try:
+        for _ in range(2):                                   # the second call reuses every buffer of the first
+            binding.ap_costtable_set_roofline(handle, rep_type, tr.t_on_us, tr.t_off_us, tr.B, tr.slo_ttft_us,
+                                              tr.slo_tpot_us, tr.penalty_us, m, g, q)
+        stream = torch.cuda.current_stream().cuda_stream
+        d_assign = torch.from_numpy(np.ascontiguousarray(rows, dtype=np.uint16).view(np.int16)).cuda()
+        d_plans = torch.from_numpy(np.ascontiguousarray(plans).view(np.int32)).cuda()
+        d_n = torch.from_numpy(n_intervals.view(np.int32)).cuda()
+        d_sched = torch.from_numpy(sched.view(np.int64)).cuda()
+        d_stale = torch.from_numpy(stale.view(np.int64)).cuda()
+        d_metrics = torch.full((48, 8), -1, dtype=torch.int64, device="cuda")
+        d_total = torch.full((n_cand, 6), -1, dtype=torch.int64, device="cuda")
+        torch.cuda.synchronize()                             # inputs are in place; nothing below waits for the device
+        binding.ap_eval_candidates(handle, d_assign.data_ptr(), 48, d_metrics.data_ptr(), stream)
+        d_serve = (d_metrics[:, 3] * 1000).reshape(n_cand, N).contiguous()       # makespan_us -> t_serve in ns
+        binding.ap_trace_time_static(m2, coef, g2, d_plans.data_ptr(), d_n.data_ptr(), d_sched.data_ptr(),
+                                     d_stale.data_ptr(), d_serve.data_ptr(), n_cand, N, d_total.data_ptr(),
+                                     binding.AP_LOAD_DEPLOYED, stream)
+        torch.cuda.synchronize()
+        got_metrics = d_metrics.cpu().numpy().view(binding.METRICS_DTYPE).reshape(-1)
+        got = d_total.cpu().numpy().view(binding.BREAKDOWN_DTYPE).reshape(-1)
+    finally:
+        binding.ap_workload_destroy(handle)
+
+    want_pre, want_tpot = rf.request_costs(MODELS, GPUS, groups, tr.prompt_len, tr.out_len)
+    want_metrics = oracle_for(tr).set_cost_tables(rep_type, want_pre, want_tpot).eval_batch(rows, nthreads=8)
+    assert_same(got_metrics, want_metrics, "replay on tables that never left the device")
+    serve = (want_metrics["makespan_us"].astype(np.uint64) * np.uint64(1000)).reshape(n_cand, N)
+    tau = rc.transfer_ns(models, coef, gpus)
+    for c in range(n_cand):
+        n, s_stale, s_reconfig, s_serve, total = rc.trace_time(tau, plans[c], n_intervals[c], sched[c], stale[c], serve[c],
+                                                               "deployed")
+        assert tuple(int(x) for x in got[c]) == (total, s_stale, s_reconfig, s_serve, int(sched[c]), n, 0), c
+    assert len(set(int(x) for x in got["sum_reconfig_ns"])) > 4 and int(got["sum_serve_ns"].min()) > 0
+
+
+def test_chained_tables_error_paths():
+    tr = traces.make_trace(3, C=4, R=300, M=6)
+    m, g, q = _pack(MODELS, GPUS, [rf.Group(1, 0, 1, 8), rf.Group(0, 0, 4, 16)])
+    handle = binding.ap_workload_create(tr.arrival_us, tr.prompt_len, tr.out_len)
+    try:
+        def status(rep_type, groups=q, B=tr.B):
+            with pytest.raises(binding.ApError) as e:
+                binding.ap_costtable_set_roofline(handle, rep_type, tr.t_on_us, tr.t_off_us, B, tr.slo_ttft_us,
+                                                  tr.slo_tpot_us, tr.penalty_us, m, g, groups)
+            return e.value.status
+        assert status(np.array([0, 1, 2, 0, 1, 0], np.uint32)) == binding.AP_ERR_INVALID       # type 2 of 2 groups
+        bad = q.copy()
+        bad["model"] = 9
+        assert status(np.zeros(6, np.uint32), bad) == binding.AP_ERR_INVALID
+        assert status(np.zeros(6, np.uint32), B=0) == binding.AP_ERR_INVALID
+        # a 70B-class model on one slow GPU: a service time of hours does not fit 32-bit microseconds
+        slow = _pack(MODELS, GPUS, [rf.Group(2, 2, 1, 64)])[2]
+        assert status(np.zeros(6, np.uint32), slow) == binding.AP_ERR_RANGE
+        d_assign = torch.zeros((1, tr.R), dtype=torch.int16, device="cuda")
+        d_out = torch.zeros((1, 8), dtype=torch.int64, device="cuda")
+        with pytest.raises(binding.ApError) as e:           # the failed call left no cost model behind
+            binding.ap_eval_candidates(handle, d_assign.data_ptr(), 1, d_out.data_ptr(), 0)
+        assert e.value.status == binding.AP_ERR_STATE
+    finally:
+        binding.ap_workload_destroy(handle)
+
+
 def test_error_paths():
     torch.cuda.init()
     m, g, q = _pack(MODELS[:1], GPUS[:1], [rf.Group(0, 0, 1, 1)])
