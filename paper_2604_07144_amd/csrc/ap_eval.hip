@@ -75,6 +75,13 @@ EvalKernel eval_kernel(bool hist16, bool len16, bool tabled) {
 constexpr size_t kNominalSumsBytes = 3u * kBins * sizeof(uint32_t) + 3u * sizeof(unsigned long long) + 4u * sizeof(uint32_t);
 
 namespace {
+// Every failed device call ends here: HIP keeps the error of a failed call until somebody reads it, and the next,
+// unrelated call must not find it.
+ap_status device_error() {
+    (void)hipGetLastError();
+    return AP_ERR_DEVICE;
+}
+
 // Device buffers of one roofline computation; freed when the object goes out of scope.
 struct RoofBuffers {
     RoofGroup* groups = nullptr;
@@ -216,7 +223,7 @@ static ap_status launch_dense(const ap_workload* w, const uint16_t* d_assign, ui
             hipLaunchKernelGGL(narrow[(aligned ? 1 : 0) + (marked ? 2 : 0)], dim3(grid), dim3(kScreenThreads),
                                w->screen_lds_bytes, stream, w->screen_params, d_assign, d_out, C, flags);
         }
-        if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
+        if (hipGetLastError() != hipSuccess) return device_error();
     }
     if (w->split && !marked) {
         // the listed / streamed evaluation, a batch of candidates at a time; what it hands back carries the pending mark
@@ -258,7 +265,7 @@ static ap_status launch_dense(const ap_workload* w, const uint16_t* d_assign, ui
                                dim3(std::min(n, w->n_cu * 8u)), dim3(kThreads), w->reduce_lds_bytes,
                                stream, w->reduce_eval, sp, d_out, c0, n, flags);
         }
-        if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
+        if (hipGetLastError() != hipSuccess) return device_error();
     }
     const uint32_t pending_only = (w->screen || (w->split && !marked)) ? 1u : 0u;
     if (w->pipeline) {
@@ -272,7 +279,7 @@ static ap_status launch_dense(const ap_workload* w, const uint16_t* d_assign, ui
             hipLaunchKernelGGL(w->hist16 ? k_reduce_candidates<true> : k_reduce_candidates<false>, dim3(n), dim3(kThreads),
                                w->reduce_lds_bytes, stream, w->reduce_eval, w->reduce_params, d_out, c0, n, pending_only);
         }
-        if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
+        if (hipGetLastError() != hipSuccess) return device_error();
         return AP_OK;
     }
     // After screening, most workgroups only find out that nothing is left for them: as many as can be
@@ -280,7 +287,7 @@ static ap_status launch_dense(const ap_workload* w, const uint16_t* d_assign, ui
     const uint32_t grid = std::min(C, pending_only ? w->resident_grid : w->max_grid);
     hipLaunchKernelGGL(eval_kernel(w->hist16, w->len16, w->tabled), dim3(grid), dim3(kThreads), w->lds_bytes, stream, w->params,
                        d_assign, d_out, C, pending_only, flags);
-    if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
+    if (hipGetLastError() != hipSuccess) return device_error();
     return AP_OK;
 }
 
@@ -532,7 +539,7 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
     off += kSplitWaves * wb;
     sp.off_hist = off;
     int lds_cap = 0;
-    if (hipDeviceGetAttribute(&lds_cap, hipDeviceAttributeMaxSharedMemoryPerBlock, w->device) != hipSuccess) return AP_ERR_DEVICE;
+    if (hipDeviceGetAttribute(&lds_cap, hipDeviceAttributeMaxSharedMemoryPerBlock, w->device) != hipSuccess) return device_error();
     if (off + hist_bytes > (uint32_t)lds_cap) return AP_OK;  // a replica table that large stays with the general replay
     w->split_lds_bytes = off;
     w->split_lds_bytes_hist = off + hist_bytes;
@@ -542,7 +549,7 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
         hipFuncSetAttribute(reinterpret_cast<const void*>(split_kernel(wide ? 2u : 1u, narrow)),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)(off + hist_bytes)) != hipSuccess) {
         (void)hipGetLastError();
-        return AP_ERR_DEVICE;
+        return device_error();
     }
     w->split_slots = B <= 8u ? 8u : B <= 16u ? 16u : B <= 32u ? 32u : 64u;
 
@@ -559,7 +566,7 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
     const size_t o_part = carve(total, (size_t)batch * sizeof(SplitPartial));
     const size_t o_hist = carve(total, (size_t)batch * hist_bytes);
     if (total > w->split_scratch_bytes) {
-        if (w->d_split_scratch && hipFree(w->d_split_scratch) != hipSuccess) return AP_ERR_DEVICE;
+        if (w->d_split_scratch && hipFree(w->d_split_scratch) != hipSuccess) return device_error();
         w->d_split_scratch = nullptr;
         w->split_scratch_bytes = 0;
         if (hipMalloc(&w->d_split_scratch, total) != hipSuccess) {
@@ -583,7 +590,7 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
                                  : reinterpret_cast<const void*>(&k_merge_candidates<true>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)w->reduce_lds_bytes) != hipSuccess) {
         (void)hipGetLastError();
-        return AP_ERR_DEVICE;
+        return device_error();
     }
     sp.req8 = w->d_req8;
     sp.tab.range = w->d_split_tab;
@@ -611,8 +618,23 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
 // coefficients are ignored).
 // tab_prefill == nullptr with rep_type set: the tables are in the workload's device buffers already
 // (ap_costtable_set_roofline) and the bounds come from a reduction over them.
+static ap_status set_cost_model_checked(ap_workload* w, const ap_replica* replicas, uint32_t M, uint32_t B, const ap_slo* slo,
+                                        const uint32_t* rep_type, const uint32_t* tab_prefill, const uint32_t* tab_tpot,
+                                        uint32_t T);
+
 static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint32_t M, uint32_t B, const ap_slo* slo,
                                 const uint32_t* rep_type, const uint32_t* tab_prefill, const uint32_t* tab_tpot, uint32_t T) {
+    try {                                                   // host containers allocate: nothing may leave through the C ABI
+        return set_cost_model_checked(w, replicas, M, B, slo, rep_type, tab_prefill, tab_tpot, T);
+    } catch (const std::bad_alloc&) {
+        if (w) w->has_model = false;
+        return AP_ERR_ALLOC;
+    }
+}
+
+static ap_status set_cost_model_checked(ap_workload* w, const ap_replica* replicas, uint32_t M, uint32_t B, const ap_slo* slo,
+                                        const uint32_t* rep_type, const uint32_t* tab_prefill, const uint32_t* tab_tpot,
+                                        uint32_t T) {
     if (!w || !replicas || !slo || M == 0 || B == 0) return AP_ERR_INVALID;
     const bool tabled = rep_type != nullptr;
     const bool on_device = tabled && tab_prefill == nullptr;
@@ -670,7 +692,7 @@ static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint
         return AP_ERR_ALLOC;
     }
     if (on_device) {
-        if (hipSetDevice(w->device) != hipSuccess) return AP_ERR_DEVICE;
+        if (hipSetDevice(w->device) != hipSuccess) return device_error();
         std::vector<uint32_t> in_use;
         try {
             for (uint32_t k : kinds) in_use.push_back(rep_type[k]);
@@ -683,7 +705,7 @@ static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint
         if (hipMemcpy(d_bounds, &bounds, sizeof(bounds), hipMemcpyHostToDevice) != hipSuccess ||
             hipMemcpy(d_in_use, in_use.data(), 4u * in_use.size(), hipMemcpyHostToDevice) != hipSuccess) {
             (void)hipGetLastError();
-            return AP_ERR_DEVICE;
+            return device_error();
         }
         const uint32_t blocks = std::max(1u, std::min(1024u, (w->R + kRoofThreads - 1u) / kRoofThreads));
         hipLaunchKernelGGL(k_table_bounds, dim3(blocks), dim3(kRoofThreads), 0, nullptr, w->d_tab_prefill, w->d_tab_tpot, d_in_use,
@@ -691,7 +713,7 @@ static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint
         if (hipGetLastError() != hipSuccess ||
             hipMemcpy(&bounds, d_bounds, sizeof(bounds), hipMemcpyDeviceToHost) != hipSuccess) {
             (void)hipGetLastError();
-            return AP_ERR_DEVICE;
+            return device_error();
         }
         if (bounds.over_range != 0u || bounds.service_sum > limit - latest) return AP_ERR_RANGE;
         service_sum = bounds.service_sum;
@@ -720,11 +742,11 @@ static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint
     }
 
     // ---- LDS plan: the largest chunk that fits ------------------------------------------
-    if (hipSetDevice(w->device) != hipSuccess) return AP_ERR_DEVICE;
+    if (hipSetDevice(w->device) != hipSuccess) return device_error();
     int lds_cap = 0, n_cu = 0;
     if (hipDeviceGetAttribute(&lds_cap, hipDeviceAttributeMaxSharedMemoryPerBlock, w->device) != hipSuccess ||
         hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, w->device) != hipSuccess)
-        return AP_ERR_DEVICE;
+        return device_error();
     EvalParams p{};
     p.M = M;
     p.B = B;
@@ -739,7 +761,7 @@ static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint
     {   // what the kernel itself declares (nothing today) comes off the dynamic part
         hipFuncAttributes attr;
         if (hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(eval_kernel(hist16, w->len16, tabled))) != hipSuccess)
-            return AP_ERR_DEVICE;
+            return device_error();
         lds_cap -= (int)std::min<size_t>(attr.sharedSizeBytes, (size_t)lds_cap);
     }
     for (uint32_t budget : {(uint32_t)lds_cap / 2u, (uint32_t)lds_cap}) {
@@ -781,7 +803,7 @@ static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint
         if (entries > w->tab_entries && !on_device) {
             if ((w->d_tab_prefill && hipFree(w->d_tab_prefill) != hipSuccess) ||
                 (w->d_tab_tpot && hipFree(w->d_tab_tpot) != hipSuccess))
-                return AP_ERR_DEVICE;
+                return device_error();
             w->d_tab_prefill = w->d_tab_tpot = nullptr;
             w->tab_entries = 0;
             w->has_model = false;     // the previous model may have pointed at the freed tables
@@ -797,7 +819,7 @@ static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint
              hipMemcpy(w->d_tab_tpot, tab_tpot, entries * 4u, hipMemcpyHostToDevice) != hipSuccess)) {
             (void)hipGetLastError();
             w->has_model = false;
-            return AP_ERR_DEVICE;
+            return device_error();
         }
     }
     if (hipMemcpy(w->d_rep, dev.data(), sizeof(DevReplica) * M, hipMemcpyHostToDevice) != hipSuccess ||
@@ -808,7 +830,7 @@ static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)reduce_lds) != hipSuccess) {
         (void)hipGetLastError();
         w->has_model = false;     // the replica table on the device may be half-written
-        return AP_ERR_DEVICE;
+        return device_error();
     }
 
     p.arrival = w->d_arrival;
@@ -826,7 +848,7 @@ static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint
     p.penalty_bin = ap_hist_bin(slo->penalty_us);
     p.k99 = (uint32_t)((99ull * w->R + 99ull) / 100ull);
     p.replayed = w->d_pending + 2;
-    if (hipMemset(p.replayed, 0, sizeof(uint32_t)) != hipSuccess) return AP_ERR_DEVICE;
+    if (hipMemset(p.replayed, 0, sizeof(uint32_t)) != hipSuccess) return device_error();
     w->n_scored = 0;
     w->has_model = false;
     w->has_parent = false;    // its analysis belonged to the previous cost model
@@ -861,7 +883,7 @@ static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint
         const size_t o_part = carve(off, (size_t)batch * M * sizeof(QueuePartial));
         const size_t o_unk = carve(off, (size_t)batch * 4u);
         if (off > w->scratch_bytes) {
-            if (w->d_scratch && hipFree(w->d_scratch) != hipSuccess) return AP_ERR_DEVICE;
+            if (w->d_scratch && hipFree(w->d_scratch) != hipSuccess) return device_error();
             w->d_scratch = nullptr;
             w->scratch_bytes = 0;
             if (hipMalloc(&w->d_scratch, off) != hipSuccess) {
@@ -870,7 +892,7 @@ static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint
             }
             w->scratch_bytes = off;
         }
-        if (hipMemset(w->d_scratch + o_unk, 0, (size_t)batch * 4u) != hipSuccess) return AP_ERR_DEVICE;
+        if (hipMemset(w->d_scratch + o_unk, 0, (size_t)batch * 4u) != hipSuccess) return device_error();
         w->batch = batch;
         GroupParams gp{};
         gp.R = R; gp.M = M; gp.chunk = chunk_g; gp.n_chunks = n_chunks; gp.key_bits = p.key_bits; gp.qs_stride = qs_stride;
@@ -897,7 +919,7 @@ static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint
         if (hipFuncSetAttribute(hist16 ? reinterpret_cast<const void*>(&k_reduce_candidates<true>)
                                        : reinterpret_cast<const void*>(&k_reduce_candidates<false>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)w->reduce_lds_bytes) != hipSuccess)
-            return AP_ERR_DEVICE;
+            return device_error();
     }
 
     // ---- screening plan: only for identical replicas that are available throughout ------
@@ -948,7 +970,7 @@ static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint
         w->screen_lds_bytes = kScreenWaves * sp.wave_bytes;
         // a thread takes two requests per turn; enough workgroups for four turns each, at most one per compute unit
         const uint32_t n_groups = std::max(1u, std::min((uint32_t)n_cu, (w->R + 8u * kThreads - 1u) / (8u * kThreads)));
-        if (hipMemsetAsync(w->d_nominal_sums, 0, kNominalSumsBytes, nullptr) != hipSuccess) return AP_ERR_DEVICE;
+        if (hipMemsetAsync(w->d_nominal_sums, 0, kNominalSumsBytes, nullptr) != hipSuccess) return device_error();
         hipLaunchKernelGGL(hist16 ? k_nominal_metrics<true> : k_nominal_metrics<false>, dim3(n_groups), dim3(kThreads),
                            reduce_lds, nullptr, w->reduce_eval, w->d_span, w->d_span_t,
                            w->screen_packed ? w->d_pair : nullptr, (uint32_t)tick_us,
@@ -956,7 +978,7 @@ static ap_status set_cost_model(ap_workload* w, const ap_replica* replicas, uint
                            reinterpret_cast<unsigned long long*>(w->d_nominal_sums + 3u * kBins * sizeof(uint32_t)), w->d_nominal);
         if (hipGetLastError() != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
             (void)hipGetLastError();
-            return AP_ERR_DEVICE;
+            return device_error();
         }
     }
     // ---- split evaluation: replicas that differ or have windows ---------------------------
@@ -1011,7 +1033,7 @@ ap_status ap_eval_counts_get(const ap_workload* w, ap_eval_counts* out) {
     if (hipSetDevice(w->device) != hipSuccess || hipDeviceSynchronize() != hipSuccess ||
         hipMemcpy(&replayed, w->d_pending + 2, sizeof(uint32_t), hipMemcpyDeviceToHost) != hipSuccess) {
         (void)hipGetLastError();
-        return AP_ERR_DEVICE;
+        return device_error();
     }
     out->candidates = w->n_scored;
     out->replayed = replayed;
@@ -1021,7 +1043,7 @@ ap_status ap_eval_counts_get(const ap_workload* w, ap_eval_counts* out) {
 ap_status ap_parent_set(ap_workload* w, const uint16_t* parent, uint32_t max_children) {
     if (!w || !parent || max_children == 0) return AP_ERR_INVALID;
     if (!w->has_model) return AP_ERR_STATE;
-    if (hipSetDevice(w->device) != hipSuccess) return AP_ERR_DEVICE;
+    if (hipSetDevice(w->device) != hipSuccess) return device_error();
     w->has_parent = false;
     if ((uint64_t)max_children > (UINT64_MAX / sizeof(uint16_t)) / w->R) return AP_ERR_ALLOC;     // the rows cannot exist
     const size_t need = (size_t)max_children * w->R * sizeof(uint16_t);
@@ -1034,7 +1056,7 @@ ap_status ap_parent_set(ap_workload* w, const uint16_t* parent, uint32_t max_chi
         return AP_ERR_ALLOC;
     }
     if (need > w->rows_bytes) {
-        if (w->d_rows && hipFree(w->d_rows) != hipSuccess) return AP_ERR_DEVICE;
+        if (w->d_rows && hipFree(w->d_rows) != hipSuccess) return device_error();
         w->d_rows = nullptr;
         w->rows_bytes = 0;
         if (hipMalloc(&w->d_rows, need) != hipSuccess) {
@@ -1045,7 +1067,7 @@ ap_status ap_parent_set(ap_workload* w, const uint16_t* parent, uint32_t max_chi
     }
     // through the pinned buffer: upload, analysis and read-back are queued together and waited for once
     std::memcpy(w->h_stage, parent, row_bytes);
-    if (hipMemcpyAsync(w->d_parent, w->h_stage, row_bytes, hipMemcpyHostToDevice, nullptr) != hipSuccess) return AP_ERR_DEVICE;
+    if (hipMemcpyAsync(w->d_parent, w->h_stage, row_bytes, hipMemcpyHostToDevice, nullptr) != hipSuccess) return device_error();
     const uint32_t M = w->params.M;
     bool certify = false;
     if (w->screen) {
@@ -1057,7 +1079,7 @@ ap_status ap_parent_set(ap_workload* w, const uint16_t* parent, uint32_t max_chi
             hipMemcpyAsync(w->h_stage, w->d_peak, sizeof(uint32_t) * (M + 1u), hipMemcpyDeviceToHost, nullptr) != hipSuccess ||
             hipStreamSynchronize(nullptr) != hipSuccess) {
             (void)hipGetLastError();
-            return AP_ERR_DEVICE;
+            return device_error();
         }
         const uint32_t* peak = reinterpret_cast<const uint32_t*>(w->h_stage);
         // ... and a parent that is contention-free itself and names only replicas of the table
@@ -1065,7 +1087,7 @@ ap_status ap_parent_set(ap_workload* w, const uint16_t* parent, uint32_t max_chi
         for (uint32_t m = 0; m < M; ++m) certify = certify && peak[m] <= w->params.B;
     } else if (hipStreamSynchronize(nullptr) != hipSuccess) {
         (void)hipGetLastError();
-        return AP_ERR_DEVICE;
+        return device_error();
     }
     ChildParams cp{};
     cp.parent = w->d_parent;
@@ -1096,7 +1118,7 @@ ap_status ap_eval_children(const ap_workload* w, const uint32_t* d_edit_first, c
     const PendingWord flags = take_pending_word(w);
     hipLaunchKernelGGL(k_certify_children, dim3(blocks), dim3(kChildThreads), (kChildWaves + 1u) * w->child_params.M * 4u, stream,
                        w->child_params, d_edit_first, d_edit_request, d_edit_replica, d_out, C, flags);
-    if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
+    if (hipGetLastError() != hipSuccess) return device_error();
     return launch_dense(w, w->d_rows, C, d_out, stream, w->child_params.certify != 0u, flags);
 }
 
@@ -1151,12 +1173,12 @@ ap_status roofline_tables_on_device(const ap_model* models, uint32_t n_models, c
     }
     if (hipMemcpy(buf.groups, host.data(), sizeof(RoofGroup) * n_groups, hipMemcpyHostToDevice) != hipSuccess) {
         (void)hipGetLastError();
-        return AP_ERR_DEVICE;
+        return device_error();
     }
     hipLaunchKernelGGL(k_roofline_steps, dim3((max_seq + kRoofThreads) / kRoofThreads, n_groups), dim3(kRoofThreads), 0, nullptr,
                        buf.groups, n_groups, max_seq, buf.prefill_ns, buf.step_ns, buf.weight_bytes, buf.feasible);
     hipLaunchKernelGGL(k_roofline_prefix, dim3(n_groups), dim3(kRoofThreads), 0, nullptr, buf.step_ns, max_seq, buf.prefix_ns);
-    if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
+    if (hipGetLastError() != hipSuccess) return device_error();
     return AP_OK;
 }
 
@@ -1168,7 +1190,7 @@ ap_status ap_costtable_set_roofline(ap_workload* w, const ap_typed_replica* repl
     if (!w || !replicas || !slo || M == 0 || B == 0 || n_groups == 0) return AP_ERR_INVALID;
     if (M > AP_MAX_REPLICAS) return AP_ERR_RANGE;
     if ((uint64_t)n_groups * w->R > 0xFFFFFFFFull) return AP_ERR_RANGE;     // table offsets are 32-bit on the device
-    if (hipSetDevice(w->device) != hipSuccess) return AP_ERR_DEVICE;
+    if (hipSetDevice(w->device) != hipSuccess) return device_error();
     std::vector<ap_replica> plain;
     std::vector<uint32_t> types;
     try {
@@ -1194,7 +1216,7 @@ ap_status ap_costtable_set_roofline(ap_workload* w, const ap_typed_replica* repl
     if (entries > w->tab_entries) {
         if ((w->d_tab_prefill && hipFree(w->d_tab_prefill) != hipSuccess) || (w->d_tab_tpot && hipFree(w->d_tab_tpot) != hipSuccess)) {
             (void)hipGetLastError();
-            return AP_ERR_DEVICE;
+            return device_error();
         }
         w->d_tab_prefill = w->d_tab_tpot = nullptr;
         w->tab_entries = 0;
@@ -1211,7 +1233,7 @@ ap_status ap_costtable_set_roofline(ap_workload* w, const ap_typed_replica* repl
     hipLaunchKernelGGL(k_roofline_request_costs, dim3((w->R + kRoofThreads - 1u) / kRoofThreads, n_groups), dim3(kRoofThreads),
                        0, nullptr, w->roof->prefill_ns, w->roof->prefix_ns, (uint32_t)longest, w->d_prompt, w->d_out, w->R,
                        w->d_tab_prefill, w->d_tab_tpot);
-    if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
+    if (hipGetLastError() != hipSuccess) return device_error();
     return set_cost_model(w, plain.data(), M, B, slo, types.data(), nullptr, nullptr, n_groups);
 }
 
@@ -1234,7 +1256,7 @@ ap_status ap_roofline_tables(const ap_model* models, uint32_t n_models, const ap
         hipMemcpy(weight_bytes, buf.weight_bytes, 8u * n_groups, hipMemcpyDeviceToHost) != hipSuccess ||
         hipMemcpy(ok.data(), buf.feasible, 4u * n_groups, hipMemcpyDeviceToHost) != hipSuccess) {
         (void)hipGetLastError();
-        return AP_ERR_DEVICE;
+        return device_error();
     }
     for (uint32_t i = 0; i < n_groups; ++i) feasible[i] = ok[i] ? 1u : 0u;
     return AP_OK;
@@ -1244,7 +1266,7 @@ ap_status ap_roofline_costs(const ap_workload* w, const ap_model* models, uint32
                             uint32_t n_gpus, const ap_group* groups, uint32_t n_groups, uint32_t* prefill_us,
                             uint32_t* tpot_us) {
     if (!w || !prefill_us || !tpot_us) return AP_ERR_INVALID;
-    if (hipSetDevice(w->device) != hipSuccess) return AP_ERR_DEVICE;
+    if (hipSetDevice(w->device) != hipSuccess) return device_error();
     uint64_t longest = 0;                                  // prompt + output of the longest request
     for (uint32_t r = 0; r < w->R; ++r) longest = std::max<uint64_t>(longest, (uint64_t)w->h_prompt[r] + (uint64_t)w->h_out[r]);
     if (longest > (1u << 24)) return AP_ERR_RANGE;
@@ -1263,7 +1285,7 @@ ap_status ap_roofline_costs(const ap_workload* w, const ap_model* models, uint32
         hipMemcpy(prefill_us, buf.prefill_us, 4u * entries, hipMemcpyDeviceToHost) != hipSuccess ||
         hipMemcpy(tpot_us, buf.tpot_us, 4u * entries, hipMemcpyDeviceToHost) != hipSuccess) {
         (void)hipGetLastError();
-        return AP_ERR_DEVICE;
+        return device_error();
     }
     return AP_OK;
 }
@@ -1321,7 +1343,7 @@ ap_status ap_trace_time(const ap_model* models, const double* pcie_coef, uint32_
         hipMemcpy(tmp.coef, pcie_coef, 8u * n_models, hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(tmp.pcie, pcie.data(), 8u * n_gpus, hipMemcpyHostToDevice) != hipSuccess) {
         (void)hipGetLastError();
-        return AP_ERR_DEVICE;
+        return device_error();
     }
     hipLaunchKernelGGL(k_transfer_times, dim3((n_models * n_gpus + kRoofThreads - 1u) / kRoofThreads), dim3(kRoofThreads), 0, stream,
                        tmp.models, tmp.coef, n_models, tmp.pcie, n_gpus, tmp.tau);
@@ -1338,7 +1360,7 @@ ap_status ap_trace_time(const ap_model* models, const double* pcie_coef, uint32_
     // the temporary tables are freed on return: wait for the stream
     if (hipGetLastError() != hipSuccess || hipStreamSynchronize(stream) != hipSuccess) {
         (void)hipGetLastError();
-        return AP_ERR_DEVICE;
+        return device_error();
     }
     return AP_OK;
 }
@@ -1375,7 +1397,7 @@ ap_status ap_trace_time_static(const ap_model* models, const double* pcie_coef, 
         args.pcie[g] = gpus[g].pcie_bytes_per_s;
     }
     int device = 0;
-    if (hipGetDevice(&device) != hipSuccess) return AP_ERR_DEVICE;
+    if (hipGetDevice(&device) != hipSuccess) return device_error();
     if (device < 0 || device >= kScratchDevices) return AP_ERR_RANGE;
     unsigned long long* tau = nullptr;
     {
@@ -1384,7 +1406,7 @@ ap_status ap_trace_time_static(const ap_model* models, const double* pcie_coef, 
             void* at = nullptr;
             if (hipGetSymbolAddress(&at, HIP_SYMBOL(scratch)) != hipSuccess || !at) {
                 (void)hipGetLastError();
-                return AP_ERR_DEVICE;
+                return device_error();
             }
             trace_scratch_at[device] = static_cast<unsigned long long*>(at);
         }
@@ -1404,7 +1426,7 @@ ap_status ap_trace_time_static(const ap_model* models, const double* pcie_coef, 
     tp.C = C; tp.N_max = N_max; tp.Z = n_models; tp.G = n_gpus;
     tp.load_changed_only = load_scope == AP_LOAD_CHANGED ? 1u : 0u;
     hipLaunchKernelGGL(k_trace_time, dim3((C + kRoofThreads - 1u) / kRoofThreads), dim3(kRoofThreads), 0, stream, tp, d_out);
-    if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
+    if (hipGetLastError() != hipSuccess) return device_error();
     return AP_OK;
 }
 
@@ -1482,24 +1504,29 @@ ap_status ap_agentic_create(const uint64_t* arrival_us, const uint64_t* slo_us, 
         delete a;
         return AP_ERR_ALLOC;
     }
-    for (uint32_t k = 0; k < K; ++k) {
-        // a predecessor listed twice counts once: keep distinct ones
-        std::vector<uint32_t> mine(pred + pred_first[k], pred + pred_first[k + 1u]);
-        std::sort(mine.begin(), mine.end());
-        mine.erase(std::unique(mine.begin(), mine.end()), mine.end());
-        if (mine.size() > 255u) { delete a; return AP_ERR_RANGE; }
-        n_pred_of[k] = (uint32_t)mine.size();
-        for (uint32_t j : mine) ++succ_first[j + 1u];
-    }
-    for (uint32_t k = 0; k < K; ++k) succ_first[k + 1u] += succ_first[k];
-    {
-        std::vector<uint32_t> fill(succ_first.begin(), succ_first.end() - 1);
+    try {                                                   // the temporaries below allocate
         for (uint32_t k = 0; k < K; ++k) {
+            // a predecessor listed twice counts once: keep distinct ones
             std::vector<uint32_t> mine(pred + pred_first[k], pred + pred_first[k + 1u]);
             std::sort(mine.begin(), mine.end());
             mine.erase(std::unique(mine.begin(), mine.end()), mine.end());
-            for (uint32_t j : mine) succ[fill[j]++] = k;
+            if (mine.size() > 255u) { delete a; return AP_ERR_RANGE; }
+            n_pred_of[k] = (uint32_t)mine.size();
+            for (uint32_t j : mine) ++succ_first[j + 1u];
         }
+        for (uint32_t k = 0; k < K; ++k) succ_first[k + 1u] += succ_first[k];
+        {
+            std::vector<uint32_t> fill(succ_first.begin(), succ_first.end() - 1);
+            for (uint32_t k = 0; k < K; ++k) {
+                std::vector<uint32_t> mine(pred + pred_first[k], pred + pred_first[k + 1u]);
+                std::sort(mine.begin(), mine.end());
+                mine.erase(std::unique(mine.begin(), mine.end()), mine.end());
+                for (uint32_t j : mine) succ[fill[j]++] = k;
+            }
+        }
+    } catch (const std::bad_alloc&) {
+        delete a;
+        return AP_ERR_ALLOC;
     }
     for (uint32_t i = 0; i < P; ++i) { pa[i] = prefill[i].base_us; pb[i] = prefill[i].per_tok_us; }
     for (uint32_t i = 0; i < Q; ++i) { qc[i] = decode[i].base_us; qd[i] = decode[i].per_kctx_us; cap[i] = decode[i].capacity_tokens; }
@@ -1567,7 +1594,7 @@ ap_status ap_agentic_eval(const ap_agentic* a, const uint16_t* d_prefill, const 
     const uint32_t blocks = std::min((C + kAgenticWaves - 1u) / kAgenticWaves, a->n_cu * 64u);
     hipLaunchKernelGGL(k_agentic_eval, dim3(blocks), dim3(kAgenticThreads), a->lds_bytes, static_cast<hipStream_t>(hip_stream),
                        a->params, d_prefill, d_decode, d_key, d_out, C);
-    if (hipGetLastError() != hipSuccess) return AP_ERR_DEVICE;
+    if (hipGetLastError() != hipSuccess) return device_error();
     return AP_OK;
 }
 

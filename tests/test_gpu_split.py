@@ -120,3 +120,58 @@ def test_tile_and_table_edges(n, M, B):
     both(tr, rows(9, n, M + 1, seed=n), f"edges n={n} M={M} B={B}")
     still = elastic(n, M, B, 2000.0, seed=n + M + 1, closing=False)
     both(still, rows(9, n, M, seed=n + 1), f"edges, nobody leaves n={n} M={M} B={B}")
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes_windows_and_objectives(seed):
+    """Shapes, loads, windows and objectives drawn at random: calm to heavily overloaded, one to three kinds of
+    replica, windows inside, around and outside the trace, penalties above and below the served latencies, rows with
+    unknown replica ids and rows that name a single replica."""
+    rng = np.random.default_rng(1000 + seed)
+    n = int(rng.choice([1, 2, 65, 700, 1024, 3000, 5000]))
+    M = int(rng.choice([1, 2, 7, 33, 64, 65, 140]))
+    B = int(rng.choice([1, 2, 7, 8, 16, 31, 64]))
+    per_slot = float(rng.choice([0.02, 0.2, 1.0, 5.0]))                 # requests in service per slot, roughly
+    rate = max(50.0, per_slot * M * B / 0.012)                          # a request is in service for about 12 ms
+    closing = bool(rng.integers(0, 2))
+    kw = {}
+    if rng.integers(0, 3) == 0:
+        kw["penalty_us"] = int(rng.choice([1, 900, 50_000]))
+    if rng.integers(0, 3) == 0:
+        kw["slo_ttft_us"], kw["slo_tpot_us"] = int(rng.choice([0, 4000, 10**9])), int(rng.choice([0, 40, 10**6]))
+    tr = elastic(n, M, B, rate, seed=2000 + seed, closing=closing, **kw)
+    t_on, t_off = tr.t_on_us.copy(), tr.t_off_us.copy()
+    for m in range(M):                                                  # some windows that do not cut the trace
+        pick = rng.integers(0, 8)
+        if pick == 0:
+            t_on[m], t_off[m] = 0, U64MAX
+        elif pick == 1:
+            t_on[m], t_off[m] = 0, int(tr.arrival_us[0])                # closed before the first arrival
+        elif pick == 2:
+            t_on[m] = t_off[m]                                          # empty
+        elif pick == 3:
+            t_on[m], t_off[m] = int(tr.arrival_us[-1]) + 1, U64MAX      # up after the last arrival
+    if rng.integers(0, 4) == 0:                                         # one kind only
+        override = dict(coef=[STD] * M, t_on_us=t_on, t_off_us=t_off)
+    else:
+        override = dict(t_on_us=t_on, t_off_us=t_off)
+    r = rows(9, n, M + int(rng.integers(0, 3)), seed=3000 + seed)
+    r[3] = int(rng.integers(0, M))
+    both(tr, r, f"random seed={seed} n={n} M={M} B={B} rate={rate:.0f} closing={closing} {kw}", **override)
+
+
+@pytest.mark.parametrize("n,M,B,rate", [(6000, 8, 4, 1500.0), (20000, 128, 64, 400000.0), (1500, 3, 64, 12000.0)])
+def test_identical_replicas_under_load_go_through_the_lists(n, M, B, rate):
+    """Identical replicas that are up throughout, with a quarter of the slots or more in service on average: the
+    screen that proves nobody waits would pass hardly any candidate, so every queue is replayed from its list and
+    the histograms are filled from the bins the replay leaves."""
+    rng = np.random.default_rng(n)
+    arrival = (np.floor(np.cumsum(rng.exponential(1.0 / rate, n)) * 1e6) + 5).astype(np.uint64)
+    prompt = np.clip(np.floor(rng.lognormal(6.0, 1.0, n)), 16, 4096)
+    out = np.clip(np.floor(rng.lognormal(5.0, 1.0, n)), 1, 1024)
+    tr = traces.custom_trace(arrival, prompt, out, [STD] * M, np.zeros(M, np.uint64), np.full(M, U64MAX, np.uint64), B=B)
+    r = rows(70, n, M, seed=n + 1)
+    r[9] = 0                                                            # everything on one replica
+    got, (_, replayed) = both(tr, r, f"identical replicas under load n={n} M={M} B={B}")
+    assert replayed == 0 and int(got["n_rejected"].max()) == 0
+    assert int(got["p99_ttft_us"][9]) > int(np.median(got["p99_ttft_us"]))
