@@ -256,10 +256,11 @@ static ap_status launch_dense(const ap_workload* w, const uint16_t* d_assign, ui
             // the list replay: where most candidates are settled by penalty, those go through the variant that
             // leaves no bins, and the wavefronts of the other variant find the few that remain
             if (sp.n_queues != 0u) {
-                const dim3 waves(sp.n_queues * ((n + kWave - 1u) / kWave));
+                const dim3 groups(sp.n_queues * ((n + kReplayListThreads - 1u) / kReplayListThreads));
                 if (w->split_expect_lazy)
-                    hipLaunchKernelGGL(replay_lean, waves, dim3(kWave), 0, stream, sp, n, 1u);
-                hipLaunchKernelGGL(replay_bins, waves, dim3(kWave), 0, stream, sp, n, w->split_expect_lazy ? 2u : 0u);
+                    hipLaunchKernelGGL(replay_lean, groups, dim3(kReplayListThreads), 0, stream, sp, n, 1u);
+                hipLaunchKernelGGL(replay_bins, groups, dim3(kReplayListThreads), 0, stream, sp, n,
+                                   w->split_expect_lazy ? 2u : 0u);
             }
             hipLaunchKernelGGL(sp.wide ? k_merge_candidates<false> : k_merge_candidates<true>,
                                dim3(std::min(n, w->n_cu * 8u)), dim3(kThreads), w->reduce_lds_bytes,

@@ -361,30 +361,40 @@ __device__ __forceinline__ uint32_t median3(uint32_t a, uint32_t b, uint32_t c) 
     return r;
 }
 
-// List replay.  One wavefront per (replica, 64 candidates of the batch): lane l replays the listed part of
-// replica m under candidate 64 * block + l.  All lanes share the replica, hence its cost coefficients and
-// window (scalar registers) and - roughly - the pace at which they move through the trace, so the request
-// records of a tile are staged in LDS once and read by every lane.  A lane keeps its B slot-free times sorted
-// in registers (s[0] the earliest); a request starts at max(ready, s[0]), and its finish time f replaces s[0]
-// by one median per register: s'[i] = med3(s[i], f, s[i+1]), i.e. min(s[i+1], max(s[i], f)).  A lane without a
-// request in a step (or whose request is rejected) inserts 0, which leaves the registers as they are.
+// List replay.  One lane per (candidate, replica) queue: the 64 lanes of a wavefront replay the listed part of
+// replica m under 64 candidates of the batch, and the kListWaves wavefronts of a workgroup take neighbouring
+// candidates of the same replica.  All lanes share the replica, hence its cost coefficients and window (scalar
+// registers) and - roughly - the pace at which they move through the trace, so the request records of
+// kReplayTiles tiles are staged in LDS once per workgroup and read by every lane; inside such a stage the
+// wavefronts run free (no barrier), and within a wavefront the lanes meet again at every tile, where the lane
+// with the most requests of the tile sets the pace.  Staging several tiles at a time for several wavefronts is
+// what keeps the share of idle lane-steps down: the counts of a stage differ less, relative to their mean, than
+// those of a single tile.
+// A lane keeps its B slot-free times sorted in registers (s[0] the earliest); a request starts at
+// max(ready, s[0]), and its finish time f replaces s[0] by one median per register:
+// s'[i] = med3(s[i], f, s[i+1]), i.e. min(s[i+1], max(s[i], f)).  A lane without a request in a step (or whose
+// request is rejected) inserts 0, which leaves the registers as they are.
 // Starts do not decrease along a queue, so once a start reaches t_off every later request is rejected too.
 // kSlots: B rounded up to a power of two; registers beyond B hold kNever and stay there.
 // kBinsOut: the variant that leaves the histogram bins of its requests for the merge.  which: 0 every
-// candidate, 1 only those settled by penalty (the lean variant's share), 2 only the others; a wavefront
+// candidate, 1 only those settled by penalty (the lean variant's share), 2 only the others; a workgroup
 // without a lane to work on ends at once.
+constexpr uint32_t kListWaves = 4;
+constexpr uint32_t kReplayListThreads = kListWaves * kWave;
+constexpr uint32_t kReplayTiles = 2;              // tiles staged at a time: 16 KiB of request records per workgroup
+
 template <uint32_t kSlots, bool kBinsOut>
-__global__ __launch_bounds__(kWave) void k_replay_lists(SplitParams p, uint32_t n_cand, uint32_t which) {
-    __shared__ uint2 recs[kTile];
-    const uint32_t lane = threadIdx.x;
-    const uint32_t n_blocks = (n_cand + kWave - 1u) / kWave;
+__global__ __launch_bounds__(kReplayListThreads) void k_replay_lists(SplitParams p, uint32_t n_cand, uint32_t which) {
+    __shared__ uint2 recs[kReplayTiles * kTile];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t n_blocks = (n_cand + kReplayListThreads - 1u) / kReplayListThreads;
     const uint32_t m = p.order[blockIdx.x / n_blocks];
-    const uint32_t cb = (blockIdx.x % n_blocks) * kWave + lane;
+    const uint32_t cb = (blockIdx.x % n_blocks) * kReplayListThreads + tid;
     bool live = cb < n_cand;
     const bool lazy = live && (p.part[cb].flags & kFlagLazy) != 0u;
     if (which == 1u) live = lazy;
     if (which == 2u) live = live && !lazy;
-    if (__ballot(live) == 0ull) return;
+    if (__syncthreads_or(live ? 1 : 0) == 0) return;
     const bool with_hist = kBinsOut && live && !lazy;                               // leave the bins of every request
     SplitQueue q = p.queue[m];
     q.a = (uint32_t)__builtin_amdgcn_readfirstlane((int)q.a);
@@ -402,11 +412,13 @@ __global__ __launch_bounds__(kWave) void k_replay_lists(SplitParams p, uint32_t 
     uint32_t last_fin = 0, n_ok = 0, n_rej = 0;
 
     const uint32_t n_t = (q.i_list + kTile - 1u) / kTile;
-    for (uint32_t j = 0; j < n_t; ++j) {
-        const uint32_t r0 = j * kTile, n = min(kTile, p.R - r0);
-        __syncthreads();                                                            // the last tile's records were read
-        for (uint32_t i = lane; i < n; i += kWave) recs[i] = p.req8[r0 + i];
+    for (uint32_t j0 = 0; j0 < n_t; j0 += kReplayTiles) {
+        const uint32_t r0 = j0 * kTile, n = min(kReplayTiles * kTile, p.R - r0);
+        __syncthreads();                                                            // the last stage's records were read
+        for (uint32_t i = tid; i < n; i += kReplayListThreads) recs[i] = p.req8[r0 + i];
         __syncthreads();
+        for (uint32_t j = j0; j < min(j0 + kReplayTiles, n_t); ++j) {
+        const uint2* tile_recs = recs + (j - j0) * kTile;
         const size_t tile_at = (size_t)(live ? cb : 0u) * p.n_list_tiles + j;
         const uint32_t d = live ? p.desc[tile_at * (p.M + 1u) + m] : 0u;
         uint32_t count = d >> 16;
@@ -420,7 +432,7 @@ __global__ __launch_bounds__(kWave) void k_replay_lists(SplitParams p, uint32_t 
             uint4 e = make_uint4(0u, 0u, 0u, 0u);
             if (more) e = src[b];
             const uint32_t word[4] = {e.x, e.y, e.z, e.w};
-            if (kBinsOut && with_hist && more && 8u * b + 8u > count) {                         // the run's last block: its padding
+            if (kBinsOut && with_hist && more && 8u * b + 8u > count) {             // the run's last block: its padding
 #pragma unroll
                 for (uint32_t k = 1; k < 8u; ++k)
                     if (8u * b + k >= count) bins[8u * b + k] = make_uint2(0u, 0u);
@@ -430,7 +442,7 @@ __global__ __launch_bounds__(kWave) void k_replay_lists(SplitParams p, uint32_t 
                 const bool active = 8u * b + k < count;
                 if (k != 0u && __ballot(active) == 0ull) break;
                 const uint32_t rl = ((k & 1u) ? word[k >> 1] >> 16 : word[k >> 1]) & (kTile - 1u);
-                const uint2 rq = recs[rl];
+                const uint2 rq = tile_recs[rl];
                 const uint32_t prompt = rq.y & 0xFFFFu, out = rq.y >> 16;
                 const uint32_t prefill = q.a + __umul24(q.b, prompt);               // the host keeps all factors below 2^24
                 const uint32_t tpot = q.c + __umul24(q.d, (prompt + 1023u) >> 10);
@@ -458,6 +470,7 @@ __global__ __launch_bounds__(kWave) void k_replay_lists(SplitParams p, uint32_t 
                     if (kBinsOut && with_hist) bins[8u * b + k] = make_uint2(0u, 0u);
                 }
             }
+        }
         }
     }
     if (!live) return;
