@@ -304,7 +304,9 @@ __device__ __forceinline__ bool cursor_claim(const uint32_t (&id)[K], const uint
     }
 #pragma unroll
     for (uint32_t e = 0; e < K; ++e) {
-        at[e] = ring0_addr + (key[e] << ring_shift) + ((turn[e] & (S - 1u)) << 2);
+        // the replica id is added to the turn: cursors of different replicas advance at much the same pace, and
+        // rings are a multiple of the bank count apart, so equal turns would send a whole step to one LDS bank
+        at[e] = ring0_addr + (key[e] << ring_shift) + (((turn[e] + key[e]) & (S - 1u)) << 2);
         old[e] = lds_max_rtn(at[e], span[e]);
     }
     bool any = false;
