@@ -932,6 +932,16 @@ static ap_status set_cost_model_checked(ap_workload* w, const ap_replica* replic
     // the trace goes straight to the listed evaluation, which replays every queue.
     const bool crowded = w->span_us == 0 || (double)service_sum / (double)w->span_us / M >= 0.25 * B;
     if (w->screen && crowded && !tabled && w->d_req8) w->screen = false;
+    // The one-wavefront screening kernel hands a step's 64 requests to rings of S slots in no particular order: with
+    // few replicas and few slots (64 / M requests per ring and step against S slots) a ring wraps within one step
+    // and hardly any candidate passes.  Such tables go to the listed evaluation as well.
+    {
+        const uint32_t want = std::min(B, kScreenMaxSlots);
+        uint32_t S_log2 = 0;
+        while ((2u << S_log2) <= want && (M + 1u) * ((2u << S_log2) + 1u) * 4u <= kScreenLdsPerWave) ++S_log2;
+        const bool wide = (1u << S_log2) < std::min(want, kScreenMinSlots);
+        if (w->screen && !wide && 128u >= M * (1u << S_log2) && !tabled && w->d_req8) w->screen = false;
+    }
     if (w->screen) {
         ScreenParams sp{};
         sp.span = w->d_span;
