@@ -143,14 +143,17 @@ def test_unknown_ids_in_otherwise_contention_free_candidates(n, M, B):
 
 @pytest.mark.parametrize("name,n,M,B,gap,C,homogeneous,windows", [
     ("max_table_light", 30000, 1024, 64, 60, 6, False, False),      # the largest replica table and slot count
-    ("max_table_homogeneous_saturated", 40000, 1024, 64, 1, 5, True, False),   # screening first, then the pipeline
+    ("max_table_homogeneous_saturated", 40000, 1024, 64, 1, 5, True, False),   # crowded: every request listed
     ("m700_saturated", 50000, 700, 64, 1, 4, False, False),
     ("m1000_b48_windows", 45000, 1000, 48, 2, 4, False, True),
     ("m600_b40_long_trace", 70000, 600, 40, 3, 3, False, True),      # R >= 65536: 32-bit histogram counters
 ])
 def test_large_replica_tables_take_the_queue_per_lane_path(name, n, M, B, gap, C, homogeneous, windows):
-    """M * B slot times of one candidate no longer fit in LDS: grouping, replay (one lane per queue)
-    and reduction run as three kernels."""
+    """M * B slot times of one candidate no longer fit in LDS, so the fused replay kernel is out.  With a linear cost
+    model these tables are scored by the listed / streamed evaluation (one lane per queue, slot times in registers),
+    and whatever it hands back (row 0 puts everything on eight replicas, which breaks its bound where the rest of the
+    trace is calm) by the three-kernel replay (grouping, one lane per queue with a heap in LDS, reduction); tabulated
+    cost models use the three kernels for every row (tests/test_gpu_costtables.py)."""
     rng = np.random.default_rng(n + M)
     t_on = t_off = None
     if windows:
