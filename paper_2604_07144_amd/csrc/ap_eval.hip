@@ -181,10 +181,24 @@ struct ap_workload {
 };
 
 typedef void (*split_fn)(SplitParams, const uint16_t*, uint32_t, uint32_t, uint32_t, PendingWord);
-static split_fn split_kernel(uint32_t hist_mode, int narrow) {
-    static const split_fn variants[6] = {k_split_candidates<0u, false>, k_split_candidates<1u, false>, k_split_candidates<2u, false>,
-                                         k_split_candidates<0u, true>,  k_split_candidates<1u, true>,  k_split_candidates<2u, true>};
-    return variants[hist_mode + (narrow ? 3u : 0u)];
+static split_fn split_kernel(uint32_t hist_mode, int narrow, bool tabled) {
+    static const split_fn variants[12] = {
+        k_split_candidates<0u, false, false>, k_split_candidates<1u, false, false>, k_split_candidates<2u, false, false>,
+        k_split_candidates<0u, true, false>,  k_split_candidates<1u, true, false>,  k_split_candidates<2u, true, false>,
+        k_split_candidates<0u, false, true>,  k_split_candidates<1u, false, true>,  k_split_candidates<2u, false, true>,
+        k_split_candidates<0u, true, true>,   k_split_candidates<1u, true, true>,   k_split_candidates<2u, true, true>};
+    return variants[hist_mode + (narrow ? 3u : 0u) + (tabled ? 6u : 0u)];
+}
+
+typedef void (*replay_lists_fn)(SplitParams, uint32_t, uint32_t);
+template <bool kBinsOut, bool kTabled>
+static replay_lists_fn replay_lists_kernel_of(uint32_t slots) {
+    return slots == 8u ? k_replay_lists<8u, kBinsOut, kTabled> : slots == 16u ? k_replay_lists<16u, kBinsOut, kTabled>
+           : slots == 32u ? k_replay_lists<32u, kBinsOut, kTabled> : k_replay_lists<64u, kBinsOut, kTabled>;
+}
+static replay_lists_fn replay_lists_kernel(uint32_t slots, bool bins_out, bool tabled) {
+    if (tabled) return bins_out ? replay_lists_kernel_of<true, true>(slots) : replay_lists_kernel_of<false, true>(slots);
+    return bins_out ? replay_lists_kernel_of<true, false>(slots) : replay_lists_kernel_of<false, false>(slots);
 }
 
 // The dense path on C rows: screening where it applies, then the exact replay of what is left.
@@ -228,15 +242,8 @@ static ap_status launch_dense(const ap_workload* w, const uint16_t* d_assign, ui
     if (w->split && !marked) {
         // the listed / streamed evaluation, a batch of candidates at a time; what it hands back carries the pending mark
         const SplitParams& sp = w->split_params;
-        typedef void (*replay_fn)(SplitParams, uint32_t, uint32_t);
-        const replay_fn replay_lean = w->split_slots == 8u    ? k_replay_lists<8u, false>
-                                      : w->split_slots == 16u ? k_replay_lists<16u, false>
-                                      : w->split_slots == 32u ? k_replay_lists<32u, false>
-                                                              : k_replay_lists<64u, false>;
-        const replay_fn replay_bins = w->split_slots == 8u    ? k_replay_lists<8u, true>
-                                      : w->split_slots == 16u ? k_replay_lists<16u, true>
-                                      : w->split_slots == 32u ? k_replay_lists<32u, true>
-                                                              : k_replay_lists<64u, true>;
+        const replay_lists_fn replay_lean = replay_lists_kernel(w->split_slots, false, w->tabled);
+        const replay_lists_fn replay_bins = replay_lists_kernel(w->split_slots, true, w->tabled);
         // batches of equal size (whole wavefronts of the list replay), none above what the scratch area holds
         const uint32_t n_batches = (C + w->split_batch - 1u) / w->split_batch;
         const uint32_t per_batch = std::min(w->split_batch, ((C + n_batches - 1u) / n_batches + 63u) / 64u * 64u);
@@ -248,10 +255,10 @@ static ap_status launch_dense(const ap_workload* w, const uint16_t* d_assign, ui
             const int narrow = sp.M <= 64u ? 1 : 0;
             const bool plain_first = w->split_expect_lazy || sp.any_streamed == 0u;
             if (plain_first)
-                hipLaunchKernelGGL(split_kernel(0u, narrow), dim3(grid), dim3(kSplitThreads), w->split_lds_bytes, stream, sp,
+                hipLaunchKernelGGL(split_kernel(0u, narrow, w->tabled), dim3(grid), dim3(kSplitThreads), w->split_lds_bytes, stream, sp,
                                    d_assign, c0, n, 0u, flags);
             if (sp.any_streamed != 0u)
-                hipLaunchKernelGGL(split_kernel(sp.wide ? 2u : 1u, narrow), dim3(grid), dim3(kSplitThreads),
+                hipLaunchKernelGGL(split_kernel(sp.wide ? 2u : 1u, narrow, w->tabled), dim3(grid), dim3(kSplitThreads),
                                    w->split_lds_bytes_hist, stream, sp, d_assign, c0, n, plain_first ? 1u : 0u, flags);
             // the list replay: where most candidates are settled by penalty, those go through the variant that
             // leaves no bins, and the wavefronts of the other variant find the few that remain
@@ -406,16 +413,20 @@ ap_status ap_workload_create(const uint64_t* arrival_us, const int32_t* prompt_l
 // Plan of the split evaluation (ap_split.hpp) for a linear cost model whose replicas differ or have windows:
 // the index ranges of every replica, the bound D on requests in service that started on arrival, the
 // scratch area for one batch of candidates.  Leaves w->split false where the path does not apply.
+// rep_type: the tabulated cost model (replica m reads row rep_type[m] of the tables, which are on the device by
+// now); table_longest_prefill / table_longest_tpot are then the largest entries of the rows in use.
 static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, const ap_replica* replicas,
                             const std::vector<uint32_t>& kinds, const std::vector<uint32_t>& worst_service,
                             const std::vector<uint64_t>& kind_sum, const std::vector<uint64_t>& kind_longest,
-                            uint64_t latest_finish_bound) {
+                            uint64_t latest_finish_bound, const uint32_t* rep_type, uint64_t table_longest_prefill,
+                            uint64_t table_longest_tpot) {
     const uint32_t R = w->R, M = w->params.M, B = w->params.B;
     if (!w->d_req8) return AP_OK;                            // request records with 16-bit lengths only
+    const bool tabled = rep_type != nullptr;
     const bool wide = R >= 65536u;                           // two range words per replica, 32-bit histogram counts
     // The kernels multiply with 24-bit factors and add up a tile's sixteen latencies per lane in 32 bits.
-    uint64_t longest_tpot = 0, longest_prefill = 0;
-    for (uint32_t m = 0; m < M; ++m) {
+    uint64_t longest_tpot = table_longest_tpot, longest_prefill = table_longest_prefill;
+    for (uint32_t m = 0; m < M && !tabled; ++m) {
         if (replicas[m].prefill_per_tok_us >= (1u << 24) || replicas[m].decode_per_kctx_us >= (1u << 24)) return AP_OK;
         longest_tpot = std::max<uint64_t>(longest_tpot, (uint64_t)replicas[m].decode_base_us + 64ull * replicas[m].decode_per_kctx_us);
         longest_prefill = std::max<uint64_t>(longest_prefill, (uint64_t)replicas[m].prefill_base_us + 65535ull * replicas[m].prefill_per_tok_us);
@@ -464,10 +475,11 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
         // which kind of replica this is (its service times: mean and longest)
         size_t ki = 0;
         for (size_t k = 0; k < kinds.size(); ++k)
-            if (replicas[kinds[k]].prefill_base_us == replicas[m].prefill_base_us &&
-                replicas[kinds[k]].prefill_per_tok_us == replicas[m].prefill_per_tok_us &&
-                replicas[kinds[k]].decode_base_us == replicas[m].decode_base_us &&
-                replicas[kinds[k]].decode_per_kctx_us == replicas[m].decode_per_kctx_us)
+            if (tabled ? rep_type[kinds[k]] == rep_type[m]
+                       : (replicas[kinds[k]].prefill_base_us == replicas[m].prefill_base_us &&
+                          replicas[kinds[k]].prefill_per_tok_us == replicas[m].prefill_per_tok_us &&
+                          replicas[kinds[k]].decode_base_us == replicas[m].decode_base_us &&
+                          replicas[kinds[k]].decode_per_kctx_us == replicas[m].decode_per_kctx_us))
                 ki = k;
         // The backlog a replica finds when it comes up is about its share of the requests so far; served B at a
         // time it is gone after so many mean service times, and the last of it after one longest service more.
@@ -483,7 +495,7 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
         i_list = std::min(std::max(i_list, i_calm), i_off);
         tab[m] = wide ? i_list : (i_list | (i_off << 16));
         tab[AP_MAX_REPLICAS + 1u + m] = i_off;
-        tab[2u * (AP_MAX_REPLICAS + 1u) + m] = (uint32_t)ki;
+        tab[2u * (AP_MAX_REPLICAS + 1u) + m] = tabled ? d.a : (uint32_t)ki;        // d.a: the type's first table entry
         any_streamed = any_streamed || i_list < i_off;
         SplitQueue q{};
         q.a = d.a; q.b = d.b; q.c = d.c; q.d = d.d; q.t_on = d.t_on; q.t_off = d.t_off;
@@ -496,7 +508,8 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
     }
     tab[M] = 0u;                                             // unknown replica ids: rejected on arrival
     tab[AP_MAX_REPLICAS + 1u + M] = 0u;
-    for (size_t k = 0; k < kinds.size(); ++k) {
+    tab[2u * (AP_MAX_REPLICAS + 1u) + M] = 0u;
+    for (size_t k = 0; k < kinds.size() && !tabled; ++k) {
         uint32_t* co = &tab[3u * (AP_MAX_REPLICAS + 1u) + 4u * k];
         co[0] = replicas[kinds[k]].prefill_base_us; co[1] = replicas[kinds[k]].prefill_per_tok_us;
         co[2] = replicas[kinds[k]].decode_base_us;  co[3] = replicas[kinds[k]].decode_per_kctx_us;
@@ -545,9 +558,9 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
     w->split_lds_bytes = off;
     w->split_lds_bytes_hist = off + hist_bytes;
     const int narrow = M <= 64u ? 1 : 0;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(split_kernel(0u, narrow)), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)off) != hipSuccess ||
-        hipFuncSetAttribute(reinterpret_cast<const void*>(split_kernel(wide ? 2u : 1u, narrow)),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(split_kernel(0u, narrow, tabled)),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)off) != hipSuccess ||
+        hipFuncSetAttribute(reinterpret_cast<const void*>(split_kernel(wide ? 2u : 1u, narrow, tabled)),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)(off + hist_bytes)) != hipSuccess) {
         (void)hipGetLastError();
         return device_error();
@@ -598,7 +611,9 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
     sp.tab.range_off = w->d_split_tab + (AP_MAX_REPLICAS + 1u);
     sp.tab.kind = w->d_split_tab + 2u * (AP_MAX_REPLICAS + 1u);
     sp.tab.coef = reinterpret_cast<const uint4*>(w->d_split_tab + 3u * (AP_MAX_REPLICAS + 1u));
-    sp.tab.n_kinds = (uint32_t)kinds.size();
+    sp.tab.n_kinds = tabled ? 0u : (uint32_t)kinds.size();
+    sp.tab_prefill = tabled ? w->d_tab_prefill : nullptr;
+    sp.tab_tpot = tabled ? w->d_tab_tpot : nullptr;
     sp.queue = w->d_split_queue;
     sp.order = w->d_split_order;
     sp.lists = reinterpret_cast<uint16_t*>(w->d_split_scratch + o_lists);
@@ -680,6 +695,7 @@ static ap_status set_cost_model_checked(ap_workload* w, const ap_replica* replic
         }
     };
     uint64_t total = latest;
+    uint64_t table_longest_prefill = 0, table_longest_tpot = 0;   // tabulated: the largest entries of the rows in use
     uint64_t latest_unqueued = 0;      // latest finish if nobody ever waited (arrival + service)
     uint64_t longest_pair = 0;         // longest time from the arrival of request 2q to the unqueued finish of 2q or 2q+1
     uint64_t service_sum = 0;
@@ -710,9 +726,12 @@ static ap_status set_cost_model_checked(ap_workload* w, const ap_replica* replic
         }
         const uint32_t blocks = std::max(1u, std::min(1024u, (w->R + kRoofThreads - 1u) / kRoofThreads));
         hipLaunchKernelGGL(k_table_bounds, dim3(blocks), dim3(kRoofThreads), 0, nullptr, w->d_tab_prefill, w->d_tab_tpot, d_in_use,
-                           (uint32_t)in_use.size(), w->d_arrival, w->d_out, w->R, d_bounds);
+                           (uint32_t)in_use.size(), w->d_arrival, w->d_out, w->R, d_bounds, w->d_span);
+        // (the table of contention-free intervals is not in use at this point: it takes every request's longest
+        // service time, 4 R bytes, which the host's sweep over the trace needs)
         if (hipGetLastError() != hipSuccess ||
-            hipMemcpy(&bounds, d_bounds, sizeof(bounds), hipMemcpyDeviceToHost) != hipSuccess) {
+            hipMemcpy(&bounds, d_bounds, sizeof(bounds), hipMemcpyDeviceToHost) != hipSuccess ||
+            hipMemcpy(worst_service.data(), w->d_span, 4u * (size_t)w->R, hipMemcpyDeviceToHost) != hipSuccess) {
             (void)hipGetLastError();
             return device_error();
         }
@@ -721,6 +740,12 @@ static ap_status set_cost_model_checked(ap_workload* w, const ap_replica* replic
         total += bounds.service_sum;
         latest_unqueued = bounds.latest_unqueued;
         longest_pair = bounds.longest_pair;
+        table_longest_prefill = bounds.longest_prefill;
+        table_longest_tpot = bounds.longest_tpot;
+        for (size_t ki = 0; ki < kinds.size(); ++ki) {      // only a guess is made from these: the kinds are not told apart
+            kind_sum[ki] = bounds.service_sum;
+            for (uint32_t r = 0; r < w->R; ++r) kind_longest[ki] = std::max<uint64_t>(kind_longest[ki], worst_service[r]);
+        }
     }
     for (uint32_t r = 0; r < (on_device ? 0u : w->R); ++r) {
         const uint64_t outl = (uint64_t)w->h_out[r];
@@ -729,6 +754,10 @@ static ap_status set_cost_model_checked(ap_workload* w, const ap_replica* replic
             uint64_t prefill, tpot;
             host_cost(kinds[ki], r, prefill, tpot);
             if (tpot > limit || prefill > limit) return AP_ERR_RANGE;
+            if (tabled) {
+                table_longest_prefill = std::max(table_longest_prefill, prefill);
+                table_longest_tpot = std::max(table_longest_tpot, tpot);
+            }
             uint64_t svc = prefill + outl * tpot;
             worst = std::max(worst, svc);
             kind_sum[ki] += std::min(svc, limit);
@@ -931,7 +960,7 @@ static ap_status set_cost_model_checked(ap_workload* w, const ap_replica* replic
     // over the trace's span, by Little's law) is a quarter of the slots or more, hardly any candidate will pass, and
     // the trace goes straight to the listed evaluation, which replays every queue.
     const bool crowded = w->span_us == 0 || (double)service_sum / (double)w->span_us / M >= 0.25 * B;
-    if (w->screen && crowded && !tabled && w->d_req8) w->screen = false;
+    if (w->screen && crowded && w->d_req8) w->screen = false;
     // The one-wavefront screening kernel hands a step's 64 requests to rings of S slots in no particular order: with
     // few replicas and few slots (64 / M requests per ring and step against S slots) a ring wraps within one step
     // and hardly any candidate passes.  Such tables go to the listed evaluation as well.
@@ -940,7 +969,7 @@ static ap_status set_cost_model_checked(ap_workload* w, const ap_replica* replic
         uint32_t S_log2 = 0;
         while ((2u << S_log2) <= want && (M + 1u) * ((2u << S_log2) + 1u) * 4u <= kScreenLdsPerWave) ++S_log2;
         const bool wide = (1u << S_log2) < std::min(want, kScreenMinSlots);
-        if (w->screen && !wide && 128u >= M * (1u << S_log2) && !tabled && w->d_req8) w->screen = false;
+        if (w->screen && !wide && 128u >= M * (1u << S_log2) && w->d_req8) w->screen = false;
     }
     if (w->screen) {
         ScreenParams sp{};
@@ -994,8 +1023,9 @@ static ap_status set_cost_model_checked(ap_workload* w, const ap_replica* replic
     }
     // ---- split evaluation: replicas that differ or have windows ---------------------------
     w->split = false;
-    if (!w->screen && !tabled) {
-        const ap_status st = plan_split(w, dev, replicas, kinds, worst_service, kind_sum, kind_longest, total);
+    if (!w->screen) {
+        const ap_status st = plan_split(w, dev, replicas, kinds, worst_service, kind_sum, kind_longest, total,
+                                        tabled ? rep_type : nullptr, table_longest_prefill, table_longest_tpot);
         if (st != AP_OK) return st;
     }
     w->has_model = true;

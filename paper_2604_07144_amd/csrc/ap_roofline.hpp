@@ -147,9 +147,11 @@ __global__ __launch_bounds__(kRoofThreads) void k_roofline_request_costs(const u
 //   service_sum     all of them added up (each clamped to 2^33, far beyond what 32-bit time allows anyway),
 //   latest_unqueued the latest arrival + service time,
 //   longest_pair    the longest time from the arrival of request 2q to the unqueued finish of 2q or 2q + 1,
-//   over_range      how many table entries reach the value reserved for "never".
+//   over_range      how many table entries reach the value reserved for "never",
+//   longest_prefill, longest_tpot   the largest entries of the rows in use;
+// and per request its longest service time (clamped to 32 bits), for the host's sweep over the trace.
 struct TableBounds {
-    unsigned long long service_sum, latest_unqueued, longest_pair, over_range;
+    unsigned long long service_sum, latest_unqueued, longest_pair, over_range, longest_prefill, longest_tpot;
 };
 
 __global__ __launch_bounds__(kRoofThreads) void k_table_bounds(const uint32_t* __restrict__ tab_prefill,
@@ -157,8 +159,10 @@ __global__ __launch_bounds__(kRoofThreads) void k_table_bounds(const uint32_t* _
                                                                const uint32_t* __restrict__ types, uint32_t n_types,
                                                                const uint32_t* __restrict__ arrival,
                                                                const uint32_t* __restrict__ outlen, uint32_t R,
-                                                               TableBounds* __restrict__ out) {
+                                                               TableBounds* __restrict__ out,
+                                                               uint32_t* __restrict__ worst_service) {
     unsigned long long sum = 0, latest = 0, pair = 0, over = 0;
+    uint32_t top_prefill = 0, top_tpot = 0;
     for (uint32_t r = blockIdx.x * kRoofThreads + threadIdx.x; r < R; r += gridDim.x * kRoofThreads) {
         unsigned long long worst = 0;
         for (uint32_t i = 0; i < n_types; ++i) {
@@ -166,7 +170,10 @@ __global__ __launch_bounds__(kRoofThreads) void k_table_bounds(const uint32_t* _
             const uint32_t prefill = tab_prefill[at], tpot = tab_tpot[at];
             over += (prefill == 0xFFFFFFFFu || tpot == 0xFFFFFFFFu) ? 1ull : 0ull;
             worst = max(worst, (unsigned long long)prefill + (unsigned long long)outlen[r] * tpot);
+            top_prefill = max(top_prefill, prefill);
+            top_tpot = max(top_tpot, tpot);
         }
+        worst_service[r] = (uint32_t)min(worst, 0xFFFFFFFEull);
         sum += min(worst, 1ull << 33);
         latest = max(latest, (unsigned long long)arrival[r] + worst);
         pair = max(pair, (unsigned long long)arrival[r] + worst - arrival[r & ~1u]);
@@ -176,12 +183,16 @@ __global__ __launch_bounds__(kRoofThreads) void k_table_bounds(const uint32_t* _
         over += (unsigned long long)__shfl_down((long long)over, dlt);
         latest = max(latest, (unsigned long long)__shfl_down((long long)latest, dlt));
         pair = max(pair, (unsigned long long)__shfl_down((long long)pair, dlt));
+        top_prefill = max(top_prefill, (uint32_t)__shfl_down((int)top_prefill, dlt));
+        top_tpot = max(top_tpot, (uint32_t)__shfl_down((int)top_tpot, dlt));
     }
     if ((threadIdx.x & 63u) == 0u) {
         if (sum) atomicAdd(&out->service_sum, sum);
         if (over) atomicAdd(&out->over_range, over);
         atomicMax(&out->latest_unqueued, latest);
         atomicMax(&out->longest_pair, pair);
+        atomicMax(&out->longest_prefill, (unsigned long long)top_prefill);
+        atomicMax(&out->longest_tpot, (unsigned long long)top_tpot);
     }
 }
 

@@ -2,6 +2,8 @@
 #ifndef AP_SPLIT_HPP
 #define AP_SPLIT_HPP
 
+#include <type_traits>
+
 #include "ap_common.hpp"
 #include "ap_screen.hpp"
 
@@ -58,7 +60,7 @@ constexpr uint32_t kBinServed = 0x80000000u;      // bins word of a listed reque
 struct SplitTables {
     const uint32_t* range;                        // [M + 1] i_list | i_off << 16; wide: i_list
     const uint32_t* range_off;                    // wide only: [M + 1] i_off
-    const uint32_t* kind;                         // [M + 1] index into coef
+    const uint32_t* kind;                         // [M + 1] index into coef; tabulated cost model: type * R
     const uint4* coef;                            // [n_kinds] a, b, c, d
     uint32_t n_kinds;
 };
@@ -89,6 +91,8 @@ struct SplitParams {
     uint32_t* hist;                               // [batch][hist_words] the streamed requests' histograms
     uint2* bins;                                  // [batch][n_list_tiles][tile_cap] bins of every listed request:
                                                   //   x = ttft bin | e2e bin << 12 | kBinServed, y = tpot bin
+    const uint32_t* tab_prefill;                  // tabulated cost model: [T][R] prefill time and time per token; the kind
+    const uint32_t* tab_tpot;                     //   word of a replica and SplitQueue::a then hold type * R
     uint32_t hist_words;                          // 3 * kBins / 2 (16-bit counts, R < 65536) or 3 * kBins
     uint32_t wide;                                // R >= 65536: two range words per replica
     uint32_t any_streamed;                        // some replica has a streamed part
@@ -111,7 +115,9 @@ struct SplitParams {
 // when nothing is streamed at all), 1 keeps them with 16-bit counts (R < 65536), 2 with 32-bit counts.
 // only_flagged: look only at candidates that an earlier launch marked kFlagNeedHist.
 // kNarrow: at most 64 replicas, so a queued request (tile index and replica) fits 16 bits, which halves the queue.
-template <uint32_t kHistMode, bool kNarrow>
+// kTabled: prefill time and time per token are read from the tables (two loads per request, issued with the
+// table look-ups of the quarter tile) instead of being evaluated from a kind's coefficients.
+template <uint32_t kHistMode, bool kNarrow, bool kTabled>
 __global__ __launch_bounds__(kSplitThreads, 5) void k_split_candidates(SplitParams p, const uint16_t* __restrict__ assign,
                                                                     uint32_t c0, uint32_t n_cand, uint32_t only_flagged,
                                                                     PendingWord flags) {
@@ -198,6 +204,7 @@ __global__ __launch_bounds__(kSplitThreads, 5) void k_split_candidates(SplitPara
             for (uint32_t h = 0; h < kParts; ++h) {
                 uint4 record[kHalf];
                 uint32_t id[2u * kHalf], from[2u * kHalf], upto[2u * kHalf], kind[2u * kHalf];   // listed below `from`, gone from `upto`
+                uint32_t cost_prefill[kTabled ? 2u * kHalf : 1u], cost_tpot[kTabled ? 2u * kHalf : 1u];
 #pragma unroll
                 for (uint32_t g = 0; g < kHalf; ++g) {
                     const uint32_t rl = (h * kHalf + g) * 2u * kWave + 2u * lane;
@@ -217,6 +224,14 @@ __global__ __launch_bounds__(kSplitThreads, 5) void k_split_candidates(SplitPara
                     }
                     kind[i] = kind_of[id[i]];
                 }
+                if (kTabled) {
+#pragma unroll
+                    for (uint32_t i = 0; i < 2u * kHalf; ++i) {                     // whether streamed or not: the entry exists
+                        const uint32_t r = min(r0 + (h * kHalf + (i >> 1)) * 2u * kWave + 2u * lane + (i & 1u), R - 1u);
+                        cost_prefill[i] = p.tab_prefill[kind[i] + r];
+                        cost_tpot[i] = p.tab_tpot[kind[i] + r];
+                    }
+                }
 #pragma unroll
                 for (uint32_t g = 0; g < kHalf; ++g) {
                     bool listed[2];
@@ -233,10 +248,16 @@ __global__ __launch_bounds__(kSplitThreads, 5) void k_split_candidates(SplitPara
                         if (streamed) {
                             // starts on arrival: ttft = prefill
                             const uint32_t arrival = e ? record[g].z : record[g].x, lens = e ? record[g].w : record[g].y;
-                            const uint4 co = coef_of[kind[i]];
                             const uint32_t prompt = lens & 0xFFFFu, out = lens >> 16;
-                            const uint32_t prefill = co.x + __umul24(co.y, prompt);    // the host keeps all factors below 2^24
-                            const uint32_t tpot = co.z + __umul24(co.w, (prompt + 1023u) >> 10);
+                            uint32_t prefill, tpot;
+                            if (kTabled) {
+                                prefill = cost_prefill[i];
+                                tpot = cost_tpot[i];
+                            } else {
+                                const uint4 co = coef_of[kind[i]];
+                                prefill = co.x + __umul24(co.y, prompt);            // the host keeps all factors below 2^24
+                                tpot = co.z + __umul24(co.w, (prompt + 1023u) >> 10);
+                            }
                             const uint32_t e2e = prefill + __umul24(out, tpot);
                             t_ttft += prefill;
                             t_e2e += e2e;
@@ -383,9 +404,12 @@ constexpr uint32_t kListWaves = 4;
 constexpr uint32_t kReplayListThreads = kListWaves * kWave;
 constexpr uint32_t kReplayTiles = 2;              // tiles staged at a time: 16 KiB of request records per workgroup
 
-template <uint32_t kSlots, bool kBinsOut>
+// kTabled: a staged record carries the request's prefill time and time per token on this replica's type, read
+// from the tables while staging, instead of its lengths.
+template <uint32_t kSlots, bool kBinsOut, bool kTabled>
 __global__ __launch_bounds__(kReplayListThreads) void k_replay_lists(SplitParams p, uint32_t n_cand, uint32_t which) {
-    __shared__ uint2 recs[kReplayTiles * kTile];
+    using staged_t = typename std::conditional<kTabled, uint4, uint2>::type;         // {arrival, out, prefill, tpot} or {arrival, lengths}
+    __shared__ staged_t recs[kReplayTiles * kTile];
     const uint32_t tid = threadIdx.x;
     const uint32_t n_blocks = (n_cand + kReplayListThreads - 1u) / kReplayListThreads;
     const uint32_t m = p.order[blockIdx.x / n_blocks];
@@ -415,10 +439,14 @@ __global__ __launch_bounds__(kReplayListThreads) void k_replay_lists(SplitParams
     for (uint32_t j0 = 0; j0 < n_t; j0 += kReplayTiles) {
         const uint32_t r0 = j0 * kTile, n = min(kReplayTiles * kTile, p.R - r0);
         __syncthreads();                                                            // the last stage's records were read
-        for (uint32_t i = tid; i < n; i += kReplayListThreads) recs[i] = p.req8[r0 + i];
+        for (uint32_t i = tid; i < n; i += kReplayListThreads) {
+            const uint2 rq = p.req8[r0 + i];
+            if constexpr (kTabled) recs[i] = make_uint4(rq.x, rq.y >> 16, p.tab_prefill[q.a + r0 + i], p.tab_tpot[q.a + r0 + i]);
+            else recs[i] = rq;
+        }
         __syncthreads();
         for (uint32_t j = j0; j < min(j0 + kReplayTiles, n_t); ++j) {
-        const uint2* tile_recs = recs + (j - j0) * kTile;
+        const staged_t* tile_recs = recs + (j - j0) * kTile;
         const size_t tile_at = (size_t)(live ? cb : 0u) * p.n_list_tiles + j;
         const uint32_t d = live ? p.desc[tile_at * (p.M + 1u) + m] : 0u;
         uint32_t count = d >> 16;
@@ -442,10 +470,18 @@ __global__ __launch_bounds__(kReplayListThreads) void k_replay_lists(SplitParams
                 const bool active = 8u * b + k < count;
                 if (k != 0u && __ballot(active) == 0ull) break;
                 const uint32_t rl = ((k & 1u) ? word[k >> 1] >> 16 : word[k >> 1]) & (kTile - 1u);
-                const uint2 rq = tile_recs[rl];
-                const uint32_t prompt = rq.y & 0xFFFFu, out = rq.y >> 16;
-                const uint32_t prefill = q.a + __umul24(q.b, prompt);               // the host keeps all factors below 2^24
-                const uint32_t tpot = q.c + __umul24(q.d, (prompt + 1023u) >> 10);
+                const staged_t rq = tile_recs[rl];
+                uint32_t prefill, tpot, out;
+                if constexpr (kTabled) {
+                    out = rq.y;
+                    prefill = rq.z;
+                    tpot = rq.w;
+                } else {
+                    const uint32_t prompt = rq.y & 0xFFFFu;
+                    out = rq.y >> 16;
+                    prefill = q.a + __umul24(q.b, prompt);                          // the host keeps all factors below 2^24
+                    tpot = q.c + __umul24(q.d, (prompt + 1023u) >> 10);
+                }
                 const uint32_t dec = __umul24(out, tpot);
                 const uint32_t start = max(max(rq.x, q.t_on), s[0]);
                 const bool served = active && start < q.t_off;

@@ -149,11 +149,10 @@ def test_unknown_ids_in_otherwise_contention_free_candidates(n, M, B):
     ("m600_b40_long_trace", 70000, 600, 40, 3, 3, False, True),      # R >= 65536: 32-bit histogram counters
 ])
 def test_large_replica_tables_take_the_queue_per_lane_path(name, n, M, B, gap, C, homogeneous, windows):
-    """M * B slot times of one candidate no longer fit in LDS, so the fused replay kernel is out.  With a linear cost
-    model these tables are scored by the listed / streamed evaluation (one lane per queue, slot times in registers),
-    and whatever it hands back (row 0 puts everything on eight replicas, which breaks its bound where the rest of the
-    trace is calm) by the three-kernel replay (grouping, one lane per queue with a heap in LDS, reduction); tabulated
-    cost models use the three kernels for every row (tests/test_gpu_costtables.py)."""
+    """M * B slot times of one candidate no longer fit in LDS, so the fused replay kernel is out.  These tables are
+    scored by the listed / streamed evaluation (one lane per queue, slot times in registers), and whatever it hands
+    back (row 0 puts everything on eight replicas, which breaks its bound where the rest of the trace is calm) by the
+    three-kernel replay (grouping, one lane per queue with a heap in LDS, reduction)."""
     rng = np.random.default_rng(n + M)
     t_on = t_off = None
     if windows:

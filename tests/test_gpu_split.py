@@ -175,3 +175,52 @@ def test_identical_replicas_under_load_go_through_the_lists(n, M, B, rate):
     got, (_, replayed) = both(tr, r, f"identical replicas under load n={n} M={M} B={B}")
     assert replayed == 0 and int(got["n_rejected"].max()) == 0
     assert int(got["p99_ttft_us"][9]) > int(np.median(got["p99_ttft_us"]))
+
+
+def _tables(tr, n_types, seed, scale=1.0):
+    """Arbitrary cost tables: per type and request a prefill time and a time per token, unrelated to the lengths."""
+    rng = np.random.default_rng(seed)
+    prefill = (rng.integers(200, 30_000, size=(n_types, tr.R)) * scale).astype(np.uint32)
+    tpot = (rng.integers(5, 120, size=(n_types, tr.R)) * scale).astype(np.uint32)
+    return prefill, tpot
+
+
+@pytest.mark.parametrize("n,M,B,rate,closing,n_types", [
+    (20000, 48, 64, 1200.0, True, 3),        # calm, windows: backlogs listed, the rest scored on arrival
+    (15000, 24, 32, 900.0, False, 2),        # nobody leaves: histograms from both parts
+    (9000, 6, 8, 20000.0, True, 4),          # dense: every request listed
+    (70000, 40, 16, 3000.0, True, 1),        # one type, R >= 65536
+    (2047, 130, 33, 2000.0, True, 5),        # more than 64 replicas, ragged tile
+])
+def test_tabulated_cost_model_through_the_lists(n, M, B, rate, closing, n_types):
+    """The listed / streamed evaluation with service times read from tables (two loads per streamed request; the
+    list replay stages its replica type's entries next to the request records)."""
+    tr = elastic(n, M, B, rate, seed=n + M, closing=closing)
+    rep_type = (np.arange(M) * 7 % n_types).astype(np.uint32)
+    prefill, tpot = _tables(tr, n_types, seed=n)
+    r = rows(11, n, M + 1, seed=n + 2)
+    r[4] = M - 1
+    with GpuWorkload(tr, tables=(rep_type, prefill, tpot)) as g:
+        got = g.eval(r)
+        scored, replayed = g.counts()
+    want = oracle_for(tr).set_cost_tables(rep_type, prefill, tpot).eval_batch(r, nthreads=8)
+    assert_same(got, want, f"tables through the lists n={n} M={M} B={B}")
+    assert scored == 11 and replayed <= 3                               # handed back at most the odd overloaded row
+
+
+def test_tabulated_identical_replicas_under_load():
+    """One type, always up, crowded: the tabulated form of the saturated case."""
+    n, M, B = 12000, 16, 8
+    rng = np.random.default_rng(5)
+    arrival = (np.floor(np.cumsum(rng.exponential(1.0 / 30000.0, n)) * 1e6) + 5).astype(np.uint64)
+    prompt = np.clip(np.floor(rng.lognormal(6.0, 1.0, n)), 16, 4096)
+    out = np.clip(np.floor(rng.lognormal(5.0, 1.0, n)), 1, 1024)
+    tr = traces.custom_trace(arrival, prompt, out, [STD] * M, np.zeros(M, np.uint64), np.full(M, U64MAX, np.uint64), B=B)
+    prefill, tpot = _tables(tr, 1, seed=6)
+    rep_type = np.zeros(M, np.uint32)
+    r = rows(20, n, M, seed=7)
+    with GpuWorkload(tr, tables=(rep_type, prefill, tpot)) as g:
+        got = g.eval(r)
+        _, replayed = g.counts()
+    assert_same(got, oracle_for(tr).set_cost_tables(rep_type, prefill, tpot).eval_batch(r, nthreads=8), "tables, crowded")
+    assert replayed == 0
