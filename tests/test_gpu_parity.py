@@ -211,6 +211,31 @@ def test_lengths_beyond_16_bits_and_coarse_ticks():
     both(mixed, rows, "long lengths, two replica types (replayed)")
 
 
+@pytest.mark.parametrize("M,B,windows", [(1024, 64, False), (700, 48, True)])
+def test_three_kernel_replay_scores_every_row_when_lengths_are_long(M, B, windows):
+    """A length of 65536 tokens or more rules out the 8-byte request records of the listed / streamed evaluation, and
+    M * B slot times do not fit in LDS: grouping, replay (one lane per queue, heap in LDS) and reduction score every row."""
+    rng = np.random.default_rng(M)
+    n = 20000
+    arrival = (np.cumsum(rng.integers(0, 60, n)) + 1_000_000_007).astype(np.uint64)
+    prompt = rng.integers(1, 3000, n)
+    out = rng.integers(1, 300, n)
+    prompt[::211] = rng.integers(65536, 120_000, len(prompt[::211]))
+    t_on = t_off = None
+    if windows:
+        xy = rng.integers(0, n * 30 + 1, size=(M, 2)) + 1_000_000_007
+        t_on, t_off = xy.min(1).astype(np.uint64), xy.max(1).astype(np.uint64)
+    tr = traces.custom_trace(arrival, prompt, out, [[(50, 1, 2, 1), (80, 2, 3, 1)][m % 2] for m in range(M)], t_on, t_off, B=B,
+                             penalty_us=2_000_000_000)
+    rows = _rows(5, n, M + 1, seed=M + 1)
+    rows[1] = rng.integers(0, 4, n)                                     # deep queues on four replicas
+    with GpuWorkload(tr) as g:
+        got = g.eval(rows)
+        scored, replayed = g.counts()
+    assert_same(got, oracle_for(tr).eval_batch(rows, nthreads=8), f"three kernels, long lengths M={M} B={B}")
+    assert (scored, replayed) == (5, 5)
+
+
 @pytest.mark.parametrize("seed", range(160))
 def test_random_shapes_against_the_oracle(seed):
     """Shapes, loads and replica tables drawn at random within the documented limits: whichever kernels the
