@@ -224,3 +224,21 @@ def test_tabulated_identical_replicas_under_load():
         _, replayed = g.counts()
     assert_same(got, oracle_for(tr).set_cost_tables(rep_type, prefill, tpot).eval_batch(r, nthreads=8), "tables, crowded")
     assert replayed == 0
+
+
+@pytest.mark.parametrize("closing", [True, False])
+def test_records_do_not_depend_on_what_else_is_in_the_call(closing):
+    """The scratch area keeps the last call's lists, bins and histograms: a row's record must be the same whatever
+    rows surround it, in whatever order, and on a repeated call (closing=False: every candidate needs the bins)."""
+    tr = elastic(9000, 20, 32, 1500.0, seed=40, closing=closing)
+    r = rows(200, tr.R, 21, seed=41)
+    r[17] = 3
+    with GpuWorkload(tr) as g:
+        whole = g.eval(r)
+        perm = np.random.default_rng(1).permutation(200)
+        assert_same(g.eval(r[perm]), whole[perm], "permuted")
+        assert_same(g.eval(r[150:]), whole[150:], "a tail of the rows, after a larger call")
+        assert_same(g.eval(r[17:18]), whole[17:18], "one row")
+        assert_same(g.eval(r[:129]), whole[:129], "129 rows: two wavefronts of queues and a ragged third")
+        assert_same(g.eval(r), whole, "the same call again")
+    assert_same(whole, oracle_for(tr).eval_batch(r, nthreads=8), "against the oracle")
