@@ -242,3 +242,31 @@ def test_records_do_not_depend_on_what_else_is_in_the_call(closing):
         assert_same(g.eval(r[:129]), whole[:129], "129 rows: two wavefronts of queues and a ragged third")
         assert_same(g.eval(r), whole, "the same call again")
     assert_same(whole, oracle_for(tr).eval_batch(r, nthreads=8), "against the oracle")
+
+
+@pytest.mark.parametrize("closing", [True, False])
+def test_captured_in_a_graph_and_replayed(closing):
+    """The listed / streamed evaluation is kernel launches only (no clears, no copies), so the call can be captured;
+    replays with new assignments in between, eager work and synchronisations around them, each against the oracle."""
+    from tests.gpu_harness import to_records
+    tr = elastic(7000, 18, 32, 1500.0, seed=50, closing=closing)
+    C = 70
+    orc = oracle_for(tr)
+    with GpuWorkload(tr) as g:
+        d_assign = torch.zeros((C, tr.R), dtype=torch.int16, device="cuda")
+        d_out = torch.full((C, 8), -1, dtype=torch.int64, device="cuda")
+        g.eval_device(d_assign, d_out)                                   # eager warm-up call
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            g.eval_device(d_assign, d_out)
+        for it in range(4):
+            r = rows(C, tr.R, 18 + (it % 2), seed=60 + it)
+            r[0] = it % 18                                               # one overloaded replica: handed back
+            d_assign.copy_(torch.from_numpy(r.view(np.int16)).cuda())
+            d_out.fill_(-1)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert_same(to_records(d_out), orc.eval_batch(r, nthreads=8), f"replay {it}")
+            assert_same(g.eval(r), to_records(d_out), f"eager call after replay {it}")
