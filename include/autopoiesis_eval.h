@@ -114,9 +114,13 @@ ap_status ap_workload_create(const uint64_t *arrival_us, const int32_t *prompt_l
  * proves that no finish time can leave that range (latest arrival or t_on, plus the sum
  * of every request's largest service time, must be below 2^32 - 1 us, about 71 minutes);
  * otherwise it returns AP_ERR_RANGE and the workload keeps its previous cost model, if any.
- * It also sizes every device buffer later evaluations need: when M*B slot times of one
- * candidate do not fit in LDS next to the histograms, evaluations go through a three-kernel
- * path and the call allocates its scratch area (about 1 GiB) here.
+ * It also decides which kernels later evaluations run and sizes every device buffer they need:
+ * replicas that differ or have windows, crowded traces and very small tables are scored by an
+ * evaluation that replays per-replica request lists, whose scratch area (lists for one batch of
+ * candidates, at most 4 GiB) is allocated here; when M*B slot times of one candidate do not fit
+ * in LDS next to the histograms, what is left for the general replay goes through a three-kernel
+ * path with a scratch area of about 1 GiB, allocated here as well.  AP_ERR_ALLOC if the device
+ * cannot provide them.
  * Synchronous (small host-to-device copies, one small kernel). */
 ap_status ap_costmodel_set(ap_workload *w, const ap_replica *replicas, uint32_t M, uint32_t B, const ap_slo *slo);
 
