@@ -573,21 +573,25 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
     uint32_t batch = (uint32_t)std::min<size_t>(16384u, std::max<size_t>(64u, ((size_t)4 << 30) / per_cand));
     batch = batch / 64u * 64u;
     auto carve = [](size_t& at, size_t bytes) { const size_t here = at; at = (at + bytes + 255u) / 256u * 256u; return here; };
-    size_t total = 0;
-    const size_t o_lists = carve(total, (size_t)batch * sp.n_list_tiles * sp.tile_cap * 2u);
-    const size_t o_bins = carve(total, (size_t)batch * sp.n_list_tiles * sp.tile_cap * 8u);
-    const size_t o_desc = carve(total, (size_t)batch * sp.n_list_tiles * (M + 1u) * 4u);
-    const size_t o_part = carve(total, (size_t)batch * sizeof(SplitPartial));
-    const size_t o_hist = carve(total, (size_t)batch * hist_bytes);
-    if (total > w->split_scratch_bytes) {
+    size_t total = 0, o_lists = 0, o_bins = 0, o_desc = 0, o_part = 0, o_hist = 0;
+    for (;; batch = std::max(64u, batch / 2u / 64u * 64u)) {        // a device short of memory gets smaller batches
+        total = 0;
+        o_lists = carve(total, (size_t)batch * sp.n_list_tiles * sp.tile_cap * 2u);
+        o_bins = carve(total, (size_t)batch * sp.n_list_tiles * sp.tile_cap * 8u);
+        o_desc = carve(total, (size_t)batch * sp.n_list_tiles * (M + 1u) * 4u);
+        o_part = carve(total, (size_t)batch * sizeof(SplitPartial));
+        o_hist = carve(total, (size_t)batch * hist_bytes);
+        if (total <= w->split_scratch_bytes) break;
         if (w->d_split_scratch && hipFree(w->d_split_scratch) != hipSuccess) return device_error();
         w->d_split_scratch = nullptr;
         w->split_scratch_bytes = 0;
-        if (hipMalloc(&w->d_split_scratch, total) != hipSuccess) {
-            (void)hipGetLastError();
-            return AP_ERR_ALLOC;
+        if (hipMalloc(&w->d_split_scratch, total) == hipSuccess) {
+            w->split_scratch_bytes = total;
+            break;
         }
-        w->split_scratch_bytes = total;
+        (void)hipGetLastError();
+        w->d_split_scratch = nullptr;
+        if (batch == 64u) return AP_ERR_ALLOC;
     }
     const size_t tab_bytes = 4u * (3u * (AP_MAX_REPLICAS + 1u) + 4u * (size_t)AP_MAX_REPLICAS + 4u);
     if ((!w->d_split_tab && hipMalloc(&w->d_split_tab, tab_bytes) != hipSuccess) ||
