@@ -410,7 +410,8 @@ ap_status ap_workload_create(const uint64_t* arrival_us, const int32_t* prompt_l
     return AP_OK;
 }
 
-// Plan of the split evaluation (ap_split.hpp) for a linear cost model whose replicas differ or have windows:
+// Plan of the split evaluation (ap_split.hpp) - replicas that differ or have windows, crowded traces, tables too
+// small for the one-wavefront screen; linear cost models (rep_type == nullptr) and tabulated ones:
 // the index ranges of every replica, the bound D on requests in service that started on arrival, the
 // scratch area for one batch of candidates.  Leaves w->split false where the path does not apply.
 // rep_type: the tabulated cost model (replica m reads row rep_type[m] of the tables, which are on the device by
