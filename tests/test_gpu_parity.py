@@ -143,16 +143,17 @@ def test_unknown_ids_in_otherwise_contention_free_candidates(n, M, B):
 
 @pytest.mark.parametrize("name,n,M,B,gap,C,homogeneous,windows", [
     ("max_table_light", 30000, 1024, 64, 60, 6, False, False),      # the largest replica table and slot count
-    ("max_table_homogeneous_saturated", 40000, 1024, 64, 1, 5, True, False),   # crowded: every request listed
+    ("max_table_homogeneous_saturated", 40000, 1024, 64, 1, 5, True, False),   # screening off (crowded), three kernels
     ("m700_saturated", 50000, 700, 64, 1, 4, False, False),
     ("m1000_b48_windows", 45000, 1000, 48, 2, 4, False, True),
     ("m600_b40_long_trace", 70000, 600, 40, 3, 3, False, True),      # R >= 65536: 32-bit histogram counters
 ])
 def test_large_replica_tables_take_the_queue_per_lane_path(name, n, M, B, gap, C, homogeneous, windows):
-    """M * B slot times of one candidate no longer fit in LDS, so the fused replay kernel is out.  These tables are
-    scored by the listed / streamed evaluation (one lane per queue, slot times in registers), and whatever it hands
-    back (row 0 puts everything on eight replicas, which breaks its bound where the rest of the trace is calm) by the
-    three-kernel replay (grouping, one lane per queue with a heap in LDS, reduction)."""
+    """M * B slot times of one candidate no longer fit in LDS, so the fused replay kernel is out.  Up to 600 - 700
+    replicas the listed / streamed evaluation scores these tables (one lane per queue, slot times in registers), and the
+    three-kernel replay (grouping, one lane per queue with a heap in LDS, reduction) whatever it hands back - row 0 puts
+    everything on eight replicas, which breaks its bound where the rest of the trace is calm; with 1000 or 1024 replicas
+    the streaming kernel's per-replica counters do not fit in LDS either and the three kernels score every row."""
     rng = np.random.default_rng(n + M)
     t_on = t_off = None
     if windows:
