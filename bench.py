@@ -132,7 +132,18 @@ def upload_rows(tr, C: int):
     return d_assign
 
 
-def side_workload(cfg: int, rate_scale: float, C: int, d_assign, steps: int, warmup: int, label: str) -> dict:
+def tables_of(tr):
+    """The trace's linear cost model evaluated once per replica type and request: the inputs of ap_costtable_set."""
+    kinds = sorted({tuple(int(x) for x in row) for row in tr.coef})
+    rep_type = np.array([kinds.index(tuple(int(x) for x in row)) for row in tr.coef], dtype=np.uint32)
+    prompt = tr.prompt_len.astype(np.int64)
+    prefill = np.stack([a + b * prompt for a, b, _, _ in kinds]).astype(np.uint32)
+    tpot = np.stack([c + d * ((prompt + 1023) // 1024) for _, _, c, d in kinds]).astype(np.uint32)
+    return rep_type, prefill, tpot
+
+
+def side_workload(cfg: int, rate_scale: float, C: int, d_assign, steps: int, warmup: int, label: str,
+                  cost_tables: bool = False) -> dict:
     """One more workload timed the same way as the main one (same protocol, fewer words): device time per
     ap_eval_candidates call, throughput, roofline fraction on its own algorithmic bytes, how many candidates went
     through the exact replay.  `d_assign` may be shared with another workload whose rows are drawn the same way."""
@@ -146,8 +157,13 @@ def side_workload(cfg: int, rate_scale: float, C: int, d_assign, steps: int, war
     stream = torch.cuda.current_stream()
     h = binding.ap_workload_create(tr.arrival_us, tr.prompt_len, tr.out_len)
     try:
-        binding.ap_costmodel_set(h, binding.make_replicas(tr.coef, tr.t_on_us, tr.t_off_us), tr.B,
-                                 tr.slo_ttft_us, tr.slo_tpot_us, tr.penalty_us)
+        if cost_tables:
+            rep_type, prefill, tpot = tables_of(tr)
+            binding.ap_costtable_set(h, rep_type, tr.t_on_us, tr.t_off_us, tr.B, tr.slo_ttft_us, tr.slo_tpot_us,
+                                     tr.penalty_us, prefill, tpot)
+        else:
+            binding.ap_costmodel_set(h, binding.make_replicas(tr.coef, tr.t_on_us, tr.t_off_us), tr.B,
+                                     tr.slo_ttft_us, tr.slo_tpot_us, tr.penalty_us)
 
         def step():
             binding.ap_eval_candidates(h, d_assign.data_ptr(), C, d_out.data_ptr(), stream.cuda_stream)
@@ -164,7 +180,8 @@ def side_workload(cfg: int, rate_scale: float, C: int, d_assign, steps: int, war
             "value": C * tr.R / (wall / steps), "unit": "sims/s", "ms_per_step": wall * 1e3 / steps,
             "kernel_ms_avg": avg_s * 1e3, "kernel_ms_min": float(np.min(ms)),
             "roofline": {"bound": "hbm", "achieved": alg / avg_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": alg / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": measured_traffic(cfg) if full else None,
+                         "frac": alg / avg_s / 1e9 / HBM_PEAK_GBS,
+                         "traffic": measured_traffic(cfg) if full and not cost_tables else None,
                          "algorithmic_bytes": alg},
             "replayed_fraction": replayed / max(1, scored)}, d_assign
 
@@ -272,11 +289,7 @@ def main() -> int:
     try:
         if args.cost_tables:
             # the same cost model, evaluated here once per replica type and request and handed over as tables
-            kinds = sorted({tuple(int(x) for x in row) for row in tr.coef})
-            rep_type = np.array([kinds.index(tuple(int(x) for x in row)) for row in tr.coef], dtype=np.uint32)
-            prompt = tr.prompt_len.astype(np.int64)
-            prefill = np.stack([a + b * prompt for a, b, _, _ in kinds]).astype(np.uint32)
-            tpot = np.stack([c + d * ((prompt + 1023) // 1024) for _, _, c, d in kinds]).astype(np.uint32)
+            rep_type, prefill, tpot = tables_of(tr)
             binding.ap_costtable_set(h, rep_type, tr.t_on_us, tr.t_off_us, tr.B, tr.slo_ttft_us, tr.slo_tpot_us,
                                      tr.penalty_us, prefill, tpot)
         else:
@@ -401,6 +414,10 @@ def main() -> int:
         alu3 = MEASURED_ALU.get(3)
         if alu3 is not None and alu3[0] == kernel_source_hash():
             side["configs3"]["alu"] = alu3[1]
+        # the same workload with its cost model handed over as tables, the form in which the paper's roofline cost
+        # model reaches the replay
+        side["configs3_cost_tables"], _ = side_workload(3, 1.0, traces.SPECS[3].C, d_rows3, args.steps, args.warmup,
+                                                        " cost model as tables", cost_tables=True)
         sat3, _ = side_workload(3, 100.0, traces.SPECS[3].C, d_rows3, args.steps, args.warmup, " (outside BASELINE.json)")
         del d_rows3
         side["configs2"], _ = side_workload(2, 1.0, traces.SPECS[2].C, None, args.steps, args.warmup, "")
