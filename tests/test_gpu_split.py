@@ -8,7 +8,7 @@ import pytest
 pytestmark = pytest.mark.gpu
 
 torch = pytest.importorskip("torch")
-from paper_2604_07144_amd import traces                   # noqa: E402
+from paper_2604_07144_amd import binding, traces          # noqa: E402
 from tests.gpu_harness import GpuWorkload, assert_same, oracle_for   # noqa: E402
 
 U64MAX = 0xFFFFFFFFFFFFFFFF
@@ -270,3 +270,51 @@ def test_captured_in_a_graph_and_replayed(closing):
             torch.cuda.synchronize()
             assert_same(to_records(d_out), orc.eval_batch(r, nthreads=8), f"replay {it}")
             assert_same(g.eval(r), to_records(d_out), f"eager call after replay {it}")
+
+
+def test_switching_cost_models_on_one_workload():
+    """One workload, its cost model replaced again and again: windows and three kinds (listed / streamed), the same as
+    tables, identical replicas that are always up (screening), a slot count that makes the trace crowded (everything
+    listed), and back.  Every set call re-plans kernels and scratch; no evaluation may see the previous plan."""
+    tr = elastic(8000, 24, 32, 4000.0, seed=70)
+    r = rows(40, tr.R, 25, seed=71)
+    M = tr.M
+    always = dict(t_on_us=np.zeros(M, np.uint64), t_off_us=np.full(M, U64MAX, np.uint64), coef=[STD] * M)
+    rep_type = (np.arange(M) % 3).astype(np.uint32)
+    prefill, tpot = _tables(tr, 3, seed=72)
+    handle = binding.ap_workload_create(tr.arrival_us, tr.prompt_len, tr.out_len)
+    d_assign = torch.from_numpy(np.ascontiguousarray(r).view(np.int16)).cuda()
+    d_out = torch.zeros((40, 8), dtype=torch.int64, device="cuda")
+
+    def run():
+        from tests.gpu_harness import to_records
+        d_out.fill_(-1)
+        binding.ap_eval_candidates(handle, d_assign.data_ptr(), 40, d_out.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        return to_records(d_out)
+
+    def linear(B, **kw):
+        binding.ap_costmodel_set(handle, binding.make_replicas(kw.get("coef", tr.coef), kw.get("t_on_us", tr.t_on_us),
+                                                               kw.get("t_off_us", tr.t_off_us)),
+                                 B, tr.slo_ttft_us, tr.slo_tpot_us, tr.penalty_us)
+        return oracle_for(tr, B=B, **kw).eval_batch(r, nthreads=8)
+
+    def tables(B):
+        binding.ap_costtable_set(handle, rep_type, tr.t_on_us, tr.t_off_us, B, tr.slo_ttft_us, tr.slo_tpot_us,
+                                 tr.penalty_us, prefill, tpot)
+        return oracle_for(tr, B=B).set_cost_tables(rep_type, prefill, tpot).eval_batch(r, nthreads=8)
+
+    try:
+        for round_ in range(2):
+            want = linear(32)
+            assert_same(run(), want, f"windows, three kinds (round {round_})")
+            want = tables(32)
+            assert_same(run(), want, f"the same windows, tables (round {round_})")
+            want = linear(64, **always)
+            assert_same(run(), want, f"identical replicas, always up (round {round_})")
+            want = linear(1, **always)
+            assert_same(run(), want, f"one slot per replica: crowded (round {round_})")
+            want = tables(2)
+            assert_same(run(), want, f"tables, two slots (round {round_})")
+    finally:
+        binding.ap_workload_destroy(handle)
