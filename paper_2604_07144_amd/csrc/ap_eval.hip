@@ -549,7 +549,8 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
     wb += align_up(M * 4u, 16u);            sp.w_queue = wb;
     wb += kTile * (M <= 64u ? 2u : 4u);     sp.w_list = wb;
     wb += align_up(sp.tile_cap * 2u, 16u);  sp.w_same = wb;
-    wb += M * 8u;
+    wb += align_up(M * 8u, 16u);            sp.w_tile = wb;
+    wb += align_up((M + 1u) * 4u, 16u);
     sp.wave_bytes = wb;
     off += kSplitWaves * wb;
     sp.off_hist = off;

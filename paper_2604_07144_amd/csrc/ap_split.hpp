@@ -102,7 +102,8 @@ struct SplitParams {
     uint32_t lazy_from;                           // rejected requests from which the p99 values are the penalty; kNever: never
     uint32_t all_within;                          // no request's prefill or time per token can exceed the objectives
     // byte offsets into the streaming kernel's dynamic LDS
-    uint32_t off_range, off_range_off, off_kind, off_coef, off_acc, off_wave, wave_bytes, w_pos, w_queue, w_list, w_same, off_hist;
+    uint32_t off_range, off_range_off, off_kind, off_coef, off_acc, off_wave, wave_bytes, w_pos, w_queue, w_list, w_same, w_tile,
+        off_hist;
 };
 
 // Streaming kernel.  One workgroup per candidate at a time; its wavefronts take the tiles of the row in turn
@@ -140,6 +141,7 @@ __global__ __launch_bounds__(kSplitThreads, 5) void k_split_candidates(SplitPara
     queued_t* queue = reinterpret_cast<queued_t*>(mine + p.w_queue);         // [kTile] tile index | replica << kIdShift, arrival order
     uint16_t* list = reinterpret_cast<uint16_t*>(mine + p.w_list);           // [tile_cap]
     unsigned long long* same = reinterpret_cast<unsigned long long*>(mine + p.w_same);   // [M] lanes naming the replica
+    uint32_t* tile_of = reinterpret_cast<uint32_t*>(mine + p.w_tile);        // [M + 1] the replica's ranges within the tile in hand
     const uint32_t R = p.R, M = p.M;
 
     if (only_flagged) {                                                             // usually nothing is: leave at once
@@ -198,6 +200,16 @@ __global__ __launch_bounds__(kSplitThreads, 5) void k_split_candidates(SplitPara
             constexpr bool kWhole = decltype(whole_tag)::value;
             const uint32_t r0 = j * kTile, n = min(kTile, R - r0);
             const bool grouping = j < p.n_list_tiles;                               // beyond: nothing can be listed
+            // The replica ranges cut down to this tile, one word per replica: listed below position `lo` of the tile,
+            // gone from position `hi` on (both 0 .. 1024, 11 bits each), and - linear cost model - the replica's kind
+            // above them, so that a request needs one look-up.  (The wavefront's own LDS accesses execute in order.)
+            for (uint32_t m = lane; m <= M; m += kWave) {
+                const uint32_t word = range_of[m];
+                const uint32_t i_list = p.wide != 0u ? word : (word & 0xFFFFu);
+                const uint32_t i_off = p.wide != 0u ? range_off_of[m] : (word >> 16);
+                const uint32_t lo = min(max(i_list, r0) - r0, kTile), hi = min(max(i_off, r0) - r0, kTile);
+                tile_of[m] = lo | (hi << 11) | (kTabled ? 0u : kind_of[m] << 22);
+            }
             uint32_t q_n = 0;                                                       // queued so far (the same in every lane)
             uint32_t t_e2e = 0, t_ttft = 0, t_tpot = 0;                             // the tile's sums: 16 values below 2^28 each
 #pragma unroll
@@ -214,15 +226,10 @@ __global__ __launch_bounds__(kSplitThreads, 5) void k_split_candidates(SplitPara
                 }
 #pragma unroll
                 for (uint32_t i = 0; i < 2u * kHalf; ++i) {
-                    const uint32_t word = range_of[id[i]];
-                    if (p.wide != 0u) {
-                        from[i] = word;
-                        upto[i] = range_off_of[id[i]];
-                    } else {
-                        from[i] = word & 0xFFFFu;
-                        upto[i] = word >> 16;
-                    }
-                    kind[i] = kind_of[id[i]];
+                    const uint32_t word = tile_of[id[i]];
+                    from[i] = word & 0x7FFu;
+                    upto[i] = (word >> 11) & 0x7FFu;
+                    kind[i] = kTabled ? kind_of[id[i]] : word >> 22;
                 }
                 if (kTabled) {
 #pragma unroll
@@ -238,10 +245,10 @@ __global__ __launch_bounds__(kSplitThreads, 5) void k_split_candidates(SplitPara
 #pragma unroll
                     for (uint32_t e = 0; e < 2u; ++e) {
                         const uint32_t i = 2u * g + e;
-                        const uint32_t rl = (h * kHalf + g) * 2u * kWave + 2u * lane + e, r = r0 + rl;
+                        const uint32_t rl = (h * kHalf + g) * 2u * kWave + 2u * lane + e;
                         const bool in = kWhole || rl < n;
-                        listed[e] = in && r < from[i];                              // i_list <= i_off
-                        const bool rejected = in && r >= upto[i];
+                        listed[e] = in && rl < from[i];                             // lo <= hi
+                        const bool rejected = in && rl >= upto[i];
                         const bool streamed = in && !listed[e] && !rejected;
                         n_rej += (uint32_t)__popcll(__ballot(rejected));
                         if (p.all_within != 0u) n_ok += (uint32_t)__popcll(__ballot(streamed));   // a wavefront total then
