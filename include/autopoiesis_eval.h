@@ -119,8 +119,10 @@ ap_status ap_workload_create(const uint64_t *arrival_us, const int32_t *prompt_l
  * evaluation that replays per-replica request lists, whose scratch area (lists for one batch of
  * candidates, at most 4 GiB) is allocated here; when M*B slot times of one candidate do not fit
  * in LDS next to the histograms, what is left for the general replay goes through a three-kernel
- * path with a scratch area of about 1 GiB, allocated here as well.  AP_ERR_ALLOC if the device
- * cannot provide them.
+ * path with a scratch area of about 1 GiB, allocated here as well.  A device that cannot provide
+ * the lists' area (or a trace so long that 64 candidates' lists exceed 8 GiB) only loses that
+ * evaluation - the general replay scores the calls instead; AP_ERR_ALLOC if it cannot provide
+ * the three-kernel path's area.
  * Synchronous (small host-to-device copies, one small kernel). */
 ap_status ap_costmodel_set(ap_workload *w, const ap_replica *replicas, uint32_t M, uint32_t B, const ap_slo *slo);
 
