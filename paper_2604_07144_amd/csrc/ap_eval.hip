@@ -167,6 +167,8 @@ struct ap_workload {
     ChildParams child_params{};
     // split evaluation (replicas that differ or have windows): listed part replayed, streamed part scored on arrival
     uint2* d_req8 = nullptr;          // [R] {arrival, prompt | out << 16}; only when every length is below 65536
+    uint2* d_tab_pair = nullptr;      // [T][R] the cost tables side by side, for the split evaluation of a tabulated model
+    size_t tab_pair_entries = 0;
     uint32_t* d_split_tab = nullptr;       // range and kind words [2][AP_MAX_REPLICAS + 1], then the coefficients of every kind
     SplitQueue* d_split_queue = nullptr;   // [AP_MAX_REPLICAS]
     uint32_t* d_split_order = nullptr;     // [AP_MAX_REPLICAS]
@@ -433,6 +435,8 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
         longest_prefill = std::max<uint64_t>(longest_prefill, (uint64_t)replicas[m].prefill_base_us + 65535ull * replicas[m].prefill_per_tok_us);
     }
     if (longest_tpot >= (1u << 24)) return AP_OK;
+    for (uint32_t m = 0; m < M && tabled; ++m)
+        if (rep_type[m] >= 1024u) return AP_OK;              // the type rides in ten bits of a tile word
     for (uint32_t r = 0; r < R; ++r)
         if (worst_service[r] >= (1u << 28)) return AP_OK;
     std::vector<uint32_t> depth_from;                        // depth_from[i] = max over r >= i of D(r); [R] = 0
@@ -496,7 +500,7 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
         i_list = std::min(std::max(i_list, i_calm), i_off);
         tab[m] = wide ? i_list : (i_list | (i_off << 16));
         tab[AP_MAX_REPLICAS + 1u + m] = i_off;
-        tab[2u * (AP_MAX_REPLICAS + 1u) + m] = tabled ? d.a : (uint32_t)ki;        // d.a: the type's first table entry
+        tab[2u * (AP_MAX_REPLICAS + 1u) + m] = tabled ? rep_type[m] : (uint32_t)ki;
         any_streamed = any_streamed || i_list < i_off;
         SplitQueue q{};
         q.a = d.a; q.b = d.b; q.c = d.c; q.d = d.d; q.t_on = d.t_on; q.t_off = d.t_off;
@@ -619,8 +623,25 @@ static ap_status plan_split(ap_workload* w, const std::vector<DevReplica>& dev, 
     sp.tab.kind = w->d_split_tab + 2u * (AP_MAX_REPLICAS + 1u);
     sp.tab.coef = reinterpret_cast<const uint4*>(w->d_split_tab + 3u * (AP_MAX_REPLICAS + 1u));
     sp.tab.n_kinds = tabled ? 0u : (uint32_t)kinds.size();
-    sp.tab_prefill = tabled ? w->d_tab_prefill : nullptr;
-    sp.tab_tpot = tabled ? w->d_tab_tpot : nullptr;
+    sp.tab_pair = nullptr;
+    if (tabled) {
+        size_t entries = 0;                                  // rows up to the highest type in use
+        for (uint32_t m = 0; m < M; ++m) entries = std::max(entries, ((size_t)rep_type[m] + 1u) * R);
+        if (entries > w->tab_pair_entries) {
+            if (w->d_tab_pair && hipFree(w->d_tab_pair) != hipSuccess) return device_error();
+            w->d_tab_pair = nullptr;
+            w->tab_pair_entries = 0;
+            if (hipMalloc(&w->d_tab_pair, entries * sizeof(uint2)) != hipSuccess) {
+                (void)hipGetLastError();
+                return AP_OK;                                // no room: the general replay scores the calls
+            }
+            w->tab_pair_entries = entries;
+        }
+        hipLaunchKernelGGL(k_pair_tables, dim3((uint32_t)std::min<size_t>(4096u, (entries + kThreads - 1u) / kThreads)),
+                           dim3(kThreads), 0, nullptr, w->d_tab_prefill, w->d_tab_tpot, w->d_tab_pair, entries);
+        if (hipGetLastError() != hipSuccess || hipDeviceSynchronize() != hipSuccess) return device_error();
+        sp.tab_pair = w->d_tab_pair;
+    }
     sp.queue = w->d_split_queue;
     sp.order = w->d_split_order;
     sp.lists = reinterpret_cast<uint16_t*>(w->d_split_scratch + o_lists);
@@ -1681,6 +1702,7 @@ ap_status ap_workload_destroy(ap_workload* w) {
     if (w->d_split_order) ok = (hipFree(w->d_split_order) == hipSuccess) && ok;
     if (w->d_split_scratch) ok = (hipFree(w->d_split_scratch) == hipSuccess) && ok;
     if (w->d_bounds) ok = (hipFree(w->d_bounds) == hipSuccess) && ok;
+    if (w->d_tab_pair) ok = (hipFree(w->d_tab_pair) == hipSuccess) && ok;
     delete w->roof;
     delete w;
     return ok ? AP_OK : AP_ERR_DEVICE;

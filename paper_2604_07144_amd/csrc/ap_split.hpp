@@ -60,7 +60,8 @@ constexpr uint32_t kBinServed = 0x80000000u;      // bins word of a listed reque
 struct SplitTables {
     const uint32_t* range;                        // [M + 1] i_list | i_off << 16; wide: i_list
     const uint32_t* range_off;                    // wide only: [M + 1] i_off
-    const uint32_t* kind;                         // [M + 1] index into coef; tabulated cost model: type * R
+    const uint32_t* kind;                         // [M + 1] index into coef; tabulated cost model: the replica's type
+                                                  //   (either way below 1024: it rides in the upper bits of a tile word)
     const uint4* coef;                            // [n_kinds] a, b, c, d
     uint32_t n_kinds;
 };
@@ -91,8 +92,8 @@ struct SplitParams {
     uint32_t* hist;                               // [batch][hist_words] the streamed requests' histograms
     uint2* bins;                                  // [batch][n_list_tiles][tile_cap] bins of every listed request:
                                                   //   x = ttft bin | e2e bin << 12 | kBinServed, y = tpot bin
-    const uint32_t* tab_prefill;                  // tabulated cost model: [T][R] prefill time and time per token; the kind
-    const uint32_t* tab_tpot;                     //   word of a replica and SplitQueue::a then hold type * R
+    const uint2* tab_pair;                        // tabulated cost model: [T][R] {prefill time, time per token}; the kind
+                                                  //   word of a replica then holds its type, SplitQueue::a type * R
     uint32_t hist_words;                          // 3 * kBins / 2 (16-bit counts, R < 65536) or 3 * kBins
     uint32_t wide;                                // R >= 65536: two range words per replica
     uint32_t any_streamed;                        // some replica has a streamed part
@@ -106,6 +107,14 @@ struct SplitParams {
         off_hist;
 };
 
+// The two cost tables of a tabulated model side by side, so that a request's prefill time and time per token come
+// with one 8-byte load.
+__global__ __launch_bounds__(kThreads) void k_pair_tables(const uint32_t* __restrict__ prefill, const uint32_t* __restrict__ tpot,
+                                                          uint2* __restrict__ pair, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (size_t)gridDim.x * kThreads)
+        pair[i] = make_uint2(prefill[i], tpot[i]);
+}
+
 // Streaming kernel.  One workgroup per candidate at a time; its wavefronts take the tiles of the row in turn
 // and share nothing but the accumulators (and the histograms), so there is no barrier inside a candidate.
 // Per tile a wavefront classifies its 1024 requests, accumulates the streamed ones, counts the listed ones per
@@ -116,7 +125,7 @@ struct SplitParams {
 // when nothing is streamed at all), 1 keeps them with 16-bit counts (R < 65536), 2 with 32-bit counts.
 // only_flagged: look only at candidates that an earlier launch marked kFlagNeedHist.
 // kNarrow: at most 64 replicas, so a queued request (tile index and replica) fits 16 bits, which halves the queue.
-// kTabled: prefill time and time per token are read from the tables (two loads per request, issued with the
+// kTabled: prefill time and time per token are read from the tables (one 8-byte load per request, issued with the
 // table look-ups of the quarter tile) instead of being evaluated from a kind's coefficients.
 template <uint32_t kHistMode, bool kNarrow, bool kTabled>
 __global__ __launch_bounds__(kSplitThreads, 5) void k_split_candidates(SplitParams p, const uint16_t* __restrict__ assign,
@@ -201,14 +210,15 @@ __global__ __launch_bounds__(kSplitThreads, 5) void k_split_candidates(SplitPara
             const uint32_t r0 = j * kTile, n = min(kTile, R - r0);
             const bool grouping = j < p.n_list_tiles;                               // beyond: nothing can be listed
             // The replica ranges cut down to this tile, one word per replica: listed below position `lo` of the tile,
-            // gone from position `hi` on (both 0 .. 1024, 11 bits each), and - linear cost model - the replica's kind
-            // above them, so that a request needs one look-up.  (The wavefront's own LDS accesses execute in order.)
+            // gone from position `hi` on (both 0 .. 1024, 11 bits each), and the replica's kind
+            // above them (or its type, when the costs come from tables), so that a request needs one look-up.
+            // (The wavefront's own LDS accesses execute in order.)
             for (uint32_t m = lane; m <= M; m += kWave) {
                 const uint32_t word = range_of[m];
                 const uint32_t i_list = p.wide != 0u ? word : (word & 0xFFFFu);
                 const uint32_t i_off = p.wide != 0u ? range_off_of[m] : (word >> 16);
                 const uint32_t lo = min(max(i_list, r0) - r0, kTile), hi = min(max(i_off, r0) - r0, kTile);
-                tile_of[m] = lo | (hi << 11) | (kTabled ? 0u : kind_of[m] << 22);
+                tile_of[m] = lo | (hi << 11) | (kind_of[m] << 22);
             }
             uint32_t q_n = 0;                                                       // queued so far (the same in every lane)
             uint32_t t_e2e = 0, t_ttft = 0, t_tpot = 0;                             // the tile's sums: 16 values below 2^28 each
@@ -229,14 +239,15 @@ __global__ __launch_bounds__(kSplitThreads, 5) void k_split_candidates(SplitPara
                     const uint32_t word = tile_of[id[i]];
                     from[i] = word & 0x7FFu;
                     upto[i] = (word >> 11) & 0x7FFu;
-                    kind[i] = kTabled ? kind_of[id[i]] : word >> 22;
+                    kind[i] = kTabled ? (word >> 22) * R : word >> 22;       // tabulated: the type's first table entry
                 }
                 if (kTabled) {
 #pragma unroll
                     for (uint32_t i = 0; i < 2u * kHalf; ++i) {                     // whether streamed or not: the entry exists
                         const uint32_t r = min(r0 + (h * kHalf + (i >> 1)) * 2u * kWave + 2u * lane + (i & 1u), R - 1u);
-                        cost_prefill[i] = p.tab_prefill[kind[i] + r];
-                        cost_tpot[i] = p.tab_tpot[kind[i] + r];
+                        const uint2 cost = p.tab_pair[kind[i] + r];
+                        cost_prefill[i] = cost.x;
+                        cost_tpot[i] = cost.y;
                     }
                 }
 #pragma unroll
@@ -448,8 +459,12 @@ __global__ __launch_bounds__(kReplayListThreads) void k_replay_lists(SplitParams
         __syncthreads();                                                            // the last stage's records were read
         for (uint32_t i = tid; i < n; i += kReplayListThreads) {
             const uint2 rq = p.req8[r0 + i];
-            if constexpr (kTabled) recs[i] = make_uint4(rq.x, rq.y >> 16, p.tab_prefill[q.a + r0 + i], p.tab_tpot[q.a + r0 + i]);
-            else recs[i] = rq;
+            if constexpr (kTabled) {
+                const uint2 cost = p.tab_pair[q.a + r0 + i];
+                recs[i] = make_uint4(rq.x, rq.y >> 16, cost.x, cost.y);
+            } else {
+                recs[i] = rq;
+            }
         }
         __syncthreads();
         for (uint32_t j = j0; j < min(j0 + kReplayTiles, n_t); ++j) {
