@@ -34,19 +34,19 @@ KERNEL_SOURCE_DIR = os.path.join(ROOT, "paper_2604_07144_amd", "csrc")
 # Keyed by configuration; valid only for the library source (all of csrc/) whose hash is recorded with it.
 MEASURED_TRAFFIC = {
     # cfg: (sha256 of the kernel source when measured, bytes per call)
-    4: ("6df3a4da4dd9505e19d2474c190a9d55dd43d446a0608a59af8d11fac65394be", 4305505181),
-    3: ("6df3a4da4dd9505e19d2474c190a9d55dd43d446a0608a59af8d11fac65394be", 2050015087),
+    4: ("1a42a8b4fa7181bd5050da52d4d30baea2d61460da69886659d22c0978f43fe2", 4305337611),
+    3: ("1a42a8b4fa7181bd5050da52d4d30baea2d61460da69886659d22c0978f43fe2", 2049930752),
 }
 # Wave-instructions per candidate-request of one ap_eval_candidates call (all its kernels), from rocprofv3 --pmc
 # SQ_INSTS_VALU / SQ_INSTS_SALU / SQ_INSTS_LDS; same validity rule.  The chip issues at most 256 CUs x 4 SIMDs x
 # 2.4 GHz / 4 cycles = 6.1e11 64-lane vector instructions per second.
 VALU_PEAK_PER_S = 256 * 4 * 2.4e9 / 4
 MEASURED_ALU = {
-    4: ("6df3a4da4dd9505e19d2474c190a9d55dd43d446a0608a59af8d11fac65394be", {"valu": 0.1381, "salu": 0.0796, "lds": 0.0353}),
-    3: ("6df3a4da4dd9505e19d2474c190a9d55dd43d446a0608a59af8d11fac65394be", {"valu": 1.6043, "salu": 0.4891, "lds": 0.1236}),
+    4: ("1a42a8b4fa7181bd5050da52d4d30baea2d61460da69886659d22c0978f43fe2", {"valu": 0.1381, "salu": 0.0796, "lds": 0.0353}),
+    3: ("1a42a8b4fa7181bd5050da52d4d30baea2d61460da69886659d22c0978f43fe2", {"valu": 1.6043, "salu": 0.4891, "lds": 0.1236}),
 }
 # the same for one ap_eval_children call on the sparse form of configs[4]
-MEASURED_TRAFFIC_CHILDREN = {4: ("6df3a4da4dd9505e19d2474c190a9d55dd43d446a0608a59af8d11fac65394be", 131213346)}
+MEASURED_TRAFFIC_CHILDREN = {4: ("1a42a8b4fa7181bd5050da52d4d30baea2d61460da69886659d22c0978f43fe2", 131102012)}
 
 
 def kernel_source_hash() -> str:
